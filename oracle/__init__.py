@@ -1,0 +1,14 @@
+"""CPU oracle for the MoIN hot path -- test infrastructure only.
+
+Only tests, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  It shares no code with the HIP library.
+"""
+from .oracle import (  # noqa: F401
+    build,
+    dist2,
+    histogram,
+    lora_linear,
+    max_threads,
+    route,
+    slot_map,
+)

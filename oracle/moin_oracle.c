@@ -1,0 +1,251 @@
+/*
+ * moin_oracle.c -- TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, obviously-correct CPU definition of what the MoIN hot path
+ * computes.  It exists so that the HIP library can be checked against
+ * something that shares no code with it.  Only tests, the smoke check and the
+ * cpu_baseline leg of the benchmark may call it; the product never does.
+ *
+ * Everything is the textbook definition written out with fp64 accumulation in
+ * index order.  bf16 and fp32 inputs widen to fp64 exactly, so the only
+ * rounding is that of the fp64 sums themselves.  No blocking, no fusion, no
+ * reordering; OpenMP splits the outermost (token / query) loop only.
+ *
+ * What each function follows:
+ *   route      -- Section 3.3 "Model inference": nearest-neighbour search of
+ *                 the query embedding over the topic embeddings, which are the
+ *                 K-means cluster centres (Section 3.1).  Squared L2; the
+ *                 lowest index wins ties.
+ *   slot map   -- Section 4 "Implementation details" (only 4697 of 5000
+ *                 clusters keep an adapter) and Section 4.1 "Downstream
+ *                 tasks" (a topic without an adapter falls back to the base
+ *                 model; the 4697-variant searches retained topics only).
+ *   histogram  -- documents per topic, Figure 3.
+ *   lora_linear-- Section 3.2: y = W x + W_b (W_a x), with one adapter per
+ *                 sequence (Section 1: each query goes to a single expert),
+ *                 a caller-given scale on the adapter term, and the base-only
+ *                 fallback for expert id -1.
+ *
+ * Parity pins live in tests/test_oracle_*.py (closed forms, numpy fp64
+ * special cases, brute force, metamorphic relations).  Anything that would
+ * need the paper's datasets or trained weights is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#define ORACLE_OK 0
+#define ORACLE_EINVAL (-1)
+
+/* bf16 is the top 16 bits of an IEEE-754 binary32: widening is exact. */
+static double bf16_to_f64(uint16_t h)
+{
+    union { uint32_t u; float f; } v;
+    v.u = ((uint32_t)h) << 16;
+    return (double)v.f;
+}
+
+/* ---- routing --------------------------------------------------------- */
+
+/* Squared L2 distance of one query to one centroid, fp64, summed in index
+ * order.  dt: 0 = fp32 storage, 1 = bf16 storage. */
+static double dist2(const void *emb, const void *cent, int64_t i, int32_t k,
+                    int32_t D, int dt)
+{
+    double acc = 0.0;
+    if (dt == 0) {
+        const float *q = (const float *)emb + (size_t)i * D;
+        const float *c = (const float *)cent + (size_t)k * D;
+        for (int32_t j = 0; j < D; ++j) {
+            double diff = (double)q[j] - (double)c[j];
+            acc += diff * diff;
+        }
+    } else {
+        const uint16_t *q = (const uint16_t *)emb + (size_t)i * D;
+        const uint16_t *c = (const uint16_t *)cent + (size_t)k * D;
+        for (int32_t j = 0; j < D; ++j) {
+            double diff = bf16_to_f64(q[j]) - bf16_to_f64(c[j]);
+            acc += diff * diff;
+        }
+    }
+    return acc;
+}
+
+/* Exported so tests can price a near-tie: D2(i, k) for chosen pairs. */
+int moin_oracle_dist2(const void *emb, const void *cent, int32_t D, int dt,
+                      const int64_t *qi, const int32_t *ki, int64_t n,
+                      double *out)
+{
+    if (!emb || !cent || !qi || !ki || !out || D <= 0 || (dt != 0 && dt != 1))
+        return ORACLE_EINVAL;
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < n; ++p)
+        out[p] = dist2(emb, cent, qi[p], ki[p], D, dt);
+    return ORACLE_OK;
+}
+
+/*
+ * centroid_ids[i] = argmin_k ||q_i - c_k||^2, scanning k upward and replacing
+ * the incumbent only on a strictly smaller distance, so ties keep the lowest
+ * index and a NaN distance never wins (a row of NaNs yields 0).
+ * If `eligible` is non-NULL, centroids with eligible[k] == 0 are skipped
+ * (search over retained topics only); if none is eligible the id is 0.
+ * best_d2 / second_d2 (optional) receive the smallest and second smallest
+ * distance seen, for the near-tie band of the parity tests.
+ */
+int moin_oracle_route(const void *emb, const void *cent, int64_t N, int32_t K,
+                      int32_t D, int dt, const uint8_t *eligible,
+                      int32_t *centroid_ids, double *best_d2,
+                      double *second_d2)
+{
+    if (N < 0 || K <= 0 || D <= 0 || (dt != 0 && dt != 1)) return ORACLE_EINVAL;
+    if (N == 0) return ORACLE_OK;
+    if (!emb || !cent || !centroid_ids) return ORACLE_EINVAL;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < N; ++i) {
+        double best = INFINITY, second = INFINITY;
+        int32_t best_k = 0;
+        for (int32_t k = 0; k < K; ++k) {
+            if (eligible && !eligible[k]) continue;
+            double d = dist2(emb, cent, i, k, D, dt);
+            if (d < best) {
+                second = best;
+                best = d;
+                best_k = k;
+            } else if (d < second) {
+                second = d;
+            }
+        }
+        centroid_ids[i] = best_k;
+        if (best_d2) best_d2[i] = best;
+        if (second_d2) second_d2[i] = second;
+    }
+    return ORACLE_OK;
+}
+
+/* expert_ids[i] = slot_of_centroid[centroid_ids[i]]; -1 marks a topic whose
+ * adapter was never trained, i.e. "use the base model alone". */
+int moin_oracle_slot_map(const int32_t *centroid_ids, int64_t N,
+                         const int32_t *slot_of_centroid, int32_t K,
+                         int32_t *expert_ids)
+{
+    if (N < 0 || K <= 0) return ORACLE_EINVAL;
+    if (N == 0) return ORACLE_OK;
+    if (!centroid_ids || !slot_of_centroid || !expert_ids) return ORACLE_EINVAL;
+    for (int64_t i = 0; i < N; ++i) {
+        int32_t c = centroid_ids[i];
+        if (c < 0 || c >= K) return ORACLE_EINVAL;
+        expert_ids[i] = slot_of_centroid[c];
+    }
+    return ORACLE_OK;
+}
+
+/* counts[k] = number of i with ids[i] == k.  counts is overwritten. */
+int moin_oracle_histogram(const int32_t *ids, int64_t N, int32_t K,
+                          int64_t *counts)
+{
+    if (N < 0 || K <= 0 || !counts) return ORACLE_EINVAL;
+    for (int32_t k = 0; k < K; ++k) counts[k] = 0;
+    if (N == 0) return ORACLE_OK;
+    if (!ids) return ORACLE_EINVAL;
+    for (int64_t i = 0; i < N; ++i) {
+        if (ids[i] < 0 || ids[i] >= K) return ORACLE_EINVAL;
+        counts[ids[i]] += 1;
+    }
+    return ORACLE_OK;
+}
+
+/* ---- routed LoRA linear ---------------------------------------------- */
+
+/*
+ * y[p, :] for the tokens listed in rows[0..n_rows) (rows == NULL: all T
+ * tokens, n_rows must then equal T).  For a token t that lies in sequence s
+ * with e = expert_ids[s]:
+ *     base_o = sum_i W[o,i] x[t,i]
+ *     u_j    = sum_i A[e,j,i] x[t,i]           (e >= 0 only)
+ *     y[t,o] = base_o + scale * sum_j B[e,o,j] u_j
+ * and y[t,o] = base_o when e == -1.  u is never rounded.
+ * x, W, A_stack, B_stack hold bf16 bit patterns; y is fp64, n_rows x d_out.
+ * work: caller-provided temporaries, work_slots * (d_in + r) doubles; each
+ * OpenMP thread (at most work_slots of them) keeps its widened token and its
+ * u vector in its own slot.
+ */
+int moin_oracle_lora_linear(const uint16_t *x, const int32_t *seq_offsets,
+                            const int32_t *expert_ids, int32_t S, int64_t T,
+                            const uint16_t *W, const uint16_t *A_stack,
+                            const uint16_t *B_stack, int32_t E, int32_t d_in,
+                            int32_t d_out, int32_t r, double scale,
+                            const int64_t *rows, int64_t n_rows, double *y,
+                            double *work, int32_t work_slots)
+{
+    if (S < 0 || T < 0 || d_in <= 0 || d_out <= 0 || r < 0 || E < 0 ||
+        n_rows < 0 || work_slots <= 0)
+        return ORACLE_EINVAL;
+    if (n_rows == 0) return ORACLE_OK;
+    if (!x || !seq_offsets || !W || !y || !work) return ORACLE_EINVAL;
+    if (S > 0 && !expert_ids) return ORACLE_EINVAL;
+    if (!rows && n_rows != T) return ORACLE_EINVAL;
+    if (seq_offsets[0] != 0 || seq_offsets[S] != T) return ORACLE_EINVAL;
+    for (int32_t s = 0; s < S; ++s) {
+        if (seq_offsets[s + 1] < seq_offsets[s]) return ORACLE_EINVAL;
+        if (expert_ids[s] < -1 || expert_ids[s] >= E) return ORACLE_EINVAL;
+        if (expert_ids[s] >= 0 && (!A_stack || !B_stack)) return ORACLE_EINVAL;
+    }
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(work_slots)
+    for (int64_t p = 0; p < n_rows; ++p) {
+        int64_t t = rows ? rows[p] : p;
+        if (t < 0 || t >= T) {
+#pragma omp atomic write
+            bad = 1;
+            continue;
+        }
+        /* which sequence holds token t: first s with seq_offsets[s+1] > t */
+        int32_t s = 0;
+        while (s < S && seq_offsets[s + 1] <= t) ++s;
+        int32_t e = expert_ids[s];
+        int slot = 0;
+#ifdef _OPENMP
+        extern int omp_get_thread_num(void);
+        slot = omp_get_thread_num();
+#endif
+        double *xt = work + (size_t)slot * ((size_t)d_in + (size_t)r);
+        double *u = xt + d_in;
+        for (int32_t i = 0; i < d_in; ++i)
+            xt[i] = bf16_to_f64(x[(size_t)t * d_in + i]);
+        if (e >= 0) {
+            const uint16_t *A = A_stack + (size_t)e * r * d_in;
+            for (int32_t j = 0; j < r; ++j) {
+                double acc = 0.0;
+                for (int32_t i = 0; i < d_in; ++i)
+                    acc += bf16_to_f64(A[(size_t)j * d_in + i]) * xt[i];
+                u[j] = acc;
+            }
+        }
+        for (int32_t o = 0; o < d_out; ++o) {
+            double base = 0.0;
+            for (int32_t i = 0; i < d_in; ++i)
+                base += bf16_to_f64(W[(size_t)o * d_in + i]) * xt[i];
+            double out = base;
+            if (e >= 0) {
+                const uint16_t *B = B_stack + (size_t)e * d_out * r;
+                double lora = 0.0;
+                for (int32_t j = 0; j < r; ++j)
+                    lora += bf16_to_f64(B[(size_t)o * r + j]) * u[j];
+                out = base + scale * lora;
+            }
+            y[(size_t)p * d_out + o] = out;
+        }
+    }
+    return bad ? ORACLE_EINVAL : ORACLE_OK;
+}
+
+int moin_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

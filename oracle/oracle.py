@@ -1,0 +1,186 @@
+"""ctypes front end of ``moin_oracle.c`` (test infrastructure only).
+
+Inputs are numpy arrays.  bf16 data travels as ``uint16`` bit patterns (numpy
+has no bf16); fp32 as ``float32``.  Every result is fp64 / exact integer.
+Nothing here touches a GPU or the HIP library.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "moin_oracle.c")
+_LIB = os.path.join(_HERE, "libmoin_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (fp64 arithmetic, no fast-math)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall",
+               "-fno-fast-math", "-ffp-contract=off", _SRC, "-o", _LIB + ".tmp", "-lm"]
+        subprocess.run(cmd, check=True)
+        os.replace(_LIB + ".tmp", _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        c = ctypes
+        lib.moin_oracle_dist2.argtypes = [c.c_void_p, c.c_void_p, c.c_int32, c.c_int,
+                                          c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p]
+        lib.moin_oracle_route.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_int32,
+                                          c.c_int32, c.c_int, c.c_void_p, c.c_void_p,
+                                          c.c_void_p, c.c_void_p]
+        lib.moin_oracle_slot_map.argtypes = [c.c_void_p, c.c_int64, c.c_void_p, c.c_int32,
+                                             c.c_void_p]
+        lib.moin_oracle_histogram.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_void_p]
+        lib.moin_oracle_lora_linear.argtypes = [
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int64,
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
+            c.c_double, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_int32]
+        for f in ("moin_oracle_dist2", "moin_oracle_route", "moin_oracle_slot_map",
+                  "moin_oracle_histogram", "moin_oracle_lora_linear",
+                  "moin_oracle_max_threads"):
+            getattr(lib, f).restype = c.c_int
+        _lib = lib
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _emb_array(a, name):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float32:
+        return a, 0
+    if a.dtype == np.uint16:
+        return a, 1
+    raise TypeError(f"{name}: float32 or uint16 (bf16 bits) expected, got {a.dtype}")
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError(f"oracle {what}: invalid argument (code {rc})")
+
+
+def max_threads() -> int:
+    return int(_load().moin_oracle_max_threads())
+
+
+def route(emb, centroids, eligible=None, want_gaps=False):
+    """argmin_k ||q_i - c_k||^2 per query; ties to the lowest k.
+
+    Returns ``ids`` (int32 centroid indices), plus ``(best_d2, second_d2)`` in
+    fp64 when ``want_gaps``.  ``eligible`` (bool[K]) limits the search.
+    """
+    emb, dt = _emb_array(emb, "emb")
+    centroids, dt2 = _emb_array(centroids, "centroids")
+    if dt != dt2 or emb.ndim != 2 or centroids.ndim != 2 or emb.shape[1] != centroids.shape[1]:
+        raise ValueError("emb [N,D] and centroids [K,D] must share dtype and D")
+    N, D = emb.shape
+    K = centroids.shape[0]
+    ids = np.zeros(N, dtype=np.int32)
+    best = np.zeros(N, dtype=np.float64) if want_gaps else None
+    second = np.zeros(N, dtype=np.float64) if want_gaps else None
+    el = None
+    if eligible is not None:
+        el = np.ascontiguousarray(np.asarray(eligible).astype(np.uint8))
+        if el.shape != (K,):
+            raise ValueError("eligible must have shape [K]")
+    _check(_load().moin_oracle_route(_ptr(emb), _ptr(centroids), N, K, D, dt, _ptr(el),
+                                     _ptr(ids), _ptr(best), _ptr(second)), "route")
+    return (ids, best, second) if want_gaps else ids
+
+
+def dist2(emb, centroids, qi, ki):
+    """fp64 squared distances for the (query, centroid) pairs ``(qi[p], ki[p])``."""
+    emb, dt = _emb_array(emb, "emb")
+    centroids, dt2 = _emb_array(centroids, "centroids")
+    if dt != dt2 or emb.shape[1] != centroids.shape[1]:
+        raise ValueError("dtype / D mismatch")
+    qi = np.ascontiguousarray(qi, dtype=np.int64)
+    ki = np.ascontiguousarray(ki, dtype=np.int32)
+    if qi.shape != ki.shape:
+        raise ValueError("qi and ki must have the same shape")
+    if qi.size and (qi.min() < 0 or qi.max() >= emb.shape[0] or ki.min() < 0
+                    or ki.max() >= centroids.shape[0]):
+        raise ValueError("pair index out of range")
+    out = np.zeros(qi.shape, dtype=np.float64)
+    _check(_load().moin_oracle_dist2(_ptr(emb), _ptr(centroids), emb.shape[1], dt, _ptr(qi),
+                                     _ptr(ki), qi.size, _ptr(out)), "dist2")
+    return out
+
+
+def slot_map(centroid_ids, slot_of_centroid):
+    centroid_ids = np.ascontiguousarray(centroid_ids, dtype=np.int32)
+    slot_of_centroid = np.ascontiguousarray(slot_of_centroid, dtype=np.int32)
+    out = np.zeros_like(centroid_ids)
+    _check(_load().moin_oracle_slot_map(_ptr(centroid_ids), centroid_ids.size,
+                                        _ptr(slot_of_centroid), slot_of_centroid.size,
+                                        _ptr(out)), "slot_map")
+    return out
+
+
+def histogram(ids, K):
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    counts = np.zeros(K, dtype=np.int64)
+    _check(_load().moin_oracle_histogram(_ptr(ids), ids.size, K, _ptr(counts)), "histogram")
+    return counts
+
+
+def lora_linear(x, seq_offsets, expert_ids, W, A_stack, B_stack, scale, rows=None,
+                threads=None):
+    """y = x W^T + scale * (x A_e^T) B_e^T with one expert per sequence (fp64).
+
+    ``x [T,d_in]``, ``W [d_out,d_in]``, ``A_stack [E,r,d_in]``, ``B_stack
+    [E,d_out,r]`` are uint16 bf16 bit patterns.  ``rows`` selects the tokens to
+    compute (default all); the result is ``[len(rows), d_out]`` float64.
+    """
+    x = np.ascontiguousarray(x)
+    W = np.ascontiguousarray(W)
+    for name, a in (("x", x), ("W", W)):
+        if a.dtype != np.uint16 or a.ndim != 2:
+            raise TypeError(f"{name}: 2-D uint16 (bf16 bits) expected")
+    T, d_in = x.shape
+    d_out = W.shape[0]
+    if W.shape[1] != d_in:
+        raise ValueError("W must be [d_out, d_in]")
+    seq_offsets = np.ascontiguousarray(seq_offsets, dtype=np.int32)
+    expert_ids = np.ascontiguousarray(expert_ids, dtype=np.int32)
+    S = expert_ids.size
+    if seq_offsets.size != S + 1:
+        raise ValueError("seq_offsets must have S+1 entries")
+    if A_stack is None or B_stack is None:
+        E, r = 0, 0
+        A_stack = B_stack = None
+    else:
+        A_stack = np.ascontiguousarray(A_stack)
+        B_stack = np.ascontiguousarray(B_stack)
+        if A_stack.dtype != np.uint16 or B_stack.dtype != np.uint16:
+            raise TypeError("A_stack/B_stack: uint16 (bf16 bits) expected")
+        E, r = A_stack.shape[0], A_stack.shape[1]
+        if A_stack.shape != (E, r, d_in) or B_stack.shape != (E, d_out, r):
+            raise ValueError("A_stack [E,r,d_in] / B_stack [E,d_out,r] shape mismatch")
+    if rows is None:
+        rows_arr, n_rows = None, T
+    else:
+        rows_arr = np.ascontiguousarray(rows, dtype=np.int64)
+        n_rows = rows_arr.size
+    y = np.zeros((n_rows, d_out), dtype=np.float64)
+    slots = int(threads) if threads else max_threads()
+    work = np.zeros(slots * (d_in + max(r, 1)), dtype=np.float64)
+    _check(_load().moin_oracle_lora_linear(
+        _ptr(x), _ptr(seq_offsets), _ptr(expert_ids), S, T, _ptr(W), _ptr(A_stack),
+        _ptr(B_stack), E, d_in, d_out, r, float(scale), _ptr(rows_arr), n_rows, _ptr(y),
+        _ptr(work), slots), "lora_linear")
+    return y
