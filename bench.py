@@ -1,0 +1,262 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoIN hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch of the q_proj
+prefill workload (64 sequences x 512 tokens, 2048 -> 2048, rank 64, 500
+experts): route the 64 sequence embeddings to their nearest topic (with
+histogram and slot map), group the batch by expert, then the routed LoRA
+linear layer.  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line: whole-path TFLOP/s (`value`), the roofline of the
+dominant kernel measured with HIP events on the launch stream, and the CPU
+oracle timed on a bounded sample of the same workload.  `--also` adds the
+decode (GB/s) and router (queries/s) workloads as extra objects.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2410_09687_amd import moin  # noqa: E402
+from paper_2410_09687_amd import workloads as wl  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+# HBM bytes per launch of the dominant (linear) kernel from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs (see profiles/); None until measured.
+LINEAR_KERNEL_TRAFFIC_BYTES = None
+
+
+def timed_region(fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(steps):
+        fn()
+    stop.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return start.elapsed_time(stop) / steps, wall * 1e3 / steps
+
+
+def kernel_times(ctx, fn, steps):
+    """Average launch duration per kernel id, from HIP events the library records
+    around each launch on the launch stream."""
+    ctx.timing_reset()
+    ctx.timing_enable(True)
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    out = {}
+    for kid, name in enumerate(moin.KERNEL_NAMES):
+        ms, n = ctx.timing_read(kid)
+        if n:
+            out[name] = {"avg_ms": ms / n, "launches": n}
+    ctx.timing_enable(False)
+    ctx.timing_reset()
+    return out
+
+
+def cpu_baseline_prefill(inp, target_s=12.0):
+    """Times the oracle, as it stands, on a bounded sample of the batch's rows."""
+    import oracle
+    A, B, ids = wl.compact_stacks(inp)
+    x, W = wl.bf16_bits(inp.x), wl.bf16_bits(inp.W)
+    off = inp.seq_offsets.cpu().numpy()
+    w = inp.wl
+    threads = min(oracle.max_threads(), os.cpu_count() or 1)
+    per_row = 2.0 * w.d_in * w.d_out + 2.0 * w.r * (w.d_in + w.d_out)
+    rng = np.random.default_rng(0)
+    probe = np.sort(rng.choice(w.T, size=min(w.T, 4 * threads), replace=False))
+    t0 = time.perf_counter()
+    oracle.lora_linear(x, off, ids, W, A, B, w.scale, rows=probe, threads=threads)
+    dt = time.perf_counter() - t0
+    n = int(min(w.T, max(len(probe), target_s / max(dt / len(probe), 1e-9))))
+    rows = np.sort(rng.choice(w.T, size=n, replace=False))
+    t0 = time.perf_counter()
+    oracle.lora_linear(x, off, ids, W, A, B, w.scale, rows=rows, threads=threads)
+    dt = time.perf_counter() - t0
+    return {"value": per_row * n / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n} of {w.T} token rows of the same batch (all {w.d_out} outputs each), "
+                      f"fp64 oracle, {dt:.1f} s"}
+
+
+def bench_prefill(ctx, steps, warmup, with_cpu):
+    w = wl.config_prefill()
+    inp = wl.make_linear_inputs(w, "cuda")
+    # the batch's 64 sequence embeddings, one topic per resident expert
+    rw = wl.RouteWorkload("c1_route", N=w.S, K=w.E, D=768, dtype="bf16", normalise=True, seed=w.seed)
+    rin = wl.make_route_inputs(rw, "cuda")
+    slots = torch.arange(w.E, dtype=torch.int32, device="cuda")
+    y = torch.empty((w.T, w.d_out), dtype=torch.bfloat16, device="cuda")
+
+    def step():
+        eids, _, _ = moin.moin_route(ctx, rin.emb, rin.centroids, slot_of_centroid=slots,
+                                     want_centroid_ids=False, want_counts=True)
+        moin.moin_lora_linear(ctx, inp.x, inp.seq_offsets, eids, inp.W, inp.A_stack, inp.B_stack,
+                              w.scale, out=y)
+
+    ms, wall_ms = timed_region(step, steps, warmup)
+    ctx.check()
+    flops = w.flops() + rw.flops()
+    kt = kernel_times(ctx, step, steps)
+    lin = kt.get("linear", {"avg_ms": float("nan")})
+    lin_flops = 2.0 * w.T * w.d_in * w.d_out + 2.0 * w.T * w.r * w.d_out
+    achieved = lin_flops / (lin["avg_ms"] * 1e-3) / 1e12
+    res = {
+        "metric": "routed-LoRA linear TFLOP/s & decode GB/s (% of MI355X roofline); route qps",
+        "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: q_proj prefill 2048->2048, r=64, E=500, 64 seq x 512 tok, "
+                               "uniform expert ids; step = route(64x768 vs 500 centroids)+histogram+"
+                               "slot map+group-by-expert+routed LoRA linear",
+                   "tokens_per_step": w.T, "tokens_per_s": w.T / (ms * 1e-3),
+                   "frac_of_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                   "wall_ms_per_step": wall_ms},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                     "traffic": LINEAR_KERNEL_TRAFFIC_BYTES, "kernel": "linear_kernel (base GEMM + fused expand)",
+                     "avg_launch_ms": lin["avg_ms"]},
+        "kernels": kt,
+    }
+    if with_cpu:
+        res["cpu_baseline"] = cpu_baseline_prefill(inp)
+    return res
+
+
+def bench_decode(ctx, steps, warmup, n_draws=8):
+    """configs[2]: three MLP projections, 256 single-token sequences, Zipf(1.1)
+    ids over 5000 experts.  Rotates through independent id draws so the adapter
+    working set (>= 2 GB) exceeds the 256 MB last-level cache."""
+    out = {}
+    for w in wl.config_decode():
+        inp = wl.make_linear_inputs(w, "cuda")
+        draws, plans, bytes_alg = [], [], []
+        for k in range(n_draws):
+            ids = wl.draw_expert_ids(w.S, w.E, "zipf", w.zipf_s, w.seed * 8 + 100 + k)
+            t = torch.from_numpy(ids).cuda()
+            draws.append(t)
+            plans.append(moin.Plan(ctx).build(inp.seq_offsets, t, w.T, w.E))
+            distinct = len(np.unique(ids))
+            bytes_alg.append(2.0 * w.d_in * w.d_out + distinct * 2.0 * w.r * (w.d_in + w.d_out)
+                             + 2.0 * w.T * (w.d_in + w.d_out))
+        y = torch.empty((w.T, w.d_out), dtype=torch.bfloat16, device="cuda")
+        state = {"i": 0}
+
+        def step():
+            k = state["i"] % n_draws
+            state["i"] += 1
+            moin.moin_lora_linear_planned(ctx, plans[k], inp.x, inp.W, inp.A_stack, inp.B_stack,
+                                          w.scale, out=y)
+
+        n = max(steps, n_draws) // n_draws * n_draws
+        state["i"] = 0
+        ms, _ = timed_region(step, n, max(warmup, n_draws))
+        ctx.check()
+        state["i"] = 0
+        kt = kernel_times(ctx, step, n)
+        avg_bytes = float(np.mean(bytes_alg))
+        out[w.name] = {"ms_per_call": ms, "algorithmic_bytes": avg_bytes,
+                       "GBps": avg_bytes / (ms * 1e-3) / 1e9,
+                       "frac_of_hbm_peak": avg_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                       "kernels": kt}
+        for p in plans:
+            p.close()
+        del inp, draws, plans
+        torch.cuda.empty_cache()
+    return out
+
+
+def bench_router(ctx, steps, warmup):
+    rw = wl.config_router()
+    rin = wl.make_route_inputs(rw, "cuda")
+
+    def step():
+        moin.moin_route(ctx, rin.emb, rin.centroids, want_counts=True)
+
+    ms, _ = timed_region(step, steps, warmup)
+    ctx.check()
+    kt = kernel_times(ctx, step, steps)
+    tf = rw.flops() / (ms * 1e-3) / 1e12
+    return {"ms_per_call": ms, "queries_per_s": rw.N / (ms * 1e-3), "TFLOPs": tf,
+            "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS, "kernels": kt}
+
+
+def bench_layer(ctx, steps, warmup):
+    """configs[4]: seven chained projections, r=128, E=5000, 32 x 2048 tokens, Zipf(1.5)."""
+    wls = wl.config_layer()
+    T = wls[0].T
+    ids = wl.draw_expert_ids(wls[0].S, wls[0].E, "zipf", 1.5, wls[0].seed * 8 + 4)
+    off = torch.from_numpy(wl.seq_offsets_of(wls[0].seq_lens)).cuda()
+    eids = torch.from_numpy(ids).cuda()
+    h0 = wl._randn_bf16((T, 2048), 1.0, torch.device("cuda"), 4242)
+    inputs = {w.name.split("_", 1)[1]: wl.make_linear_inputs(w, "cuda", expert_ids=ids, x=h0[:1])
+              for w in wls}
+    outs = {n: torch.empty((T, i.wl.d_out), dtype=torch.bfloat16, device="cuda") for n, i in inputs.items()}
+    src = {"q": None, "k": None, "v": None, "o": "q", "gate": "o", "up": "o", "down": "gate"}
+    plan = moin.Plan(ctx)
+
+    def step():
+        plan.build(off, eids, T, wls[0].E)
+        for n, i in inputs.items():
+            x = h0 if src[n] is None else outs[src[n]]
+            moin.moin_lora_linear_planned(ctx, plan, x, i.W, i.A_stack, i.B_stack, i.wl.scale, out=outs[n])
+
+    ms, _ = timed_region(step, steps, warmup)
+    ctx.check()
+    kt = kernel_times(ctx, step, steps)
+    flops = sum(w.flops() for w in wls)
+    tf = flops / (ms * 1e-3) / 1e12
+    plan.close()
+    return {"ms_per_layer": ms, "TFLOPs": tf, "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS,
+            "tokens_per_s": T / (ms * 1e-3), "kernels": kt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--also", default="decode,router",
+                    help="comma list of extra workloads to report: decode,router,layer (or 'none')")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU figure exists)",
+              file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    ctx = moin.Context(0)
+    res = bench_prefill(ctx, args.steps, args.warmup, not args.no_cpu_baseline)
+    extra = [s for s in args.also.split(",") if s and s != "none"]
+    if "decode" in extra:
+        res["decode"] = bench_decode(ctx, args.steps, args.warmup)
+    if "router" in extra:
+        res["router"] = bench_router(ctx, max(5, args.steps // 5), 2)
+    if "layer" in extra:
+        res["layer"] = bench_layer(ctx, max(5, args.steps // 5), 2)
+    ctx.close()
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,168 @@
+/*
+ * libmoin -- MI355X (gfx950) kernels for the MoIN inference hot path:
+ * nearest-topic routing of whole sequences and the sequence-routed
+ * multi-adapter LoRA linear layer.
+ *
+ * Conventions that hold for every call unless a comment says otherwise
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     never frees, reallocates or keeps it after the call returns.
+ *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  No call synchronises or reads device data on the
+ *     host, so ids produced by moin_route can feed moin_lora_linear directly.
+ *   - Return value: MOIN_OK (0) or a negative moin_status.  Nothing throws or
+ *     aborts across this boundary.  Faults only visible in device data (an
+ *     expert id >= E, offsets that run backwards) set a sticky error word in
+ *     the context; the offending sequences are treated as base-only / empty
+ *     and moin_check() reports MOIN_EDATA.
+ *   - N = 0, S = 0 or T = 0 are successful no-ops.  Zero-length sequences are
+ *     legal.
+ *   - A context owns a private device workspace (grown on demand with
+ *     hipMalloc, so a call that needs more may synchronise the device once).
+ *     One context serves one stream at a time; it is not thread-safe.
+ *   - bf16 rows must be 16-byte aligned: base pointers 16-byte aligned and
+ *     D, d_in, r multiples of 8.
+ */
+#ifndef MOIN_H
+#define MOIN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct moin_ctx moin_ctx;
+typedef struct moin_plan moin_plan;
+
+typedef enum { MOIN_F32 = 0, MOIN_BF16 = 1 } moin_dtype;
+
+typedef enum {
+    MOIN_OK = 0,
+    MOIN_EINVAL = -1, /* null pointer, negative size, unsupported shape/alignment */
+    MOIN_ENOMEM = -2, /* workspace allocation failed */
+    MOIN_EHIP = -3,   /* a HIP runtime call failed */
+    MOIN_EDATA = -4   /* sticky device-side data fault, reported by moin_check */
+} moin_status;
+
+/* moin_route flags */
+#define MOIN_ROUTE_RETAINED_ONLY 1u /* search only centroids whose slot is >= 0 */
+
+/* Which kernel a timing slot refers to (moin_timing_*). */
+typedef enum {
+    MOIN_K_PLAN = 0,
+    MOIN_K_SHRINK = 1,        /* prefill: u = s * x A_e^T                       */
+    MOIN_K_LINEAR = 2,        /* prefill: y = x W^T + u B_e^T (base + expand)   */
+    MOIN_K_ROUTE = 3,         /* distance GEMM fused with argmin                */
+    MOIN_K_ROUTE_AUX = 4,     /* centroid norms, histogram, slot map            */
+    MOIN_K_DECODE_SHRINK = 5, /* decode: gather-matvec u = A_e x                */
+    MOIN_K_DECODE_EXPAND = 6, /* decode: gather-matvec s * B_e u                */
+    MOIN_K_DECODE_BASE = 7,   /* decode: thin base GEMM + combine               */
+    MOIN_K_COUNT = 8
+} moin_kernel_id;
+
+/* ---- context ----------------------------------------------------------- */
+
+/* Creates a context bound to HIP device `device`.  Allocates only its own
+ * small bookkeeping (the sticky error word); workspace grows on first use. */
+int moin_create(moin_ctx **out, int device);
+
+/* Frees the context and its workspace.  The caller must have synchronised
+ * every stream that still runs work issued through it.  NULL is a no-op. */
+void moin_destroy(moin_ctx *ctx);
+
+/* Static, NUL-terminated description of a moin_status value. */
+const char *moin_strerror(int code);
+
+/* Synchronises `stream`, returns MOIN_EDATA if any call since the last check
+ * met a device-side data fault (and clears the word), else MOIN_OK. */
+int moin_check(moin_ctx *ctx, void *stream);
+
+/* ---- routing ------------------------------------------------------------
+ * Section 3.3 "Model inference": the query embedding is matched to the nearest
+ * topic embedding; Section 3.1: topic embeddings are the K-means centres, so the
+ * same call is the assignment step of K-means.  Squared L2 distance, ties to
+ * the lowest centroid index.  Section 4 "Implementation details" / 4.1
+ * "Downstream tasks": only some clusters keep an adapter; a topic without one
+ * falls back to the base model (slot -1), or -- with
+ * MOIN_ROUTE_RETAINED_ONLY -- is left out of the search altogether.
+ * Figure 3: per-topic counts.
+ *
+ *   emb              [N, D] row-major, dt (fp32 or bf16)
+ *   centroids        [K, D] row-major, same dt
+ *   slot_of_centroid [K] int32 or NULL: adapter slot of each centroid, -1 = none
+ *   flags            0 or MOIN_ROUTE_RETAINED_ONLY (needs slot_of_centroid)
+ *   expert_ids       [N] int32 out or NULL: slot_of_centroid[centroid] (or the
+ *                    centroid index itself when slot_of_centroid is NULL)
+ *   centroid_ids     [N] int32 out or NULL: argmin centroid index
+ *   counts           [K] int32 out or NULL: number of queries per centroid;
+ *                    overwritten, not accumulated
+ * D must be a multiple of 8 (bf16) or 4 (fp32).  A NaN distance never wins; a
+ * query whose distances are all NaN gets centroid 0.
+ */
+int moin_route(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N,
+               int32_t K, int32_t D, moin_dtype dt,
+               const int32_t *slot_of_centroid, uint32_t flags,
+               int32_t *expert_ids, int32_t *centroid_ids, int32_t *counts,
+               void *stream);
+
+/* Figure 3 on its own: counts[k] = #{i : ids[i] == k}, ids outside [0, K) are
+ * ignored and raise the sticky data fault.  counts is overwritten. */
+int moin_histogram(moin_ctx *ctx, const int32_t *ids, int64_t N, int32_t K,
+                   int32_t *counts, void *stream);
+
+/* ---- routed LoRA linear ---------------------------------------------------
+ * Section 3.2: y = W x + W_b (W_a x) for every token, with the adapter
+ * (W_a, W_b) = (A_stack[e], B_stack[e]) chosen per SEQUENCE (Section 1: each
+ * query is routed to a single expert) and `scale` applied to the adapter
+ * term.  Expert id -1 means the topic has no adapter: y = W x (Section 4.1).
+ *
+ *   x           [T, d_in]      bf16 row-major
+ *   seq_offsets [S+1] int32    seq_offsets[0] = 0, non-decreasing, [S] = T
+ *   expert_ids  [S]   int32    in [-1, E)
+ *   W           [d_out, d_in]  bf16 (y = x W^T)
+ *   A_stack     [E, r, d_in]   bf16   (may be NULL when E == 0 or r == 0)
+ *   B_stack     [E, d_out, r]  bf16
+ *   y           [T, d_out]     out, y_dt = MOIN_BF16 (round-to-nearest-even
+ *                              from the fp32 accumulator) or MOIN_F32
+ * Accumulation is fp32; u = s * W_a x is carried as a sum of two bf16 values
+ * (high part + remainder) into the expand product.
+ * d_in and r must be multiples of 8; d_out a multiple of 8 (bf16 y) or 4.
+ * Small batches (T <= 1024) take the decode path: tokens are grouped by
+ * expert so each distinct adapter is read from HBM once.
+ */
+int moin_lora_linear(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
+                     const int32_t *expert_ids, int32_t S, int64_t T,
+                     const void *W, const void *A_stack, const void *B_stack,
+                     int32_t E, int32_t d_in, int32_t d_out, int32_t r,
+                     float scale, void *y, moin_dtype y_dt, void *stream);
+
+/* The grouping of sequences by expert depends only on (seq_offsets,
+ * expert_ids, E); a plan computes it once for all projections of a layer
+ * (Section 3.2: every linear layer carries an adapter).
+ * moin_plan_build overwrites the plan; the plan must outlive, and must not be
+ * rebuilt before the completion of, the calls that use it. */
+int moin_plan_create(moin_ctx *ctx, moin_plan **out);
+void moin_plan_destroy(moin_plan *plan);
+int moin_plan_build(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
+                    const int32_t *expert_ids, int32_t S, int64_t T, int32_t E,
+                    void *stream);
+int moin_lora_linear_planned(moin_ctx *ctx, const moin_plan *plan, const void *x,
+                             const void *W, const void *A_stack,
+                             const void *B_stack, int32_t d_in, int32_t d_out,
+                             int32_t r, float scale, void *y, moin_dtype y_dt,
+                             void *stream);
+
+/* ---- per-kernel timing ----------------------------------------------------
+ * When enabled, every kernel launch is bracketed by HIP events on the launch
+ * stream.  moin_timing_read synchronises those events and returns, for one
+ * kernel id, the summed duration in milliseconds and the number of launches
+ * since the last moin_timing_reset.  Meant for benchmarks; off by default. */
+int moin_timing_enable(moin_ctx *ctx, int on);
+int moin_timing_reset(moin_ctx *ctx);
+int moin_timing_read(moin_ctx *ctx, int kernel_id, double *ms_sum,
+                     int64_t *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOIN_H */

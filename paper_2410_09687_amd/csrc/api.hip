@@ -1,0 +1,538 @@
+// C-ABI front end of libmoin: argument validation, workspace and plan
+// management, kernel sequencing and optional per-kernel event timing.  All
+// arithmetic of the method lives in the kernels; nothing here touches tensor
+// data on the host.
+#include "../../include/moin.h"
+
+#include <hip/hip_runtime.h>
+
+#include <new>
+#include <vector>
+
+#include "kernels.h"
+
+namespace moin {
+hipError_t prepare_linear_kernels();
+hipError_t prepare_route_kernels();
+hipError_t prepare_kernels()
+{
+    hipError_t e = prepare_linear_kernels();
+    if (e != hipSuccess) return e;
+    return prepare_route_kernels();
+}
+}  // namespace moin
+
+using namespace moin;
+
+struct moin_plan {
+    PlanView pv;
+    void *buf;
+    size_t bytes;
+    int device;
+    int built;
+};
+
+struct TimedSpan {
+    hipEvent_t start, stop;
+    int kernel;
+};
+
+struct moin_ctx {
+    int device;
+    int *err_word;
+    void *ws;
+    size_t ws_bytes;
+    moin_plan *own_plan;
+    int timing;
+    std::vector<TimedSpan> spans;
+    std::vector<hipEvent_t> free_events;
+    double ms_sum[MOIN_K_COUNT];
+    int64_t launches[MOIN_K_COUNT];
+};
+
+namespace {
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
+
+struct DeviceGuard {
+    int prev;
+    bool ok;
+    explicit DeviceGuard(int dev) : prev(-1), ok(false)
+    {
+        if (hipGetDevice(&prev) != hipSuccess) return;
+        ok = (prev == dev) || (hipSetDevice(dev) == hipSuccess);
+    }
+    ~DeviceGuard()
+    {
+        int cur = -1;
+        if (ok && hipGetDevice(&cur) == hipSuccess && cur != prev) (void)hipSetDevice(prev);
+    }
+};
+
+int ensure_ws(moin_ctx *ctx, size_t bytes)
+{
+    if (bytes <= ctx->ws_bytes) return MOIN_OK;
+    if (ctx->ws) {
+        // hipFree waits for work that may still read the old block
+        if (hipFree(ctx->ws) != hipSuccess) return MOIN_EHIP;
+        ctx->ws = nullptr;
+        ctx->ws_bytes = 0;
+    }
+    const size_t want = align_up(bytes + bytes / 4, 1 << 20);
+    void *p = nullptr;
+    if (hipMalloc(&p, want) != hipSuccess) {
+        (void)hipGetLastError();
+        return MOIN_ENOMEM;
+    }
+    ctx->ws = p;
+    ctx->ws_bytes = want;
+    return MOIN_OK;
+}
+
+hipEvent_t take_event(moin_ctx *ctx)
+{
+    if (!ctx->free_events.empty()) {
+        hipEvent_t e = ctx->free_events.back();
+        ctx->free_events.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+// Runs `launch` (which enqueues exactly one kernel id's work) and, when timing
+// is on, brackets it with events on the same stream.
+template <typename F>
+hipError_t timed(moin_ctx *ctx, int kernel, hipStream_t stream, F launch)
+{
+    if (!ctx->timing) return launch();
+    TimedSpan s;
+    s.kernel = kernel;
+    s.start = take_event(ctx);
+    s.stop = take_event(ctx);
+    if (!s.start || !s.stop) return hipErrorOutOfMemory;
+    hipError_t e = hipEventRecord(s.start, stream);
+    if (e != hipSuccess) return e;
+    e = launch();
+    if (e != hipSuccess) return e;
+    e = hipEventRecord(s.stop, stream);
+    if (e != hipSuccess) return e;
+    ctx->spans.push_back(s);
+    return hipSuccess;
+}
+
+int drain_spans(moin_ctx *ctx)
+{
+    int rc = MOIN_OK;
+    for (const TimedSpan &s : ctx->spans) {
+        float ms = 0.f;
+        if (hipEventSynchronize(s.stop) != hipSuccess ||
+            hipEventElapsedTime(&ms, s.start, s.stop) != hipSuccess) {
+            rc = MOIN_EHIP;
+        } else {
+            ctx->ms_sum[s.kernel] += ms;
+            ctx->launches[s.kernel] += 1;
+        }
+        ctx->free_events.push_back(s.start);
+        ctx->free_events.push_back(s.stop);
+    }
+    ctx->spans.clear();
+    return rc;
+}
+
+struct PlanLayout {
+    size_t tile_row0, tile_rows, tile_expert, n_tiles, tok_sorted, row_expert, grp_expert,
+        grp_start, n_groups, keys, tmp, total;
+    int max_tiles, max_groups, decode;
+};
+
+PlanLayout plan_layout(int32_t S, int64_t T)
+{
+    PlanLayout L;
+    L.decode = T <= DECODE_MAX_T;
+    L.max_tiles = (int)(T / TILE_M) + S + 1;
+    L.max_groups = L.decode ? S : 0;
+    size_t npow2 = 1;
+    while (npow2 < (size_t)S) npow2 <<= 1;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    L.keys = take(npow2 * 8);
+    L.tile_row0 = take((size_t)L.max_tiles * 4);
+    L.tile_rows = take((size_t)L.max_tiles * 4);
+    L.tile_expert = take((size_t)L.max_tiles * 4);
+    L.n_tiles = take(4);
+    L.tok_sorted = take(L.decode ? (size_t)T * 4 : 4);
+    L.row_expert = take(L.decode ? (size_t)T * 4 : 4);
+    L.grp_expert = take((size_t)(L.max_groups + 1) * 4);
+    L.grp_start = take((size_t)(L.max_groups + 2) * 4);
+    L.n_groups = take(4);
+    L.tmp = take((size_t)4 * ((size_t)S + 1) * 4);
+    L.total = off;
+    return L;
+}
+
+int plan_build_impl(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
+                    const int32_t *expert_ids, int32_t S, int64_t T, int32_t E, hipStream_t stream)
+{
+    if (S < 0 || T < 0 || E < 0 || T > 0x7fffffffLL - TILE_M) return MOIN_EINVAL;
+    plan->built = 0;
+    plan->pv.S = S;
+    plan->pv.T = T;
+    plan->pv.E = E;
+    if (S == 0 || T == 0) {
+        // nothing to compute; a planned call returns at once
+        plan->built = 1;
+        return MOIN_OK;
+    }
+    if (!seq_offsets || !expert_ids) return MOIN_EINVAL;
+    const PlanLayout L = plan_layout(S, T);
+    if (L.total > plan->bytes) {
+        if (plan->buf && hipFree(plan->buf) != hipSuccess) return MOIN_EHIP;
+        plan->buf = nullptr;
+        plan->bytes = 0;
+        void *p = nullptr;
+        if (hipMalloc(&p, L.total) != hipSuccess) {
+            (void)hipGetLastError();
+            return MOIN_ENOMEM;
+        }
+        plan->buf = p;
+        plan->bytes = L.total;
+    }
+    char *b = static_cast<char *>(plan->buf);
+    PlanView &pv = plan->pv;
+    pv.keys = reinterpret_cast<unsigned long long *>(b + L.keys);
+    pv.tile_row0 = reinterpret_cast<int *>(b + L.tile_row0);
+    pv.tile_rows = reinterpret_cast<int *>(b + L.tile_rows);
+    pv.tile_expert = reinterpret_cast<int *>(b + L.tile_expert);
+    pv.n_tiles = reinterpret_cast<int *>(b + L.n_tiles);
+    pv.tok_sorted = reinterpret_cast<int *>(b + L.tok_sorted);
+    pv.row_expert = reinterpret_cast<int *>(b + L.row_expert);
+    pv.grp_expert = reinterpret_cast<int *>(b + L.grp_expert);
+    pv.grp_start = reinterpret_cast<int *>(b + L.grp_start);
+    pv.n_groups = reinterpret_cast<int *>(b + L.n_groups);
+    pv.tmp = reinterpret_cast<int *>(b + L.tmp);
+    pv.max_tiles = L.max_tiles;
+    pv.max_groups = L.max_groups;
+    pv.decode = L.decode;
+    const hipError_t e = timed(ctx, MOIN_K_PLAN, stream, [&] {
+        return launch_plan(pv, seq_offsets, expert_ids, ctx->err_word, stream);
+    });
+    if (e != hipSuccess) return MOIN_EHIP;
+    plan->built = 1;
+    return MOIN_OK;
+}
+
+int linear_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, const void *W,
+                        const void *A_stack, const void *B_stack, int32_t d_in, int32_t d_out,
+                        int32_t r, float scale, void *y, moin_dtype y_dt, hipStream_t stream)
+{
+    if (!plan->built) return MOIN_EINVAL;
+    const PlanView &pv = plan->pv;
+    if (pv.S == 0 || pv.T == 0) return MOIN_OK;
+    if (!x || !W || !y) return MOIN_EINVAL;
+    if (d_in <= 0 || d_out <= 0 || r < 0) return MOIN_EINVAL;
+    if (d_in % 8 || d_out % 8 || r % 8) return MOIN_EINVAL;
+    if (d_in > (1 << 22) || d_out > (1 << 24) || r > (1 << 16)) return MOIN_EINVAL;
+    if (y_dt != MOIN_BF16 && y_dt != MOIN_F32) return MOIN_EINVAL;
+    if (misaligned(x, 16) || misaligned(W, 16) || misaligned(y, 16)) return MOIN_EINVAL;
+    const bool adapters = pv.E > 0 && r > 0;
+    if (adapters && (!A_stack || !B_stack || misaligned(A_stack, 16) || misaligned(B_stack, 16)))
+        return MOIN_EINVAL;
+    if (!(scale == scale)) return MOIN_EINVAL;
+
+    LinearArgs a;
+    a.x = x; a.W = W; a.A_stack = A_stack; a.B_stack = B_stack;
+    a.y = y; a.y_f32 = (y_dt == MOIN_F32);
+    a.d_in = d_in; a.d_out = d_out; a.r = adapters ? r : 0; a.scale = scale;
+    a.u_hi = a.u_lo = nullptr;
+
+    const size_t u_bytes = align_up((size_t)pv.T * (size_t)a.r * 2, 256);
+    if (!pv.decode) {
+        if (a.r > 0) {
+            const int rc = ensure_ws(ctx, 2 * u_bytes);
+            if (rc != MOIN_OK) return rc;
+            a.u_hi = ctx->ws;
+            a.u_lo = static_cast<char *>(ctx->ws) + u_bytes;
+            if (timed(ctx, MOIN_K_SHRINK, stream, [&] { return launch_prefill_shrink(pv, a, stream); }) !=
+                hipSuccess)
+                return MOIN_EHIP;
+        }
+        if (timed(ctx, MOIN_K_LINEAR, stream, [&] { return launch_prefill_linear(pv, a, stream); }) !=
+            hipSuccess)
+            return MOIN_EHIP;
+        return MOIN_OK;
+    }
+
+    DecodeArgs d;
+    d.lin = a;
+    d.ug_hi = d.ug_lo = nullptr;
+    d.ylora = nullptr;
+    if (a.r > 0) {
+        const size_t yl_bytes = align_up((size_t)pv.T * (size_t)d_out * 4, 256);
+        const int rc = ensure_ws(ctx, 2 * u_bytes + yl_bytes);
+        if (rc != MOIN_OK) return rc;
+        char *w = static_cast<char *>(ctx->ws);
+        d.ug_hi = w;
+        d.ug_lo = w + u_bytes;
+        d.ylora = reinterpret_cast<float *>(w + 2 * u_bytes);
+        if (timed(ctx, MOIN_K_DECODE_SHRINK, stream, [&] { return launch_decode_shrink(pv, d, stream); }) !=
+            hipSuccess)
+            return MOIN_EHIP;
+        if (timed(ctx, MOIN_K_DECODE_EXPAND, stream, [&] { return launch_decode_expand(pv, d, stream); }) !=
+            hipSuccess)
+            return MOIN_EHIP;
+    }
+    if (timed(ctx, MOIN_K_DECODE_BASE, stream, [&] { return launch_decode_base(pv, d, stream); }) !=
+        hipSuccess)
+        return MOIN_EHIP;
+    return MOIN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int moin_create(moin_ctx **out, int device)
+{
+    if (!out || device < 0) return MOIN_EINVAL;
+    *out = nullptr;
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess) {
+        (void)hipGetLastError();
+        return MOIN_EHIP;
+    }
+    if (device >= n) return MOIN_EINVAL;
+    DeviceGuard guard(device);
+    if (!guard.ok) return MOIN_EHIP;
+    moin_ctx *ctx = new (std::nothrow) moin_ctx();
+    if (!ctx) return MOIN_ENOMEM;
+    ctx->device = device;
+    ctx->err_word = nullptr;
+    ctx->ws = nullptr;
+    ctx->ws_bytes = 0;
+    ctx->own_plan = nullptr;
+    ctx->timing = 0;
+    for (int i = 0; i < MOIN_K_COUNT; ++i) {
+        ctx->ms_sum[i] = 0.0;
+        ctx->launches[i] = 0;
+    }
+    if (prepare_kernels() != hipSuccess) {
+        delete ctx;
+        return MOIN_EHIP;
+    }
+    if (hipMalloc(reinterpret_cast<void **>(&ctx->err_word), 256) != hipSuccess) {
+        (void)hipGetLastError();
+        delete ctx;
+        return MOIN_ENOMEM;
+    }
+    if (hipMemset(ctx->err_word, 0, 256) != hipSuccess) {
+        (void)hipFree(ctx->err_word);
+        delete ctx;
+        return MOIN_EHIP;
+    }
+    *out = ctx;
+    return MOIN_OK;
+}
+
+void moin_destroy(moin_ctx *ctx)
+{
+    if (!ctx) return;
+    DeviceGuard guard(ctx->device);
+    (void)drain_spans(ctx);
+    for (hipEvent_t e : ctx->free_events) (void)hipEventDestroy(e);
+    if (ctx->own_plan) moin_plan_destroy(ctx->own_plan);
+    if (ctx->ws) (void)hipFree(ctx->ws);
+    if (ctx->err_word) (void)hipFree(ctx->err_word);
+    delete ctx;
+}
+
+const char *moin_strerror(int code)
+{
+    switch (code) {
+    case MOIN_OK: return "success";
+    case MOIN_EINVAL: return "invalid argument (null pointer, bad size, unsupported shape or alignment)";
+    case MOIN_ENOMEM: return "workspace allocation failed";
+    case MOIN_EHIP: return "HIP runtime call failed";
+    case MOIN_EDATA: return "device-side data fault (expert id out of range, bad offsets or ids)";
+    default: return "unknown moin status";
+    }
+}
+
+int moin_check(moin_ctx *ctx, void *stream)
+{
+    if (!ctx) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int word = 0;
+    if (hipMemcpyAsync(&word, ctx->err_word, sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return MOIN_EHIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return MOIN_EHIP;
+    if (word != 0) {
+        if (hipMemsetAsync(ctx->err_word, 0, sizeof(int), st) != hipSuccess) return MOIN_EHIP;
+        if (hipStreamSynchronize(st) != hipSuccess) return MOIN_EHIP;
+        return MOIN_EDATA;
+    }
+    return MOIN_OK;
+}
+
+int moin_route(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N, int32_t K,
+               int32_t D, moin_dtype dt, const int32_t *slot_of_centroid, uint32_t flags,
+               int32_t *expert_ids, int32_t *centroid_ids, int32_t *counts, void *stream)
+{
+    if (!ctx || N < 0 || K <= 0 || D <= 0) return MOIN_EINVAL;
+    if (dt != MOIN_BF16 && dt != MOIN_F32) return MOIN_EINVAL;
+    if (flags & ~MOIN_ROUTE_RETAINED_ONLY) return MOIN_EINVAL;
+    if ((flags & MOIN_ROUTE_RETAINED_ONLY) && !slot_of_centroid) return MOIN_EINVAL;
+    if (!centroids) return MOIN_EINVAL;
+    if (N > 0 && !emb) return MOIN_EINVAL;
+    if (dt == MOIN_BF16 ? (D % 8 != 0) : (D % 4 != 0)) return MOIN_EINVAL;
+    if (D > (1 << 20) || K > (1 << 28)) return MOIN_EINVAL;
+    if (misaligned(centroids, 16) || (emb && misaligned(emb, 16))) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    const size_t Kpad = align_up((size_t)K, 256);
+    const size_t cn_bytes = align_up(Kpad * 4, 256);
+    const bool need_cid_ws = counts && !centroid_ids && N > 0;
+    const int rc = ensure_ws(ctx, cn_bytes + (need_cid_ws ? (size_t)N * 4 : 0));
+    if (rc != MOIN_OK) return rc;
+
+    RouteArgs a;
+    a.emb = emb; a.cent = centroids; a.N = N; a.K = K; a.D = D;
+    a.is_bf16 = (dt == MOIN_BF16);
+    a.slot = slot_of_centroid;
+    a.retained_only = (flags & MOIN_ROUTE_RETAINED_ONLY) ? 1 : 0;
+    a.cnorm = static_cast<float *>(ctx->ws);
+    a.cid = centroid_ids ? centroid_ids
+                         : (need_cid_ws ? reinterpret_cast<int *>(static_cast<char *>(ctx->ws) + cn_bytes)
+                                        : nullptr);
+    a.expert_ids = expert_ids;
+
+    if (N > 0 && (a.cid || a.expert_ids)) {
+        if (timed(ctx, MOIN_K_ROUTE_AUX, st, [&] { return launch_centroid_norms(a, st); }) != hipSuccess)
+            return MOIN_EHIP;
+        if (timed(ctx, MOIN_K_ROUTE, st, [&] { return launch_route(a, st); }) != hipSuccess)
+            return MOIN_EHIP;
+    }
+    if (counts) {
+        if (timed(ctx, MOIN_K_ROUTE_AUX, st, [&] {
+                return launch_histogram(a.cid, N, K, counts, ctx->err_word, st);
+            }) != hipSuccess)
+            return MOIN_EHIP;
+    }
+    return MOIN_OK;
+}
+
+int moin_histogram(moin_ctx *ctx, const int32_t *ids, int64_t N, int32_t K, int32_t *counts,
+                   void *stream)
+{
+    if (!ctx || N < 0 || K <= 0 || !counts) return MOIN_EINVAL;
+    if (N > 0 && !ids) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (timed(ctx, MOIN_K_ROUTE_AUX, st, [&] {
+            return launch_histogram(ids, N, K, counts, ctx->err_word, st);
+        }) != hipSuccess)
+        return MOIN_EHIP;
+    return MOIN_OK;
+}
+
+int moin_plan_create(moin_ctx *ctx, moin_plan **out)
+{
+    if (!ctx || !out) return MOIN_EINVAL;
+    moin_plan *p = new (std::nothrow) moin_plan();
+    if (!p) return MOIN_ENOMEM;
+    p->buf = nullptr;
+    p->bytes = 0;
+    p->device = ctx->device;
+    p->built = 0;
+    *out = p;
+    return MOIN_OK;
+}
+
+void moin_plan_destroy(moin_plan *plan)
+{
+    if (!plan) return;
+    DeviceGuard guard(plan->device);
+    if (plan->buf) (void)hipFree(plan->buf);
+    delete plan;
+}
+
+int moin_plan_build(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
+                    const int32_t *expert_ids, int32_t S, int64_t T, int32_t E, void *stream)
+{
+    if (!ctx || !plan || plan->device != ctx->device) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    return plan_build_impl(ctx, plan, seq_offsets, expert_ids, S, T, E, static_cast<hipStream_t>(stream));
+}
+
+int moin_lora_linear_planned(moin_ctx *ctx, const moin_plan *plan, const void *x, const void *W,
+                             const void *A_stack, const void *B_stack, int32_t d_in, int32_t d_out,
+                             int32_t r, float scale, void *y, moin_dtype y_dt, void *stream)
+{
+    if (!ctx || !plan || plan->device != ctx->device) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    return linear_planned_impl(ctx, plan, x, W, A_stack, B_stack, d_in, d_out, r, scale, y, y_dt,
+                               static_cast<hipStream_t>(stream));
+}
+
+int moin_lora_linear(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
+                     const int32_t *expert_ids, int32_t S, int64_t T, const void *W,
+                     const void *A_stack, const void *B_stack, int32_t E, int32_t d_in,
+                     int32_t d_out, int32_t r, float scale, void *y, moin_dtype y_dt, void *stream)
+{
+    if (!ctx) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    if (!ctx->own_plan) {
+        const int rc = moin_plan_create(ctx, &ctx->own_plan);
+        if (rc != MOIN_OK) return rc;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc = plan_build_impl(ctx, ctx->own_plan, seq_offsets, expert_ids, S, T, E, st);
+    if (rc != MOIN_OK) return rc;
+    return linear_planned_impl(ctx, ctx->own_plan, x, W, A_stack, B_stack, d_in, d_out, r, scale, y,
+                               y_dt, st);
+}
+
+int moin_timing_enable(moin_ctx *ctx, int on)
+{
+    if (!ctx) return MOIN_EINVAL;
+    ctx->timing = on ? 1 : 0;
+    return MOIN_OK;
+}
+
+int moin_timing_reset(moin_ctx *ctx)
+{
+    if (!ctx) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    const int rc = drain_spans(ctx);
+    for (int i = 0; i < MOIN_K_COUNT; ++i) {
+        ctx->ms_sum[i] = 0.0;
+        ctx->launches[i] = 0;
+    }
+    return rc;
+}
+
+int moin_timing_read(moin_ctx *ctx, int kernel_id, double *ms_sum, int64_t *launches)
+{
+    if (!ctx || kernel_id < 0 || kernel_id >= MOIN_K_COUNT) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    const int rc = drain_spans(ctx);
+    if (ms_sum) *ms_sum = ctx->ms_sum[kernel_id];
+    if (launches) *launches = ctx->launches[kernel_id];
+    return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+// Internal launch interface between the C-ABI front end (api.cpp) and the HIP
+// kernels.  Every function only enqueues work on `stream`; shapes have been
+// validated by the caller.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moin {
+
+constexpr int TILE_M = 256;        // rows per plan tile (prefill)
+constexpr int DECODE_MAX_T = 1024; // batches up to this many tokens take the decode path
+
+// sticky error bits (device word)
+constexpr int ERR_BAD_EXPERT = 1;
+constexpr int ERR_BAD_OFFSETS = 2;
+constexpr int ERR_BAD_ID = 4;
+
+// Device-resident result of grouping a batch by expert.
+struct PlanView {
+    // prefill tiles (no tile spans two sequences; tiles sorted by expert)
+    int *tile_row0;    // [max_tiles] first token of the tile
+    int *tile_rows;    // [max_tiles] 1..TILE_M valid rows
+    int *tile_expert;  // [max_tiles] adapter slot or -1
+    int *n_tiles;      // [1]
+    // decode grouping (built only when T <= DECODE_MAX_T)
+    int *tok_sorted;   // [T] token index, grouped by expert
+    int *row_expert;   // [T] adapter slot or -1 of each token (original order)
+    int *grp_expert;   // [max_groups]
+    int *grp_start;    // [max_groups + 1] range in tok_sorted
+    int *n_groups;     // [1]
+    // scratch used while building
+    unsigned long long *keys; // [pow2 >= S]
+    int *tmp;                 // [4 * (S + 1)]
+    int max_tiles;
+    int max_groups;
+    int S;
+    int64_t T;
+    int E;
+    int decode;  // grouping arrays valid
+};
+
+hipError_t launch_plan(const PlanView &pv, const int *seq_offsets, const int *expert_ids,
+                       int *err_word, hipStream_t stream);
+
+struct LinearArgs {
+    const void *x, *W, *A_stack, *B_stack;
+    void *u_hi, *u_lo;     // [T, r] bf16 scratch
+    void *y;
+    int y_f32;
+    int d_in, d_out, r;
+    float scale;
+};
+
+hipError_t launch_prefill_shrink(const PlanView &pv, const LinearArgs &a, hipStream_t stream);
+hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStream_t stream);
+
+struct DecodeArgs {
+    LinearArgs lin;
+    void *ug_hi, *ug_lo;   // [T, r] bf16, indexed by position in tok_sorted
+    float *ylora;          // [T, d_out] fp32, original token order
+};
+hipError_t launch_decode_shrink(const PlanView &pv, const DecodeArgs &a, hipStream_t stream);
+hipError_t launch_decode_expand(const PlanView &pv, const DecodeArgs &a, hipStream_t stream);
+hipError_t launch_decode_base(const PlanView &pv, const DecodeArgs &a, hipStream_t stream);
+
+struct RouteArgs {
+    const void *emb, *cent;
+    int64_t N;
+    int K, D;
+    int is_bf16;
+    const int *slot;       // [K] or null
+    int retained_only;
+    float *cnorm;          // [K rounded up to 256] workspace
+    int *cid;              // [N] centroid ids (user buffer or workspace)
+    int *expert_ids;       // [N] or null
+};
+hipError_t launch_centroid_norms(const RouteArgs &a, hipStream_t stream);
+hipError_t launch_route(const RouteArgs &a, hipStream_t stream);
+hipError_t launch_histogram(const int *ids, int64_t N, int K, int *counts, int *err_word,
+                            hipStream_t stream);
+
+hipError_t prepare_kernels();  // one-time attribute set-up (large dynamic LDS)
+
+}  // namespace moin

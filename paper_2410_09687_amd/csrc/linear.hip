@@ -1,0 +1,286 @@
+// Prefill path of the routed LoRA linear layer (Section 3.2:
+// y = W x + W_b (W_a x), one adapter per sequence).
+//
+//   shrink : u = scale * x A_e^T, written as a bf16 pair (u_hi + u_lo) so the
+//            expand product sees ~16 significant bits of u.
+//   linear : y = x W^T + u_hi B_e^T + u_lo B_e^T  -- the adapter term is simply
+//            2r more contraction steps appended to the base GEMM of the same
+//            output tile, so y is written once, from one fp32 accumulator.
+// Tiles come from the plan: no tile spans two sequences, hence one adapter per
+// tile.  The same linear kernel, in a smaller tile shape, is the decode path's
+// base GEMM (it then adds the separately computed adapter term per token).
+#include "gemm_core.h"
+#include "kernels.h"
+
+namespace moin {
+
+struct LinearKParams {
+    const char *x, *W, *B_stack;
+    const char *u_hi, *u_lo;
+    char *y;
+    const int *tile_row0, *tile_rows, *tile_expert, *n_tiles;
+    const float *ylora;      // decode combine (null in prefill)
+    const int *row_expert;   // decode combine
+    int64_t T;
+    int d_in, d_out, r;
+    int n_tiles_n;
+    int y_f32;
+    int plain_tiles;         // 1: tiles are the regular grid over T, no adapters in-kernel
+};
+
+template <class C, class Issue>
+__device__ __forceinline__ void pipelined_blocks(char *smem, int total, Issue issue,
+                                                 typename C::Acc &acc)
+{
+    typename C::Stage g;
+    issue(0, g);
+    C::store_stage(smem, g);
+    __syncthreads();
+    for (int it = 0; it < total; ++it) {
+        char *cur = smem + (it & 1) * C::STAGE_BYTES;
+        char *nxt = smem + ((it + 1) & 1) * C::STAGE_BYTES;
+        const bool more = it + 1 < total;
+        if (more) issue(it + 1, g);
+        C::compute_stage(cur, acc);
+        if (more) C::store_stage(nxt, g);
+        __syncthreads();
+    }
+}
+
+template <class C>
+__global__ __launch_bounds__(C::NT) void linear_kernel(LinearKParams p)
+{
+    extern __shared__ __align__(16) char smem[];
+    int ntm, row0, rows, e;
+    int id;
+    if (p.plain_tiles) {
+        ntm = (int)((p.T + C::BM - 1) / C::BM);
+        id = xcd_band_id(blockIdx.x, ntm * p.n_tiles_n);
+        if (id < 0) return;
+        const int tm = id / p.n_tiles_n;
+        row0 = tm * C::BM;
+        rows = (int)min((int64_t)C::BM, p.T - row0);
+        e = -1;
+    } else {
+        // plan tiles are TILE_M rows; this kernel's BM divides TILE_M
+        constexpr int SUB = TILE_M / C::BM;
+        ntm = *p.n_tiles * SUB;
+        id = xcd_band_id(blockIdx.x, ntm * p.n_tiles_n);
+        if (id < 0) return;
+        const int tm = id / p.n_tiles_n;
+        const int t = tm / SUB, sub = tm % SUB;
+        rows = p.tile_rows[t] - sub * C::BM;
+        if (rows <= 0) return;
+        rows = min(rows, C::BM);
+        row0 = p.tile_row0[t] + sub * C::BM;
+        e = p.tile_expert[t];
+    }
+    const int tn = id % p.n_tiles_n;
+    const int n0 = tn * C::BN;
+    const int ncols = min(C::BN, p.d_out - n0);
+
+    const uint32_t ldx = (uint32_t)p.d_in * 2u, ldu = (uint32_t)p.r * 2u;
+    const bool lora = (e >= 0) && p.r > 0;
+    const auto vx = C::template make_view<C::A_CH>(p.x + (int64_t)row0 * ldx, ldx, rows);
+    const auto vw = C::template make_view<C::B_CH>(p.W + (int64_t)n0 * ldx, ldx, ncols);
+    // adapter operands; harmless aliases of x / W when the tile has no adapter
+    auto vu = C::template make_view<C::A_CH>(lora ? p.u_hi + (int64_t)row0 * ldu : p.x, ldu, rows);
+    const auto vb = C::template make_view<C::B_CH>(
+        lora ? p.B_stack + ((int64_t)e * p.d_out + n0) * ldu : p.W, ldu, ncols);
+    const int64_t hi_to_lo = p.u_lo - p.u_hi;
+
+    const int nkb0 = (p.d_in + C::BK - 1) / C::BK;
+    const int nkb1 = lora ? (p.r + C::BK - 1) / C::BK : 0;
+
+    typename C::Acc acc;
+    C::zero(acc);
+    auto issue = [&](int it, typename C::Stage &g) {
+        if (it < nkb0) {
+            C::load_stage(g, vx, vw, (uint32_t)it * (C::BK * 2), ldx);
+        } else {
+            int j = it - nkb0;
+            if (j == nkb1) vu.base += hi_to_lo;   // second pass: the remainder part of u
+            if (j >= nkb1) j -= nkb1;
+            C::load_stage(g, vu, vb, (uint32_t)j * (C::BK * 2), ldu);
+        }
+    };
+    pipelined_blocks<C>(smem, nkb0 + 2 * nkb1, issue, acc);
+
+    const int64_t ldy = (int64_t)p.d_out * (p.y_f32 ? 4 : 2);
+    char *yb = p.y + (int64_t)row0 * ldy;
+    C::epilogue(smem, acc, [&](int row, int col, float(&v)[8]) {
+        if (row >= rows || col >= ncols) return;
+        const int gc = n0 + col;
+        if (p.ylora != nullptr && p.row_expert[row0 + row] >= 0) {
+            const float *yl = p.ylora + (int64_t)(row0 + row) * p.d_out + gc;
+            const f32x4_t a = *reinterpret_cast<const f32x4_t *>(yl);
+            const f32x4_t b = *reinterpret_cast<const f32x4_t *>(yl + 4);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                v[q] += a[q];
+                v[q + 4] += b[q];
+            }
+        }
+        if (p.y_f32) {
+            float *dst = reinterpret_cast<float *>(yb + (int64_t)row * ldy) + gc;
+            *reinterpret_cast<f32x4_t *>(dst) = f32x4_t{v[0], v[1], v[2], v[3]};
+            *reinterpret_cast<f32x4_t *>(dst + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
+        } else {
+            uint4 o;
+            o.x = pack_bf16x2(v[0], v[1]);
+            o.y = pack_bf16x2(v[2], v[3]);
+            o.z = pack_bf16x2(v[4], v[5]);
+            o.w = pack_bf16x2(v[6], v[7]);
+            *reinterpret_cast<uint4 *>(yb + (int64_t)row * ldy + (int64_t)gc * 2) = o;
+        }
+    });
+}
+
+struct ShrinkKParams {
+    const char *x, *A_stack;
+    char *u_hi, *u_lo;
+    const int *tile_row0, *tile_rows, *tile_expert, *n_tiles;
+    int d_in, r;
+    int n_tiles_n;
+    float scale;
+};
+
+template <class C>
+__global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
+{
+    extern __shared__ __align__(16) char smem[];
+    constexpr int SUB = TILE_M / C::BM;
+    const int ntm = *p.n_tiles * SUB;
+    const int id = blockIdx.x;
+    if (id >= ntm * p.n_tiles_n) return;
+    const int tm = id / p.n_tiles_n, tn = id % p.n_tiles_n;
+    const int t = tm / SUB, sub = tm % SUB;
+    const int e = p.tile_expert[t];
+    int rows = p.tile_rows[t] - sub * C::BM;
+    if (e < 0 || rows <= 0) return;
+    rows = min(rows, C::BM);
+    const int row0 = p.tile_row0[t] + sub * C::BM;
+    const int n0 = tn * C::BN;
+    const int ncols = min(C::BN, p.r - n0);
+
+    const uint32_t ldx = (uint32_t)p.d_in * 2u;
+    const auto vx = C::template make_view<C::A_CH>(p.x + (int64_t)row0 * ldx, ldx, rows);
+    const auto va = C::template make_view<C::B_CH>(
+        p.A_stack + ((int64_t)e * p.r + n0) * ldx, ldx, ncols);
+    const int nkb = (p.d_in + C::BK - 1) / C::BK;
+
+    typename C::Acc acc;
+    C::zero(acc);
+    auto issue = [&](int it, typename C::Stage &g) {
+        C::load_stage(g, vx, va, (uint32_t)it * (C::BK * 2), ldx);
+    };
+    pipelined_blocks<C>(smem, nkb, issue, acc);
+
+    const int64_t ldu = (int64_t)p.r * 2;
+    char *uh = p.u_hi + (int64_t)row0 * ldu;
+    char *ul = p.u_lo + (int64_t)row0 * ldu;
+    const float s = p.scale;
+    C::epilogue(smem, acc, [&](int row, int col, float(&v)[8]) {
+        if (row >= rows || col >= ncols) return;
+        uint32_t h[8], l[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const float f = v[q] * s;
+            h[q] = f32_to_bf16_bits(f);
+            l[q] = f32_to_bf16_bits(f - bf16_bits_to_f32(h[q]));
+        }
+        uint4 oh, ol;
+        oh.x = h[0] | (h[1] << 16); oh.y = h[2] | (h[3] << 16);
+        oh.z = h[4] | (h[5] << 16); oh.w = h[6] | (h[7] << 16);
+        ol.x = l[0] | (l[1] << 16); ol.y = l[2] | (l[3] << 16);
+        ol.z = l[4] | (l[5] << 16); ol.w = l[6] | (l[7] << 16);
+        const int64_t off = (int64_t)row * ldu + (int64_t)(n0 + col) * 2;
+        *reinterpret_cast<uint4 *>(uh + off) = oh;
+        *reinterpret_cast<uint4 *>(ul + off) = ol;
+    });
+}
+
+// tile shapes
+using CfgMain = GemmCore<256, 256, 64, 4, 2>;   // 8 waves, wave patch 64 x 128
+using CfgShrink = GemmCore<64, 64, 64, 2, 2>;   // 4 waves, wave patch 32 x 32
+using CfgThin = GemmCore<128, 64, 64, 2, 2>;    // decode base GEMM: 4 waves, 64 x 32
+
+hipError_t prepare_linear_kernels()
+{
+    hipError_t e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_kernel<CfgMain>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, CfgMain::SMEM_BYTES);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_kernel<CfgThin>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, CfgThin::SMEM_BYTES);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&shrink_kernel<CfgShrink>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, CfgShrink::SMEM_BYTES);
+    return e;
+}
+
+static inline int round_up8(int v) { return (v + 7) & ~7; }
+
+hipError_t launch_prefill_shrink(const PlanView &pv, const LinearArgs &a, hipStream_t stream)
+{
+    using C = CfgShrink;
+    if (a.r <= 0 || pv.max_tiles <= 0) return hipSuccess;
+    ShrinkKParams p;
+    p.x = (const char *)a.x; p.A_stack = (const char *)a.A_stack;
+    p.u_hi = (char *)a.u_hi; p.u_lo = (char *)a.u_lo;
+    p.tile_row0 = pv.tile_row0; p.tile_rows = pv.tile_rows; p.tile_expert = pv.tile_expert;
+    p.n_tiles = pv.n_tiles;
+    p.d_in = a.d_in; p.r = a.r; p.scale = a.scale;
+    p.n_tiles_n = (a.r + C::BN - 1) / C::BN;
+    const int64_t grid = (int64_t)pv.max_tiles * (TILE_M / C::BM) * p.n_tiles_n;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(shrink_kernel<C>, dim3((unsigned)grid), dim3(C::NT), C::SMEM_BYTES, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStream_t stream)
+{
+    using C = CfgMain;
+    if (pv.max_tiles <= 0) return hipSuccess;
+    LinearKParams p;
+    p.x = (const char *)a.x; p.W = (const char *)a.W; p.B_stack = (const char *)a.B_stack;
+    p.u_hi = (const char *)a.u_hi; p.u_lo = (const char *)a.u_lo;
+    p.y = (char *)a.y;
+    p.tile_row0 = pv.tile_row0; p.tile_rows = pv.tile_rows; p.tile_expert = pv.tile_expert;
+    p.n_tiles = pv.n_tiles;
+    p.ylora = nullptr; p.row_expert = nullptr;
+    p.T = pv.T;
+    p.d_in = a.d_in; p.d_out = a.d_out; p.r = a.r;
+    p.n_tiles_n = (a.d_out + C::BN - 1) / C::BN;
+    p.y_f32 = a.y_f32;
+    p.plain_tiles = 0;
+    const int64_t grid = (int64_t)round_up8(pv.max_tiles * (TILE_M / C::BM) * p.n_tiles_n) ;
+    if ((int64_t)pv.max_tiles * p.n_tiles_n > 0x7ffffff0LL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(linear_kernel<C>, dim3((unsigned)grid), dim3(C::NT), C::SMEM_BYTES, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_base(const PlanView &pv, const DecodeArgs &d, hipStream_t stream)
+{
+    using C = CfgThin;
+    const LinearArgs &a = d.lin;
+    if (pv.T <= 0) return hipSuccess;
+    LinearKParams p;
+    p.x = (const char *)a.x; p.W = (const char *)a.W; p.B_stack = nullptr;
+    p.u_hi = nullptr; p.u_lo = nullptr;
+    p.y = (char *)a.y;
+    p.tile_row0 = nullptr; p.tile_rows = nullptr; p.tile_expert = nullptr; p.n_tiles = nullptr;
+    p.ylora = (a.r > 0) ? d.ylora : nullptr;
+    p.row_expert = pv.row_expert;
+    p.T = pv.T;
+    p.d_in = a.d_in; p.d_out = a.d_out; p.r = 0;
+    p.n_tiles_n = (a.d_out + C::BN - 1) / C::BN;
+    p.y_f32 = a.y_f32;
+    p.plain_tiles = 1;
+    const int ntm = (int)((pv.T + C::BM - 1) / C::BM);
+    const int grid = round_up8(ntm * p.n_tiles_n);
+    hipLaunchKernelGGL(linear_kernel<C>, dim3((unsigned)grid), dim3(C::NT), C::SMEM_BYTES, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace moin

@@ -1,0 +1,165 @@
+// Grouping of a batch by expert: sequences are sorted by (expert id, sequence
+// index) and cut into row tiles that never span two sequences, so every tile
+// has exactly one adapter (Section 1: one expert per query; Section 4.1: id -1
+// = no adapter, base model only).  For small batches the tokens themselves are
+// also grouped by expert, so that the decode kernels read each distinct
+// adapter once.  Everything happens on the device in one workgroup: the host
+// never looks at the ids.
+#include "kernels.h"
+
+namespace moin {
+
+constexpr int PLAN_THREADS = 1024;
+
+// In-place exclusive prefix sum of data[0..n) by one workgroup; returns the total.
+__device__ int block_exclusive_scan(int *data, int n, int *lds /* PLAN_THREADS + 1 ints */)
+{
+    const int tid = threadIdx.x;
+    const int per = (n + PLAN_THREADS - 1) / PLAN_THREADS;
+    const int lo = min(tid * per, n), hi = min(lo + per, n);
+    int sum = 0;
+    for (int i = lo; i < hi; ++i) sum += data[i];
+    lds[tid] = sum;
+    __syncthreads();
+    // Hillis-Steele inclusive scan over the per-thread sums
+    for (int off = 1; off < PLAN_THREADS; off <<= 1) {
+        const int v = (tid >= off) ? lds[tid - off] : 0;
+        __syncthreads();
+        lds[tid] += v;
+        __syncthreads();
+    }
+    const int total = lds[PLAN_THREADS - 1];
+    int run = lds[tid] - sum;
+    __syncthreads();
+    for (int i = lo; i < hi; ++i) {
+        const int v = data[i];
+        data[i] = run;
+        run += v;
+    }
+    __syncthreads();
+    return total;
+}
+
+__global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const int *seq_offsets,
+                                                            const int *expert_ids, int *err_word)
+{
+    __shared__ int lds[PLAN_THREADS + 1];
+    const int tid = threadIdx.x;
+    const int S = pv.S;
+    const int T = (int)pv.T;
+    int npow2 = 1;
+    while (npow2 < S) npow2 <<= 1;
+
+    int *lens = pv.tmp;                  // [S]   length of each sequence (by sequence)
+    int *a1 = pv.tmp + (S + 1);          // [S+1] per sorted position: tile count -> tile base
+    int *a2 = pv.tmp + 2 * (S + 1);      // [S+1] per sorted position: length -> token base
+    int *a3 = pv.tmp + 3 * (S + 1);      // [S+1] per sorted position: group head flag -> group id
+
+    // 1. validate, build sort keys (expert + 1 in the high word: -1 sorts first)
+    int err = 0;
+    if (tid == 0 && (seq_offsets[0] != 0 || seq_offsets[S] != T)) err |= ERR_BAD_OFFSETS;
+    for (int s = tid; s < npow2; s += PLAN_THREADS) {
+        unsigned long long key = ~0ull;
+        if (s < S) {
+            int lo = seq_offsets[s], hi = seq_offsets[s + 1];
+            int e = expert_ids[s];
+            if (lo < 0 || hi > T || hi < lo) {
+                err |= ERR_BAD_OFFSETS;
+                lo = 0;
+                hi = 0;
+            }
+            if (e < -1 || e >= pv.E) {
+                err |= ERR_BAD_EXPERT;
+                e = -1;
+            }
+            lens[s] = hi - lo;
+            key = ((unsigned long long)(unsigned)(e + 1) << 32) | (unsigned)s;
+        }
+        pv.keys[s] = key;
+    }
+    if (err) atomicOr(err_word, err);
+    if (pv.decode)   // tokens that no (valid) sequence covers stay base-only
+        for (int t = tid; t < T; t += PLAN_THREADS) pv.row_expert[t] = -1;
+    __syncthreads();
+
+    // 2. bitonic sort of the keys (workgroup-wide, in global memory)
+    for (int k = 2; k <= npow2; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = tid; i < npow2; i += PLAN_THREADS) {
+                const int l = i ^ j;
+                if (l > i) {
+                    const unsigned long long a = pv.keys[i], b = pv.keys[l];
+                    const bool up = (i & k) == 0;
+                    if ((a > b) == up) {
+                        pv.keys[i] = b;
+                        pv.keys[l] = a;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    // 3. per sorted position: tile count, token count, group-head flag
+    for (int p = tid; p < S; p += PLAN_THREADS) {
+        const unsigned long long key = pv.keys[p];
+        const int s = (int)(key & 0xffffffffu);
+        const int len = lens[s];
+        a1[p] = (len + TILE_M - 1) / TILE_M;
+        a2[p] = len;
+        const bool head = (p == 0) || ((pv.keys[p - 1] >> 32) != (key >> 32));
+        a3[p] = head ? 1 : 0;
+    }
+    __syncthreads();
+    const int n_tiles = block_exclusive_scan(a1, S, lds);
+    if (tid == 0) *pv.n_tiles = min(n_tiles, pv.max_tiles);
+    int n_groups = 0;
+    if (pv.decode) {
+        const int n_tok = block_exclusive_scan(a2, S, lds);
+        n_groups = block_exclusive_scan(a3, S, lds);   // a3[p] = groups before p
+        if (tid == 0) {
+            *pv.n_groups = n_groups;
+            pv.grp_start[n_groups] = min(n_tok, T);
+        }
+    }
+
+    // 4. emit
+    for (int p = tid; p < S; p += PLAN_THREADS) {
+        const unsigned long long key = pv.keys[p];
+        const int s = (int)(key & 0xffffffffu);
+        const int e = (int)(key >> 32) - 1;
+        const int lo = seq_offsets[s];
+        const int len = lens[s];
+        const int tb = a1[p];
+        for (int j = 0, left = len; left > 0 && tb + j < pv.max_tiles; ++j, left -= TILE_M) {
+            pv.tile_row0[tb + j] = lo + j * TILE_M;
+            pv.tile_rows[tb + j] = min(left, TILE_M);
+            pv.tile_expert[tb + j] = e;
+        }
+        if (pv.decode) {
+            // offsets that overlap (flagged above) could list more than T
+            // tokens; everything past T is dropped
+            const int base = min(a2[p], T);
+            for (int j = 0; j < len && base + j < T; ++j) {
+                pv.tok_sorted[base + j] = lo + j;
+                pv.row_expert[lo + j] = e;
+            }
+            const bool head = (p == 0) || ((pv.keys[p - 1] >> 32) != (key >> 32));
+            if (head) {
+                const int gi = a3[p];   // exclusive count of heads before p
+                pv.grp_expert[gi] = e;
+                pv.grp_start[gi] = base;
+            }
+        }
+    }
+}
+
+hipError_t launch_plan(const PlanView &pv, const int *seq_offsets, const int *expert_ids,
+                       int *err_word, hipStream_t stream)
+{
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, stream, pv, seq_offsets,
+                       expert_ids, err_word);
+    return hipGetLastError();
+}
+
+}  // namespace moin

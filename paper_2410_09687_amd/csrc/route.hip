@@ -1,0 +1,303 @@
+// Nearest-topic routing (Section 3.3: nearest-neighbour search of the query
+// embedding over the topic embeddings; Section 3.1: those are the K-means
+// centres) and the per-topic histogram (Figure 3).
+//
+// bf16 path: argmin_k ||q - c_k||^2 = argmin_k (||c_k||^2 - 2 q.c_k); the dot
+// products are one dense bf16 MFMA contraction [K x D] . [D x N].  Centroids
+// are the MFMA row operand and queries the column operand, so one lane holds
+// 16 centroid scores of a single query per accumulator and the running
+// (score, index) minimum lives in registers; nothing but the winning index
+// ever leaves the workgroup.  A workgroup owns 256 queries and sweeps all
+// centroid tiles in ascending order, which makes "lowest index wins a tie"
+// fall out of a strict '<'.
+// fp32 path: small inputs only; direct sum of squared differences in fp32.
+#include "gemm_core.h"
+#include "kernels.h"
+
+namespace moin {
+
+using CfgRoute = GemmCore<256, 256, 64, 4, 2>;  // rows: centroids, cols: queries
+
+struct RouteKParams {
+    const char *emb, *cent;
+    const float *cnorm;   // [K padded to a multiple of 256]; +inf for excluded / padding
+    const int *slot;
+    int *cid;
+    int *expert_ids;
+    int64_t N;
+    int K, D;
+};
+
+__device__ __forceinline__ bool lex_less(float v, int i, float bv, int bi)
+{
+    return (v < bv) || (v == bv && i < bi);
+}
+
+template <class C>
+__global__ __launch_bounds__(C::NT) void route_kernel(RouteKParams p)
+{
+    extern __shared__ __align__(16) char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int wm = wave / C::WN, wn = wave % C::WN;
+    const int64_t q0 = (int64_t)blockIdx.x * C::BN;
+    const int nq = (int)min((int64_t)C::BN, p.N - q0);
+    const uint32_t ld = (uint32_t)p.D * 2u;
+    const int nkb = (p.D + C::BK - 1) / C::BK;
+    const int nct = (p.K + C::BM - 1) / C::BM;
+
+    const auto vq = C::template make_view<C::B_CH>(p.emb + q0 * (int64_t)ld, ld, nq);
+
+    float bestv[C::FN];
+    int besti[C::FN];
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j) {
+        bestv[j] = __builtin_inff();
+        besti[j] = 0;
+    }
+
+    typename C::Acc acc;
+    C::zero(acc);
+    typename C::Stage g;
+    const int total = nct * nkb;
+
+    auto issue = [&](int it) {
+        const int ct = it / nkb, kb = it - ct * nkb;
+        const int crow = ct * C::BM;
+        const auto vc = C::template make_view<C::A_CH>(p.cent + (int64_t)crow * ld, ld,
+                                                       min(C::BM, p.K - crow));
+        C::load_stage(g, vc, vq, (uint32_t)kb * (C::BK * 2), ld);
+    };
+
+    issue(0);
+    C::store_stage(smem, g);
+    __syncthreads();
+    int kb = 0, ct = 0;
+    for (int it = 0; it < total; ++it) {
+        char *cur = smem + (it & 1) * C::STAGE_BYTES;
+        char *nxt = smem + ((it + 1) & 1) * C::STAGE_BYTES;
+        const bool more = it + 1 < total;
+        if (more) issue(it + 1);
+        C::compute_stage(cur, acc);
+        if (++kb == nkb) {
+            // scores of this centroid tile: ascending centroid index within a lane
+            const float *cn = p.cnorm + ct * C::BM + wm * C::WTM + 4 * (lane >> 5);
+#pragma unroll
+            for (int i = 0; i < C::FM; ++i) {
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    const f32x4_t c4 = *reinterpret_cast<const f32x4_t *>(cn + i * 32 + e4 * 8);
+                    const int idx0 = ct * C::BM + wm * C::WTM + i * 32 + e4 * 8 + 4 * (lane >> 5);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                        for (int j = 0; j < C::FN; ++j) {
+                            const float s = fmaf(-2.f, acc.v[i][j][e4 * 4 + q], c4[q]);
+                            const bool lt = s < bestv[j];
+                            bestv[j] = lt ? s : bestv[j];
+                            besti[j] = lt ? idx0 + q : besti[j];
+                        }
+                    }
+                }
+            }
+            C::zero(acc);
+            kb = 0;
+            ++ct;
+        }
+        if (more) C::store_stage(nxt, g);
+        __syncthreads();
+    }
+
+    // merge the two lane halves (rows 4*(lane>>5) interleave), then the WM waves
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j) {
+        const float ov = __shfl_xor(bestv[j], 32);
+        const int oi = __shfl_xor(besti[j], 32);
+        if (lex_less(ov, oi, bestv[j], besti[j])) {
+            bestv[j] = ov;
+            besti[j] = oi;
+        }
+    }
+    float *sv = reinterpret_cast<float *>(smem);                  // [WM][BN]
+    int *si = reinterpret_cast<int *>(smem + C::WM * C::BN * 4);  // [WM][BN]
+    if (lane < 32) {
+#pragma unroll
+        for (int j = 0; j < C::FN; ++j) {
+            const int col = wn * C::WTN + j * 32 + lane;
+            sv[wm * C::BN + col] = bestv[j];
+            si[wm * C::BN + col] = besti[j];
+        }
+    }
+    __syncthreads();
+    for (int col = threadIdx.x; col < nq; col += C::NT) {
+        float bv = sv[col];
+        int bi = si[col];
+#pragma unroll
+        for (int w = 1; w < C::WM; ++w) {
+            const float v = sv[w * C::BN + col];
+            const int i = si[w * C::BN + col];
+            if (lex_less(v, i, bv, bi)) {
+                bv = v;
+                bi = i;
+            }
+        }
+        if (p.cid) p.cid[q0 + col] = bi;
+        if (p.expert_ids) p.expert_ids[q0 + col] = p.slot ? p.slot[bi] : bi;
+    }
+}
+
+// ||c_k||^2 in fp32 (one wave per centroid), +inf for centroids left out of the
+// search and for the padding up to a multiple of 256.
+__global__ __launch_bounds__(256) void centroid_norm_kernel(const char *cent, int K, int Kpad,
+                                                            int D, int is_bf16, const int *slot,
+                                                            int retained_only, float *cnorm)
+{
+    const int lane = threadIdx.x & 63;
+    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (k >= Kpad) return;
+    float acc = 0.f;
+    if (k < K) {
+        if (is_bf16) {
+            const uint16_t *c = reinterpret_cast<const uint16_t *>(cent) + (int64_t)k * D;
+            for (int j = lane; j < D; j += 64) {
+                const float v = bf16_bits_to_f32(c[j]);
+                acc = fmaf(v, v, acc);
+            }
+        } else {
+            const float *c = reinterpret_cast<const float *>(cent) + (int64_t)k * D;
+            for (int j = lane; j < D; j += 64) acc = fmaf(c[j], c[j], acc);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+        if (retained_only && slot[k] < 0) acc = __builtin_inff();
+    } else {
+        acc = __builtin_inff();
+    }
+    if (lane == 0) cnorm[k] = acc;
+}
+
+// fp32 embeddings: one wave per query, direct sum of squared differences.
+// cnorm is only consulted for its +inf marks (centroids left out of the search).
+__global__ __launch_bounds__(256) void route_f32_kernel(const float *emb, const float *cent,
+                                                        const float *cnorm, int64_t N, int K, int D,
+                                                        const int *slot, int *cid, int *expert_ids)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= N) return;
+    const float *q = emb + i * D;
+    float bv = __builtin_inff();
+    int bi = 0;
+    for (int k = 0; k < K; ++k) {
+        const float *c = cent + (int64_t)k * D;
+        float acc = 0.f;
+        for (int j = lane; j < D; j += 64) {
+            const float d = q[j] - c[j];
+            acc = fmaf(d, d, acc);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+        if (cnorm[k] == __builtin_inff()) acc = __builtin_inff();
+        if (acc < bv) {
+            bv = acc;
+            bi = k;
+        }
+    }
+    if (lane == 0) {
+        if (cid) cid[i] = bi;
+        if (expert_ids) expert_ids[i] = slot ? slot[bi] : bi;
+    }
+}
+
+// counts[k] = #{i : ids[i] == k}.  Workgroups tally a slice of ids in LDS and
+// flush the non-zero bins with integer atomics (order-independent, exact).
+constexpr int HIST_LDS_BINS = 16384;
+__global__ __launch_bounds__(1024) void histogram_kernel(const int *ids, int64_t N, int K,
+                                                         int *counts, int *err_word)
+{
+    __shared__ int bins[HIST_LDS_BINS];
+    const bool use_lds = K <= HIST_LDS_BINS;
+    if (use_lds) {
+        for (int k = threadIdx.x; k < K; k += blockDim.x) bins[k] = 0;
+        __syncthreads();
+    }
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    bool bad = false;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N; i += stride) {
+        const int id = ids[i];
+        if (id < 0 || id >= K) {
+            bad = true;
+            continue;
+        }
+        if (use_lds) atomicAdd(&bins[id], 1);
+        else atomicAdd(&counts[id], 1);
+    }
+    if (bad) atomicOr(err_word, ERR_BAD_ID);
+    if (use_lds) {
+        __syncthreads();
+        for (int k = threadIdx.x; k < K; k += blockDim.x)
+            if (bins[k]) atomicAdd(&counts[k], bins[k]);
+    }
+}
+
+// Plain fill: a memset node recorded into a captured graph is unreliable on
+// this platform, a kernel is not.
+__global__ __launch_bounds__(256) void fill_i32_kernel(int *dst, int n, int value)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dst[i] = value;
+}
+
+hipError_t prepare_route_kernels()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&route_kernel<CfgRoute>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, CfgRoute::SMEM_BYTES);
+}
+
+hipError_t launch_centroid_norms(const RouteArgs &a, hipStream_t stream)
+{
+    const int Kpad = (a.K + 255) / 256 * 256;
+    hipLaunchKernelGGL(centroid_norm_kernel, dim3((Kpad + 3) / 4), dim3(256), 0, stream,
+                       (const char *)a.cent, a.K, Kpad, a.D, a.is_bf16, a.slot, a.retained_only,
+                       a.cnorm);
+    return hipGetLastError();
+}
+
+hipError_t launch_route(const RouteArgs &a, hipStream_t stream)
+{
+    if (a.N <= 0) return hipSuccess;
+    if (a.is_bf16) {
+        using C = CfgRoute;
+        RouteKParams p;
+        p.emb = (const char *)a.emb; p.cent = (const char *)a.cent;
+        p.cnorm = a.cnorm; p.slot = a.slot; p.cid = a.cid; p.expert_ids = a.expert_ids;
+        p.N = a.N; p.K = a.K; p.D = a.D;
+        const int64_t grid = (a.N + C::BN - 1) / C::BN;
+        if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(route_kernel<C>, dim3((unsigned)grid), dim3(C::NT), C::SMEM_BYTES,
+                           stream, p);
+    } else {
+        const int64_t grid = (a.N + 3) / 4;
+        if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(route_f32_kernel, dim3((unsigned)grid), dim3(256), 0, stream,
+                           (const float *)a.emb, (const float *)a.cent, a.cnorm, a.N, a.K, a.D,
+                           a.slot, a.cid, a.expert_ids);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_histogram(const int *ids, int64_t N, int K, int *counts, int *err_word,
+                            hipStream_t stream)
+{
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((K + 255) / 256), dim3(256), 0, stream, counts, K, 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || N <= 0) return e;
+    int64_t blocks = (N + 1024 * 16 - 1) / (1024 * 16);
+    if (blocks > 1024) blocks = 1024;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(histogram_kernel, dim3((unsigned)blocks), dim3(1024), 0, stream, ids, N, K,
+                       counts, err_word);
+    return hipGetLastError();
+}
+
+}  // namespace moin

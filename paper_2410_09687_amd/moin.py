@@ -1,0 +1,263 @@
+"""Thin ctypes binding of ``libmoin.so`` -- argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, passes their
+device pointers and the current torch stream across the C ABI declared in
+``include/moin.h`` and returns torch tensors.  No step of the method runs
+here, and there is no fallback: without the built library, or with tensors
+that are not on a GPU, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoin.so")
+
+MOIN_F32, MOIN_BF16 = 0, 1
+MOIN_ROUTE_RETAINED_ONLY = 1
+K_PLAN, K_SHRINK, K_LINEAR, K_ROUTE, K_ROUTE_AUX, K_DECODE_SHRINK, K_DECODE_EXPAND, K_DECODE_BASE = range(8)
+KERNEL_NAMES = ["plan", "shrink", "linear", "route", "route_aux", "decode_shrink", "decode_expand",
+                "decode_base"]
+
+EXPORTS = [
+    "moin_create", "moin_destroy", "moin_strerror", "moin_check", "moin_route", "moin_histogram",
+    "moin_lora_linear", "moin_plan_create", "moin_plan_destroy", "moin_plan_build",
+    "moin_lora_linear_planned", "moin_timing_enable", "moin_timing_reset", "moin_timing_read",
+]
+
+_lib = None
+
+
+class MoinError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {_strerror(code)} (code {code})")
+
+
+def load() -> ctypes.CDLL:
+    """Opens libmoin.so; a missing library is a hard error (build it with
+    ``python -m paper_2410_09687_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2410_09687_amd.build`; "
+            "there is no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp, i32, i64, u32 = c.c_void_p, c.c_int32, c.c_int64, c.c_uint32
+    lib.moin_create.argtypes = [c.POINTER(vp), c.c_int]
+    lib.moin_destroy.argtypes = [vp]
+    lib.moin_destroy.restype = None
+    lib.moin_strerror.argtypes = [c.c_int]
+    lib.moin_strerror.restype = c.c_char_p
+    lib.moin_check.argtypes = [vp, vp]
+    lib.moin_route.argtypes = [vp, vp, vp, i64, i32, i32, c.c_int, vp, u32, vp, vp, vp, vp]
+    lib.moin_histogram.argtypes = [vp, vp, i64, i32, vp, vp]
+    lib.moin_lora_linear.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp, i32, i32, i32, i32,
+                                     c.c_float, vp, c.c_int, vp]
+    lib.moin_plan_create.argtypes = [vp, c.POINTER(vp)]
+    lib.moin_plan_destroy.argtypes = [vp]
+    lib.moin_plan_destroy.restype = None
+    lib.moin_plan_build.argtypes = [vp, vp, vp, vp, i32, i64, i32, vp]
+    lib.moin_lora_linear_planned.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, c.c_float, vp,
+                                             c.c_int, vp]
+    lib.moin_timing_enable.argtypes = [vp, c.c_int]
+    lib.moin_timing_reset.argtypes = [vp]
+    lib.moin_timing_read.argtypes = [vp, c.c_int, c.POINTER(c.c_double), c.POINTER(i64)]
+    for name in EXPORTS:
+        if name not in ("moin_destroy", "moin_plan_destroy", "moin_strerror"):
+            getattr(lib, name).restype = c.c_int
+    _lib = lib
+    return lib
+
+
+def _strerror(code: int) -> str:
+    return load().moin_strerror(int(code)).decode()
+
+
+def _ck(code: int, what: str):
+    if code != 0:
+        raise MoinError(code, what)
+
+
+def _dev_ptr(t: Optional[torch.Tensor], name: str, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream=None):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+class Context:
+    """Owns a ``moin_ctx`` (workspace, sticky error word, timing slots)."""
+
+    def __init__(self, device: int = 0):
+        self._h = ctypes.c_void_p()
+        _ck(load().moin_create(ctypes.byref(self._h), int(device)), "moin_create")
+        self.device = int(device)
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            load().moin_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def check(self, stream=None) -> None:
+        """Synchronises the stream; raises ``MoinError`` on a device-side data fault."""
+        _ck(load().moin_check(self._h, _stream_ptr(stream)), "moin_check")
+
+    def timing_enable(self, on: bool = True):
+        _ck(load().moin_timing_enable(self._h, int(on)), "moin_timing_enable")
+
+    def timing_reset(self):
+        _ck(load().moin_timing_reset(self._h), "moin_timing_reset")
+
+    def timing_read(self, kernel_id: int):
+        ms, n = ctypes.c_double(0), ctypes.c_int64(0)
+        _ck(load().moin_timing_read(self._h, int(kernel_id), ctypes.byref(ms), ctypes.byref(n)),
+            "moin_timing_read")
+        return ms.value, n.value
+
+
+def moin_route(ctx: Context, emb: torch.Tensor, centroids: torch.Tensor,
+               slot_of_centroid: Optional[torch.Tensor] = None, retained_only: bool = False,
+               want_centroid_ids: bool = True, want_counts: bool = False, stream=None):
+    """Returns ``(expert_ids, centroid_ids or None, counts or None)`` as int32 tensors."""
+    if emb.dim() != 2 or centroids.dim() != 2 or emb.shape[1] != centroids.shape[1]:
+        raise ValueError("emb [N,D] and centroids [K,D] expected")
+    if emb.dtype != centroids.dtype or emb.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("emb/centroids must both be float32 or both bfloat16")
+    N, D = emb.shape
+    K = centroids.shape[0]
+    dt = MOIN_BF16 if emb.dtype == torch.bfloat16 else MOIN_F32
+    dev = centroids.device
+    expert_ids = torch.empty(N, dtype=torch.int32, device=dev)
+    cids = torch.empty(N, dtype=torch.int32, device=dev) if want_centroid_ids else None
+    counts = torch.empty(K, dtype=torch.int32, device=dev) if want_counts else None
+    _ck(load().moin_route(ctx._h, _dev_ptr(emb, "emb") if N else None, _dev_ptr(centroids, "centroids"),
+                          N, K, D, dt, _dev_ptr(slot_of_centroid, "slot_of_centroid", torch.int32),
+                          MOIN_ROUTE_RETAINED_ONLY if retained_only else 0,
+                          _dev_ptr(expert_ids, "expert_ids") if N else None,
+                          _dev_ptr(cids, "centroid_ids") if (cids is not None and N) else None,
+                          _dev_ptr(counts, "counts"), _stream_ptr(stream)), "moin_route")
+    return expert_ids, cids, counts
+
+
+def moin_histogram(ctx: Context, ids: torch.Tensor, K: int, stream=None) -> torch.Tensor:
+    counts = torch.empty(K, dtype=torch.int32, device=ids.device)
+    _ck(load().moin_histogram(ctx._h, _dev_ptr(ids, "ids", torch.int32) if ids.numel() else None,
+                              ids.numel(), K, _dev_ptr(counts, "counts"), _stream_ptr(stream)),
+        "moin_histogram")
+    return counts
+
+
+def _y_out(x, d_out, y_dtype, out):
+    if y_dtype not in (torch.bfloat16, torch.float32):
+        raise TypeError("y dtype must be bfloat16 or float32")
+    if out is None:
+        out = torch.empty((x.shape[0], d_out), dtype=y_dtype, device=x.device)
+    elif out.shape != (x.shape[0], d_out) or out.dtype != y_dtype:
+        raise ValueError("out has the wrong shape or dtype")
+    return out, (MOIN_BF16 if y_dtype == torch.bfloat16 else MOIN_F32)
+
+
+def _stack_dims(W, A_stack, B_stack):
+    d_out, d_in = W.shape
+    if A_stack is None or B_stack is None:
+        return d_in, d_out, 0, 0
+    E, r = A_stack.shape[0], A_stack.shape[1]
+    if tuple(A_stack.shape) != (E, r, d_in) or tuple(B_stack.shape) != (E, d_out, r):
+        raise ValueError("A_stack [E,r,d_in] / B_stack [E,d_out,r] shape mismatch")
+    return d_in, d_out, E, r
+
+
+def moin_lora_linear(ctx: Context, x: torch.Tensor, seq_offsets: torch.Tensor,
+                     expert_ids: torch.Tensor, W: torch.Tensor, A_stack: Optional[torch.Tensor],
+                     B_stack: Optional[torch.Tensor], scale: float, y_dtype=torch.bfloat16,
+                     out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    if x.dim() != 2 or W.dim() != 2 or x.shape[1] != W.shape[1]:
+        raise ValueError("x [T,d_in] and W [d_out,d_in] expected")
+    d_in, d_out, E, r = _stack_dims(W, A_stack, B_stack)
+    S = expert_ids.numel()
+    if seq_offsets.numel() != S + 1:
+        raise ValueError("seq_offsets must have S+1 entries")
+    T = x.shape[0]
+    y, ydt = _y_out(x, d_out, y_dtype, out)
+    bf = torch.bfloat16
+    _ck(load().moin_lora_linear(
+        ctx._h, _dev_ptr(x, "x", bf) if T else None, _dev_ptr(seq_offsets, "seq_offsets", torch.int32),
+        _dev_ptr(expert_ids, "expert_ids", torch.int32) if S else None, S, T, _dev_ptr(W, "W", bf),
+        _dev_ptr(A_stack, "A_stack", bf), _dev_ptr(B_stack, "B_stack", bf), E, d_in, d_out, r,
+        float(scale), _dev_ptr(y, "y") if T else None, ydt, _stream_ptr(stream)), "moin_lora_linear")
+    return y
+
+
+class Plan:
+    """Grouping of one batch by expert, reusable by every projection of a layer."""
+
+    def __init__(self, ctx: Context):
+        self.ctx = ctx
+        self._h = ctypes.c_void_p()
+        _ck(load().moin_plan_create(ctx._h, ctypes.byref(self._h)), "moin_plan_create")
+        self.T = self.S = self.E = 0
+
+    def build(self, seq_offsets: torch.Tensor, expert_ids: torch.Tensor, T: int, E: int, stream=None):
+        S = expert_ids.numel()
+        if seq_offsets.numel() != S + 1:
+            raise ValueError("seq_offsets must have S+1 entries")
+        _ck(load().moin_plan_build(self.ctx._h, self._h, _dev_ptr(seq_offsets, "seq_offsets", torch.int32),
+                                   _dev_ptr(expert_ids, "expert_ids", torch.int32) if S else None,
+                                   S, T, E, _stream_ptr(stream)), "moin_plan_build")
+        self.T, self.S, self.E = T, S, E
+        return self
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            load().moin_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def moin_lora_linear_planned(ctx: Context, plan: Plan, x: torch.Tensor, W: torch.Tensor,
+                             A_stack: Optional[torch.Tensor], B_stack: Optional[torch.Tensor],
+                             scale: float, y_dtype=torch.bfloat16, out: Optional[torch.Tensor] = None,
+                             stream=None) -> torch.Tensor:
+    if x.dim() != 2 or W.dim() != 2 or x.shape[1] != W.shape[1] or x.shape[0] != plan.T:
+        raise ValueError("x [T,d_in] (T as planned) and W [d_out,d_in] expected")
+    d_in, d_out, E, r = _stack_dims(W, A_stack, B_stack)
+    if E and E != plan.E:
+        raise ValueError("stack holds a different number of experts than the plan was built for")
+    y, ydt = _y_out(x, d_out, y_dtype, out)
+    bf = torch.bfloat16
+    T = x.shape[0]
+    _ck(load().moin_lora_linear_planned(
+        ctx._h, plan._h, _dev_ptr(x, "x", bf) if T else None, _dev_ptr(W, "W", bf),
+        _dev_ptr(A_stack, "A_stack", bf), _dev_ptr(B_stack, "B_stack", bf), d_in, d_out, r,
+        float(scale), _dev_ptr(y, "y") if T else None, ydt, _stream_ptr(stream)),
+        "moin_lora_linear_planned")
+    return y

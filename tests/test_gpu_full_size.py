@@ -1,0 +1,94 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py
+times: sampled outputs the oracle computes one by one, plus properties that
+hold at any size."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2410_09687_amd import moin
+from paper_2410_09687_amd import workloads as wl
+from tests import gpu_common as gc
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_rows(T, seq_offsets, n_random, seed):
+    """First and last rows of the batch and of a few sequences, plus random rows."""
+    rng = np.random.default_rng(seed)
+    off = seq_offsets.cpu().numpy()
+    picks = {0, T - 1}
+    for s in rng.choice(len(off) - 1, size=min(8, len(off) - 1), replace=False):
+        if off[s + 1] > off[s]:
+            picks.update({int(off[s]), int(off[s + 1] - 1)})
+    picks.update(int(v) for v in rng.integers(0, T, size=n_random))
+    return np.array(sorted(picks), dtype=np.int64)
+
+
+def test_prefill_q_proj_full_size():
+    w = wl.config_prefill()
+    inp = wl.make_linear_inputs(w, "cuda")
+    rows = _sample_rows(w.T, inp.seq_offsets, 360, seed=1)
+    ref = gc.oracle_rows(inp, rows)
+    for dt in (torch.bfloat16, torch.float32):
+        print(f"[gpu] c1 full size y={dt}", flush=True)
+        y = gc.run_linear(inp, dt)
+        print(gc.compare_linear(y, ref, rows, what=f"c1/{dt}"), flush=True)
+        assert torch.isfinite(y.float()).all()
+
+
+def test_decode_mlp_full_size():
+    for w in wl.config_decode():
+        inp = wl.make_linear_inputs(w, "cuda")
+        ref = gc.oracle_rows(inp)
+        for dt in (torch.bfloat16, torch.float32):
+            print(f"[gpu] {w.name} y={dt}", flush=True)
+            y = gc.run_linear(inp, dt)
+            print(gc.compare_linear(y, ref, what=f"{w.name}/{dt}"), flush=True)
+        del inp
+        torch.cuda.empty_cache()
+
+
+def test_router_full_size():
+    rw = wl.config_router()
+    rin = wl.make_route_inputs(rw, "cuda")
+    print("[gpu] c3 router full size", flush=True)
+    eids, cids, counts = moin.moin_route(gc.ctx(), rin.emb, rin.centroids, want_counts=True)
+    gc.ctx().check()
+    # properties at full size: histogram is the exact tally of the ids returned
+    assert counts.sum().item() == rw.N
+    assert torch.equal(counts.long(), torch.bincount(cids.long(), minlength=rw.K))
+    # sampled queries against the oracle (every 256th + the ragged ends)
+    sample = np.unique(np.concatenate([np.arange(0, rw.N, 256), [rw.N - 1, rw.N - 255, 255, 256]]))
+    n_band = gc.check_route(rin.emb, rin.centroids, cids, sample=sample)
+    print(f"[gpu] c3: {sample.size} sampled queries, {n_band} differ inside the near-tie band", flush=True)
+
+
+def test_layer_chain_full_size():
+    """Seven projections of one layer chained through their bf16 outputs; each
+    projection is checked against the oracle run on the GPU's actual input."""
+    wls = wl.config_layer()
+    T = wls[0].T
+    ids = wl.draw_expert_ids(wls[0].S, wls[0].E, "zipf", 1.5, wls[0].seed * 8 + 4)
+    c = gc.ctx()
+    off = torch.from_numpy(wl.seq_offsets_of(wls[0].seq_lens)).cuda()
+    eids = torch.from_numpy(ids).cuda()
+    plan = moin.Plan(c).build(off, eids, T, wls[0].E)
+    h0 = wl._randn_bf16((T, 2048), 1.0, torch.device("cuda"), 4242)
+    outs = {}
+    src = {"q": "h0", "k": "h0", "v": "h0", "o": "q", "gate": "o", "up": "o", "down": "gate"}
+    outs["h0"] = h0
+    rows = _sample_rows(T, off, 40, seed=2)
+    for w in wls:
+        name = w.name.split("_", 1)[1]
+        x = outs[src[name]]
+        inp = wl.make_linear_inputs(w, "cuda", expert_ids=ids, x=x)
+        print(f"[gpu] c4 {name} {w.d_in}->{w.d_out}", flush=True)
+        y = moin.moin_lora_linear_planned(c, plan, inp.x, inp.W, inp.A_stack, inp.B_stack, w.scale)
+        c.check()
+        ref = gc.oracle_rows(inp, rows)
+        print(name, gc.compare_linear(y, ref, rows, what=f"c4/{name}"), flush=True)
+        if name in ("q", "o", "gate"):
+            outs[name] = y
+        del inp
+        torch.cuda.empty_cache()
+    plan.close()

@@ -1,0 +1,89 @@
+"""GPU parity of moin_route / moin_histogram (through the C ABI) against the
+CPU oracle: ids exact outside the 1e-4 near-tie band, histograms exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2410_09687_amd import moin
+from paper_2410_09687_amd import workloads as wl
+from tests import gpu_common as gc
+
+pytestmark = pytest.mark.gpu
+
+
+def _route_case(N, K, D, dtype, normalise, seed):
+    return wl.make_route_inputs(wl.RouteWorkload("t", N, K, D, dtype, normalise, seed), "cuda")
+
+
+@pytest.mark.parametrize("N,K,D", [(700, 300, 96), (256, 256, 64), (1, 1, 8), (513, 1000, 200)])
+def test_bf16_router_small(N, K, D):
+    rin = _route_case(N, K, D, "bf16", True, seed=N + K)
+    print(f"[gpu] route bf16 N={N} K={K} D={D}", flush=True)
+    eids, cids, counts = moin.moin_route(gc.ctx(), rin.emb, rin.centroids, want_counts=True)
+    gc.ctx().check()
+    gc.check_route(rin.emb, rin.centroids, cids)
+    assert torch.equal(eids, cids)
+    assert torch.equal(counts.long(), torch.bincount(cids.long(), minlength=K))
+
+
+def test_f32_router_small():
+    rin = _route_case(300, 77, 100, "f32", False, seed=3)
+    eids, cids, counts = moin.moin_route(gc.ctx(), rin.emb, rin.centroids, want_counts=True)
+    gc.ctx().check()
+    gc.check_route(rin.emb, rin.centroids, cids)
+    assert counts.sum().item() == 300
+
+
+def test_queries_equal_centroids_and_duplicates():
+    rin = _route_case(8, 600, 128, "bf16", True, seed=9)
+    cent = rin.centroids.clone()
+    cent[400] = cent[17]                       # duplicate: lowest index must win
+    eids, cids, counts = moin.moin_route(gc.ctx(), cent, cent, want_counts=True)
+    gc.ctx().check()
+    expect = torch.arange(600, device="cuda", dtype=torch.int32)
+    expect[400] = 17
+    assert torch.equal(cids, expect)
+    assert counts[17].item() == 2 and counts[400].item() == 0 and counts.sum().item() == 600
+
+
+def test_slot_map_and_retained_only_search():
+    rin = _route_case(900, 260, 64, "bf16", True, seed=21)
+    table = wl.retained_slot_table(260, 231, seed=4)
+    slots = torch.from_numpy(table).cuda()
+    eids, cids, _ = moin.moin_route(gc.ctx(), rin.emb, rin.centroids, slot_of_centroid=slots)
+    gc.ctx().check()
+    gc.check_route(rin.emb, rin.centroids, cids)
+    assert np.array_equal(eids.cpu().numpy(), oracle.slot_map(cids.cpu().numpy(), table))
+    assert (eids == -1).any()
+    eids2, cids2, counts2 = moin.moin_route(gc.ctx(), rin.emb, rin.centroids, slot_of_centroid=slots,
+                                            retained_only=True, want_counts=True)
+    gc.ctx().check()
+    gc.check_route(rin.emb, rin.centroids, cids2, eligible=table >= 0)
+    assert (eids2 >= 0).all()
+    assert counts2[torch.from_numpy(table < 0).cuda()].sum().item() == 0
+
+
+def test_histogram_alone_and_bad_ids():
+    ids = torch.randint(0, 5000, (200_000,), device="cuda", dtype=torch.int32)
+    counts = moin.moin_histogram(gc.ctx(), ids, 5000)
+    gc.ctx().check()
+    assert np.array_equal(counts.cpu().numpy(), oracle.histogram(ids.cpu().numpy(), 5000))
+    big = moin.moin_histogram(gc.ctx(), ids, 40_000)      # more bins than the LDS tally holds
+    assert torch.equal(big[:5000], counts) and big[5000:].sum().item() == 0
+    ids[5] = 7000
+    moin.moin_histogram(gc.ctx(), ids, 5000)
+    with pytest.raises(moin.MoinError):
+        gc.ctx().check()
+    assert moin.moin_histogram(gc.ctx(), ids[:0], 16).sum().item() == 0
+    gc.ctx().check()
+
+
+def test_route_argument_errors():
+    rin = _route_case(16, 16, 64, "bf16", True, seed=2)
+    with pytest.raises(moin.MoinError):
+        moin.moin_route(gc.ctx(), rin.emb[:, :12].contiguous(), rin.centroids[:, :12].contiguous())
+    with pytest.raises(moin.MoinError):
+        moin.moin_route(gc.ctx(), rin.emb, rin.centroids, retained_only=True)
+    e, c, _ = moin.moin_route(gc.ctx(), rin.emb[:0], rin.centroids)
+    assert e.numel() == 0
