@@ -228,6 +228,24 @@ int plan_build_impl(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
     return MOIN_OK;
 }
 
+// Host-checkable faults of a linear call; nothing is launched when this fails.
+int validate_linear(const void *x, const void *W, const void *A_stack, const void *B_stack,
+                    int32_t E, int32_t d_in, int32_t d_out, int32_t r, float scale, const void *y,
+                    moin_dtype y_dt)
+{
+    if (!x || !W || !y) return MOIN_EINVAL;
+    if (d_in <= 0 || d_out <= 0 || r < 0 || E < 0) return MOIN_EINVAL;
+    if (d_in % 8 || d_out % 8 || r % 8) return MOIN_EINVAL;
+    if (d_in > (1 << 22) || d_out > (1 << 24) || r > (1 << 16)) return MOIN_EINVAL;
+    if (y_dt != MOIN_BF16 && y_dt != MOIN_F32) return MOIN_EINVAL;
+    if (misaligned(x, 16) || misaligned(W, 16) || misaligned(y, 16)) return MOIN_EINVAL;
+    if (E > 0 && r > 0 &&
+        (!A_stack || !B_stack || misaligned(A_stack, 16) || misaligned(B_stack, 16)))
+        return MOIN_EINVAL;
+    if (!(scale == scale)) return MOIN_EINVAL;
+    return MOIN_OK;
+}
+
 int linear_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, const void *W,
                         const void *A_stack, const void *B_stack, int32_t d_in, int32_t d_out,
                         int32_t r, float scale, void *y, moin_dtype y_dt, hipStream_t stream)
@@ -235,16 +253,9 @@ int linear_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, con
     if (!plan->built) return MOIN_EINVAL;
     const PlanView &pv = plan->pv;
     if (pv.S == 0 || pv.T == 0) return MOIN_OK;
-    if (!x || !W || !y) return MOIN_EINVAL;
-    if (d_in <= 0 || d_out <= 0 || r < 0) return MOIN_EINVAL;
-    if (d_in % 8 || d_out % 8 || r % 8) return MOIN_EINVAL;
-    if (d_in > (1 << 22) || d_out > (1 << 24) || r > (1 << 16)) return MOIN_EINVAL;
-    if (y_dt != MOIN_BF16 && y_dt != MOIN_F32) return MOIN_EINVAL;
-    if (misaligned(x, 16) || misaligned(W, 16) || misaligned(y, 16)) return MOIN_EINVAL;
+    const int vrc = validate_linear(x, W, A_stack, B_stack, pv.E, d_in, d_out, r, scale, y, y_dt);
+    if (vrc != MOIN_OK) return vrc;
     const bool adapters = pv.E > 0 && r > 0;
-    if (adapters && (!A_stack || !B_stack || misaligned(A_stack, 16) || misaligned(B_stack, 16)))
-        return MOIN_EINVAL;
-    if (!(scale == scale)) return MOIN_EINVAL;
 
     LinearArgs a;
     a.x = x; a.W = W; a.A_stack = A_stack; a.B_stack = B_stack;
@@ -500,6 +511,11 @@ int moin_lora_linear(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
         if (rc != MOIN_OK) return rc;
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (S < 0 || T < 0 || E < 0) return MOIN_EINVAL;
+    if (S > 0 && T > 0) {
+        const int vrc = validate_linear(x, W, A_stack, B_stack, E, d_in, d_out, r, scale, y, y_dt);
+        if (vrc != MOIN_OK) return vrc;
+    }
     int rc = plan_build_impl(ctx, ctx->own_plan, seq_offsets, expert_ids, S, T, E, st);
     if (rc != MOIN_OK) return rc;
     return linear_planned_impl(ctx, ctx->own_plan, x, W, A_stack, B_stack, d_in, d_out, r, scale, y,
