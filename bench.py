@@ -33,9 +33,11 @@ from paper_2410_09687_amd import workloads as wl  # noqa: E402
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM bytes per launch of the dominant (linear) kernel from rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE runs (see profiles/); None until measured.
-LINEAR_KERNEL_TRAFFIC_BYTES = None
+# HBM-side bytes per launch of the dominant (linear) kernel on configs[1], from the
+# rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised in
+# profiles/prefill_q_proj_hbm_traffic.md: (2.0 * 209204 KiB + 1.0 * 131072 KiB) * 1024,
+# the factors being what the same counters read for a plain 1 GiB copy.
+LINEAR_KERNEL_TRAFFIC_BYTES = int((2.0 * 209204.2 + 1.0 * 131072.0) * 1024)
 
 
 def timed_region(fn, steps, warmup):
@@ -234,6 +236,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-mib", type=int, default=0,
+                    help="first run a plain device copy of this many MiB (3 times): the known-size "
+                         "kernel that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--also", default="decode,router",
                     help="comma list of extra workloads to report: decode,router,layer (or 'none')")
     args = ap.parse_args()
@@ -245,6 +250,13 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.copy_mib > 0:
+        src = torch.empty(args.copy_mib << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     ctx = moin.Context(0)
     res = bench_prefill(ctx, args.steps, args.warmup, not args.no_cpu_baseline)
     extra = [s for s in args.also.split(",") if s and s != "none"]
