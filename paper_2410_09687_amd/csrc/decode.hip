@@ -37,10 +37,10 @@ __global__ __launch_bounds__(256) void decode_shrink_kernel(
 {
     __shared__ float red[4][64][4];
     const int g = blockIdx.x;
-    if (g >= *n_groups) return;
-    const int e = grp_expert[g];
+    if (g >= uniform(*n_groups)) return;
+    const int e = uniform(grp_expert[g]);
     if (e < 0) return;
-    const int gs = grp_start[g], ge = grp_start[g + 1];
+    const int gs = uniform(grp_start[g]), ge = uniform(grp_start[g + 1]);
     if (ge <= gs) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j0 = blockIdx.y * 16;
@@ -56,12 +56,20 @@ __global__ __launch_bounds__(256) void decode_shrink_kernel(
         const bool tvalid = pos < ge;
         const char *xrow = x + (int64_t)(tvalid ? tok_sorted[pos] : 0) * ld;
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
-        for (int ks = wave; ks < nks; ks += 4) {
-            const int k = ks * 32 + kq;
-            const bf16x8_t a = ldg_frag(arow, k, d_in);
-            const bf16x8_t b = ldg_frag(xrow, k, d_in);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
+        // UNR independent load pairs in flight per lane before the MFMAs that
+        // consume them; steps past the row end are zero-masked by ldg_frag
+        constexpr int UNR = 8;
+        for (int ks0 = wave; ks0 < nks; ks0 += 4 * UNR) {
+            bf16x8_t a[UNR], b[UNR];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const int k = (ks0 + 4 * u) * 32 + kq;
+                a[u] = ldg_frag(arow, k, d_in);
+                b[u] = ldg_frag(xrow, k, d_in);
+            }
+#pragma unroll
+            for (int u = 0; u < UNR; ++u)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b[u], acc, 0, 0, 0);
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) red[wave][lane][i] = acc[i];
@@ -95,10 +103,10 @@ __global__ __launch_bounds__(256) void decode_expand_kernel(
     const int *grp_expert, const int *grp_start, const int *n_groups, int d_out, int r)
 {
     const int g = blockIdx.x;
-    if (g >= *n_groups) return;
-    const int e = grp_expert[g];
+    if (g >= uniform(*n_groups)) return;
+    const int e = uniform(grp_expert[g]);
     if (e < 0) return;
-    const int gs = grp_start[g], ge = grp_start[g + 1];
+    const int gs = uniform(grp_start[g]), ge = uniform(grp_start[g + 1]);
     if (ge <= gs) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int o_base = blockIdx.y * 256 + wave * 64;

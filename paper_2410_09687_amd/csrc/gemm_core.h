@@ -5,8 +5,13 @@
 // a lane can fetch the 8 consecutive bf16 that v_mfma_f32_32x32x16_bf16 wants
 // with one 16-byte load.  A workgroup tile is BM x BN x BK; waves form a
 // WM x WN grid and each owns a (BM/WM) x (BN/WN) patch made of 32x32 MFMA
-// accumulators.  Global -> registers -> LDS staging, two LDS stages, one
-// barrier per BK block.
+// accumulators.  Two ways of staging operands in LDS:
+//   GemmCore : global -> registers -> LDS, rows padded by 16 B, two stages.
+//              Handles any contraction length (the tail block is zero-filled).
+//   DmaCore  : global -> LDS directly (global_load_lds_dwordx4), NS stages in
+//              flight, unpadded rows with an XOR swizzle of the 16-byte chunks.
+//              Needs the contraction length to be a multiple of BK.
+// One barrier per BK block in both.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -33,6 +38,11 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
 }
 
+// Values read from global memory with a workgroup-uniform address are uniform,
+// but the compiler cannot know; telling it keeps control flow and addressing
+// that depend on them on the scalar unit.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
 // Workgroups are handed to the 8 XCDs round-robin by linear id.  Remap so that
 // each XCD works through one contiguous band of logical tile ids (its L2 then
 // sees the same operand slabs from neighbouring tiles).  `total` logical ids;
@@ -48,8 +58,55 @@ __device__ __forceinline__ int xcd_band_id(int bid, int total)
     return (slot < per && id < total) ? id : -1;
 }
 
+// Row of the 32x32 accumulator that element e of a lane belongs to; the column
+// is lane % 32.
+__device__ __forceinline__ int mfma32_acc_row(int e, int lane)
+{
+    return 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+}
+
+// Hands a wave's accumulator patch to `emit(row, col, v[8])`, 8 consecutive
+// columns of one row at a time (row/col relative to the workgroup tile), by
+// transposing 32-row bands through the wave's private LDS scratch, so that
+// global stores can be 16 bytes per lane and row-contiguous.  All waves must
+// have passed a barrier after their last read of the staging buffers.
+template <class C, typename Emit>
+__device__ __forceinline__ void tile_epilogue(char *smem, const typename C::Acc &acc, Emit emit)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int wm = wave / C::WN, wn = wave % C::WN;
+    float *scr = reinterpret_cast<float *>(smem + wave * C::SCR_BYTES);
+    constexpr int LPR = C::WTN / 8;   // lanes per row when reading back
+    constexpr int RPASS = 64 / LPR;   // rows per read pass
+#pragma unroll
+    for (int i = 0; i < C::FM; ++i) {
+#pragma unroll
+        for (int j = 0; j < C::FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                scr[mfma32_acc_row(e, lane) * C::SCR_PITCH + j * 32 + (lane & 31)] = acc.v[i][j][e];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int p = 0; p < 32 / RPASS; ++p) {
+            const int rr = p * RPASS + lane / LPR;
+            const int cc = (lane % LPR) * 8;
+            const f32x4_t lo = *reinterpret_cast<const f32x4_t *>(scr + rr * C::SCR_PITCH + cc);
+            const f32x4_t hi = *reinterpret_cast<const f32x4_t *>(scr + rr * C::SCR_PITCH + cc + 4);
+            float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            emit(wm * C::WTM + i * 32 + rr, wn * C::WTN + cc, v);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
+
 template <int BM_, int BN_, int BK_, int WM_, int WN_>
 struct GemmCore {
+    static constexpr bool IS_DMA = false;
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
     static constexpr int NT = 64 * WM * WN;          // threads per workgroup
     static constexpr int KCH = BK / 8;               // 16-byte chunks per tile row
@@ -182,50 +239,201 @@ struct GemmCore {
         }
     }
 
-    // Row of the 32x32 accumulator that element e of a lane belongs to; the
-    // column is lane % 32.
-    __device__ static __forceinline__ int acc_row(int e, int lane)
-    {
-        return 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-    }
-
-    // Hands the wave's patch to `emit(row, col, v[8])`, 8 consecutive columns
-    // of one row at a time (row/col relative to the workgroup tile), by
-    // transposing 32-row bands through the wave's private LDS scratch.  All
-    // waves must have passed a barrier after their last compute_stage.
     template <typename Emit>
     __device__ static __forceinline__ void epilogue(char *smem, const Acc &acc, Emit emit)
     {
-        const int lane = threadIdx.x & 63;
-        const int wave = threadIdx.x >> 6;
-        const int wm = wave / WN, wn = wave % WN;
-        float *scr = reinterpret_cast<float *>(smem + wave * SCR_BYTES);
-        constexpr int LPR = WTN / 8;      // lanes per row when reading back
-        constexpr int RPASS = 64 / LPR;   // rows per read pass
+        tile_epilogue<GemmCore>(smem, acc, emit);
+    }
+};
+
+// Main loop of the register-staged core over `total` BK blocks; `issue(it, g)`
+// loads block `it` into the staging registers.
+template <class C, class Issue>
+__device__ __forceinline__ void pipelined_blocks(char *smem, int total, Issue issue,
+                                                 typename C::Acc &acc)
+{
+    typename C::Stage g;
+    issue(0, g);
+    C::store_stage(smem, g);
+    __syncthreads();
+    for (int it = 0; it < total; ++it) {
+        char *cur = smem + (it & 1) * C::STAGE_BYTES;
+        char *nxt = smem + ((it + 1) & 1) * C::STAGE_BYTES;
+        const bool more = it + 1 < total;
+        if (more) issue(it + 1, g);
+        C::compute_stage(cur, acc);
+        if (more) C::store_stage(nxt, g);
+        __syncthreads();
+    }
+}
+
+#define MOIN_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define MOIN_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+// Waits until at most N of this wave's vector-memory operations are still in
+// flight (they retire in order), then meets the other waves at the barrier.
+// The "memory" clobber keeps the compiler from moving LDS accesses across it.
+template <int N>
+__device__ __forceinline__ void wait_vm_then_barrier()
+{
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int NS_>
+struct DmaCore {
+    static constexpr bool IS_DMA = true;
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, NS = NS_;
+    static constexpr int NW = WM * WN, NT = 64 * NW;
+    static constexpr int KCH = BK / 8;                 // 16-byte chunks per tile row
+    static constexpr int ROWB = BK * 2;                // LDS row pitch: no padding
+    static constexpr int RPI = 64 / KCH;               // tile rows one wave instruction fills
+    static constexpr int A_I = BM / RPI / NW;          // load instructions per wave per block
+    static constexpr int B_I = BN / RPI / NW;
+    static constexpr int LPB = A_I + B_I;
+    static constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int WTM = BM / WM, WTN = BN / WN;
+    static constexpr int FM = WTM / 32, FN = WTN / 32;
+    static constexpr int KSTEPS = BK / 16;
+    static constexpr int SCR_PITCH = WTN + 4;
+    static constexpr int SCR_BYTES = 32 * SCR_PITCH * 4;
+    static constexpr int SMEM_BYTES =
+        (NS * STAGE_BYTES > NW * SCR_BYTES) ? NS * STAGE_BYTES : NW * SCR_BYTES;
+
+    static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "load mapping");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % 16 == 0 && NS >= 2, "tiling");
+    static_assert((NS - 2) * LPB < 64, "vmcnt field");
+
+    struct Acc {
+        f32x16_t v[FM][FN];
+    };
+
+    __device__ static __forceinline__ void zero(Acc &acc)
+    {
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
             for (int j = 0; j < FN; ++j)
 #pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    scr[acc_row(e, lane) * SCR_PITCH + j * 32 + (lane & 31)] = acc.v[i][j][e];
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                for (int e = 0; e < 16; ++e) acc.v[i][j][e] = 0.f;
+    }
+
+    // A wave instruction writes 64 consecutive 16-byte slots of LDS, so LDS slot
+    // p of an operand tile is (row p / KCH, physical chunk p % KCH).  The lane
+    // that fills it fetches logical chunk (p % KCH) ^ swz(row) from global
+    // memory; readers apply the same XOR.  With swz(row) = (row >> 1) % KCH the
+    // ds_read_b128 of 32 consecutive rows at one logical chunk is conflict-free.
+    __device__ static __forceinline__ int swz(int row) { return (row >> 1) & (KCH - 1); }
+
+    // For each of its wave's NI load instructions: the tile row this lane
+    // fetches and the byte offset of its (swizzled) 16-byte chunk inside a BK
+    // block.  Independent of the row pitch, so one table serves every operand
+    // that shares the tile's row range (x and u; W and B_e).
+    template <int NI>
+    struct Lanes {
+        uint32_t row[NI];
+        uint32_t c16[NI];
+    };
+
+    // Rows past `rows` re-read the last valid row (their results are masked by
+    // the epilogue).  rows >= 1.
+    template <int NI>
+    __device__ static __forceinline__ Lanes<NI> make_lanes(int rows)
+    {
+        Lanes<NI> o;
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
-            for (int p = 0; p < 32 / RPASS; ++p) {
-                const int rr = p * RPASS + lane / LPR;
-                const int cc = (lane % LPR) * 8;
-                const f32x4_t lo = *reinterpret_cast<const f32x4_t *>(scr + rr * SCR_PITCH + cc);
-                const f32x4_t hi = *reinterpret_cast<const f32x4_t *>(scr + rr * SCR_PITCH + cc + 4);
-                float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                emit(wm * WTM + i * 32 + rr, wn * WTN + cc, v);
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (int j = 0; j < NI; ++j) {
+            const int row = (wave * NI + j) * RPI + lane / KCH;
+            o.row[j] = (uint32_t)min(row, rows - 1);
+            o.c16[j] = (uint32_t)(((lane % KCH) ^ swz(row)) * 16);
+        }
+        return o;
+    }
+
+    // Starts the loads of one BK block (byte offset kbyte inside the rows) of
+    // both operands into `stage`.  a / b: uniform pointers to (first tile row,
+    // k = 0); lda / ldb: row pitches in bytes; (rows - 1) * pitch + pitch must
+    // fit 32 bits.
+    __device__ static __forceinline__ void issue(char *stage, const char *a, uint32_t lda,
+                                                 const Lanes<A_I> &la, const char *b, uint32_t ldb,
+                                                 const Lanes<B_I> &lb, uint32_t kbyte)
+    {
+        const int wave = threadIdx.x >> 6;
+#pragma unroll
+        for (int j = 0; j < A_I; ++j)
+            __builtin_amdgcn_global_load_lds(
+                MOIN_GPTR(a + (la.row[j] * lda + la.c16[j] + kbyte)),
+                MOIN_LPTR(stage + (wave * A_I + j) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int j = 0; j < B_I; ++j)
+            __builtin_amdgcn_global_load_lds(
+                MOIN_GPTR(b + (lb.row[j] * ldb + lb.c16[j] + kbyte)),
+                MOIN_LPTR(stage + A_BYTES + (wave * B_I + j) * 1024), 16, 0, 0);
+    }
+
+    __device__ static __forceinline__ void compute_stage(const char *stage, Acc &acc)
+    {
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int wm = wave / WN, wn = wave % WN;
+        const int r = lane & 31, h = lane >> 5;
+        // patch bases are multiples of 32 rows, so the swizzle depends on r only
+        const int f = swz(r);
+        const char *pa = stage + (wm * WTM + r) * ROWB;
+        const char *pb = stage + A_BYTES + (wn * WTN + r) * ROWB;
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            bf16x8_t a[FM], b[FN];
+            const int o = (((ks * 2 + h) ^ f) & (KCH - 1)) * 16;
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+                a[i] = __builtin_bit_cast(
+                    bf16x8_t, *reinterpret_cast<const uint4 *>(pa + i * 32 * ROWB + o));
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                b[j] = __builtin_bit_cast(
+                    bf16x8_t, *reinterpret_cast<const uint4 *>(pb + j * 32 * ROWB + o));
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc.v[i][j] =
+                        __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc.v[i][j], 0, 0, 0);
         }
     }
+
+    template <typename Emit>
+    __device__ static __forceinline__ void epilogue(char *smem, const Acc &acc, Emit emit)
+    {
+        tile_epilogue<DmaCore>(smem, acc, emit);
+    }
 };
+
+// Main loop of the direct-to-LDS core.  `issue(it, stage)` starts the loads of
+// block `it` into `stage`; NS - 1 blocks are kept in flight.  `after(it)` runs
+// after block `it` has been accumulated (router: fold a finished centroid tile).
+// Ends with a barrier, so the staging buffers may be reused at once.
+template <class C, class Issue, class After>
+__device__ __forceinline__ void dma_pipelined_blocks(char *smem, int total, Issue issue,
+                                                     typename C::Acc &acc, After after)
+{
+#pragma unroll
+    for (int s = 0; s < C::NS - 1; ++s)
+        if (s < total) issue(s, smem + s * C::STAGE_BYTES);
+    int st = 0;   // stage that holds block `it`
+    for (int it = 0; it < total; ++it) {
+        // everything but the newest NS - 2 blocks has landed => block `it` is in LDS;
+        // past the barrier every wave is done with block it - 1, whose stage is reused
+        if (it + C::NS - 2 < total) wait_vm_then_barrier<(C::NS - 2) * C::LPB>();
+        else wait_vm_then_barrier<0>();
+        const int nb = it + C::NS - 1;
+        const int ns = (st == 0) ? C::NS - 1 : st - 1;
+        if (nb < total) issue(nb, smem + ns * C::STAGE_BYTES);
+        C::compute_stage(smem + st * C::STAGE_BYTES, acc);
+        after(it);
+        st = (st + 1 == C::NS) ? 0 : st + 1;
+    }
+    __syncthreads();
+}
 
 }  // namespace moin

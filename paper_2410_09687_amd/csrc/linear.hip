@@ -28,25 +28,6 @@ struct LinearKParams {
     int plain_tiles;         // 1: tiles are the regular grid over T, no adapters in-kernel
 };
 
-template <class C, class Issue>
-__device__ __forceinline__ void pipelined_blocks(char *smem, int total, Issue issue,
-                                                 typename C::Acc &acc)
-{
-    typename C::Stage g;
-    issue(0, g);
-    C::store_stage(smem, g);
-    __syncthreads();
-    for (int it = 0; it < total; ++it) {
-        char *cur = smem + (it & 1) * C::STAGE_BYTES;
-        char *nxt = smem + ((it + 1) & 1) * C::STAGE_BYTES;
-        const bool more = it + 1 < total;
-        if (more) issue(it + 1, g);
-        C::compute_stage(cur, acc);
-        if (more) C::store_stage(nxt, g);
-        __syncthreads();
-    }
-}
-
 template <class C>
 __global__ __launch_bounds__(C::NT) void linear_kernel(LinearKParams p)
 {
@@ -57,54 +38,93 @@ __global__ __launch_bounds__(C::NT) void linear_kernel(LinearKParams p)
         ntm = (int)((p.T + C::BM - 1) / C::BM);
         id = xcd_band_id(blockIdx.x, ntm * p.n_tiles_n);
         if (id < 0) return;
-        const int tm = id / p.n_tiles_n;
+        const int tm = uniform(id / p.n_tiles_n);
         row0 = tm * C::BM;
         rows = (int)min((int64_t)C::BM, p.T - row0);
         e = -1;
     } else {
         // plan tiles are TILE_M rows; this kernel's BM divides TILE_M
         constexpr int SUB = TILE_M / C::BM;
-        ntm = *p.n_tiles * SUB;
+        ntm = uniform(*p.n_tiles) * SUB;
         id = xcd_band_id(blockIdx.x, ntm * p.n_tiles_n);
         if (id < 0) return;
-        const int tm = id / p.n_tiles_n;
+        const int tm = uniform(id / p.n_tiles_n);
         const int t = tm / SUB, sub = tm % SUB;
-        rows = p.tile_rows[t] - sub * C::BM;
+        rows = uniform(p.tile_rows[t]) - sub * C::BM;
         if (rows <= 0) return;
         rows = min(rows, C::BM);
-        row0 = p.tile_row0[t] + sub * C::BM;
-        e = p.tile_expert[t];
+        row0 = uniform(p.tile_row0[t]) + sub * C::BM;
+        e = uniform(p.tile_expert[t]);
     }
-    const int tn = id % p.n_tiles_n;
+    const int tn = uniform(id % p.n_tiles_n);
     const int n0 = tn * C::BN;
     const int ncols = min(C::BN, p.d_out - n0);
 
     const uint32_t ldx = (uint32_t)p.d_in * 2u, ldu = (uint32_t)p.r * 2u;
     const bool lora = (e >= 0) && p.r > 0;
-    const auto vx = C::template make_view<C::A_CH>(p.x + (int64_t)row0 * ldx, ldx, rows);
-    const auto vw = C::template make_view<C::B_CH>(p.W + (int64_t)n0 * ldx, ldx, ncols);
-    // adapter operands; harmless aliases of x / W when the tile has no adapter
-    auto vu = C::template make_view<C::A_CH>(lora ? p.u_hi + (int64_t)row0 * ldu : p.x, ldu, rows);
-    const auto vb = C::template make_view<C::B_CH>(
-        lora ? p.B_stack + ((int64_t)e * p.d_out + n0) * ldu : p.W, ldu, ncols);
-    const int64_t hi_to_lo = p.u_lo - p.u_hi;
-
     const int nkb0 = (p.d_in + C::BK - 1) / C::BK;
     const int nkb1 = lora ? (p.r + C::BK - 1) / C::BK : 0;
+    // adapter operands are harmless aliases of x / W when the tile has no adapter
+    const char *uh = lora ? p.u_hi + (int64_t)row0 * ldu : p.x;
+    const char *ul = lora ? p.u_lo + (int64_t)row0 * ldu : p.x;
+    const char *be = lora ? p.B_stack + ((int64_t)e * p.d_out + n0) * ldu : p.W;
 
     typename C::Acc acc;
     C::zero(acc);
-    auto issue = [&](int it, typename C::Stage &g) {
-        if (it < nkb0) {
-            C::load_stage(g, vx, vw, (uint32_t)it * (C::BK * 2), ldx);
-        } else {
-            int j = it - nkb0;
-            if (j == nkb1) vu.base += hi_to_lo;   // second pass: the remainder part of u
-            if (j >= nkb1) j -= nkb1;
-            C::load_stage(g, vu, vb, (uint32_t)j * (C::BK * 2), ldu);
+    if constexpr (C::IS_DMA) {
+        const char *xa = p.x + (int64_t)row0 * ldx;
+        const char *wb = p.W + (int64_t)n0 * ldx;
+        const auto la = C::template make_lanes<C::A_I>(rows);
+        const auto lb = C::template make_lanes<C::B_I>(ncols);
+        // Block sequence: base blocks first, then the adapter blocks (the high
+        // part of u, then the remainder); only uniform scalars differ between
+        // them.  Written out here rather than through a callable: the operand
+        // choice then stays a select of register values.
+        const int total = nkb0 + 2 * nkb1;
+#define MOIN_ISSUE_BLOCK(blk, stage)                                                      \
+    do {                                                                                  \
+        const int b_ = (blk);                                                             \
+        const bool base_ = b_ < nkb0;                                                     \
+        const int j_ = b_ - nkb0;                                                         \
+        const bool hi_ = j_ < nkb1;                                                       \
+        const char *pa_ = base_ ? xa : (hi_ ? uh : ul);                                   \
+        const char *pb_ = base_ ? wb : be;                                                \
+        const uint32_t ld_ = base_ ? ldx : ldu;                                           \
+        const int kb_ = base_ ? b_ : (hi_ ? j_ : j_ - nkb1);                              \
+        C::issue((stage), pa_, ld_, la, pb_, ld_, lb, (uint32_t)kb_ * (C::BK * 2));       \
+    } while (0)
+#pragma unroll
+        for (int s = 0; s < C::NS - 1; ++s)
+            if (s < total) MOIN_ISSUE_BLOCK(s, smem + s * C::STAGE_BYTES);
+        int st = 0;
+        for (int it = 0; it < total; ++it) {
+            if (it + C::NS - 2 < total) wait_vm_then_barrier<(C::NS - 2) * C::LPB>();
+            else wait_vm_then_barrier<0>();
+            const int nb = it + C::NS - 1;
+            const int ns = (st == 0) ? C::NS - 1 : st - 1;
+            if (nb < total) MOIN_ISSUE_BLOCK(nb, smem + ns * C::STAGE_BYTES);
+            C::compute_stage(smem + st * C::STAGE_BYTES, acc);
+            st = (st + 1 == C::NS) ? 0 : st + 1;
         }
-    };
-    pipelined_blocks<C>(smem, nkb0 + 2 * nkb1, issue, acc);
+        __syncthreads();
+#undef MOIN_ISSUE_BLOCK
+    } else {
+        const auto vx = C::template make_view<C::A_CH>(p.x + (int64_t)row0 * ldx, ldx, rows);
+        const auto vw = C::template make_view<C::B_CH>(p.W + (int64_t)n0 * ldx, ldx, ncols);
+        const auto vuh = C::template make_view<C::A_CH>(uh, ldu, rows);
+        const auto vul = C::template make_view<C::A_CH>(ul, ldu, rows);
+        const auto vb = C::template make_view<C::B_CH>(be, ldu, ncols);
+        auto issue = [=](int it, typename C::Stage &g) __attribute__((always_inline)) {
+            if (it < nkb0) {
+                C::load_stage(g, vx, vw, (uint32_t)it * (C::BK * 2), ldx);
+            } else if (it < nkb0 + nkb1) {
+                C::load_stage(g, vuh, vb, (uint32_t)(it - nkb0) * (C::BK * 2), ldu);
+            } else {
+                C::load_stage(g, vul, vb, (uint32_t)(it - nkb0 - nkb1) * (C::BK * 2), ldu);
+            }
+        };
+        pipelined_blocks<C>(smem, nkb0 + 2 * nkb1, issue, acc);
+    }
 
     const int64_t ldy = (int64_t)p.d_out * (p.y_f32 ? 4 : 2);
     char *yb = p.y + (int64_t)row0 * ldy;
@@ -150,31 +170,41 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
 {
     extern __shared__ __align__(16) char smem[];
     constexpr int SUB = TILE_M / C::BM;
-    const int ntm = *p.n_tiles * SUB;
+    const int ntm = uniform(*p.n_tiles) * SUB;
     const int id = blockIdx.x;
     if (id >= ntm * p.n_tiles_n) return;
-    const int tm = id / p.n_tiles_n, tn = id % p.n_tiles_n;
+    const int tm = uniform(id / p.n_tiles_n), tn = uniform(id % p.n_tiles_n);
     const int t = tm / SUB, sub = tm % SUB;
-    const int e = p.tile_expert[t];
-    int rows = p.tile_rows[t] - sub * C::BM;
+    const int e = uniform(p.tile_expert[t]);
+    int rows = uniform(p.tile_rows[t]) - sub * C::BM;
     if (e < 0 || rows <= 0) return;
     rows = min(rows, C::BM);
-    const int row0 = p.tile_row0[t] + sub * C::BM;
+    const int row0 = uniform(p.tile_row0[t]) + sub * C::BM;
     const int n0 = tn * C::BN;
     const int ncols = min(C::BN, p.r - n0);
 
     const uint32_t ldx = (uint32_t)p.d_in * 2u;
-    const auto vx = C::template make_view<C::A_CH>(p.x + (int64_t)row0 * ldx, ldx, rows);
-    const auto va = C::template make_view<C::B_CH>(
-        p.A_stack + ((int64_t)e * p.r + n0) * ldx, ldx, ncols);
+    const char *xa = p.x + (int64_t)row0 * ldx;
+    const char *ae = p.A_stack + ((int64_t)e * p.r + n0) * ldx;
     const int nkb = (p.d_in + C::BK - 1) / C::BK;
 
     typename C::Acc acc;
     C::zero(acc);
-    auto issue = [&](int it, typename C::Stage &g) {
-        C::load_stage(g, vx, va, (uint32_t)it * (C::BK * 2), ldx);
-    };
-    pipelined_blocks<C>(smem, nkb, issue, acc);
+    if constexpr (C::IS_DMA) {
+        const auto la = C::template make_lanes<C::A_I>(rows);
+        const auto lb = C::template make_lanes<C::B_I>(ncols);
+        auto issue = [=](int it, char *stage) __attribute__((always_inline)) {
+            C::issue(stage, xa, ldx, la, ae, ldx, lb, (uint32_t)it * (C::BK * 2));
+        };
+        dma_pipelined_blocks<C>(smem, nkb, issue, acc, [](int) {});
+    } else {
+        const auto vx = C::template make_view<C::A_CH>(xa, ldx, rows);
+        const auto va = C::template make_view<C::B_CH>(ae, ldx, ncols);
+        auto issue = [=](int it, typename C::Stage &g) __attribute__((always_inline)) {
+            C::load_stage(g, vx, va, (uint32_t)it * (C::BK * 2), ldx);
+        };
+        pipelined_blocks<C>(smem, nkb, issue, acc);
+    }
 
     const int64_t ldu = (int64_t)p.r * 2;
     char *uh = p.u_hi + (int64_t)row0 * ldu;
@@ -200,31 +230,39 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
     });
 }
 
-// tile shapes
-using CfgMain = GemmCore<256, 256, 64, 4, 2>;   // 8 waves, wave patch 64 x 128
-using CfgShrink = GemmCore<64, 64, 64, 2, 2>;   // 4 waves, wave patch 32 x 32
-using CfgThin = GemmCore<128, 64, 64, 2, 2>;    // decode base GEMM: 4 waves, 64 x 32
+// Tile shapes.  The *Dma variants need every contraction length (d_in, and r
+// for the linear kernel) to be a multiple of BK = 64; the register-staged ones
+// take any multiple of 8.
+using CfgMain = GemmCore<256, 256, 64, 4, 2>;        // 8 waves, wave patch 64 x 128
+using CfgMainDma = DmaCore<256, 256, 64, 4, 2, 2>;
+using CfgShrink = GemmCore<64, 64, 64, 2, 2>;        // 4 waves, wave patch 32 x 32
+using CfgShrinkDma = DmaCore<64, 64, 64, 2, 2, 4>;
+using CfgThin = GemmCore<128, 64, 64, 2, 2>;         // decode base GEMM: 4 waves, 64 x 32
+using CfgThinDma = DmaCore<128, 64, 64, 2, 2, 6>;
+
+template <class K>
+static hipError_t allow_lds(K kern, int bytes)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
 
 hipError_t prepare_linear_kernels()
 {
     hipError_t e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_kernel<CfgMain>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, CfgMain::SMEM_BYTES);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_kernel<CfgThin>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, CfgThin::SMEM_BYTES);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&shrink_kernel<CfgShrink>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, CfgShrink::SMEM_BYTES);
-    return e;
+    if ((e = allow_lds(&linear_kernel<CfgMain>, CfgMain::SMEM_BYTES)) != hipSuccess) return e;
+    if ((e = allow_lds(&linear_kernel<CfgMainDma>, CfgMainDma::SMEM_BYTES)) != hipSuccess) return e;
+    if ((e = allow_lds(&linear_kernel<CfgThin>, CfgThin::SMEM_BYTES)) != hipSuccess) return e;
+    if ((e = allow_lds(&linear_kernel<CfgThinDma>, CfgThinDma::SMEM_BYTES)) != hipSuccess) return e;
+    if ((e = allow_lds(&shrink_kernel<CfgShrink>, CfgShrink::SMEM_BYTES)) != hipSuccess) return e;
+    return allow_lds(&shrink_kernel<CfgShrinkDma>, CfgShrinkDma::SMEM_BYTES);
 }
 
 static inline int round_up8(int v) { return (v + 7) & ~7; }
 
-hipError_t launch_prefill_shrink(const PlanView &pv, const LinearArgs &a, hipStream_t stream)
+template <class C>
+static hipError_t launch_shrink_as(const PlanView &pv, const LinearArgs &a, hipStream_t stream)
 {
-    using C = CfgShrink;
-    if (a.r <= 0 || pv.max_tiles <= 0) return hipSuccess;
     ShrinkKParams p;
     p.x = (const char *)a.x; p.A_stack = (const char *)a.A_stack;
     p.u_hi = (char *)a.u_hi; p.u_lo = (char *)a.u_lo;
@@ -238,9 +276,27 @@ hipError_t launch_prefill_shrink(const PlanView &pv, const LinearArgs &a, hipStr
     return hipGetLastError();
 }
 
+hipError_t launch_prefill_shrink(const PlanView &pv, const LinearArgs &a, hipStream_t stream)
+{
+    if (a.r <= 0 || pv.max_tiles <= 0) return hipSuccess;
+    if (a.d_in % 64 == 0) return launch_shrink_as<CfgShrinkDma>(pv, a, stream);
+    return launch_shrink_as<CfgShrink>(pv, a, stream);
+}
+
+template <class C>
+static hipError_t launch_linear_as(const LinearKParams &p0, int64_t m_tiles, hipStream_t stream)
+{
+    LinearKParams p = p0;
+    p.n_tiles_n = (p.d_out + C::BN - 1) / C::BN;
+    const int64_t total = m_tiles * p.n_tiles_n;
+    if (total > 0x7ffffff0LL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(linear_kernel<C>, dim3((unsigned)round_up8((int)total)), dim3(C::NT),
+                       C::SMEM_BYTES, stream, p);
+    return hipGetLastError();
+}
+
 hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStream_t stream)
 {
-    using C = CfgMain;
     if (pv.max_tiles <= 0) return hipSuccess;
     LinearKParams p;
     p.x = (const char *)a.x; p.W = (const char *)a.W; p.B_stack = (const char *)a.B_stack;
@@ -251,18 +307,16 @@ hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStr
     p.ylora = nullptr; p.row_expert = nullptr;
     p.T = pv.T;
     p.d_in = a.d_in; p.d_out = a.d_out; p.r = a.r;
-    p.n_tiles_n = (a.d_out + C::BN - 1) / C::BN;
+    p.n_tiles_n = 0;
     p.y_f32 = a.y_f32;
     p.plain_tiles = 0;
-    const int64_t grid = (int64_t)round_up8(pv.max_tiles * (TILE_M / C::BM) * p.n_tiles_n) ;
-    if ((int64_t)pv.max_tiles * p.n_tiles_n > 0x7ffffff0LL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(linear_kernel<C>, dim3((unsigned)grid), dim3(C::NT), C::SMEM_BYTES, stream, p);
-    return hipGetLastError();
+    if (a.d_in % 64 == 0 && a.r % 64 == 0)
+        return launch_linear_as<CfgMainDma>(p, pv.max_tiles, stream);
+    return launch_linear_as<CfgMain>(p, pv.max_tiles, stream);
 }
 
 hipError_t launch_decode_base(const PlanView &pv, const DecodeArgs &d, hipStream_t stream)
 {
-    using C = CfgThin;
     const LinearArgs &a = d.lin;
     if (pv.T <= 0) return hipSuccess;
     LinearKParams p;
@@ -274,13 +328,12 @@ hipError_t launch_decode_base(const PlanView &pv, const DecodeArgs &d, hipStream
     p.row_expert = pv.row_expert;
     p.T = pv.T;
     p.d_in = a.d_in; p.d_out = a.d_out; p.r = 0;
-    p.n_tiles_n = (a.d_out + C::BN - 1) / C::BN;
+    p.n_tiles_n = 0;
     p.y_f32 = a.y_f32;
     p.plain_tiles = 1;
-    const int ntm = (int)((pv.T + C::BM - 1) / C::BM);
-    const int grid = round_up8(ntm * p.n_tiles_n);
-    hipLaunchKernelGGL(linear_kernel<C>, dim3((unsigned)grid), dim3(C::NT), C::SMEM_BYTES, stream, p);
-    return hipGetLastError();
+    const int64_t ntm = (pv.T + CfgThin::BM - 1) / CfgThin::BM;
+    if (a.d_in % 64 == 0) return launch_linear_as<CfgThinDma>(p, ntm, stream);
+    return launch_linear_as<CfgThin>(p, ntm, stream);
 }
 
 }  // namespace moin
