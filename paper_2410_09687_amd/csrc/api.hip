@@ -412,30 +412,36 @@ int moin_route(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N,
 
     const size_t Kpad = align_up((size_t)K, 256);
     const size_t cn_bytes = align_up(Kpad * 4, 256);
+    const size_t best_bytes = (size_t)ROUTE_SMALL_MAX_N * 8 + 256;
     const bool need_cid_ws = counts && !centroid_ids && N > 0;
-    const int rc = ensure_ws(ctx, cn_bytes + (need_cid_ws ? (size_t)N * 4 : 0));
+    const int rc = ensure_ws(ctx, cn_bytes + best_bytes + (need_cid_ws ? (size_t)N * 4 : 0));
     if (rc != MOIN_OK) return rc;
+    char *w = static_cast<char *>(ctx->ws);
 
     RouteArgs a;
     a.emb = emb; a.cent = centroids; a.N = N; a.K = K; a.D = D;
     a.is_bf16 = (dt == MOIN_BF16);
     a.slot = slot_of_centroid;
     a.retained_only = (flags & MOIN_ROUTE_RETAINED_ONLY) ? 1 : 0;
-    a.cnorm = static_cast<float *>(ctx->ws);
+    a.cnorm = reinterpret_cast<float *>(w);
+    a.best = reinterpret_cast<unsigned long long *>(w + cn_bytes);
+    a.arrivals = reinterpret_cast<int *>(w + cn_bytes + (size_t)ROUTE_SMALL_MAX_N * 8);
     a.cid = centroid_ids ? centroid_ids
-                         : (need_cid_ws ? reinterpret_cast<int *>(static_cast<char *>(ctx->ws) + cn_bytes)
-                                        : nullptr);
+                         : (need_cid_ws ? reinterpret_cast<int *>(w + cn_bytes + best_bytes) : nullptr);
     a.expert_ids = expert_ids;
+    a.counts = counts;
 
-    if (N > 0 && (a.cid || a.expert_ids)) {
+    const bool routed = N > 0 && (a.cid || a.expert_ids);
+    if (routed) {
         if (timed(ctx, MOIN_K_ROUTE_AUX, st, [&] { return launch_centroid_norms(a, st); }) != hipSuccess)
             return MOIN_EHIP;
         if (timed(ctx, MOIN_K_ROUTE, st, [&] { return launch_route(a, st); }) != hipSuccess)
             return MOIN_EHIP;
     }
     if (counts) {
+        // the norms kernel, when it ran, has already zeroed counts
         if (timed(ctx, MOIN_K_ROUTE_AUX, st, [&] {
-                return launch_histogram(a.cid, N, K, counts, ctx->err_word, st);
+                return launch_histogram(a.cid, N, K, counts, routed ? 0 : 1, ctx->err_word, st);
             }) != hipSuccess)
             return MOIN_EHIP;
     }
@@ -451,7 +457,7 @@ int moin_histogram(moin_ctx *ctx, const int32_t *ids, int64_t N, int32_t K, int3
     if (!guard.ok) return MOIN_EHIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (timed(ctx, MOIN_K_ROUTE_AUX, st, [&] {
-            return launch_histogram(ids, N, K, counts, ctx->err_word, st);
+            return launch_histogram(ids, N, K, counts, 1, ctx->err_word, st);
         }) != hipSuccess)
         return MOIN_EHIP;
     return MOIN_OK;

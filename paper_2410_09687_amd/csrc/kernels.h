@@ -73,11 +73,17 @@ struct RouteArgs {
     float *cnorm;          // [K rounded up to 256] workspace
     int *cid;              // [N] centroid ids (user buffer or workspace)
     int *expert_ids;       // [N] or null
+    // small batches: per-query packed (score, index) minimum merged across
+    // workgroups, and the arrival counter that elects the finishing workgroup
+    unsigned long long *best;  // [ROUTE_SMALL_MAX_N] workspace
+    int *arrivals;             // [1] workspace
+    int *counts;               // [K] or null: zeroed by the norms kernel
 };
+constexpr int ROUTE_SMALL_MAX_N = 4096;  // up to here the K range is split across workgroups
 hipError_t launch_centroid_norms(const RouteArgs &a, hipStream_t stream);
 hipError_t launch_route(const RouteArgs &a, hipStream_t stream);
-hipError_t launch_histogram(const int *ids, int64_t N, int K, int *counts, int *err_word,
-                            hipStream_t stream);
+hipError_t launch_histogram(const int *ids, int64_t N, int K, int *counts, int zero_first,
+                            int *err_word, hipStream_t stream);
 
 hipError_t prepare_kernels();  // one-time attribute set-up (large dynamic LDS)
 

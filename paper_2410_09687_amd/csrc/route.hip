@@ -16,7 +16,9 @@
 
 namespace moin {
 
-using CfgRoute = GemmCore<256, 256, 64, 4, 2>;  // rows: centroids, cols: queries
+using CfgRoute = GemmCore<256, 256, 64, 4, 2>;      // rows: centroids, cols: queries; any D % 8 == 0
+using CfgRouteDma = DmaCore<256, 256, 64, 4, 2, 2>;  // D % 64 == 0
+using CfgRouteSmall = DmaCore<64, 64, 64, 2, 2, 6>;  // small batches: one (centroid chunk, query tile) per workgroup
 
 struct RouteKParams {
     const char *emb, *cent;
@@ -24,6 +26,8 @@ struct RouteKParams {
     const int *slot;
     int *cid;
     int *expert_ids;
+    unsigned long long *best;
+    int *arrivals;
     int64_t N;
     int K, D;
 };
@@ -31,6 +35,36 @@ struct RouteKParams {
 __device__ __forceinline__ bool lex_less(float v, int i, float bv, int bi)
 {
     return (v < bv) || (v == bv && i < bi);
+}
+
+// Folds one finished centroid tile into the running per-lane minima.  A lane
+// holds, per accumulator, 16 centroid scores of one query in ascending
+// centroid order, so a strict '<' keeps the lowest index among equal scores.
+template <class C>
+__device__ __forceinline__ void fold_scores(const typename C::Acc &acc, const float *cnorm_tile,
+                                            int idx_tile, float (&bestv)[C::FN], int (&besti)[C::FN])
+{
+    const int lane = threadIdx.x & 63;
+    const int wm = (threadIdx.x >> 6) / C::WN;
+    const float *cn = cnorm_tile + wm * C::WTM + 4 * (lane >> 5);
+#pragma unroll
+    for (int i = 0; i < C::FM; ++i) {
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+            const f32x4_t c4 = *reinterpret_cast<const f32x4_t *>(cn + i * 32 + e4 * 8);
+            const int idx0 = idx_tile + wm * C::WTM + i * 32 + e4 * 8 + 4 * (lane >> 5);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                for (int j = 0; j < C::FN; ++j) {
+                    const float s = fmaf(-2.f, acc.v[i][j][e4 * 4 + q], c4[q]);
+                    const bool lt = s < bestv[j];
+                    bestv[j] = lt ? s : bestv[j];
+                    besti[j] = lt ? idx0 + q : besti[j];
+                }
+            }
+        }
+    }
 }
 
 template <class C>
@@ -45,8 +79,7 @@ __global__ __launch_bounds__(C::NT) void route_kernel(RouteKParams p)
     const uint32_t ld = (uint32_t)p.D * 2u;
     const int nkb = (p.D + C::BK - 1) / C::BK;
     const int nct = (p.K + C::BM - 1) / C::BM;
-
-    const auto vq = C::template make_view<C::B_CH>(p.emb + q0 * (int64_t)ld, ld, nq);
+    const char *qb = p.emb + q0 * (int64_t)ld;
 
     float bestv[C::FN];
     int besti[C::FN];
@@ -58,54 +91,69 @@ __global__ __launch_bounds__(C::NT) void route_kernel(RouteKParams p)
 
     typename C::Acc acc;
     C::zero(acc);
-    typename C::Stage g;
     const int total = nct * nkb;
 
-    auto issue = [&](int it) {
-        const int ct = it / nkb, kb = it - ct * nkb;
-        const int crow = ct * C::BM;
-        const auto vc = C::template make_view<C::A_CH>(p.cent + (int64_t)crow * ld, ld,
-                                                       min(C::BM, p.K - crow));
-        C::load_stage(g, vc, vq, (uint32_t)kb * (C::BK * 2), ld);
-    };
-
-    issue(0);
-    C::store_stage(smem, g);
-    __syncthreads();
-    int kb = 0, ct = 0;
-    for (int it = 0; it < total; ++it) {
-        char *cur = smem + (it & 1) * C::STAGE_BYTES;
-        char *nxt = smem + ((it + 1) & 1) * C::STAGE_BYTES;
-        const bool more = it + 1 < total;
-        if (more) issue(it + 1);
-        C::compute_stage(cur, acc);
-        if (++kb == nkb) {
-            // scores of this centroid tile: ascending centroid index within a lane
-            const float *cn = p.cnorm + ct * C::BM + wm * C::WTM + 4 * (lane >> 5);
-#pragma unroll
-            for (int i = 0; i < C::FM; ++i) {
-#pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) {
-                    const f32x4_t c4 = *reinterpret_cast<const f32x4_t *>(cn + i * 32 + e4 * 8);
-                    const int idx0 = ct * C::BM + wm * C::WTM + i * 32 + e4 * 8 + 4 * (lane >> 5);
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-#pragma unroll
-                        for (int j = 0; j < C::FN; ++j) {
-                            const float s = fmaf(-2.f, acc.v[i][j][e4 * 4 + q], c4[q]);
-                            const bool lt = s < bestv[j];
-                            bestv[j] = lt ? s : bestv[j];
-                            besti[j] = lt ? idx0 + q : besti[j];
-                        }
-                    }
-                }
+    if constexpr (C::IS_DMA) {
+        static_assert(C::NS == 2, "stage bookkeeping below assumes two stages");
+        const auto lq = C::template make_lanes<C::B_I>(nq);
+        // the last centroid tile may be short: its lanes clamp to the last valid row
+        const auto lc_full = C::template make_lanes<C::A_I>(C::BM);
+        const auto lc_last = C::template make_lanes<C::A_I>(p.K - (nct - 1) * C::BM);
+#define MOIN_ROUTE_ISSUE(blk, stage)                                                         \
+    do {                                                                                     \
+        const int ct_ = (blk) / nkb, kb_ = (blk) - ct_ * nkb;                                \
+        typename C::template Lanes<C::A_I> lc_;                                              \
+        _Pragma("unroll") for (int q_ = 0; q_ < C::A_I; ++q_) {                              \
+            lc_.row[q_] = (ct_ == nct - 1) ? lc_last.row[q_] : lc_full.row[q_];              \
+            lc_.c16[q_] = lc_full.c16[q_];                                                   \
+        }                                                                                    \
+        C::issue((stage), p.cent + (int64_t)ct_ * C::BM * ld, ld, lc_, qb, ld, lq,           \
+                 (uint32_t)kb_ * (C::BK * 2));                                               \
+    } while (0)
+        MOIN_ROUTE_ISSUE(0, smem);
+        int kb = 0, ct = 0;
+        for (int it = 0; it < total; ++it) {
+            wait_vm_then_barrier<0>();
+            if (it + 1 < total) MOIN_ROUTE_ISSUE(it + 1, smem + ((it + 1) & 1) * C::STAGE_BYTES);
+            C::compute_stage(smem + (it & 1) * C::STAGE_BYTES, acc);
+            if (++kb == nkb) {
+                fold_scores<C>(acc, p.cnorm + ct * C::BM, ct * C::BM, bestv, besti);
+                C::zero(acc);
+                kb = 0;
+                ++ct;
             }
-            C::zero(acc);
-            kb = 0;
-            ++ct;
         }
-        if (more) C::store_stage(nxt, g);
         __syncthreads();
+#undef MOIN_ROUTE_ISSUE
+    } else {
+        const auto vq = C::template make_view<C::B_CH>(qb, ld, nq);
+        typename C::Stage g;
+        auto issue = [&](int it) __attribute__((always_inline)) {
+            const int ct = it / nkb, kb = it - ct * nkb;
+            const int crow = ct * C::BM;
+            const auto vc = C::template make_view<C::A_CH>(p.cent + (int64_t)crow * ld, ld,
+                                                           min(C::BM, p.K - crow));
+            C::load_stage(g, vc, vq, (uint32_t)kb * (C::BK * 2), ld);
+        };
+        issue(0);
+        C::store_stage(smem, g);
+        __syncthreads();
+        int kb = 0, ct = 0;
+        for (int it = 0; it < total; ++it) {
+            char *cur = smem + (it & 1) * C::STAGE_BYTES;
+            char *nxt = smem + ((it + 1) & 1) * C::STAGE_BYTES;
+            const bool more = it + 1 < total;
+            if (more) issue(it + 1);
+            C::compute_stage(cur, acc);
+            if (++kb == nkb) {
+                fold_scores<C>(acc, p.cnorm + ct * C::BM, ct * C::BM, bestv, besti);
+                C::zero(acc);
+                kb = 0;
+                ++ct;
+            }
+            if (more) C::store_stage(nxt, g);
+            __syncthreads();
+        }
     }
 
     // merge the two lane halves (rows 4*(lane>>5) interleave), then the WM waves
@@ -146,12 +194,108 @@ __global__ __launch_bounds__(C::NT) void route_kernel(RouteKParams p)
     }
 }
 
+// Order-preserving map of a finite float (or +-inf) to an unsigned integer.
+__device__ __forceinline__ uint32_t float_order_key(float f)
+{
+    const uint32_t u = f32_bits(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Small batches: too few queries to fill the chip with 256-query workgroups, so
+// the centroid range is split as well.  Workgroup (ct, qt) scores 64 centroids
+// against 64 queries and merges its per-query minimum into best[] with a 64-bit
+// atomic min on (score key << 32 | index): exact, order-independent, and the
+// lowest index wins equal scores.  The workgroup that arrives last unpacks.
+template <class C>
+__global__ __launch_bounds__(C::NT) void route_small_kernel(RouteKParams p, int nqt)
+{
+    extern __shared__ __align__(16) char smem[];
+    __shared__ int last_flag;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int wn = wave % C::WN;
+    const int qt = blockIdx.x % nqt, ct = blockIdx.x / nqt;
+    const int q0 = qt * C::BN, c0 = ct * C::BM;
+    const int nq = min(C::BN, (int)p.N - q0), nc = min(C::BM, p.K - c0);
+    const uint32_t ld = (uint32_t)p.D * 2u;
+    const int nkb = p.D / C::BK;
+    const char *cb = p.cent + (int64_t)c0 * ld;
+    const char *qb = p.emb + (int64_t)q0 * ld;
+    const auto lc = C::template make_lanes<C::A_I>(nc);
+    const auto lq = C::template make_lanes<C::B_I>(nq);
+
+    typename C::Acc acc;
+    C::zero(acc);
+#pragma unroll
+    for (int s = 0; s < C::NS - 1; ++s)
+        if (s < nkb) C::issue(smem + s * C::STAGE_BYTES, cb, ld, lc, qb, ld, lq, (uint32_t)s * (C::BK * 2));
+    int st = 0;
+    for (int it = 0; it < nkb; ++it) {
+        if (it + C::NS - 2 < nkb) wait_vm_then_barrier<(C::NS - 2) * C::LPB>();
+        else wait_vm_then_barrier<0>();
+        const int nb = it + C::NS - 1;
+        const int ns = (st == 0) ? C::NS - 1 : st - 1;
+        if (nb < nkb) C::issue(smem + ns * C::STAGE_BYTES, cb, ld, lc, qb, ld, lq, (uint32_t)nb * (C::BK * 2));
+        C::compute_stage(smem + st * C::STAGE_BYTES, acc);
+        st = (st + 1 == C::NS) ? 0 : st + 1;
+    }
+
+    float bestv[C::FN];
+    int besti[C::FN];
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j) {
+        bestv[j] = __builtin_inff();
+        besti[j] = 0;
+    }
+    fold_scores<C>(acc, p.cnorm + c0, c0, bestv, besti);
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j) {
+        const float ov = __shfl_xor(bestv[j], 32);
+        const int oi = __shfl_xor(besti[j], 32);
+        if (lex_less(ov, oi, bestv[j], besti[j])) {
+            bestv[j] = ov;
+            besti[j] = oi;
+        }
+        const int col = wn * C::WTN + j * 32 + lane;
+        // a score that is not below +inf (excluded centroid, NaN) never wins
+        if (lane < 32 && col < nq && bestv[j] < __builtin_inff())
+            atomicMin(&p.best[q0 + col],
+                      ((unsigned long long)float_order_key(bestv[j]) << 32) | (unsigned)besti[j]);
+    }
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0)
+        last_flag = (atomicAdd(p.arrivals, 1) == (int)gridDim.x - 1);
+    __syncthreads();
+    if (!last_flag) return;
+    __threadfence();
+    for (int q = threadIdx.x; q < (int)p.N; q += C::NT) {
+        const unsigned long long key =
+            __hip_atomic_load(&p.best[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned idx = (unsigned)(key & 0xffffffffu);
+        const int bi = (idx < (unsigned)p.K) ? (int)idx : 0;   // nothing won: centroid 0
+        if (p.cid) p.cid[q] = bi;
+        if (p.expert_ids) p.expert_ids[q] = p.slot ? p.slot[bi] : bi;
+    }
+}
+
 // ||c_k||^2 in fp32 (one wave per centroid), +inf for centroids left out of the
-// search and for the padding up to a multiple of 256.
+// search and for the padding up to a multiple of 256.  The same launch resets
+// what the kernels after it accumulate into: the packed minima and arrival
+// counter of the small-batch router, and the histogram.
 __global__ __launch_bounds__(256) void centroid_norm_kernel(const char *cent, int K, int Kpad,
                                                             int D, int is_bf16, const int *slot,
-                                                            int retained_only, float *cnorm)
+                                                            int retained_only, float *cnorm,
+                                                            unsigned long long *best, int nbest,
+                                                            int *arrivals, int *counts)
 {
+    const int gid = blockIdx.x * 256 + threadIdx.x;
+    const int gsz = gridDim.x * 256;
+    for (int i = gid; i < nbest; i += gsz) best[i] = ~0ull;
+    if (counts)
+        for (int i = gid; i < K; i += gsz) counts[i] = 0;
+    if (gid == 0) *arrivals = 0;
+
     const int lane = threadIdx.x & 63;
     const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (k >= Kpad) return;
@@ -248,18 +392,33 @@ __global__ __launch_bounds__(256) void fill_i32_kernel(int *dst, int n, int valu
     if (i < n) dst[i] = value;
 }
 
+template <class K>
+static hipError_t allow_lds(K kern, int bytes)
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
 hipError_t prepare_route_kernels()
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&route_kernel<CfgRoute>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, CfgRoute::SMEM_BYTES);
+    hipError_t e;
+    if ((e = allow_lds(&route_kernel<CfgRoute>, CfgRoute::SMEM_BYTES)) != hipSuccess) return e;
+    if ((e = allow_lds(&route_kernel<CfgRouteDma>, CfgRouteDma::SMEM_BYTES)) != hipSuccess) return e;
+    return allow_lds(&route_small_kernel<CfgRouteSmall>, CfgRouteSmall::SMEM_BYTES);
+}
+
+static bool use_small_route(const RouteArgs &a)
+{
+    return a.is_bf16 && a.D % 64 == 0 && a.N <= ROUTE_SMALL_MAX_N;
 }
 
 hipError_t launch_centroid_norms(const RouteArgs &a, hipStream_t stream)
 {
     const int Kpad = (a.K + 255) / 256 * 256;
+    const int nbest = use_small_route(a) ? (int)a.N : 0;
     hipLaunchKernelGGL(centroid_norm_kernel, dim3((Kpad + 3) / 4), dim3(256), 0, stream,
                        (const char *)a.cent, a.K, Kpad, a.D, a.is_bf16, a.slot, a.retained_only,
-                       a.cnorm);
+                       a.cnorm, a.best, nbest, a.arrivals, a.counts);
     return hipGetLastError();
 }
 
@@ -267,15 +426,28 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t stream)
 {
     if (a.N <= 0) return hipSuccess;
     if (a.is_bf16) {
-        using C = CfgRoute;
         RouteKParams p;
         p.emb = (const char *)a.emb; p.cent = (const char *)a.cent;
         p.cnorm = a.cnorm; p.slot = a.slot; p.cid = a.cid; p.expert_ids = a.expert_ids;
+        p.best = a.best; p.arrivals = a.arrivals;
         p.N = a.N; p.K = a.K; p.D = a.D;
-        const int64_t grid = (a.N + C::BN - 1) / C::BN;
+        if (use_small_route(a)) {
+            using C = CfgRouteSmall;
+            const int nqt = (int)((a.N + C::BN - 1) / C::BN);
+            const int64_t grid = (int64_t)nqt * ((a.K + C::BM - 1) / C::BM);
+            if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+            hipLaunchKernelGGL(route_small_kernel<C>, dim3((unsigned)grid), dim3(C::NT),
+                               C::SMEM_BYTES, stream, p, nqt);
+            return hipGetLastError();
+        }
+        const int64_t grid = (a.N + CfgRoute::BN - 1) / CfgRoute::BN;
         if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-        hipLaunchKernelGGL(route_kernel<C>, dim3((unsigned)grid), dim3(C::NT), C::SMEM_BYTES,
-                           stream, p);
+        if (a.D % 64 == 0)
+            hipLaunchKernelGGL(route_kernel<CfgRouteDma>, dim3((unsigned)grid), dim3(CfgRouteDma::NT),
+                               CfgRouteDma::SMEM_BYTES, stream, p);
+        else
+            hipLaunchKernelGGL(route_kernel<CfgRoute>, dim3((unsigned)grid), dim3(CfgRoute::NT),
+                               CfgRoute::SMEM_BYTES, stream, p);
     } else {
         const int64_t grid = (a.N + 3) / 4;
         if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -286,12 +458,15 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_histogram(const int *ids, int64_t N, int K, int *counts, int *err_word,
-                            hipStream_t stream)
+hipError_t launch_histogram(const int *ids, int64_t N, int K, int *counts, int zero_first,
+                            int *err_word, hipStream_t stream)
 {
-    hipLaunchKernelGGL(fill_i32_kernel, dim3((K + 255) / 256), dim3(256), 0, stream, counts, K, 0);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || N <= 0) return e;
+    if (zero_first) {
+        hipLaunchKernelGGL(fill_i32_kernel, dim3((K + 255) / 256), dim3(256), 0, stream, counts, K, 0);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (N <= 0) return hipSuccess;
     int64_t blocks = (N + 1024 * 16 - 1) / (1024 * 16);
     if (blocks > 1024) blocks = 1024;
     if (blocks < 1) blocks = 1;
