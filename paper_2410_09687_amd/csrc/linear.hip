@@ -171,8 +171,10 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
     extern __shared__ __align__(16) char smem[];
     constexpr int SUB = TILE_M / C::BM;
     const int ntm = uniform(*p.n_tiles) * SUB;
-    const int id = blockIdx.x;
-    if (id >= ntm * p.n_tiles_n) return;
+    // neighbouring sub-tiles share A_e: keep them on one XCD so that its L2
+    // fetches each adapter slab from HBM once
+    const int id = xcd_band_id(blockIdx.x, ntm * p.n_tiles_n);
+    if (id < 0) return;
     const int tm = uniform(id / p.n_tiles_n), tn = uniform(id % p.n_tiles_n);
     const int t = tm / SUB, sub = tm % SUB;
     const int e = uniform(p.tile_expert[t]);
@@ -271,8 +273,9 @@ static hipError_t launch_shrink_as(const PlanView &pv, const LinearArgs &a, hipS
     p.d_in = a.d_in; p.r = a.r; p.scale = a.scale;
     p.n_tiles_n = (a.r + C::BN - 1) / C::BN;
     const int64_t grid = (int64_t)pv.max_tiles * (TILE_M / C::BM) * p.n_tiles_n;
-    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(shrink_kernel<C>, dim3((unsigned)grid), dim3(C::NT), C::SMEM_BYTES, stream, p);
+    if (grid > 0x7ffffff0LL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(shrink_kernel<C>, dim3((unsigned)round_up8((int)grid)), dim3(C::NT),
+                       C::SMEM_BYTES, stream, p);
     return hipGetLastError();
 }
 

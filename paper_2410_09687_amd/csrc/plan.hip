@@ -10,6 +10,7 @@
 namespace moin {
 
 constexpr int PLAN_THREADS = 1024;
+constexpr int PLAN_LDS_S = 2048;
 
 // In-place exclusive prefix sum of data[0..n) by one workgroup; returns the total.
 __device__ int block_exclusive_scan(int *data, int n, int *lds /* PLAN_THREADS + 1 ints */)
@@ -44,16 +45,24 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
                                                             const int *expert_ids, int *err_word)
 {
     __shared__ int lds[PLAN_THREADS + 1];
+    // batches of up to PLAN_LDS_S sequences sort and scan entirely in LDS (a
+    // barrier-separated pass then costs tens of nanoseconds, not a round trip
+    // to L2); larger ones use the plan's global scratch
+    __shared__ unsigned long long lds_keys[PLAN_LDS_S];
+    __shared__ int lds_tmp[4 * (PLAN_LDS_S + 1)];
     const int tid = threadIdx.x;
     const int S = pv.S;
     const int T = (int)pv.T;
     int npow2 = 1;
     while (npow2 < S) npow2 <<= 1;
+    const bool small = npow2 <= PLAN_LDS_S;
+    unsigned long long *keys = small ? lds_keys : pv.keys;
+    int *tmp = small ? lds_tmp : pv.tmp;
 
-    int *lens = pv.tmp;                  // [S]   length of each sequence (by sequence)
-    int *a1 = pv.tmp + (S + 1);          // [S+1] per sorted position: tile count -> tile base
-    int *a2 = pv.tmp + 2 * (S + 1);      // [S+1] per sorted position: length -> token base
-    int *a3 = pv.tmp + 3 * (S + 1);      // [S+1] per sorted position: group head flag -> group id
+    int *lens = tmp;                  // [S]   length of each sequence (by sequence)
+    int *a1 = tmp + (S + 1);          // [S+1] per sorted position: tile count -> tile base
+    int *a2 = tmp + 2 * (S + 1);      // [S+1] per sorted position: length -> token base
+    int *a3 = tmp + 3 * (S + 1);      // [S+1] per sorted position: group head flag -> group id
 
     // 1. validate, build sort keys (expert + 1 in the high word: -1 sorts first)
     int err = 0;
@@ -75,7 +84,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
             lens[s] = hi - lo;
             key = ((unsigned long long)(unsigned)(e + 1) << 32) | (unsigned)s;
         }
-        pv.keys[s] = key;
+        keys[s] = key;
     }
     if (err) atomicOr(err_word, err);
     if (pv.decode)   // tokens that no (valid) sequence covers stay base-only
@@ -88,11 +97,11 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
             for (int i = tid; i < npow2; i += PLAN_THREADS) {
                 const int l = i ^ j;
                 if (l > i) {
-                    const unsigned long long a = pv.keys[i], b = pv.keys[l];
+                    const unsigned long long a = keys[i], b = keys[l];
                     const bool up = (i & k) == 0;
                     if ((a > b) == up) {
-                        pv.keys[i] = b;
-                        pv.keys[l] = a;
+                        keys[i] = b;
+                        keys[l] = a;
                     }
                 }
             }
@@ -102,12 +111,12 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
 
     // 3. per sorted position: tile count, token count, group-head flag
     for (int p = tid; p < S; p += PLAN_THREADS) {
-        const unsigned long long key = pv.keys[p];
+        const unsigned long long key = keys[p];
         const int s = (int)(key & 0xffffffffu);
         const int len = lens[s];
         a1[p] = (len + TILE_M - 1) / TILE_M;
         a2[p] = len;
-        const bool head = (p == 0) || ((pv.keys[p - 1] >> 32) != (key >> 32));
+        const bool head = (p == 0) || ((keys[p - 1] >> 32) != (key >> 32));
         a3[p] = head ? 1 : 0;
     }
     __syncthreads();
@@ -125,7 +134,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
 
     // 4. emit
     for (int p = tid; p < S; p += PLAN_THREADS) {
-        const unsigned long long key = pv.keys[p];
+        const unsigned long long key = keys[p];
         const int s = (int)(key & 0xffffffffu);
         const int e = (int)(key >> 32) - 1;
         const int lo = seq_offsets[s];
@@ -144,7 +153,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
                 pv.tok_sorted[base + j] = lo + j;
                 pv.row_expert[lo + j] = e;
             }
-            const bool head = (p == 0) || ((pv.keys[p - 1] >> 32) != (key >> 32));
+            const bool head = (p == 0) || ((keys[p - 1] >> 32) != (key >> 32));
             if (head) {
                 const int gi = a3[p];   // exclusive count of heads before p
                 pv.grp_expert[gi] = e;

@@ -87,6 +87,16 @@ def test_decode_mixed_lengths_and_big_groups():
     _full_check(inp, "decode_mixed")
 
 
+def test_many_short_sequences_use_the_global_sort_scratch():
+    # more sequences than the plan kernel sorts in LDS; every tile is 1..3 rows
+    rng = np.random.default_rng(3)
+    lens = rng.integers(0, 4, size=2500).tolist()
+    ids = rng.integers(-1, 6, size=2500).tolist()
+    inp = _case("many_seqs", 64, 64, 8, 6, lens, ids, seed=91)
+    assert inp.wl.T > 1024
+    _full_check(inp, "many_seqs")
+
+
 def test_planned_calls_share_one_plan():
     lens = [400, 300, 500]
     ids = [1, -1, 0]
