@@ -12,8 +12,10 @@
  *   - Return value: MOIN_OK (0) or a negative moin_status.  Nothing throws or
  *     aborts across this boundary.  Faults only visible in device data (an
  *     expert id >= E, offsets that run backwards) set a sticky error word in
- *     the context; the offending sequences are treated as base-only / empty
- *     and moin_check() reports MOIN_EDATA.
+ *     the context and moin_check() reports MOIN_EDATA.  A sequence with a bad
+ *     expert id is computed base-only; offsets that do not tile [0, T) in
+ *     order make the whole batch base-only.  Every output row is written
+ *     either way.
  *   - N = 0, S = 0 or T = 0 are successful no-ops.  Zero-length sequences are
  *     legal.
  *   - A context owns a private device workspace (grown on demand with
@@ -54,9 +56,9 @@ typedef enum {
     MOIN_K_LINEAR = 2,        /* prefill: y = x W^T + u B_e^T (base + expand)   */
     MOIN_K_ROUTE = 3,         /* distance GEMM fused with argmin                */
     MOIN_K_ROUTE_AUX = 4,     /* centroid norms, histogram, slot map            */
-    MOIN_K_DECODE_SHRINK = 5, /* decode: gather-matvec u = A_e x                */
-    MOIN_K_DECODE_EXPAND = 6, /* decode: gather-matvec s * B_e u                */
-    MOIN_K_DECODE_BASE = 7,   /* decode: thin base GEMM + combine               */
+    MOIN_K_DECODE_SHRINK = 5, /* decode: gather-matvec u = s * A_e x            */
+    MOIN_K_DECODE_EXPAND = 6, /* decode: gather-matvec B_e u + base, writes y   */
+    MOIN_K_DECODE_BASE = 7,   /* decode: thin base GEMM (fp32 partial sums)     */
     MOIN_K_COUNT = 8
 } moin_kernel_id;
 

@@ -143,7 +143,7 @@ int drain_spans(moin_ctx *ctx)
 }
 
 struct PlanLayout {
-    size_t tile_row0, tile_rows, tile_expert, n_tiles, tok_sorted, row_expert, grp_expert,
+    size_t tile_row0, tile_rows, tile_expert, n_tiles, tok_sorted, grp_meta,
         grp_start, n_groups, keys, tmp, total;
     int max_tiles, max_groups, decode;
 };
@@ -168,8 +168,7 @@ PlanLayout plan_layout(int32_t S, int64_t T)
     L.tile_expert = take((size_t)L.max_tiles * 4);
     L.n_tiles = take(4);
     L.tok_sorted = take(L.decode ? (size_t)T * 4 : 4);
-    L.row_expert = take(L.decode ? (size_t)T * 4 : 4);
-    L.grp_expert = take((size_t)(L.max_groups + 1) * 4);
+    L.grp_meta = take((size_t)(L.max_groups + 1) * 16);
     L.grp_start = take((size_t)(L.max_groups + 2) * 4);
     L.n_groups = take(4);
     L.tmp = take((size_t)4 * ((size_t)S + 1) * 4);
@@ -212,8 +211,7 @@ int plan_build_impl(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
     pv.tile_expert = reinterpret_cast<int *>(b + L.tile_expert);
     pv.n_tiles = reinterpret_cast<int *>(b + L.n_tiles);
     pv.tok_sorted = reinterpret_cast<int *>(b + L.tok_sorted);
-    pv.row_expert = reinterpret_cast<int *>(b + L.row_expert);
-    pv.grp_expert = reinterpret_cast<int *>(b + L.grp_expert);
+    pv.grp_meta = reinterpret_cast<int4 *>(b + L.grp_meta);
     pv.grp_start = reinterpret_cast<int *>(b + L.grp_start);
     pv.n_groups = reinterpret_cast<int *>(b + L.n_groups);
     pv.tmp = reinterpret_cast<int *>(b + L.tmp);
@@ -280,26 +278,30 @@ int linear_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, con
         return MOIN_OK;
     }
 
+    if (a.r == 0) {
+        // no adapters anywhere in the call: the base GEMM writes y itself
+        if (timed(ctx, MOIN_K_DECODE_BASE, stream, [&] { return launch_decode_base_only(pv, a, stream); }) !=
+            hipSuccess)
+            return MOIN_EHIP;
+        return MOIN_OK;
+    }
     DecodeArgs d;
     d.lin = a;
-    d.ug_hi = d.ug_lo = nullptr;
-    d.ylora = nullptr;
-    if (a.r > 0) {
-        const size_t yl_bytes = align_up((size_t)pv.T * (size_t)d_out * 4, 256);
-        const int rc = ensure_ws(ctx, 2 * u_bytes + yl_bytes);
-        if (rc != MOIN_OK) return rc;
-        char *w = static_cast<char *>(ctx->ws);
-        d.ug_hi = w;
-        d.ug_lo = w + u_bytes;
-        d.ylora = reinterpret_cast<float *>(w + 2 * u_bytes);
-        if (timed(ctx, MOIN_K_DECODE_SHRINK, stream, [&] { return launch_decode_shrink(pv, d, stream); }) !=
-            hipSuccess)
-            return MOIN_EHIP;
-        if (timed(ctx, MOIN_K_DECODE_EXPAND, stream, [&] { return launch_decode_expand(pv, d, stream); }) !=
-            hipSuccess)
-            return MOIN_EHIP;
-    }
+    d.k_splits = decode_base_splits(pv.T, d_in, d_out);
+    const size_t yb_bytes = align_up((size_t)d.k_splits * (size_t)pv.T * (size_t)d_out * 4, 256);
+    const int rc = ensure_ws(ctx, 2 * u_bytes + yb_bytes);
+    if (rc != MOIN_OK) return rc;
+    char *w = static_cast<char *>(ctx->ws);
+    d.ug_hi = w;
+    d.ug_lo = w + u_bytes;
+    d.ybase = reinterpret_cast<float *>(w + 2 * u_bytes);
     if (timed(ctx, MOIN_K_DECODE_BASE, stream, [&] { return launch_decode_base(pv, d, stream); }) !=
+        hipSuccess)
+        return MOIN_EHIP;
+    if (timed(ctx, MOIN_K_DECODE_SHRINK, stream, [&] { return launch_decode_shrink(pv, d, stream); }) !=
+        hipSuccess)
+        return MOIN_EHIP;
+    if (timed(ctx, MOIN_K_DECODE_EXPAND, stream, [&] { return launch_decode_expand(pv, d, stream); }) !=
         hipSuccess)
         return MOIN_EHIP;
     return MOIN_OK;

@@ -8,10 +8,14 @@
 // straight into MFMA operands -- no LDS staging, each adapter byte is used by
 // exactly one wave -- and multiplies it against the (at most a few) tokens of
 // that expert with v_mfma_f32_16x16x32_bf16, whose 16 columns are 16 tokens.
-// Idle MFMA columns cost nothing here: the kernels are HBM-bound.
+// Idle MFMA columns cost nothing here: the kernels are HBM-bound, and what
+// decides their speed is how many independent loads are in flight, so every
+// wave issues all loads of a batch before the first MFMA that consumes them
+// and the grid is shaped for several resident workgroups per compute unit.
 //
-//   shrink : ug[pos, :]   = scale * A_e x_tok     (bf16 high part + remainder)
-//   expand : ylora[tok,:] = B_e ug[pos]           (fp32, added by the base GEMM)
+//   base   : ybase[s] = x[:, range s] W[:, range s]^T   (fp32, linear.hip)
+//   shrink : ug[pos, :] = scale * A_e x_tok             (bf16 high part + remainder)
+//   expand : y[tok, :]  = sum_s ybase[s][tok, :] + B_e ug[pos]
 #include "gemm_core.h"
 #include "kernels.h"
 
@@ -30,42 +34,51 @@ __device__ __forceinline__ bf16x8_t ldg_frag(const char *row, int k, int klen)
     return __builtin_bit_cast(bf16x8_t, v);
 }
 
-// grid (max_groups, ceil(r / 16)), 256 threads: the 4 waves split the d_in range.
-__global__ __launch_bounds__(256) void decode_shrink_kernel(
-    const char *x, const char *A_stack, char *ug_hi, char *ug_lo, const int *tok_sorted,
-    const int *grp_expert, const int *grp_start, const int *n_groups, int d_in, int r, float scale)
+constexpr int SHRINK_WAVES = 8;   // waves of a workgroup split the d_in range
+constexpr int SHRINK_BATCH = 4;   // k-steps (of 32) whose loads are issued together
+
+// grid (ceil(r / 16), max_groups): the slabs of one expert are neighbours in
+// dispatch order, so its rows of A_e stream from HBM as one contiguous run.
+__global__ __launch_bounds__(SHRINK_WAVES * 64) void decode_shrink_kernel(
+    const char *__restrict__ x, const char *__restrict__ A_stack, char *__restrict__ ug_hi,
+    char *__restrict__ ug_lo, const int *__restrict__ tok_sorted, const int4 *__restrict__ grp_meta,
+    const int *__restrict__ n_groups, int d_in, int r, float scale)
 {
-    __shared__ float red[4][64][4];
-    const int g = blockIdx.x;
+    constexpr int NW = SHRINK_WAVES, UNR = SHRINK_BATCH;
+    __shared__ float red[NW][64][4];
+    const int g = blockIdx.y;
     if (g >= uniform(*n_groups)) return;
-    const int e = uniform(grp_expert[g]);
+    const int4 gm = grp_meta[g];
+    const int e = uniform(gm.x);
     if (e < 0) return;
-    const int gs = uniform(grp_start[g]), ge = uniform(grp_start[g + 1]);
+    const int gs = uniform(gm.y), ge = uniform(gm.z);
     if (ge <= gs) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int j0 = blockIdx.y * 16;
+    const int j0 = blockIdx.x * 16;
     const int jrow = j0 + (lane & 15);
-    const bool jvalid = jrow < r;
     const int kq = (lane >> 4) * 8;               // element offset of this lane's k-group
     const int64_t ld = (int64_t)d_in * 2;
-    const char *arow = A_stack + ((int64_t)e * r + (jvalid ? jrow : 0)) * ld;
+    const char *arow = A_stack + ((int64_t)e * r + (jrow < r ? jrow : 0)) * ld;
+    // each wave owns a contiguous run of k-steps: its 16 rows are read as 16
+    // contiguous segments
     const int nks = (d_in + 31) / 32;
+    const int per = (nks + NW - 1) / NW;
+    const int ks_beg = wave * per;
+    const int ks_end = min(nks, ks_beg + per);
+    const int klen = min(d_in, ks_end * 32);
 
     for (int t0 = gs; t0 < ge; t0 += 16) {
         const int pos = t0 + (lane & 15);
         const bool tvalid = pos < ge;
-        const char *xrow = x + (int64_t)(tvalid ? tok_sorted[pos] : 0) * ld;
+        const char *xrow = x + (int64_t)tok_sorted[tvalid ? pos : gs] * ld;
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-        // UNR independent load pairs in flight per lane before the MFMAs that
-        // consume them; steps past the row end are zero-masked by ldg_frag
-        constexpr int UNR = 8;
-        for (int ks0 = wave; ks0 < nks; ks0 += 4 * UNR) {
+        for (int ks0 = ks_beg; ks0 < ks_end; ks0 += UNR) {
             bf16x8_t a[UNR], b[UNR];
 #pragma unroll
             for (int u = 0; u < UNR; ++u) {
-                const int k = (ks0 + 4 * u) * 32 + kq;
-                a[u] = ldg_frag(arow, k, d_in);
-                b[u] = ldg_frag(xrow, k, d_in);
+                const int k = (ks0 + u) * 32 + kq;   // past the wave's range: zero
+                a[u] = ldg_frag(arow, k, klen);
+                b[u] = ldg_frag(xrow, k, klen);
             }
 #pragma unroll
             for (int u = 0; u < UNR; ++u)
@@ -75,12 +88,15 @@ __global__ __launch_bounds__(256) void decode_shrink_kernel(
         for (int i = 0; i < 4; ++i) red[wave][lane][i] = acc[i];
         __syncthreads();
         if (wave == 0) {
-            // lane holds u[token = lane % 16][j0 + 4 * (lane / 16) + i]
+            // lane holds u[token = lane % 16][j0 + 4 * (lane / 16) + i]; the
+            // partial sums are added in wave order, so runs repeat bit for bit
             uint32_t h[4], l[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const float f =
-                    (red[0][lane][i] + red[1][lane][i] + red[2][lane][i] + red[3][lane][i]) * scale;
+                float f = 0.f;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) f += red[w][lane][i];
+                f *= scale;
                 h[i] = f32_to_bf16_bits(f);
                 l[i] = f32_to_bf16_bits(f - bf16_bits_to_f32(h[i]));
             }
@@ -95,70 +111,128 @@ __global__ __launch_bounds__(256) void decode_shrink_kernel(
     }
 }
 
-// grid (max_groups, ceil(d_out / 256)), 256 threads: each wave owns 64 rows of
-// B_e (a contiguous 64 * r * 2 byte slab).
-template <int KS_HOLD>
-__global__ __launch_bounds__(256) void decode_expand_kernel(
-    const char *B_stack, const char *ug_hi, const char *ug_lo, float *ylora, const int *tok_sorted,
-    const int *grp_expert, const int *grp_start, const int *n_groups, int d_out, int r)
+struct ExpandKParams {
+    const char *B_stack, *ug_hi, *ug_lo;
+    const float *ybase;        // [k_splits, T, d_out]
+    char *y;
+    const int *tok_sorted;
+    const int4 *grp_meta;
+    const int *n_groups;
+    int64_t T;
+    int d_out, r, k_splits, y_f32;
+};
+
+constexpr int EXPAND_WAVES = 4;
+constexpr int EXPAND_RB = 4;                                  // 16-row blocks per wave
+constexpr int EXPAND_ROWS = EXPAND_WAVES * EXPAND_RB * 16;    // output rows per workgroup
+
+// Sum of the base partial results for four consecutive outputs of one token,
+// in part order (repeatable).  NSPLIT is a compile-time count so that all the
+// loads can be issued together, ahead of the adapter loads.
+template <int NSPLIT>
+__device__ __forceinline__ f32x4_t base_sum(const ExpandKParams &p, int tok, int o)
 {
-    const int g = blockIdx.x;
-    if (g >= uniform(*n_groups)) return;
-    const int e = uniform(grp_expert[g]);
-    if (e < 0) return;
-    const int gs = uniform(grp_start[g]), ge = uniform(grp_start[g + 1]);
+    const int64_t at = (int64_t)tok * p.d_out + o;
+    const int64_t plane = p.T * (int64_t)p.d_out;
+    f32x4_t part[NSPLIT];
+#pragma unroll
+    for (int s = 0; s < NSPLIT; ++s) part[s] = *reinterpret_cast<const f32x4_t *>(p.ybase + s * plane + at);
+    f32x4_t v = part[0];
+#pragma unroll
+    for (int s = 1; s < NSPLIT; ++s) v += part[s];
+    return v;
+}
+
+__device__ __forceinline__ void store_out(const ExpandKParams &p, int tok, int o, f32x4_t v)
+{
+    const int64_t at = (int64_t)tok * p.d_out + o;
+    if (p.y_f32) {
+        *reinterpret_cast<f32x4_t *>(p.y + at * 4) = v;
+    } else {
+        *reinterpret_cast<uint2 *>(p.y + at * 2) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+    }
+}
+
+// grid (ceil(d_out / EXPAND_ROWS), max_groups).  KS_HOLD > 0: r <= 32 * KS_HOLD,
+// the u fragments of a token block stay in registers and all B_e fragments of
+// the wave's rows are requested before the first MFMA; KS_HOLD == 0: any r.
+// The accumulators start from the base result, so y leaves in one pass.
+template <int KS_HOLD, int NSPLIT>
+__global__ __launch_bounds__(EXPAND_WAVES * 64) void decode_expand_kernel(ExpandKParams p)
+{
+    const int g = blockIdx.y;
+    if (g >= uniform(*p.n_groups)) return;
+    const int4 gm = p.grp_meta[g];
+    const int e = uniform(gm.x);
+    const int gs = uniform(gm.y), ge = uniform(gm.z);
     if (ge <= gs) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int o_base = blockIdx.y * 256 + wave * 64;
-    if (o_base >= d_out) return;
+    const int o_base = (blockIdx.x * EXPAND_WAVES + wave) * (EXPAND_RB * 16);
+    if (o_base >= p.d_out) return;
     const int kq = (lane >> 4) * 8;
+    const int r = p.r, d_out = p.d_out;
     const int64_t ldb = (int64_t)r * 2;
-    const int nks = (r + 31) / 32;
-    const char *bexp = B_stack + (int64_t)e * d_out * ldb;
+    const char *bexp = p.B_stack + (int64_t)(e < 0 ? 0 : e) * d_out * ldb;
+    const bool lora = e >= 0 && r > 0;
 
     for (int t0 = gs; t0 < ge; t0 += 16) {
         const int pos = t0 + (lane & 15);
         const bool tvalid = pos < ge;
-        const int tok = tvalid ? tok_sorted[pos] : 0;
-        const char *uh = ug_hi + (int64_t)(tvalid ? pos : gs) * ldb;
-        const char *ul = ug_lo + (int64_t)(tvalid ? pos : gs) * ldb;
-        bf16x8_t fh[KS_HOLD > 0 ? KS_HOLD : 1], fl[KS_HOLD > 0 ? KS_HOLD : 1];
-        if (KS_HOLD > 0) {
+        const int tok = p.tok_sorted[tvalid ? pos : gs];
+        // lane holds y[token = lane % 16][o_base + c*16 + 4*(lane/16) + i]; rows
+        // past d_out read (and never store) the last valid group of four
+        f32x4_t acc[EXPAND_RB];
 #pragma unroll
-            for (int ks = 0; ks < KS_HOLD; ++ks) {
-                const int k = ks * 32 + kq;
-                fh[ks] = ldg_frag(uh, k, r);
-                fl[ks] = ldg_frag(ul, k, r);
+        for (int c = 0; c < EXPAND_RB; ++c) {
+            const int oo = o_base + c * 16 + 4 * (lane >> 4);
+            acc[c] = base_sum<NSPLIT>(p, tok, min(oo, d_out - 4));
+        }
+        if (lora) {
+            const char *uh = p.ug_hi + (int64_t)(tvalid ? pos : gs) * ldb;
+            const char *ul = p.ug_lo + (int64_t)(tvalid ? pos : gs) * ldb;
+            if constexpr (KS_HOLD > 0) {
+                bf16x8_t fh[KS_HOLD], fl[KS_HOLD];
+#pragma unroll
+                for (int ks = 0; ks < KS_HOLD; ++ks) {
+                    fh[ks] = ldg_frag(uh, ks * 32 + kq, r);
+                    fl[ks] = ldg_frag(ul, ks * 32 + kq, r);
+                }
+                bf16x8_t a[EXPAND_RB][KS_HOLD];
+#pragma unroll
+                for (int c = 0; c < EXPAND_RB; ++c) {
+                    const int orow = o_base + c * 16 + (lane & 15);
+                    const char *brow = bexp + (int64_t)(orow < d_out ? orow : 0) * ldb;
+#pragma unroll
+                    for (int ks = 0; ks < KS_HOLD; ++ks) a[c][ks] = ldg_frag(brow, ks * 32 + kq, r);
+                }
+#pragma unroll
+                for (int c = 0; c < EXPAND_RB; ++c)
+#pragma unroll
+                    for (int ks = 0; ks < KS_HOLD; ++ks) {
+                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[c][ks], fh[ks], acc[c], 0, 0, 0);
+                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[c][ks], fl[ks], acc[c], 0, 0, 0);
+                    }
+            } else {
+                const int nks = (r + 31) / 32;
+#pragma unroll
+                for (int c = 0; c < EXPAND_RB; ++c) {
+                    const int orow = o_base + c * 16 + (lane & 15);
+                    const char *brow = bexp + (int64_t)(orow < d_out ? orow : 0) * ldb;
+                    for (int ks = 0; ks < nks; ++ks) {
+                        const int k = ks * 32 + kq;
+                        const bf16x8_t a = ldg_frag(brow, k, r);
+                        const bf16x8_t bh = ldg_frag(uh, k, r);
+                        const bf16x8_t bl = ldg_frag(ul, k, r);
+                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[c], 0, 0, 0);
+                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[c], 0, 0, 0);
+                    }
+                }
             }
         }
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int orow = o_base + c * 16 + (lane & 15);
-            const bool ovalid = orow < d_out;
-            const char *brow = bexp + (int64_t)(ovalid ? orow : 0) * ldb;
-            f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-            if (KS_HOLD > 0) {
-#pragma unroll
-                for (int ks = 0; ks < KS_HOLD; ++ks) {
-                    const int k = ks * 32 + kq;
-                    const bf16x8_t a = ldg_frag(brow, k, r);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, fh[ks], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, fl[ks], acc, 0, 0, 0);
-                }
-            } else {
-                for (int ks = 0; ks < nks; ++ks) {
-                    const int k = ks * 32 + kq;
-                    const bf16x8_t a = ldg_frag(brow, k, r);
-                    const bf16x8_t bh = ldg_frag(uh, k, r);
-                    const bf16x8_t bl = ldg_frag(ul, k, r);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc, 0, 0, 0);
-                }
-            }
-            // lane holds ylora[token = lane % 16][o_base + c*16 + 4*(lane/16) + i]
+        for (int c = 0; c < EXPAND_RB; ++c) {
             const int oo = o_base + c * 16 + 4 * (lane >> 4);
-            if (tvalid && oo < d_out)   // d_out % 4 == 0
-                *reinterpret_cast<f32x4_t *>(ylora + (int64_t)tok * d_out + oo) = acc;
+            if (tvalid && oo < d_out) store_out(p, tok, oo, acc[c]);   // d_out % 4 == 0
         }
     }
 }
@@ -167,29 +241,40 @@ hipError_t launch_decode_shrink(const PlanView &pv, const DecodeArgs &d, hipStre
 {
     const LinearArgs &a = d.lin;
     if (a.r <= 0 || pv.max_groups <= 0) return hipSuccess;
-    dim3 grid((unsigned)pv.max_groups, (unsigned)((a.r + 15) / 16));
-    hipLaunchKernelGGL(decode_shrink_kernel, grid, dim3(256), 0, stream, (const char *)a.x,
-                       (const char *)a.A_stack, (char *)d.ug_hi, (char *)d.ug_lo, pv.tok_sorted,
-                       pv.grp_expert, pv.grp_start, pv.n_groups, a.d_in, a.r, a.scale);
+    dim3 grid((unsigned)((a.r + 15) / 16), (unsigned)pv.max_groups);
+    hipLaunchKernelGGL(decode_shrink_kernel, grid, dim3(SHRINK_WAVES * 64), 0, stream,
+                       (const char *)a.x, (const char *)a.A_stack, (char *)d.ug_hi, (char *)d.ug_lo,
+                       pv.tok_sorted, pv.grp_meta, pv.n_groups, a.d_in, a.r, a.scale);
     return hipGetLastError();
 }
 
 hipError_t launch_decode_expand(const PlanView &pv, const DecodeArgs &d, hipStream_t stream)
 {
     const LinearArgs &a = d.lin;
-    if (a.r <= 0 || pv.max_groups <= 0) return hipSuccess;
-    dim3 grid((unsigned)pv.max_groups, (unsigned)((a.d_out + 255) / 256));
+    if (pv.max_groups <= 0) return hipSuccess;
+    ExpandKParams p;
+    p.B_stack = (const char *)a.B_stack; p.ug_hi = (const char *)d.ug_hi; p.ug_lo = (const char *)d.ug_lo;
+    p.ybase = d.ybase; p.y = (char *)a.y;
+    p.tok_sorted = pv.tok_sorted; p.grp_meta = pv.grp_meta; p.n_groups = pv.n_groups;
+    p.T = pv.T; p.d_out = a.d_out; p.r = a.r; p.k_splits = d.k_splits; p.y_f32 = a.y_f32;
+    dim3 grid((unsigned)((a.d_out + EXPAND_ROWS - 1) / EXPAND_ROWS), (unsigned)pv.max_groups);
     const int nks = (a.r + 31) / 32;
-#define MOIN_EXPAND(KS)                                                                         \
-    hipLaunchKernelGGL(decode_expand_kernel<KS>, grid, dim3(256), 0, stream,                    \
-                       (const char *)a.B_stack, (const char *)d.ug_hi, (const char *)d.ug_lo,   \
-                       d.ylora, pv.tok_sorted, pv.grp_expert, pv.grp_start, pv.n_groups,        \
-                       a.d_out, a.r)
-    if (nks <= 1) MOIN_EXPAND(1);
-    else if (nks <= 2) MOIN_EXPAND(2);
-    else if (nks <= 4) MOIN_EXPAND(4);
-    else MOIN_EXPAND(0);
+#define MOIN_EXPAND_S(KS, NS) \
+    hipLaunchKernelGGL((decode_expand_kernel<KS, NS>), grid, dim3(EXPAND_WAVES * 64), 0, stream, p)
+#define MOIN_EXPAND(KS)                                  \
+    switch (d.k_splits) {                                \
+    case 1: MOIN_EXPAND_S(KS, 1); break;                 \
+    case 2: MOIN_EXPAND_S(KS, 2); break;                 \
+    case 3: MOIN_EXPAND_S(KS, 3); break;                 \
+    case 4: MOIN_EXPAND_S(KS, 4); break;                 \
+    default: return hipErrorInvalidValue;                \
+    }
+    if (nks <= 1) MOIN_EXPAND(1)
+    else if (nks <= 2) MOIN_EXPAND(2)
+    else if (nks <= 4) MOIN_EXPAND(4)
+    else MOIN_EXPAND(0)
 #undef MOIN_EXPAND
+#undef MOIN_EXPAND_S
     return hipGetLastError();
 }
 

@@ -24,9 +24,8 @@ struct PlanView {
     int *n_tiles;      // [1]
     // decode grouping (built only when T <= DECODE_MAX_T)
     int *tok_sorted;   // [T] token index, grouped by expert
-    int *row_expert;   // [T] adapter slot or -1 of each token (original order)
-    int *grp_expert;   // [max_groups]
-    int *grp_start;    // [max_groups + 1] range in tok_sorted
+    int4 *grp_meta;    // [max_groups] {adapter slot or -1, first, one-past-last position in tok_sorted, 0}
+    int *grp_start;    // [max_groups + 1] scratch while building
     int *n_groups;     // [1]
     // scratch used while building
     unsigned long long *keys; // [pow2 >= S]
@@ -57,11 +56,19 @@ hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStr
 struct DecodeArgs {
     LinearArgs lin;
     void *ug_hi, *ug_lo;   // [T, r] bf16, indexed by position in tok_sorted
-    float *ylora;          // [T, d_out] fp32, original token order
+    float *ybase;          // [k_splits, T, d_out] fp32 partial sums of x W^T over disjoint k ranges
+    int k_splits;
 };
-hipError_t launch_decode_shrink(const PlanView &pv, const DecodeArgs &a, hipStream_t stream);
-hipError_t launch_decode_expand(const PlanView &pv, const DecodeArgs &a, hipStream_t stream);
+// Number of k ranges the decode base GEMM is cut into for this shape (>= 1).
+int decode_base_splits(int64_t T, int d_in, int d_out);
+// ybase[s] = x[:, k range s] W[:, k range s]^T
 hipError_t launch_decode_base(const PlanView &pv, const DecodeArgs &a, hipStream_t stream);
+// ug = scale * A_e x per expert group
+hipError_t launch_decode_shrink(const PlanView &pv, const DecodeArgs &a, hipStream_t stream);
+// y = sum_s ybase[s] + B_e ug, rounded to the output type
+hipError_t launch_decode_expand(const PlanView &pv, const DecodeArgs &a, hipStream_t stream);
+// y = x W^T in one pass (no adapters anywhere in the call)
+hipError_t launch_decode_base_only(const PlanView &pv, const LinearArgs &a, hipStream_t stream);
 
 struct RouteArgs {
     const void *emb, *cent;

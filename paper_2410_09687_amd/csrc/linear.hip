@@ -7,8 +7,9 @@
 //            2r more contraction steps appended to the base GEMM of the same
 //            output tile, so y is written once, from one fp32 accumulator.
 // Tiles come from the plan: no tile spans two sequences, hence one adapter per
-// tile.  The same linear kernel, in a smaller tile shape, is the decode path's
-// base GEMM (it then adds the separately computed adapter term per token).
+// tile.  The same linear kernel, in a smaller tile shape and over a regular
+// grid of tiles, is the decode path's base GEMM; there the contraction range
+// may be cut into several parts, each writing its own fp32 partial result.
 #include "gemm_core.h"
 #include "kernels.h"
 
@@ -19,13 +20,13 @@ struct LinearKParams {
     const char *u_hi, *u_lo;
     char *y;
     const int *tile_row0, *tile_rows, *tile_expert, *n_tiles;
-    const float *ylora;      // decode combine (null in prefill)
-    const int *row_expert;   // decode combine
     int64_t T;
     int d_in, d_out, r;
     int n_tiles_n;
     int y_f32;
     int plain_tiles;         // 1: tiles are the regular grid over T, no adapters in-kernel
+    int k_splits;            // plain tiles only: parts of the contraction range, one output plane each
+    int kb_per_split;        // BK blocks per part
 };
 
 template <class C>
@@ -34,14 +35,23 @@ __global__ __launch_bounds__(C::NT) void linear_kernel(LinearKParams p)
     extern __shared__ __align__(16) char smem[];
     int ntm, row0, rows, e;
     int id;
+    int kb_lo = 0, kb_hi = (p.d_in + C::BK - 1) / C::BK;   // BK blocks of the base contraction
+    int split = 0;
     if (p.plain_tiles) {
+        // id = ((n tile * k_splits + part) * ntm + m tile): the tiles that share a
+        // slab of W are neighbours
         ntm = (int)((p.T + C::BM - 1) / C::BM);
-        id = xcd_band_id(blockIdx.x, ntm * p.n_tiles_n);
-        if (id < 0) return;
-        const int tm = uniform(id / p.n_tiles_n);
+        const int raw = xcd_band_id(blockIdx.x, ntm * p.n_tiles_n * p.k_splits);
+        if (raw < 0) return;
+        const int tm = uniform(raw % ntm);
+        const int rest = uniform(raw / ntm);
+        split = rest % p.k_splits;
+        id = tm * p.n_tiles_n + rest / p.k_splits;
         row0 = tm * C::BM;
         rows = (int)min((int64_t)C::BM, p.T - row0);
         e = -1;
+        kb_lo = split * p.kb_per_split;
+        kb_hi = min(kb_hi, kb_lo + p.kb_per_split);
     } else {
         // plan tiles are TILE_M rows; this kernel's BM divides TILE_M
         constexpr int SUB = TILE_M / C::BM;
@@ -62,7 +72,7 @@ __global__ __launch_bounds__(C::NT) void linear_kernel(LinearKParams p)
 
     const uint32_t ldx = (uint32_t)p.d_in * 2u, ldu = (uint32_t)p.r * 2u;
     const bool lora = (e >= 0) && p.r > 0;
-    const int nkb0 = (p.d_in + C::BK - 1) / C::BK;
+    const int nkb0 = kb_hi - kb_lo;
     const int nkb1 = lora ? (p.r + C::BK - 1) / C::BK : 0;
     // adapter operands are harmless aliases of x / W when the tile has no adapter
     const char *uh = lora ? p.u_hi + (int64_t)row0 * ldu : p.x;
@@ -90,7 +100,7 @@ __global__ __launch_bounds__(C::NT) void linear_kernel(LinearKParams p)
         const char *pa_ = base_ ? xa : (hi_ ? uh : ul);                                   \
         const char *pb_ = base_ ? wb : be;                                                \
         const uint32_t ld_ = base_ ? ldx : ldu;                                           \
-        const int kb_ = base_ ? b_ : (hi_ ? j_ : j_ - nkb1);                              \
+        const int kb_ = base_ ? b_ + kb_lo : (hi_ ? j_ : j_ - nkb1);                      \
         C::issue((stage), pa_, ld_, la, pb_, ld_, lb, (uint32_t)kb_ * (C::BK * 2));       \
     } while (0)
 #pragma unroll
@@ -116,7 +126,7 @@ __global__ __launch_bounds__(C::NT) void linear_kernel(LinearKParams p)
         const auto vb = C::template make_view<C::B_CH>(be, ldu, ncols);
         auto issue = [=](int it, typename C::Stage &g) __attribute__((always_inline)) {
             if (it < nkb0) {
-                C::load_stage(g, vx, vw, (uint32_t)it * (C::BK * 2), ldx);
+                C::load_stage(g, vx, vw, (uint32_t)(it + kb_lo) * (C::BK * 2), ldx);
             } else if (it < nkb0 + nkb1) {
                 C::load_stage(g, vuh, vb, (uint32_t)(it - nkb0) * (C::BK * 2), ldu);
             } else {
@@ -127,20 +137,10 @@ __global__ __launch_bounds__(C::NT) void linear_kernel(LinearKParams p)
     }
 
     const int64_t ldy = (int64_t)p.d_out * (p.y_f32 ? 4 : 2);
-    char *yb = p.y + (int64_t)row0 * ldy;
+    char *yb = p.y + ((int64_t)split * p.T + row0) * ldy;
     C::epilogue(smem, acc, [&](int row, int col, float(&v)[8]) {
         if (row >= rows || col >= ncols) return;
         const int gc = n0 + col;
-        if (p.ylora != nullptr && p.row_expert[row0 + row] >= 0) {
-            const float *yl = p.ylora + (int64_t)(row0 + row) * p.d_out + gc;
-            const f32x4_t a = *reinterpret_cast<const f32x4_t *>(yl);
-            const f32x4_t b = *reinterpret_cast<const f32x4_t *>(yl + 4);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                v[q] += a[q];
-                v[q + 4] += b[q];
-            }
-        }
         if (p.y_f32) {
             float *dst = reinterpret_cast<float *>(yb + (int64_t)row * ldy) + gc;
             *reinterpret_cast<f32x4_t *>(dst) = f32x4_t{v[0], v[1], v[2], v[3]};
@@ -240,7 +240,7 @@ using CfgMainDma = DmaCore<256, 256, 64, 4, 2, 2>;
 using CfgShrink = GemmCore<64, 64, 64, 2, 2>;        // 4 waves, wave patch 32 x 32
 using CfgShrinkDma = DmaCore<64, 64, 64, 2, 2, 4>;
 using CfgThin = GemmCore<128, 64, 64, 2, 2>;         // decode base GEMM: 4 waves, 64 x 32
-using CfgThinDma = DmaCore<128, 64, 64, 2, 2, 6>;
+using CfgThinDma = DmaCore<128, 64, 64, 2, 2, 3>;    // 72 KB of LDS: two workgroups per compute unit
 
 template <class K>
 static hipError_t allow_lds(K kern, int bytes)
@@ -307,36 +307,75 @@ hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStr
     p.y = (char *)a.y;
     p.tile_row0 = pv.tile_row0; p.tile_rows = pv.tile_rows; p.tile_expert = pv.tile_expert;
     p.n_tiles = pv.n_tiles;
-    p.ylora = nullptr; p.row_expert = nullptr;
     p.T = pv.T;
     p.d_in = a.d_in; p.d_out = a.d_out; p.r = a.r;
     p.n_tiles_n = 0;
     p.y_f32 = a.y_f32;
     p.plain_tiles = 0;
+    p.k_splits = 1; p.kb_per_split = 0;
     if (a.d_in % 64 == 0 && a.r % 64 == 0)
         return launch_linear_as<CfgMainDma>(p, pv.max_tiles, stream);
     return launch_linear_as<CfgMain>(p, pv.max_tiles, stream);
 }
 
-hipError_t launch_decode_base(const PlanView &pv, const DecodeArgs &d, hipStream_t stream)
+// The decode base GEMM has few output tiles (T <= 1024 rows); cutting the
+// contraction range gives the chip enough workgroups to keep many loads in
+// flight.  The parts are summed, in order, by the expand kernel.
+constexpr int DECODE_BASE_TARGET_WGS = 512;
+constexpr int DECODE_BASE_MAX_SPLITS = 4;   // the expand kernel sums up to four parts
+constexpr int DECODE_BASE_MIN_BLOCKS = 4;   // BK blocks per part at least
+
+static void decode_base_shape(int64_t T, int d_in, int d_out, int *k_splits, int *kb_per_split)
 {
-    const LinearArgs &a = d.lin;
+    const int64_t tiles = ((T + CfgThin::BM - 1) / CfgThin::BM) * ((d_out + CfgThin::BN - 1) / CfgThin::BN);
+    const int nkb = (d_in + CfgThin::BK - 1) / CfgThin::BK;
+    int want = (int)((DECODE_BASE_TARGET_WGS + tiles - 1) / (tiles > 0 ? tiles : 1));
+    if (want > DECODE_BASE_MAX_SPLITS) want = DECODE_BASE_MAX_SPLITS;
+    if (want > nkb / DECODE_BASE_MIN_BLOCKS) want = nkb / DECODE_BASE_MIN_BLOCKS;
+    if (want < 1) want = 1;
+    const int per = (nkb + want - 1) / want;
+    *kb_per_split = per;
+    *k_splits = (nkb + per - 1) / per;   // no empty part
+}
+
+int decode_base_splits(int64_t T, int d_in, int d_out)
+{
+    int ks, per;
+    decode_base_shape(T, d_in, d_out, &ks, &per);
+    return ks;
+}
+
+static hipError_t launch_plain(const PlanView &pv, const LinearArgs &a, void *out, int out_f32,
+                               int k_splits, int kb_per_split, hipStream_t stream)
+{
     if (pv.T <= 0) return hipSuccess;
     LinearKParams p;
     p.x = (const char *)a.x; p.W = (const char *)a.W; p.B_stack = nullptr;
     p.u_hi = nullptr; p.u_lo = nullptr;
-    p.y = (char *)a.y;
+    p.y = (char *)out;
     p.tile_row0 = nullptr; p.tile_rows = nullptr; p.tile_expert = nullptr; p.n_tiles = nullptr;
-    p.ylora = (a.r > 0) ? d.ylora : nullptr;
-    p.row_expert = pv.row_expert;
     p.T = pv.T;
     p.d_in = a.d_in; p.d_out = a.d_out; p.r = 0;
     p.n_tiles_n = 0;
-    p.y_f32 = a.y_f32;
+    p.y_f32 = out_f32;
     p.plain_tiles = 1;
+    p.k_splits = k_splits; p.kb_per_split = kb_per_split;
     const int64_t ntm = (pv.T + CfgThin::BM - 1) / CfgThin::BM;
-    if (a.d_in % 64 == 0) return launch_linear_as<CfgThinDma>(p, ntm, stream);
-    return launch_linear_as<CfgThin>(p, ntm, stream);
+    if (a.d_in % 64 == 0) return launch_linear_as<CfgThinDma>(p, ntm * k_splits, stream);
+    return launch_linear_as<CfgThin>(p, ntm * k_splits, stream);
+}
+
+hipError_t launch_decode_base(const PlanView &pv, const DecodeArgs &d, hipStream_t stream)
+{
+    int ks, per;
+    decode_base_shape(pv.T, d.lin.d_in, d.lin.d_out, &ks, &per);
+    if (ks != d.k_splits) return hipErrorInvalidValue;
+    return launch_plain(pv, d.lin, d.ybase, 1, ks, per, stream);
+}
+
+hipError_t launch_decode_base_only(const PlanView &pv, const LinearArgs &a, hipStream_t stream)
+{
+    return launch_plain(pv, a, a.y, a.y_f32, 1, (a.d_in + CfgThin::BK - 1) / CfgThin::BK, stream);
 }
 
 }  // namespace moin

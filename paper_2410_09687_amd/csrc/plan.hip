@@ -4,7 +4,9 @@
 // = no adapter, base model only).  For small batches the tokens themselves are
 // also grouped by expert, so that the decode kernels read each distinct
 // adapter once.  Everything happens on the device in one workgroup: the host
-// never looks at the ids.
+// never looks at the ids.  Offsets that do not tile [0, T) in order make the
+// whole batch base-only (and raise the sticky fault): every output row is still
+// written.
 #include "kernels.h"
 
 namespace moin {
@@ -50,6 +52,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
     // to L2); larger ones use the plan's global scratch
     __shared__ unsigned long long lds_keys[PLAN_LDS_S];
     __shared__ int lds_tmp[4 * (PLAN_LDS_S + 1)];
+    __shared__ int bad_offsets;
     const int tid = threadIdx.x;
     const int S = pv.S;
     const int T = (int)pv.T;
@@ -66,6 +69,8 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
 
     // 1. validate, build sort keys (expert + 1 in the high word: -1 sorts first)
     int err = 0;
+    if (tid == 0) bad_offsets = 0;
+    __syncthreads();
     if (tid == 0 && (seq_offsets[0] != 0 || seq_offsets[S] != T)) err |= ERR_BAD_OFFSETS;
     for (int s = tid; s < npow2; s += PLAN_THREADS) {
         unsigned long long key = ~0ull;
@@ -87,9 +92,27 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
         keys[s] = key;
     }
     if (err) atomicOr(err_word, err);
-    if (pv.decode)   // tokens that no (valid) sequence covers stay base-only
-        for (int t = tid; t < T; t += PLAN_THREADS) pv.row_expert[t] = -1;
+    if (err & ERR_BAD_OFFSETS) bad_offsets = 1;
     __syncthreads();
+    if (bad_offsets) {
+        // the sequences do not cover every token exactly once: one base-only
+        // sequence over the whole batch instead
+        const int nt = (T + TILE_M - 1) / TILE_M;   // <= max_tiles
+        for (int j = tid; j < nt; j += PLAN_THREADS) {
+            pv.tile_row0[j] = j * TILE_M;
+            pv.tile_rows[j] = min(TILE_M, T - j * TILE_M);
+            pv.tile_expert[j] = -1;
+        }
+        if (tid == 0) *pv.n_tiles = nt;
+        if (pv.decode) {
+            for (int t = tid; t < T; t += PLAN_THREADS) pv.tok_sorted[t] = t;
+            if (tid == 0) {
+                *pv.n_groups = 1;
+                pv.grp_meta[0] = make_int4(-1, 0, T, 0);
+            }
+        }
+        return;
+    }
 
     // 2. bitonic sort of the keys (workgroup-wide, in global memory)
     for (int k = 2; k <= npow2; k <<= 1) {
@@ -146,19 +169,23 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
             pv.tile_expert[tb + j] = e;
         }
         if (pv.decode) {
-            // offsets that overlap (flagged above) could list more than T
-            // tokens; everything past T is dropped
             const int base = min(a2[p], T);
-            for (int j = 0; j < len && base + j < T; ++j) {
-                pv.tok_sorted[base + j] = lo + j;
-                pv.row_expert[lo + j] = e;
-            }
+            for (int j = 0; j < len && base + j < T; ++j) pv.tok_sorted[base + j] = lo + j;
             const bool head = (p == 0) || ((keys[p - 1] >> 32) != (key >> 32));
             if (head) {
                 const int gi = a3[p];   // exclusive count of heads before p
-                pv.grp_expert[gi] = e;
+                pv.grp_meta[gi].x = e;
                 pv.grp_start[gi] = base;
             }
+        }
+    }
+    if (pv.decode) {
+        // a group ends where the next one starts
+        __syncthreads();
+        for (int gi = tid; gi < n_groups; gi += PLAN_THREADS) {
+            pv.grp_meta[gi].y = pv.grp_start[gi];
+            pv.grp_meta[gi].z = pv.grp_start[gi + 1];
+            pv.grp_meta[gi].w = 0;
         }
     }
 }

@@ -154,3 +154,19 @@ def test_device_side_data_faults_are_sticky_and_fall_back_to_base():
         y2 = moin.moin_lora_linear(c, inp.x, inp.seq_offsets, ok, inp.W, inp.A_stack, inp.B_stack, 2.0)
         c.check()
         assert torch.equal(y, y2)
+
+
+def test_offsets_that_do_not_tile_the_batch_give_base_only_rows_everywhere():
+    c = gc.ctx()
+    for lens in ([600, 600, 300], [3, 4, 5]):          # prefill and decode paths
+        inp = _case("badoff", 64, 64, 8, 2, lens, [0, 1, 0], seed=73)
+        bad = inp.seq_offsets.clone()
+        bad[1], bad[2] = inp.seq_offsets[2].item(), inp.seq_offsets[1].item()   # runs backwards
+        y = moin.moin_lora_linear(c, inp.x, bad, inp.expert_ids, inp.W, inp.A_stack, inp.B_stack, 2.0)
+        with pytest.raises(moin.MoinError) as ei:
+            c.check()
+        assert ei.value.code == -4
+        none = torch.full_like(inp.expert_ids, -1)
+        y2 = moin.moin_lora_linear(c, inp.x, inp.seq_offsets, none, inp.W, inp.A_stack, inp.B_stack, 2.0)
+        c.check()
+        assert torch.equal(y, y2)
