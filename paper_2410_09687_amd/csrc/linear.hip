@@ -232,11 +232,11 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
     });
 }
 
-// Tile shapes.  The *Dma variants need every contraction length (d_in, and r
-// for the linear kernel) to be a multiple of BK = 64; the register-staged ones
-// take any multiple of 8.
+// Tile shapes.  The *Dma variants need the contraction length to be a multiple
+// of BK = 64; the register-staged ones take any multiple of 8.  CfgMain is the
+// prefill fallback for shapes the streaming kernel (linear_stream.hip) does not
+// take.
 using CfgMain = GemmCore<256, 256, 64, 4, 2>;        // 8 waves, wave patch 64 x 128
-using CfgMainDma = DmaCore<256, 256, 64, 4, 2, 2>;
 using CfgShrink = GemmCore<64, 64, 64, 2, 2>;        // 4 waves, wave patch 32 x 32
 using CfgShrinkDma = DmaCore<64, 64, 64, 2, 2, 4>;
 using CfgThin = GemmCore<128, 64, 64, 2, 2>;         // decode base GEMM: 4 waves, 64 x 32
@@ -249,11 +249,15 @@ static hipError_t allow_lds(K kern, int bytes)
                                hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
 }
 
+hipError_t prepare_stream_kernel();
+bool stream_kernel_fits(const LinearArgs &a);
+hipError_t launch_linear_stream(const PlanView &pv, const LinearArgs &a, int n_cus, hipStream_t stream);
+
 hipError_t prepare_linear_kernels()
 {
     hipError_t e;
+    if ((e = prepare_stream_kernel()) != hipSuccess) return e;
     if ((e = allow_lds(&linear_kernel<CfgMain>, CfgMain::SMEM_BYTES)) != hipSuccess) return e;
-    if ((e = allow_lds(&linear_kernel<CfgMainDma>, CfgMainDma::SMEM_BYTES)) != hipSuccess) return e;
     if ((e = allow_lds(&linear_kernel<CfgThin>, CfgThin::SMEM_BYTES)) != hipSuccess) return e;
     if ((e = allow_lds(&linear_kernel<CfgThinDma>, CfgThinDma::SMEM_BYTES)) != hipSuccess) return e;
     if ((e = allow_lds(&shrink_kernel<CfgShrink>, CfgShrink::SMEM_BYTES)) != hipSuccess) return e;
@@ -261,6 +265,20 @@ hipError_t prepare_linear_kernels()
 }
 
 static inline int round_up8(int v) { return (v + 7) & ~7; }
+
+// Compute units of the current device (queried once per device).
+static int compute_units()
+{
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
+    }
+    return cached[dev];
+}
 
 template <class C>
 static hipError_t launch_shrink_as(const PlanView &pv, const LinearArgs &a, hipStream_t stream)
@@ -301,6 +319,7 @@ static hipError_t launch_linear_as(const LinearKParams &p0, int64_t m_tiles, hip
 hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStream_t stream)
 {
     if (pv.max_tiles <= 0) return hipSuccess;
+    if (stream_kernel_fits(a)) return launch_linear_stream(pv, a, compute_units(), stream);
     LinearKParams p;
     p.x = (const char *)a.x; p.W = (const char *)a.W; p.B_stack = (const char *)a.B_stack;
     p.u_hi = (const char *)a.u_hi; p.u_lo = (const char *)a.u_lo;
@@ -313,8 +332,6 @@ hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStr
     p.y_f32 = a.y_f32;
     p.plain_tiles = 0;
     p.k_splits = 1; p.kb_per_split = 0;
-    if (a.d_in % 64 == 0 && a.r % 64 == 0)
-        return launch_linear_as<CfgMainDma>(p, pv.max_tiles, stream);
     return launch_linear_as<CfgMain>(p, pv.max_tiles, stream);
 }
 

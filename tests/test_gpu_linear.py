@@ -49,6 +49,30 @@ def test_prefill_ragged_tiles_and_tails():
     _full_check(inp, "ragged_prefill")
 
 
+def test_prefill_streaming_kernel_ragged_tiles_mixed_adapters():
+    # shapes the persistent streaming kernel takes (d_in, r multiples of 64): ragged
+    # token tiles, an output tail of 8 columns, base-only sequences between adapter
+    # ones, rank spanning two k blocks
+    lens = [300, 1, 0, 257, 255, 512, 77, 256, 3, 640]
+    ids = [3, 0, 5, -1, 3, 6, 2, 2, -1, 1]
+    inp = _case("stream_ragged", 192, 520, 128, 7, lens, ids, seed=11)
+    assert inp.wl.T > 1024
+    _full_check(inp, "stream_ragged")
+    # a single tile (fewer work items than workgroups), d_in at the two-block minimum
+    inp = _case("stream_one_tile", 128, 64, 64, 2, [1030], [1], seed=12)
+    _full_check(inp, "stream_one_tile")
+
+
+def test_prefill_streaming_kernel_many_tiles_per_workgroup():
+    # > 256 * 8 work items: every workgroup walks several tiles, adapter and
+    # base-only tiles alternating in its stream
+    rng = np.random.default_rng(5)
+    lens = rng.integers(1, 300, size=700).tolist()
+    ids = rng.integers(-1, 4, size=700).tolist()
+    inp = _case("stream_many", 128, 1024, 64, 4, lens, ids, seed=13)
+    _full_check(inp, "stream_many")
+
+
 def test_prefill_rank_multiple_tiles():
     # r = 136 spans several rank tiles of the shrink and three K blocks of the expand
     inp = _case("rank136", 192, 520, 136, 3, [700, 400], [2, 0], seed=77)
