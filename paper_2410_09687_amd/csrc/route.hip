@@ -11,6 +11,8 @@
 // centroid tiles in ascending order, which makes "lowest index wins a tie"
 // fall out of a strict '<'.
 // fp32 path: small inputs only; direct sum of squared differences in fp32.
+#include <type_traits>
+
 #include "gemm_core.h"
 #include "kernels.h"
 
@@ -168,6 +170,191 @@ __global__ __launch_bounds__(C::NT) void route_kernel(RouteKParams p)
     }
     float *sv = reinterpret_cast<float *>(smem);                  // [WM][BN]
     int *si = reinterpret_cast<int *>(smem + C::WM * C::BN * 4);  // [WM][BN]
+    if (lane < 32) {
+#pragma unroll
+        for (int j = 0; j < C::FN; ++j) {
+            const int col = wn * C::WTN + j * 32 + lane;
+            sv[wm * C::BN + col] = bestv[j];
+            si[wm * C::BN + col] = besti[j];
+        }
+    }
+    __syncthreads();
+    for (int col = threadIdx.x; col < nq; col += C::NT) {
+        float bv = sv[col];
+        int bi = si[col];
+#pragma unroll
+        for (int w = 1; w < C::WM; ++w) {
+            const float v = sv[w * C::BN + col];
+            const int i = si[w * C::BN + col];
+            if (lex_less(v, i, bv, bi)) {
+                bv = v;
+                bi = i;
+            }
+        }
+        if (p.cid) p.cid[q0 + col] = bi;
+        if (p.expert_ids) p.expert_ids[q0 + col] = p.slot ? p.slot[bi] : bi;
+    }
+}
+
+// Large batches, D a multiple of 64: same tiling as route_kernel, with the
+// block pipeline of the prefill linear kernel -- two direct-to-LDS stages, MFMA
+// fragments read one k-step ahead, the block barrier placed before the last
+// k-step (whose fragments are already in registers) and the first fragments of
+// the next block read during that k-step.  The blocks of all centroid tiles
+// form one stream; a finished tile is folded into the running minima between
+// two blocks.
+__global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKParams p)
+{
+    using C = CfgRouteDma;
+    extern __shared__ __align__(16) char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = uniform(threadIdx.x >> 6);
+    const int wm = wave / C::WN, wn = wave % C::WN;
+    const int r = lane & 31, h = lane >> 5;
+    const int64_t q0 = (int64_t)blockIdx.x * C::BN;
+    const int nq = (int)min((int64_t)C::BN, p.N - q0);
+    const uint32_t ld = (uint32_t)p.D * 2u;
+    const int nkb = p.D / C::BK;
+    const int nct = (p.K + C::BM - 1) / C::BM;
+    const int last_rows = p.K - (nct - 1) * C::BM;
+    const char *qb = p.emb + q0 * (int64_t)ld;
+    const int total = nct * nkb;
+
+    // DMA mapping (see DmaCore): instruction j of a wave fills tile rows
+    // (wave*4 + j)*8 .. +8; only j's parity enters the chunk swizzle
+    constexpr int LOADS = C::A_I;
+    static_assert(C::A_I == 4 && C::B_I == 4 && C::KSTEPS == 4 && C::NS == 2, "pipeline shape");
+    const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8) + (lane >> 3));
+    uint32_t dma_c16[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) dma_c16[j] = (uint32_t)(((lane & 7) ^ (((j * 8 + (lane >> 3)) >> 1) & 7)) * 16);
+    uint32_t q_off[LOADS];   // query rows never change
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j)
+        q_off[j] = min(dma_row + 8u * j, (uint32_t)(nq - 1)) * ld + dma_c16[j & 1];
+
+    auto issue = [&](int ct, int kb, char *stage) __attribute__((always_inline)) {
+        const char *cb = p.cent + (int64_t)ct * C::BM * ld;
+        const uint32_t rows = (uint32_t)((ct == nct - 1) ? last_rows : C::BM);
+        const uint32_t kbyte = (uint32_t)kb * (C::BK * 2);
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            const uint32_t row = min(dma_row + 8u * j, rows - 1u);
+            const uint32_t off = __umul24(row, ld) + dma_c16[j & 1] + kbyte;
+            __builtin_amdgcn_global_load_lds(MOIN_GPTR(cb + off), MOIN_LPTR(stage + (wave * LOADS + j) * 1024), 16, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j)
+            __builtin_amdgcn_global_load_lds(MOIN_GPTR(qb + (q_off[j] + kbyte)),
+                                             MOIN_LPTR(stage + C::A_BYTES + (wave * LOADS + j) * 1024), 16, 0, 0);
+    };
+
+    const int f = (r >> 1) & 7;
+    const int offA = (wm * C::WTM + r) * C::ROWB, offB = C::A_BYTES + (wn * C::WTN + r) * C::ROWB;
+    bf16x8_t fa[2][C::FM], fb[2][C::FN];
+    auto read_frags = [&](const char *stage, int ks, int slot) __attribute__((always_inline)) {
+        const int o = (((ks * 2 + h) ^ f) & 7) * 16;
+#pragma unroll
+        for (int i = 0; i < C::FM; ++i)
+            fa[slot][i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(stage + offA + i * 32 * C::ROWB + o));
+#pragma unroll
+        for (int j = 0; j < C::FN; ++j)
+            fb[slot][j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(stage + offB + j * 32 * C::ROWB + o));
+    };
+    typename C::Acc acc;
+    C::zero(acc);
+    auto mfmas = [&](int slot) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+            for (int j = 0; j < C::FN; ++j)
+                acc.v[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc.v[i][j], 0, 0, 0);
+    };
+
+    float bestv[C::FN];
+    int besti[C::FN];
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j) {
+        bestv[j] = __builtin_inff();
+        besti[j] = 0;
+    }
+
+    int kb = 0, ct = 0;        // block being computed
+    int pkb = 2, pct = 0;      // block to fetch next (two ahead)
+    while (pkb >= nkb) {       // D = 64: one block per centroid tile
+        pkb -= nkb;
+        ++pct;
+    }
+    auto body = [&](int s, auto issue_tag, auto read_tag) __attribute__((always_inline)) {
+        constexpr bool ISSUE = decltype(issue_tag)::value, READ = decltype(read_tag)::value;
+        char *st_cur = smem + (s & 1) * C::STAGE_BYTES;
+        const char *st_nxt = smem + ((s + 1) & 1) * C::STAGE_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < C::KSTEPS - 1; ++ks) {
+            read_frags(st_cur, ks + 1, (ks + 1) & 1);
+            mfmas(ks & 1);
+#pragma unroll
+            for (int n = 0; n < C::FM + C::FN; ++n) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, C::FM * C::FN - (C::FM + C::FN), 0);
+        }
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if constexpr (ISSUE) {
+            issue(pct, pkb, st_cur);
+            if (++pkb == nkb) {
+                pkb = 0;
+                ++pct;
+            }
+        }
+        if constexpr (READ) read_frags(st_nxt, 0, 0);
+        mfmas((C::KSTEPS - 1) & 1);
+        if constexpr (ISSUE && READ) {
+#pragma unroll
+            for (int n = 0; n < C::FM * C::FN; ++n) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                if (n < C::FM + C::FN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+        }
+        if (++kb == nkb) {
+            fold_scores<C>(acc, p.cnorm + ct * C::BM, ct * C::BM, bestv, besti);
+            C::zero(acc);
+            kb = 0;
+            ++ct;
+        }
+    };
+
+    issue(0, 0, smem);
+    if (total > 1) {
+        issue(nkb > 1 ? 0 : 1, nkb > 1 ? 1 : 0, smem + C::STAGE_BYTES);
+        wait_vm_then_barrier<2 * LOADS>();
+    } else {
+        wait_vm_then_barrier<0>();
+    }
+    read_frags(smem, 0, 0);
+    int s = 0;
+    for (; s < total - 2; ++s) body(s, std::true_type{}, std::true_type{});
+    if (total > 1) {
+        body(s, std::false_type{}, std::true_type{});
+        ++s;
+    }
+    body(s, std::false_type{}, std::false_type{});
+    __syncthreads();
+
+    // merge the two lane halves (rows 4*(lane>>5) interleave), then the WM waves
+#pragma unroll
+    for (int j = 0; j < C::FN; ++j) {
+        const float ov = __shfl_xor(bestv[j], 32);
+        const int oi = __shfl_xor(besti[j], 32);
+        if (lex_less(ov, oi, bestv[j], besti[j])) {
+            bestv[j] = ov;
+            besti[j] = oi;
+        }
+    }
+    float *sv = reinterpret_cast<float *>(smem);
+    int *si = reinterpret_cast<int *>(smem + C::WM * C::BN * 4);
     if (lane < 32) {
 #pragma unroll
         for (int j = 0; j < C::FN; ++j) {
@@ -403,7 +590,7 @@ hipError_t prepare_route_kernels()
 {
     hipError_t e;
     if ((e = allow_lds(&route_kernel<CfgRoute>, CfgRoute::SMEM_BYTES)) != hipSuccess) return e;
-    if ((e = allow_lds(&route_kernel<CfgRouteDma>, CfgRouteDma::SMEM_BYTES)) != hipSuccess) return e;
+    if ((e = allow_lds(&route_stream_kernel, CfgRouteDma::SMEM_BYTES)) != hipSuccess) return e;
     return allow_lds(&route_small_kernel<CfgRouteSmall>, CfgRouteSmall::SMEM_BYTES);
 }
 
@@ -443,7 +630,7 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t stream)
         const int64_t grid = (a.N + CfgRoute::BN - 1) / CfgRoute::BN;
         if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
         if (a.D % 64 == 0)
-            hipLaunchKernelGGL(route_kernel<CfgRouteDma>, dim3((unsigned)grid), dim3(CfgRouteDma::NT),
+            hipLaunchKernelGGL(route_stream_kernel, dim3((unsigned)grid), dim3(CfgRouteDma::NT),
                                CfgRouteDma::SMEM_BYTES, stream, p);
         else
             hipLaunchKernelGGL(route_kernel<CfgRoute>, dim3((unsigned)grid), dim3(CfgRoute::NT),

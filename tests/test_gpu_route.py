@@ -27,6 +27,18 @@ def test_bf16_router_small(N, K, D):
     assert torch.equal(counts.long(), torch.bincount(cids.long(), minlength=K))
 
 
+@pytest.mark.parametrize("N,K,D", [(5000, 700, 128), (4100, 300, 64), (4097, 256, 192), (4500, 100, 64)])
+def test_bf16_router_streaming_kernel_edges(N, K, D):
+    # more than 4096 queries and D a multiple of 64: the large-batch kernel, with a
+    # ragged last centroid tile, a ragged last query tile, one or two k blocks per tile
+    rin = _route_case(N, K, D, "bf16", True, seed=N + K + D)
+    print(f"[gpu] route bf16 stream N={N} K={K} D={D}", flush=True)
+    eids, cids, counts = moin.moin_route(gc.ctx(), rin.emb, rin.centroids, want_counts=True)
+    gc.ctx().check()
+    gc.check_route(rin.emb, rin.centroids, cids)
+    assert torch.equal(counts.long(), torch.bincount(cids.long(), minlength=K))
+
+
 def test_f32_router_small():
     rin = _route_case(300, 77, 100, "f32", False, seed=3)
     eids, cids, counts = moin.moin_route(gc.ctx(), rin.emb, rin.centroids, want_counts=True)
