@@ -56,9 +56,10 @@ typedef enum {
     MOIN_K_LINEAR = 2,        /* prefill: y = x W^T + u B_e^T (base + expand)   */
     MOIN_K_ROUTE = 3,         /* distance GEMM fused with argmin                */
     MOIN_K_ROUTE_AUX = 4,     /* centroid norms, histogram, slot map            */
-    MOIN_K_DECODE_SHRINK = 5, /* decode: gather-matvec u = s * A_e x            */
+    MOIN_K_DECODE_SHRINK = 5, /* decode: gather-matvec u = s * A_e x; also holds
+                                 the base GEMM when both share one launch       */
     MOIN_K_DECODE_EXPAND = 6, /* decode: gather-matvec B_e u + base, writes y   */
-    MOIN_K_DECODE_BASE = 7,   /* decode: thin base GEMM (fp32 partial sums)     */
+    MOIN_K_DECODE_BASE = 7,   /* decode: thin base GEMM launched on its own     */
     MOIN_K_COUNT = 8
 } moin_kernel_id;
 

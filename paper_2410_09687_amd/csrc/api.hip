@@ -14,10 +14,12 @@
 namespace moin {
 hipError_t prepare_linear_kernels();
 hipError_t prepare_route_kernels();
+hipError_t prepare_decode_kernels();
 hipError_t prepare_kernels()
 {
     hipError_t e = prepare_linear_kernels();
     if (e != hipSuccess) return e;
+    if ((e = prepare_decode_kernels()) != hipSuccess) return e;
     return prepare_route_kernels();
 }
 }  // namespace moin
@@ -295,12 +297,18 @@ int linear_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, con
     d.ug_hi = w;
     d.ug_lo = w + u_bytes;
     d.ybase = reinterpret_cast<float *>(w + 2 * u_bytes);
-    if (timed(ctx, MOIN_K_DECODE_BASE, stream, [&] { return launch_decode_base(pv, d, stream); }) !=
-        hipSuccess)
-        return MOIN_EHIP;
-    if (timed(ctx, MOIN_K_DECODE_SHRINK, stream, [&] { return launch_decode_shrink(pv, d, stream); }) !=
-        hipSuccess)
-        return MOIN_EHIP;
+    if (decode_base_shrink_fits(pv, d)) {
+        if (timed(ctx, MOIN_K_DECODE_SHRINK, stream, [&] { return launch_decode_base_shrink(pv, d, stream); }) !=
+            hipSuccess)
+            return MOIN_EHIP;
+    } else {
+        if (timed(ctx, MOIN_K_DECODE_BASE, stream, [&] { return launch_decode_base(pv, d, stream); }) !=
+            hipSuccess)
+            return MOIN_EHIP;
+        if (timed(ctx, MOIN_K_DECODE_SHRINK, stream, [&] { return launch_decode_shrink(pv, d, stream); }) !=
+            hipSuccess)
+            return MOIN_EHIP;
+    }
     if (timed(ctx, MOIN_K_DECODE_EXPAND, stream, [&] { return launch_decode_expand(pv, d, stream); }) !=
         hipSuccess)
         return MOIN_EHIP;

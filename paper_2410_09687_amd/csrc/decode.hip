@@ -18,6 +18,7 @@
 //   expand : y[tok, :]  = sum_s ybase[s][tok, :] + B_e ug[pos]
 #include "gemm_core.h"
 #include "kernels.h"
+#include "linear_tile.h"
 
 namespace moin {
 
@@ -37,16 +38,32 @@ __device__ __forceinline__ bf16x8_t ldg_frag(const char *row, int k, int klen)
 constexpr int SHRINK_WAVES = 8;   // waves of a workgroup split the d_in range
 constexpr int SHRINK_BATCH = 4;   // k-steps (of 32) whose loads are issued together
 
-// grid (ceil(r / 16), max_groups): the slabs of one expert are neighbours in
-// dispatch order, so its rows of A_e stream from HBM as one contiguous run.
-__global__ __launch_bounds__(SHRINK_WAVES * 64) void decode_shrink_kernel(
-    const char *__restrict__ x, const char *__restrict__ A_stack, char *__restrict__ ug_hi,
-    char *__restrict__ ug_lo, const int *__restrict__ tok_sorted, const int4 *__restrict__ grp_meta,
-    const int *__restrict__ n_groups, int d_in, int r, float scale)
+struct ShrinkDParams {
+    const char *x, *A_stack;
+    char *ug_hi, *ug_lo;
+    const int *tok_sorted;
+    const int4 *grp_meta;
+    const int *n_groups;
+    int d_in, r;
+    float scale;
+};
+
+// One (expert group g, 16-row slab of A_e) of the decode shrink; `red` is the
+// workgroup's [SHRINK_WAVES][64][4] floats of LDS.
+template <int UNR>
+__device__ __forceinline__ void decode_shrink_slab(const ShrinkDParams &p, int slab, int g,
+                                                   float (*red)[64][4])
 {
-    constexpr int NW = SHRINK_WAVES, UNR = SHRINK_BATCH;
-    __shared__ float red[NW][64][4];
-    const int g = blockIdx.y;
+    constexpr int NW = SHRINK_WAVES;
+    const char *__restrict__ x = p.x;
+    const char *__restrict__ A_stack = p.A_stack;
+    char *__restrict__ ug_hi = p.ug_hi;
+    char *__restrict__ ug_lo = p.ug_lo;
+    const int *__restrict__ tok_sorted = p.tok_sorted;
+    const int4 *__restrict__ grp_meta = p.grp_meta;
+    const int *__restrict__ n_groups = p.n_groups;
+    const int d_in = p.d_in, r = p.r;
+    const float scale = p.scale;
     if (g >= uniform(*n_groups)) return;
     const int4 gm = grp_meta[g];
     const int e = uniform(gm.x);
@@ -54,7 +71,7 @@ __global__ __launch_bounds__(SHRINK_WAVES * 64) void decode_shrink_kernel(
     const int gs = uniform(gm.y), ge = uniform(gm.z);
     if (ge <= gs) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int j0 = blockIdx.x * 16;
+    const int j0 = slab * 16;
     const int jrow = j0 + (lane & 15);
     const int kq = (lane >> 4) * 8;               // element offset of this lane's k-group
     const int64_t ld = (int64_t)d_in * 2;
@@ -70,8 +87,8 @@ __global__ __launch_bounds__(SHRINK_WAVES * 64) void decode_shrink_kernel(
     for (int t0 = gs; t0 < ge; t0 += 16) {
         const int pos = t0 + (lane & 15);
         const bool tvalid = pos < ge;
-        const char *xrow = x + (int64_t)tok_sorted[tvalid ? pos : gs] * ld;
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        const char *xrow = x + (int64_t)tok_sorted[tvalid ? pos : gs] * ld;
         for (int ks0 = ks_beg; ks0 < ks_end; ks0 += UNR) {
             bf16x8_t a[UNR], b[UNR];
 #pragma unroll
@@ -108,6 +125,33 @@ __global__ __launch_bounds__(SHRINK_WAVES * 64) void decode_shrink_kernel(
             }
         }
         __syncthreads();
+    }
+}
+
+// grid (ceil(r / 16), max_groups): the slabs of one expert are neighbours in
+// dispatch order, so its rows of A_e stream from HBM as one contiguous run.
+__global__ __launch_bounds__(SHRINK_WAVES * 64) void decode_shrink_kernel(ShrinkDParams p)
+{
+    __shared__ float red[SHRINK_WAVES][64][4];
+    decode_shrink_slab<SHRINK_BATCH>(p, (int)blockIdx.x, (int)blockIdx.y, red);
+}
+
+// Base GEMM tiles and shrink slabs in one launch: the two are independent, the
+// shrink is bound by HBM and the base GEMM by the latency of its short serial
+// loops, so side by side the base GEMM costs little time of its own.  The
+// first `n_base` workgroups take base tiles (dispatched first, they run
+// longest), the others one shrink slab each.
+static_assert(CfgDecodeBase::NT == SHRINK_WAVES * 64, "both roles share one workgroup size");
+__global__ __launch_bounds__(SHRINK_WAVES * 64) void decode_base_shrink_kernel(LinearKParams lp, ShrinkDParams sp,
+                                                                             int n_base, int n_slabs)
+{
+    extern __shared__ __align__(16) char smem[];
+    __shared__ float red[SHRINK_WAVES][64][4];
+    if ((int)blockIdx.x < n_base) {
+        linear_tile<CfgDecodeBase>(lp, (int)blockIdx.x, smem);
+    } else {
+        const int idx = (int)blockIdx.x - n_base;
+        decode_shrink_slab<SHRINK_BATCH>(sp, idx % n_slabs, idx / n_slabs, red);
     }
 }
 
@@ -237,14 +281,50 @@ __global__ __launch_bounds__(EXPAND_WAVES * 64) void decode_expand_kernel(Expand
     }
 }
 
+static ShrinkDParams shrink_params(const PlanView &pv, const DecodeArgs &d)
+{
+    const LinearArgs &a = d.lin;
+    ShrinkDParams p;
+    p.x = (const char *)a.x; p.A_stack = (const char *)a.A_stack;
+    p.ug_hi = (char *)d.ug_hi; p.ug_lo = (char *)d.ug_lo;
+    p.tok_sorted = pv.tok_sorted; p.grp_meta = pv.grp_meta; p.n_groups = pv.n_groups;
+    p.d_in = a.d_in; p.r = a.r; p.scale = a.scale;
+    return p;
+}
+
 hipError_t launch_decode_shrink(const PlanView &pv, const DecodeArgs &d, hipStream_t stream)
 {
     const LinearArgs &a = d.lin;
     if (a.r <= 0 || pv.max_groups <= 0) return hipSuccess;
     dim3 grid((unsigned)((a.r + 15) / 16), (unsigned)pv.max_groups);
-    hipLaunchKernelGGL(decode_shrink_kernel, grid, dim3(SHRINK_WAVES * 64), 0, stream,
-                       (const char *)a.x, (const char *)a.A_stack, (char *)d.ug_hi, (char *)d.ug_lo,
-                       pv.tok_sorted, pv.grp_meta, pv.n_groups, a.d_in, a.r, a.scale);
+    hipLaunchKernelGGL(decode_shrink_kernel, grid, dim3(SHRINK_WAVES * 64), 0, stream, shrink_params(pv, d));
+    return hipGetLastError();
+}
+
+bool decode_base_shrink_fits(const PlanView &pv, const DecodeArgs &d)
+{
+    return d.lin.r > 0 && pv.max_groups > 0 && pv.T > 0 &&
+           decode_base_shape(pv.T, d.lin.d_in, d.lin.d_out).dma;
+}
+
+hipError_t prepare_decode_kernels()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_base_shrink_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, CfgDecodeBase::SMEM_BYTES);
+}
+
+hipError_t launch_decode_base_shrink(const PlanView &pv, const DecodeArgs &d, hipStream_t stream)
+{
+    const LinearArgs &a = d.lin;
+    const DecodeBaseShape sh = decode_base_shape(pv.T, a.d_in, a.d_out);
+    if (!sh.dma || sh.k_splits != d.k_splits) return hipErrorInvalidValue;
+    const LinearKParams lp = decode_base_params(pv, a, d.ybase, 1, sh);
+    const int n_slabs = (a.r + 15) / 16;
+    const int64_t n_shrink = (int64_t)n_slabs * pv.max_groups;
+    const int64_t grid = (int64_t)sh.grid + n_shrink;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(decode_base_shrink_kernel, dim3((unsigned)grid), dim3(SHRINK_WAVES * 64),
+                       CfgDecodeBase::SMEM_BYTES, stream, lp, shrink_params(pv, d), sh.grid, n_slabs);
     return hipGetLastError();
 }
 

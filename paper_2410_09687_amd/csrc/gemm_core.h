@@ -302,6 +302,7 @@ struct DmaCore {
 
     static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "load mapping");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0 && BK % 16 == 0 && NS >= 2, "tiling");
+    static_assert(ROWB <= 256 && 256 % ROWB == 0, "swizzle");
     static_assert((NS - 2) * LPB < 64, "vmcnt field");
 
     struct Acc {
@@ -321,9 +322,10 @@ struct DmaCore {
     // A wave instruction writes 64 consecutive 16-byte slots of LDS, so LDS slot
     // p of an operand tile is (row p / KCH, physical chunk p % KCH).  The lane
     // that fills it fetches logical chunk (p % KCH) ^ swz(row) from global
-    // memory; readers apply the same XOR.  With swz(row) = (row >> 1) % KCH the
-    // ds_read_b128 of 32 consecutive rows at one logical chunk is conflict-free.
-    __device__ static __forceinline__ int swz(int row) { return (row >> 1) & (KCH - 1); }
+    // memory; readers apply the same XOR.  With swz(row) = (row / rows per 256
+    // bytes) % KCH the ds_read_b128 of 32 consecutive rows at one logical chunk
+    // is conflict-free.
+    __device__ static __forceinline__ int swz(int row) { return (row / (256 / ROWB)) & (KCH - 1); }
 
     // For each of its wave's NI load instructions: the tile row this lane
     // fetches and the byte offset of its (swizzled) 16-byte chunk inside a BK

@@ -67,6 +67,9 @@ hipError_t launch_decode_base(const PlanView &pv, const DecodeArgs &a, hipStream
 hipError_t launch_decode_shrink(const PlanView &pv, const DecodeArgs &a, hipStream_t stream);
 // y = sum_s ybase[s] + B_e ug, rounded to the output type
 hipError_t launch_decode_expand(const PlanView &pv, const DecodeArgs &a, hipStream_t stream);
+// base GEMM and shrink in one launch (shapes for which decode_base_shrink_fits)
+bool decode_base_shrink_fits(const PlanView &pv, const DecodeArgs &a);
+hipError_t launch_decode_base_shrink(const PlanView &pv, const DecodeArgs &a, hipStream_t stream);
 // y = x W^T in one pass (no adapters anywhere in the call)
 hipError_t launch_decode_base_only(const PlanView &pv, const LinearArgs &a, hipStream_t stream);
 

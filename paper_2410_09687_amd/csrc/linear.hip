@@ -12,149 +12,10 @@
 // may be cut into several parts, each writing its own fp32 partial result.
 #include "gemm_core.h"
 #include "kernels.h"
+#include "linear_tile.h"
 
 namespace moin {
 
-struct LinearKParams {
-    const char *x, *W, *B_stack;
-    const char *u_hi, *u_lo;
-    char *y;
-    const int *tile_row0, *tile_rows, *tile_expert, *n_tiles;
-    int64_t T;
-    int d_in, d_out, r;
-    int n_tiles_n;
-    int y_f32;
-    int plain_tiles;         // 1: tiles are the regular grid over T, no adapters in-kernel
-    int k_splits;            // plain tiles only: parts of the contraction range, one output plane each
-    int kb_per_split;        // BK blocks per part
-};
-
-template <class C>
-__global__ __launch_bounds__(C::NT) void linear_kernel(LinearKParams p)
-{
-    extern __shared__ __align__(16) char smem[];
-    int ntm, row0, rows, e;
-    int id;
-    int kb_lo = 0, kb_hi = (p.d_in + C::BK - 1) / C::BK;   // BK blocks of the base contraction
-    int split = 0;
-    if (p.plain_tiles) {
-        // id = ((n tile * k_splits + part) * ntm + m tile): the tiles that share a
-        // slab of W are neighbours
-        ntm = (int)((p.T + C::BM - 1) / C::BM);
-        const int raw = xcd_band_id(blockIdx.x, ntm * p.n_tiles_n * p.k_splits);
-        if (raw < 0) return;
-        const int tm = uniform(raw % ntm);
-        const int rest = uniform(raw / ntm);
-        split = rest % p.k_splits;
-        id = tm * p.n_tiles_n + rest / p.k_splits;
-        row0 = tm * C::BM;
-        rows = (int)min((int64_t)C::BM, p.T - row0);
-        e = -1;
-        kb_lo = split * p.kb_per_split;
-        kb_hi = min(kb_hi, kb_lo + p.kb_per_split);
-    } else {
-        // plan tiles are TILE_M rows; this kernel's BM divides TILE_M
-        constexpr int SUB = TILE_M / C::BM;
-        ntm = uniform(*p.n_tiles) * SUB;
-        id = xcd_band_id(blockIdx.x, ntm * p.n_tiles_n);
-        if (id < 0) return;
-        const int tm = uniform(id / p.n_tiles_n);
-        const int t = tm / SUB, sub = tm % SUB;
-        rows = uniform(p.tile_rows[t]) - sub * C::BM;
-        if (rows <= 0) return;
-        rows = min(rows, C::BM);
-        row0 = uniform(p.tile_row0[t]) + sub * C::BM;
-        e = uniform(p.tile_expert[t]);
-    }
-    const int tn = uniform(id % p.n_tiles_n);
-    const int n0 = tn * C::BN;
-    const int ncols = min(C::BN, p.d_out - n0);
-
-    const uint32_t ldx = (uint32_t)p.d_in * 2u, ldu = (uint32_t)p.r * 2u;
-    const bool lora = (e >= 0) && p.r > 0;
-    const int nkb0 = kb_hi - kb_lo;
-    const int nkb1 = lora ? (p.r + C::BK - 1) / C::BK : 0;
-    // adapter operands are harmless aliases of x / W when the tile has no adapter
-    const char *uh = lora ? p.u_hi + (int64_t)row0 * ldu : p.x;
-    const char *ul = lora ? p.u_lo + (int64_t)row0 * ldu : p.x;
-    const char *be = lora ? p.B_stack + ((int64_t)e * p.d_out + n0) * ldu : p.W;
-
-    typename C::Acc acc;
-    C::zero(acc);
-    if constexpr (C::IS_DMA) {
-        const char *xa = p.x + (int64_t)row0 * ldx;
-        const char *wb = p.W + (int64_t)n0 * ldx;
-        const auto la = C::template make_lanes<C::A_I>(rows);
-        const auto lb = C::template make_lanes<C::B_I>(ncols);
-        // Block sequence: base blocks first, then the adapter blocks (the high
-        // part of u, then the remainder); only uniform scalars differ between
-        // them.  Written out here rather than through a callable: the operand
-        // choice then stays a select of register values.
-        const int total = nkb0 + 2 * nkb1;
-#define MOIN_ISSUE_BLOCK(blk, stage)                                                      \
-    do {                                                                                  \
-        const int b_ = (blk);                                                             \
-        const bool base_ = b_ < nkb0;                                                     \
-        const int j_ = b_ - nkb0;                                                         \
-        const bool hi_ = j_ < nkb1;                                                       \
-        const char *pa_ = base_ ? xa : (hi_ ? uh : ul);                                   \
-        const char *pb_ = base_ ? wb : be;                                                \
-        const uint32_t ld_ = base_ ? ldx : ldu;                                           \
-        const int kb_ = base_ ? b_ + kb_lo : (hi_ ? j_ : j_ - nkb1);                      \
-        C::issue((stage), pa_, ld_, la, pb_, ld_, lb, (uint32_t)kb_ * (C::BK * 2));       \
-    } while (0)
-#pragma unroll
-        for (int s = 0; s < C::NS - 1; ++s)
-            if (s < total) MOIN_ISSUE_BLOCK(s, smem + s * C::STAGE_BYTES);
-        int st = 0;
-        for (int it = 0; it < total; ++it) {
-            if (it + C::NS - 2 < total) wait_vm_then_barrier<(C::NS - 2) * C::LPB>();
-            else wait_vm_then_barrier<0>();
-            const int nb = it + C::NS - 1;
-            const int ns = (st == 0) ? C::NS - 1 : st - 1;
-            if (nb < total) MOIN_ISSUE_BLOCK(nb, smem + ns * C::STAGE_BYTES);
-            C::compute_stage(smem + st * C::STAGE_BYTES, acc);
-            st = (st + 1 == C::NS) ? 0 : st + 1;
-        }
-        __syncthreads();
-#undef MOIN_ISSUE_BLOCK
-    } else {
-        const auto vx = C::template make_view<C::A_CH>(p.x + (int64_t)row0 * ldx, ldx, rows);
-        const auto vw = C::template make_view<C::B_CH>(p.W + (int64_t)n0 * ldx, ldx, ncols);
-        const auto vuh = C::template make_view<C::A_CH>(uh, ldu, rows);
-        const auto vul = C::template make_view<C::A_CH>(ul, ldu, rows);
-        const auto vb = C::template make_view<C::B_CH>(be, ldu, ncols);
-        auto issue = [=](int it, typename C::Stage &g) __attribute__((always_inline)) {
-            if (it < nkb0) {
-                C::load_stage(g, vx, vw, (uint32_t)(it + kb_lo) * (C::BK * 2), ldx);
-            } else if (it < nkb0 + nkb1) {
-                C::load_stage(g, vuh, vb, (uint32_t)(it - nkb0) * (C::BK * 2), ldu);
-            } else {
-                C::load_stage(g, vul, vb, (uint32_t)(it - nkb0 - nkb1) * (C::BK * 2), ldu);
-            }
-        };
-        pipelined_blocks<C>(smem, nkb0 + 2 * nkb1, issue, acc);
-    }
-
-    const int64_t ldy = (int64_t)p.d_out * (p.y_f32 ? 4 : 2);
-    char *yb = p.y + ((int64_t)split * p.T + row0) * ldy;
-    C::epilogue(smem, acc, [&](int row, int col, float(&v)[8]) {
-        if (row >= rows || col >= ncols) return;
-        const int gc = n0 + col;
-        if (p.y_f32) {
-            float *dst = reinterpret_cast<float *>(yb + (int64_t)row * ldy) + gc;
-            *reinterpret_cast<f32x4_t *>(dst) = f32x4_t{v[0], v[1], v[2], v[3]};
-            *reinterpret_cast<f32x4_t *>(dst + 4) = f32x4_t{v[4], v[5], v[6], v[7]};
-        } else {
-            uint4 o;
-            o.x = pack_bf16x2(v[0], v[1]);
-            o.y = pack_bf16x2(v[2], v[3]);
-            o.z = pack_bf16x2(v[4], v[5]);
-            o.w = pack_bf16x2(v[6], v[7]);
-            *reinterpret_cast<uint4 *>(yb + (int64_t)row * ldy + (int64_t)gc * 2) = o;
-        }
-    });
-}
 
 struct ShrinkKParams {
     const char *x, *A_stack;
@@ -239,8 +100,6 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
 using CfgMain = GemmCore<256, 256, 64, 4, 2>;        // 8 waves, wave patch 64 x 128
 using CfgShrink = GemmCore<64, 64, 64, 2, 2>;        // 4 waves, wave patch 32 x 32
 using CfgShrinkDma = DmaCore<64, 64, 64, 2, 2, 4>;
-using CfgThin = GemmCore<128, 64, 64, 2, 2>;         // decode base GEMM: 4 waves, 64 x 32
-using CfgThinDma = DmaCore<128, 64, 64, 2, 2, 3>;    // 72 KB of LDS: two workgroups per compute unit
 
 template <class K>
 static hipError_t allow_lds(K kern, int bytes)
@@ -259,7 +118,7 @@ hipError_t prepare_linear_kernels()
     if ((e = prepare_stream_kernel()) != hipSuccess) return e;
     if ((e = allow_lds(&linear_kernel<CfgMain>, CfgMain::SMEM_BYTES)) != hipSuccess) return e;
     if ((e = allow_lds(&linear_kernel<CfgThin>, CfgThin::SMEM_BYTES)) != hipSuccess) return e;
-    if ((e = allow_lds(&linear_kernel<CfgThinDma>, CfgThinDma::SMEM_BYTES)) != hipSuccess) return e;
+    if ((e = allow_lds(&linear_kernel<CfgDecodeBase>, CfgDecodeBase::SMEM_BYTES)) != hipSuccess) return e;
     if ((e = allow_lds(&shrink_kernel<CfgShrink>, CfgShrink::SMEM_BYTES)) != hipSuccess) return e;
     return allow_lds(&shrink_kernel<CfgShrinkDma>, CfgShrinkDma::SMEM_BYTES);
 }
@@ -342,30 +201,39 @@ constexpr int DECODE_BASE_TARGET_WGS = 512;
 constexpr int DECODE_BASE_MAX_SPLITS = 4;   // the expand kernel sums up to four parts
 constexpr int DECODE_BASE_MIN_BLOCKS = 4;   // BK blocks per part at least
 
-static void decode_base_shape(int64_t T, int d_in, int d_out, int *k_splits, int *kb_per_split)
+template <class C>
+static void shape_for(int64_t T, int d_in, int d_out, bool may_split, DecodeBaseShape *sh)
 {
-    const int64_t tiles = ((T + CfgThin::BM - 1) / CfgThin::BM) * ((d_out + CfgThin::BN - 1) / CfgThin::BN);
-    const int nkb = (d_in + CfgThin::BK - 1) / CfgThin::BK;
-    int want = (int)((DECODE_BASE_TARGET_WGS + tiles - 1) / (tiles > 0 ? tiles : 1));
+    sh->m_tiles = (T + C::BM - 1) / C::BM;
+    sh->n_tiles_n = (d_out + C::BN - 1) / C::BN;
+    const int64_t tiles = sh->m_tiles * sh->n_tiles_n;
+    const int nkb = (d_in + C::BK - 1) / C::BK;
+    int want = may_split ? (int)((DECODE_BASE_TARGET_WGS + tiles - 1) / (tiles > 0 ? tiles : 1)) : 1;
     if (want > DECODE_BASE_MAX_SPLITS) want = DECODE_BASE_MAX_SPLITS;
     if (want > nkb / DECODE_BASE_MIN_BLOCKS) want = nkb / DECODE_BASE_MIN_BLOCKS;
     if (want < 1) want = 1;
     const int per = (nkb + want - 1) / want;
-    *kb_per_split = per;
-    *k_splits = (nkb + per - 1) / per;   // no empty part
+    sh->kb_per_split = per;
+    sh->k_splits = (nkb + per - 1) / per;   // no empty part
+    sh->grid = round_up8((int)(tiles * sh->k_splits));
 }
 
-int decode_base_splits(int64_t T, int d_in, int d_out)
+static DecodeBaseShape base_shape(int64_t T, int d_in, int d_out, bool may_split)
 {
-    int ks, per;
-    decode_base_shape(T, d_in, d_out, &ks, &per);
-    return ks;
+    DecodeBaseShape sh;
+    sh.dma = (d_in % 64 == 0);
+    if (sh.dma) shape_for<CfgDecodeBase>(T, d_in, d_out, may_split, &sh);
+    else shape_for<CfgThin>(T, d_in, d_out, may_split, &sh);
+    return sh;
 }
 
-static hipError_t launch_plain(const PlanView &pv, const LinearArgs &a, void *out, int out_f32,
-                               int k_splits, int kb_per_split, hipStream_t stream)
+DecodeBaseShape decode_base_shape(int64_t T, int d_in, int d_out) { return base_shape(T, d_in, d_out, true); }
+
+int decode_base_splits(int64_t T, int d_in, int d_out) { return decode_base_shape(T, d_in, d_out).k_splits; }
+
+LinearKParams decode_base_params(const PlanView &pv, const LinearArgs &a, void *out, int out_f32,
+                                 const DecodeBaseShape &sh)
 {
-    if (pv.T <= 0) return hipSuccess;
     LinearKParams p;
     p.x = (const char *)a.x; p.W = (const char *)a.W; p.B_stack = nullptr;
     p.u_hi = nullptr; p.u_lo = nullptr;
@@ -373,26 +241,37 @@ static hipError_t launch_plain(const PlanView &pv, const LinearArgs &a, void *ou
     p.tile_row0 = nullptr; p.tile_rows = nullptr; p.tile_expert = nullptr; p.n_tiles = nullptr;
     p.T = pv.T;
     p.d_in = a.d_in; p.d_out = a.d_out; p.r = 0;
-    p.n_tiles_n = 0;
+    p.n_tiles_n = sh.n_tiles_n;
     p.y_f32 = out_f32;
     p.plain_tiles = 1;
-    p.k_splits = k_splits; p.kb_per_split = kb_per_split;
-    const int64_t ntm = (pv.T + CfgThin::BM - 1) / CfgThin::BM;
-    if (a.d_in % 64 == 0) return launch_linear_as<CfgThinDma>(p, ntm * k_splits, stream);
-    return launch_linear_as<CfgThin>(p, ntm * k_splits, stream);
+    p.k_splits = sh.k_splits; p.kb_per_split = sh.kb_per_split;
+    return p;
+}
+
+static hipError_t launch_plain(const PlanView &pv, const LinearArgs &a, void *out, int out_f32,
+                               const DecodeBaseShape &sh, hipStream_t stream)
+{
+    if (pv.T <= 0) return hipSuccess;
+    const LinearKParams p = decode_base_params(pv, a, out, out_f32, sh);
+    if (sh.dma)
+        hipLaunchKernelGGL(linear_kernel<CfgDecodeBase>, dim3((unsigned)sh.grid), dim3(CfgDecodeBase::NT),
+                           CfgDecodeBase::SMEM_BYTES, stream, p);
+    else
+        hipLaunchKernelGGL(linear_kernel<CfgThin>, dim3((unsigned)sh.grid), dim3(CfgThin::NT),
+                           CfgThin::SMEM_BYTES, stream, p);
+    return hipGetLastError();
 }
 
 hipError_t launch_decode_base(const PlanView &pv, const DecodeArgs &d, hipStream_t stream)
 {
-    int ks, per;
-    decode_base_shape(pv.T, d.lin.d_in, d.lin.d_out, &ks, &per);
-    if (ks != d.k_splits) return hipErrorInvalidValue;
-    return launch_plain(pv, d.lin, d.ybase, 1, ks, per, stream);
+    const DecodeBaseShape sh = decode_base_shape(pv.T, d.lin.d_in, d.lin.d_out);
+    if (sh.k_splits != d.k_splits) return hipErrorInvalidValue;
+    return launch_plain(pv, d.lin, d.ybase, 1, sh, stream);
 }
 
 hipError_t launch_decode_base_only(const PlanView &pv, const LinearArgs &a, hipStream_t stream)
 {
-    return launch_plain(pv, a, a.y, a.y_f32, 1, (a.d_in + CfgThin::BK - 1) / CfgThin::BK, stream);
+    return launch_plain(pv, a, a.y, a.y_f32, base_shape(pv.T, a.d_in, a.d_out, false), stream);
 }
 
 }  // namespace moin
