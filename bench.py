@@ -35,9 +35,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 # HBM-side bytes per launch of the dominant (linear) kernel on configs[1], from the
 # rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised in
-# profiles/prefill_q_proj_hbm_traffic.md: (2.0 * 209204 KiB + 1.0 * 131072 KiB) * 1024,
+# profiles/prefill_and_decode_hbm_traffic.md: (2.0 * 212817 KiB + 1.0 * 136704 KiB) * 1024,
 # the factors being what the same counters read for a plain 1 GiB copy.
-LINEAR_KERNEL_TRAFFIC_BYTES = int((2.0 * 209204.2 + 1.0 * 131072.0) * 1024)
+LINEAR_KERNEL_TRAFFIC_BYTES = int((2.0 * 212817.4 + 1.0 * 136704.0) * 1024)
 
 
 def timed_region(fn, steps, warmup):
@@ -133,7 +133,7 @@ def bench_prefill(ctx, steps, warmup, with_cpu):
                    "wall_ms_per_step": wall_ms},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                     "traffic": LINEAR_KERNEL_TRAFFIC_BYTES, "kernel": "linear_kernel (base GEMM + fused expand)",
+                     "traffic": LINEAR_KERNEL_TRAFFIC_BYTES, "kernel": "linear_stream_kernel (base GEMM + fused expand)",
                      "avg_launch_ms": lin["avg_ms"]},
         "kernels": kt,
     }
@@ -177,6 +177,9 @@ def bench_decode(ctx, steps, warmup, n_draws=8):
         out[w.name] = {"ms_per_call": ms, "algorithmic_bytes": avg_bytes,
                        "GBps": avg_bytes / (ms * 1e-3) / 1e9,
                        "frac_of_hbm_peak": avg_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                       "roofline": {"bound": "hbm", "achieved": avg_bytes / (ms * 1e-3) / 1e9,
+                                    "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                    "frac": avg_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
                        "kernels": kt}
         for p in plans:
             p.close()
@@ -239,7 +242,7 @@ def main():
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="first run a plain device copy of this many MiB (3 times): the known-size "
                          "kernel that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
-    ap.add_argument("--also", default="decode,router",
+    ap.add_argument("--also", default="decode,router,layer",
                     help="comma list of extra workloads to report: decode,router,layer (or 'none')")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -448,7 +448,7 @@ int moin_route(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N,
         if (timed(ctx, MOIN_K_ROUTE, st, [&] { return launch_route(a, st); }) != hipSuccess)
             return MOIN_EHIP;
     }
-    if (counts) {
+    if (counts && !(routed && route_tallies_counts(a))) {
         // the norms kernel, when it ran, has already zeroed counts
         if (timed(ctx, MOIN_K_ROUTE_AUX, st, [&] {
                 return launch_histogram(a.cid, N, K, counts, routed ? 0 : 1, ctx->err_word, st);

@@ -92,6 +92,8 @@ struct RouteArgs {
 constexpr int ROUTE_SMALL_MAX_N = 4096;  // up to here the K range is split across workgroups
 hipError_t launch_centroid_norms(const RouteArgs &a, hipStream_t stream);
 hipError_t launch_route(const RouteArgs &a, hipStream_t stream);
+// true when launch_route itself fills a.counts (no histogram launch needed)
+bool route_tallies_counts(const RouteArgs &a);
 hipError_t launch_histogram(const int *ids, int64_t N, int K, int *counts, int zero_first,
                             int *err_word, hipStream_t stream);
 

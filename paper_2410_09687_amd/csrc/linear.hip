@@ -100,6 +100,8 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
 using CfgMain = GemmCore<256, 256, 64, 4, 2>;        // 8 waves, wave patch 64 x 128
 using CfgShrink = GemmCore<64, 64, 64, 2, 2>;        // 4 waves, wave patch 32 x 32
 using CfgShrinkDma = DmaCore<64, 64, 64, 2, 2, 4>;
+// ranks from 65 to 128: the whole rank in one tile, so x streams from HBM once
+using CfgShrinkR128 = DmaCore<128, 128, 32, 2, 4, 4>;
 
 template <class K>
 static hipError_t allow_lds(K kern, int bytes)
@@ -120,6 +122,7 @@ hipError_t prepare_linear_kernels()
     if ((e = allow_lds(&linear_kernel<CfgThin>, CfgThin::SMEM_BYTES)) != hipSuccess) return e;
     if ((e = allow_lds(&linear_kernel<CfgDecodeBase>, CfgDecodeBase::SMEM_BYTES)) != hipSuccess) return e;
     if ((e = allow_lds(&shrink_kernel<CfgShrink>, CfgShrink::SMEM_BYTES)) != hipSuccess) return e;
+    if ((e = allow_lds(&shrink_kernel<CfgShrinkR128>, CfgShrinkR128::SMEM_BYTES)) != hipSuccess) return e;
     return allow_lds(&shrink_kernel<CfgShrinkDma>, CfgShrinkDma::SMEM_BYTES);
 }
 
@@ -159,6 +162,7 @@ static hipError_t launch_shrink_as(const PlanView &pv, const LinearArgs &a, hipS
 hipError_t launch_prefill_shrink(const PlanView &pv, const LinearArgs &a, hipStream_t stream)
 {
     if (a.r <= 0 || pv.max_tiles <= 0) return hipSuccess;
+    if (a.d_in % 64 == 0 && a.r > 64 && a.r <= 128) return launch_shrink_as<CfgShrinkR128>(pv, a, stream);
     if (a.d_in % 64 == 0) return launch_shrink_as<CfgShrinkDma>(pv, a, stream);
     return launch_shrink_as<CfgShrink>(pv, a, stream);
 }

@@ -30,6 +30,7 @@ struct RouteKParams {
     int *expert_ids;
     unsigned long long *best;
     int *arrivals;
+    int *counts;          // small batches only: tallied by the finishing workgroup (zeroed beforehand)
     int64_t N;
     int K, D;
 };
@@ -463,6 +464,7 @@ __global__ __launch_bounds__(C::NT) void route_small_kernel(RouteKParams p, int 
         const int bi = (idx < (unsigned)p.K) ? (int)idx : 0;   // nothing won: centroid 0
         if (p.cid) p.cid[q] = bi;
         if (p.expert_ids) p.expert_ids[q] = p.slot ? p.slot[bi] : bi;
+        if (p.counts) atomicAdd(&p.counts[bi], 1);
     }
 }
 
@@ -599,6 +601,8 @@ static bool use_small_route(const RouteArgs &a)
     return a.is_bf16 && a.D % 64 == 0 && a.N <= ROUTE_SMALL_MAX_N;
 }
 
+bool route_tallies_counts(const RouteArgs &a) { return a.N > 0 && a.counts != nullptr && use_small_route(a); }
+
 hipError_t launch_centroid_norms(const RouteArgs &a, hipStream_t stream)
 {
     const int Kpad = (a.K + 255) / 256 * 256;
@@ -617,6 +621,7 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t stream)
         p.emb = (const char *)a.emb; p.cent = (const char *)a.cent;
         p.cnorm = a.cnorm; p.slot = a.slot; p.cid = a.cid; p.expert_ids = a.expert_ids;
         p.best = a.best; p.arrivals = a.arrivals;
+        p.counts = use_small_route(a) ? a.counts : nullptr;
         p.N = a.N; p.K = a.K; p.D = a.D;
         if (use_small_route(a)) {
             using C = CfgRouteSmall;
