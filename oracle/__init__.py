@@ -7,6 +7,7 @@ from .oracle import (  # noqa: F401
     build,
     dist2,
     histogram,
+    kmeans_update,
     lora_linear,
     max_threads,
     route,

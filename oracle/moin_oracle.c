@@ -21,6 +21,16 @@
  *                 tasks" (a topic without an adapter falls back to the base
  *                 model; the 4697-variant searches retained topics only).
  *   histogram  -- documents per topic, Figure 3.
+ *   kmeans_update -- Section 3.1 / Section 4 "Implementation details": the
+ *                 topics are the cells of a plain K-means clustering of the
+ *                 document embeddings and the topic embeddings are its cluster
+ *                 centres.  This is the textbook centre update of one Lloyd
+ *                 iteration: each centre becomes the mean of the embeddings
+ *                 assigned to it; a centre nobody was assigned to keeps its
+ *                 old value (the paper drops tiny clusters afterwards, it does
+ *                 not say what its K-means does with empty ones).  Also the
+ *                 clustering objective (sum of squared distances to the
+ *                 assigned old centres).
  *   lora_linear-- Section 3.2: y = W x + W_b (W_a x), with one adapter per
  *                 sequence (Section 1: each query goes to a single expert),
  *                 a caller-given scale on the adapter term, and the base-only
@@ -238,6 +248,50 @@ int moin_oracle_lora_linear(const uint16_t *x, const int32_t *seq_offsets,
         }
     }
     return bad ? ORACLE_EINVAL : ORACLE_OK;
+}
+
+/* ---- K-means centre update -------------------------------------------- */
+
+static double emb_at(const void *a, size_t idx, int dt)
+{
+    return dt == 0 ? (double)((const float *)a)[idx] : bf16_to_f64(((const uint16_t *)a)[idx]);
+}
+
+/* new_c[k] = mean of emb[i] over {i : ids[i] == k} (fp64 sums in index order),
+ * old_c[k] when the set is empty; counts[k] = set size; *inertia = sum_i
+ * ||emb[i] - old_c[ids[i]]||^2 summed in index order.  ids outside [0, K) are
+ * an error.  Single-threaded on purpose: one fixed summation order. */
+int moin_oracle_kmeans_update(const void *emb, const int32_t *ids, int64_t N,
+                              const void *old_c, int32_t K, int32_t D, int dt,
+                              double *new_c, int64_t *counts, double *inertia)
+{
+    if (N < 0 || K <= 0 || D <= 0 || !old_c || !new_c || !counts) return ORACLE_EINVAL;
+    if (N > 0 && (!emb || !ids)) return ORACLE_EINVAL;
+    for (int32_t k = 0; k < K; ++k) {
+        counts[k] = 0;
+        for (int32_t j = 0; j < D; ++j) new_c[(size_t)k * D + j] = 0.0;
+    }
+    double total = 0.0;
+    for (int64_t i = 0; i < N; ++i) {
+        const int32_t k = ids[i];
+        if (k < 0 || k >= K) return ORACLE_EINVAL;
+        counts[k] += 1;
+        double d2 = 0.0;
+        for (int32_t j = 0; j < D; ++j) {
+            const double q = emb_at(emb, (size_t)i * D + j, dt);
+            const double diff = q - emb_at(old_c, (size_t)k * D + j, dt);
+            new_c[(size_t)k * D + j] += q;
+            d2 += diff * diff;
+        }
+        total += d2;
+    }
+    for (int32_t k = 0; k < K; ++k)
+        for (int32_t j = 0; j < D; ++j) {
+            if (counts[k] > 0) new_c[(size_t)k * D + j] /= (double)counts[k];
+            else new_c[(size_t)k * D + j] = emb_at(old_c, (size_t)k * D + j, dt);
+        }
+    if (inertia) *inertia = total;
+    return ORACLE_OK;
 }
 
 int moin_oracle_max_threads(void)

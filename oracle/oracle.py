@@ -47,6 +47,10 @@ def _load():
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int64,
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
             c.c_double, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_int32]
+        lib.moin_oracle_kmeans_update.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p,
+                                                  c.c_int32, c.c_int32, c.c_int, c.c_void_p,
+                                                  c.c_void_p, c.c_void_p]
+        lib.moin_oracle_kmeans_update.restype = c.c_int
         for f in ("moin_oracle_dist2", "moin_oracle_route", "moin_oracle_slot_map",
                   "moin_oracle_histogram", "moin_oracle_lora_linear",
                   "moin_oracle_max_threads"):
@@ -136,6 +140,27 @@ def histogram(ids, K):
     counts = np.zeros(K, dtype=np.int64)
     _check(_load().moin_oracle_histogram(_ptr(ids), ids.size, K, _ptr(counts)), "histogram")
     return counts
+
+
+def kmeans_update(emb, ids, old_centroids):
+    """Centre update of one Lloyd iteration (fp64): returns ``(new_centroids
+    [K,D] float64, counts [K] int64, inertia float)``.  A centre with no
+    members keeps its old value; inertia is measured against the old centres."""
+    emb, dt = _emb_array(emb, "emb")
+    old_centroids, dt2 = _emb_array(old_centroids, "old_centroids")
+    if dt != dt2 or emb.ndim != 2 or old_centroids.ndim != 2 or emb.shape[1] != old_centroids.shape[1]:
+        raise ValueError("emb [N,D] and old_centroids [K,D] must share dtype and D")
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    N, D = emb.shape
+    K = old_centroids.shape[0]
+    if ids.shape != (N,):
+        raise ValueError("ids must have shape [N]")
+    new_c = np.zeros((K, D), dtype=np.float64)
+    counts = np.zeros(K, dtype=np.int64)
+    inertia = np.zeros(1, dtype=np.float64)
+    _check(_load().moin_oracle_kmeans_update(_ptr(emb), _ptr(ids), N, _ptr(old_centroids), K, D, dt,
+                                             _ptr(new_c), _ptr(counts), _ptr(inertia)), "kmeans_update")
+    return new_c, counts, float(inertia[0])
 
 
 def lora_linear(x, seq_offsets, expert_ids, W, A_stack, B_stack, scale, rows=None,
