@@ -25,18 +25,16 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint32_t f32_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
 __device__ __forceinline__ float bits_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
 
-// fp32 -> bf16, round to nearest even; NaN stays a (quiet) NaN.
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
-{
-    uint32_t u = f32_bits(f);
-    uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-    return (f != f) ? 0x7FC0u : rounded;
-}
-__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return bits_f32(h << 16); }
+// fp32 -> bf16, round to nearest even; NaN stays a (quiet) NaN.  The plain
+// conversion compiles to gfx950's v_cvt_pk_bf16_f32 (two values per instruction).
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
 }
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) { return pack_bf16x2(f, 0.f) & 0xFFFFu; }
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return bits_f32(h << 16); }
 
 // Values read from global memory with a workgroup-uniform address are uniform,
 // but the compiler cannot know; telling it keeps control flow and addressing

@@ -23,6 +23,12 @@ def _full_check(inp, what):
         print(f"[gpu] {what} y={dt}", flush=True)
         y = gc.run_linear(inp, dt)
         out[dt] = gc.compare_linear(y, ref, what=f"{what}/{dt}")
+        out[("y", dt)] = y
+    # both outputs come from the same fp32 accumulators (runs repeat bit for bit),
+    # so the bf16 one must be the round-to-nearest-even image of the fp32 one
+    y16, y32 = out.pop(("y", torch.bfloat16)), out.pop(("y", torch.float32))
+    assert torch.equal(y16.view(torch.int16), y32.to(torch.bfloat16).view(torch.int16)), \
+        f"{what}: bf16 output is not RNE(fp32 output)"
     return out
 
 
