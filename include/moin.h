@@ -60,7 +60,10 @@ typedef enum {
                                  the base GEMM when both share one launch       */
     MOIN_K_DECODE_EXPAND = 6, /* decode: gather-matvec B_e u + base, writes y   */
     MOIN_K_DECODE_BASE = 7,   /* decode: thin base GEMM launched on its own     */
-    MOIN_K_COUNT = 8
+    MOIN_K_KMEANS_SORT = 8,   /* K-means update: stable grouping of points by centre */
+    MOIN_K_KMEANS_SUM = 9,    /* K-means update: the pass over the embeddings    */
+    MOIN_K_KMEANS_FINAL = 10, /* K-means update: means, objective; cluster pruning */
+    MOIN_K_COUNT = 11
 } moin_kernel_id;
 
 /* ---- context ----------------------------------------------------------- */
@@ -154,6 +157,51 @@ int moin_lora_linear_planned(moin_ctx *ctx, const moin_plan *plan, const void *x
                              const void *B_stack, int32_t d_in, int32_t d_out,
                              int32_t r, float scale, void *y, moin_dtype y_dt,
                              void *stream);
+
+/* ---- K-means (topic modelling) --------------------------------------------
+ * Section 3.1: the topics are the cells of a plain K-means clustering of the
+ * document embeddings, and its cluster centres are the topic embeddings that
+ * moin_route searches.  The assignment step of an iteration IS moin_route;
+ * moin_kmeans_update is the centre update: every centre becomes the mean of
+ * the embeddings assigned to it.  The paper does not say what happens to a
+ * centre nobody was assigned to: here it keeps its old value.
+ *
+ *   emb           [N, D] row-major, dt (fp32 or bf16)
+ *   ids           [N] int32, centre of each embedding, in [0, K); others are
+ *                 skipped and raise the sticky data fault
+ *   centroids     [K, D] old centres, same dt
+ *   new_centroids [K, D] out, out_dt (rounded to nearest even when bf16), or
+ *                 NULL.  May be the same buffer as centroids when out_dt == dt.
+ *   counts        [K] int32 out or NULL: points per centre (overwritten)
+ *   inertia       [1] double out (DEVICE pointer) or NULL: the K-means objective
+ *                 sum_i ||emb_i - centroids[ids_i]||^2 against the OLD centres
+ * Column sums are accumulated in fp32 over at most 512 points at a time and in
+ * fp64 across such pieces; the objective is summed in fp64.  Points are added
+ * in index order, so results repeat bit for bit.  K <= 32768; D a multiple of
+ * 8 (bf16) or 4 (fp32); N < 2^31 - 4096.
+ */
+int moin_kmeans_update(moin_ctx *ctx, const void *emb, const int32_t *ids, int64_t N,
+                       const void *centroids, int32_t K, int32_t D, moin_dtype dt,
+                       void *new_centroids, moin_dtype out_dt, int32_t *counts,
+                       double *inertia, void *stream);
+
+/* Section 4 "Implementation details": clusters that stay extremely small are
+ * dropped and get no adapter (4697 of 5000 were kept).  The paper gives no
+ * threshold, so it is an argument: slot_of_centroid[k] = rank of k among the
+ * centres with counts[k] >= min_count (ascending k), -1 for the others -- the
+ * table moin_route takes.  n_retained [1] int32 out (device) or NULL. */
+int moin_retain_clusters(moin_ctx *ctx, const int32_t *counts, int32_t K, int32_t min_count,
+                         int32_t *slot_of_centroid, int32_t *n_retained, void *stream);
+
+/* `iters` rounds of (moin_route, moin_kmeans_update) with the centres updated
+ * in place, then one more assignment, so that ids / counts belong to the centres
+ * returned.  inertia: [iters + 1] doubles (device) or NULL; entry t is the
+ * objective of assignment t against the centres it was made with, so the
+ * sequence never increases (up to rounding of the centres to dt).  ids [N] is
+ * required when N > 0.  No host synchronisation: the iteration count is fixed. */
+int moin_kmeans_fit(moin_ctx *ctx, const void *emb, int64_t N, void *centroids, int32_t K,
+                    int32_t D, moin_dtype dt, int32_t iters, int32_t *ids, int32_t *counts,
+                    double *inertia, void *stream);
 
 /* ---- per-kernel timing ----------------------------------------------------
  * When enabled, every kernel launch is bracketed by HIP events on the launch

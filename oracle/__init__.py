@@ -10,6 +10,7 @@ from .oracle import (  # noqa: F401
     kmeans_update,
     lora_linear,
     max_threads,
+    retain_clusters,
     route,
     slot_map,
 )

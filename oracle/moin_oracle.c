@@ -31,6 +31,8 @@
  *                 not say what its K-means does with empty ones).  Also the
  *                 clustering objective (sum of squared distances to the
  *                 assigned old centres).
+ *   retain_clusters -- Section 4 "Implementation details": clusters below a
+ *                 size threshold are dropped; the others are numbered in order.
  *   lora_linear-- Section 3.2: y = W x + W_b (W_a x), with one adapter per
  *                 sequence (Section 1: each query goes to a single expert),
  *                 a caller-given scale on the adapter term, and the base-only
@@ -292,6 +294,23 @@ int moin_oracle_kmeans_update(const void *emb, const int32_t *ids, int64_t N,
         }
     if (inertia) *inertia = total;
     return ORACLE_OK;
+}
+
+/* Section 4 "Implementation details": clusters that stay extremely small are
+ * dropped and the remaining ones get an adapter each.  The paper names no
+ * threshold, so it is an input: a cluster is kept iff it has at least min_count
+ * members; kept clusters are numbered 0, 1, ... in ascending cluster index (the
+ * adapter slots), dropped ones get -1.  Returns the number kept. */
+int moin_oracle_retain_clusters(const int64_t *counts, int32_t K, int64_t min_count,
+                                int32_t *slot_of_centroid)
+{
+    if (K <= 0 || !counts || !slot_of_centroid) return ORACLE_EINVAL;
+    int32_t kept = 0;
+    for (int32_t k = 0; k < K; ++k) {
+        if (counts[k] >= min_count) slot_of_centroid[k] = kept++;
+        else slot_of_centroid[k] = -1;
+    }
+    return kept;
 }
 
 int moin_oracle_max_threads(void)

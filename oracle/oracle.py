@@ -51,6 +51,8 @@ def _load():
                                                   c.c_int32, c.c_int32, c.c_int, c.c_void_p,
                                                   c.c_void_p, c.c_void_p]
         lib.moin_oracle_kmeans_update.restype = c.c_int
+        lib.moin_oracle_retain_clusters.argtypes = [c.c_void_p, c.c_int32, c.c_int64, c.c_void_p]
+        lib.moin_oracle_retain_clusters.restype = c.c_int
         for f in ("moin_oracle_dist2", "moin_oracle_route", "moin_oracle_slot_map",
                   "moin_oracle_histogram", "moin_oracle_lora_linear",
                   "moin_oracle_max_threads"):
@@ -161,6 +163,17 @@ def kmeans_update(emb, ids, old_centroids):
     _check(_load().moin_oracle_kmeans_update(_ptr(emb), _ptr(ids), N, _ptr(old_centroids), K, D, dt,
                                              _ptr(new_c), _ptr(counts), _ptr(inertia)), "kmeans_update")
     return new_c, counts, float(inertia[0])
+
+
+def retain_clusters(counts, min_count):
+    """Adapter slot of each cluster (kept clusters numbered in ascending order,
+    -1 for clusters with fewer than ``min_count`` members) and how many are kept."""
+    counts = np.ascontiguousarray(counts, dtype=np.int64)
+    slot = np.zeros(counts.size, dtype=np.int32)
+    kept = _load().moin_oracle_retain_clusters(_ptr(counts), counts.size, int(min_count), _ptr(slot))
+    if kept < 0:
+        raise ValueError("oracle retain_clusters: invalid argument")
+    return slot, int(kept)
 
 
 def lora_linear(x, seq_offsets, expert_ids, W, A_stack, B_stack, scale, rows=None,

@@ -15,11 +15,13 @@ namespace moin {
 hipError_t prepare_linear_kernels();
 hipError_t prepare_route_kernels();
 hipError_t prepare_decode_kernels();
+hipError_t prepare_kmeans_kernels();
 hipError_t prepare_kernels()
 {
     hipError_t e = prepare_linear_kernels();
     if (e != hipSuccess) return e;
     if ((e = prepare_decode_kernels()) != hipSuccess) return e;
+    if ((e = prepare_kmeans_kernels()) != hipSuccess) return e;
     return prepare_route_kernels();
 }
 }  // namespace moin
@@ -536,6 +538,105 @@ int moin_lora_linear(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
     if (rc != MOIN_OK) return rc;
     return linear_planned_impl(ctx, ctx->own_plan, x, W, A_stack, B_stack, d_in, d_out, r, scale, y,
                                y_dt, st);
+}
+
+int moin_kmeans_update(moin_ctx *ctx, const void *emb, const int32_t *ids, int64_t N,
+                       const void *centroids, int32_t K, int32_t D, moin_dtype dt,
+                       void *new_centroids, moin_dtype out_dt, int32_t *counts, double *inertia,
+                       void *stream)
+{
+    if (!ctx || N < 0 || K <= 0 || D <= 0 || !centroids) return MOIN_EINVAL;
+    if (dt != MOIN_BF16 && dt != MOIN_F32) return MOIN_EINVAL;
+    if (out_dt != MOIN_BF16 && out_dt != MOIN_F32) return MOIN_EINVAL;
+    if (N > 0 && (!emb || !ids)) return MOIN_EINVAL;
+    if (dt == MOIN_BF16 ? (D % 8 != 0) : (D % 4 != 0)) return MOIN_EINVAL;
+    if (K > KM_MAX_K || D > (1 << 20) || N > 0x7fffffffLL - 4096) return MOIN_EINVAL;
+    if (misaligned(centroids, 16) || (emb && misaligned(emb, 16)) ||
+        (new_centroids && misaligned(new_centroids, 16)))
+        return MOIN_EINVAL;
+    if (new_centroids == centroids && out_dt != dt) return MOIN_EINVAL;
+    if (!new_centroids && !counts && !inertia) return MOIN_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    KmeansArgs a;
+    a.emb = emb; a.ids = ids; a.N = N; a.cent = centroids; a.K = K; a.D = D;
+    a.is_bf16 = (dt == MOIN_BF16);
+    a.out = new_centroids; a.out_bf16 = (out_dt == MOIN_BF16);
+    a.inertia = inertia;
+    a.err_word = ctx->err_word;
+    kmeans_shape(N, K, D, a.is_bf16, &a.chunk, &a.n_chunks, &a.max_pieces, &a.ncb);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off = align_up(off + bytes, 256);
+        return at;
+    };
+    const size_t o_table = take((size_t)a.n_chunks * K * 4);
+    const size_t o_counts = take((size_t)K * 4);
+    const size_t o_seg = take((size_t)(K + 1) * 4);
+    const size_t o_pst = take((size_t)(K + 1) * 4);
+    const size_t o_pieces = take((size_t)(a.max_pieces + 1) * 16);
+    const size_t o_np = take(4);
+    const size_t o_perm = take((size_t)(N + 1) * 4);
+    const size_t o_part = take((size_t)(a.max_pieces + 1) * D * 4);
+    const size_t o_ipart = take((size_t)(a.max_pieces + 1) * a.ncb * 8);
+    const int rc = ensure_ws(ctx, off);
+    if (rc != MOIN_OK) return rc;
+    char *w = static_cast<char *>(ctx->ws);
+    a.table = reinterpret_cast<int *>(w + o_table);
+    a.counts = counts ? counts : reinterpret_cast<int *>(w + o_counts);
+    a.seg_start = reinterpret_cast<int *>(w + o_seg);
+    a.piece_start = reinterpret_cast<int *>(w + o_pst);
+    a.pieces = reinterpret_cast<int4 *>(w + o_pieces);
+    a.n_pieces = reinterpret_cast<int *>(w + o_np);
+    a.perm = reinterpret_cast<int *>(w + o_perm);
+    a.partial = reinterpret_cast<float *>(w + o_part);
+    a.inertia_part = reinterpret_cast<double *>(w + o_ipart);
+
+    if (timed(ctx, MOIN_K_KMEANS_SORT, st, [&] { return launch_kmeans_sort(a, st); }) != hipSuccess)
+        return MOIN_EHIP;
+    if (!new_centroids && !inertia) return MOIN_OK;   // counts only
+    if (timed(ctx, MOIN_K_KMEANS_SUM, st, [&] { return launch_kmeans_segsum(a, st); }) != hipSuccess)
+        return MOIN_EHIP;
+    if (timed(ctx, MOIN_K_KMEANS_FINAL, st, [&] { return launch_kmeans_finalize(a, st); }) != hipSuccess)
+        return MOIN_EHIP;
+    return MOIN_OK;
+}
+
+int moin_retain_clusters(moin_ctx *ctx, const int32_t *counts, int32_t K, int32_t min_count,
+                         int32_t *slot_of_centroid, int32_t *n_retained, void *stream)
+{
+    if (!ctx || K <= 0 || !counts || !slot_of_centroid) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (timed(ctx, MOIN_K_KMEANS_FINAL, st, [&] {
+            return launch_kmeans_retain(counts, K, min_count, slot_of_centroid, n_retained, st);
+        }) != hipSuccess)
+        return MOIN_EHIP;
+    return MOIN_OK;
+}
+
+int moin_kmeans_fit(moin_ctx *ctx, const void *emb, int64_t N, void *centroids, int32_t K, int32_t D,
+                    moin_dtype dt, int32_t iters, int32_t *ids, int32_t *counts, double *inertia,
+                    void *stream)
+{
+    if (!ctx || iters < 0 || N < 0 || !centroids) return MOIN_EINVAL;
+    if (N > 0 && (!emb || !ids)) return MOIN_EINVAL;
+    if (K <= 0 || K > KM_MAX_K) return MOIN_EINVAL;
+    for (int32_t it = 0; it <= iters; ++it) {
+        // assignment against the current centres
+        int rc = moin_route(ctx, emb, centroids, N, K, D, dt, nullptr, 0, nullptr, ids, nullptr, stream);
+        if (rc != MOIN_OK) return rc;
+        // objective of this assignment; all but the last round also move the centres (in place)
+        const bool last = it == iters;
+        rc = moin_kmeans_update(ctx, emb, ids, N, centroids, K, D, dt, last ? nullptr : centroids, dt,
+                                last ? counts : nullptr, inertia ? inertia + it : nullptr, stream);
+        if (rc != MOIN_OK) return rc;
+    }
+    return MOIN_OK;
 }
 
 int moin_timing_enable(moin_ctx *ctx, int on)

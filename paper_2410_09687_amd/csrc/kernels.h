@@ -97,6 +97,42 @@ bool route_tallies_counts(const RouteArgs &a);
 hipError_t launch_histogram(const int *ids, int64_t N, int K, int *counts, int zero_first,
                             int *err_word, hipStream_t stream);
 
+
+// K-means centre update (kmeans.hip)
+constexpr int KM_PIECE = 512;     // a cluster's points are summed in pieces of at most this many
+constexpr int KM_MAX_K = 32768;   // per-chunk cursor table lives in LDS
+struct KmeansArgs {
+    const void *emb;       // [N, D]
+    const int *ids;        // [N] centre of each point
+    int64_t N;
+    const void *cent;      // [K, D] old centres, same type as emb
+    int K, D;
+    int is_bf16;
+    void *out;             // [K, D] new centres or null (objective / counts only)
+    int out_bf16;
+    int *counts;           // [K] (user buffer or workspace)
+    double *inertia;       // [1] or null
+    // workspace
+    int *table;            // [n_chunks, K]
+    int *seg_start;        // [K + 1]
+    int *piece_start;      // [K + 1]
+    int4 *pieces;          // [max_pieces]
+    int *n_pieces;         // [1]
+    int *perm;             // [N]
+    float *partial;        // [max_pieces, D]
+    double *inertia_part;  // [max_pieces * ncb]
+    int chunk, n_chunks, max_pieces, ncb;
+    int *err_word;
+};
+// Launch shape for a problem size: points per chunk, number of chunks, upper
+// bound on the number of pieces, column blocks of 256 16-byte chunks per row.
+void kmeans_shape(int64_t N, int K, int D, int is_bf16, int *chunk, int *n_chunks, int *max_pieces, int *ncb);
+hipError_t launch_kmeans_sort(const KmeansArgs &a, hipStream_t stream);     // perm[] and the piece list
+hipError_t launch_kmeans_segsum(const KmeansArgs &a, hipStream_t stream);   // piece sums + objective shares
+hipError_t launch_kmeans_finalize(const KmeansArgs &a, hipStream_t stream); // means, objective
+hipError_t launch_kmeans_retain(const int *counts, int K, int min_count, int *slot, int *n_retained,
+                                hipStream_t stream);
+
 hipError_t prepare_kernels();  // one-time attribute set-up (large dynamic LDS)
 
 }  // namespace moin

@@ -19,14 +19,16 @@ LIB_PATH = os.path.join(_HERE, "libmoin.so")
 
 MOIN_F32, MOIN_BF16 = 0, 1
 MOIN_ROUTE_RETAINED_ONLY = 1
-K_PLAN, K_SHRINK, K_LINEAR, K_ROUTE, K_ROUTE_AUX, K_DECODE_SHRINK, K_DECODE_EXPAND, K_DECODE_BASE = range(8)
+(K_PLAN, K_SHRINK, K_LINEAR, K_ROUTE, K_ROUTE_AUX, K_DECODE_SHRINK, K_DECODE_EXPAND, K_DECODE_BASE,
+ K_KMEANS_SORT, K_KMEANS_SUM, K_KMEANS_FINAL) = range(11)
 KERNEL_NAMES = ["plan", "shrink", "linear", "route", "route_aux", "decode_shrink", "decode_expand",
-                "decode_base"]
+                "decode_base", "kmeans_sort", "kmeans_sum", "kmeans_final"]
 
 EXPORTS = [
     "moin_create", "moin_destroy", "moin_strerror", "moin_check", "moin_route", "moin_histogram",
     "moin_lora_linear", "moin_plan_create", "moin_plan_destroy", "moin_plan_build",
     "moin_lora_linear_planned", "moin_timing_enable", "moin_timing_reset", "moin_timing_read",
+    "moin_kmeans_update", "moin_retain_clusters", "moin_kmeans_fit",
 ]
 
 _lib = None
@@ -67,6 +69,9 @@ def load() -> ctypes.CDLL:
     lib.moin_plan_build.argtypes = [vp, vp, vp, vp, i32, i64, i32, vp]
     lib.moin_lora_linear_planned.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, c.c_float, vp,
                                              c.c_int, vp]
+    lib.moin_kmeans_update.argtypes = [vp, vp, vp, i64, vp, i32, i32, c.c_int, vp, c.c_int, vp, vp, vp]
+    lib.moin_retain_clusters.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+    lib.moin_kmeans_fit.argtypes = [vp, vp, i64, vp, i32, i32, c.c_int, i32, vp, vp, vp, vp]
     lib.moin_timing_enable.argtypes = [vp, c.c_int]
     lib.moin_timing_reset.argtypes = [vp]
     lib.moin_timing_read.argtypes = [vp, c.c_int, c.POINTER(c.c_double), c.POINTER(i64)]
@@ -261,3 +266,71 @@ def moin_lora_linear_planned(ctx: Context, plan: Plan, x: torch.Tensor, W: torch
         float(scale), _dev_ptr(y, "y") if T else None, ydt, _stream_ptr(stream)),
         "moin_lora_linear_planned")
     return y
+
+
+def _emb_dt(emb, centroids):
+    if emb.dim() != 2 or centroids.dim() != 2 or emb.shape[1] != centroids.shape[1]:
+        raise ValueError("emb [N,D] and centroids [K,D] expected")
+    if emb.dtype != centroids.dtype or emb.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("emb/centroids must both be float32 or both bfloat16")
+    return MOIN_BF16 if emb.dtype == torch.bfloat16 else MOIN_F32
+
+
+def moin_kmeans_update(ctx: Context, emb: torch.Tensor, ids: torch.Tensor, centroids: torch.Tensor,
+                       out_dtype=None, out: Optional[torch.Tensor] = None, want_centroids: bool = True,
+                       want_counts: bool = True, want_inertia: bool = True, stream=None):
+    """Returns ``(new_centroids or None, counts or None, inertia or None)``;
+    inertia is a 1-element float64 tensor on the device."""
+    dt = _emb_dt(emb, centroids)
+    N, D = emb.shape
+    K = centroids.shape[0]
+    if ids.numel() != N:
+        raise ValueError("ids must have N entries")
+    dev = centroids.device
+    new = None
+    odt = dt
+    if want_centroids:
+        if out is not None:
+            new = out
+            if new.shape != centroids.shape:
+                raise ValueError("out must have the shape of centroids")
+        else:
+            new = torch.empty((K, D), dtype=out_dtype or centroids.dtype, device=dev)
+        if new.dtype not in (torch.float32, torch.bfloat16):
+            raise TypeError("new centroids must be float32 or bfloat16")
+        odt = MOIN_BF16 if new.dtype == torch.bfloat16 else MOIN_F32
+    counts = torch.empty(K, dtype=torch.int32, device=dev) if want_counts else None
+    inertia = torch.empty(1, dtype=torch.float64, device=dev) if want_inertia else None
+    _ck(load().moin_kmeans_update(
+        ctx._h, _dev_ptr(emb, "emb") if N else None, _dev_ptr(ids, "ids", torch.int32) if N else None, N,
+        _dev_ptr(centroids, "centroids"), K, D, dt, _dev_ptr(new, "new_centroids"), odt,
+        _dev_ptr(counts, "counts"), _dev_ptr(inertia, "inertia"), _stream_ptr(stream)), "moin_kmeans_update")
+    return new, counts, inertia
+
+
+def moin_retain_clusters(ctx: Context, counts: torch.Tensor, min_count: int, stream=None):
+    """Returns ``(slot_of_centroid [K] int32, n_retained [1] int32)``."""
+    K = counts.numel()
+    slot = torch.empty(K, dtype=torch.int32, device=counts.device)
+    n = torch.empty(1, dtype=torch.int32, device=counts.device)
+    _ck(load().moin_retain_clusters(ctx._h, _dev_ptr(counts, "counts", torch.int32), K, int(min_count),
+                                    _dev_ptr(slot, "slot_of_centroid"), _dev_ptr(n, "n_retained"),
+                                    _stream_ptr(stream)), "moin_retain_clusters")
+    return slot, n
+
+
+def moin_kmeans_fit(ctx: Context, emb: torch.Tensor, centroids: torch.Tensor, iters: int, stream=None):
+    """Runs ``iters`` Lloyd iterations on ``centroids`` IN PLACE; returns
+    ``(ids [N], counts [K], inertia [iters + 1] float64)``."""
+    dt = _emb_dt(emb, centroids)
+    N, D = emb.shape
+    K = centroids.shape[0]
+    dev = centroids.device
+    ids = torch.empty(N, dtype=torch.int32, device=dev)
+    counts = torch.empty(K, dtype=torch.int32, device=dev)
+    inertia = torch.empty(iters + 1, dtype=torch.float64, device=dev)
+    _ck(load().moin_kmeans_fit(ctx._h, _dev_ptr(emb, "emb") if N else None, N, _dev_ptr(centroids, "centroids"),
+                               K, D, dt, int(iters), _dev_ptr(ids, "ids") if N else None,
+                               _dev_ptr(counts, "counts"), _dev_ptr(inertia, "inertia"), _stream_ptr(stream)),
+        "moin_kmeans_fit")
+    return ids, counts, inertia

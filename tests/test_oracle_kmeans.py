@@ -108,3 +108,25 @@ def test_bad_ids_are_rejected_and_dtypes_agree():
     a = oracle.kmeans_update(xb, ids, cb)
     b = oracle.kmeans_update(bits_to_f64(xb).astype(np.float32), ids, bits_to_f64(cb).astype(np.float32))
     assert np.array_equal(a[0], b[0]) and a[2] == b[2]
+
+
+def test_retained_clusters_are_numbered_in_order():
+    # hand example: threshold 3 keeps clusters 0, 2 and 5
+    slot, kept = oracle.retain_clusters([3, 2, 10, 0, 1, 3], 3)
+    assert slot.tolist() == [0, -1, 1, -1, -1, 2] and kept == 3
+    # threshold 0 keeps everything (identity map), a threshold above the maximum nothing
+    slot, kept = oracle.retain_clusters([0, 5, 1], 0)
+    assert slot.tolist() == [0, 1, 2] and kept == 3
+    slot, kept = oracle.retain_clusters([0, 5, 1], 6)
+    assert slot.tolist() == [-1, -1, -1] and kept == 0
+    # invariants on random counts: kept == #(counts >= t); kept slots are 0..kept-1 ascending
+    rng = np.random.default_rng(6)
+    counts = rng.integers(0, 50, size=200)
+    slot, kept = oracle.retain_clusters(counts, 20)
+    assert kept == int((counts >= 20).sum())
+    assert np.array_equal(slot[slot >= 0], np.arange(kept))
+    assert np.array_equal(slot >= 0, counts >= 20)
+    # composing with the slot map sends members of dropped clusters to the base model (-1)
+    ids = rng.integers(0, 200, size=1000).astype(np.int32)
+    mapped = oracle.slot_map(ids, slot)
+    assert np.array_equal(mapped < 0, counts[ids] < 20)
