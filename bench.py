@@ -10,7 +10,8 @@ linear layer.  Inputs are resident in HBM before the timed region starts.
 Prints ONE JSON line: whole-path TFLOP/s (`value`), the roofline of the
 dominant kernel measured with HIP events on the launch stream, and the CPU
 oracle timed on a bounded sample of the same workload.  `--also` adds the
-decode (GB/s) and router (queries/s) workloads as extra objects.
+decode (GB/s), router (queries/s), full-layer and K-means-update workloads as
+extra objects.
 """
 from __future__ import annotations
 
@@ -203,6 +204,31 @@ def bench_router(ctx, steps, warmup):
             "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS, "kernels": kt}
 
 
+def bench_kmeans(ctx, steps, warmup):
+    """One Lloyd iteration on the router workload (configs[3] shapes): assignment =
+    moin_route, then the centre update, which reads every embedding once."""
+    rw = wl.config_router()
+    rin = wl.make_route_inputs(rw, "cuda")
+    ids, _, _ = moin.moin_route(ctx, rin.emb, rin.centroids, want_counts=False)
+    new = torch.empty_like(rin.centroids)
+
+    def step():
+        moin.moin_kmeans_update(ctx, rin.emb, ids, rin.centroids, out=new)
+
+    ms, _ = timed_region(step, steps, warmup)
+    ctx.check()
+    kt = kernel_times(ctx, step, steps)
+    # what the update must move: every embedding and id once, old and new centres
+    bytes_alg = rw.N * rw.D * 2.0 + rw.N * 4.0 + 2 * rw.K * rw.D * 2.0
+    seg = kt.get("kmeans_sum", {"avg_ms": float("nan")})
+    gbs = bytes_alg / (seg["avg_ms"] * 1e-3) / 1e9
+    return {"ms_per_update": ms, "points_per_s": rw.N / (ms * 1e-3), "algorithmic_bytes": bytes_alg,
+            "GBps_whole_update": bytes_alg / (ms * 1e-3) / 1e9,
+            "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": gbs / PEAK_HBM_GBS, "kernel": "km_segsum", "avg_launch_ms": seg["avg_ms"]},
+            "kernels": kt}
+
+
 def bench_layer(ctx, steps, warmup):
     """configs[4]: seven chained projections, r=128, E=5000, 32 x 2048 tokens, Zipf(1.5)."""
     wls = wl.config_layer()
@@ -242,8 +268,8 @@ def main():
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="first run a plain device copy of this many MiB (3 times): the known-size "
                          "kernel that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
-    ap.add_argument("--also", default="decode,router,layer",
-                    help="comma list of extra workloads to report: decode,router,layer (or 'none')")
+    ap.add_argument("--also", default="decode,router,layer,kmeans",
+                    help="comma list of extra workloads to report: decode,router,layer,kmeans (or 'none')")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU figure exists)",
@@ -269,6 +295,8 @@ def main():
         res["router"] = bench_router(ctx, max(5, args.steps // 5), 2)
     if "layer" in extra:
         res["layer"] = bench_layer(ctx, max(5, args.steps // 5), 2)
+    if "kmeans" in extra:
+        res["kmeans"] = bench_kmeans(ctx, max(5, args.steps // 5), 2)
     ctx.close()
     print(json.dumps(res))
 

@@ -58,32 +58,54 @@ __global__ __launch_bounds__(256) void km_chunk_hist(KmeansArgs a)
 }
 
 // Exclusive prefix of table[.][k] along the chunks, for 64 centres per
-// workgroup (lane = centre, the four waves take a quarter of the chunks each);
+// workgroup (lane = centre, each of the 16 waves takes a run of chunks);
 // counts[k] = column total.
-__global__ __launch_bounds__(256) void km_col_scan(KmeansArgs a)
+constexpr int KM_SCAN_WAVES = 16;
+__global__ __launch_bounds__(64 * KM_SCAN_WAVES) void km_col_scan(KmeansArgs a)
 {
-    __shared__ int part[4][64];
+    __shared__ int part[KM_SCAN_WAVES][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int k = blockIdx.x * 64 + lane;
     const bool valid = k < a.K;
-    const int q = (a.n_chunks + 3) >> 2;
+    const int q = (a.n_chunks + KM_SCAN_WAVES - 1) / KM_SCAN_WAVES;
     const int c0 = min(wave * q, a.n_chunks), c1 = min(c0 + q, a.n_chunks);
     int *col = a.table + (valid ? k : 0);
+    const int64_t K = a.K;
     int sum = 0;
-    if (valid)
-        for (int c = c0; c < c1; ++c) sum += col[(int64_t)c * a.K];
+    if (valid) {
+        int c = c0;
+        for (; c + 8 <= c1; c += 8) {   // eight independent loads in flight
+            int v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = col[(c + u) * K];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) sum += v[u];
+        }
+        for (; c < c1; ++c) sum += col[c * K];
+    }
     part[wave][lane] = sum;
     __syncthreads();
     int run = 0, total = 0;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < KM_SCAN_WAVES; ++w) {
         if (w < wave) run += part[w][lane];
         total += part[w][lane];
     }
     if (valid) {
-        for (int c = c0; c < c1; ++c) {
-            const int v = col[(int64_t)c * a.K];
-            col[(int64_t)c * a.K] = run;
+        int c = c0;
+        for (; c + 8 <= c1; c += 8) {
+            int v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = col[(c + u) * K];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                col[(c + u) * K] = run;
+                run += v[u];
+            }
+        }
+        for (; c < c1; ++c) {
+            const int v = col[c * K];
+            col[c * K] = run;
             run += v;
         }
         if (wave == 0) a.counts[k] = total;
@@ -132,41 +154,65 @@ __global__ __launch_bounds__(1024) void km_segments(KmeansArgs a)
     }
 }
 
-// One wave per chunk walks its points in order, 64 at a time.  Lanes holding
-// the same centre find each other with one ballot per id bit; the lowest of
-// them reserves the group's positions in the chunk's private cursor table (in
-// LDS), and each lane takes the slot of its rank inside the group.  Ranks and
-// cursors follow the point order, so the sort is stable.
-__global__ __launch_bounds__(64) void km_scatter(KmeansArgs a)
+// One workgroup per chunk walks the chunk's points in order, 64 at a time.
+// Lanes holding the same centre find each other with one ballot per id bit; the
+// lowest of them reserves the group's positions in the chunk's private cursor
+// table (in LDS), and each lane takes the slot of its rank inside the group.
+// The matching (most of the instructions) runs on KM_SCATTER_WAVES batches at
+// once, one per wave; the cursor updates then take turns in batch order, so
+// ranks and cursors follow the point order and the sort is stable.
+constexpr int KM_SCATTER_WAVES = 8;
+__global__ __launch_bounds__(64 * KM_SCATTER_WAVES) void km_scatter(KmeansArgs a)
 {
     extern __shared__ int km_pos[];
+    constexpr int NT = 64 * KM_SCATTER_WAVES;
+    static_assert(KM_MAX_K <= (1 << 15), "id bits matched per batch");
     const int K = a.K;
-    const int lane = threadIdx.x;
     const int *row = a.table + (int64_t)blockIdx.x * K;
-    for (int k = lane; k < K; k += 64) km_pos[k] = a.seg_start[k] + row[k];
-    __syncthreads();
-    int nbits = 0;
-    while ((1 << nbits) < K) ++nbits;
+    for (int k0 = threadIdx.x; k0 < K; k0 += NT * 4) {   // four independent loads per thread in flight
+        int v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int k = k0 + u * NT;
+            v[u] = (k < K) ? a.seg_start[k] + row[k] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (k0 + u * NT < K) km_pos[k0 + u * NT] = v[u];
+    }
+    const int wave = uniform(threadIdx.x >> 6);
     const uint64_t lt = lanemask_lt();
     const int64_t i0 = (int64_t)blockIdx.x * a.chunk;
     const int64_t i1 = min(a.N, i0 + a.chunk);
-    for (int64_t b = i0; b < i1; b += 64) {
-        const int64_t i = b + lane;
-        const int id = (i < i1) ? a.ids[i] : -1;
+    int64_t i = i0 + threadIdx.x;
+    int nxt = (i < i1) ? a.ids[i] : -1;
+    __syncthreads();
+    for (int64_t b = i0; b < i1; b += NT) {   // uniform trip count for the whole workgroup
+        i = b + threadIdx.x;
+        const int id = nxt;
+        nxt = (i + NT < i1) ? a.ids[i + NT] : -1;
         const bool ok = (unsigned)id < (unsigned)K;
         uint64_t m = __ballot(ok);
-        for (int bit = 0; bit < nbits; ++bit) {
+        // bits above log2(K) are zero in every valid id and cost nothing but their turn; a
+        // fixed trip count lets all ballots issue before the first select
+#pragma unroll
+        for (int bit = 0; bit < 15; ++bit) {
             const bool one = (id >> bit) & 1;
             const uint64_t bal = __ballot(one);
             m &= one ? bal : ~bal;
         }
         const int rank = __popcll(m & lt);
-        int base = 0;
-        if (ok && rank == 0) {
-            base = km_pos[id];
-            km_pos[id] = base + __popcll(m);
-        }
+        const int cnt = __popcll(m);
         const int leader = ok ? (__ffsll((unsigned long long)m) - 1) : 0;
+        int base = 0;
+#pragma unroll 1
+        for (int turn = 0; turn < KM_SCATTER_WAVES; ++turn) {
+            if (wave == turn && ok && rank == 0) {
+                base = km_pos[id];
+                km_pos[id] = base + cnt;
+            }
+            __syncthreads();
+        }
         base = __shfl(base, leader);
         if (ok) a.perm[base + rank] = (int)i;
     }
@@ -359,9 +405,9 @@ hipError_t launch_kmeans_sort(const KmeansArgs &a, hipStream_t stream)
 {
     const size_t lds = (size_t)a.K * 4;
     if (a.N > 0) hipLaunchKernelGGL(km_chunk_hist, dim3(a.n_chunks), dim3(256), lds, stream, a);
-    hipLaunchKernelGGL(km_col_scan, dim3((a.K + 63) / 64), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(km_col_scan, dim3((a.K + 63) / 64), dim3(64 * KM_SCAN_WAVES), 0, stream, a);
     hipLaunchKernelGGL(km_segments, dim3(1), dim3(1024), 0, stream, a);
-    if (a.N > 0) hipLaunchKernelGGL(km_scatter, dim3(a.n_chunks), dim3(64), lds, stream, a);
+    if (a.N > 0) hipLaunchKernelGGL(km_scatter, dim3(a.n_chunks), dim3(64 * KM_SCATTER_WAVES), lds, stream, a);
     return hipGetLastError();
 }
 

@@ -92,3 +92,32 @@ def test_layer_chain_full_size():
         del inp
         torch.cuda.empty_cache()
     plan.close()
+
+
+def test_kmeans_update_full_size():
+    """One centre update at the router workload's size (1 048 576 x 768 bf16,
+    5000 centres), ids from the GPU router: every centre against the oracle,
+    which reads the same bytes (about 1 s of host time per Gflop of sums)."""
+    import oracle
+    rw = wl.config_router()
+    rin = wl.make_route_inputs(rw, "cuda")
+    print("[gpu] c3 kmeans update full size: route", flush=True)
+    _, cids, rcounts = moin.moin_route(gc.ctx(), rin.emb, rin.centroids, want_counts=True)
+    print("[gpu] c3 kmeans update full size: update", flush=True)
+    new, counts, inertia = moin.moin_kmeans_update(gc.ctx(), rin.emb, cids, rin.centroids, out_dtype=torch.float32)
+    gc.ctx().check()
+    assert torch.equal(counts, rcounts)
+    emb_h, ids_h = wl.bf16_bits(rin.emb), cids.cpu().numpy()
+    print("[gpu] c3 kmeans update full size: oracle", flush=True)
+    ref_new, ref_counts, ref_inertia = oracle.kmeans_update(emb_h, ids_h, wl.bf16_bits(rin.centroids))
+    assert np.array_equal(counts.cpu().numpy(), ref_counts)
+    assert abs(inertia.item() - ref_inertia) <= 2e-6 * ref_inertia
+    got = new.double().cpu().numpy()
+    # bound of tests/test_gpu_kmeans.py with mean|x| replaced by its upper bound
+    # max|x| over the table (unit vectors in 768 dimensions: entries are small)
+    xmax = float(rin.emb.abs().max().item())
+    tol = 520 * 2.0 ** -24 * xmax + 2 * 2.0 ** -24 * np.abs(ref_new)
+    err = np.abs(got - ref_new)
+    assert not (err > tol).any(), f"{int((err > tol).sum())} entries beyond the bound, worst {err.max():.3e}"
+    print(f"[gpu] c3 kmeans: worst centre error {err.max():.3e} (bound {tol.min():.3e}), "
+          f"{int((ref_counts == 0).sum())} empty clusters", flush=True)
