@@ -424,9 +424,13 @@ int moin_route(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N,
 
     const size_t Kpad = align_up((size_t)K, 256);
     const size_t cn_bytes = align_up(Kpad * 4, 256);
-    const size_t best_bytes = (size_t)ROUTE_SMALL_MAX_N * 8 + 256;
+    const int group = route_stream_group(N, K, D, dt == MOIN_BF16);
+    const size_t n_best = group > 1 ? (size_t)N : (size_t)ROUTE_SMALL_MAX_N;
+    const size_t n_arr = 1;
+    const size_t best_bytes = align_up(n_best * 8, 256);
+    const size_t arr_bytes = align_up(n_arr * 4, 256);
     const bool need_cid_ws = counts && !centroid_ids && N > 0;
-    const int rc = ensure_ws(ctx, cn_bytes + best_bytes + (need_cid_ws ? (size_t)N * 4 : 0));
+    const int rc = ensure_ws(ctx, 2 * cn_bytes + best_bytes + arr_bytes + (need_cid_ws ? (size_t)N * 4 : 0));
     if (rc != MOIN_OK) return rc;
     char *w = static_cast<char *>(ctx->ws);
 
@@ -435,11 +439,14 @@ int moin_route(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N,
     a.is_bf16 = (dt == MOIN_BF16);
     a.slot = slot_of_centroid;
     a.retained_only = (flags & MOIN_ROUTE_RETAINED_ONLY) ? 1 : 0;
+    a.group = group;
     a.cnorm = reinterpret_cast<float *>(w);
-    a.best = reinterpret_cast<unsigned long long *>(w + cn_bytes);
-    a.arrivals = reinterpret_cast<int *>(w + cn_bytes + (size_t)ROUTE_SMALL_MAX_N * 8);
+    a.cinit = reinterpret_cast<float *>(w + cn_bytes);
+    a.best = reinterpret_cast<unsigned long long *>(w + 2 * cn_bytes);
+    a.arrivals = reinterpret_cast<int *>(w + 2 * cn_bytes + best_bytes);
     a.cid = centroid_ids ? centroid_ids
-                         : (need_cid_ws ? reinterpret_cast<int *>(w + cn_bytes + best_bytes) : nullptr);
+                         : (need_cid_ws ? reinterpret_cast<int *>(w + 2 * cn_bytes + best_bytes + arr_bytes)
+                                        : nullptr);
     a.expert_ids = expert_ids;
     a.counts = counts;
 

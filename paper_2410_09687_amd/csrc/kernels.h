@@ -81,15 +81,19 @@ struct RouteArgs {
     const int *slot;       // [K] or null
     int retained_only;
     float *cnorm;          // [K rounded up to 256] workspace
+    float *cinit;          // [same] workspace: -cnorm / 2
     int *cid;              // [N] centroid ids (user buffer or workspace)
     int *expert_ids;       // [N] or null
     // small batches: per-query packed (score, index) minimum merged across
     // workgroups, and the arrival counter that elects the finishing workgroup
-    unsigned long long *best;  // [ROUTE_SMALL_MAX_N] workspace
+    unsigned long long *best;  // [ROUTE_SMALL_MAX_N, or N when group > 1] workspace
     int *arrivals;             // [1] workspace
     int *counts;               // [K] or null: zeroed by the norms kernel
+    int group;                 // route_stream_group() of the call
 };
 constexpr int ROUTE_SMALL_MAX_N = 4096;  // up to here the K range is split across workgroups
+// Workgroups that share one query tile in the large-batch bf16 kernel (1: none).
+int route_stream_group(int64_t N, int K, int D, int is_bf16);
 hipError_t launch_centroid_norms(const RouteArgs &a, hipStream_t stream);
 hipError_t launch_route(const RouteArgs &a, hipStream_t stream);
 // true when launch_route itself fills a.counts (no histogram launch needed)

@@ -25,14 +25,16 @@ using CfgRouteSmall = DmaCore<64, 64, 64, 2, 2, 6>;  // small batches: one (cent
 struct RouteKParams {
     const char *emb, *cent;
     const float *cnorm;   // [K padded to a multiple of 256]; +inf for excluded / padding
+    const float *cinit;   // [same]: -||c||^2 / 2, -inf for excluded / padding
     const int *slot;
     int *cid;
     int *expert_ids;
     unsigned long long *best;
-    int *arrivals;
+    int *arrivals;        // small-batch kernel
     int *counts;          // small batches only: tallied by the finishing workgroup (zeroed beforehand)
     int64_t N;
     int K, D;
+    int group;            // streaming kernel: workgroups that share one query tile
 };
 
 __device__ __forceinline__ bool lex_less(float v, int i, float bv, int bi)
@@ -197,13 +199,24 @@ __global__ __launch_bounds__(C::NT) void route_kernel(RouteKParams p)
     }
 }
 
+// Order-preserving map of a finite float (or +-inf) to an unsigned integer.
+__device__ __forceinline__ uint32_t float_order_key(float f)
+{
+    const uint32_t u = f32_bits(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
 // Large batches, D a multiple of 64: same tiling as route_kernel, with the
 // block pipeline of the prefill linear kernel -- two direct-to-LDS stages, MFMA
 // fragments read one k-step ahead, the block barrier placed before the last
 // k-step (whose fragments are already in registers) and the first fragments of
 // the next block read during that k-step.  The blocks of all centroid tiles
-// form one stream; a finished tile is folded into the running minima between
-// two blocks.
+// form one stream; a finished tile is folded into the running best between two
+// blocks.  argmin ||q - c||^2 is taken as argmax (q.c - ||c||^2 / 2): the first
+// MFMA of a tile takes -||c||^2 / 2 as its addend, so accumulators are never
+// cleared and the fold is a compare and two selects per score.  The position
+// inside the tile travels as a small code (tile, accumulator, element) that is
+// the same for all lanes, i.e. a scalar operand.
 __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKParams p)
 {
     using C = CfgRouteDma;
@@ -212,14 +225,24 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
     const int wave = uniform(threadIdx.x >> 6);
     const int wm = wave / C::WN, wn = wave % C::WN;
     const int r = lane & 31, h = lane >> 5;
-    const int64_t q0 = (int64_t)blockIdx.x * C::BN;
+    // `group` workgroups next to each other on one XCD share a query tile and
+    // take every group-th centroid tile: the XCD's L2 then holds few query
+    // tiles at a time, each fetched once for all of its workgroups, instead of
+    // one tile per compute unit that falls out of the cache between two uses.
+    const int G = p.group;
+    const int slot = blockIdx.x >> 3;
+    const int member = slot % G;
+    const int64_t qtile = (int64_t)(slot / G) * 8 + (blockIdx.x & 7);
+    const int64_t q0 = qtile * C::BN;
+    if (q0 >= p.N) return;
     const int nq = (int)min((int64_t)C::BN, p.N - q0);
     const uint32_t ld = (uint32_t)p.D * 2u;
     const int nkb = p.D / C::BK;
     const int nct = (p.K + C::BM - 1) / C::BM;
     const int last_rows = p.K - (nct - 1) * C::BM;
     const char *qb = p.emb + q0 * (int64_t)ld;
-    const int total = nct * nkb;
+    const int my_tiles = (nct - member + G - 1) / G;   // >= 1: G <= nct
+    const int total = my_tiles * nkb;
 
     // DMA mapping (see DmaCore): instruction j of a wave fills tile rows
     // (wave*4 + j)*8 .. +8; only j's parity enters the chunk swizzle
@@ -263,7 +286,6 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
             fb[slot][j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(stage + offB + j * 32 * C::ROWB + o));
     };
     typename C::Acc acc;
-    C::zero(acc);
     auto mfmas = [&](int slot) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < C::FM; ++i)
@@ -271,27 +293,71 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
             for (int j = 0; j < C::FN; ++j)
                 acc.v[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc.v[i][j], 0, 0, 0);
     };
+    // start values of the next tile's accumulators: element e of accumulator i
+    // belongs to centroid row wm*WTM + 32 i + 8 (e / 4) + 4 h + e % 4 of the tile
+    f32x16_t cin[C::FM];
+    auto load_init = [&](int ct_) __attribute__((always_inline)) {
+        const float *cn = p.cinit + ct_ * C::BM + wm * C::WTM + 4 * h;
+#pragma unroll
+        for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4_t v = *reinterpret_cast<const f32x4_t *>(cn + i * 32 + g * 8);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) cin[i][4 * g + q] = v[q];
+            }
+    };
+    auto mfmas_first = [&](int slot) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+            for (int j = 0; j < C::FN; ++j)
+                acc.v[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], cin[i], 0, 0, 0);
+    };
 
     float bestv[C::FN];
-    int besti[C::FN];
+    int bestc[C::FN];   // (tile << 5) | (accumulator i << 4) | element
+    static_assert(C::FM == 2, "position code");
 #pragma unroll
     for (int j = 0; j < C::FN; ++j) {
-        bestv[j] = __builtin_inff();
-        besti[j] = 0;
+        bestv[j] = -__builtin_inff();
+        bestc[j] = 0;
     }
 
-    int kb = 0, ct = 0;        // block being computed
-    int pkb = 2, pct = 0;      // block to fetch next (two ahead)
+    int kb = 0, ct = member;   // block being computed
+    int pkb = 2, pct = member; // block to fetch next (two ahead)
     while (pkb >= nkb) {       // D = 64: one block per centroid tile
         pkb -= nkb;
-        ++pct;
+        pct += G;
     }
     auto body = [&](int s, auto issue_tag, auto read_tag) __attribute__((always_inline)) {
         constexpr bool ISSUE = decltype(issue_tag)::value, READ = decltype(read_tag)::value;
         char *st_cur = smem + (s & 1) * C::STAGE_BYTES;
         const char *st_nxt = smem + ((s + 1) & 1) * C::STAGE_BYTES;
+        // first k-step: a tile's first block starts from -||c||^2 / 2
+        read_frags(st_cur, 1, 1);
+        if (kb == 0) {
+            mfmas_first(0);
 #pragma unroll
-        for (int ks = 0; ks < C::KSTEPS - 1; ++ks) {
+            for (int n = 0; n < C::FM + C::FN; ++n) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, C::FM * C::FN - (C::FM + C::FN), 0);
+        } else {
+            mfmas(0);
+#pragma unroll
+            for (int n = 0; n < C::FM + C::FN; ++n) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, C::FM * C::FN - (C::FM + C::FN), 0);
+        }
+        // the tile's last block fetches the next tile's start values; they land
+        // before this block's barrier (vmcnt(0))
+        if (kb == nkb - 1 && ct + G < nct) load_init(ct + G);
+#pragma unroll
+        for (int ks = 1; ks < C::KSTEPS - 1; ++ks) {
             read_frags(st_cur, ks + 1, (ks + 1) & 1);
             mfmas(ks & 1);
 #pragma unroll
@@ -306,7 +372,7 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
             issue(pct, pkb, st_cur);
             if (++pkb == nkb) {
                 pkb = 0;
-                ++pct;
+                pct += G;
             }
         }
         if constexpr (READ) read_frags(st_nxt, 0, 0);
@@ -320,16 +386,29 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
             }
         }
         if (++kb == nkb) {
-            fold_scores<C>(acc, p.cnorm + ct * C::BM, ct * C::BM, bestv, besti);
-            C::zero(acc);
+            // a lane's scores come in ascending centroid order, so a strict '>'
+            // keeps the lowest index among equal scores
+            const int code0 = ct << 5;
+#pragma unroll
+            for (int i = 0; i < C::FM; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+#pragma unroll
+                    for (int j = 0; j < C::FN; ++j) {
+                        const float sc = acc.v[i][j][e];
+                        const bool gt = sc > bestv[j];
+                        bestv[j] = gt ? sc : bestv[j];
+                        bestc[j] = gt ? code0 + (i * 16 + e) : bestc[j];
+                    }
             kb = 0;
-            ++ct;
+            ct += G;
         }
     };
 
-    issue(0, 0, smem);
+    load_init(member);
+    issue(member, 0, smem);
     if (total > 1) {
-        issue(nkb > 1 ? 0 : 1, nkb > 1 ? 1 : 0, smem + C::STAGE_BYTES);
+        issue(nkb > 1 ? member : member + G, nkb > 1 ? 1 : 0, smem + C::STAGE_BYTES);
         wait_vm_then_barrier<2 * LOADS>();
     } else {
         wait_vm_then_barrier<0>();
@@ -344,12 +423,16 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
     body(s, std::false_type{}, std::false_type{});
     __syncthreads();
 
-    // merge the two lane halves (rows 4*(lane>>5) interleave), then the WM waves
+    // position code -> centroid index; then merge the two lane halves (rows
+    // 4*(lane>>5) interleave) and the WM waves: higher score, else lower index
+    int besti[C::FN];
 #pragma unroll
     for (int j = 0; j < C::FN; ++j) {
+        const int c = bestc[j], e = c & 15;
+        besti[j] = (c >> 5) * C::BM + wm * C::WTM + ((c >> 4) & 1) * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
         const float ov = __shfl_xor(bestv[j], 32);
         const int oi = __shfl_xor(besti[j], 32);
-        if (lex_less(ov, oi, bestv[j], besti[j])) {
+        if (lex_less(-ov, oi, -bestv[j], besti[j])) {
             bestv[j] = ov;
             besti[j] = oi;
         }
@@ -372,21 +455,35 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
         for (int w = 1; w < C::WM; ++w) {
             const float v = sv[w * C::BN + col];
             const int i = si[w * C::BN + col];
-            if (lex_less(v, i, bv, bi)) {
+            if (lex_less(-v, i, -bv, bi)) {
                 bv = v;
                 bi = i;
             }
         }
-        if (p.cid) p.cid[q0 + col] = bi;
-        if (p.expert_ids) p.expert_ids[q0 + col] = p.slot ? p.slot[bi] : bi;
+        if (G == 1) {
+            if (p.cid) p.cid[q0 + col] = bi;
+            if (p.expert_ids) p.expert_ids[q0 + col] = p.slot ? p.slot[bi] : bi;
+        } else if (bv > -__builtin_inff()) {
+            // exact, order-independent merge across the group: smallest -score,
+            // then lowest index; a score of -inf (excluded centroid, NaN) never enters
+            atomicMin(&p.best[q0 + col], ((unsigned long long)float_order_key(-bv) << 32) | (unsigned)bi);
+        }
     }
+    // G > 1: route_unpack_kernel turns the packed winners into ids.  (Electing a
+    // finishing workgroup here would need device-scope fences, and an acquire
+    // fence drops the XCD's L2 contents -- the very thing the grouping protects.)
 }
 
-// Order-preserving map of a finite float (or +-inf) to an unsigned integer.
-__device__ __forceinline__ uint32_t float_order_key(float f)
+// Packed (score key, index) winners of the grouped streaming kernel -> ids.
+__global__ __launch_bounds__(256) void route_unpack_kernel(const unsigned long long *best, int64_t N, int K,
+                                                           const int *slot, int *cid, int *expert_ids)
 {
-    const uint32_t u = f32_bits(f);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (q >= N) return;
+    const unsigned idx = (unsigned)(best[q] & 0xffffffffu);
+    const int bi = (idx < (unsigned)K) ? (int)idx : 0;   // nothing won: centroid 0
+    if (cid) cid[q] = bi;
+    if (expert_ids) expert_ids[q] = slot ? slot[bi] : bi;
 }
 
 // Small batches: too few queries to fill the chip with 256-query workgroups, so
@@ -475,15 +572,16 @@ __global__ __launch_bounds__(C::NT) void route_small_kernel(RouteKParams p, int 
 __global__ __launch_bounds__(256) void centroid_norm_kernel(const char *cent, int K, int Kpad,
                                                             int D, int is_bf16, const int *slot,
                                                             int retained_only, float *cnorm,
-                                                            unsigned long long *best, int nbest,
-                                                            int *arrivals, int *counts)
+                                                            float *cinit,
+                                                            unsigned long long *best, int64_t nbest,
+                                                            int *arrivals, int narrivals, int *counts)
 {
     const int gid = blockIdx.x * 256 + threadIdx.x;
     const int gsz = gridDim.x * 256;
-    for (int i = gid; i < nbest; i += gsz) best[i] = ~0ull;
+    for (int64_t i = gid; i < nbest; i += gsz) best[i] = ~0ull;
     if (counts)
         for (int i = gid; i < K; i += gsz) counts[i] = 0;
-    if (gid == 0) *arrivals = 0;
+    for (int i = gid; i < narrivals; i += gsz) arrivals[i] = 0;
 
     const int lane = threadIdx.x & 63;
     const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -506,7 +604,10 @@ __global__ __launch_bounds__(256) void centroid_norm_kernel(const char *cent, in
     } else {
         acc = __builtin_inff();
     }
-    if (lane == 0) cnorm[k] = acc;
+    if (lane == 0) {
+        cnorm[k] = acc;
+        cinit[k] = -0.5f * acc;
+    }
 }
 
 // fp32 embeddings: one wave per query, direct sum of squared differences.
@@ -601,15 +702,42 @@ static bool use_small_route(const RouteArgs &a)
     return a.is_bf16 && a.D % 64 == 0 && a.N <= ROUTE_SMALL_MAX_N;
 }
 
+static bool use_stream_route(const RouteArgs &a) { return a.is_bf16 && a.D % 64 == 0 && !use_small_route(a); }
+
+// Workgroups per query tile of the streaming kernel: prefers 4 (eight query
+// tiles per XCD in flight), among the sizes that split the centroid tiles
+// evenly or nearly so; 1 = no sharing (few centroid tiles).
+int route_stream_group(int64_t N, int K, int D, int is_bf16)
+{
+    RouteArgs a{};
+    a.N = N; a.K = K; a.D = D; a.is_bf16 = is_bf16;
+    if (!use_stream_route(a)) return 1;
+    const int nct = (K + CfgRouteDma::BM - 1) / CfgRouteDma::BM;
+    const int pref[] = {4, 8, 2, 5, 3, 6, 7};
+    int best_g = 1;
+    double best_waste = 1.05;   // accept at most 5 % of idle tile slots over the plain scheme
+    for (int g : pref) {
+        if (g > nct) continue;
+        const double waste = (double)((nct + g - 1) / g * g) / nct;
+        if (waste < best_waste) {
+            best_waste = waste;
+            best_g = g;
+            if (waste == 1.0) break;
+        }
+    }
+    return best_g;
+}
+
 bool route_tallies_counts(const RouteArgs &a) { return a.N > 0 && a.counts != nullptr && use_small_route(a); }
 
 hipError_t launch_centroid_norms(const RouteArgs &a, hipStream_t stream)
 {
     const int Kpad = (a.K + 255) / 256 * 256;
-    const int nbest = use_small_route(a) ? (int)a.N : 0;
+    const int64_t nbest = (use_small_route(a) || a.group > 1) ? a.N : 0;
+    const int narr = 1;
     hipLaunchKernelGGL(centroid_norm_kernel, dim3((Kpad + 3) / 4), dim3(256), 0, stream,
                        (const char *)a.cent, a.K, Kpad, a.D, a.is_bf16, a.slot, a.retained_only,
-                       a.cnorm, a.best, nbest, a.arrivals, a.counts);
+                       a.cnorm, a.cinit, a.best, nbest, a.arrivals, narr, a.counts);
     return hipGetLastError();
 }
 
@@ -619,10 +747,11 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t stream)
     if (a.is_bf16) {
         RouteKParams p;
         p.emb = (const char *)a.emb; p.cent = (const char *)a.cent;
-        p.cnorm = a.cnorm; p.slot = a.slot; p.cid = a.cid; p.expert_ids = a.expert_ids;
+        p.cnorm = a.cnorm; p.cinit = a.cinit; p.slot = a.slot; p.cid = a.cid; p.expert_ids = a.expert_ids;
         p.best = a.best; p.arrivals = a.arrivals;
         p.counts = use_small_route(a) ? a.counts : nullptr;
         p.N = a.N; p.K = a.K; p.D = a.D;
+        p.group = a.group > 1 ? a.group : 1;
         if (use_small_route(a)) {
             using C = CfgRouteSmall;
             const int nqt = (int)((a.N + C::BN - 1) / C::BN);
@@ -634,10 +763,16 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t stream)
         }
         const int64_t grid = (a.N + CfgRoute::BN - 1) / CfgRoute::BN;
         if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-        if (a.D % 64 == 0)
-            hipLaunchKernelGGL(route_stream_kernel, dim3((unsigned)grid), dim3(CfgRouteDma::NT),
+        if (a.D % 64 == 0) {
+            // query tile t runs on XCD t % 8, its workgroups in consecutive slots there
+            const int64_t sgrid = (grid + 7) / 8 * 8 * p.group;
+            if (sgrid > 0x7fffffffLL) return hipErrorInvalidValue;
+            hipLaunchKernelGGL(route_stream_kernel, dim3((unsigned)sgrid), dim3(CfgRouteDma::NT),
                                CfgRouteDma::SMEM_BYTES, stream, p);
-        else
+            if (p.group > 1)
+                hipLaunchKernelGGL(route_unpack_kernel, dim3((unsigned)((a.N + 255) / 256)), dim3(256), 0,
+                                   stream, p.best, a.N, a.K, a.slot, a.cid, a.expert_ids);
+        } else
             hipLaunchKernelGGL(route_kernel<CfgRoute>, dim3((unsigned)grid), dim3(CfgRoute::NT),
                                CfgRoute::SMEM_BYTES, stream, p);
     } else {
