@@ -204,6 +204,7 @@ hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStr
 constexpr int DECODE_BASE_TARGET_WGS = 512;
 constexpr int DECODE_BASE_MAX_SPLITS = 4;   // the expand kernel sums up to four parts
 constexpr int DECODE_BASE_MIN_BLOCKS = 4;   // BK blocks per part at least
+constexpr int DECODE_BASE_SPLIT_BLOCKS = 32;
 
 template <class C>
 static void shape_for(int64_t T, int d_in, int d_out, bool may_split, DecodeBaseShape *sh)
@@ -214,6 +215,10 @@ static void shape_for(int64_t T, int d_in, int d_out, bool may_split, DecodeBase
     const int nkb = (d_in + C::BK - 1) / C::BK;
     int want = may_split ? (int)((DECODE_BASE_TARGET_WGS + tiles - 1) / (tiles > 0 ? tiles : 1)) : 1;
     if (want > DECODE_BASE_MAX_SPLITS) want = DECODE_BASE_MAX_SPLITS;
+    // every part costs a plane of fp32 partial sums written and read back: no more
+    // parts than it takes to keep a tile's serial loop to about DECODE_BASE_SPLIT_BLOCKS blocks
+    const int by_len = (nkb + DECODE_BASE_SPLIT_BLOCKS - 1) / DECODE_BASE_SPLIT_BLOCKS;
+    if (want > by_len) want = by_len;
     if (want > nkb / DECODE_BASE_MIN_BLOCKS) want = nkb / DECODE_BASE_MIN_BLOCKS;
     if (want < 1) want = 1;
     const int per = (nkb + want - 1) / want;

@@ -110,6 +110,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
                 *pv.n_groups = 1;
                 pv.grp_meta[0] = make_int4(-1, 0, T, 0);
             }
+            for (int gi = 1 + tid; gi < pv.max_groups; gi += PLAN_THREADS) pv.grp_meta[gi] = make_int4(-1, 0, 0, 0);
         }
         return;
     }
@@ -187,6 +188,9 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
             pv.grp_meta[gi].z = pv.grp_start[gi + 1];
             pv.grp_meta[gi].w = 0;
         }
+        // unused records read as empty groups, so the decode kernels need not
+        // fetch the group count before their own record
+        for (int gi = n_groups + tid; gi < pv.max_groups; gi += PLAN_THREADS) pv.grp_meta[gi] = make_int4(-1, 0, 0, 0);
     }
 }
 
