@@ -36,9 +36,9 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 # HBM-side bytes per launch of the dominant (linear) kernel on configs[1], from the
 # rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised in
-# profiles/prefill_and_decode_hbm_traffic.md: (2.0 * 212817 KiB + 1.0 * 136704 KiB) * 1024,
+# profiles/hbm_traffic_all_workloads.md: (2.0 * 212133 KiB + 1.0 * 135680 KiB) * 1024,
 # the factors being what the same counters read for a plain 1 GiB copy.
-LINEAR_KERNEL_TRAFFIC_BYTES = int((2.0 * 212817.4 + 1.0 * 136704.0) * 1024)
+LINEAR_KERNEL_TRAFFIC_BYTES = int((2.0 * 212133.3 + 1.0 * 135680.0) * 1024)
 
 
 def timed_region(fn, steps, warmup):
