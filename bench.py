@@ -229,6 +229,62 @@ def bench_kmeans(ctx, steps, warmup):
             "kernels": kt}
 
 
+def bench_cache(ctx, n_batches=48, n_slots=512):
+    """Decode batches of the gate projection (configs[2] shapes) served through the adapter
+    residency cache: 5000 experts in pinned host memory, `n_slots` resident, one request
+    stream with a fixed Zipf(1.1) popularity order.  Reports the hit rate, the host-to-device
+    rate of the misses and the time per batch against the all-resident case."""
+    w = wl.config_decode()[0]
+    per_a, per_b = w.r * w.d_in, w.d_out * w.r
+    blk = wl._randn_bf16((1 << 24,), 0.02, torch.device("cpu"), 99)      # 32 MB of values, repeated
+    def host_stack(per):
+        t = torch.empty((w.E, per), dtype=torch.bfloat16, pin_memory=True)
+        flat = t.view(-1)
+        for lo in range(0, flat.numel(), blk.numel()):
+            n = min(blk.numel(), flat.numel() - lo)
+            flat[lo:lo + n] = blk[:n]
+        return t
+    A_host = host_stack(per_a).view(w.E, w.r, w.d_in)
+    B_host = host_stack(per_b).view(w.E, w.d_out, w.r)
+    A_slots = torch.zeros((n_slots, w.r, w.d_in), dtype=torch.bfloat16, device="cuda")
+    B_slots = torch.zeros((n_slots, w.d_out, w.r), dtype=torch.bfloat16, device="cuda")
+    W = wl._randn_bf16((w.d_out, w.d_in), w.d_in ** -0.5, torch.device("cuda"), 5)
+    x = wl._randn_bf16((w.T, w.d_in), 1.0, torch.device("cuda"), 6)
+    off = torch.from_numpy(wl.seq_offsets_of(w.seq_lens)).cuda()
+    y = torch.empty((w.T, w.d_out), dtype=torch.bfloat16, device="cuda")
+    cache = moin.Cache(w.E, n_slots)
+    cache.add_stack(A_host, B_host, A_slots, B_slots)
+    batches = [wl.draw_expert_ids(w.S, w.E, "zipf", w.zipf_s, 5000 + k, perm_seed=4242) for k in range(2 * n_batches)]
+
+    def serve(ids):
+        slots = cache.admit(ids)
+        moin.moin_lora_linear(ctx, x, off, slots.cuda(non_blocking=True), W, A_slots, B_slots, w.scale, out=y)
+
+    for ids in batches[:n_batches]:       # warm the cache
+        serve(ids)
+    torch.cuda.synchronize()
+    s0 = cache.stats()
+    t0 = time.perf_counter()
+    for ids in batches[n_batches:]:
+        serve(ids)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    s1 = cache.stats()
+    ctx.check()
+    d = {k: s1[k] - s0[k] for k in s1}
+    # all-resident reference: the same batches, slot ids = what the warm cache holds (no copies)
+    slots_dev = [cache.admit(ids).cuda() for ids in batches[n_batches:n_batches + 8]]
+    torch.cuda.synchronize()
+    ms_res, _ = timed_region(lambda: [moin.moin_lora_linear(ctx, x, off, sd, W, A_slots, B_slots, w.scale, out=y)
+                                      for sd in slots_dev], 4, 1)
+    cache.close()
+    return {"experts": w.E, "slots": n_slots, "bytes_per_expert": 2 * (per_a + per_b),
+            "hit_rate": d["seq_hits"] / max(1, d["seq_hits"] + d["seq_misses"]),
+            "loads_per_batch": d["loads"] / n_batches, "h2d_GB_per_batch": d["bytes"] / n_batches / 1e9,
+            "ms_per_batch": dt * 1e3 / n_batches, "h2d_GBps_over_the_batch_time": d["bytes"] / dt / 1e9,
+            "ms_per_batch_all_resident": ms_res / len(slots_dev), "overflows": d["overflows"]}
+
+
 def bench_layer(ctx, steps, warmup):
     """configs[4]: seven chained projections, r=128, E=5000, 32 x 2048 tokens, Zipf(1.5)."""
     wls = wl.config_layer()
@@ -269,7 +325,8 @@ def main():
                     help="first run a plain device copy of this many MiB (3 times): the known-size "
                          "kernel that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--also", default="decode,router,layer,kmeans",
-                    help="comma list of extra workloads to report: decode,router,layer,kmeans (or 'none')")
+                    help="comma list of extra workloads to report: decode,router,layer,kmeans,cache "
+                         "(or 'none'); cache is not in the default list (it pins 10 GB of host memory)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU figure exists)",
@@ -297,6 +354,8 @@ def main():
         res["layer"] = bench_layer(ctx, max(5, args.steps // 5), 2)
     if "kmeans" in extra:
         res["kmeans"] = bench_kmeans(ctx, max(5, args.steps // 5), 2)
+    if "cache" in extra:
+        res["cache"] = bench_cache(ctx)
     ctx.close()
     print(json.dumps(res))
 

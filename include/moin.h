@@ -203,6 +203,56 @@ int moin_kmeans_fit(moin_ctx *ctx, const void *emb, int64_t N, void *centroids, 
                     int32_t D, moin_dtype dt, int32_t iters, int32_t *ids, int32_t *counts,
                     double *inertia, void *stream);
 
+/* ---- adapter residency cache ------------------------------------------------
+ * Section 2 (serving paragraph): the adapters of all topics are kept in CPU
+ * memory and the most frequently routed ones are cached in GPU memory.  A
+ * moin_cache maps E stored experts onto n_slots resident slots.  Per batch,
+ * moin_cache_admit takes the batch's expert ids (a HOST array: paging is decided
+ * on the host), makes every needed expert resident and returns one slot id per
+ * sequence; moin_lora_linear then runs on the slot stacks (E = n_slots) with
+ * those slot ids.  Policy: every sequence adds one to its expert's use count;
+ * a needed expert is always loaded; free slots go lowest index first; the
+ * victim is the resident expert not needed by the batch with the fewest uses,
+ * then the least recently used, then the lowest slot; when every slot holds an
+ * expert of the batch, the rest of the batch's experts get slot -1 (base model
+ * only, Section 4.1).
+ *
+ * moin_cache_add_stack registers one projection: A_host [E, ...] / B_host
+ * [E, ...] in HOST memory (pinned, if the copies are to be asynchronous) and
+ * A_slots [n_slots, ...] / B_slots [n_slots, ...] in DEVICE memory, with the
+ * bytes of one expert in each; all owned by the caller and alive as long as the
+ * cache.  Stacks are registered before the first batch.  moin_cache_admit
+ * enqueues the copies on `stream`, the stream the batch's kernels will run on
+ * (so a slot is never overwritten under a kernel that still reads it); with no
+ * stack registered it is pure bookkeeping and needs no GPU.  expert id -1 maps
+ * to slot -1; ids outside [-1, E) fail with MOIN_EINVAL before anything
+ * changes.  Not thread-safe.
+ */
+typedef struct moin_cache moin_cache;
+typedef enum {
+    MOIN_CACHE_BATCHES = 0,
+    MOIN_CACHE_SEQ_HITS = 1,   /* sequences whose expert was resident          */
+    MOIN_CACHE_SEQ_MISSES = 2, /* sequences whose expert was not               */
+    MOIN_CACHE_LOADS = 3,      /* experts copied in (per expert, not per stack) */
+    MOIN_CACHE_EVICTIONS = 4,
+    MOIN_CACHE_OVERFLOWS = 5,  /* experts left without a slot                  */
+    MOIN_CACHE_BYTES = 6,      /* host-to-device bytes enqueued                */
+    MOIN_CACHE_STAT_COUNT = 7
+} moin_cache_stat;
+int moin_cache_create(moin_cache **out, int32_t E, int32_t n_slots);
+void moin_cache_destroy(moin_cache *cache);
+int moin_cache_add_stack(moin_cache *cache, const void *A_host, const void *B_host,
+                         void *A_slots, void *B_slots, int64_t a_bytes_per_expert,
+                         int64_t b_bytes_per_expert);
+int moin_cache_admit(moin_cache *cache, const int32_t *expert_ids, int32_t S,
+                     int32_t *slot_ids, void *stream);
+/* Copies of the tables (HOST arrays, either may be NULL): slot_of_expert [E],
+ * expert_in_slot [n_slots]; -1 = not resident / free. */
+int moin_cache_table(const moin_cache *cache, int32_t *slot_of_expert,
+                     int32_t *expert_in_slot);
+/* stats [MOIN_CACHE_STAT_COUNT] (HOST array), totals since creation. */
+int moin_cache_stats(const moin_cache *cache, int64_t *stats);
+
 /* ---- per-kernel timing ----------------------------------------------------
  * When enabled, every kernel launch is bracketed by HIP events on the launch
  * stream.  moin_timing_read synchronises those events and returns, for one

@@ -4,6 +4,7 @@ Only tests, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 ``bench.py`` may import this package.  It shares no code with the HIP library.
 """
 from .oracle import (  # noqa: F401
+    AdapterCache,
     build,
     dist2,
     histogram,

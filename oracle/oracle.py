@@ -222,3 +222,70 @@ def lora_linear(x, seq_offsets, expert_ids, W, A_stack, B_stack, scale, rows=Non
         _ptr(B_stack), E, d_in, d_out, r, float(scale), _ptr(rows_arr), n_rows, _ptr(y),
         _ptr(work), slots), "lora_linear")
     return y
+
+
+class AdapterCache:
+    """Residency of adapters in a fixed number of GPU slots (Section 2, serving
+    paragraph: adapters live in CPU memory, the most frequently routed ones are
+    cached on the GPU).  Plain bookkeeping, one batch at a time:
+
+    * each sequence adds one use to its expert;
+    * an expert the batch needs is always brought in;
+    * a free slot is taken lowest index first, otherwise the resident expert that
+      the batch does not need with the fewest uses goes (then the one used
+      longest ago, then the lowest slot);
+    * with no such expert left the newcomer gets no slot (-1: base model only).
+    """
+
+    def __init__(self, n_experts, n_slots):
+        self.n_experts, self.n_slots = int(n_experts), int(n_slots)
+        self.slot_of = {}                      # expert -> slot
+        self.expert_in = [None] * self.n_slots
+        self.uses = {}
+        self.last = {}
+        self.batches = 0
+        self.hits = self.misses = self.loads = self.evictions = self.overflows = 0
+
+    def admit(self, expert_ids):
+        ids = [int(e) for e in expert_ids]
+        if any(e < -1 or e >= self.n_experts for e in ids):
+            raise ValueError("expert id out of range")
+        self.batches += 1
+        needed = []
+        for e in ids:
+            if e >= 0 and e not in needed:
+                needed.append(e)
+        for e in needed:
+            self.uses[e] = self.uses.get(e, 0) + ids.count(e)
+            self.last[e] = self.batches
+        loaded = []
+        for e in needed:
+            n = ids.count(e)
+            if e in self.slot_of:
+                self.hits += n
+                continue
+            self.misses += n
+            free = [s for s in range(self.n_slots) if self.expert_in[s] is None]
+            if free:
+                slot = free[0]
+            else:
+                cand = [s for s in range(self.n_slots) if self.expert_in[s] not in needed]
+                if not cand:
+                    self.overflows += 1
+                    continue
+                slot = min(cand, key=lambda s: (self.uses[self.expert_in[s]], self.last[self.expert_in[s]], s))
+                del self.slot_of[self.expert_in[slot]]
+                self.evictions += 1
+            self.expert_in[slot] = e
+            self.slot_of[e] = slot
+            self.loads += 1
+            loaded.append((e, slot))
+        slots = np.array([self.slot_of.get(e, -1) if e >= 0 else -1 for e in ids], dtype=np.int32)
+        return slots, loaded
+
+    def tables(self):
+        slot_of = np.full(self.n_experts, -1, dtype=np.int32)
+        for e, s in self.slot_of.items():
+            slot_of[e] = s
+        expert_in = np.array([-1 if e is None else e for e in self.expert_in], dtype=np.int32)
+        return slot_of, expert_in

@@ -29,7 +29,10 @@ EXPORTS = [
     "moin_lora_linear", "moin_plan_create", "moin_plan_destroy", "moin_plan_build",
     "moin_lora_linear_planned", "moin_timing_enable", "moin_timing_reset", "moin_timing_read",
     "moin_kmeans_update", "moin_retain_clusters", "moin_kmeans_fit",
+    "moin_cache_create", "moin_cache_destroy", "moin_cache_add_stack", "moin_cache_admit",
+    "moin_cache_table", "moin_cache_stats",
 ]
+CACHE_STATS = ["batches", "seq_hits", "seq_misses", "loads", "evictions", "overflows", "bytes"]
 
 _lib = None
 
@@ -72,11 +75,18 @@ def load() -> ctypes.CDLL:
     lib.moin_kmeans_update.argtypes = [vp, vp, vp, i64, vp, i32, i32, c.c_int, vp, c.c_int, vp, vp, vp]
     lib.moin_retain_clusters.argtypes = [vp, vp, i32, i32, vp, vp, vp]
     lib.moin_kmeans_fit.argtypes = [vp, vp, i64, vp, i32, i32, c.c_int, i32, vp, vp, vp, vp]
+    lib.moin_cache_create.argtypes = [c.POINTER(vp), i32, i32]
+    lib.moin_cache_destroy.argtypes = [vp]
+    lib.moin_cache_destroy.restype = None
+    lib.moin_cache_add_stack.argtypes = [vp, vp, vp, vp, vp, i64, i64]
+    lib.moin_cache_admit.argtypes = [vp, vp, i32, vp, vp]
+    lib.moin_cache_table.argtypes = [vp, vp, vp]
+    lib.moin_cache_stats.argtypes = [vp, vp]
     lib.moin_timing_enable.argtypes = [vp, c.c_int]
     lib.moin_timing_reset.argtypes = [vp]
     lib.moin_timing_read.argtypes = [vp, c.c_int, c.POINTER(c.c_double), c.POINTER(i64)]
     for name in EXPORTS:
-        if name not in ("moin_destroy", "moin_plan_destroy", "moin_strerror"):
+        if name not in ("moin_destroy", "moin_plan_destroy", "moin_strerror", "moin_cache_destroy"):
             getattr(lib, name).restype = c.c_int
     _lib = lib
     return lib
@@ -334,3 +344,66 @@ def moin_kmeans_fit(ctx: Context, emb: torch.Tensor, centroids: torch.Tensor, it
                                _dev_ptr(counts, "counts"), _dev_ptr(inertia, "inertia"), _stream_ptr(stream)),
         "moin_kmeans_fit")
     return ids, counts, inertia
+
+
+class Cache:
+    """Adapter residency cache: ``E`` experts in host memory, ``n_slots`` resident
+    on the GPU.  ``add_stack`` registers one projection (host stacks pinned,
+    slot stacks on the device); ``admit`` takes a batch's expert ids as a host
+    int32 tensor / array and returns the slot ids as a host int32 tensor."""
+
+    def __init__(self, E: int, n_slots: int):
+        self._h = ctypes.c_void_p()
+        _ck(load().moin_cache_create(ctypes.byref(self._h), int(E), int(n_slots)), "moin_cache_create")
+        self.E, self.n_slots = int(E), int(n_slots)
+        self._keep = []
+
+    def add_stack(self, A_host: torch.Tensor, B_host: torch.Tensor, A_slots: torch.Tensor, B_slots: torch.Tensor):
+        for t, name in ((A_host, "A_host"), (B_host, "B_host")):
+            if t.is_cuda or not t.is_contiguous() or t.shape[0] != self.E:
+                raise ValueError(f"{name}: contiguous host tensor with E leading entries expected")
+        for t, name in ((A_slots, "A_slots"), (B_slots, "B_slots")):
+            if not t.is_cuda or not t.is_contiguous() or t.shape[0] != self.n_slots:
+                raise ValueError(f"{name}: contiguous device tensor with n_slots leading entries expected")
+        if A_host.shape[1:] != A_slots.shape[1:] or B_host.shape[1:] != B_slots.shape[1:] \
+                or A_host.dtype != A_slots.dtype or B_host.dtype != B_slots.dtype:
+            raise ValueError("host and slot stacks must agree in per-expert shape and dtype")
+        a_bytes = A_host[0].numel() * A_host.element_size()
+        b_bytes = B_host[0].numel() * B_host.element_size()
+        _ck(load().moin_cache_add_stack(self._h, ctypes.c_void_p(A_host.data_ptr()), ctypes.c_void_p(B_host.data_ptr()),
+                                        ctypes.c_void_p(A_slots.data_ptr()), ctypes.c_void_p(B_slots.data_ptr()),
+                                        a_bytes, b_bytes), "moin_cache_add_stack")
+        self._keep.append((A_host, B_host, A_slots, B_slots))
+
+    def admit(self, expert_ids, stream=None) -> torch.Tensor:
+        ids = torch.as_tensor(expert_ids, dtype=torch.int32).contiguous()
+        if ids.is_cuda:
+            raise ValueError("expert_ids must be a host array (paging is decided on the host)")
+        slots = torch.empty_like(ids)
+        sp = _stream_ptr(stream) if self._keep else None
+        _ck(load().moin_cache_admit(self._h, ctypes.c_void_p(ids.data_ptr()), ids.numel(),
+                                    ctypes.c_void_p(slots.data_ptr()), sp), "moin_cache_admit")
+        return slots
+
+    def tables(self):
+        slot_of = torch.empty(self.E, dtype=torch.int32)
+        expert_in = torch.empty(self.n_slots, dtype=torch.int32)
+        _ck(load().moin_cache_table(self._h, ctypes.c_void_p(slot_of.data_ptr()),
+                                    ctypes.c_void_p(expert_in.data_ptr())), "moin_cache_table")
+        return slot_of, expert_in
+
+    def stats(self) -> dict:
+        buf = (ctypes.c_int64 * len(CACHE_STATS))()
+        _ck(load().moin_cache_stats(self._h, buf), "moin_cache_stats")
+        return dict(zip(CACHE_STATS, [int(v) for v in buf]))
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h:
+            load().moin_cache_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

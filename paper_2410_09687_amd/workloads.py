@@ -125,15 +125,16 @@ def zipf_probabilities(E: int, s: float) -> np.ndarray:
     return w / w.sum()
 
 
-def draw_expert_ids(S: int, E: int, dist: str, zipf_s: float, seed: int) -> np.ndarray:
+def draw_expert_ids(S: int, E: int, dist: str, zipf_s: float, seed: int, perm_seed=None) -> np.ndarray:
     """One expert id per sequence.  Zipf ranks are sent through a seeded
-    permutation so popular experts are not neighbours in memory."""
+    permutation so popular experts are not neighbours in memory; batches of one
+    request stream share ``perm_seed`` (the same experts stay popular)."""
     rng = np.random.default_rng(seed)
     if dist == "uniform":
         return rng.integers(0, E, size=S, dtype=np.int64).astype(np.int32)
     if dist == "zipf":
         ranks = rng.choice(E, size=S, p=zipf_probabilities(E, zipf_s))
-        perm = np.random.default_rng(seed ^ 0x5EED).permutation(E)
+        perm = np.random.default_rng((seed ^ 0x5EED) if perm_seed is None else perm_seed).permutation(E)
         return perm[ranks].astype(np.int32)
     raise ValueError(f"unknown id distribution {dist!r}")
 

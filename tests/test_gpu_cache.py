@@ -1,0 +1,92 @@
+"""The adapter residency cache end to end on the GPU: experts held in pinned
+host memory, a few slots on the device, batches served through the slot
+stacks.  Outputs must equal the oracle's on the full stacks (same bars as
+tests/test_gpu_linear.py) and, bit for bit, the GPU's own output on the full
+stacks; the slot tables must equal the oracle's bookkeeping."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2410_09687_amd import moin
+from paper_2410_09687_amd import workloads as wl
+from tests import gpu_common as gc
+
+pytestmark = pytest.mark.gpu
+
+
+def _stacks(E, r, d_in, d_out, seed):
+    A = wl._randn_bf16((E, r, d_in), d_in ** -0.5, torch.device("cpu"), seed).pin_memory()
+    B = wl._randn_bf16((E, d_out, r), r ** -0.5, torch.device("cpu"), seed + 1).pin_memory()
+    return A, B
+
+
+def test_batches_through_the_cache_match_full_stacks_and_the_oracle():
+    E, n_slots, r, d_in, d_out = 40, 6, 16, 128, 72
+    A_host, B_host = _stacks(E, r, d_in, d_out, 100)
+    A_full, B_full = A_host.cuda(), B_host.cuda()
+    A_slots = torch.zeros((n_slots, r, d_in), dtype=torch.bfloat16, device="cuda")
+    B_slots = torch.zeros((n_slots, d_out, r), dtype=torch.bfloat16, device="cuda")
+    W = wl._randn_bf16((d_out, d_in), d_in ** -0.5, torch.device("cuda"), 7)
+    cache = moin.Cache(E, n_slots)
+    cache.add_stack(A_host, B_host, A_slots, B_slots)
+    ref_cache = oracle.AdapterCache(E, n_slots)
+    rng = np.random.default_rng(5)
+    per_expert = (A_host[0].numel() + B_host[0].numel()) * 2
+    for b in range(12):
+        S = int(rng.integers(1, 9))          # 8 distinct experts can exceed the 6 slots: overflow -> base only
+        ids = (rng.zipf(1.4, size=S) % (E + 1) - 1).astype(np.int32)
+        lens = rng.integers(1, 40, size=S).tolist() if b % 2 else [1] * S   # decode-shaped and ragged batches
+        off = torch.from_numpy(wl.seq_offsets_of(lens)).cuda()
+        x = wl._randn_bf16((int(sum(lens)), d_in), 1.0, torch.device("cuda"), 200 + b)
+        print(f"[gpu] cache batch {b} ids {ids.tolist()}", flush=True)
+        slots = cache.admit(ids)
+        want_slots, _ = ref_cache.admit(ids)
+        assert np.array_equal(slots.numpy(), want_slots)
+        y = moin.moin_lora_linear(gc.ctx(), x, off, slots.cuda(), W, A_slots, B_slots, 2.0, y_dtype=torch.float32)
+        gc.ctx().check()
+        # an expert left without a slot runs base only: the reference gets -1 for it too
+        eff = np.where(slots.numpy() >= 0, ids, -1).astype(np.int32)
+        y_full = moin.moin_lora_linear(gc.ctx(), x, off, torch.from_numpy(eff).cuda(), W, A_full, B_full, 2.0,
+                                       y_dtype=torch.float32)
+        gc.ctx().check()
+        assert torch.equal(y, y_full), f"batch {b}: slot stacks and full stacks disagree"
+        ref = oracle.lora_linear(wl.bf16_bits(x), off.cpu().numpy(), eff, wl.bf16_bits(W), wl.bf16_bits(A_host),
+                                 wl.bf16_bits(B_host), 2.0)
+        gc.compare_linear(y, ref, what=f"cache batch {b}")
+    so, ei = cache.tables()
+    rso, rei = ref_cache.tables()
+    assert np.array_equal(so.numpy(), rso) and np.array_equal(ei.numpy(), rei)
+    st = cache.stats()
+    assert st["loads"] == ref_cache.loads and st["evictions"] == ref_cache.evictions
+    assert st["overflows"] == ref_cache.overflows and st["bytes"] == ref_cache.loads * per_expert
+    # what sits in the slots is what the tables say
+    torch.cuda.synchronize()
+    for s, e in enumerate(ei.tolist()):
+        if e >= 0:
+            assert torch.equal(A_slots[s].cpu(), A_host[e]) and torch.equal(B_slots[s].cpu(), B_host[e])
+    cache.close()
+
+
+def test_two_projections_share_one_residency():
+    E, n_slots = 12, 3
+    A1, B1 = _stacks(E, 8, 64, 64, 300)
+    A2, B2 = _stacks(E, 8, 64, 128, 310)
+    dev = lambda t: torch.zeros((n_slots,) + tuple(t.shape[1:]), dtype=t.dtype, device="cuda")
+    s1, s2 = (dev(A1), dev(B1)), (dev(A2), dev(B2))
+    cache = moin.Cache(E, n_slots)
+    cache.add_stack(A1, B1, *s1)
+    cache.add_stack(A2, B2, *s2)
+    for ids in ([3, 7], [7, 1, 1], [9], [3]):
+        cache.admit(np.asarray(ids, np.int32))
+    torch.cuda.synchronize()
+    _, ei = cache.tables()
+    for s, e in enumerate(ei.tolist()):
+        assert e >= 0
+        assert torch.equal(s1[0][s].cpu(), A1[e]) and torch.equal(s1[1][s].cpu(), B1[e])
+        assert torch.equal(s2[0][s].cpu(), A2[e]) and torch.equal(s2[1][s].cpu(), B2[e])
+    per = (A1[0].numel() + B1[0].numel() + A2[0].numel() + B2[0].numel()) * 2
+    assert cache.stats()["bytes"] == cache.stats()["loads"] * per
+    with pytest.raises(moin.MoinError):   # stacks are registered before the first batch
+        cache.add_stack(A1, B1, *s1)
+    cache.close()
