@@ -64,7 +64,7 @@ __device__ __forceinline__ void decode_shrink_slab(const ShrinkDParams &p, int s
     const int *__restrict__ n_groups = p.n_groups;
     const int d_in = p.d_in, r = p.r;
     const float scale = p.scale;
-    if (g >= uniform(*n_groups)) return;
+    (void)n_groups;   // records past the group count are empty
     const int4 gm = grp_meta[g];
     const int e = uniform(gm.x);
     if (e < 0) return;
@@ -205,8 +205,7 @@ template <int KS_HOLD, int NSPLIT>
 __global__ __launch_bounds__(EXPAND_WAVES * 64) void decode_expand_kernel(ExpandKParams p)
 {
     const int g = blockIdx.y;
-    if (g >= uniform(*p.n_groups)) return;
-    const int4 gm = p.grp_meta[g];
+    const int4 gm = p.grp_meta[g];   // records past the group count are empty
     const int e = uniform(gm.x);
     const int gs = uniform(gm.y), ge = uniform(gm.z);
     if (ge <= gs) return;
@@ -218,6 +217,22 @@ __global__ __launch_bounds__(EXPAND_WAVES * 64) void decode_expand_kernel(Expand
     const int64_t ldb = (int64_t)r * 2;
     const char *bexp = p.B_stack + (int64_t)(e < 0 ? 0 : e) * d_out * ldb;
     const bool lora = e >= 0 && r > 0;
+
+    // the wave's rows of B_e do not depend on the token block: requested first
+    // (they are the HBM traffic), held across blocks
+    constexpr int KH = KS_HOLD > 0 ? KS_HOLD : 1;
+    bf16x8_t a[EXPAND_RB][KH];
+    if constexpr (KS_HOLD > 0) {
+        if (lora) {
+#pragma unroll
+            for (int c = 0; c < EXPAND_RB; ++c) {
+                const int orow = o_base + c * 16 + (lane & 15);
+                const char *brow = bexp + (int64_t)(orow < d_out ? orow : 0) * ldb;
+#pragma unroll
+                for (int ks = 0; ks < KS_HOLD; ++ks) a[c][ks] = ldg_frag(brow, ks * 32 + kq, r);
+            }
+        }
+    }
 
     for (int t0 = gs; t0 < ge; t0 += 16) {
         const int pos = t0 + (lane & 15);
@@ -241,14 +256,6 @@ __global__ __launch_bounds__(EXPAND_WAVES * 64) void decode_expand_kernel(Expand
                     fh[ks] = ldg_frag(uh, ks * 32 + kq, r);
                     fl[ks] = ldg_frag(ul, ks * 32 + kq, r);
                 }
-                bf16x8_t a[EXPAND_RB][KS_HOLD];
-#pragma unroll
-                for (int c = 0; c < EXPAND_RB; ++c) {
-                    const int orow = o_base + c * 16 + (lane & 15);
-                    const char *brow = bexp + (int64_t)(orow < d_out ? orow : 0) * ldb;
-#pragma unroll
-                    for (int ks = 0; ks < KS_HOLD; ++ks) a[c][ks] = ldg_frag(brow, ks * 32 + kq, r);
-                }
 #pragma unroll
                 for (int c = 0; c < EXPAND_RB; ++c)
 #pragma unroll
@@ -264,11 +271,11 @@ __global__ __launch_bounds__(EXPAND_WAVES * 64) void decode_expand_kernel(Expand
                     const char *brow = bexp + (int64_t)(orow < d_out ? orow : 0) * ldb;
                     for (int ks = 0; ks < nks; ++ks) {
                         const int k = ks * 32 + kq;
-                        const bf16x8_t a = ldg_frag(brow, k, r);
+                        const bf16x8_t ab = ldg_frag(brow, k, r);
                         const bf16x8_t bh = ldg_frag(uh, k, r);
                         const bf16x8_t bl = ldg_frag(ul, k, r);
-                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bh, acc[c], 0, 0, 0);
-                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bl, acc[c], 0, 0, 0);
+                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bh, acc[c], 0, 0, 0);
+                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bl, acc[c], 0, 0, 0);
                     }
                 }
             }
