@@ -11,10 +11,12 @@
 
 namespace moin {
 
-constexpr int PLAN_THREADS = 1024;
+constexpr int PLAN_THREADS_MAX = 1024;   // large batches
+constexpr int PLAN_THREADS_SMALL = 256;  // up to 512 sequences: four waves meet at a barrier much faster than sixteen
 constexpr int PLAN_LDS_S = 2048;
 
 // In-place exclusive prefix sum of data[0..n) by one workgroup; returns the total.
+template <int PLAN_THREADS>
 __device__ int block_exclusive_scan(int *data, int n, int *lds /* PLAN_THREADS + 1 ints */)
 {
     const int tid = threadIdx.x;
@@ -43,6 +45,7 @@ __device__ int block_exclusive_scan(int *data, int n, int *lds /* PLAN_THREADS +
     return total;
 }
 
+template <int PLAN_THREADS>
 __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const int *seq_offsets,
                                                             const int *expert_ids, int *err_word)
 {
@@ -144,12 +147,12 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
         a3[p] = head ? 1 : 0;
     }
     __syncthreads();
-    const int n_tiles = block_exclusive_scan(a1, S, lds);
+    const int n_tiles = block_exclusive_scan<PLAN_THREADS>(a1, S, lds);
     if (tid == 0) *pv.n_tiles = min(n_tiles, pv.max_tiles);
     int n_groups = 0;
     if (pv.decode) {
-        const int n_tok = block_exclusive_scan(a2, S, lds);
-        n_groups = block_exclusive_scan(a3, S, lds);   // a3[p] = groups before p
+        const int n_tok = block_exclusive_scan<PLAN_THREADS>(a2, S, lds);
+        n_groups = block_exclusive_scan<PLAN_THREADS>(a3, S, lds);   // a3[p] = groups before p
         if (tid == 0) {
             *pv.n_groups = n_groups;
             pv.grp_start[n_groups] = min(n_tok, T);
@@ -197,8 +200,12 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
 hipError_t launch_plan(const PlanView &pv, const int *seq_offsets, const int *expert_ids,
                        int *err_word, hipStream_t stream)
 {
-    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, stream, pv, seq_offsets,
-                       expert_ids, err_word);
+    if (pv.S <= 2 * PLAN_THREADS_SMALL)
+        hipLaunchKernelGGL(plan_kernel<PLAN_THREADS_SMALL>, dim3(1), dim3(PLAN_THREADS_SMALL), 0, stream, pv,
+                           seq_offsets, expert_ids, err_word);
+    else
+        hipLaunchKernelGGL(plan_kernel<PLAN_THREADS_MAX>, dim3(1), dim3(PLAN_THREADS_MAX), 0, stream, pv,
+                           seq_offsets, expert_ids, err_word);
     return hipGetLastError();
 }
 
