@@ -91,12 +91,12 @@ __device__ __forceinline__ void decode_shrink_slab(const ShrinkDParams &p, int s
         const char *xrow = x + (int64_t)tok_sorted[tvalid ? pos : gs] * ld;
         for (int ks0 = ks_beg; ks0 < ks_end; ks0 += UNR) {
             bf16x8_t a[UNR], b[UNR];
+            // A_e first: its address needs the group record only, the x rows also the
+            // token list -- the HBM requests must not queue behind that round trip
 #pragma unroll
-            for (int u = 0; u < UNR; ++u) {
-                const int k = (ks0 + u) * 32 + kq;   // past the wave's range: zero
-                a[u] = ldg_frag(arow, k, klen);
-                b[u] = ldg_frag(xrow, k, klen);
-            }
+            for (int u = 0; u < UNR; ++u) a[u] = ldg_frag(arow, (ks0 + u) * 32 + kq, klen);   // past the wave's range: zero
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) b[u] = ldg_frag(xrow, (ks0 + u) * 32 + kq, klen);
 #pragma unroll
             for (int u = 0; u < UNR; ++u)
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b[u], acc, 0, 0, 0);
