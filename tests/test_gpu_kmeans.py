@@ -205,3 +205,15 @@ def test_lloyd_loop_bf16_descends_and_is_consistent():
     assert np.array_equal(counts.cpu().numpy(), np.bincount(ids.cpu().numpy(), minlength=K))
     ref = oracle.kmeans_update(_host(emb), ids.cpu().numpy(), _host(cent))
     assert abs(gi[-1] - ref[2]) <= 2e-6 * ref[2]
+
+
+def test_launch_shape_limits():
+    # K = 1 (no id bits to match), fewer points than one batch of 64
+    emb, ids, cent = _inputs(37, 1, 8, torch.bfloat16, 20)
+    _check_update(emb, ids, cent, "K=1", out_dtypes=(torch.float32,))
+    # the largest K the cursor table in LDS holds (128 KB), most clusters empty
+    emb, ids, cent = _inputs(3000, 32768, 8, torch.bfloat16, 21)
+    _check_update(emb, ids, cent, "K=32768", out_dtypes=(torch.float32,))
+    # more than 1024 chunks of 4096 points: the chunk grows instead (4 400 000 points -> chunks of 4352)
+    emb, ids, cent = _inputs(4_400_000, 300, 8, torch.bfloat16, 22)
+    _check_update(emb, ids, cent, "many chunks", out_dtypes=(torch.float32,))
