@@ -177,6 +177,10 @@ int moin_oracle_histogram(const int32_t *ids, int64_t N, int32_t K,
  *     u_j    = sum_i A[e,j,i] x[t,i]           (e >= 0 only)
  *     y[t,o] = base_o + scale * sum_j B[e,o,j] u_j
  * and y[t,o] = base_o when e == -1.  u is never rounded.
+ * rank_of_expert (may be NULL): "Future Works", adaptive rank per topic -- expert
+ * e uses only its first rank_of_expert[e] rows of A[e] and columns of B[e]
+ * (0 <= rank <= r); the stacks keep their [E, r, ...] shape and whatever lies
+ * beyond an expert's rank is never read.
  * x, W, A_stack, B_stack hold bf16 bit patterns; y is fp64, n_rows x d_out.
  * work: caller-provided temporaries, work_slots * (d_in + r) doubles; each
  * OpenMP thread (at most work_slots of them) keeps its widened token and its
@@ -187,6 +191,7 @@ int moin_oracle_lora_linear(const uint16_t *x, const int32_t *seq_offsets,
                             const uint16_t *W, const uint16_t *A_stack,
                             const uint16_t *B_stack, int32_t E, int32_t d_in,
                             int32_t d_out, int32_t r, double scale,
+                            const int32_t *rank_of_expert,
                             const int64_t *rows, int64_t n_rows, double *y,
                             double *work, int32_t work_slots)
 {
@@ -202,6 +207,9 @@ int moin_oracle_lora_linear(const uint16_t *x, const int32_t *seq_offsets,
         if (seq_offsets[s + 1] < seq_offsets[s]) return ORACLE_EINVAL;
         if (expert_ids[s] < -1 || expert_ids[s] >= E) return ORACLE_EINVAL;
         if (expert_ids[s] >= 0 && (!A_stack || !B_stack)) return ORACLE_EINVAL;
+        if (expert_ids[s] >= 0 && rank_of_expert &&
+            (rank_of_expert[expert_ids[s]] < 0 || rank_of_expert[expert_ids[s]] > r))
+            return ORACLE_EINVAL;
     }
     int bad = 0;
 #pragma omp parallel for schedule(dynamic, 1) num_threads(work_slots)
@@ -225,9 +233,10 @@ int moin_oracle_lora_linear(const uint16_t *x, const int32_t *seq_offsets,
         double *u = xt + d_in;
         for (int32_t i = 0; i < d_in; ++i)
             xt[i] = bf16_to_f64(x[(size_t)t * d_in + i]);
+        const int32_t re = (e >= 0 && rank_of_expert) ? rank_of_expert[e] : r;
         if (e >= 0) {
             const uint16_t *A = A_stack + (size_t)e * r * d_in;
-            for (int32_t j = 0; j < r; ++j) {
+            for (int32_t j = 0; j < re; ++j) {
                 double acc = 0.0;
                 for (int32_t i = 0; i < d_in; ++i)
                     acc += bf16_to_f64(A[(size_t)j * d_in + i]) * xt[i];
@@ -242,7 +251,7 @@ int moin_oracle_lora_linear(const uint16_t *x, const int32_t *seq_offsets,
             if (e >= 0) {
                 const uint16_t *B = B_stack + (size_t)e * d_out * r;
                 double lora = 0.0;
-                for (int32_t j = 0; j < r; ++j)
+                for (int32_t j = 0; j < re; ++j)
                     lora += bf16_to_f64(B[(size_t)o * r + j]) * u[j];
                 out = base + scale * lora;
             }

@@ -46,7 +46,7 @@ def _load():
         lib.moin_oracle_lora_linear.argtypes = [
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int64,
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
-            c.c_double, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_int32]
+            c.c_double, c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_int32]
         lib.moin_oracle_kmeans_update.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p,
                                                   c.c_int32, c.c_int32, c.c_int, c.c_void_p,
                                                   c.c_void_p, c.c_void_p]
@@ -177,12 +177,14 @@ def retain_clusters(counts, min_count):
 
 
 def lora_linear(x, seq_offsets, expert_ids, W, A_stack, B_stack, scale, rows=None,
-                threads=None):
+                threads=None, rank_of_expert=None):
     """y = x W^T + scale * (x A_e^T) B_e^T with one expert per sequence (fp64).
 
     ``x [T,d_in]``, ``W [d_out,d_in]``, ``A_stack [E,r,d_in]``, ``B_stack
     [E,d_out,r]`` are uint16 bf16 bit patterns.  ``rows`` selects the tokens to
     compute (default all); the result is ``[len(rows), d_out]`` float64.
+    ``rank_of_expert [E]`` (optional): expert e uses only its first
+    ``rank_of_expert[e]`` rows of A_e / columns of B_e.
     """
     x = np.ascontiguousarray(x)
     W = np.ascontiguousarray(W)
@@ -214,12 +216,17 @@ def lora_linear(x, seq_offsets, expert_ids, W, A_stack, B_stack, scale, rows=Non
     else:
         rows_arr = np.ascontiguousarray(rows, dtype=np.int64)
         n_rows = rows_arr.size
+    ranks = None
+    if rank_of_expert is not None:
+        ranks = np.ascontiguousarray(rank_of_expert, dtype=np.int32)
+        if ranks.shape != (E,):
+            raise ValueError("rank_of_expert must have E entries")
     y = np.zeros((n_rows, d_out), dtype=np.float64)
     slots = int(threads) if threads else max_threads()
     work = np.zeros(slots * (d_in + max(r, 1)), dtype=np.float64)
     _check(_load().moin_oracle_lora_linear(
         _ptr(x), _ptr(seq_offsets), _ptr(expert_ids), S, T, _ptr(W), _ptr(A_stack),
-        _ptr(B_stack), E, d_in, d_out, r, float(scale), _ptr(rows_arr), n_rows, _ptr(y),
+        _ptr(B_stack), E, d_in, d_out, r, float(scale), _ptr(ranks), _ptr(rows_arr), n_rows, _ptr(y),
         _ptr(work), slots), "lora_linear")
     return y
 

@@ -186,3 +186,46 @@ def test_empty_and_invalid_inputs():
         oracle.lora_linear(x, np.array([0, 3, 2], dtype=np.int32), ids, W, A, B, 2.0)  # not monotone / end != T
     with pytest.raises(ValueError):
         oracle.lora_linear(x, off, np.array([0, -2], dtype=np.int32), W, A, B, 2.0)
+
+
+def test_adaptive_rank_per_expert():
+    """"Future Works" (adaptive rank per topic): expert e uses its first rank_e rows of
+    A_e and columns of B_e.  Pinned against numpy fp64 on truncated copies, against the
+    padded-with-zeros equivalence, and against the limits rank = r and rank = 0."""
+    rng = np.random.default_rng(21)
+    d_in, d_out, r, E = 24, 16, 8, 4
+    lens = [3, 2, 4, 1, 2]
+    ids = np.array([2, 0, 3, 1, 2], np.int32)
+    ranks = np.array([8, 0, 3, 5], np.int32)
+    T = sum(lens)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    x = to_bf16_bits(rng.standard_normal((T, d_in)))
+    W = to_bf16_bits(rng.standard_normal((d_out, d_in)) * 0.2)
+    A = to_bf16_bits(rng.standard_normal((E, r, d_in)) * 0.2)
+    B = to_bf16_bits(rng.standard_normal((E, d_out, r)) * 0.3)
+    got = oracle.lora_linear(x, off, ids, W, A, B, 2.0, rank_of_expert=ranks)
+    # numpy fp64 on explicitly truncated factors, token by token
+    xs, Ws, As, Bs = bits_to_f64(x), bits_to_f64(W), bits_to_f64(A), bits_to_f64(B)
+    want = np.zeros((T, d_out))
+    for s, e in enumerate(ids):
+        k = ranks[e]
+        for t in range(off[s], off[s + 1]):
+            want[t] = Ws @ xs[t] + 2.0 * (Bs[e][:, :k] @ (As[e][:k] @ xs[t]))
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
+    # same as full rank on stacks whose tail is zeroed; what lies in the tail is never read
+    Az, Bz = A.copy(), B.copy()
+    An, Bn = A.copy(), B.copy()
+    for e in range(E):
+        Az[e, ranks[e]:] = 0
+        Bz[e][:, ranks[e]:] = 0
+        An[e, ranks[e]:] = 0x7FC0          # bf16 NaN
+        Bn[e][:, ranks[e]:] = 0x7FC0
+    assert np.array_equal(got, oracle.lora_linear(x, off, ids, W, Az, Bz, 2.0))
+    assert np.array_equal(got, oracle.lora_linear(x, off, ids, W, An, Bn, 2.0, rank_of_expert=ranks))
+    # limits: all ranks = r is the plain layer; all ranks = 0 is the base layer
+    full = oracle.lora_linear(x, off, ids, W, A, B, 2.0)
+    assert np.array_equal(full, oracle.lora_linear(x, off, ids, W, A, B, 2.0, rank_of_expert=np.full(E, r)))
+    base = oracle.lora_linear(x, off, np.full(len(ids), -1, np.int32), W, A, B, 2.0)
+    assert np.array_equal(base, oracle.lora_linear(x, off, ids, W, A, B, 2.0, rank_of_expert=np.zeros(E, np.int32)))
+    with pytest.raises(ValueError):
+        oracle.lora_linear(x, off, ids, W, A, B, 2.0, rank_of_expert=np.array([9, 0, 0, 0]))
