@@ -229,6 +229,46 @@ def bench_kmeans(ctx, steps, warmup):
             "kernels": kt}
 
 
+def bench_ranks(ctx, steps, warmup, n_draws=8):
+    """configs[2] gate projection with a rank per expert ("Future Works": larger adapters
+    for bigger topics): the 10 % most popular experts keep rank 128, the next 30 % get 64,
+    the rest 32.  The decode kernels read only rank_e rows / columns of each distinct
+    adapter; algorithmic bytes shrink accordingly."""
+    w = wl.config_decode()[0]
+    inp = wl.make_linear_inputs(w, "cuda")
+    perm = np.random.default_rng(777).permutation(w.E)          # popularity order of this stream
+    ranks = np.full(w.E, 32, np.int32)
+    ranks[perm[: w.E * 4 // 10]] = 64
+    ranks[perm[: w.E // 10]] = 128
+    ranks_dev = torch.from_numpy(ranks).cuda()
+    out = {}
+    for label, rk in (("full_rank", None), ("adaptive_rank", ranks_dev)):
+        plans, bytes_alg = [], []
+        for k in range(n_draws):
+            ids = wl.draw_expert_ids(w.S, w.E, "zipf", w.zipf_s, 9000 + k, perm_seed=777)
+            plans.append(moin.Plan(ctx).build(inp.seq_offsets, torch.from_numpy(ids).cuda(), w.T, w.E,
+                                              rank_of_expert=rk))
+            per = np.array([w.r if rk is None else ranks[e] for e in np.unique(ids)], np.float64)
+            bytes_alg.append(2.0 * w.d_in * w.d_out + per.sum() * 2.0 * (w.d_in + w.d_out)
+                             + 2.0 * w.T * (w.d_in + w.d_out))
+        y = torch.empty((w.T, w.d_out), dtype=torch.bfloat16, device="cuda")
+        state = {"i": 0}
+
+        def step():
+            k = state["i"] % n_draws
+            state["i"] += 1
+            moin.moin_lora_linear_planned(ctx, plans[k], inp.x, inp.W, inp.A_stack, inp.B_stack, w.scale, out=y)
+
+        n = max(steps, n_draws) // n_draws * n_draws
+        ms, _ = timed_region(step, n, max(warmup, n_draws))
+        ctx.check()
+        avg = float(np.mean(bytes_alg))
+        out[label] = {"ms_per_call": ms, "algorithmic_bytes": avg, "GBps": avg / (ms * 1e-3) / 1e9}
+        for p in plans:
+            p.close()
+    return out
+
+
 def bench_cache(ctx, n_batches=48, n_slots=512):
     """Decode batches of the gate projection (configs[2] shapes) served through the adapter
     residency cache: 5000 experts in pinned host memory, `n_slots` resident, one request
@@ -325,8 +365,8 @@ def main():
                     help="first run a plain device copy of this many MiB (3 times): the known-size "
                          "kernel that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--also", default="decode,router,layer,kmeans",
-                    help="comma list of extra workloads to report: decode,router,layer,kmeans,cache "
-                         "(or 'none'); cache is not in the default list (it pins 10 GB of host memory)")
+                    help="comma list of extra workloads to report: decode,router,layer,kmeans,cache,ranks "
+                         "(or 'none'); cache (it pins 10 GB of host memory) and ranks are not in the default list")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU figure exists)",
@@ -356,6 +396,8 @@ def main():
         res["kmeans"] = bench_kmeans(ctx, max(5, args.steps // 5), 2)
     if "cache" in extra:
         res["cache"] = bench_cache(ctx)
+    if "ranks" in extra:
+        res["ranks"] = bench_ranks(ctx, args.steps, args.warmup)
     ctx.close()
     print(json.dumps(res))
 

@@ -142,6 +142,25 @@ int moin_lora_linear(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
                      int32_t E, int32_t d_in, int32_t d_out, int32_t r,
                      float scale, void *y, moin_dtype y_dt, void *stream);
 
+/* "Future Works", adaptive rank per topic (also Section 4.2: the rank could follow
+ * the amount of training data): the same layer with a rank per expert.
+ * rank_of_expert [E] int32 (DEVICE) or NULL; expert e uses the first
+ * rank_of_expert[e] rows of A_stack[e] and columns of B_stack[e], 0 <= rank <= r,
+ * a multiple of 8 (rank 0: base model only).  The stacks keep their [E, r, ...]
+ * shape.  What lies beyond an expert's rank is not used: rows of A_e beyond it are
+ * never read; columns of B_e from the rank up to the next multiple of 64 are
+ * multiplied by zeros on the prefill path and must therefore be finite (zero
+ * padding is the natural choice), further columns are never read.  The decode
+ * path reads only rank_e rows / columns of every distinct adapter.  A rank that
+ * is negative or not a multiple of 8 raises the sticky data fault (it is rounded
+ * down; negative: full rank); a rank above r counts as r. */
+int moin_lora_linear_ranked(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
+                            const int32_t *expert_ids, int32_t S, int64_t T,
+                            const void *W, const void *A_stack, const void *B_stack,
+                            int32_t E, int32_t d_in, int32_t d_out, int32_t r,
+                            const int32_t *rank_of_expert, float scale, void *y,
+                            moin_dtype y_dt, void *stream);
+
 /* The grouping of sequences by expert depends only on (seq_offsets,
  * expert_ids, E); a plan computes it once for all projections of a layer
  * (Section 3.2: every linear layer carries an adapter).
@@ -152,6 +171,11 @@ void moin_plan_destroy(moin_plan *plan);
 int moin_plan_build(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
                     const int32_t *expert_ids, int32_t S, int64_t T, int32_t E,
                     void *stream);
+/* moin_plan_build with per-expert ranks (see moin_lora_linear_ranked); the ranks are
+ * resolved into the plan, rank_of_expert need not outlive the call's completion. */
+int moin_plan_build_ranked(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
+                           const int32_t *expert_ids, int32_t S, int64_t T, int32_t E,
+                           const int32_t *rank_of_expert, void *stream);
 int moin_lora_linear_planned(moin_ctx *ctx, const moin_plan *plan, const void *x,
                              const void *W, const void *A_stack,
                              const void *B_stack, int32_t d_in, int32_t d_out,

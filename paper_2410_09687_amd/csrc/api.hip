@@ -147,7 +147,7 @@ int drain_spans(moin_ctx *ctx)
 }
 
 struct PlanLayout {
-    size_t tile_row0, tile_rows, tile_expert, n_tiles, tok_sorted, grp_meta,
+    size_t tile_row0, tile_rows, tile_expert, tile_rank, n_tiles, tok_sorted, grp_meta,
         grp_start, n_groups, keys, tmp, total;
     int max_tiles, max_groups, decode;
 };
@@ -170,6 +170,7 @@ PlanLayout plan_layout(int32_t S, int64_t T)
     L.tile_row0 = take((size_t)L.max_tiles * 4);
     L.tile_rows = take((size_t)L.max_tiles * 4);
     L.tile_expert = take((size_t)L.max_tiles * 4);
+    L.tile_rank = take((size_t)L.max_tiles * 4);
     L.n_tiles = take(4);
     L.tok_sorted = take(L.decode ? (size_t)T * 4 : 4);
     L.grp_meta = take((size_t)(L.max_groups + 1) * 16);
@@ -181,7 +182,8 @@ PlanLayout plan_layout(int32_t S, int64_t T)
 }
 
 int plan_build_impl(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
-                    const int32_t *expert_ids, int32_t S, int64_t T, int32_t E, hipStream_t stream)
+                    const int32_t *expert_ids, int32_t S, int64_t T, int32_t E,
+                    const int32_t *rank_of_expert, hipStream_t stream)
 {
     if (S < 0 || T < 0 || E < 0 || T > 0x7fffffffLL - TILE_M) return MOIN_EINVAL;
     plan->built = 0;
@@ -213,6 +215,7 @@ int plan_build_impl(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
     pv.tile_row0 = reinterpret_cast<int *>(b + L.tile_row0);
     pv.tile_rows = reinterpret_cast<int *>(b + L.tile_rows);
     pv.tile_expert = reinterpret_cast<int *>(b + L.tile_expert);
+    pv.tile_rank = reinterpret_cast<int *>(b + L.tile_rank);
     pv.n_tiles = reinterpret_cast<int *>(b + L.n_tiles);
     pv.tok_sorted = reinterpret_cast<int *>(b + L.tok_sorted);
     pv.grp_meta = reinterpret_cast<int4 *>(b + L.grp_meta);
@@ -223,7 +226,7 @@ int plan_build_impl(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
     pv.max_groups = L.max_groups;
     pv.decode = L.decode;
     const hipError_t e = timed(ctx, MOIN_K_PLAN, stream, [&] {
-        return launch_plan(pv, seq_offsets, expert_ids, ctx->err_word, stream);
+        return launch_plan(pv, seq_offsets, expert_ids, rank_of_expert, ctx->err_word, stream);
     });
     if (e != hipSuccess) return MOIN_EHIP;
     plan->built = 1;
@@ -382,7 +385,7 @@ const char *moin_strerror(int code)
     case MOIN_EINVAL: return "invalid argument (null pointer, bad size, unsupported shape or alignment)";
     case MOIN_ENOMEM: return "workspace allocation failed";
     case MOIN_EHIP: return "HIP runtime call failed";
-    case MOIN_EDATA: return "device-side data fault (expert id out of range, bad offsets or ids)";
+    case MOIN_EDATA: return "device-side data fault (expert id or rank out of range, bad offsets or ids)";
     default: return "unknown moin status";
     }
 }
@@ -503,13 +506,21 @@ void moin_plan_destroy(moin_plan *plan)
     delete plan;
 }
 
-int moin_plan_build(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
-                    const int32_t *expert_ids, int32_t S, int64_t T, int32_t E, void *stream)
+int moin_plan_build_ranked(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
+                           const int32_t *expert_ids, int32_t S, int64_t T, int32_t E,
+                           const int32_t *rank_of_expert, void *stream)
 {
     if (!ctx || !plan || plan->device != ctx->device) return MOIN_EINVAL;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return MOIN_EHIP;
-    return plan_build_impl(ctx, plan, seq_offsets, expert_ids, S, T, E, static_cast<hipStream_t>(stream));
+    return plan_build_impl(ctx, plan, seq_offsets, expert_ids, S, T, E, rank_of_expert,
+                           static_cast<hipStream_t>(stream));
+}
+
+int moin_plan_build(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
+                    const int32_t *expert_ids, int32_t S, int64_t T, int32_t E, void *stream)
+{
+    return moin_plan_build_ranked(ctx, plan, seq_offsets, expert_ids, S, T, E, nullptr, stream);
 }
 
 int moin_lora_linear_planned(moin_ctx *ctx, const moin_plan *plan, const void *x, const void *W,
@@ -523,10 +534,11 @@ int moin_lora_linear_planned(moin_ctx *ctx, const moin_plan *plan, const void *x
                                static_cast<hipStream_t>(stream));
 }
 
-int moin_lora_linear(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
-                     const int32_t *expert_ids, int32_t S, int64_t T, const void *W,
-                     const void *A_stack, const void *B_stack, int32_t E, int32_t d_in,
-                     int32_t d_out, int32_t r, float scale, void *y, moin_dtype y_dt, void *stream)
+int moin_lora_linear_ranked(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
+                            const int32_t *expert_ids, int32_t S, int64_t T, const void *W,
+                            const void *A_stack, const void *B_stack, int32_t E, int32_t d_in,
+                            int32_t d_out, int32_t r, const int32_t *rank_of_expert, float scale,
+                            void *y, moin_dtype y_dt, void *stream)
 {
     if (!ctx) return MOIN_EINVAL;
     DeviceGuard guard(ctx->device);
@@ -541,10 +553,19 @@ int moin_lora_linear(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
         const int vrc = validate_linear(x, W, A_stack, B_stack, E, d_in, d_out, r, scale, y, y_dt);
         if (vrc != MOIN_OK) return vrc;
     }
-    int rc = plan_build_impl(ctx, ctx->own_plan, seq_offsets, expert_ids, S, T, E, st);
+    int rc = plan_build_impl(ctx, ctx->own_plan, seq_offsets, expert_ids, S, T, E, rank_of_expert, st);
     if (rc != MOIN_OK) return rc;
     return linear_planned_impl(ctx, ctx->own_plan, x, W, A_stack, B_stack, d_in, d_out, r, scale, y,
                                y_dt, st);
+}
+
+int moin_lora_linear(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
+                     const int32_t *expert_ids, int32_t S, int64_t T, const void *W,
+                     const void *A_stack, const void *B_stack, int32_t E, int32_t d_in,
+                     int32_t d_out, int32_t r, float scale, void *y, moin_dtype y_dt, void *stream)
+{
+    return moin_lora_linear_ranked(ctx, x, seq_offsets, expert_ids, S, T, W, A_stack, B_stack, E, d_in,
+                                   d_out, r, nullptr, scale, y, y_dt, stream);
 }
 
 int moin_kmeans_update(moin_ctx *ctx, const void *emb, const int32_t *ids, int64_t N,

@@ -62,7 +62,7 @@ __device__ __forceinline__ void decode_shrink_slab(const ShrinkDParams &p, int s
     const int *__restrict__ tok_sorted = p.tok_sorted;
     const int4 *__restrict__ grp_meta = p.grp_meta;
     const int *__restrict__ n_groups = p.n_groups;
-    const int d_in = p.d_in, r = p.r;
+    const int d_in = p.d_in;
     const float scale = p.scale;
     (void)n_groups;   // records past the group count are empty
     const int4 gm = grp_meta[g];
@@ -70,12 +70,17 @@ __device__ __forceinline__ void decode_shrink_slab(const ShrinkDParams &p, int s
     if (e < 0) return;
     const int gs = uniform(gm.y), ge = uniform(gm.z);
     if (ge <= gs) return;
+    // the expert's own rank (a multiple of 8): slabs beyond it are never read, u is
+    // stored [pos, p.r] and only its first r columns are written and later read
+    const int r = min(p.r, uniform(gm.w));
+    const int ldr = p.r;
+    if (slab * 16 >= r) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int j0 = slab * 16;
     const int jrow = j0 + (lane & 15);
     const int kq = (lane >> 4) * 8;               // element offset of this lane's k-group
     const int64_t ld = (int64_t)d_in * 2;
-    const char *arow = A_stack + ((int64_t)e * r + (jrow < r ? jrow : 0)) * ld;
+    const char *arow = A_stack + ((int64_t)e * ldr + (jrow < r ? jrow : 0)) * ld;
     // each wave owns a contiguous run of k-steps: its 16 rows are read as 16
     // contiguous segments
     const int nks = (d_in + 31) / 32;
@@ -119,7 +124,7 @@ __device__ __forceinline__ void decode_shrink_slab(const ShrinkDParams &p, int s
             }
             const int jj = j0 + 4 * (lane >> 4);
             if (tvalid && jj < r) {   // r % 8 == 0, so a group of 4 is all in or all out
-                const int64_t off = ((int64_t)pos * r + jj) * 2;
+                const int64_t off = ((int64_t)pos * ldr + jj) * 2;
                 *reinterpret_cast<uint2 *>(ug_hi + off) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
                 *reinterpret_cast<uint2 *>(ug_lo + off) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
             }
@@ -213,8 +218,11 @@ __global__ __launch_bounds__(EXPAND_WAVES * 64) void decode_expand_kernel(Expand
     const int o_base = (blockIdx.x * EXPAND_WAVES + wave) * (EXPAND_RB * 16);
     if (o_base >= p.d_out) return;
     const int kq = (lane >> 4) * 8;
-    const int r = p.r, d_out = p.d_out;
-    const int64_t ldb = (int64_t)r * 2;
+    const int d_out = p.d_out;
+    // rows of B_e and u are p.r long; the expert's own rank r (a multiple of 8) says how
+    // much of them exists -- fragments past it are zero-filled, not read
+    const int r = min(p.r, uniform(gm.w));
+    const int64_t ldb = (int64_t)p.r * 2;
     const char *bexp = p.B_stack + (int64_t)(e < 0 ? 0 : e) * d_out * ldb;
     const bool lora = e >= 0 && r > 0;
 

@@ -14,6 +14,8 @@ constexpr int DECODE_MAX_T = 1024; // batches up to this many tokens take the de
 constexpr int ERR_BAD_EXPERT = 1;
 constexpr int ERR_BAD_OFFSETS = 2;
 constexpr int ERR_BAD_ID = 4;
+constexpr int ERR_BAD_RANK = 8;    // a per-expert rank that is negative or not a multiple of 8
+constexpr int RANK_FULL = 0x7fffffff;   // "no per-expert rank": kernels take min(r, rank)
 
 // Device-resident result of grouping a batch by expert.
 struct PlanView {
@@ -21,10 +23,11 @@ struct PlanView {
     int *tile_row0;    // [max_tiles] first token of the tile
     int *tile_rows;    // [max_tiles] 1..TILE_M valid rows
     int *tile_expert;  // [max_tiles] adapter slot or -1
+    int *tile_rank;    // [max_tiles] rank of that adapter (RANK_FULL without a rank table, 0 for slot -1)
     int *n_tiles;      // [1]
     // decode grouping (built only when T <= DECODE_MAX_T)
     int *tok_sorted;   // [T] token index, grouped by expert
-    int4 *grp_meta;    // [max_groups] {adapter slot or -1, first, one-past-last position in tok_sorted, 0}
+    int4 *grp_meta;    // [max_groups] {adapter slot or -1, first, one-past-last position in tok_sorted, rank}
     int *grp_start;    // [max_groups + 1] scratch while building
     int *n_groups;     // [1]
     // scratch used while building
@@ -38,8 +41,9 @@ struct PlanView {
     int decode;  // grouping arrays valid
 };
 
+// rank_of_expert: [E] or null (every adapter at the stacks' full rank)
 hipError_t launch_plan(const PlanView &pv, const int *seq_offsets, const int *expert_ids,
-                       int *err_word, hipStream_t stream);
+                       const int *rank_of_expert, int *err_word, hipStream_t stream);
 
 struct LinearArgs {
     const void *x, *W, *A_stack, *B_stack;

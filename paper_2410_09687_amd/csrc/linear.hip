@@ -20,7 +20,7 @@ namespace moin {
 struct ShrinkKParams {
     const char *x, *A_stack;
     char *u_hi, *u_lo;
-    const int *tile_row0, *tile_rows, *tile_expert, *n_tiles;
+    const int *tile_row0, *tile_rows, *tile_expert, *tile_rank, *n_tiles;
     int d_in, r;
     int n_tiles_n;
     float scale;
@@ -44,7 +44,13 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
     rows = min(rows, C::BM);
     const int row0 = uniform(p.tile_row0[t]) + sub * C::BM;
     const int n0 = tn * C::BN;
-    const int ncols = min(C::BN, p.r - n0);
+    // the expert's own rank: rows of A_e beyond it do not exist; the main kernel
+    // reads u in blocks of 64 columns, so the rest of the last block is written as zeros
+    const int re = min(p.r, uniform(p.tile_rank[t]));
+    const int r_read = min(p.r, (re + 63) & ~63);
+    if (n0 >= r_read) return;
+    const int ncols = max(1, min(C::BN, re - n0));      // rows of A_e to fetch (at least one, in bounds)
+    const int ncols_out = min(C::BN, r_read - n0);      // columns of u to write
 
     const uint32_t ldx = (uint32_t)p.d_in * 2u;
     const char *xa = p.x + (int64_t)row0 * ldx;
@@ -74,11 +80,11 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
     char *ul = p.u_lo + (int64_t)row0 * ldu;
     const float s = p.scale;
     C::epilogue(smem, acc, [&](int row, int col, float(&v)[8]) {
-        if (row >= rows || col >= ncols) return;
+        if (row >= rows || col >= ncols_out) return;
         uint32_t h[8], l[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            const float f = v[q] * s;
+            const float f = (n0 + col + q < re) ? v[q] * s : 0.f;
             h[q] = f32_to_bf16_bits(f);
             l[q] = f32_to_bf16_bits(f - bf16_bits_to_f32(h[q]));
         }
@@ -149,6 +155,7 @@ static hipError_t launch_shrink_as(const PlanView &pv, const LinearArgs &a, hipS
     p.x = (const char *)a.x; p.A_stack = (const char *)a.A_stack;
     p.u_hi = (char *)a.u_hi; p.u_lo = (char *)a.u_lo;
     p.tile_row0 = pv.tile_row0; p.tile_rows = pv.tile_rows; p.tile_expert = pv.tile_expert;
+    p.tile_rank = pv.tile_rank;
     p.n_tiles = pv.n_tiles;
     p.d_in = a.d_in; p.r = a.r; p.scale = a.scale;
     p.n_tiles_n = (a.r + C::BN - 1) / C::BN;
@@ -188,6 +195,7 @@ hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStr
     p.u_hi = (const char *)a.u_hi; p.u_lo = (const char *)a.u_lo;
     p.y = (char *)a.y;
     p.tile_row0 = pv.tile_row0; p.tile_rows = pv.tile_rows; p.tile_expert = pv.tile_expert;
+    p.tile_rank = pv.tile_rank;
     p.n_tiles = pv.n_tiles;
     p.T = pv.T;
     p.d_in = a.d_in; p.d_out = a.d_out; p.r = a.r;
@@ -247,7 +255,8 @@ LinearKParams decode_base_params(const PlanView &pv, const LinearArgs &a, void *
     p.x = (const char *)a.x; p.W = (const char *)a.W; p.B_stack = nullptr;
     p.u_hi = nullptr; p.u_lo = nullptr;
     p.y = (char *)out;
-    p.tile_row0 = nullptr; p.tile_rows = nullptr; p.tile_expert = nullptr; p.n_tiles = nullptr;
+    p.tile_row0 = nullptr; p.tile_rows = nullptr; p.tile_expert = nullptr; p.tile_rank = nullptr;
+    p.n_tiles = nullptr;
     p.T = pv.T;
     p.d_in = a.d_in; p.d_out = a.d_out; p.r = 0;
     p.n_tiles_n = sh.n_tiles_n;

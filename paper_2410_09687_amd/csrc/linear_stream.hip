@@ -44,7 +44,7 @@ constexpr int KSTEPS = BK / 16;
 struct Params {
     const char *x, *W, *B_stack, *u_hi, *u_lo;
     char *y;
-    const int *tile_row0, *tile_rows, *tile_expert, *n_tiles;
+    const int *tile_row0, *tile_rows, *tile_expert, *tile_rank, *n_tiles;
     int d_in, d_out, r;
     int n_tiles_n;
     int y_f32;
@@ -75,8 +75,10 @@ __device__ __forceinline__ Tile load_tile(const Params &p, int id, int n_work)
     const int64_t ldx = (int64_t)p.d_in * 2, ldu = (int64_t)p.r * 2;
     t.q0 = p.x + (int64_t)t.row0 * ldx;
     t.p0 = p.W + (int64_t)t.n0 * ldx;
-    const bool lora = e >= 0 && p.r > 0;
-    t.nkb1 = lora ? p.r / BK : 0;
+    // adapter blocks up to the expert's own rank (the shrink wrote zeros from there to the block end)
+    const int re = min(p.r, uniform(p.tile_rank[tm]));
+    const bool lora = e >= 0 && re > 0;
+    t.nkb1 = lora ? (re + BK - 1) / BK : 0;
     t.total = p.d_in / BK + 2 * t.nkb1;
     t.uh = lora ? p.u_hi + (int64_t)t.row0 * ldu : t.q0;
     t.ul = lora ? p.u_lo + (int64_t)t.row0 * ldu : t.q0;
@@ -349,6 +351,7 @@ hipError_t launch_linear_stream(const PlanView &pv, const LinearArgs &a, int n_c
     p.u_hi = (const char *)a.u_hi; p.u_lo = (const char *)a.u_lo;
     p.y = (char *)a.y;
     p.tile_row0 = pv.tile_row0; p.tile_rows = pv.tile_rows; p.tile_expert = pv.tile_expert;
+    p.tile_rank = pv.tile_rank;
     p.n_tiles = pv.n_tiles;
     p.d_in = a.d_in; p.d_out = a.d_out; p.r = a.r;
     p.n_tiles_n = (a.d_out + stream::BT - 1) / stream::BT;

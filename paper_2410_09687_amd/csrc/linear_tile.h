@@ -10,7 +10,7 @@ struct LinearKParams {
     const char *x, *W, *B_stack;
     const char *u_hi, *u_lo;
     char *y;
-    const int *tile_row0, *tile_rows, *tile_expert, *n_tiles;
+    const int *tile_row0, *tile_rows, *tile_expert, *tile_rank, *n_tiles;
     int64_t T;
     int d_in, d_out, r;
     int n_tiles_n;
@@ -26,6 +26,7 @@ template <class C>
 __device__ __forceinline__ void linear_tile(const LinearKParams &p, int bid, char *smem)
 {
     int ntm, row0, rows, e;
+    int re = 0;   // the tile's adapter rank (at most p.r)
     int id;
     int kb_lo = 0, kb_hi = (p.d_in + C::BK - 1) / C::BK;   // BK blocks of the base contraction
     int split = 0;
@@ -57,15 +58,17 @@ __device__ __forceinline__ void linear_tile(const LinearKParams &p, int bid, cha
         rows = min(rows, C::BM);
         row0 = uniform(p.tile_row0[t]) + sub * C::BM;
         e = uniform(p.tile_expert[t]);
+        re = min(p.r, uniform(p.tile_rank[t]));
     }
     const int tn = uniform(id % p.n_tiles_n);
     const int n0 = tn * C::BN;
     const int ncols = min(C::BN, p.d_out - n0);
 
     const uint32_t ldx = (uint32_t)p.d_in * 2u, ldu = (uint32_t)p.r * 2u;
-    const bool lora = (e >= 0) && p.r > 0;
+    const bool lora = (e >= 0) && re > 0;
     const int nkb0 = kb_hi - kb_lo;
-    const int nkb1 = lora ? (p.r + C::BK - 1) / C::BK : 0;
+    // adapter blocks up to the expert's own rank (the shrink wrote zeros from there to the block end)
+    const int nkb1 = lora ? (re + C::BK - 1) / C::BK : 0;
     // adapter operands are harmless aliases of x / W when the tile has no adapter
     const char *uh = lora ? p.u_hi + (int64_t)row0 * ldu : p.x;
     const char *ul = lora ? p.u_lo + (int64_t)row0 * ldu : p.x;

@@ -47,8 +47,21 @@ __device__ int block_exclusive_scan(int *data, int n, int *lds /* PLAN_THREADS +
 
 template <int PLAN_THREADS>
 __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const int *seq_offsets,
-                                                            const int *expert_ids, int *err_word)
+                                                            const int *expert_ids, const int *rank_of_expert,
+                                                            int *err_word)
 {
+    // Rank of adapter slot e ("Future Works": adaptive rank per topic).  Multiples of 8,
+    // like the stacks' own rank; anything else is rounded down and raises the sticky fault.
+    auto rank_of = [&](int e) -> int {
+        if (e < 0) return 0;
+        if (!rank_of_expert) return RANK_FULL;
+        int rk = rank_of_expert[e];
+        if (rk < 0 || (rk & 7)) {
+            atomicOr(err_word, ERR_BAD_RANK);
+            rk = rk < 0 ? RANK_FULL : (rk & ~7);
+        }
+        return rk;
+    };
     __shared__ int lds[PLAN_THREADS + 1];
     // batches of up to PLAN_LDS_S sequences sort and scan entirely in LDS (a
     // barrier-separated pass then costs tens of nanoseconds, not a round trip
@@ -105,6 +118,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
             pv.tile_row0[j] = j * TILE_M;
             pv.tile_rows[j] = min(TILE_M, T - j * TILE_M);
             pv.tile_expert[j] = -1;
+            pv.tile_rank[j] = 0;
         }
         if (tid == 0) *pv.n_tiles = nt;
         if (pv.decode) {
@@ -167,10 +181,12 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
         const int lo = seq_offsets[s];
         const int len = lens[s];
         const int tb = a1[p];
+        const int rk = rank_of(e);
         for (int j = 0, left = len; left > 0 && tb + j < pv.max_tiles; ++j, left -= TILE_M) {
             pv.tile_row0[tb + j] = lo + j * TILE_M;
             pv.tile_rows[tb + j] = min(left, TILE_M);
             pv.tile_expert[tb + j] = e;
+            pv.tile_rank[tb + j] = rk;
         }
         if (pv.decode) {
             const int base = min(a2[p], T);
@@ -179,6 +195,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
             if (head) {
                 const int gi = a3[p];   // exclusive count of heads before p
                 pv.grp_meta[gi].x = e;
+                pv.grp_meta[gi].w = rk;
                 pv.grp_start[gi] = base;
             }
         }
@@ -189,7 +206,6 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
         for (int gi = tid; gi < n_groups; gi += PLAN_THREADS) {
             pv.grp_meta[gi].y = pv.grp_start[gi];
             pv.grp_meta[gi].z = pv.grp_start[gi + 1];
-            pv.grp_meta[gi].w = 0;
         }
         // unused records read as empty groups, so the decode kernels need not
         // fetch the group count before their own record
@@ -198,14 +214,14 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
 }
 
 hipError_t launch_plan(const PlanView &pv, const int *seq_offsets, const int *expert_ids,
-                       int *err_word, hipStream_t stream)
+                       const int *rank_of_expert, int *err_word, hipStream_t stream)
 {
     if (pv.S <= 2 * PLAN_THREADS_SMALL)
         hipLaunchKernelGGL(plan_kernel<PLAN_THREADS_SMALL>, dim3(1), dim3(PLAN_THREADS_SMALL), 0, stream, pv,
-                           seq_offsets, expert_ids, err_word);
+                           seq_offsets, expert_ids, rank_of_expert, err_word);
     else
         hipLaunchKernelGGL(plan_kernel<PLAN_THREADS_MAX>, dim3(1), dim3(PLAN_THREADS_MAX), 0, stream, pv,
-                           seq_offsets, expert_ids, err_word);
+                           seq_offsets, expert_ids, rank_of_expert, err_word);
     return hipGetLastError();
 }
 

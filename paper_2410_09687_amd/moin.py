@@ -30,7 +30,7 @@ EXPORTS = [
     "moin_lora_linear_planned", "moin_timing_enable", "moin_timing_reset", "moin_timing_read",
     "moin_kmeans_update", "moin_retain_clusters", "moin_kmeans_fit",
     "moin_cache_create", "moin_cache_destroy", "moin_cache_add_stack", "moin_cache_admit",
-    "moin_cache_table", "moin_cache_stats",
+    "moin_cache_table", "moin_cache_stats", "moin_lora_linear_ranked", "moin_plan_build_ranked",
 ]
 CACHE_STATS = ["batches", "seq_hits", "seq_misses", "loads", "evictions", "overflows", "bytes"]
 
@@ -66,6 +66,9 @@ def load() -> ctypes.CDLL:
     lib.moin_histogram.argtypes = [vp, vp, i64, i32, vp, vp]
     lib.moin_lora_linear.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp, i32, i32, i32, i32,
                                      c.c_float, vp, c.c_int, vp]
+    lib.moin_lora_linear_ranked.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp, i32, i32, i32, i32, vp,
+                                            c.c_float, vp, c.c_int, vp]
+    lib.moin_plan_build_ranked.argtypes = [vp, vp, vp, vp, i32, i64, i32, vp, vp]
     lib.moin_plan_create.argtypes = [vp, c.POINTER(vp)]
     lib.moin_plan_destroy.argtypes = [vp]
     lib.moin_plan_destroy.restype = None
@@ -209,16 +212,28 @@ def _stack_dims(W, A_stack, B_stack):
 def moin_lora_linear(ctx: Context, x: torch.Tensor, seq_offsets: torch.Tensor,
                      expert_ids: torch.Tensor, W: torch.Tensor, A_stack: Optional[torch.Tensor],
                      B_stack: Optional[torch.Tensor], scale: float, y_dtype=torch.bfloat16,
-                     out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+                     out: Optional[torch.Tensor] = None, stream=None,
+                     rank_of_expert: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """``rank_of_expert`` (int32 [E] on the device, optional): per-expert adapter rank."""
     if x.dim() != 2 or W.dim() != 2 or x.shape[1] != W.shape[1]:
         raise ValueError("x [T,d_in] and W [d_out,d_in] expected")
     d_in, d_out, E, r = _stack_dims(W, A_stack, B_stack)
+    if rank_of_expert is not None and rank_of_expert.numel() != E:
+        raise ValueError("rank_of_expert must have E entries")
     S = expert_ids.numel()
     if seq_offsets.numel() != S + 1:
         raise ValueError("seq_offsets must have S+1 entries")
     T = x.shape[0]
     y, ydt = _y_out(x, d_out, y_dtype, out)
     bf = torch.bfloat16
+    if rank_of_expert is not None:
+        _ck(load().moin_lora_linear_ranked(
+            ctx._h, _dev_ptr(x, "x", bf) if T else None, _dev_ptr(seq_offsets, "seq_offsets", torch.int32),
+            _dev_ptr(expert_ids, "expert_ids", torch.int32) if S else None, S, T, _dev_ptr(W, "W", bf),
+            _dev_ptr(A_stack, "A_stack", bf), _dev_ptr(B_stack, "B_stack", bf), E, d_in, d_out, r,
+            _dev_ptr(rank_of_expert, "rank_of_expert", torch.int32), float(scale),
+            _dev_ptr(y, "y") if T else None, ydt, _stream_ptr(stream)), "moin_lora_linear_ranked")
+        return y
     _ck(load().moin_lora_linear(
         ctx._h, _dev_ptr(x, "x", bf) if T else None, _dev_ptr(seq_offsets, "seq_offsets", torch.int32),
         _dev_ptr(expert_ids, "expert_ids", torch.int32) if S else None, S, T, _dev_ptr(W, "W", bf),
@@ -236,13 +251,17 @@ class Plan:
         _ck(load().moin_plan_create(ctx._h, ctypes.byref(self._h)), "moin_plan_create")
         self.T = self.S = self.E = 0
 
-    def build(self, seq_offsets: torch.Tensor, expert_ids: torch.Tensor, T: int, E: int, stream=None):
+    def build(self, seq_offsets: torch.Tensor, expert_ids: torch.Tensor, T: int, E: int, stream=None,
+              rank_of_expert: Optional[torch.Tensor] = None):
         S = expert_ids.numel()
         if seq_offsets.numel() != S + 1:
             raise ValueError("seq_offsets must have S+1 entries")
-        _ck(load().moin_plan_build(self.ctx._h, self._h, _dev_ptr(seq_offsets, "seq_offsets", torch.int32),
-                                   _dev_ptr(expert_ids, "expert_ids", torch.int32) if S else None,
-                                   S, T, E, _stream_ptr(stream)), "moin_plan_build")
+        if rank_of_expert is not None and rank_of_expert.numel() != E:
+            raise ValueError("rank_of_expert must have E entries")
+        _ck(load().moin_plan_build_ranked(self.ctx._h, self._h, _dev_ptr(seq_offsets, "seq_offsets", torch.int32),
+                                          _dev_ptr(expert_ids, "expert_ids", torch.int32) if S else None,
+                                          S, T, E, _dev_ptr(rank_of_expert, "rank_of_expert", torch.int32),
+                                          _stream_ptr(stream)), "moin_plan_build_ranked")
         self.T, self.S, self.E = T, S, E
         return self
 
