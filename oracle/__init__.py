@@ -10,7 +10,10 @@ from .oracle import (  # noqa: F401
     histogram,
     kmeans_update,
     lora_linear,
+    lora_linear_mx,
     max_threads,
+    mx_dequantize,
+    mx_quantize,
     retain_clusters,
     route,
     slot_map,

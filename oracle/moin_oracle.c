@@ -37,6 +37,16 @@
  *                 sequence (Section 1: each query goes to a single expert),
  *                 a caller-given scale on the adapter term, and the base-only
  *                 fallback for expert id -1.
+ *   mx_quantize / lora_linear_mx -- "Future Works", quantising the base
+ *                 model: the paper only names the idea (a QLoRA-like, aggressively
+ *                 quantised base with full-precision experts).  The format taken
+ *                 here is the OCP Microscaling (MX) v1.0 "MXFP8" block format:
+ *                 blocks of 32 consecutive elements along the contraction index
+ *                 share one power-of-two scale (E8M0 byte) and hold FP8 E4M3
+ *                 elements (OCP 8-bit floating point: bias 7, largest finite 448,
+ *                 no infinities).  The base product runs on the quantised
+ *                 weight and the quantised activations, the adapter term on the
+ *                 unquantised bf16 activations.
  *
  * Parity pins live in tests/test_oracle_*.py (closed forms, numpy fp64
  * special cases, brute force, metamorphic relations).  Anything that would
@@ -247,6 +257,204 @@ int moin_oracle_lora_linear(const uint16_t *x, const int32_t *seq_offsets,
             double base = 0.0;
             for (int32_t i = 0; i < d_in; ++i)
                 base += bf16_to_f64(W[(size_t)o * d_in + i]) * xt[i];
+            double out = base;
+            if (e >= 0) {
+                const uint16_t *B = B_stack + (size_t)e * d_out * r;
+                double lora = 0.0;
+                for (int32_t j = 0; j < re; ++j)
+                    lora += bf16_to_f64(B[(size_t)o * r + j]) * u[j];
+                out = base + scale * lora;
+            }
+            y[(size_t)p * d_out + o] = out;
+        }
+    }
+    return bad ? ORACLE_EINVAL : ORACLE_OK;
+}
+
+/* ---- MX (microscaled) FP8 base operands -------------------------------- */
+
+/* Value of an FP8 E4M3 code (OCP 8-bit floating point specification): 1 sign
+ * bit, 4 exponent bits with bias 7, 3 mantissa bits; exponent field 0 holds
+ * the subnormals m/8 * 2^-6; there are no infinities and S.1111.111 is NaN. */
+static double e4m3_to_f64(uint8_t c)
+{
+    const int sign = c >> 7, ef = (c >> 3) & 15, m = c & 7;
+    double v;
+    if (ef == 15 && m == 7) return NAN;
+    if (ef == 0) v = ldexp((double)m / 8.0, -6);
+    else v = ldexp(1.0 + (double)m / 8.0, ef - 7);
+    return sign ? -v : v;
+}
+
+/* Nearest E4M3 code of a finite value: round to nearest, ties to the code with
+ * an even mantissa, magnitudes beyond the largest finite value (448) saturate
+ * to it.  Written as a search over all 127 finite magnitudes so that the
+ * rounding rule is the definition itself and not a bit trick. */
+static uint8_t f64_to_e4m3(double v)
+{
+    const uint8_t sign = signbit(v) ? 0x80 : 0;
+    const double a = fabs(v);
+    int best = 0;
+    double best_err = a;                       /* code 0 is the value 0 */
+    for (int c = 1; c <= 0x7E; ++c) {
+        const double err = fabs(e4m3_to_f64((uint8_t)c) - a);
+        if (err < best_err || (err == best_err && (c & 1) == 0)) {
+            best = c;
+            best_err = err;
+        }
+    }
+    return (uint8_t)(sign | best);
+}
+
+/* Shared scale of one block (MX v1.0, conversion of a vector to an MX block):
+ * the largest power of two not above the block's largest magnitude, divided by
+ * the largest power of two of the element format (2^8 for E4M3), stored as the
+ * biased exponent byte E (scale = 2^(E-127)), kept inside 0..254.  A block of
+ * zeros takes scale 1 (E = 127); the specification leaves that case open. */
+static uint8_t mx_block_scale(const double *v, int n)
+{
+    double amax = 0.0;
+    for (int i = 0; i < n; ++i)
+        if (fabs(v[i]) > amax) amax = fabs(v[i]);
+    if (amax == 0.0) return 127;
+    int ex;
+    (void)frexp(amax, &ex);                    /* amax = f * 2^ex, 0.5 <= f < 1 */
+    int E = (ex - 1) - 8 + 127;                /* floor(log2 amax) - emax + bias */
+    if (E < 0) E = 0;
+    if (E > 254) E = 254;
+    return (uint8_t)E;
+}
+
+#define MX_BLOCK 32
+
+/* Quantises rows x cols finite bf16 values (cols a multiple of 32) to MXFP8:
+ * codes[rows, cols] E4M3 bytes and scales[rows, cols/32] E8M0 bytes, the
+ * element being the rounded quotient value / scale. */
+int moin_oracle_mx_quantize(const uint16_t *src, int64_t rows, int32_t cols,
+                            uint8_t *codes, uint8_t *scales)
+{
+    if (rows < 0 || cols <= 0 || cols % MX_BLOCK) return ORACLE_EINVAL;
+    if (rows == 0) return ORACLE_OK;
+    if (!src || !codes || !scales) return ORACLE_EINVAL;
+    const int32_t nb = cols / MX_BLOCK;
+    int bad = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i)
+        for (int32_t b = 0; b < nb; ++b) {
+            double v[MX_BLOCK];
+            for (int k = 0; k < MX_BLOCK; ++k) {
+                v[k] = bf16_to_f64(src[(size_t)i * cols + (size_t)b * MX_BLOCK + k]);
+                if (!isfinite(v[k])) {
+#pragma omp atomic write
+                    bad = 1;
+                    v[k] = 0.0;
+                }
+            }
+            const uint8_t E = mx_block_scale(v, MX_BLOCK);
+            scales[(size_t)i * nb + b] = E;
+            for (int k = 0; k < MX_BLOCK; ++k)
+                codes[(size_t)i * cols + (size_t)b * MX_BLOCK + k] =
+                    f64_to_e4m3(ldexp(v[k], 127 - (int)E));
+        }
+    return bad ? ORACLE_EINVAL : ORACLE_OK;
+}
+
+/* out[i, j] = value(codes[i, j]) * 2^(scales[i, j / 32] - 127), exact in fp64. */
+int moin_oracle_mx_dequantize(const uint8_t *codes, const uint8_t *scales, int64_t rows,
+                              int32_t cols, double *out)
+{
+    if (rows < 0 || cols <= 0 || cols % MX_BLOCK) return ORACLE_EINVAL;
+    if (rows == 0) return ORACLE_OK;
+    if (!codes || !scales || !out) return ORACLE_EINVAL;
+    const int32_t nb = cols / MX_BLOCK;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int32_t j = 0; j < cols; ++j)
+            out[(size_t)i * cols + j] = ldexp(e4m3_to_f64(codes[(size_t)i * cols + j]),
+                                              (int)scales[(size_t)i * nb + j / MX_BLOCK] - 127);
+    return ORACLE_OK;
+}
+
+/*
+ * The routed LoRA linear layer on a quantised base: like
+ * moin_oracle_lora_linear, but the base term is
+ *     base_o = sum_i Wd[o,i] xd[t,i]
+ * with Wd the dequantised MXFP8 weight (Wq codes [d_out, d_in], Ws scales
+ * [d_out, d_in/32]) and xd the token's activations after a round trip through
+ * the same MXFP8 quantisation; the adapter term still uses the bf16 x:
+ *     y[t,o] = base_o + scale * sum_j B[e,o,j] (sum_i A[e,j,i] x[t,i]).
+ * work: work_slots * (2 * d_in + r) doubles.
+ */
+int moin_oracle_lora_linear_mx(const uint16_t *x, const int32_t *seq_offsets,
+                               const int32_t *expert_ids, int32_t S, int64_t T,
+                               const uint8_t *Wq, const uint8_t *Ws, const uint16_t *A_stack,
+                               const uint16_t *B_stack, int32_t E, int32_t d_in,
+                               int32_t d_out, int32_t r, double scale,
+                               const int32_t *rank_of_expert,
+                               const int64_t *rows, int64_t n_rows, double *y,
+                               double *work, int32_t work_slots)
+{
+    if (S < 0 || T < 0 || d_in <= 0 || d_in % MX_BLOCK || d_out <= 0 || r < 0 || E < 0 ||
+        n_rows < 0 || work_slots <= 0)
+        return ORACLE_EINVAL;
+    if (n_rows == 0) return ORACLE_OK;
+    if (!x || !seq_offsets || !Wq || !Ws || !y || !work) return ORACLE_EINVAL;
+    if (S > 0 && !expert_ids) return ORACLE_EINVAL;
+    if (!rows && n_rows != T) return ORACLE_EINVAL;
+    if (seq_offsets[0] != 0 || seq_offsets[S] != T) return ORACLE_EINVAL;
+    for (int32_t s = 0; s < S; ++s) {
+        if (seq_offsets[s + 1] < seq_offsets[s]) return ORACLE_EINVAL;
+        if (expert_ids[s] < -1 || expert_ids[s] >= E) return ORACLE_EINVAL;
+        if (expert_ids[s] >= 0 && (!A_stack || !B_stack)) return ORACLE_EINVAL;
+        if (expert_ids[s] >= 0 && rank_of_expert &&
+            (rank_of_expert[expert_ids[s]] < 0 || rank_of_expert[expert_ids[s]] > r))
+            return ORACLE_EINVAL;
+    }
+    const int32_t nb = d_in / MX_BLOCK;
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(work_slots)
+    for (int64_t p = 0; p < n_rows; ++p) {
+        int64_t t = rows ? rows[p] : p;
+        if (t < 0 || t >= T) {
+#pragma omp atomic write
+            bad = 1;
+            continue;
+        }
+        int32_t s = 0;
+        while (s < S && seq_offsets[s + 1] <= t) ++s;
+        int32_t e = expert_ids[s];
+        int slot = 0;
+#ifdef _OPENMP
+        extern int omp_get_thread_num(void);
+        slot = omp_get_thread_num();
+#endif
+        double *xt = work + (size_t)slot * (2 * (size_t)d_in + (size_t)r);
+        double *xd = xt + d_in;
+        double *u = xd + d_in;
+        for (int32_t i = 0; i < d_in; ++i)
+            xt[i] = bf16_to_f64(x[(size_t)t * d_in + i]);
+        /* the token through the quantiser and back */
+        for (int32_t b = 0; b < nb; ++b) {
+            const double *v = xt + (size_t)b * MX_BLOCK;
+            const uint8_t Eb = mx_block_scale(v, MX_BLOCK);
+            for (int k = 0; k < MX_BLOCK; ++k)
+                xd[(size_t)b * MX_BLOCK + k] =
+                    ldexp(e4m3_to_f64(f64_to_e4m3(ldexp(v[k], 127 - (int)Eb))), (int)Eb - 127);
+        }
+        const int32_t re = (e >= 0 && rank_of_expert) ? rank_of_expert[e] : r;
+        if (e >= 0) {
+            const uint16_t *A = A_stack + (size_t)e * r * d_in;
+            for (int32_t j = 0; j < re; ++j) {
+                double acc = 0.0;
+                for (int32_t i = 0; i < d_in; ++i)
+                    acc += bf16_to_f64(A[(size_t)j * d_in + i]) * xt[i];
+                u[j] = acc;
+            }
+        }
+        for (int32_t o = 0; o < d_out; ++o) {
+            double base = 0.0;
+            for (int32_t i = 0; i < d_in; ++i)
+                base += ldexp(e4m3_to_f64(Wq[(size_t)o * d_in + i]),
+                              (int)Ws[(size_t)o * nb + i / MX_BLOCK] - 127) * xd[i];
             double out = base;
             if (e >= 0) {
                 const uint16_t *B = B_stack + (size_t)e * d_out * r;

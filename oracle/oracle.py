@@ -47,6 +47,15 @@ def _load():
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int64,
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
             c.c_double, c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_int32]
+        lib.moin_oracle_lora_linear_mx.argtypes = [
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int64,
+            c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
+            c.c_int32, c.c_double, c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p,
+            c.c_int32]
+        lib.moin_oracle_mx_quantize.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_void_p,
+                                                c.c_void_p]
+        lib.moin_oracle_mx_dequantize.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_int32,
+                                                  c.c_void_p]
         lib.moin_oracle_kmeans_update.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p,
                                                   c.c_int32, c.c_int32, c.c_int, c.c_void_p,
                                                   c.c_void_p, c.c_void_p]
@@ -55,6 +64,8 @@ def _load():
         lib.moin_oracle_retain_clusters.restype = c.c_int
         for f in ("moin_oracle_dist2", "moin_oracle_route", "moin_oracle_slot_map",
                   "moin_oracle_histogram", "moin_oracle_lora_linear",
+                  "moin_oracle_lora_linear_mx", "moin_oracle_mx_quantize",
+                  "moin_oracle_mx_dequantize",
                   "moin_oracle_max_threads"):
             getattr(lib, f).restype = c.c_int
         _lib = lib
@@ -228,6 +239,92 @@ def lora_linear(x, seq_offsets, expert_ids, W, A_stack, B_stack, scale, rows=Non
         _ptr(x), _ptr(seq_offsets), _ptr(expert_ids), S, T, _ptr(W), _ptr(A_stack),
         _ptr(B_stack), E, d_in, d_out, r, float(scale), _ptr(ranks), _ptr(rows_arr), n_rows, _ptr(y),
         _ptr(work), slots), "lora_linear")
+    return y
+
+
+MX_BLOCK = 32
+
+
+def mx_quantize(values):
+    """MXFP8 quantisation along the last axis of ``values [rows, cols]`` (uint16
+    bf16 bit patterns, finite, cols a multiple of 32): returns ``codes [rows,
+    cols]`` (uint8 FP8 E4M3) and ``scales [rows, cols/32]`` (uint8 E8M0)."""
+    v = np.ascontiguousarray(values)
+    if v.dtype != np.uint16 or v.ndim != 2:
+        raise TypeError("values: 2-D uint16 (bf16 bits) expected")
+    rows, cols = v.shape
+    if cols == 0 or cols % MX_BLOCK:
+        raise ValueError("cols must be a positive multiple of 32")
+    codes = np.zeros((rows, cols), dtype=np.uint8)
+    scales = np.zeros((rows, cols // MX_BLOCK), dtype=np.uint8)
+    _check(_load().moin_oracle_mx_quantize(_ptr(v), rows, cols, _ptr(codes), _ptr(scales)),
+           "mx_quantize")
+    return codes, scales
+
+
+def mx_dequantize(codes, scales):
+    """fp64 values of an MXFP8 matrix (exact)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.uint8)
+    rows, cols = codes.shape
+    if cols == 0 or cols % MX_BLOCK or scales.shape != (rows, cols // MX_BLOCK):
+        raise ValueError("codes [rows, cols] / scales [rows, cols/32] shape mismatch")
+    out = np.zeros((rows, cols), dtype=np.float64)
+    _check(_load().moin_oracle_mx_dequantize(_ptr(codes), _ptr(scales), rows, cols, _ptr(out)),
+           "mx_dequantize")
+    return out
+
+
+def lora_linear_mx(x, seq_offsets, expert_ids, Wq, Ws, A_stack, B_stack, scale, rows=None,
+                   threads=None, rank_of_expert=None):
+    """Routed LoRA linear on an MXFP8 base: y = xd Wd^T + scale * (x A_e^T) B_e^T
+    with Wd the dequantised weight (``Wq [d_out,d_in]`` codes, ``Ws
+    [d_out,d_in/32]`` scales), xd the bf16 activations after an MXFP8 round trip
+    and the adapter term on the bf16 activations themselves (fp64)."""
+    x = np.ascontiguousarray(x)
+    if x.dtype != np.uint16 or x.ndim != 2:
+        raise TypeError("x: 2-D uint16 (bf16 bits) expected")
+    Wq = np.ascontiguousarray(Wq)
+    Ws = np.ascontiguousarray(Ws)
+    if Wq.dtype != np.uint8 or Ws.dtype != np.uint8 or Wq.ndim != 2:
+        raise TypeError("Wq / Ws: uint8 expected")
+    T, d_in = x.shape
+    d_out = Wq.shape[0]
+    if d_in % MX_BLOCK or Wq.shape[1] != d_in or Ws.shape != (d_out, d_in // MX_BLOCK):
+        raise ValueError("Wq [d_out, d_in] / Ws [d_out, d_in/32] shape mismatch")
+    seq_offsets = np.ascontiguousarray(seq_offsets, dtype=np.int32)
+    expert_ids = np.ascontiguousarray(expert_ids, dtype=np.int32)
+    S = expert_ids.size
+    if seq_offsets.size != S + 1:
+        raise ValueError("seq_offsets must have S+1 entries")
+    if A_stack is None or B_stack is None:
+        E, r = 0, 0
+        A_stack = B_stack = None
+    else:
+        A_stack = np.ascontiguousarray(A_stack)
+        B_stack = np.ascontiguousarray(B_stack)
+        if A_stack.dtype != np.uint16 or B_stack.dtype != np.uint16:
+            raise TypeError("A_stack/B_stack: uint16 (bf16 bits) expected")
+        E, r = A_stack.shape[0], A_stack.shape[1]
+        if A_stack.shape != (E, r, d_in) or B_stack.shape != (E, d_out, r):
+            raise ValueError("A_stack [E,r,d_in] / B_stack [E,d_out,r] shape mismatch")
+    if rows is None:
+        rows_arr, n_rows = None, T
+    else:
+        rows_arr = np.ascontiguousarray(rows, dtype=np.int64)
+        n_rows = rows_arr.size
+    ranks = None
+    if rank_of_expert is not None:
+        ranks = np.ascontiguousarray(rank_of_expert, dtype=np.int32)
+        if ranks.shape != (E,):
+            raise ValueError("rank_of_expert must have E entries")
+    y = np.zeros((n_rows, d_out), dtype=np.float64)
+    slots = int(threads) if threads else max_threads()
+    work = np.zeros(slots * (2 * d_in + max(r, 1)), dtype=np.float64)
+    _check(_load().moin_oracle_lora_linear_mx(
+        _ptr(x), _ptr(seq_offsets), _ptr(expert_ids), S, T, _ptr(Wq), _ptr(Ws), _ptr(A_stack),
+        _ptr(B_stack), E, d_in, d_out, r, float(scale), _ptr(ranks), _ptr(rows_arr), n_rows,
+        _ptr(y), _ptr(work), slots), "lora_linear_mx")
     return y
 
 
