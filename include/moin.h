@@ -63,7 +63,9 @@ typedef enum {
     MOIN_K_KMEANS_SORT = 8,   /* K-means update: stable grouping of points by centre */
     MOIN_K_KMEANS_SUM = 9,    /* K-means update: the pass over the embeddings    */
     MOIN_K_KMEANS_FINAL = 10, /* K-means update: means, objective; cluster pruning */
-    MOIN_K_COUNT = 11
+    MOIN_K_MX_QUANT = 11,     /* quantised base: bf16 -> MXFP8 codes + scales    */
+    MOIN_K_MX_LINEAR = 12,    /* quantised base: y = xq Wq^T + u B_e^T           */
+    MOIN_K_COUNT = 13
 } moin_kernel_id;
 
 /* ---- context ----------------------------------------------------------- */
@@ -160,6 +162,38 @@ int moin_lora_linear_ranked(moin_ctx *ctx, const void *x, const int32_t *seq_off
                             int32_t E, int32_t d_in, int32_t d_out, int32_t r,
                             const int32_t *rank_of_expert, float scale, void *y,
                             moin_dtype y_dt, void *stream);
+
+/* "Future Works", quantising the base model (a QLoRA-like, aggressively quantised
+ * base whose loss the experts recover; the paper names the idea only).  The
+ * format here is OCP Microscaling MXFP8: along the last axis, blocks of 32
+ * consecutive values share one power-of-two scale 2^(E-127) (E8M0 byte E) and
+ * hold FP8 E4M3 elements (bias 7, largest finite value 448, no infinities).
+ *
+ * moin_mx_quantize: src [rows, cols] bf16 (DEVICE, finite values; NaN / Inf give
+ * unspecified codes) -> codes [rows, cols] uint8 and scales [rows, cols/32] uint8
+ * (both DEVICE, caller-owned).  E = max(0, floor(log2 max|v|) + 127 - 8) per
+ * block (127 for a block of zeros); element = v / 2^(E-127) rounded to nearest
+ * even, magnitudes above 448 clamped to 448.  cols must be a multiple of 32,
+ * src and codes 16-byte aligned.  Used once for the weight. */
+int moin_mx_quantize(moin_ctx *ctx, const void *src, int64_t rows, int64_t cols, void *codes,
+                     void *scales, void *stream);
+
+/* moin_lora_linear_ranked on a quantised base:
+ *     y = dq(q(x)) dq(Wq)^T + scale * (x A_e^T) B_e^T
+ * Wq [d_out, d_in] codes and Ws [d_out, d_in/32] scales come from
+ * moin_mx_quantize; x [T, d_in] is bf16 and is quantised by the call itself
+ * (into the context's workspace) for the base product, which runs on the
+ * block-scaled FP8 matrix cores; the adapter term uses the bf16 x and the bf16
+ * stacks exactly as in moin_lora_linear.  rank_of_expert may be NULL.
+ * Shapes: d_in a multiple of 128 and at least 256, r a multiple of 64, d_out a
+ * multiple of 8; anything else returns MOIN_EINVAL.  Every batch size takes the
+ * tiled path (no separate decode path). */
+int moin_lora_linear_mx(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
+                        const int32_t *expert_ids, int32_t S, int64_t T,
+                        const void *Wq, const void *Ws, const void *A_stack, const void *B_stack,
+                        int32_t E, int32_t d_in, int32_t d_out, int32_t r,
+                        const int32_t *rank_of_expert, float scale, void *y,
+                        moin_dtype y_dt, void *stream);
 
 /* The grouping of sequences by expert depends only on (seq_offsets,
  * expert_ids, E); a plan computes it once for all projections of a layer

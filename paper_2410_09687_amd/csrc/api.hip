@@ -16,12 +16,14 @@ hipError_t prepare_linear_kernels();
 hipError_t prepare_route_kernels();
 hipError_t prepare_decode_kernels();
 hipError_t prepare_kmeans_kernels();
+hipError_t prepare_mx_kernels();
 hipError_t prepare_kernels()
 {
     hipError_t e = prepare_linear_kernels();
     if (e != hipSuccess) return e;
     if ((e = prepare_decode_kernels()) != hipSuccess) return e;
     if ((e = prepare_kmeans_kernels()) != hipSuccess) return e;
+    if ((e = prepare_mx_kernels()) != hipSuccess) return e;
     return prepare_route_kernels();
 }
 }  // namespace moin
@@ -320,6 +322,49 @@ int linear_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, con
     return MOIN_OK;
 }
 
+// Quantised-base variant of the prefill sequence: shrink on the bf16 x, x
+// through the quantiser, then the block-scaled main kernel.
+int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, const void *Wq,
+                           const void *Ws, const void *A_stack, const void *B_stack, int32_t d_in,
+                           int32_t d_out, int32_t r, float scale, void *y, moin_dtype y_dt,
+                           hipStream_t stream)
+{
+    if (!plan->built) return MOIN_EINVAL;
+    const PlanView &pv = plan->pv;
+    if (pv.S == 0 || pv.T == 0) return MOIN_OK;
+    const bool adapters = pv.E > 0 && r > 0;
+    MxLinearArgs m;
+    LinearArgs &a = m.lin;
+    a.x = x; a.W = nullptr; a.A_stack = A_stack; a.B_stack = B_stack;
+    a.y = y; a.y_f32 = (y_dt == MOIN_F32);
+    a.d_in = d_in; a.d_out = d_out; a.r = adapters ? r : 0; a.scale = scale;
+    a.u_hi = a.u_lo = nullptr;
+    const size_t u_bytes = align_up((size_t)pv.T * (size_t)a.r * 2, 256);
+    const size_t xq_bytes = align_up((size_t)pv.T * (size_t)d_in, 256);
+    const size_t xs_bytes = align_up((size_t)pv.T * (size_t)(d_in / 32), 256);
+    const int rc = ensure_ws(ctx, 2 * u_bytes + xq_bytes + xs_bytes);
+    if (rc != MOIN_OK) return rc;
+    char *w = static_cast<char *>(ctx->ws);
+    a.u_hi = w;
+    a.u_lo = w + u_bytes;
+    m.xq = w + 2 * u_bytes;
+    m.xs = w + 2 * u_bytes + xq_bytes;
+    m.Wq = Wq;
+    m.Ws = Ws;
+    if (a.r > 0 &&
+        timed(ctx, MOIN_K_SHRINK, stream, [&] { return launch_prefill_shrink(pv, a, stream); }) != hipSuccess)
+        return MOIN_EHIP;
+    if (timed(ctx, MOIN_K_MX_QUANT, stream, [&] {
+            return launch_mx_quantize(x, pv.T, d_in, const_cast<void *>(m.xq), const_cast<void *>(m.xs), stream);
+        }) != hipSuccess)
+        return MOIN_EHIP;
+    if (timed(ctx, MOIN_K_MX_LINEAR, stream, [&] {
+            return launch_linear_mx_stream(pv, m, compute_units(), stream);
+        }) != hipSuccess)
+        return MOIN_EHIP;
+    return MOIN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -566,6 +611,50 @@ int moin_lora_linear(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
 {
     return moin_lora_linear_ranked(ctx, x, seq_offsets, expert_ids, S, T, W, A_stack, B_stack, E, d_in,
                                    d_out, r, nullptr, scale, y, y_dt, stream);
+}
+
+int moin_mx_quantize(moin_ctx *ctx, const void *src, int64_t rows, int64_t cols, void *codes,
+                     void *scales, void *stream)
+{
+    if (!ctx || rows < 0 || cols <= 0 || cols % 32) return MOIN_EINVAL;
+    if (rows == 0) return MOIN_OK;
+    if (!src || !codes || !scales || misaligned(src, 16) || misaligned(codes, 16)) return MOIN_EINVAL;
+    if (rows > (int64_t)1 << 40 || cols > (int64_t)1 << 30 || rows * cols > (int64_t)1 << 46)
+        return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (timed(ctx, MOIN_K_MX_QUANT, st, [&] { return launch_mx_quantize(src, rows, cols, codes, scales, st); }) !=
+        hipSuccess)
+        return MOIN_EHIP;
+    return MOIN_OK;
+}
+
+int moin_lora_linear_mx(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
+                        const int32_t *expert_ids, int32_t S, int64_t T, const void *Wq,
+                        const void *Ws, const void *A_stack, const void *B_stack, int32_t E,
+                        int32_t d_in, int32_t d_out, int32_t r, const int32_t *rank_of_expert,
+                        float scale, void *y, moin_dtype y_dt, void *stream)
+{
+    if (!ctx) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    if (!ctx->own_plan) {
+        const int rc = moin_plan_create(ctx, &ctx->own_plan);
+        if (rc != MOIN_OK) return rc;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (S < 0 || T < 0 || E < 0) return MOIN_EINVAL;
+    if (S > 0 && T > 0) {
+        const int vrc = validate_linear(x, Wq, A_stack, B_stack, E, d_in, d_out, r, scale, y, y_dt);
+        if (vrc != MOIN_OK) return vrc;
+        if (!Ws || misaligned(Ws, 16)) return MOIN_EINVAL;
+        if (!mx_stream_kernel_fits(d_in, (E > 0 && r > 0) ? r : 0)) return MOIN_EINVAL;
+    }
+    int rc = plan_build_impl(ctx, ctx->own_plan, seq_offsets, expert_ids, S, T, E, rank_of_expert, st);
+    if (rc != MOIN_OK) return rc;
+    return linear_mx_planned_impl(ctx, ctx->own_plan, x, Wq, Ws, A_stack, B_stack, d_in, d_out, r, scale,
+                                  y, y_dt, st);
 }
 
 int moin_kmeans_update(moin_ctx *ctx, const void *emb, const int32_t *ids, int64_t N,

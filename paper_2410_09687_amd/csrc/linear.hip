@@ -135,7 +135,7 @@ hipError_t prepare_linear_kernels()
 static inline int round_up8(int v) { return (v + 7) & ~7; }
 
 // Compute units of the current device (queried once per device).
-static int compute_units()
+int compute_units()
 {
     static int cached[64];
     int dev = 0;

@@ -1,0 +1,426 @@
+// Routed LoRA linear layer on a quantised base ("Future Works", quantising the
+// base model: an aggressively quantised base whose loss the full-precision
+// experts recover).  The base operands are in the OCP Microscaling MXFP8 format:
+// blocks of 32 contraction steps share a power-of-two scale (one E8M0 byte) and
+// hold FP8 E4M3 elements.
+//
+//   mx_quantize_kernel      bf16 -> codes + scales (the weight once, the
+//                           activations per call);
+//   linear_mx_stream_kernel y tile = xq Wq^T (block-scaled FP8 MFMA)
+//                                    + u_hi B_e^T + u_lo B_e^T (bf16 MFMA),
+//                           all into the same fp32 accumulators.
+//
+// The main kernel is the streaming prefill kernel with another block format: an
+// operand row of a block is still 128 bytes, which now are 128 FP8 contraction
+// steps of the base product, or 64 bf16 ones of the adapter term.
+// v_mfma_scale_f32_32x32x64_f8f6f4 takes, per lane, 16 + 16 bytes of an operand
+// row: bytes [16 h, 16 h + 16) of the first and of the second 32-step block of a
+// 64-step slice (h = lane / 32), and the scale byte of the first block from the
+// lanes with h = 0, of the second from those with h = 1.  Read as bf16 the same
+// two 16-byte pieces are the operands of two v_mfma_f32_32x32x16_bf16, so both
+// block kinds share one LDS read pattern.
+#include <type_traits>
+
+#include "gemm_core.h"
+#include "kernels.h"
+#include "stream_epilogue.h"
+
+namespace moin {
+
+typedef int i32x8_t __attribute__((ext_vector_type(8)));
+
+// ---- quantiser -----------------------------------------------------------
+
+// One thread per 8 consecutive values, four threads per block of 32.  All the
+// arithmetic is exact until the final rounding: the shared scale is the power
+// of two 2^(floor(log2 amax) - 8) (byte E = exponent field of amax - 8, at
+// least 0; 127 for a block of zeros), the quotient value / scale is a product
+// with a power of two, magnitudes above 448 clamp to 448, and the conversion
+// rounds to nearest even.
+__global__ __launch_bounds__(256) void mx_quantize_kernel(const uint4 *__restrict__ src, uint2 *__restrict__ codes,
+                                                          uint8_t *__restrict__ scales, int64_t n8)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < n8; t += stride) {
+        const uint4 v = src[t];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        uint32_t m = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            m = max(m, w[i] & 0x7FFFu);
+            m = max(m, (w[i] >> 16) & 0x7FFFu);
+        }
+        // n8 is a multiple of 4 and the stride of 64: the four lanes of a block are active together
+        m = max(m, (uint32_t)__shfl_xor((int)m, 1));
+        m = max(m, (uint32_t)__shfl_xor((int)m, 2));
+        const int E = m == 0 ? 127 : max(0, (int)(m >> 7) - 8);
+        const float inv = bits_f32((uint32_t)(254 - E) << 23);   // 2^(127 - E), a normal number for E <= 246
+        float f[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = bits_f32(w[i] << 16) * inv;
+            f[2 * i + 1] = bits_f32(w[i] & 0xFFFF0000u) * inv;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f[i] = fminf(fmaxf(f[i], -448.f), 448.f);
+        int lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[0], f[1], 0, false);
+        lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[2], f[3], lo, true);
+        int hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[4], f[5], 0, false);
+        hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], hi, true);
+        codes[t] = make_uint2((uint32_t)lo, (uint32_t)hi);
+        if ((t & 3) == 0) scales[t >> 2] = (uint8_t)E;
+    }
+}
+
+hipError_t launch_mx_quantize(const void *src, int64_t rows, int64_t cols, void *codes, void *scales,
+                              hipStream_t stream)
+{
+    const int64_t n8 = rows * cols / 8;
+    if (n8 <= 0) return hipSuccess;
+    int64_t grid = (n8 + 255) / 256;
+    if (grid > 256 * 32) grid = 256 * 32;
+    hipLaunchKernelGGL(mx_quantize_kernel, dim3((unsigned)grid), dim3(256), 0, stream,
+                       reinterpret_cast<const uint4 *>(src), reinterpret_cast<uint2 *>(codes),
+                       reinterpret_cast<uint8_t *>(scales), n8);
+    return hipGetLastError();
+}
+
+// ---- main kernel -----------------------------------------------------------
+
+namespace mxs {
+
+constexpr int BT = 256;              // tile edge, both ways
+constexpr int ROWB = 128;            // bytes of one operand row per block
+constexpr int KB8 = 128;             // contraction steps of a base block (FP8)
+constexpr int KB16 = 64;             // contraction steps of an adapter block (bf16)
+constexpr int NW = 8, NT = NW * 64;
+constexpr int WQ = 2;                // waves along tokens (Q); NW / WQ along outputs (P)
+constexpr int FP = 2, FQ = 4;        // 32 x 32 accumulators per wave: 64 outputs x 128 tokens
+constexpr int OP_BYTES = BT * ROWB;  // one operand tile: 32 KB
+constexpr int STAGE_BYTES = 2 * OP_BYTES;
+constexpr int SMEM_STAGES = 2 * STAGE_BYTES;
+constexpr int SCR_BYTES = 4096;      // per-wave epilogue scratch
+constexpr int SMEM_BYTES = SMEM_STAGES + NW * SCR_BYTES;   // 160 KB: all of a compute unit's LDS
+constexpr int LOADS = 4;             // DMA instructions per wave per operand per block
+constexpr int NSC = FP + FQ;         // scale words a lane holds per block
+
+struct Params {
+    const char *xq, *Wq;             // FP8 codes [T, d_in], [d_out, d_in]
+    const char *xs, *Ws;             // scale bytes [T, d_in / 32], [d_out, d_in / 32]
+    const char *B_stack, *u_hi, *u_lo;
+    char *y;
+    const int *tile_row0, *tile_rows, *tile_expert, *tile_rank, *n_tiles;
+    int d_in, d_out, r;
+    int n_tiles_n;
+    int y_f32;
+};
+
+// Everything a tile needs, all wave-uniform.
+struct Tile {
+    const char *q0, *p0;       // code rows of the tile's tokens / outputs at k = 0
+    const char *qs, *ps;       // their scale rows
+    const char *uh, *ul, *be;  // adapter operands (aliases of q0 / p0 without adapter)
+    int q_rows, p_rows;        // valid tokens / outputs (1..256)
+    int nkb1;                  // adapter blocks per half (0: no adapter)
+    int total;                 // blocks of the tile: nkb0 + 2 * nkb1
+    int row0, n0;
+    int valid;
+};
+
+__device__ __forceinline__ Tile load_tile(const Params &p, int id, int n_work)
+{
+    Tile t;
+    t.valid = id < n_work;
+    const int cid = t.valid ? id : 0;
+    const int tm = cid / p.n_tiles_n, tn = cid - tm * p.n_tiles_n;
+    const int e = uniform(p.tile_expert[tm]);
+    t.row0 = uniform(p.tile_row0[tm]);
+    t.q_rows = uniform(p.tile_rows[tm]);
+    t.n0 = tn * BT;
+    t.p_rows = min(BT, p.d_out - t.n0);
+    const int64_t ldq = p.d_in, lds = p.d_in / 32, ldu = (int64_t)p.r * 2;
+    t.q0 = p.xq + (int64_t)t.row0 * ldq;
+    t.p0 = p.Wq + (int64_t)t.n0 * ldq;
+    t.qs = p.xs + (int64_t)t.row0 * lds;
+    t.ps = p.Ws + (int64_t)t.n0 * lds;
+    const int re = min(p.r, uniform(p.tile_rank[tm]));
+    const bool lora = e >= 0 && re > 0;
+    t.nkb1 = lora ? (re + KB16 - 1) / KB16 : 0;
+    t.total = p.d_in / KB8 + 2 * t.nkb1;
+    t.uh = lora ? p.u_hi + (int64_t)t.row0 * ldu : t.q0;
+    t.ul = lora ? p.u_lo + (int64_t)t.row0 * ldu : t.q0;
+    t.be = lora ? p.B_stack + ((int64_t)e * p.d_out + t.n0) * ldu : t.p0;
+    return t;
+}
+
+struct Frag {
+    uint4 lo, hi;
+};
+
+}  // namespace mxs
+
+__global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p)
+{
+    using namespace mxs;
+    extern __shared__ __align__(16) char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = uniform(threadIdx.x >> 6);
+    const int wp = wave / WQ, wq = wave % WQ;
+    const int r = lane & 31, h = lane >> 5;
+
+    // work list of this workgroup: the 8 XCDs take workgroups round-robin, each
+    // XCD owns one contiguous band of tile ids, and its workgroups stride
+    // through the band together (neighbouring ids share W or x panels in L2)
+    const int n_work = uniform(*p.n_tiles) * p.n_tiles_n;
+    const int per = (n_work + 7) >> 3;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, nslot = gridDim.x >> 3;
+    const int band_end = min((xcd + 1) * per, n_work);
+    int id = xcd * per + slot;
+    if (id >= band_end) return;
+
+    const int nkb0 = p.d_in / KB8;
+    const uint32_t ldq = (uint32_t)p.d_in, lds = (uint32_t)p.d_in / 32u, ldu = (uint32_t)p.r * 2u;
+
+    // DMA mapping: instruction j of a wave fills LDS rows (wave*4 + j)*8 .. +8 of
+    // an operand tile; the lane fetches logical 16-byte chunk (lane%8) ^ swz(row),
+    // swz(row) = (row >> 1) & 7 with row = wave*32 + j*8 + lane/8: only j's parity matters
+    const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8) + (lane >> 3));   // + 8 * j
+    uint32_t dma_c16[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) dma_c16[j] = (uint32_t)(((lane & 7) ^ (((j * 8 + (lane >> 3)) >> 1) & 7)) * 16);
+
+    // Starts the loads of block b of tile t into `stage`.
+    auto issue = [&](const Tile &t, int b, char *stage) __attribute__((always_inline)) {
+        const bool base = b < nkb0;
+        const int jb = b - nkb0;
+        const bool hi = jb < t.nkb1;
+        const char *pq = base ? t.q0 : (hi ? t.uh : t.ul);
+        const char *pp = base ? t.p0 : t.be;
+        const uint32_t ld = base ? ldq : ldu;
+        const int kb = base ? b : (hi ? jb : jb - t.nkb1);
+        const uint32_t kbyte = (uint32_t)kb * ROWB;
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            const uint32_t row = min(dma_row + 8u * j, (uint32_t)(t.p_rows - 1));
+            const uint32_t off = __umul24(row, ld) + dma_c16[j & 1] + kbyte;
+            __builtin_amdgcn_global_load_lds(MOIN_GPTR(pp + off), MOIN_LPTR(stage + (wave * LOADS + j) * 1024),
+                                             16, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            const uint32_t row = min(dma_row + 8u * j, (uint32_t)(t.q_rows - 1));
+            const uint32_t off = __umul24(row, ld) + dma_c16[j & 1] + kbyte;
+            __builtin_amdgcn_global_load_lds(MOIN_GPTR(pq + off),
+                                             MOIN_LPTR(stage + OP_BYTES + (wave * LOADS + j) * 1024), 16, 0, 0);
+        }
+    };
+
+    // Scale words of block b of tile t for this lane's rows: the four scale bytes
+    // of a row's 128 steps are one aligned word; lanes with h = 1 shift theirs by
+    // one byte so that byte 2 * ks is the one the MFMA of k-step ks takes from
+    // this lane.  Adapter blocks have none.
+    auto fetch_scales = [&](const Tile &t, int b, uint32_t (&dst)[NSC]) __attribute__((always_inline)) {
+        if (b < nkb0) {
+#pragma unroll
+            for (int i = 0; i < FP; ++i) {
+                const uint32_t row = min((uint32_t)(wp * (FP * 32) + i * 32 + r), (uint32_t)(t.p_rows - 1));
+                dst[i] = *reinterpret_cast<const uint32_t *>(t.ps + (__umul24(row, lds) + (uint32_t)b * 4u));
+            }
+#pragma unroll
+            for (int j = 0; j < FQ; ++j) {
+                const uint32_t row = min((uint32_t)(wq * (FQ * 32) + j * 32 + r), (uint32_t)(t.q_rows - 1));
+                dst[FP + j] = *reinterpret_cast<const uint32_t *>(t.qs + (__umul24(row, lds) + (uint32_t)b * 4u));
+            }
+        }
+    };
+
+    // fragment addresses: patch bases are multiples of 32 rows, so the swizzle
+    // depends on r only.  A compute unit's two waves per SIMD leave each 256
+    // registers, half of them accumulators, so only the output-side fragments
+    // (fp) and the last token-side one (fq3) are double-buffered; the other
+    // token-side fragments are re-read for the next k-step as soon as the two
+    // MFMAs that use them have been issued.
+    const int f = (r >> 1) & 7;
+    const int offP = (wp * (FP * 32) + r) * ROWB;
+    const int offQ = OP_BYTES + (wq * (FQ * 32) + r) * ROWB;
+    Frag fp[2][FP], fq[FQ - 1], fq3[2];
+    auto read_frag = [&](Frag &g, const char *row, int ks) __attribute__((always_inline)) {
+        g.lo = *reinterpret_cast<const uint4 *>(row + (((ks * 4 + h) ^ f) & 7) * 16);
+        g.hi = *reinterpret_cast<const uint4 *>(row + (((ks * 4 + 2 + h) ^ f) & 7) * 16);
+    };
+    // fragments of k-step ks that have a buffer of their own for that k-step
+    auto read_buffered = [&](const char *stage, int ks) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < FP; ++i) read_frag(fp[ks][i], stage + offP + i * 32 * ROWB, ks);
+        read_frag(fq3[ks], stage + offQ + (FQ - 1) * 32 * ROWB, ks);
+    };
+    f32x16_t acc[FP][FQ];
+    // scale bytes: sc_ld as loaded (one word per fragment row: the four bytes of the
+    // row's 128 steps), sc_nxt / sc_cur regrouped so that word n holds, for
+    // fragments 2n and 2n + 1, the bytes this lane feeds the MFMAs of k-steps 0, 1
+    uint32_t sc_ld[NSC], sc_nxt[NSC / 2], sc_cur[NSC / 2];
+    const uint32_t pick = h ? 0x07050301u : 0x06040200u;
+    auto regroup = [&](uint32_t (&dst)[NSC / 2]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int n = 0; n < NSC / 2; ++n) dst[n] = __builtin_amdgcn_perm(sc_ld[2 * n + 1], sc_ld[2 * n], pick);
+    };
+    auto frag8 = [](const Frag &g) __attribute__((always_inline)) {
+        return i32x8_t{(int)g.lo.x, (int)g.lo.y, (int)g.lo.z, (int)g.lo.w,
+                       (int)g.hi.x, (int)g.hi.y, (int)g.hi.z, (int)g.hi.w};
+    };
+    // acc[i][J] += (fragment pair) for i = 0..FP-1: one scaled FP8 MFMA each on a
+    // base block, two bf16 MFMAs each on an adapter block
+    auto mfma_pair = [&](auto base_tag, auto ks_tag, auto j_tag, const Frag &q) __attribute__((always_inline)) {
+        constexpr bool BASE = decltype(base_tag)::value;
+        constexpr int KS = decltype(ks_tag)::value, J = decltype(j_tag)::value;
+        if constexpr (BASE) {
+            acc[0][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                frag8(fp[KS][0]), frag8(q), acc[0][J], 0, 0, KS, (int)sc_cur[0], (J & 1) * 2 + KS,
+                (int)sc_cur[1 + J / 2]);
+            acc[1][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                frag8(fp[KS][1]), frag8(q), acc[1][J], 0, 0, 2 + KS, (int)sc_cur[0], (J & 1) * 2 + KS,
+                (int)sc_cur[1 + J / 2]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < FP; ++i) {
+                acc[i][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8_t, fp[KS][i].lo), __builtin_bit_cast(bf16x8_t, q.lo), acc[i][J], 0, 0, 0);
+                acc[i][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8_t, fp[KS][i].hi), __builtin_bit_cast(bf16x8_t, q.hi), acc[i][J], 0, 0, 0);
+            }
+        }
+    };
+    static_assert(FP == 2 && FQ == 4, "the MFMA order below is written out for 2 x 4 accumulators");
+    // One k-step: MFMAs of token fragments 0..2, each followed (RELOAD) by the read
+    // of the same fragment for the next k-step from `next_rows` at k-step NKS,
+    // then those of fragment 3.
+    auto kstep = [&](auto base_tag, auto ks_tag, auto reload_tag, const char *next_stage, int nks)
+                     __attribute__((always_inline)) {
+        constexpr bool RELOAD = decltype(reload_tag)::value;
+        constexpr int KS = decltype(ks_tag)::value;
+        mfma_pair(base_tag, ks_tag, std::integral_constant<int, 0>{}, fq[0]);
+        if constexpr (RELOAD) read_frag(fq[0], next_stage + offQ + 0 * 32 * ROWB, nks);
+        mfma_pair(base_tag, ks_tag, std::integral_constant<int, 1>{}, fq[1]);
+        if constexpr (RELOAD) read_frag(fq[1], next_stage + offQ + 1 * 32 * ROWB, nks);
+        mfma_pair(base_tag, ks_tag, std::integral_constant<int, 2>{}, fq[2]);
+        if constexpr (RELOAD) read_frag(fq[2], next_stage + offQ + 2 * 32 * ROWB, nks);
+        mfma_pair(base_tag, ks_tag, std::integral_constant<int, 3>{}, fq3[KS]);
+    };
+
+    Tile cur = load_tile(p, id, band_end);
+    id += nslot;
+    Tile nxt = load_tile(p, id, band_end);
+
+    // fetch cursor: tile and block index of the next block to request
+    Tile pft = cur;
+    int pfb = 2;
+
+    // One block of the stream.  BASE: kind of this block; ISSUE: a block two
+    // positions ahead exists and is fetched into the stage this block frees;
+    // READ: a next block exists.
+    auto body = [&](int s, auto base_tag, auto issue_tag, auto read_tag) __attribute__((always_inline)) {
+        constexpr bool ISSUE = decltype(issue_tag)::value, READ = decltype(read_tag)::value;
+        char *st_cur = smem + (s & 1) * STAGE_BYTES;
+        const char *st_nxt = smem + ((s + 1) & 1) * STAGE_BYTES;
+        read_buffered(st_cur, 1);
+        kstep(base_tag, std::integral_constant<int, 0>{}, std::true_type{}, st_cur, 1);
+        // own share of block s+1 (and its scales) has landed and every fragment of
+        // block s is in registers; past the barrier that holds for all waves
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        regroup(sc_nxt);
+        if constexpr (ISSUE) {
+            // the fetch cursor runs two blocks ahead; when it has used up its tile
+            // it moves to the tile after the one being computed (checked here, not
+            // when the cursor advances: by now `nxt` is that tile in every case)
+            if (pfb == pft.total) {
+                pft = nxt;
+                pfb = 0;
+            }
+            fetch_scales(pft, pfb, sc_ld);
+            issue(pft, pfb, st_cur);
+            ++pfb;
+        }
+        if constexpr (READ) read_buffered(st_nxt, 0);
+        kstep(base_tag, std::integral_constant<int, 1>{}, read_tag, st_nxt, 0);
+#pragma unroll
+        for (int n = 0; n < NSC / 2; ++n) sc_cur[n] = sc_nxt[n];
+    };
+
+    // prologue of the stream: two blocks in flight, the first one's leading fragments read
+    fetch_scales(cur, 0, sc_ld);
+    issue(cur, 0, smem);
+    regroup(sc_cur);
+    fetch_scales(cur, 1, sc_ld);
+    issue(cur, 1, smem + STAGE_BYTES);   // every tile has at least two blocks
+    wait_vm_then_barrier<2 * LOADS>();
+    read_buffered(smem, 0);
+#pragma unroll
+    for (int j = 0; j < FQ - 1; ++j) read_frag(fq[j], smem + offQ + j * 32 * ROWB, 0);
+
+    int s = 0;
+    for (;;) {
+#pragma unroll
+        for (int i = 0; i < FP; ++i)
+#pragma unroll
+            for (int j = 0; j < FQ; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+        const int total = cur.total;
+        // blocks that are followed by two more in the stream, then the stream's last two
+        const int full = nxt.valid ? total : total - 2;
+        int b = 0;
+        for (; b < min(full, nkb0); ++b, ++s) body(s, std::true_type{}, std::true_type{}, std::true_type{});
+        for (; b < full; ++b, ++s) body(s, std::false_type{}, std::true_type{}, std::true_type{});
+        if (!nxt.valid) {
+            if (b < nkb0) body(s, std::true_type{}, std::false_type{}, std::true_type{});
+            else body(s, std::false_type{}, std::false_type{}, std::true_type{});
+            ++s, ++b;
+            if (b < nkb0) body(s, std::true_type{}, std::false_type{}, std::false_type{});
+            else body(s, std::false_type{}, std::false_type{}, std::false_type{});
+            ++s, ++b;
+        }
+
+        // epilogue through the wave's private 4 KB of LDS beyond the two stages
+        // (which the next tile's loads are already filling)
+        stream_epilogue<FP, FQ>(smem + SMEM_STAGES + wave * SCR_BYTES, acc, p.y, p.y_f32, p.d_out, cur.row0,
+                                cur.n0, cur.q_rows, cur.p_rows, wp, wq, lane);
+        if (!nxt.valid) break;
+        cur = nxt;
+        id += nslot;
+        nxt = load_tile(p, id, band_end);
+    }
+}
+
+hipError_t prepare_mx_kernels()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_mx_stream_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, mxs::SMEM_BYTES);
+}
+
+bool mx_stream_kernel_fits(int d_in, int r) { return d_in % 128 == 0 && d_in >= 256 && r % 64 == 0; }
+
+hipError_t launch_linear_mx_stream(const PlanView &pv, const MxLinearArgs &a, int n_cus, hipStream_t stream_)
+{
+    mxs::Params p;
+    p.xq = (const char *)a.xq; p.Wq = (const char *)a.Wq; p.xs = (const char *)a.xs; p.Ws = (const char *)a.Ws;
+    p.B_stack = (const char *)a.lin.B_stack;
+    p.u_hi = (const char *)a.lin.u_hi; p.u_lo = (const char *)a.lin.u_lo;
+    p.y = (char *)a.lin.y;
+    p.tile_row0 = pv.tile_row0; p.tile_rows = pv.tile_rows; p.tile_expert = pv.tile_expert;
+    p.tile_rank = pv.tile_rank;
+    p.n_tiles = pv.n_tiles;
+    p.d_in = a.lin.d_in; p.d_out = a.lin.d_out; p.r = a.lin.r;
+    p.n_tiles_n = (a.lin.d_out + mxs::BT - 1) / mxs::BT;
+    p.y_f32 = a.lin.y_f32;
+    // one workgroup per compute unit (the LDS footprint allows no more), fewer
+    // when the batch has fewer tiles than that; always a multiple of 8
+    const int64_t max_work = (int64_t)pv.max_tiles * p.n_tiles_n;
+    int64_t grid = n_cus > 0 ? n_cus : 256;
+    if (grid > max_work) grid = max_work;
+    grid = (grid + 7) / 8 * 8;
+    hipLaunchKernelGGL(linear_mx_stream_kernel, dim3((unsigned)grid), dim3(mxs::NT), mxs::SMEM_BYTES, stream_, p);
+    return hipGetLastError();
+}
+
+}  // namespace moin

@@ -22,7 +22,7 @@ MOIN_ROUTE_RETAINED_ONLY = 1
 (K_PLAN, K_SHRINK, K_LINEAR, K_ROUTE, K_ROUTE_AUX, K_DECODE_SHRINK, K_DECODE_EXPAND, K_DECODE_BASE,
  K_KMEANS_SORT, K_KMEANS_SUM, K_KMEANS_FINAL) = range(11)
 KERNEL_NAMES = ["plan", "shrink", "linear", "route", "route_aux", "decode_shrink", "decode_expand",
-                "decode_base", "kmeans_sort", "kmeans_sum", "kmeans_final"]
+                "decode_base", "kmeans_sort", "kmeans_sum", "kmeans_final", "mx_quant", "mx_linear"]
 
 EXPORTS = [
     "moin_create", "moin_destroy", "moin_strerror", "moin_check", "moin_route", "moin_histogram",
@@ -31,6 +31,7 @@ EXPORTS = [
     "moin_kmeans_update", "moin_retain_clusters", "moin_kmeans_fit",
     "moin_cache_create", "moin_cache_destroy", "moin_cache_add_stack", "moin_cache_admit",
     "moin_cache_table", "moin_cache_stats", "moin_lora_linear_ranked", "moin_plan_build_ranked",
+    "moin_mx_quantize", "moin_lora_linear_mx",
 ]
 CACHE_STATS = ["batches", "seq_hits", "seq_misses", "loads", "evictions", "overflows", "bytes"]
 
@@ -68,6 +69,9 @@ def load() -> ctypes.CDLL:
                                      c.c_float, vp, c.c_int, vp]
     lib.moin_lora_linear_ranked.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp, i32, i32, i32, i32, vp,
                                             c.c_float, vp, c.c_int, vp]
+    lib.moin_mx_quantize.argtypes = [vp, vp, i64, i64, vp, vp, vp]
+    lib.moin_lora_linear_mx.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp, vp, i32, i32, i32, i32, vp,
+                                        c.c_float, vp, c.c_int, vp]
     lib.moin_plan_build_ranked.argtypes = [vp, vp, vp, vp, i32, i64, i32, vp, vp]
     lib.moin_plan_create.argtypes = [vp, c.POINTER(vp)]
     lib.moin_plan_destroy.argtypes = [vp]
@@ -239,6 +243,49 @@ def moin_lora_linear(ctx: Context, x: torch.Tensor, seq_offsets: torch.Tensor,
         _dev_ptr(expert_ids, "expert_ids", torch.int32) if S else None, S, T, _dev_ptr(W, "W", bf),
         _dev_ptr(A_stack, "A_stack", bf), _dev_ptr(B_stack, "B_stack", bf), E, d_in, d_out, r,
         float(scale), _dev_ptr(y, "y") if T else None, ydt, _stream_ptr(stream)), "moin_lora_linear")
+    return y
+
+
+def moin_mx_quantize(ctx: Context, values: torch.Tensor, stream=None):
+    """MXFP8 codes ``[rows, cols]`` and scale bytes ``[rows, cols/32]`` (both uint8)
+    of a bf16 matrix, quantised in blocks of 32 along the last axis."""
+    if values.dim() != 2 or values.shape[1] % 32 or values.shape[1] == 0:
+        raise ValueError("values [rows, cols] with cols a positive multiple of 32 expected")
+    rows, cols = values.shape
+    codes = torch.empty((rows, cols), dtype=torch.uint8, device=values.device)
+    scales = torch.empty((rows, cols // 32), dtype=torch.uint8, device=values.device)
+    _ck(load().moin_mx_quantize(ctx._h, _dev_ptr(values, "values", torch.bfloat16) if rows else None, rows, cols,
+                                _dev_ptr(codes, "codes") if rows else None,
+                                _dev_ptr(scales, "scales") if rows else None, _stream_ptr(stream)),
+        "moin_mx_quantize")
+    return codes, scales
+
+
+def moin_lora_linear_mx(ctx: Context, x: torch.Tensor, seq_offsets: torch.Tensor, expert_ids: torch.Tensor,
+                        Wq: torch.Tensor, Ws: torch.Tensor, A_stack: Optional[torch.Tensor],
+                        B_stack: Optional[torch.Tensor], scale: float, y_dtype=torch.bfloat16,
+                        out: Optional[torch.Tensor] = None, stream=None,
+                        rank_of_expert: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Routed LoRA linear on an MXFP8 base (``Wq``, ``Ws`` from ``moin_mx_quantize``)."""
+    if x.dim() != 2 or Wq.dim() != 2 or x.shape[1] != Wq.shape[1]:
+        raise ValueError("x [T,d_in] and Wq [d_out,d_in] expected")
+    if Wq.dtype != torch.uint8 or Ws.dtype != torch.uint8 or tuple(Ws.shape) != (Wq.shape[0], Wq.shape[1] // 32):
+        raise ValueError("Wq [d_out,d_in] / Ws [d_out,d_in/32] uint8 expected")
+    d_in, d_out, E, r = _stack_dims(Wq, A_stack, B_stack)
+    if rank_of_expert is not None and rank_of_expert.numel() != E:
+        raise ValueError("rank_of_expert must have E entries")
+    S = expert_ids.numel()
+    if seq_offsets.numel() != S + 1:
+        raise ValueError("seq_offsets must have S+1 entries")
+    T = x.shape[0]
+    y, ydt = _y_out(x, d_out, y_dtype, out)
+    bf = torch.bfloat16
+    _ck(load().moin_lora_linear_mx(
+        ctx._h, _dev_ptr(x, "x", bf) if T else None, _dev_ptr(seq_offsets, "seq_offsets", torch.int32),
+        _dev_ptr(expert_ids, "expert_ids", torch.int32) if S else None, S, T, _dev_ptr(Wq, "Wq", torch.uint8),
+        _dev_ptr(Ws, "Ws", torch.uint8), _dev_ptr(A_stack, "A_stack", bf), _dev_ptr(B_stack, "B_stack", bf),
+        E, d_in, d_out, r, _dev_ptr(rank_of_expert, "rank_of_expert", torch.int32), float(scale),
+        _dev_ptr(y, "y") if T else None, ydt, _stream_ptr(stream)), "moin_lora_linear_mx")
     return y
 
 

@@ -1,0 +1,189 @@
+"""GPU parity of the quantised-base path (moin_mx_quantize, moin_lora_linear_mx,
+through the C ABI) against the CPU oracle: codes and scale bytes bit for bit, the
+layer element by element to the same bars as the bf16 layer (both sides use the
+same codes, so only the fp32 accumulation differs)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2410_09687_amd import moin
+from paper_2410_09687_amd import workloads as wl
+from tests import gpu_common as gc
+
+pytestmark = pytest.mark.gpu
+
+
+def _bits_tensor(bits: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).cuda()
+
+
+def _quantize_both(bits: np.ndarray, what: str):
+    print(f"[gpu] mx_quantize {what} {bits.shape}", flush=True)
+    codes, scales = moin.moin_mx_quantize(gc.ctx(), _bits_tensor(bits))
+    gc.ctx().check()
+    rc, rs = oracle.mx_quantize(bits)
+    assert np.array_equal(scales.cpu().numpy(), rs), f"{what}: scale bytes differ"
+    got = codes.cpu().numpy()
+    bad = np.argwhere(got != rc)
+    assert bad.size == 0, f"{what}: {len(bad)} codes differ, first at {bad[0]}: {got[tuple(bad[0])]} vs {rc[tuple(bad[0])]}"
+    return got, rs
+
+
+def test_quantiser_every_bf16_value_and_every_scale():
+    # every finite bf16 pattern once, in blocks whose leading element pins the scale: for
+    # each candidate, a block led by the largest power of two not above 448 times a spread of
+    # magnitudes, so elements land in the normal, subnormal, clamped and zero ranges
+    allb = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    finite = allb[(allb & 0x7F80) != 0x7F80]
+    rng = np.random.default_rng(21)
+    rows = []
+    for shift in (0, 3, 9, 20):
+        perm = rng.permutation(finite)
+        pad = (-perm.size) % 32
+        rows.append(np.concatenate([perm, np.zeros(pad, np.uint16)]).reshape(-1, 32))
+        # the same values next to a leader 2^shift times their own largest
+        v = rows[-1].copy()
+        lead = ((v[:, 1:] & 0x7FFF).max(axis=1).astype(np.int32) + (shift << 7)).clip(0, 0x7F7F).astype(np.uint16)
+        v[:, 0] = lead
+        rows.append(v)
+    blocks = np.concatenate(rows, axis=0)
+    blocks = blocks[: blocks.shape[0] // 4 * 4].reshape(-1, 128)
+    _quantize_both(blocks, "all bf16 values")
+
+
+def test_quantiser_shapes_zero_blocks_and_signs():
+    rng = np.random.default_rng(22)
+    for rows, cols in ((1, 32), (3, 96), (257, 2048), (64, 5632)):
+        x = rng.standard_normal((rows, cols)) * np.exp2(rng.integers(-12, 12, size=(rows, 1)))
+        x[0, :32] = 0.0
+        if rows > 2:
+            x[2, 32:64] = -0.0
+        bits = wl.bf16_bits(torch.from_numpy(x).to(torch.bfloat16))
+        codes, scales = _quantize_both(bits, f"{rows}x{cols}")
+        assert scales[0, 0] == 127 and not codes[0, :32].any()
+    # empty input and bad shapes
+    c, s = moin.moin_mx_quantize(gc.ctx(), torch.empty((0, 64), dtype=torch.bfloat16, device="cuda"))
+    assert c.shape == (0, 64) and s.shape == (0, 2)
+    with pytest.raises(ValueError):
+        moin.moin_mx_quantize(gc.ctx(), torch.zeros((4, 48), dtype=torch.bfloat16, device="cuda"))
+
+
+def _case(name, d_in, d_out, r, E, lens, ids=None, seed=1234, dist="uniform"):
+    w = wl.LinearWorkload(name, d_in, d_out, r, E, lens, dist, scale=2.0, seed=seed)
+    return wl.make_linear_inputs(w, "cuda", expert_ids=None if ids is None else np.asarray(ids, np.int32))
+
+
+def _mx_check(inp, what, rows=None, rank_of_expert=None):
+    ctx = gc.ctx()
+    Wq, Ws = moin.moin_mx_quantize(ctx, inp.W)
+    A, B, ids = wl.compact_stacks(inp)
+    ranks_c = None
+    ranks_t = None
+    if rank_of_expert is not None:
+        ranks_t = torch.from_numpy(np.asarray(rank_of_expert, np.int32)).cuda()
+        used = np.unique(inp.expert_ids.cpu().numpy())
+        ranks_c = np.asarray(rank_of_expert, np.int32)[used[used >= 0]]
+    ref = oracle.lora_linear_mx(wl.bf16_bits(inp.x), inp.seq_offsets.cpu().numpy(), ids, Wq.cpu().numpy(),
+                                Ws.cpu().numpy(), A, B, inp.wl.scale, rows=rows, rank_of_expert=ranks_c)
+    out = {}
+    for dt in (torch.bfloat16, torch.float32):
+        print(f"[gpu] mx linear {what} y={dt}", flush=True)
+        y = moin.moin_lora_linear_mx(ctx, inp.x, inp.seq_offsets, inp.expert_ids, Wq, Ws, inp.A_stack,
+                                     inp.B_stack, inp.wl.scale, y_dtype=dt, rank_of_expert=ranks_t)
+        ctx.check()
+        out[dt] = y
+        gc.compare_linear(y, ref, rows=rows, what=f"{what}/{dt}")
+    assert torch.equal(out[torch.bfloat16].view(torch.int16),
+                       out[torch.float32].to(torch.bfloat16).view(torch.int16)), f"{what}: bf16 output is not RNE(fp32)"
+    return out[torch.float32], ref
+
+
+def test_mx_linear_ragged_tiles_mixed_adapters():
+    lens = [300, 1, 0, 257, 255, 512, 77, 256, 3, 640]
+    ids = [3, 0, 5, -1, 3, 6, 2, 2, -1, 1]
+    inp = _case("mx_ragged", 384, 520, 128, 7, lens, ids, seed=31)
+    y, ref = _mx_check(inp, "mx_ragged")
+    # the quantised base is what was computed: the bf16 layer's result is measurably different
+    plain = gc.oracle_rows(inp)
+    assert np.abs(plain - ref).max() > 10 * gc.MAX_ABS_F32 or np.linalg.norm(plain - ref) / np.linalg.norm(ref) > 1e-2
+
+
+def test_mx_linear_one_tile_and_minimum_depth():
+    inp = _case("mx_one_tile", 256, 64, 64, 2, [130], [1], seed=32)
+    _mx_check(inp, "mx_one_tile")
+    inp = _case("mx_base_only", 256, 136, 64, 2, [600, 500], [-1, -1], seed=33)
+    _mx_check(inp, "mx_base_only")
+    # no stacks at all
+    Wq, Ws = moin.moin_mx_quantize(gc.ctx(), inp.W)
+    y0 = moin.moin_lora_linear_mx(gc.ctx(), inp.x, inp.seq_offsets, inp.expert_ids, Wq, Ws, None, None, 2.0)
+    y1 = moin.moin_lora_linear_mx(gc.ctx(), inp.x, inp.seq_offsets, inp.expert_ids, Wq, Ws, inp.A_stack,
+                                  inp.B_stack, 2.0)
+    gc.ctx().check()
+    assert torch.equal(y0, y1)
+
+
+def test_mx_linear_many_tiles_per_workgroup_and_decode_sized_batches():
+    rng = np.random.default_rng(35)
+    lens = rng.integers(1, 300, size=700).tolist()
+    ids = rng.integers(-1, 4, size=700).tolist()
+    inp = _case("mx_many", 256, 1024, 64, 4, lens, ids, seed=34)
+    _mx_check(inp, "mx_many")
+    # single-token sequences (the tiled path serves every batch size)
+    w = wl.LinearWorkload("mx_dec", 512, 520, 64, 50, [1] * 96, "zipf", 1.1, 2.0, seed=36)
+    _mx_check(wl.make_linear_inputs(w, "cuda"), "mx_decode_96x1")
+
+
+def test_mx_linear_block_scales_of_very_different_size():
+    # rows and column blocks of x and W scaled by powers of two far apart: a wrong scale
+    # byte or a scale applied to the wrong block shows as an error of orders of magnitude
+    inp = _case("mx_scales", 512, 264, 64, 3, [200, 150, 90], [0, -1, 2], seed=37)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    sx = torch.exp2(torch.randint(-6, 7, (inp.x.shape[0], 512 // 32), generator=g, device="cuda").float())
+    sw = torch.exp2(torch.randint(-6, 7, (264, 512 // 32), generator=g, device="cuda").float())
+    inp.x = (inp.x.float().view(-1, 16, 32) * sx[:, :, None]).view(-1, 512).to(torch.bfloat16)
+    inp.W = (inp.W.float().view(264, 16, 32) * sw[:, :, None]).view(264, 512).to(torch.bfloat16)
+    ctx = gc.ctx()
+    Wq, Ws = moin.moin_mx_quantize(ctx, inp.W)
+    A, B, ids = wl.compact_stacks(inp)
+    ref = oracle.lora_linear_mx(wl.bf16_bits(inp.x), inp.seq_offsets.cpu().numpy(), ids, Wq.cpu().numpy(),
+                                Ws.cpu().numpy(), A, B, inp.wl.scale)
+    y = moin.moin_lora_linear_mx(ctx, inp.x, inp.seq_offsets, inp.expert_ids, Wq, Ws, inp.A_stack, inp.B_stack,
+                                 inp.wl.scale, y_dtype=torch.float32)
+    ctx.check()
+    got = y.double().cpu().numpy()
+    fro = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+    # magnitudes span 2^+-12 here, so the absolute bar is taken relative to each row's size
+    rel_row = np.abs(got - ref).max(axis=1) / np.abs(ref).max(axis=1)
+    assert fro <= gc.REL_FRO_MAX and rel_row.max() <= 1e-2, (fro, rel_row.max())
+
+
+def test_mx_linear_with_per_expert_ranks():
+    lens = [300, 200, 257, 100, 280]
+    ids = [0, 1, 2, -1, 3]
+    inp = _case("mx_ranks", 256, 264, 128, 4, lens, ids, seed=38)
+    ranks = [128, 64, 8, 0]
+    # beyond its rank an adapter holds NaN where nothing may be read
+    for e, k in enumerate(ranks):
+        inp.A_stack[e, k:] = float("nan")
+        inp.B_stack[e, :, (k + 63) // 64 * 64:] = float("nan")
+        inp.B_stack[e, :, k:(k + 63) // 64 * 64] = 0
+    _mx_check(inp, "mx_ranks", rank_of_expert=ranks)
+
+
+def test_mx_linear_rejects_unsupported_shapes():
+    ctx = gc.ctx()
+    inp = _case("mx_bad", 192, 64, 64, 2, [40], [0], seed=39)
+    Wq = torch.zeros((64, 192), dtype=torch.uint8, device="cuda")
+    Ws = torch.zeros((64, 6), dtype=torch.uint8, device="cuda")
+    with pytest.raises(moin.MoinError):
+        moin.moin_lora_linear_mx(ctx, inp.x, inp.seq_offsets, inp.expert_ids, Wq, Ws, inp.A_stack, inp.B_stack, 1.0)
+    inp = _case("mx_bad_r", 256, 64, 24, 2, [40], [0], seed=40)
+    Wq = torch.zeros((64, 256), dtype=torch.uint8, device="cuda")
+    Ws = torch.zeros((64, 8), dtype=torch.uint8, device="cuda")
+    with pytest.raises(moin.MoinError):
+        moin.moin_lora_linear_mx(ctx, inp.x, inp.seq_offsets, inp.expert_ids, Wq, Ws, inp.A_stack, inp.B_stack, 1.0)
+    # empty batch: nothing to do
+    y = moin.moin_lora_linear_mx(ctx, inp.x[:0], torch.zeros(1, dtype=torch.int32, device="cuda"),
+                                 torch.zeros(0, dtype=torch.int32, device="cuda"), Wq, Ws, None, None, 1.0)
+    assert y.shape == (0, 64)
