@@ -32,6 +32,7 @@ from paper_2410_09687_amd import moin  # noqa: E402
 from paper_2410_09687_amd import workloads as wl  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_FP8_TFLOPS = 5000.0    # MI355X dense FP8 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 # HBM-side bytes per launch of the dominant (linear) kernel on configs[1], from the
@@ -269,6 +270,48 @@ def bench_ranks(ctx, steps, warmup, n_draws=8):
     return out
 
 
+def bench_mx(ctx, steps, warmup):
+    """configs[1] projection on a quantised base ("Future Works", quantising the base model):
+    W held as MXFP8 codes + scales, x quantised per call, base product on the block-scaled FP8
+    matrix cores, adapter term in bf16.  Same step as the headline (route + plan + layer);
+    the roofline is that of the main kernel against the dense FP8 peak."""
+    w = wl.config_prefill()
+    inp = wl.make_linear_inputs(w, "cuda")
+    rw = wl.RouteWorkload("c1_route", N=w.S, K=w.E, D=768, dtype="bf16", normalise=True, seed=w.seed)
+    rin = wl.make_route_inputs(rw, "cuda")
+    slots = torch.arange(w.E, dtype=torch.int32, device="cuda")
+    y = torch.empty((w.T, w.d_out), dtype=torch.bfloat16, device="cuda")
+    Wq, Ws = moin.moin_mx_quantize(ctx, inp.W, blocked=True)
+
+    def step():
+        eids, _, _ = moin.moin_route(ctx, rin.emb, rin.centroids, slot_of_centroid=slots,
+                                     want_centroid_ids=False, want_counts=True)
+        moin.moin_lora_linear_mx(ctx, inp.x, inp.seq_offsets, eids, Wq, Ws, inp.A_stack, inp.B_stack,
+                                 w.scale, out=y)
+
+    ms, _ = timed_region(step, steps, warmup)
+    ctx.check()
+    kt = kernel_times(ctx, step, steps)
+    lin = kt.get("mx_linear", {"avg_ms": float("nan")})
+    qt = kt.get("mx_quant", {"avg_ms": float("nan")})
+    base_flops = 2.0 * w.T * w.d_in * w.d_out
+    lora_flops = 2.0 * w.T * w.r * w.d_out
+    # the kernel mixes FP8 (base) and bf16 (adapter) MFMA work: time at peak = sum of both
+    t_peak = base_flops / (PEAK_FP8_TFLOPS * 1e12) + 2.0 * lora_flops / (PEAK_BF16_TFLOPS * 1e12)
+    achieved = (base_flops + lora_flops) / (lin["avg_ms"] * 1e-3) / 1e12
+    q_bytes = w.T * w.d_in * (2.0 + 1.0 + 1.0 / 32)
+    return {"ms_per_step": ms, "TFLOPs_whole_step": (w.flops() + rw.flops()) / (ms * 1e-3) / 1e12,
+            "tokens_per_s": w.T / (ms * 1e-3),
+            "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s",
+                         "frac": achieved / PEAK_FP8_TFLOPS,
+                         "frac_of_mixed_peak": t_peak / (lin["avg_ms"] * 1e-3),
+                         "kernel": "linear_mx_stream_kernel (MXFP8 base + bf16 adapter term)",
+                         "avg_launch_ms": lin["avg_ms"]},
+            "quantise_x": {"avg_launch_ms": qt["avg_ms"], "algorithmic_bytes": q_bytes,
+                           "GBps": q_bytes / (qt["avg_ms"] * 1e-3) / 1e9},
+            "kernels": kt}
+
+
 def bench_cache(ctx, n_batches=48, n_slots=512):
     """Decode batches of the gate projection (configs[2] shapes) served through the adapter
     residency cache: 5000 experts in pinned host memory, `n_slots` resident, one request
@@ -365,8 +408,8 @@ def main():
                     help="first run a plain device copy of this many MiB (3 times): the known-size "
                          "kernel that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--also", default="decode,router,layer,kmeans",
-                    help="comma list of extra workloads to report: decode,router,layer,kmeans,cache,ranks "
-                         "(or 'none'); cache (it pins 10 GB of host memory) and ranks are not in the default list")
+                    help="comma list of extra workloads to report: decode,router,layer,kmeans,cache,ranks,mx "
+                         "(or 'none'); cache (it pins 10 GB of host memory) ranks and mx are not in the default list")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU figure exists)",
@@ -398,6 +441,8 @@ def main():
         res["cache"] = bench_cache(ctx)
     if "ranks" in extra:
         res["ranks"] = bench_ranks(ctx, args.steps, args.warmup)
+    if "mx" in extra:
+        res["mx"] = bench_mx(ctx, args.steps, args.warmup)
     ctx.close()
     print(json.dumps(res))
 

@@ -170,18 +170,23 @@ int moin_lora_linear_ranked(moin_ctx *ctx, const void *x, const int32_t *seq_off
  * hold FP8 E4M3 elements (bias 7, largest finite value 448, no infinities).
  *
  * moin_mx_quantize: src [rows, cols] bf16 (DEVICE, finite values; NaN / Inf give
- * unspecified codes) -> codes [rows, cols] uint8 and scales [rows, cols/32] uint8
- * (both DEVICE, caller-owned).  E = max(0, floor(log2 max|v|) + 127 - 8) per
+ * unspecified codes) -> codes [rows, cols] uint8 and rows * cols/32 scale bytes
+ * (both DEVICE, caller-owned).  scale_layout: MOIN_MX_ROW_MAJOR, scales
+ * [rows, cols/32]; MOIN_MX_BLOCKED (cols a multiple of 128), scales
+ * [cols/128, rows, 4] -- the four bytes of 128 consecutive values of a row form
+ * one word and the words of consecutive rows are adjacent, which is the order
+ * the matrix-core kernel fetches them in.  E = max(0, floor(log2 max|v|) + 127 - 8) per
  * block (127 for a block of zeros); element = v / 2^(E-127) rounded to nearest
  * even, magnitudes above 448 clamped to 448.  cols must be a multiple of 32,
  * src and codes 16-byte aligned.  Used once for the weight. */
+enum { MOIN_MX_ROW_MAJOR = 0, MOIN_MX_BLOCKED = 1 };
 int moin_mx_quantize(moin_ctx *ctx, const void *src, int64_t rows, int64_t cols, void *codes,
-                     void *scales, void *stream);
+                     void *scales, int32_t scale_layout, void *stream);
 
 /* moin_lora_linear_ranked on a quantised base:
  *     y = dq(q(x)) dq(Wq)^T + scale * (x A_e^T) B_e^T
- * Wq [d_out, d_in] codes and Ws [d_out, d_in/32] scales come from
- * moin_mx_quantize; x [T, d_in] is bf16 and is quantised by the call itself
+ * Wq [d_out, d_in] codes and Ws (MOIN_MX_BLOCKED layout: [d_in/128, d_out, 4])
+ * come from moin_mx_quantize; x [T, d_in] is bf16 and is quantised by the call itself
  * (into the context's workspace) for the base product, which runs on the
  * block-scaled FP8 matrix cores; the adapter term uses the bf16 x and the bf16
  * stacks exactly as in moin_lora_linear.  rank_of_expert may be NULL.

@@ -355,7 +355,7 @@ int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, 
         timed(ctx, MOIN_K_SHRINK, stream, [&] { return launch_prefill_shrink(pv, a, stream); }) != hipSuccess)
         return MOIN_EHIP;
     if (timed(ctx, MOIN_K_MX_QUANT, stream, [&] {
-            return launch_mx_quantize(x, pv.T, d_in, const_cast<void *>(m.xq), const_cast<void *>(m.xs), stream);
+            return launch_mx_quantize(x, pv.T, d_in, const_cast<void *>(m.xq), const_cast<void *>(m.xs), 1, stream);
         }) != hipSuccess)
         return MOIN_EHIP;
     if (timed(ctx, MOIN_K_MX_LINEAR, stream, [&] {
@@ -614,17 +614,20 @@ int moin_lora_linear(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
 }
 
 int moin_mx_quantize(moin_ctx *ctx, const void *src, int64_t rows, int64_t cols, void *codes,
-                     void *scales, void *stream)
+                     void *scales, int32_t scale_layout, void *stream)
 {
     if (!ctx || rows < 0 || cols <= 0 || cols % 32) return MOIN_EINVAL;
+    if (scale_layout != MOIN_MX_ROW_MAJOR && scale_layout != MOIN_MX_BLOCKED) return MOIN_EINVAL;
+    if (scale_layout == MOIN_MX_BLOCKED && cols % 128) return MOIN_EINVAL;
     if (rows == 0) return MOIN_OK;
-    if (!src || !codes || !scales || misaligned(src, 16) || misaligned(codes, 16)) return MOIN_EINVAL;
+    if (!src || !codes || !scales || misaligned(src, 16) || misaligned(codes, 16) || misaligned(scales, 4))
+        return MOIN_EINVAL;
     if (rows > (int64_t)1 << 40 || cols > (int64_t)1 << 30 || rows * cols > (int64_t)1 << 46)
         return MOIN_EINVAL;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return MOIN_EHIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (timed(ctx, MOIN_K_MX_QUANT, st, [&] { return launch_mx_quantize(src, rows, cols, codes, scales, st); }) !=
+    if (timed(ctx, MOIN_K_MX_QUANT, st, [&] { return launch_mx_quantize(src, rows, cols, codes, scales, scale_layout == MOIN_MX_BLOCKED, st); }) !=
         hipSuccess)
         return MOIN_EHIP;
     return MOIN_OK;

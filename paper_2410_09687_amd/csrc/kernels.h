@@ -144,12 +144,13 @@ hipError_t launch_kmeans_retain(const int *counts, int K, int min_count, int *sl
 // Quantised base (mx.hip): MXFP8 codes and scale bytes of the base operands.
 struct MxLinearArgs {
     LinearArgs lin;        // x (bf16, for the shrink), A_stack, B_stack, u_hi / u_lo, y; lin.W unused
-    const void *xq, *xs;   // [T, d_in] codes, [T, d_in / 32] scales (workspace, written per call)
-    const void *Wq, *Ws;   // [d_out, d_in] codes, [d_out, d_in / 32] scales
+    const void *xq, *xs;   // [T, d_in] codes, [d_in / 128, T, 4] scales (workspace, written per call)
+    const void *Wq, *Ws;   // [d_out, d_in] codes, [d_in / 128, d_out, 4] scales
 };
-// codes / scales of rows x cols bf16 values (cols a multiple of 32, rows * cols of 8)
+// codes / scales of rows x cols bf16 values (cols a multiple of 32); scales row-major
+// [rows, cols / 32] or, blocked (cols a multiple of 128), [cols / 128, rows, 4]
 hipError_t launch_mx_quantize(const void *src, int64_t rows, int64_t cols, void *codes, void *scales,
-                              hipStream_t stream);
+                              int blocked, hipStream_t stream);
 bool mx_stream_kernel_fits(int d_in, int r);
 hipError_t launch_linear_mx_stream(const PlanView &pv, const MxLinearArgs &a, int n_cus, hipStream_t stream);
 int compute_units();   // of the current device

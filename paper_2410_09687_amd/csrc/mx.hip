@@ -37,8 +37,16 @@ typedef int i32x8_t __attribute__((ext_vector_type(8)));
 // least 0; 127 for a block of zeros), the quotient value / scale is a product
 // with a power of two, magnitudes above 448 clamp to 448, and the conversion
 // rounds to nearest even.
+//
+// Scale bytes go out row-major ([rows, cols / 32], BLOCKED = false) or in the
+// order the main kernel fetches them (BLOCKED = true, cols a multiple of 128):
+// [cols / 128, rows, 4], i.e. the four bytes of a row's 128 consecutive values as
+// one word, words of consecutive rows adjacent, so that 32 lanes holding 32
+// consecutive rows fetch one 128-byte line.
+template <bool BLOCKED>
 __global__ __launch_bounds__(256) void mx_quantize_kernel(const uint4 *__restrict__ src, uint2 *__restrict__ codes,
-                                                          uint8_t *__restrict__ scales, int64_t n8)
+                                                          uint8_t *__restrict__ scales, int64_t n8, int64_t rows,
+                                                          int cols8)
 {
     const int64_t stride = (int64_t)gridDim.x * 256;
     for (int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x; t < n8; t += stride) {
@@ -68,20 +76,38 @@ __global__ __launch_bounds__(256) void mx_quantize_kernel(const uint4 *__restric
         int hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[4], f[5], 0, false);
         hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], hi, true);
         codes[t] = make_uint2((uint32_t)lo, (uint32_t)hi);
-        if ((t & 3) == 0) scales[t >> 2] = (uint8_t)E;
+        if constexpr (BLOCKED) {
+            // n8 is a multiple of 16 here: the 16 lanes of a row's 128 values are active together
+            uint32_t word = (uint32_t)E;
+            word |= (uint32_t)__shfl_down(E, 4) << 8;
+            word |= (uint32_t)__shfl_down(E, 8) << 16;
+            word |= (uint32_t)__shfl_down(E, 12) << 24;
+            if ((t & 15) == 0) {
+                const int64_t row = t / cols8, kb = (t - row * cols8) >> 4;
+                reinterpret_cast<uint32_t *>(scales)[kb * rows + row] = word;
+            }
+        } else {
+            if ((t & 3) == 0) scales[t >> 2] = (uint8_t)E;
+        }
     }
 }
 
 hipError_t launch_mx_quantize(const void *src, int64_t rows, int64_t cols, void *codes, void *scales,
-                              hipStream_t stream)
+                              int blocked, hipStream_t stream)
 {
     const int64_t n8 = rows * cols / 8;
     if (n8 <= 0) return hipSuccess;
+    if (blocked && cols % 128) return hipErrorInvalidValue;
     int64_t grid = (n8 + 255) / 256;
     if (grid > 256 * 32) grid = 256 * 32;
-    hipLaunchKernelGGL(mx_quantize_kernel, dim3((unsigned)grid), dim3(256), 0, stream,
-                       reinterpret_cast<const uint4 *>(src), reinterpret_cast<uint2 *>(codes),
-                       reinterpret_cast<uint8_t *>(scales), n8);
+    if (blocked)
+        hipLaunchKernelGGL(mx_quantize_kernel<true>, dim3((unsigned)grid), dim3(256), 0, stream,
+                           reinterpret_cast<const uint4 *>(src), reinterpret_cast<uint2 *>(codes),
+                           reinterpret_cast<uint8_t *>(scales), n8, rows, (int)(cols / 8));
+    else
+        hipLaunchKernelGGL(mx_quantize_kernel<false>, dim3((unsigned)grid), dim3(256), 0, stream,
+                           reinterpret_cast<const uint4 *>(src), reinterpret_cast<uint2 *>(codes),
+                           reinterpret_cast<uint8_t *>(scales), n8, rows, (int)(cols / 8));
     return hipGetLastError();
 }
 
@@ -106,7 +132,8 @@ constexpr int NSC = FP + FQ;         // scale words a lane holds per block
 
 struct Params {
     const char *xq, *Wq;             // FP8 codes [T, d_in], [d_out, d_in]
-    const char *xs, *Ws;             // scale bytes [T, d_in / 32], [d_out, d_in / 32]
+    const char *xs, *Ws;             // scale words [d_in / 128, T], [d_in / 128, d_out] (four bytes each)
+    int64_t T;
     const char *B_stack, *u_hi, *u_lo;
     char *y;
     const int *tile_row0, *tile_rows, *tile_expert, *tile_rank, *n_tiles;
@@ -118,7 +145,6 @@ struct Params {
 // Everything a tile needs, all wave-uniform.
 struct Tile {
     const char *q0, *p0;       // code rows of the tile's tokens / outputs at k = 0
-    const char *qs, *ps;       // their scale rows
     const char *uh, *ul, *be;  // adapter operands (aliases of q0 / p0 without adapter)
     int q_rows, p_rows;        // valid tokens / outputs (1..256)
     int nkb1;                  // adapter blocks per half (0: no adapter)
@@ -138,11 +164,9 @@ __device__ __forceinline__ Tile load_tile(const Params &p, int id, int n_work)
     t.q_rows = uniform(p.tile_rows[tm]);
     t.n0 = tn * BT;
     t.p_rows = min(BT, p.d_out - t.n0);
-    const int64_t ldq = p.d_in, lds = p.d_in / 32, ldu = (int64_t)p.r * 2;
+    const int64_t ldq = p.d_in, ldu = (int64_t)p.r * 2;
     t.q0 = p.xq + (int64_t)t.row0 * ldq;
     t.p0 = p.Wq + (int64_t)t.n0 * ldq;
-    t.qs = p.xs + (int64_t)t.row0 * lds;
-    t.ps = p.Ws + (int64_t)t.n0 * lds;
     const int re = min(p.r, uniform(p.tile_rank[tm]));
     const bool lora = e >= 0 && re > 0;
     t.nkb1 = lora ? (re + KB16 - 1) / KB16 : 0;
@@ -153,9 +177,9 @@ __device__ __forceinline__ Tile load_tile(const Params &p, int id, int n_work)
     return t;
 }
 
-struct Frag {
-    uint4 lo, hi;
-};
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+// One MFMA operand of a lane: 16 + 16 bytes of a row (see the head of the file).
+typedef i32x8_t Frag;
 
 }  // namespace mxs
 
@@ -179,15 +203,17 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
     if (id >= band_end) return;
 
     const int nkb0 = p.d_in / KB8;
-    const uint32_t ldq = (uint32_t)p.d_in, lds = (uint32_t)p.d_in / 32u, ldu = (uint32_t)p.r * 2u;
+    const uint32_t ldq = (uint32_t)p.d_in, ldu = (uint32_t)p.r * 2u;
 
-    // DMA mapping: instruction j of a wave fills LDS rows (wave*4 + j)*8 .. +8 of
-    // an operand tile; the lane fetches logical 16-byte chunk (lane%8) ^ swz(row),
-    // swz(row) = (row >> 1) & 7 with row = wave*32 + j*8 + lane/8: only j's parity matters
-    const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8) + (lane >> 3));   // + 8 * j
-    uint32_t dma_c16[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) dma_c16[j] = (uint32_t)(((lane & 7) ^ (((j * 8 + (lane >> 3)) >> 1) & 7)) * 16);
+    // Per-lane constants of the loads are recomputed from the lane id at every use
+    // (through an opaque copy, so that the compiler does not keep two dozen of them
+    // alive across the main loop, where they would be spilled and reloaded through
+    // the same counter the DMA loads are waited on).
+    auto fresh_lane = [&]() __attribute__((always_inline)) {
+        int v = lane;
+        asm volatile("; lane id, rematerialised" : "+v"(v));
+        return v;
+    };
 
     // Starts the loads of block b of tile t into `stage`.
     auto issue = [&](const Tile &t, int b, char *stage) __attribute__((always_inline)) {
@@ -199,74 +225,88 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
         const uint32_t ld = base ? ldq : ldu;
         const int kb = base ? b : (hi ? jb : jb - t.nkb1);
         const uint32_t kbyte = (uint32_t)kb * ROWB;
+        // DMA mapping: instruction j of a wave fills LDS rows (wave*4 + j)*8 .. +8 of
+        // an operand tile; the lane fetches logical 16-byte chunk (lane%8) ^ swz(row),
+        // swz(row) = (row >> 1) & 7 with row = wave*32 + j*8 + lane/8, which is
+        // lane/16 for even j and lane/16 + 4 for odd j
+        const uint32_t ln = (uint32_t)fresh_lane();
+        const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8)) + (ln >> 3);   // + 8 * j
+        const uint32_t c16 = (((ln & 7) ^ (ln >> 4)) * 16) + kbyte;           // odd j: ^ 64
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) {
             const uint32_t row = min(dma_row + 8u * j, (uint32_t)(t.p_rows - 1));
-            const uint32_t off = __umul24(row, ld) + dma_c16[j & 1] + kbyte;
+            const uint32_t off = __umul24(row, ld) + (c16 ^ ((j & 1) ? 64u : 0u));
             __builtin_amdgcn_global_load_lds(MOIN_GPTR(pp + off), MOIN_LPTR(stage + (wave * LOADS + j) * 1024),
                                              16, 0, 0);
         }
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) {
             const uint32_t row = min(dma_row + 8u * j, (uint32_t)(t.q_rows - 1));
-            const uint32_t off = __umul24(row, ld) + dma_c16[j & 1] + kbyte;
+            const uint32_t off = __umul24(row, ld) + (c16 ^ ((j & 1) ? 64u : 0u));
             __builtin_amdgcn_global_load_lds(MOIN_GPTR(pq + off),
                                              MOIN_LPTR(stage + OP_BYTES + (wave * LOADS + j) * 1024), 16, 0, 0);
         }
     };
 
-    // Scale words of block b of tile t for this lane's rows: the four scale bytes
-    // of a row's 128 steps are one aligned word; lanes with h = 1 shift theirs by
-    // one byte so that byte 2 * ks is the one the MFMA of k-step ks takes from
-    // this lane.  Adapter blocks have none.
+    // Scale words of block b of tile t for this lane's rows (one word = the four
+    // scale bytes of a row's 128 steps; the words of a block's rows are adjacent, so
+    // each load of a wave is one 128-byte line).  Adapter blocks have none.
     auto fetch_scales = [&](const Tile &t, int b, uint32_t (&dst)[NSC]) __attribute__((always_inline)) {
         if (b < nkb0) {
+            const uint32_t r = (uint32_t)fresh_lane() & 31u;
+            const char *ps = p.Ws + ((int64_t)b * p.d_out + t.n0) * 4;
+            const char *qs = p.xs + ((int64_t)b * p.T + t.row0) * 4;
 #pragma unroll
             for (int i = 0; i < FP; ++i) {
-                const uint32_t row = min((uint32_t)(wp * (FP * 32) + i * 32 + r), (uint32_t)(t.p_rows - 1));
-                dst[i] = *reinterpret_cast<const uint32_t *>(t.ps + (__umul24(row, lds) + (uint32_t)b * 4u));
+                const uint32_t row = min((uint32_t)(wp * (FP * 32) + i * 32) + r, (uint32_t)(t.p_rows - 1));
+                dst[i] = *reinterpret_cast<const uint32_t *>(ps + row * 4u);
             }
 #pragma unroll
             for (int j = 0; j < FQ; ++j) {
-                const uint32_t row = min((uint32_t)(wq * (FQ * 32) + j * 32 + r), (uint32_t)(t.q_rows - 1));
-                dst[FP + j] = *reinterpret_cast<const uint32_t *>(t.qs + (__umul24(row, lds) + (uint32_t)b * 4u));
+                const uint32_t row = min((uint32_t)(wq * (FQ * 32) + j * 32) + r, (uint32_t)(t.q_rows - 1));
+                dst[FP + j] = *reinterpret_cast<const uint32_t *>(qs + row * 4u);
             }
         }
     };
 
-    // fragment addresses: patch bases are multiples of 32 rows, so the swizzle
-    // depends on r only.  A compute unit's two waves per SIMD leave each 256
-    // registers, half of them accumulators, so only the output-side fragments
-    // (fp) and the last token-side one (fq3) are double-buffered; the other
-    // token-side fragments are re-read for the next k-step as soon as the two
-    // MFMAs that use them have been issued.
-    const int f = (r >> 1) & 7;
-    const int offP = (wp * (FP * 32) + r) * ROWB;
-    const int offQ = OP_BYTES + (wq * (FQ * 32) + r) * ROWB;
+    // byte (16 h) ^ (16 f) of the lane's row in the first patch of each operand; the
+    // row offsets are multiples of 128, so chunk c = 4 ks + 2 * half of that row is
+    // at (this address) ^ (16 c)
+    // (recomputed at each use like the load constants: f = (lane >> 1) & 7, r = lane & 31)
+    auto lane_off = [&]() __attribute__((always_inline)) {
+        const int ln = fresh_lane();
+        return ((ln & 31) * ROWB) | ((((ln >> 5) ^ (ln >> 1)) & 7) * 16);
+    };
+    const int baseP = wp * (FP * 32) * ROWB, baseQ = OP_BYTES + wq * (FQ * 32) * ROWB;   // wave-uniform
     Frag fp[2][FP], fq[FQ - 1], fq3[2];
-    auto read_frag = [&](Frag &g, const char *row, int ks) __attribute__((always_inline)) {
-        g.lo = *reinterpret_cast<const uint4 *>(row + (((ks * 4 + h) ^ f) & 7) * 16);
-        g.hi = *reinterpret_cast<const uint4 *>(row + (((ks * 4 + 2 + h) ^ f) & 7) * 16);
+    auto read_frag = [&](Frag &g, const char *stage_, int row, int ks) __attribute__((always_inline)) {
+        const i32x4_t lo = *reinterpret_cast<const i32x4_t *>(stage_ + (row ^ (ks * 64)));
+        const i32x4_t hi = *reinterpret_cast<const i32x4_t *>(stage_ + (row ^ (ks * 64 + 32)));
+        g = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
     // fragments of k-step ks that have a buffer of their own for that k-step
     auto read_buffered = [&](const char *stage, int ks) __attribute__((always_inline)) {
+        const int lo_ = lane_off();
+        const int offP = baseP + lo_, offQ = baseQ + lo_;
 #pragma unroll
-        for (int i = 0; i < FP; ++i) read_frag(fp[ks][i], stage + offP + i * 32 * ROWB, ks);
-        read_frag(fq3[ks], stage + offQ + (FQ - 1) * 32 * ROWB, ks);
+        for (int i = 0; i < FP; ++i) read_frag(fp[ks][i], stage, offP + i * 32 * ROWB, ks);
+        read_frag(fq3[ks], stage, offQ + (FQ - 1) * 32 * ROWB, ks);
     };
     f32x16_t acc[FP][FQ];
     // scale bytes: sc_ld as loaded (one word per fragment row: the four bytes of the
     // row's 128 steps), sc_nxt / sc_cur regrouped so that word n holds, for
     // fragments 2n and 2n + 1, the bytes this lane feeds the MFMAs of k-steps 0, 1
     uint32_t sc_ld[NSC], sc_nxt[NSC / 2], sc_cur[NSC / 2];
-    const uint32_t pick = h ? 0x07050301u : 0x06040200u;
     auto regroup = [&](uint32_t (&dst)[NSC / 2]) __attribute__((always_inline)) {
+        const uint32_t pick = 0x06040200u + (uint32_t)(fresh_lane() >> 5) * 0x01010101u;   // h = 1: 0x07050301
 #pragma unroll
         for (int n = 0; n < NSC / 2; ++n) dst[n] = __builtin_amdgcn_perm(sc_ld[2 * n + 1], sc_ld[2 * n], pick);
     };
-    auto frag8 = [](const Frag &g) __attribute__((always_inline)) {
-        return i32x8_t{(int)g.lo.x, (int)g.lo.y, (int)g.lo.z, (int)g.lo.w,
-                       (int)g.hi.x, (int)g.hi.y, (int)g.hi.z, (int)g.hi.w};
+    auto lo16 = [](const Frag &g) __attribute__((always_inline)) {
+        return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(g, g, 0, 1, 2, 3));
+    };
+    auto hi16 = [](const Frag &g) __attribute__((always_inline)) {
+        return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(g, g, 4, 5, 6, 7));
     };
     // acc[i][J] += (fragment pair) for i = 0..FP-1: one scaled FP8 MFMA each on a
     // base block, two bf16 MFMAs each on an adapter block
@@ -275,21 +315,22 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
         constexpr int KS = decltype(ks_tag)::value, J = decltype(j_tag)::value;
         if constexpr (BASE) {
             acc[0][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                frag8(fp[KS][0]), frag8(q), acc[0][J], 0, 0, KS, (int)sc_cur[0], (J & 1) * 2 + KS,
+                fp[KS][0], q, acc[0][J], 0, 0, KS, (int)sc_cur[0], (J & 1) * 2 + KS,
                 (int)sc_cur[1 + J / 2]);
             acc[1][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                frag8(fp[KS][1]), frag8(q), acc[1][J], 0, 0, 2 + KS, (int)sc_cur[0], (J & 1) * 2 + KS,
+                fp[KS][1], q, acc[1][J], 0, 0, 2 + KS, (int)sc_cur[0], (J & 1) * 2 + KS,
                 (int)sc_cur[1 + J / 2]);
         } else {
 #pragma unroll
             for (int i = 0; i < FP; ++i) {
                 acc[i][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    __builtin_bit_cast(bf16x8_t, fp[KS][i].lo), __builtin_bit_cast(bf16x8_t, q.lo), acc[i][J], 0, 0, 0);
+                    lo16(fp[KS][i]), lo16(q), acc[i][J], 0, 0, 0);
                 acc[i][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    __builtin_bit_cast(bf16x8_t, fp[KS][i].hi), __builtin_bit_cast(bf16x8_t, q.hi), acc[i][J], 0, 0, 0);
+                    hi16(fp[KS][i]), hi16(q), acc[i][J], 0, 0, 0);
             }
         }
     };
+    auto pin = [](f32x16_t &a, f32x16_t &b) __attribute__((always_inline)) { asm volatile("" : "+v"(a), "+v"(b)); };
     static_assert(FP == 2 && FQ == 4, "the MFMA order below is written out for 2 x 4 accumulators");
     // One k-step: MFMAs of token fragments 0..2, each followed (RELOAD) by the read
     // of the same fragment for the next k-step from `next_rows` at k-step NKS,
@@ -298,13 +339,23 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
                      __attribute__((always_inline)) {
         constexpr bool RELOAD = decltype(reload_tag)::value;
         constexpr int KS = decltype(ks_tag)::value;
+        const int offQ = RELOAD ? baseQ + lane_off() : 0;
+        // MFMAs have no side effects, so nothing but data flow orders them against
+        // the LDS reads and the barrier: pin() makes each pair's results an operand
+        // of an (empty) volatile asm, which keeps the pair ahead of the re-read that
+        // overwrites its operand registers (moved up, the re-read would need
+        // registers of its own) and ahead of the barrier
         mfma_pair(base_tag, ks_tag, std::integral_constant<int, 0>{}, fq[0]);
-        if constexpr (RELOAD) read_frag(fq[0], next_stage + offQ + 0 * 32 * ROWB, nks);
+        pin(acc[0][0], acc[1][0]);
+        if constexpr (RELOAD) read_frag(fq[0], next_stage, offQ + 0 * 32 * ROWB, nks);
         mfma_pair(base_tag, ks_tag, std::integral_constant<int, 1>{}, fq[1]);
-        if constexpr (RELOAD) read_frag(fq[1], next_stage + offQ + 1 * 32 * ROWB, nks);
+        pin(acc[0][1], acc[1][1]);
+        if constexpr (RELOAD) read_frag(fq[1], next_stage, offQ + 1 * 32 * ROWB, nks);
         mfma_pair(base_tag, ks_tag, std::integral_constant<int, 2>{}, fq[2]);
-        if constexpr (RELOAD) read_frag(fq[2], next_stage + offQ + 2 * 32 * ROWB, nks);
+        pin(acc[0][2], acc[1][2]);
+        if constexpr (RELOAD) read_frag(fq[2], next_stage, offQ + 2 * 32 * ROWB, nks);
         mfma_pair(base_tag, ks_tag, std::integral_constant<int, 3>{}, fq3[KS]);
+        pin(acc[0][3], acc[1][3]);
     };
 
     Tile cur = load_tile(p, id, band_end);
@@ -328,6 +379,7 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
         // block s is in registers; past the barrier that holds for all waves
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
         regroup(sc_nxt);
+        __builtin_amdgcn_sched_barrier(0);   // the words it reads have landed: keep it ahead of the new loads
         if constexpr (ISSUE) {
             // the fetch cursor runs two blocks ahead; when it has used up its tile
             // it moves to the tile after the one being computed (checked here, not
@@ -355,7 +407,7 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
     wait_vm_then_barrier<2 * LOADS>();
     read_buffered(smem, 0);
 #pragma unroll
-    for (int j = 0; j < FQ - 1; ++j) read_frag(fq[j], smem + offQ + j * 32 * ROWB, 0);
+    for (int j = 0; j < FQ - 1; ++j) read_frag(fq[j], smem, baseQ + lane_off() + j * 32 * ROWB, 0);
 
     int s = 0;
     for (;;) {
@@ -411,6 +463,7 @@ hipError_t launch_linear_mx_stream(const PlanView &pv, const MxLinearArgs &a, in
     p.tile_rank = pv.tile_rank;
     p.n_tiles = pv.n_tiles;
     p.d_in = a.lin.d_in; p.d_out = a.lin.d_out; p.r = a.lin.r;
+    p.T = pv.T;
     p.n_tiles_n = (a.lin.d_out + mxs::BT - 1) / mxs::BT;
     p.y_f32 = a.lin.y_f32;
     // one workgroup per compute unit (the LDS footprint allows no more), fewer

@@ -69,7 +69,7 @@ def load() -> ctypes.CDLL:
                                      c.c_float, vp, c.c_int, vp]
     lib.moin_lora_linear_ranked.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp, i32, i32, i32, i32, vp,
                                             c.c_float, vp, c.c_int, vp]
-    lib.moin_mx_quantize.argtypes = [vp, vp, i64, i64, vp, vp, vp]
+    lib.moin_mx_quantize.argtypes = [vp, vp, i64, i64, vp, vp, i32, vp]
     lib.moin_lora_linear_mx.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp, vp, i32, i32, i32, i32, vp,
                                         c.c_float, vp, c.c_int, vp]
     lib.moin_plan_build_ranked.argtypes = [vp, vp, vp, vp, i32, i64, i32, vp, vp]
@@ -246,17 +246,23 @@ def moin_lora_linear(ctx: Context, x: torch.Tensor, seq_offsets: torch.Tensor,
     return y
 
 
-def moin_mx_quantize(ctx: Context, values: torch.Tensor, stream=None):
-    """MXFP8 codes ``[rows, cols]`` and scale bytes ``[rows, cols/32]`` (both uint8)
-    of a bf16 matrix, quantised in blocks of 32 along the last axis."""
+def moin_mx_quantize(ctx: Context, values: torch.Tensor, blocked: bool = False, stream=None):
+    """MXFP8 codes ``[rows, cols]`` and scale bytes (both uint8) of a bf16 matrix,
+    quantised in blocks of 32 along the last axis.  Scales are ``[rows, cols/32]``,
+    or with ``blocked`` (cols a multiple of 128) ``[cols/128, rows, 4]``, the layout
+    ``moin_lora_linear_mx`` wants for the weight."""
     if values.dim() != 2 or values.shape[1] % 32 or values.shape[1] == 0:
         raise ValueError("values [rows, cols] with cols a positive multiple of 32 expected")
     rows, cols = values.shape
+    if blocked and cols % 128:
+        raise ValueError("the blocked scale layout needs cols to be a multiple of 128")
     codes = torch.empty((rows, cols), dtype=torch.uint8, device=values.device)
-    scales = torch.empty((rows, cols // 32), dtype=torch.uint8, device=values.device)
+    scales = torch.empty((cols // 128, rows, 4) if blocked else (rows, cols // 32), dtype=torch.uint8,
+                         device=values.device)
     _ck(load().moin_mx_quantize(ctx._h, _dev_ptr(values, "values", torch.bfloat16) if rows else None, rows, cols,
                                 _dev_ptr(codes, "codes") if rows else None,
-                                _dev_ptr(scales, "scales") if rows else None, _stream_ptr(stream)),
+                                _dev_ptr(scales, "scales") if rows else None, 1 if blocked else 0,
+                                _stream_ptr(stream)),
         "moin_mx_quantize")
     return codes, scales
 
@@ -266,11 +272,12 @@ def moin_lora_linear_mx(ctx: Context, x: torch.Tensor, seq_offsets: torch.Tensor
                         B_stack: Optional[torch.Tensor], scale: float, y_dtype=torch.bfloat16,
                         out: Optional[torch.Tensor] = None, stream=None,
                         rank_of_expert: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """Routed LoRA linear on an MXFP8 base (``Wq``, ``Ws`` from ``moin_mx_quantize``)."""
+    """Routed LoRA linear on an MXFP8 base (``Wq``, ``Ws`` from ``moin_mx_quantize(..., blocked=True)``)."""
     if x.dim() != 2 or Wq.dim() != 2 or x.shape[1] != Wq.shape[1]:
         raise ValueError("x [T,d_in] and Wq [d_out,d_in] expected")
-    if Wq.dtype != torch.uint8 or Ws.dtype != torch.uint8 or tuple(Ws.shape) != (Wq.shape[0], Wq.shape[1] // 32):
-        raise ValueError("Wq [d_out,d_in] / Ws [d_out,d_in/32] uint8 expected")
+    if Wq.dtype != torch.uint8 or Ws.dtype != torch.uint8 or Wq.shape[1] % 128 or \
+            tuple(Ws.shape) != (Wq.shape[1] // 128, Wq.shape[0], 4):
+        raise ValueError("Wq [d_out,d_in] / Ws [d_in/128,d_out,4] (blocked layout) uint8 expected")
     d_in, d_out, E, r = _stack_dims(Wq, A_stack, B_stack)
     if rank_of_expert is not None and rank_of_expert.numel() != E:
         raise ValueError("rank_of_expert must have E entries")

@@ -18,12 +18,23 @@ def _bits_tensor(bits: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).cuda()
 
 
+def _row_major(scales_blocked: torch.Tensor) -> np.ndarray:
+    """[cols/128, rows, 4] -> [rows, cols/32] (a pure change of layout)."""
+    nb, rows, _ = scales_blocked.shape
+    return scales_blocked.permute(1, 0, 2).reshape(rows, nb * 4).cpu().numpy()
+
+
 def _quantize_both(bits: np.ndarray, what: str):
     print(f"[gpu] mx_quantize {what} {bits.shape}", flush=True)
     codes, scales = moin.moin_mx_quantize(gc.ctx(), _bits_tensor(bits))
     gc.ctx().check()
     rc, rs = oracle.mx_quantize(bits)
     assert np.array_equal(scales.cpu().numpy(), rs), f"{what}: scale bytes differ"
+    if bits.shape[1] % 128 == 0:
+        codes_b, scales_b = moin.moin_mx_quantize(gc.ctx(), _bits_tensor(bits), blocked=True)
+        gc.ctx().check()
+        assert torch.equal(codes_b, codes), f"{what}: codes depend on the scale layout"
+        assert np.array_equal(_row_major(scales_b), rs), f"{what}: blocked scale bytes differ"
     got = codes.cpu().numpy()
     bad = np.argwhere(got != rc)
     assert bad.size == 0, f"{what}: {len(bad)} codes differ, first at {bad[0]}: {got[tuple(bad[0])]} vs {rc[tuple(bad[0])]}"
@@ -54,7 +65,7 @@ def test_quantiser_every_bf16_value_and_every_scale():
 
 def test_quantiser_shapes_zero_blocks_and_signs():
     rng = np.random.default_rng(22)
-    for rows, cols in ((1, 32), (3, 96), (257, 2048), (64, 5632)):
+    for rows, cols in ((1, 32), (3, 96), (5, 128), (257, 2048), (64, 5632)):
         x = rng.standard_normal((rows, cols)) * np.exp2(rng.integers(-12, 12, size=(rows, 1)))
         x[0, :32] = 0.0
         if rows > 2:
@@ -65,8 +76,16 @@ def test_quantiser_shapes_zero_blocks_and_signs():
     # empty input and bad shapes
     c, s = moin.moin_mx_quantize(gc.ctx(), torch.empty((0, 64), dtype=torch.bfloat16, device="cuda"))
     assert c.shape == (0, 64) and s.shape == (0, 2)
+    # a weight too shallow for the kernel (d_in = 128) is refused by the library itself
+    inp = _case("mx_shallow", 128, 64, 64, 2, [40], [0], seed=41)
+    Wq, Ws = moin.moin_mx_quantize(gc.ctx(), inp.W, blocked=True)
+    with pytest.raises(moin.MoinError):
+        moin.moin_lora_linear_mx(gc.ctx(), inp.x, inp.seq_offsets, inp.expert_ids, Wq, Ws, inp.A_stack,
+                                 inp.B_stack, 1.0)
     with pytest.raises(ValueError):
         moin.moin_mx_quantize(gc.ctx(), torch.zeros((4, 48), dtype=torch.bfloat16, device="cuda"))
+    with pytest.raises(ValueError):
+        moin.moin_mx_quantize(gc.ctx(), torch.zeros((4, 96), dtype=torch.bfloat16, device="cuda"), blocked=True)
 
 
 def _case(name, d_in, d_out, r, E, lens, ids=None, seed=1234, dist="uniform"):
@@ -76,7 +95,7 @@ def _case(name, d_in, d_out, r, E, lens, ids=None, seed=1234, dist="uniform"):
 
 def _mx_check(inp, what, rows=None, rank_of_expert=None):
     ctx = gc.ctx()
-    Wq, Ws = moin.moin_mx_quantize(ctx, inp.W)
+    Wq, Ws = moin.moin_mx_quantize(ctx, inp.W, blocked=True)
     A, B, ids = wl.compact_stacks(inp)
     ranks_c = None
     ranks_t = None
@@ -85,7 +104,7 @@ def _mx_check(inp, what, rows=None, rank_of_expert=None):
         used = np.unique(inp.expert_ids.cpu().numpy())
         ranks_c = np.asarray(rank_of_expert, np.int32)[used[used >= 0]]
     ref = oracle.lora_linear_mx(wl.bf16_bits(inp.x), inp.seq_offsets.cpu().numpy(), ids, Wq.cpu().numpy(),
-                                Ws.cpu().numpy(), A, B, inp.wl.scale, rows=rows, rank_of_expert=ranks_c)
+                                _row_major(Ws), A, B, inp.wl.scale, rows=rows, rank_of_expert=ranks_c)
     out = {}
     for dt in (torch.bfloat16, torch.float32):
         print(f"[gpu] mx linear {what} y={dt}", flush=True)
@@ -115,7 +134,7 @@ def test_mx_linear_one_tile_and_minimum_depth():
     inp = _case("mx_base_only", 256, 136, 64, 2, [600, 500], [-1, -1], seed=33)
     _mx_check(inp, "mx_base_only")
     # no stacks at all
-    Wq, Ws = moin.moin_mx_quantize(gc.ctx(), inp.W)
+    Wq, Ws = moin.moin_mx_quantize(gc.ctx(), inp.W, blocked=True)
     y0 = moin.moin_lora_linear_mx(gc.ctx(), inp.x, inp.seq_offsets, inp.expert_ids, Wq, Ws, None, None, 2.0)
     y1 = moin.moin_lora_linear_mx(gc.ctx(), inp.x, inp.seq_offsets, inp.expert_ids, Wq, Ws, inp.A_stack,
                                   inp.B_stack, 2.0)
@@ -144,10 +163,10 @@ def test_mx_linear_block_scales_of_very_different_size():
     inp.x = (inp.x.float().view(-1, 16, 32) * sx[:, :, None]).view(-1, 512).to(torch.bfloat16)
     inp.W = (inp.W.float().view(264, 16, 32) * sw[:, :, None]).view(264, 512).to(torch.bfloat16)
     ctx = gc.ctx()
-    Wq, Ws = moin.moin_mx_quantize(ctx, inp.W)
+    Wq, Ws = moin.moin_mx_quantize(ctx, inp.W, blocked=True)
     A, B, ids = wl.compact_stacks(inp)
     ref = oracle.lora_linear_mx(wl.bf16_bits(inp.x), inp.seq_offsets.cpu().numpy(), ids, Wq.cpu().numpy(),
-                                Ws.cpu().numpy(), A, B, inp.wl.scale)
+                                _row_major(Ws), A, B, inp.wl.scale)
     y = moin.moin_lora_linear_mx(ctx, inp.x, inp.seq_offsets, inp.expert_ids, Wq, Ws, inp.A_stack, inp.B_stack,
                                  inp.wl.scale, y_dtype=torch.float32)
     ctx.check()
@@ -175,12 +194,12 @@ def test_mx_linear_rejects_unsupported_shapes():
     ctx = gc.ctx()
     inp = _case("mx_bad", 192, 64, 64, 2, [40], [0], seed=39)
     Wq = torch.zeros((64, 192), dtype=torch.uint8, device="cuda")
-    Ws = torch.zeros((64, 6), dtype=torch.uint8, device="cuda")
-    with pytest.raises(moin.MoinError):
+    Ws = torch.zeros((1, 64, 4), dtype=torch.uint8, device="cuda")
+    with pytest.raises(ValueError):
         moin.moin_lora_linear_mx(ctx, inp.x, inp.seq_offsets, inp.expert_ids, Wq, Ws, inp.A_stack, inp.B_stack, 1.0)
     inp = _case("mx_bad_r", 256, 64, 24, 2, [40], [0], seed=40)
     Wq = torch.zeros((64, 256), dtype=torch.uint8, device="cuda")
-    Ws = torch.zeros((64, 8), dtype=torch.uint8, device="cuda")
+    Ws = torch.zeros((2, 64, 4), dtype=torch.uint8, device="cuda")
     with pytest.raises(moin.MoinError):
         moin.moin_lora_linear_mx(ctx, inp.x, inp.seq_offsets, inp.expert_ids, Wq, Ws, inp.A_stack, inp.B_stack, 1.0)
     # empty batch: nothing to do
