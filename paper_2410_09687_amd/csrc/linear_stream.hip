@@ -257,8 +257,14 @@ __global__ __launch_bounds__(stream::NT) void linear_stream_kernel(stream::Param
 
         // epilogue through the wave's private 4 KB of LDS beyond the two stages
         // (which the next tile's loads are already filling)
+        // (the lane id goes in through an opaque copy: the epilogue's per-lane
+        // addresses are then recomputed per tile instead of being kept, and
+        // spilled, across the main loop; a reload between two stores would wait
+        // for the first store to complete)
+        int lane_e = lane;
+        asm volatile("; lane id, rematerialised" : "+v"(lane_e));
         stream_epilogue<FP, FQ>(smem + SMEM_STAGES + wave * SCR_BYTES, acc, p.y, p.y_f32, p.d_out, cur.row0,
-                                cur.n0, cur.q_rows, cur.p_rows, wp, wq, lane);
+                                cur.n0, cur.q_rows, cur.p_rows, wp, wq, lane_e);
         if (!nxt.valid) break;
         cur = nxt;
         id += nslot;

@@ -119,16 +119,18 @@ constexpr int BT = 256;              // tile edge, both ways
 constexpr int ROWB = 128;            // bytes of one operand row per block
 constexpr int KB8 = 128;             // contraction steps of a base block (FP8)
 constexpr int KB16 = 64;             // contraction steps of an adapter block (bf16)
-constexpr int NW = 8, NT = NW * 64;
+constexpr int NW = 4, NT = NW * 64;  // one wave per SIMD: 512 registers each
 constexpr int WQ = 2;                // waves along tokens (Q); NW / WQ along outputs (P)
-constexpr int FP = 2, FQ = 4;        // 32 x 32 accumulators per wave: 64 outputs x 128 tokens
+constexpr int FP = 4, FQ = 4;        // 32 x 32 accumulators per wave: 128 outputs x 128 tokens
 constexpr int OP_BYTES = BT * ROWB;  // one operand tile: 32 KB
 constexpr int STAGE_BYTES = 2 * OP_BYTES;
 constexpr int SMEM_STAGES = 2 * STAGE_BYTES;
+constexpr int SC_BYTES = 2 * BT * 4; // scale words of a block: 256 output rows, then 256 tokens
+constexpr int SMEM_SCALES = 2 * SC_BYTES;
 constexpr int SCR_BYTES = 4096;      // per-wave epilogue scratch
-constexpr int SMEM_BYTES = SMEM_STAGES + NW * SCR_BYTES;   // 160 KB: all of a compute unit's LDS
-constexpr int LOADS = 4;             // DMA instructions per wave per operand per block
-constexpr int NSC = FP + FQ;         // scale words a lane holds per block
+constexpr int SMEM_BYTES = SMEM_STAGES + SMEM_SCALES + NW * SCR_BYTES;   // 148 KB
+constexpr int LOADS = 8;             // DMA instructions per wave per operand per block
+constexpr int NSC = FP + FQ;         // scale words a lane needs per block
 
 struct Params {
     const char *xq, *Wq;             // FP8 codes [T, d_in], [d_out, d_in]
@@ -183,6 +185,14 @@ typedef i32x8_t Frag;
 
 }  // namespace mxs
 
+// Shape of the kernel: one persistent workgroup of four waves per compute unit
+// (one wave per SIMD, so each has the full 512 registers: 256 of accumulators for
+// its 128 x 128 patch and two complete sets of MFMA operands), walking a list of
+// 256 x 256 output tiles whose operand blocks form one stream through two LDS
+// stages.  Codes, adapter operands and scale words all reach LDS directly
+// (global_load_lds); the loop itself has no load into registers from global
+// memory, so the only wait on the memory counter is the one in front of the
+// per-block barrier.
 __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p)
 {
     using namespace mxs;
@@ -205,18 +215,14 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
     const int nkb0 = p.d_in / KB8;
     const uint32_t ldq = (uint32_t)p.d_in, ldu = (uint32_t)p.r * 2u;
 
-    // Per-lane constants of the loads are recomputed from the lane id at every use
-    // (through an opaque copy, so that the compiler does not keep two dozen of them
-    // alive across the main loop, where they would be spilled and reloaded through
-    // the same counter the DMA loads are waited on).
-    auto fresh_lane = [&]() __attribute__((always_inline)) {
-        int v = lane;
-        asm volatile("; lane id, rematerialised" : "+v"(v));
-        return v;
-    };
-
-    // Starts the loads of block b of tile t into `stage`.
-    auto issue = [&](const Tile &t, int b, char *stage) __attribute__((always_inline)) {
+    // Starts the loads of block b of tile t into stage `st` (0 / 1).
+    // DMA mapping: instruction j of a wave fills LDS rows (wave*8 + j)*8 .. +8 of an
+    // operand tile; the lane fetches logical 16-byte chunk (lane%8) ^ swz(row),
+    // swz(row) = (row >> 1) & 7 with row = wave*64 + j*8 + lane/8, which is lane/16
+    // for even j and lane/16 + 4 for odd j.  A base block also brings its scale
+    // words: 64 rows of either operand per wave, one word per lane.
+    auto issue = [&](const Tile &t, int b, int st) __attribute__((always_inline)) {
+        char *stage = smem + st * STAGE_BYTES;
         const bool base = b < nkb0;
         const int jb = b - nkb0;
         const bool hi = jb < t.nkb1;
@@ -225,13 +231,8 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
         const uint32_t ld = base ? ldq : ldu;
         const int kb = base ? b : (hi ? jb : jb - t.nkb1);
         const uint32_t kbyte = (uint32_t)kb * ROWB;
-        // DMA mapping: instruction j of a wave fills LDS rows (wave*4 + j)*8 .. +8 of
-        // an operand tile; the lane fetches logical 16-byte chunk (lane%8) ^ swz(row),
-        // swz(row) = (row >> 1) & 7 with row = wave*32 + j*8 + lane/8, which is
-        // lane/16 for even j and lane/16 + 4 for odd j
-        const uint32_t ln = (uint32_t)fresh_lane();
-        const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8)) + (ln >> 3);   // + 8 * j
-        const uint32_t c16 = (((ln & 7) ^ (ln >> 4)) * 16) + kbyte;           // odd j: ^ 64
+        const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8) + (lane >> 3));   // + 8 * j
+        const uint32_t c16 = (uint32_t)(((lane & 7) ^ (lane >> 4)) * 16) + kbyte;   // odd j: ^ 64
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) {
             const uint32_t row = min(dma_row + 8u * j, (uint32_t)(t.p_rows - 1));
@@ -246,116 +247,85 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
             __builtin_amdgcn_global_load_lds(MOIN_GPTR(pq + off),
                                              MOIN_LPTR(stage + OP_BYTES + (wave * LOADS + j) * 1024), 16, 0, 0);
         }
-    };
-
-    // Scale words of block b of tile t for this lane's rows (one word = the four
-    // scale bytes of a row's 128 steps; the words of a block's rows are adjacent, so
-    // each load of a wave is one 128-byte line).  Adapter blocks have none.
-    auto fetch_scales = [&](const Tile &t, int b, uint32_t (&dst)[NSC]) __attribute__((always_inline)) {
-        if (b < nkb0) {
-            const uint32_t r = (uint32_t)fresh_lane() & 31u;
+        if (base) {
+            char *sc = smem + SMEM_STAGES + st * SC_BYTES;
             const char *ps = p.Ws + ((int64_t)b * p.d_out + t.n0) * 4;
             const char *qs = p.xs + ((int64_t)b * p.T + t.row0) * 4;
-#pragma unroll
-            for (int i = 0; i < FP; ++i) {
-                const uint32_t row = min((uint32_t)(wp * (FP * 32) + i * 32) + r, (uint32_t)(t.p_rows - 1));
-                dst[i] = *reinterpret_cast<const uint32_t *>(ps + row * 4u);
-            }
-#pragma unroll
-            for (int j = 0; j < FQ; ++j) {
-                const uint32_t row = min((uint32_t)(wq * (FQ * 32) + j * 32) + r, (uint32_t)(t.q_rows - 1));
-                dst[FP + j] = *reinterpret_cast<const uint32_t *>(qs + row * 4u);
-            }
+            const uint32_t prow = min((uint32_t)(wave * 64 + lane), (uint32_t)(t.p_rows - 1));
+            const uint32_t qrow = min((uint32_t)(wave * 64 + lane), (uint32_t)(t.q_rows - 1));
+            __builtin_amdgcn_global_load_lds(MOIN_GPTR(ps + prow * 4u), MOIN_LPTR(sc + wave * 256), 4, 0, 0);
+            __builtin_amdgcn_global_load_lds(MOIN_GPTR(qs + qrow * 4u), MOIN_LPTR(sc + BT * 4 + wave * 256), 4, 0, 0);
         }
     };
 
-    // byte (16 h) ^ (16 f) of the lane's row in the first patch of each operand; the
-    // row offsets are multiples of 128, so chunk c = 4 ks + 2 * half of that row is
-    // at (this address) ^ (16 c)
-    // (recomputed at each use like the load constants: f = (lane >> 1) & 7, r = lane & 31)
-    auto lane_off = [&]() __attribute__((always_inline)) {
-        const int ln = fresh_lane();
-        return ((ln & 31) * ROWB) | ((((ln >> 5) ^ (ln >> 1)) & 7) * 16);
-    };
-    const int baseP = wp * (FP * 32) * ROWB, baseQ = OP_BYTES + wq * (FQ * 32) * ROWB;   // wave-uniform
-    Frag fp[2][FP], fq[FQ - 1], fq3[2];
+    // fragment addresses: byte (16 h) ^ (16 f) of the lane's row in the first patch of
+    // each operand, f = (r >> 1) & 7; the row offsets are multiples of 128, so chunk
+    // c = 4 ks + 2 * half of that row is at (this address) ^ (16 c)
+    const int f = (r >> 1) & 7;
+    const int offP = (wp * (FP * 32) + r) * ROWB + ((h ^ f) & 7) * 16;
+    const int offQ = OP_BYTES + (wq * (FQ * 32) + r) * ROWB + ((h ^ f) & 7) * 16;
+    Frag fp[2][FP], fq[2][FQ];
     auto read_frag = [&](Frag &g, const char *stage_, int row, int ks) __attribute__((always_inline)) {
         const i32x4_t lo = *reinterpret_cast<const i32x4_t *>(stage_ + (row ^ (ks * 64)));
         const i32x4_t hi = *reinterpret_cast<const i32x4_t *>(stage_ + (row ^ (ks * 64 + 32)));
         g = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
-    // fragments of k-step ks that have a buffer of their own for that k-step
-    auto read_buffered = [&](const char *stage, int ks) __attribute__((always_inline)) {
-        const int lo_ = lane_off();
-        const int offP = baseP + lo_, offQ = baseQ + lo_;
+    auto read_frags = [&](const char *stage, int ks) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < FP; ++i) read_frag(fp[ks][i], stage, offP + i * 32 * ROWB, ks);
-        read_frag(fq3[ks], stage, offQ + (FQ - 1) * 32 * ROWB, ks);
-    };
-    f32x16_t acc[FP][FQ];
-    // scale bytes: sc_ld as loaded (one word per fragment row: the four bytes of the
-    // row's 128 steps), sc_nxt / sc_cur regrouped so that word n holds, for
-    // fragments 2n and 2n + 1, the bytes this lane feeds the MFMAs of k-steps 0, 1
-    uint32_t sc_ld[NSC], sc_nxt[NSC / 2], sc_cur[NSC / 2];
-    auto regroup = [&](uint32_t (&dst)[NSC / 2]) __attribute__((always_inline)) {
-        const uint32_t pick = 0x06040200u + (uint32_t)(fresh_lane() >> 5) * 0x01010101u;   // h = 1: 0x07050301
 #pragma unroll
-        for (int n = 0; n < NSC / 2; ++n) dst[n] = __builtin_amdgcn_perm(sc_ld[2 * n + 1], sc_ld[2 * n], pick);
+        for (int j = 0; j < FQ; ++j) read_frag(fq[ks][j], stage, offQ + j * 32 * ROWB, ks);
     };
+    // scale words of this lane's rows, as they lie in LDS (sc_raw: the four bytes of
+    // a row's 128 steps) and regrouped (sc: word n holds, for fragments 2n and 2n + 1,
+    // the bytes this lane feeds the MFMAs of k-steps 0 and 1; a lane supplies the
+    // scale of the first 32-step block of a 64-step slice if h = 0, of the second if 1)
+    uint32_t sc_raw[NSC], sc[NSC / 2];
+    auto read_scales = [&](const char *area) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < FP; ++i)
+            sc_raw[i] = *reinterpret_cast<const uint32_t *>(area + (wp * (FP * 32) + i * 32 + r) * 4);
+#pragma unroll
+        for (int j = 0; j < FQ; ++j)
+            sc_raw[FP + j] = *reinterpret_cast<const uint32_t *>(area + (BT + wq * (FQ * 32) + j * 32 + r) * 4);
+    };
+    const uint32_t pick = h ? 0x07050301u : 0x06040200u;
+    auto regroup = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int n = 0; n < NSC / 2; ++n) sc[n] = __builtin_amdgcn_perm(sc_raw[2 * n + 1], sc_raw[2 * n], pick);
+    };
+
+    f32x16_t acc[FP][FQ];
     auto lo16 = [](const Frag &g) __attribute__((always_inline)) {
         return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(g, g, 0, 1, 2, 3));
     };
     auto hi16 = [](const Frag &g) __attribute__((always_inline)) {
         return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(g, g, 4, 5, 6, 7));
     };
-    // acc[i][J] += (fragment pair) for i = 0..FP-1: one scaled FP8 MFMA each on a
-    // base block, two bf16 MFMAs each on an adapter block
-    auto mfma_pair = [&](auto base_tag, auto ks_tag, auto j_tag, const Frag &q) __attribute__((always_inline)) {
+    // acc[I][J] += fragment pair: one scaled FP8 MFMA on a base block, two bf16
+    // MFMAs on an adapter block
+    auto mfma_one = [&](auto base_tag, auto ks_tag, auto i_tag, auto j_tag) __attribute__((always_inline)) {
         constexpr bool BASE = decltype(base_tag)::value;
-        constexpr int KS = decltype(ks_tag)::value, J = decltype(j_tag)::value;
+        constexpr int KS = decltype(ks_tag)::value, I = decltype(i_tag)::value, J = decltype(j_tag)::value;
         if constexpr (BASE) {
-            acc[0][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                fp[KS][0], q, acc[0][J], 0, 0, KS, (int)sc_cur[0], (J & 1) * 2 + KS,
-                (int)sc_cur[1 + J / 2]);
-            acc[1][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                fp[KS][1], q, acc[1][J], 0, 0, 2 + KS, (int)sc_cur[0], (J & 1) * 2 + KS,
-                (int)sc_cur[1 + J / 2]);
+            acc[I][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                fp[KS][I], fq[KS][J], acc[I][J], 0, 0, (I & 1) * 2 + KS, (int)sc[I / 2], (J & 1) * 2 + KS,
+                (int)sc[FP / 2 + J / 2]);
         } else {
-#pragma unroll
-            for (int i = 0; i < FP; ++i) {
-                acc[i][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    lo16(fp[KS][i]), lo16(q), acc[i][J], 0, 0, 0);
-                acc[i][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    hi16(fp[KS][i]), hi16(q), acc[i][J], 0, 0, 0);
-            }
+            acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo16(fp[KS][I]), lo16(fq[KS][J]), acc[I][J], 0, 0, 0);
+            acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi16(fp[KS][I]), hi16(fq[KS][J]), acc[I][J], 0, 0, 0);
         }
     };
-    auto pin = [](f32x16_t &a, f32x16_t &b) __attribute__((always_inline)) { asm volatile("" : "+v"(a), "+v"(b)); };
-    static_assert(FP == 2 && FQ == 4, "the MFMA order below is written out for 2 x 4 accumulators");
-    // One k-step: MFMAs of token fragments 0..2, each followed (RELOAD) by the read
-    // of the same fragment for the next k-step from `next_rows` at k-step NKS,
-    // then those of fragment 3.
-    auto kstep = [&](auto base_tag, auto ks_tag, auto reload_tag, const char *next_stage, int nks)
-                     __attribute__((always_inline)) {
-        constexpr bool RELOAD = decltype(reload_tag)::value;
-        constexpr int KS = decltype(ks_tag)::value;
-        const int offQ = RELOAD ? baseQ + lane_off() : 0;
-        // MFMAs have no side effects, so nothing but data flow orders them against
-        // the LDS reads and the barrier: pin() makes each pair's results an operand
-        // of an (empty) volatile asm, which keeps the pair ahead of the re-read that
-        // overwrites its operand registers (moved up, the re-read would need
-        // registers of its own) and ahead of the barrier
-        mfma_pair(base_tag, ks_tag, std::integral_constant<int, 0>{}, fq[0]);
-        pin(acc[0][0], acc[1][0]);
-        if constexpr (RELOAD) read_frag(fq[0], next_stage, offQ + 0 * 32 * ROWB, nks);
-        mfma_pair(base_tag, ks_tag, std::integral_constant<int, 1>{}, fq[1]);
-        pin(acc[0][1], acc[1][1]);
-        if constexpr (RELOAD) read_frag(fq[1], next_stage, offQ + 1 * 32 * ROWB, nks);
-        mfma_pair(base_tag, ks_tag, std::integral_constant<int, 2>{}, fq[2]);
-        pin(acc[0][2], acc[1][2]);
-        if constexpr (RELOAD) read_frag(fq[2], next_stage, offQ + 2 * 32 * ROWB, nks);
-        mfma_pair(base_tag, ks_tag, std::integral_constant<int, 3>{}, fq3[KS]);
-        pin(acc[0][3], acc[1][3]);
+    static_assert(FP == 4 && FQ == 4, "the MFMA list below is written out for 4 x 4 accumulators");
+    auto mfmas = [&](auto base_tag, auto ks_tag) __attribute__((always_inline)) {
+        using std::integral_constant;
+#define MOIN_MX_ROW(I)                                                                   \
+    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 0>{}); \
+    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 1>{}); \
+    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 2>{}); \
+    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 3>{});
+        MOIN_MX_ROW(0) MOIN_MX_ROW(1) MOIN_MX_ROW(2) MOIN_MX_ROW(3)
+#undef MOIN_MX_ROW
     };
 
     Tile cur = load_tile(p, id, band_end);
@@ -366,21 +336,27 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
     Tile pft = cur;
     int pfb = 2;
 
-    // One block of the stream.  BASE: kind of this block; ISSUE: a block two
-    // positions ahead exists and is fetched into the stage this block frees;
-    // READ: a next block exists.
-    auto body = [&](int s, auto base_tag, auto issue_tag, auto read_tag) __attribute__((always_inline)) {
-        constexpr bool ISSUE = decltype(issue_tag)::value, READ = decltype(read_tag)::value;
-        char *st_cur = smem + (s & 1) * STAGE_BYTES;
+    // One block of the stream.  BASE: kind of this block.  While a block two
+    // positions ahead exists it is fetched into the stage this block frees.  The
+    // next block's scales and leading fragments are read in any case: after the
+    // stream's last block they are stale bytes of LDS that nothing uses.
+    auto body = [&](int s, bool two_ahead, auto base_tag) __attribute__((always_inline)) {
+        const char *st_cur = smem + (s & 1) * STAGE_BYTES;
         const char *st_nxt = smem + ((s + 1) & 1) * STAGE_BYTES;
-        read_buffered(st_cur, 1);
-        kstep(base_tag, std::integral_constant<int, 0>{}, std::true_type{}, st_cur, 1);
-        // own share of block s+1 (and its scales) has landed and every fragment of
-        // block s is in registers; past the barrier that holds for all waves
+        read_frags(st_cur, 1);
+        mfmas(base_tag, std::integral_constant<int, 0>{});
+        // MFMAs have no side effects, so only data flow orders them against the
+        // barrier: making their results operands of an (empty) volatile asm keeps the
+        // first k-step's MFMAs ahead of it, where they cover the latency of the
+        // fragment reads above
+        asm volatile("" : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]),
+                          "+a"(acc[1][1]), "+a"(acc[1][2]), "+a"(acc[1][3]), "+a"(acc[2][0]), "+a"(acc[2][1]),
+                          "+a"(acc[2][2]), "+a"(acc[2][3]), "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]),
+                          "+a"(acc[3][3]));
+        // own share of block s+1 has landed and every fragment of block s is in
+        // registers; past the barrier that holds for all waves
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        regroup(sc_nxt);
-        __builtin_amdgcn_sched_barrier(0);   // the words it reads have landed: keep it ahead of the new loads
-        if constexpr (ISSUE) {
+        if (two_ahead) {
             // the fetch cursor runs two blocks ahead; when it has used up its tile
             // it moves to the tile after the one being computed (checked here, not
             // when the cursor advances: by now `nxt` is that tile in every case)
@@ -388,26 +364,22 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
                 pft = nxt;
                 pfb = 0;
             }
-            fetch_scales(pft, pfb, sc_ld);
-            issue(pft, pfb, st_cur);
+            issue(pft, pfb, s & 1);
             ++pfb;
         }
-        if constexpr (READ) read_buffered(st_nxt, 0);
-        kstep(base_tag, std::integral_constant<int, 1>{}, read_tag, st_nxt, 0);
-#pragma unroll
-        for (int n = 0; n < NSC / 2; ++n) sc_cur[n] = sc_nxt[n];
+        read_scales(smem + SMEM_STAGES + ((s + 1) & 1) * SC_BYTES);
+        read_frags(st_nxt, 0);
+        mfmas(base_tag, std::integral_constant<int, 1>{});
+        regroup();
     };
 
-    // prologue of the stream: two blocks in flight, the first one's leading fragments read
-    fetch_scales(cur, 0, sc_ld);
-    issue(cur, 0, smem);
-    regroup(sc_cur);
-    fetch_scales(cur, 1, sc_ld);
-    issue(cur, 1, smem + STAGE_BYTES);   // every tile has at least two blocks
-    wait_vm_then_barrier<2 * LOADS>();
-    read_buffered(smem, 0);
-#pragma unroll
-    for (int j = 0; j < FQ - 1; ++j) read_frag(fq[j], smem, baseQ + lane_off() + j * 32 * ROWB, 0);
+    // prologue of the stream: two blocks in flight, the first one's scales and leading fragments read
+    issue(cur, 0, 0);
+    issue(cur, 1, 1);   // every tile has at least two blocks
+    wait_vm_then_barrier<2 * LOADS + 2>();
+    read_scales(smem + SMEM_STAGES);
+    read_frags(smem, 0);
+    regroup();
 
     int s = 0;
     for (;;) {
@@ -419,24 +391,19 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
         const int total = cur.total;
-        // blocks that are followed by two more in the stream, then the stream's last two
-        const int full = nxt.valid ? total : total - 2;
         int b = 0;
-        for (; b < min(full, nkb0); ++b, ++s) body(s, std::true_type{}, std::true_type{}, std::true_type{});
-        for (; b < full; ++b, ++s) body(s, std::false_type{}, std::true_type{}, std::true_type{});
-        if (!nxt.valid) {
-            if (b < nkb0) body(s, std::true_type{}, std::false_type{}, std::true_type{});
-            else body(s, std::false_type{}, std::false_type{}, std::true_type{});
-            ++s, ++b;
-            if (b < nkb0) body(s, std::true_type{}, std::false_type{}, std::false_type{});
-            else body(s, std::false_type{}, std::false_type{}, std::false_type{});
-            ++s, ++b;
-        }
+        for (; b < nkb0; ++b, ++s) body(s, nxt.valid || b + 2 < total, std::true_type{});
+        for (; b < total; ++b, ++s) body(s, nxt.valid || b + 2 < total, std::false_type{});
 
-        // epilogue through the wave's private 4 KB of LDS beyond the two stages
-        // (which the next tile's loads are already filling)
-        stream_epilogue<FP, FQ>(smem + SMEM_STAGES + wave * SCR_BYTES, acc, p.y, p.y_f32, p.d_out, cur.row0,
-                                cur.n0, cur.q_rows, cur.p_rows, wp, wq, lane);
+        // epilogue through the wave's private 4 KB of LDS beyond the stages (which
+        // the next tile's loads are already filling)
+        // (the lane id goes in through an opaque copy: the epilogue's per-lane
+        // addresses are then recomputed per tile instead of being kept, and
+        // spilled, across the main loop)
+        int lane_e = lane;
+        asm volatile("; lane id, rematerialised" : "+v"(lane_e));
+        stream_epilogue<FP, FQ>(smem + SMEM_STAGES + SMEM_SCALES + wave * SCR_BYTES, acc, p.y, p.y_f32, p.d_out,
+                                cur.row0, cur.n0, cur.q_rows, cur.p_rows, wp, wq, lane_e);
         if (!nxt.valid) break;
         cur = nxt;
         id += nslot;
@@ -456,6 +423,7 @@ hipError_t launch_linear_mx_stream(const PlanView &pv, const MxLinearArgs &a, in
 {
     mxs::Params p;
     p.xq = (const char *)a.xq; p.Wq = (const char *)a.Wq; p.xs = (const char *)a.xs; p.Ws = (const char *)a.Ws;
+    p.T = pv.T;
     p.B_stack = (const char *)a.lin.B_stack;
     p.u_hi = (const char *)a.lin.u_hi; p.u_lo = (const char *)a.lin.u_lo;
     p.y = (char *)a.lin.y;
@@ -463,7 +431,6 @@ hipError_t launch_linear_mx_stream(const PlanView &pv, const MxLinearArgs &a, in
     p.tile_rank = pv.tile_rank;
     p.n_tiles = pv.n_tiles;
     p.d_in = a.lin.d_in; p.d_out = a.lin.d_out; p.r = a.lin.r;
-    p.T = pv.T;
     p.n_tiles_n = (a.lin.d_out + mxs::BT - 1) / mxs::BT;
     p.y_f32 = a.lin.y_f32;
     // one workgroup per compute unit (the LDS footprint allows no more), fewer

@@ -1,5 +1,5 @@
-// Epilogue shared by the streaming prefill kernels (256 x 256 output tiles, eight
-// waves as 4 x 2, each with FP x FQ accumulators of 32 outputs x 32 tokens).
+// Epilogue shared by the streaming prefill kernels (256 x 256 output tiles; each
+// wave holds FP x FQ accumulators of 32 outputs x 32 tokens).
 #pragma once
 #include "gemm_core.h"
 
@@ -11,6 +11,18 @@ namespace moin {
 // so that eight lanes store one full 128-byte line of a token's row.
 // row0 / n0: first token / output of the tile; q_rows / p_rows: valid tokens /
 // outputs; wp / wq: the wave's position along outputs / tokens.
+// Orders this wave's LDS accesses before and after it.  A wave's LDS instructions
+// execute in the order they were issued, so lanes see each other's earlier writes
+// without any wait; only the compiler has to be kept from moving accesses across.
+// (A wavefront-scope fence would do as well, but it is compiled to a wait on every
+// outstanding memory operation, the tile's own global stores included.)
+__device__ __forceinline__ void lds_order()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_wave_barrier();
+    asm volatile("" ::: "memory");
+}
+
 template <int FP, int FQ>
 __device__ __forceinline__ void stream_epilogue(char *scr, const f32x16_t (&acc)[FP][FQ], char *y, int y_f32,
                                                 int d_out, int row0, int n0, int q_rows, int p_rows,
@@ -31,9 +43,7 @@ __device__ __forceinline__ void stream_epilogue(char *scr, const f32x16_t (&acc)
                     *reinterpret_cast<f32x4_t *>(scr + r * 128 + (((2 * g + h) ^ (r & 7)) * 16)) =
                         f32x4_t{a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]};
                 }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                lds_order();
 #pragma unroll
                 for (int ps = 0; ps < 4; ++ps) {
                     const int mt = ps * 8 + m2;
@@ -43,9 +53,7 @@ __device__ __forceinline__ void stream_epilogue(char *scr, const f32x16_t (&acc)
                     if (m < q_rows && n < p_rows)   // d_out % 8 == 0: a chunk is all in or all out
                         *reinterpret_cast<f32x4_t *>(y + (int64_t)(row0 + m) * ldy + (int64_t)(n0 + n) * 4) = v;
                 }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                lds_order();
             }
         }
     } else {
@@ -53,34 +61,34 @@ __device__ __forceinline__ void stream_epilogue(char *scr, const f32x16_t (&acc)
         // 32 tokens x 64 outputs bf16: 128-byte rows of sixteen 8-byte slots;
         // the slot index is XORed with an even number, so slot pairs stay adjacent
         const int fw = ((r >> 1) & 7) << 1;
+        static_assert(FP % 2 == 0, "outputs are regrouped 64 at a time");
 #pragma unroll
         for (int j = 0; j < FQ; ++j) {
 #pragma unroll
-            for (int i = 0; i < FP; ++i) {
+            for (int ip = 0; ip < FP / 2; ++ip) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const f32x16_t &a = acc[i][j];
-                    const int slot = i * 8 + 2 * g + h;
-                    *reinterpret_cast<uint2 *>(scr + r * 128 + ((slot ^ fw) * 8)) =
-                        make_uint2(pack_bf16x2(a[4 * g], a[4 * g + 1]), pack_bf16x2(a[4 * g + 2], a[4 * g + 3]));
+                for (int ii = 0; ii < 2; ++ii) {
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const f32x16_t &a = acc[ip * 2 + ii][j];
+                        const int slot = ii * 8 + 2 * g + h;
+                        *reinterpret_cast<uint2 *>(scr + r * 128 + ((slot ^ fw) * 8)) =
+                            make_uint2(pack_bf16x2(a[4 * g], a[4 * g + 1]), pack_bf16x2(a[4 * g + 2], a[4 * g + 3]));
+                    }
                 }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                lds_order();
 #pragma unroll
-            for (int ps = 0; ps < 4; ++ps) {
-                const int mt = ps * 8 + m2;
-                const int fr = ((mt >> 1) & 7) << 1;
-                const uint4 v = *reinterpret_cast<const uint4 *>(scr + mt * 128 + (((2 * c2) ^ fr) * 8));
-                const int m = wq * (FQ * 32) + j * 32 + mt;
-                const int n = wp * (FP * 32) + c2 * 8;
-                if (m < q_rows && n < p_rows)
-                    *reinterpret_cast<uint4 *>(y + (int64_t)(row0 + m) * ldy + (int64_t)(n0 + n) * 2) = v;
+                for (int ps = 0; ps < 4; ++ps) {
+                    const int mt = ps * 8 + m2;
+                    const int fr = ((mt >> 1) & 7) << 1;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(scr + mt * 128 + (((2 * c2) ^ fr) * 8));
+                    const int m = wq * (FQ * 32) + j * 32 + mt;
+                    const int n = wp * (FP * 32) + ip * 64 + c2 * 8;
+                    if (m < q_rows && n < p_rows)
+                        *reinterpret_cast<uint4 *>(y + (int64_t)(row0 + m) * ldy + (int64_t)(n0 + n) * 2) = v;
+                }
+                lds_order();
             }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
     }
 }
