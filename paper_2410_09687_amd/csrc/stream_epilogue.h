@@ -44,14 +44,20 @@ __device__ __forceinline__ void stream_epilogue(char *scr, const f32x16_t (&acc)
                         f32x4_t{a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]};
                 }
                 lds_order();
+                // all four reads first, then the stores: one wait on LDS per block
+                f32x4_t v[4];
 #pragma unroll
                 for (int ps = 0; ps < 4; ++ps) {
                     const int mt = ps * 8 + m2;
-                    const f32x4_t v = *reinterpret_cast<const f32x4_t *>(scr + mt * 128 + ((c2 ^ (mt & 7)) * 16));
+                    v[ps] = *reinterpret_cast<const f32x4_t *>(scr + mt * 128 + ((c2 ^ (mt & 7)) * 16));
+                }
+#pragma unroll
+                for (int ps = 0; ps < 4; ++ps) {
+                    const int mt = ps * 8 + m2;
                     const int m = wq * (FQ * 32) + j * 32 + mt;
                     const int n = wp * (FP * 32) + i * 32 + c2 * 4;
                     if (m < q_rows && n < p_rows)   // d_out % 8 == 0: a chunk is all in or all out
-                        *reinterpret_cast<f32x4_t *>(y + (int64_t)(row0 + m) * ldy + (int64_t)(n0 + n) * 4) = v;
+                        *reinterpret_cast<f32x4_t *>(y + (int64_t)(row0 + m) * ldy + (int64_t)(n0 + n) * 4) = v[ps];
                 }
                 lds_order();
             }
@@ -77,15 +83,20 @@ __device__ __forceinline__ void stream_epilogue(char *scr, const f32x16_t (&acc)
                     }
                 }
                 lds_order();
+                uint4 v[4];
 #pragma unroll
                 for (int ps = 0; ps < 4; ++ps) {
                     const int mt = ps * 8 + m2;
                     const int fr = ((mt >> 1) & 7) << 1;
-                    const uint4 v = *reinterpret_cast<const uint4 *>(scr + mt * 128 + (((2 * c2) ^ fr) * 8));
+                    v[ps] = *reinterpret_cast<const uint4 *>(scr + mt * 128 + (((2 * c2) ^ fr) * 8));
+                }
+#pragma unroll
+                for (int ps = 0; ps < 4; ++ps) {
+                    const int mt = ps * 8 + m2;
                     const int m = wq * (FQ * 32) + j * 32 + mt;
                     const int n = wp * (FP * 32) + ip * 64 + c2 * 8;
                     if (m < q_rows && n < p_rows)
-                        *reinterpret_cast<uint4 *>(y + (int64_t)(row0 + m) * ldy + (int64_t)(n0 + n) * 2) = v;
+                        *reinterpret_cast<uint4 *>(y + (int64_t)(row0 + m) * ldy + (int64_t)(n0 + n) * 2) = v[ps];
                 }
                 lds_order();
             }

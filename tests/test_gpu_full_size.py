@@ -36,6 +36,35 @@ def test_prefill_q_proj_full_size():
         assert torch.isfinite(y.float()).all()
 
 
+def test_prefill_q_proj_quantised_base_full_size():
+    # the same batch on the MXFP8 base ("Future Works", quantising the base model), in the launch
+    # shape `bench.py --also mx` times: the activations' codes and scale bytes bit for bit on sampled
+    # rows, the layer on the same rows, and the weight's codes / scales in full
+    import oracle
+    w = wl.config_prefill()
+    inp = wl.make_linear_inputs(w, "cuda")
+    ctx = gc.ctx()
+    Wq, Ws = moin.moin_mx_quantize(ctx, inp.W, blocked=True)
+    ctx.check()
+    Ws_rows = Ws.permute(1, 0, 2).reshape(w.d_out, w.d_in // 32).cpu().numpy()
+    rc, rs = oracle.mx_quantize(wl.bf16_bits(inp.W))
+    assert np.array_equal(Wq.cpu().numpy(), rc) and np.array_equal(Ws_rows, rs)
+    rows = _sample_rows(w.T, inp.seq_offsets, 200, seed=3)
+    xq, xs = moin.moin_mx_quantize(ctx, inp.x)
+    xc, xsc = oracle.mx_quantize(wl.bf16_bits(inp.x[torch.from_numpy(rows).cuda()]))
+    assert np.array_equal(xq.cpu().numpy()[rows], xc) and np.array_equal(xs.cpu().numpy()[rows], xsc)
+    A, B, ids = wl.compact_stacks(inp)
+    ref = oracle.lora_linear_mx(wl.bf16_bits(inp.x), inp.seq_offsets.cpu().numpy(), ids, rc, rs, A, B,
+                                w.scale, rows=rows)
+    for dt in (torch.bfloat16, torch.float32):
+        print(f"[gpu] c1 quantised base full size y={dt}", flush=True)
+        y = moin.moin_lora_linear_mx(ctx, inp.x, inp.seq_offsets, inp.expert_ids, Wq, Ws, inp.A_stack,
+                                     inp.B_stack, w.scale, y_dtype=dt)
+        ctx.check()
+        print(gc.compare_linear(y, ref, rows, what=f"c1 mx/{dt}"), flush=True)
+        assert torch.isfinite(y.float()).all()
+
+
 def test_decode_mlp_full_size():
     for w in wl.config_decode():
         inp = wl.make_linear_inputs(w, "cuda")
