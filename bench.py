@@ -407,9 +407,9 @@ def main():
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="first run a plain device copy of this many MiB (3 times): the known-size "
                          "kernel that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
-    ap.add_argument("--also", default="decode,router,layer,kmeans",
+    ap.add_argument("--also", default="decode,router,layer,kmeans,mx",
                     help="comma list of extra workloads to report: decode,router,layer,kmeans,cache,ranks,mx "
-                         "(or 'none'); cache (it pins 10 GB of host memory) ranks and mx are not in the default list")
+                         "(or 'none'); cache (it pins 10 GB of host memory) and ranks are not in the default list")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU figure exists)",
