@@ -155,8 +155,10 @@ struct Tile {
     int valid;
 };
 
+template <bool MX>
 __device__ __forceinline__ Tile load_tile(const Params &p, int id, int n_work)
 {
+    constexpr int EB = MX ? 1 : 2;   // bytes per base operand element
     Tile t;
     t.valid = id < n_work;
     const int cid = t.valid ? id : 0;
@@ -166,13 +168,13 @@ __device__ __forceinline__ Tile load_tile(const Params &p, int id, int n_work)
     t.q_rows = uniform(p.tile_rows[tm]);
     t.n0 = tn * BT;
     t.p_rows = min(BT, p.d_out - t.n0);
-    const int64_t ldq = p.d_in, ldu = (int64_t)p.r * 2;
+    const int64_t ldq = (int64_t)p.d_in * EB, ldu = (int64_t)p.r * 2;
     t.q0 = p.xq + (int64_t)t.row0 * ldq;
     t.p0 = p.Wq + (int64_t)t.n0 * ldq;
     const int re = min(p.r, uniform(p.tile_rank[tm]));
     const bool lora = e >= 0 && re > 0;
     t.nkb1 = lora ? (re + KB16 - 1) / KB16 : 0;
-    t.total = p.d_in / KB8 + 2 * t.nkb1;
+    t.total = p.d_in * EB / ROWB + 2 * t.nkb1;
     t.uh = lora ? p.u_hi + (int64_t)t.row0 * ldu : t.q0;
     t.ul = lora ? p.u_lo + (int64_t)t.row0 * ldu : t.q0;
     t.be = lora ? p.B_stack + ((int64_t)e * p.d_out + t.n0) * ldu : t.p0;
@@ -193,9 +195,16 @@ typedef i32x8_t Frag;
 // (global_load_lds); the loop itself has no load into registers from global
 // memory, so the only wait on the memory counter is the one in front of the
 // per-block barrier.
-__global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p)
+//
+// MX = false runs the same stream on a bf16 base (xq / Wq then hold x and W, there
+// are no scales, and every block takes the bf16 MFMAs); it is not instantiated:
+// measured against the eight-wave bf16 kernel on the 2048 -> 2048 prefill shape it
+// took 280 us against 225 us.
+template <bool MX>
+__global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
 {
     using namespace mxs;
+    constexpr int EB = MX ? 1 : 2;
     extern __shared__ __align__(16) char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = uniform(threadIdx.x >> 6);
@@ -212,14 +221,14 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
     int id = xcd * per + slot;
     if (id >= band_end) return;
 
-    const int nkb0 = p.d_in / KB8;
-    const uint32_t ldq = (uint32_t)p.d_in, ldu = (uint32_t)p.r * 2u;
+    const int nkb0 = p.d_in * EB / ROWB;
+    const uint32_t ldq = (uint32_t)p.d_in * EB, ldu = (uint32_t)p.r * 2u;
 
     // Starts the loads of block b of tile t into stage `st` (0 / 1).
     // DMA mapping: instruction j of a wave fills LDS rows (wave*8 + j)*8 .. +8 of an
     // operand tile; the lane fetches logical 16-byte chunk (lane%8) ^ swz(row),
     // swz(row) = (row >> 1) & 7 with row = wave*64 + j*8 + lane/8, which is lane/16
-    // for even j and lane/16 + 4 for odd j.  A base block also brings its scale
+    // for even j and lane/16 + 4 for odd j.  With them come the block's scale
     // words: 64 rows of either operand per wave, one word per lane.
     auto issue = [&](const Tile &t, int b, int st) __attribute__((always_inline)) {
         char *stage = smem + st * STAGE_BYTES;
@@ -247,10 +256,13 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
             __builtin_amdgcn_global_load_lds(MOIN_GPTR(pq + off),
                                              MOIN_LPTR(stage + OP_BYTES + (wave * LOADS + j) * 1024), 16, 0, 0);
         }
-        if (base) {
+        if constexpr (MX) {
+            // (an adapter block has no scales; it repeats the loads of the tile's first
+            // block, so that the body needs no branch)
             char *sc = smem + SMEM_STAGES + st * SC_BYTES;
-            const char *ps = p.Ws + ((int64_t)b * p.d_out + t.n0) * 4;
-            const char *qs = p.xs + ((int64_t)b * p.T + t.row0) * 4;
+            const int sb = base ? b : 0;
+            const char *ps = p.Ws + ((int64_t)sb * p.d_out + t.n0) * 4;
+            const char *qs = p.xs + ((int64_t)sb * p.T + t.row0) * 4;
             const uint32_t prow = min((uint32_t)(wave * 64 + lane), (uint32_t)(t.p_rows - 1));
             const uint32_t qrow = min((uint32_t)(wave * 64 + lane), (uint32_t)(t.q_rows - 1));
             __builtin_amdgcn_global_load_lds(MOIN_GPTR(ps + prow * 4u), MOIN_LPTR(sc + wave * 256), 4, 0, 0);
@@ -328,19 +340,20 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
 #undef MOIN_MX_ROW
     };
 
-    Tile cur = load_tile(p, id, band_end);
+    Tile cur = load_tile<MX>(p, id, band_end);
     id += nslot;
-    Tile nxt = load_tile(p, id, band_end);
+    Tile nxt = load_tile<MX>(p, id, band_end);
 
     // fetch cursor: tile and block index of the next block to request
     Tile pft = cur;
     int pfb = 2;
 
-    // One block of the stream.  BASE: kind of this block.  While a block two
-    // positions ahead exists it is fetched into the stage this block frees.  The
-    // next block's scales and leading fragments are read in any case: after the
-    // stream's last block they are stale bytes of LDS that nothing uses.
-    auto body = [&](int s, bool two_ahead, auto base_tag) __attribute__((always_inline)) {
+    // One block of the stream.  BASE: kind of this block.  The block two positions
+    // ahead is fetched into the stage this block frees, and the next block's scales
+    // and leading fragments are read, in any case: at the stream's end they are
+    // repeated requests and stale bytes of LDS that nothing uses.
+    auto body = [&](int s, auto base_tag) __attribute__((always_inline)) {
+        constexpr bool BASE = decltype(base_tag)::value;
         const char *st_cur = smem + (s & 1) * STAGE_BYTES;
         const char *st_nxt = smem + ((s + 1) & 1) * STAGE_BYTES;
         read_frags(st_cur, 1);
@@ -356,30 +369,44 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
         // own share of block s+1 has landed and every fragment of block s is in
         // registers; past the barrier that holds for all waves
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        if (two_ahead) {
-            // the fetch cursor runs two blocks ahead; when it has used up its tile
-            // it moves to the tile after the one being computed (checked here, not
-            // when the cursor advances: by now `nxt` is that tile in every case)
-            if (pfb == pft.total) {
+        // The fetch cursor runs two blocks ahead; when it has used up its tile it
+        // moves to the tile after the one being computed (by now `nxt` is that tile
+        // in every case); past the last tile it requests that tile's last block
+        // again, into the stage that is free anyway.
+        if (pfb == pft.total) {
+            if (nxt.valid) {
                 pft = nxt;
                 pfb = 0;
+            } else {
+                pfb = pft.total - 1;
             }
-            issue(pft, pfb, s & 1);
-            ++pfb;
         }
-        read_scales(smem + SMEM_STAGES + ((s + 1) & 1) * SC_BYTES);
+        // From here to the end of the block there is no branch, so that the reads of
+        // the next block's operands, the requests for the block after it and the
+        // second k-step's MFMAs can be interleaved (one wave per SIMD: whatever
+        // delays the next MFMA leaves the matrix core idle).
+        if constexpr (MX) read_scales(smem + SMEM_STAGES + ((s + 1) & 1) * SC_BYTES);
         read_frags(st_nxt, 0);
+        issue(pft, pfb, s & 1);
+        ++pfb;
         mfmas(base_tag, std::integral_constant<int, 1>{});
-        regroup();
+        if constexpr (MX) regroup();
+#pragma unroll
+        for (int n = 0; n < FP * FQ; ++n) {
+            __builtin_amdgcn_sched_group_barrier(0x008, BASE ? 1 : 2, 0);   // MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);              // LDS reads: all issued in the first 12 groups
+            __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);              // DMA requests
+            __builtin_amdgcn_sched_group_barrier(0x006, 10, 0);             // their address arithmetic
+        }
     };
 
     // prologue of the stream: two blocks in flight, the first one's scales and leading fragments read
     issue(cur, 0, 0);
     issue(cur, 1, 1);   // every tile has at least two blocks
-    wait_vm_then_barrier<2 * LOADS + 2>();
-    read_scales(smem + SMEM_STAGES);
+    wait_vm_then_barrier<2 * LOADS + (MX ? 2 : 0)>();
+    if constexpr (MX) read_scales(smem + SMEM_STAGES);
     read_frags(smem, 0);
-    regroup();
+    if constexpr (MX) regroup();
 
     int s = 0;
     for (;;) {
@@ -392,8 +419,8 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
 
         const int total = cur.total;
         int b = 0;
-        for (; b < nkb0; ++b, ++s) body(s, nxt.valid || b + 2 < total, std::true_type{});
-        for (; b < total; ++b, ++s) body(s, nxt.valid || b + 2 < total, std::false_type{});
+        for (; b < nkb0; ++b, ++s) body(s, std::integral_constant<bool, MX>{});
+        for (; b < total; ++b, ++s) body(s, std::false_type{});
 
         // epilogue through the wave's private 4 KB of LDS beyond the stages (which
         // the next tile's loads are already filling)
@@ -407,13 +434,15 @@ __global__ __launch_bounds__(mxs::NT) void linear_mx_stream_kernel(mxs::Params p
         if (!nxt.valid) break;
         cur = nxt;
         id += nslot;
-        nxt = load_tile(p, id, band_end);
+        nxt = load_tile<MX>(p, id, band_end);
     }
+    // the last blocks' repeated requests must have landed before the LDS is released
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 hipError_t prepare_mx_kernels()
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_mx_stream_kernel),
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_stream4_kernel<true>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, mxs::SMEM_BYTES);
 }
 
@@ -439,7 +468,8 @@ hipError_t launch_linear_mx_stream(const PlanView &pv, const MxLinearArgs &a, in
     int64_t grid = n_cus > 0 ? n_cus : 256;
     if (grid > max_work) grid = max_work;
     grid = (grid + 7) / 8 * 8;
-    hipLaunchKernelGGL(linear_mx_stream_kernel, dim3((unsigned)grid), dim3(mxs::NT), mxs::SMEM_BYTES, stream_, p);
+    hipLaunchKernelGGL(linear_stream4_kernel<true>, dim3((unsigned)grid), dim3(mxs::NT), mxs::SMEM_BYTES, stream_,
+                       p);
     return hipGetLastError();
 }
 
