@@ -200,7 +200,7 @@ typedef i32x8_t Frag;
 // are no scales, and every block takes the bf16 MFMAs); it is not instantiated:
 // measured against the eight-wave bf16 kernel on the 2048 -> 2048 prefill shape it
 // took 280 us against 225 us.
-template <bool MX>
+template <bool MX, bool Y_F32>
 __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
 {
     using namespace mxs;
@@ -209,7 +209,6 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
     const int lane = threadIdx.x & 63;
     const int wave = uniform(threadIdx.x >> 6);
     const int wp = wave / WQ, wq = wave % WQ;
-    const int r = lane & 31, h = lane >> 5;
 
     // work list of this workgroup: the 8 XCDs take workgroups round-robin, each
     // XCD owns one contiguous band of tile ids, and its workgroups stride
@@ -223,6 +222,15 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
 
     const int nkb0 = p.d_in * EB / ROWB;
     const uint32_t ldq = (uint32_t)p.d_in * EB, ldu = (uint32_t)p.r * 2u;
+
+    // Per-lane constants are recomputed from the lane id at every use (through an
+    // opaque copy): kept alive across the main loop they are spilled, and a reload
+    // goes through the same counter the DMA loads are waited on.
+    auto fresh_lane = [&]() __attribute__((always_inline)) {
+        int v = lane;
+        asm volatile("; lane id, rematerialised" : "+v"(v));
+        return v;
+    };
 
     // Starts the loads of block b of tile t into stage `st` (0 / 1).
     // DMA mapping: instruction j of a wave fills LDS rows (wave*8 + j)*8 .. +8 of an
@@ -240,8 +248,9 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
         const uint32_t ld = base ? ldq : ldu;
         const int kb = base ? b : (hi ? jb : jb - t.nkb1);
         const uint32_t kbyte = (uint32_t)kb * ROWB;
-        const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8) + (lane >> 3));   // + 8 * j
-        const uint32_t c16 = (uint32_t)(((lane & 7) ^ (lane >> 4)) * 16) + kbyte;   // odd j: ^ 64
+        const uint32_t ln = (uint32_t)fresh_lane();
+        const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8)) + (ln >> 3);   // + 8 * j
+        const uint32_t c16 = (((ln & 7) ^ (ln >> 4)) * 16) + kbyte;             // odd j: ^ 64
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) {
             const uint32_t row = min(dma_row + 8u * j, (uint32_t)(t.p_rows - 1));
@@ -263,8 +272,8 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
             const int sb = base ? b : 0;
             const char *ps = p.Ws + ((int64_t)sb * p.d_out + t.n0) * 4;
             const char *qs = p.xs + ((int64_t)sb * p.T + t.row0) * 4;
-            const uint32_t prow = min((uint32_t)(wave * 64 + lane), (uint32_t)(t.p_rows - 1));
-            const uint32_t qrow = min((uint32_t)(wave * 64 + lane), (uint32_t)(t.q_rows - 1));
+            const uint32_t prow = min((uint32_t)(wave * 64) + ln, (uint32_t)(t.p_rows - 1));
+            const uint32_t qrow = min((uint32_t)(wave * 64) + ln, (uint32_t)(t.q_rows - 1));
             __builtin_amdgcn_global_load_lds(MOIN_GPTR(ps + prow * 4u), MOIN_LPTR(sc + wave * 256), 4, 0, 0);
             __builtin_amdgcn_global_load_lds(MOIN_GPTR(qs + qrow * 4u), MOIN_LPTR(sc + BT * 4 + wave * 256), 4, 0, 0);
         }
@@ -273,9 +282,11 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
     // fragment addresses: byte (16 h) ^ (16 f) of the lane's row in the first patch of
     // each operand, f = (r >> 1) & 7; the row offsets are multiples of 128, so chunk
     // c = 4 ks + 2 * half of that row is at (this address) ^ (16 c)
-    const int f = (r >> 1) & 7;
-    const int offP = (wp * (FP * 32) + r) * ROWB + ((h ^ f) & 7) * 16;
-    const int offQ = OP_BYTES + (wq * (FQ * 32) + r) * ROWB + ((h ^ f) & 7) * 16;
+    auto lane_off = [&]() __attribute__((always_inline)) {   // r * ROWB + ((h ^ f) & 7) * 16
+        const int ln = fresh_lane();
+        return ((ln & 31) * ROWB) | ((((ln >> 5) ^ (ln >> 1)) & 7) * 16);
+    };
+    const int baseP = wp * (FP * 32) * ROWB, baseQ = OP_BYTES + wq * (FQ * 32) * ROWB;   // wave-uniform
     Frag fp[2][FP], fq[2][FQ];
     auto read_frag = [&](Frag &g, const char *stage_, int row, int ks) __attribute__((always_inline)) {
         const i32x4_t lo = *reinterpret_cast<const i32x4_t *>(stage_ + (row ^ (ks * 64)));
@@ -283,6 +294,8 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
         g = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
     auto read_frags = [&](const char *stage, int ks) __attribute__((always_inline)) {
+        const int lo_ = lane_off();
+        const int offP = baseP + lo_, offQ = baseQ + lo_;
 #pragma unroll
         for (int i = 0; i < FP; ++i) read_frag(fp[ks][i], stage, offP + i * 32 * ROWB, ks);
 #pragma unroll
@@ -294,6 +307,7 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
     // scale of the first 32-step block of a 64-step slice if h = 0, of the second if 1)
     uint32_t sc_raw[NSC], sc[NSC / 2];
     auto read_scales = [&](const char *area) __attribute__((always_inline)) {
+        const int r = fresh_lane() & 31;
 #pragma unroll
         for (int i = 0; i < FP; ++i)
             sc_raw[i] = *reinterpret_cast<const uint32_t *>(area + (wp * (FP * 32) + i * 32 + r) * 4);
@@ -301,8 +315,8 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
         for (int j = 0; j < FQ; ++j)
             sc_raw[FP + j] = *reinterpret_cast<const uint32_t *>(area + (BT + wq * (FQ * 32) + j * 32 + r) * 4);
     };
-    const uint32_t pick = h ? 0x07050301u : 0x06040200u;
     auto regroup = [&]() __attribute__((always_inline)) {
+        const uint32_t pick = 0x06040200u + (uint32_t)(fresh_lane() >> 5) * 0x01010101u;   // h = 1: 0x07050301
 #pragma unroll
         for (int n = 0; n < NSC / 2; ++n) sc[n] = __builtin_amdgcn_perm(sc_raw[2 * n + 1], sc_raw[2 * n], pick);
     };
@@ -400,16 +414,20 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
         }
     };
 
-    // prologue of the stream: two blocks in flight, the first one's scales and leading fragments read
+    // prologue of the stream: two blocks in flight, the first one landed
     issue(cur, 0, 0);
     issue(cur, 1, 1);   // every tile has at least two blocks
     wait_vm_then_barrier<2 * LOADS + (MX ? 2 : 0)>();
-    if constexpr (MX) read_scales(smem + SMEM_STAGES);
-    read_frags(smem, 0);
-    if constexpr (MX) regroup();
 
     int s = 0;
     for (;;) {
+        // scales and leading fragments of the tile's first block (it has landed: the
+        // prologue, or the previous tile's last barrier, waited for it).  The previous
+        // tile's last block read them too, like every block reads its successor's, but
+        // operands held across the epilogue would be spilled there and reloaded here.
+        if constexpr (MX) read_scales(smem + SMEM_STAGES + (s & 1) * SC_BYTES);
+        read_frags(smem + (s & 1) * STAGE_BYTES, 0);
+        if constexpr (MX) regroup();
 #pragma unroll
         for (int i = 0; i < FP; ++i)
 #pragma unroll
@@ -429,8 +447,8 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
         // spilled, across the main loop)
         int lane_e = lane;
         asm volatile("; lane id, rematerialised" : "+v"(lane_e));
-        stream_epilogue<FP, FQ>(smem + SMEM_STAGES + SMEM_SCALES + wave * SCR_BYTES, acc, p.y, p.y_f32, p.d_out,
-                                cur.row0, cur.n0, cur.q_rows, cur.p_rows, wp, wq, lane_e);
+        stream_epilogue_as<FP, FQ, Y_F32>(smem + SMEM_STAGES + SMEM_SCALES + wave * SCR_BYTES, acc, p.y, p.d_out,
+                                          cur.row0, cur.n0, cur.q_rows, cur.p_rows, wp, wq, lane_e);
         if (!nxt.valid) break;
         cur = nxt;
         id += nslot;
@@ -442,7 +460,10 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
 
 hipError_t prepare_mx_kernels()
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_stream4_kernel<true>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_stream4_kernel<true, false>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, mxs::SMEM_BYTES);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_stream4_kernel<true, true>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, mxs::SMEM_BYTES);
 }
 
@@ -468,8 +489,14 @@ hipError_t launch_linear_mx_stream(const PlanView &pv, const MxLinearArgs &a, in
     int64_t grid = n_cus > 0 ? n_cus : 256;
     if (grid > max_work) grid = max_work;
     grid = (grid + 7) / 8 * 8;
-    hipLaunchKernelGGL(linear_stream4_kernel<true>, dim3((unsigned)grid), dim3(mxs::NT), mxs::SMEM_BYTES, stream_,
-                       p);
+    // (one instantiation per output type: with both epilogues in one kernel the
+    // compiler moved accumulators through scratch memory at every tile's end)
+    if (a.lin.y_f32)
+        hipLaunchKernelGGL((linear_stream4_kernel<true, true>), dim3((unsigned)grid), dim3(mxs::NT), mxs::SMEM_BYTES,
+                           stream_, p);
+    else
+        hipLaunchKernelGGL((linear_stream4_kernel<true, false>), dim3((unsigned)grid), dim3(mxs::NT), mxs::SMEM_BYTES,
+                           stream_, p);
     return hipGetLastError();
 }
 

@@ -16,21 +16,25 @@ namespace moin {
 // without any wait; only the compiler has to be kept from moving accesses across.
 // (A wavefront-scope fence would do as well, but it is compiled to a wait on every
 // outstanding memory operation, the tile's own global stores included.)
+// The scheduling fence also keeps the next block's accumulator reads from being
+// hoisted above this point: all at once they do not fit the register file.
 __device__ __forceinline__ void lds_order()
 {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_sched_barrier(0);
     asm volatile("" ::: "memory");
 }
 
-template <int FP, int FQ>
-__device__ __forceinline__ void stream_epilogue(char *scr, const f32x16_t (&acc)[FP][FQ], char *y, int y_f32,
-                                                int d_out, int row0, int n0, int q_rows, int p_rows,
-                                                int wp, int wq, int lane)
+// Y_F32: y is fp32 (else bf16, rounded to nearest even).
+template <int FP, int FQ, bool Y_F32>
+__device__ __forceinline__ void stream_epilogue_as(char *scr, const f32x16_t (&acc)[FP][FQ], char *y, int d_out,
+                                                   int row0, int n0, int q_rows, int p_rows, int wp, int wq,
+                                                   int lane)
 {
     const int r = lane & 31, h = lane >> 5;
     const int m2 = lane >> 3, c2 = lane & 7;   // read-back: token m2 + 8 * pass, 16-byte chunk c2
-    if (y_f32) {
+    if constexpr (Y_F32) {
         const int64_t ldy = (int64_t)d_out * 4;
 #pragma unroll
         for (int j = 0; j < FQ; ++j) {
@@ -44,20 +48,14 @@ __device__ __forceinline__ void stream_epilogue(char *scr, const f32x16_t (&acc)
                         f32x4_t{a[4 * g], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]};
                 }
                 lds_order();
-                // all four reads first, then the stores: one wait on LDS per block
-                f32x4_t v[4];
 #pragma unroll
                 for (int ps = 0; ps < 4; ++ps) {
                     const int mt = ps * 8 + m2;
-                    v[ps] = *reinterpret_cast<const f32x4_t *>(scr + mt * 128 + ((c2 ^ (mt & 7)) * 16));
-                }
-#pragma unroll
-                for (int ps = 0; ps < 4; ++ps) {
-                    const int mt = ps * 8 + m2;
+                    const f32x4_t v = *reinterpret_cast<const f32x4_t *>(scr + mt * 128 + ((c2 ^ (mt & 7)) * 16));
                     const int m = wq * (FQ * 32) + j * 32 + mt;
                     const int n = wp * (FP * 32) + i * 32 + c2 * 4;
                     if (m < q_rows && n < p_rows)   // d_out % 8 == 0: a chunk is all in or all out
-                        *reinterpret_cast<f32x4_t *>(y + (int64_t)(row0 + m) * ldy + (int64_t)(n0 + n) * 4) = v[ps];
+                        *reinterpret_cast<f32x4_t *>(y + (int64_t)(row0 + m) * ldy + (int64_t)(n0 + n) * 4) = v;
                 }
                 lds_order();
             }
@@ -83,25 +81,30 @@ __device__ __forceinline__ void stream_epilogue(char *scr, const f32x16_t (&acc)
                     }
                 }
                 lds_order();
-                uint4 v[4];
 #pragma unroll
                 for (int ps = 0; ps < 4; ++ps) {
                     const int mt = ps * 8 + m2;
                     const int fr = ((mt >> 1) & 7) << 1;
-                    v[ps] = *reinterpret_cast<const uint4 *>(scr + mt * 128 + (((2 * c2) ^ fr) * 8));
-                }
-#pragma unroll
-                for (int ps = 0; ps < 4; ++ps) {
-                    const int mt = ps * 8 + m2;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(scr + mt * 128 + (((2 * c2) ^ fr) * 8));
                     const int m = wq * (FQ * 32) + j * 32 + mt;
                     const int n = wp * (FP * 32) + ip * 64 + c2 * 8;
                     if (m < q_rows && n < p_rows)
-                        *reinterpret_cast<uint4 *>(y + (int64_t)(row0 + m) * ldy + (int64_t)(n0 + n) * 2) = v[ps];
+                        *reinterpret_cast<uint4 *>(y + (int64_t)(row0 + m) * ldy + (int64_t)(n0 + n) * 2) = v;
                 }
                 lds_order();
             }
         }
     }
+}
+
+// The same with the output type chosen at run time.
+template <int FP, int FQ>
+__device__ __forceinline__ void stream_epilogue(char *scr, const f32x16_t (&acc)[FP][FQ], char *y, int y_f32,
+                                                int d_out, int row0, int n0, int q_rows, int p_rows,
+                                                int wp, int wq, int lane)
+{
+    if (y_f32) stream_epilogue_as<FP, FQ, true>(scr, acc, y, d_out, row0, n0, q_rows, p_rows, wp, wq, lane);
+    else stream_epilogue_as<FP, FQ, false>(scr, acc, y, d_out, row0, n0, q_rows, p_rows, wp, wq, lane);
 }
 
 }  // namespace moin
