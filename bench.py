@@ -42,6 +42,10 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 LINEAR_KERNEL_TRAFFIC_BYTES = int((2.0 * 212133.3 + 1.0 * 135680.0) * 1024)
 
 
+# the same for the quantised-base main kernel (profiles/hbm_traffic_quantised_base.md)
+MX_KERNEL_TRAFFIC_BYTES = int((2.0 * 113802.7 + 1.0 * 131072.0) * 1024)
+
+
 def timed_region(fn, steps, warmup):
     for _ in range(warmup):
         fn()
@@ -305,6 +309,7 @@ def bench_mx(ctx, steps, warmup):
             "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s",
                          "frac": achieved / PEAK_FP8_TFLOPS,
                          "frac_of_mixed_peak": t_peak / (lin["avg_ms"] * 1e-3),
+                         "traffic": MX_KERNEL_TRAFFIC_BYTES,
                          "kernel": "linear_mx_stream_kernel (MXFP8 base + bf16 adapter term)",
                          "avg_launch_ms": lin["avg_ms"]},
             "quantise_x": {"avg_launch_ms": qt["avg_ms"], "algorithmic_bytes": q_bytes,
