@@ -403,6 +403,44 @@ def bench_layer(ctx, steps, warmup):
             "tokens_per_s": T / (ms * 1e-3), "kernels": kt}
 
 
+def bench_layer_mx(ctx, steps, warmup):
+    """configs[4] on a quantised base: the seven projections' weights in MXFP8 (quantised once, outside
+    the step); activations quantised once per distinct input (q, k, v share theirs, gate and up theirs:
+    four quantiser launches per layer)."""
+    wls = wl.config_layer()
+    T = wls[0].T
+    ids = wl.draw_expert_ids(wls[0].S, wls[0].E, "zipf", 1.5, wls[0].seed * 8 + 4)
+    off = torch.from_numpy(wl.seq_offsets_of(wls[0].seq_lens)).cuda()
+    eids = torch.from_numpy(ids).cuda()
+    h0 = wl._randn_bf16((T, 2048), 1.0, torch.device("cuda"), 4242)
+    inputs = {w.name.split("_", 1)[1]: wl.make_linear_inputs(w, "cuda", expert_ids=ids, x=h0[:1])
+              for w in wls}
+    outs = {n: torch.empty((T, i.wl.d_out), dtype=torch.bfloat16, device="cuda") for n, i in inputs.items()}
+    src = {"q": None, "k": None, "v": None, "o": "q", "gate": "o", "up": "o", "down": "gate"}
+    wq = {n: moin.moin_mx_quantize(ctx, i.W, blocked=True) for n, i in inputs.items()}
+    plan = moin.Plan(ctx)
+
+    def step():
+        plan.build(off, eids, T, wls[0].E)
+        quantised = {}
+        for n, i in inputs.items():
+            x = h0 if src[n] is None else outs[src[n]]
+            if src[n] not in quantised:
+                quantised[src[n]] = moin.moin_mx_quantize(ctx, x, blocked=True)
+            xq, xs = quantised[src[n]]
+            moin.moin_lora_linear_mx_planned(ctx, plan, x, wq[n][0], wq[n][1], i.A_stack, i.B_stack, i.wl.scale,
+                                             xq=xq, xs=xs, out=outs[n])
+
+    ms, _ = timed_region(step, steps, warmup)
+    ctx.check()
+    kt = kernel_times(ctx, step, steps)
+    flops = sum(w.flops() for w in wls)
+    tf = flops / (ms * 1e-3) / 1e12
+    plan.close()
+    return {"ms_per_layer": ms, "TFLOPs": tf, "frac_of_fp8_peak": tf / PEAK_FP8_TFLOPS,
+            "tokens_per_s": T / (ms * 1e-3), "kernels": kt}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -448,6 +486,7 @@ def main():
         res["ranks"] = bench_ranks(ctx, args.steps, args.warmup)
     if "mx" in extra:
         res["mx"] = bench_mx(ctx, args.steps, args.warmup)
+        res["mx"]["layer"] = bench_layer_mx(ctx, max(5, args.steps // 5), 2)
     ctx.close()
     print(json.dumps(res))
 

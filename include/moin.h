@@ -200,6 +200,18 @@ int moin_lora_linear_mx(moin_ctx *ctx, const void *x, const int32_t *seq_offsets
                         const int32_t *rank_of_expert, float scale, void *y,
                         moin_dtype y_dt, void *stream);
 
+/* moin_lora_linear_mx on a plan (moin_plan_build / moin_plan_build_ranked), for the
+ * projections of a layer.  xq [T, d_in] / xs (MOIN_MX_BLOCKED layout,
+ * [d_in/128, T, 4]): the activations as quantised by moin_mx_quantize, so that
+ * projections that share their input (q, k, v; gate, up) quantise it once; both
+ * NULL: the call quantises x itself, into the context's workspace.  x (bf16) is
+ * needed in either case, for the adapter term. */
+int moin_lora_linear_mx_planned(moin_ctx *ctx, const moin_plan *plan, const void *x,
+                                const void *xq, const void *xs, const void *Wq, const void *Ws,
+                                const void *A_stack, const void *B_stack, int32_t d_in,
+                                int32_t d_out, int32_t r, float scale, void *y, moin_dtype y_dt,
+                                void *stream);
+
 /* The grouping of sequences by expert depends only on (seq_offsets,
  * expert_ids, E); a plan computes it once for all projections of a layer
  * (Section 3.2: every linear layer carries an adapter).

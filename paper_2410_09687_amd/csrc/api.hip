@@ -324,10 +324,12 @@ int linear_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, con
 
 // Quantised-base variant of the prefill sequence: shrink on the bf16 x, x
 // through the quantiser, then the block-scaled main kernel.
-int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, const void *Wq,
-                           const void *Ws, const void *A_stack, const void *B_stack, int32_t d_in,
-                           int32_t d_out, int32_t r, float scale, void *y, moin_dtype y_dt,
-                           hipStream_t stream)
+// xq / xs: the activations already quantised (blocked scale layout), or both null:
+// then they are quantised here, into the workspace.
+int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, const void *xq,
+                           const void *xs, const void *Wq, const void *Ws, const void *A_stack,
+                           const void *B_stack, int32_t d_in, int32_t d_out, int32_t r, float scale,
+                           void *y, moin_dtype y_dt, hipStream_t stream)
 {
     if (!plan->built) return MOIN_EINVAL;
     const PlanView &pv = plan->pv;
@@ -340,21 +342,22 @@ int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, 
     a.d_in = d_in; a.d_out = d_out; a.r = adapters ? r : 0; a.scale = scale;
     a.u_hi = a.u_lo = nullptr;
     const size_t u_bytes = align_up((size_t)pv.T * (size_t)a.r * 2, 256);
-    const size_t xq_bytes = align_up((size_t)pv.T * (size_t)d_in, 256);
-    const size_t xs_bytes = align_up((size_t)pv.T * (size_t)(d_in / 32), 256);
+    const bool own_q = xq == nullptr;
+    const size_t xq_bytes = own_q ? align_up((size_t)pv.T * (size_t)d_in, 256) : 0;
+    const size_t xs_bytes = own_q ? align_up((size_t)pv.T * (size_t)(d_in / 32), 256) : 0;
     const int rc = ensure_ws(ctx, 2 * u_bytes + xq_bytes + xs_bytes);
     if (rc != MOIN_OK) return rc;
     char *w = static_cast<char *>(ctx->ws);
     a.u_hi = w;
     a.u_lo = w + u_bytes;
-    m.xq = w + 2 * u_bytes;
-    m.xs = w + 2 * u_bytes + xq_bytes;
+    m.xq = own_q ? w + 2 * u_bytes : xq;
+    m.xs = own_q ? w + 2 * u_bytes + xq_bytes : xs;
     m.Wq = Wq;
     m.Ws = Ws;
     if (a.r > 0 &&
         timed(ctx, MOIN_K_SHRINK, stream, [&] { return launch_prefill_shrink(pv, a, stream); }) != hipSuccess)
         return MOIN_EHIP;
-    if (timed(ctx, MOIN_K_MX_QUANT, stream, [&] {
+    if (own_q && timed(ctx, MOIN_K_MX_QUANT, stream, [&] {
             return launch_mx_quantize(x, pv.T, d_in, const_cast<void *>(m.xq), const_cast<void *>(m.xs), 1, stream);
         }) != hipSuccess)
         return MOIN_EHIP;
@@ -656,8 +659,28 @@ int moin_lora_linear_mx(moin_ctx *ctx, const void *x, const int32_t *seq_offsets
     }
     int rc = plan_build_impl(ctx, ctx->own_plan, seq_offsets, expert_ids, S, T, E, rank_of_expert, st);
     if (rc != MOIN_OK) return rc;
-    return linear_mx_planned_impl(ctx, ctx->own_plan, x, Wq, Ws, A_stack, B_stack, d_in, d_out, r, scale,
-                                  y, y_dt, st);
+    return linear_mx_planned_impl(ctx, ctx->own_plan, x, nullptr, nullptr, Wq, Ws, A_stack, B_stack, d_in,
+                                  d_out, r, scale, y, y_dt, st);
+}
+
+int moin_lora_linear_mx_planned(moin_ctx *ctx, const moin_plan *plan, const void *x, const void *xq,
+                                const void *xs, const void *Wq, const void *Ws, const void *A_stack,
+                                const void *B_stack, int32_t d_in, int32_t d_out, int32_t r,
+                                float scale, void *y, moin_dtype y_dt, void *stream)
+{
+    if (!ctx || !plan || plan->device != ctx->device) return MOIN_EINVAL;
+    if ((xq == nullptr) != (xs == nullptr)) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    if (plan->built && plan->pv.S > 0 && plan->pv.T > 0) {
+        const int vrc = validate_linear(x, Wq, A_stack, B_stack, plan->pv.E, d_in, d_out, r, scale, y, y_dt);
+        if (vrc != MOIN_OK) return vrc;
+        if (!Ws || misaligned(Ws, 16)) return MOIN_EINVAL;
+        if (xq && (misaligned(xq, 16) || misaligned(xs, 16))) return MOIN_EINVAL;
+        if (!mx_stream_kernel_fits(d_in, (plan->pv.E > 0 && r > 0) ? r : 0)) return MOIN_EINVAL;
+    }
+    return linear_mx_planned_impl(ctx, plan, x, xq, xs, Wq, Ws, A_stack, B_stack, d_in, d_out, r, scale, y,
+                                  y_dt, static_cast<hipStream_t>(stream));
 }
 
 int moin_kmeans_update(moin_ctx *ctx, const void *emb, const int32_t *ids, int64_t N,

@@ -31,7 +31,7 @@ EXPORTS = [
     "moin_kmeans_update", "moin_retain_clusters", "moin_kmeans_fit",
     "moin_cache_create", "moin_cache_destroy", "moin_cache_add_stack", "moin_cache_admit",
     "moin_cache_table", "moin_cache_stats", "moin_lora_linear_ranked", "moin_plan_build_ranked",
-    "moin_mx_quantize", "moin_lora_linear_mx",
+    "moin_mx_quantize", "moin_lora_linear_mx", "moin_lora_linear_mx_planned",
 ]
 CACHE_STATS = ["batches", "seq_hits", "seq_misses", "loads", "evictions", "overflows", "bytes"]
 
@@ -72,6 +72,8 @@ def load() -> ctypes.CDLL:
     lib.moin_mx_quantize.argtypes = [vp, vp, i64, i64, vp, vp, i32, vp]
     lib.moin_lora_linear_mx.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp, vp, i32, i32, i32, i32, vp,
                                         c.c_float, vp, c.c_int, vp]
+    lib.moin_lora_linear_mx_planned.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, c.c_float, vp,
+                                                c.c_int, vp]
     lib.moin_plan_build_ranked.argtypes = [vp, vp, vp, vp, i32, i64, i32, vp, vp]
     lib.moin_plan_create.argtypes = [vp, c.POINTER(vp)]
     lib.moin_plan_destroy.argtypes = [vp]
@@ -348,6 +350,35 @@ def moin_lora_linear_planned(ctx: Context, plan: Plan, x: torch.Tensor, W: torch
         _dev_ptr(A_stack, "A_stack", bf), _dev_ptr(B_stack, "B_stack", bf), d_in, d_out, r,
         float(scale), _dev_ptr(y, "y") if T else None, ydt, _stream_ptr(stream)),
         "moin_lora_linear_planned")
+    return y
+
+
+def moin_lora_linear_mx_planned(ctx: Context, plan: "Plan", x: torch.Tensor, Wq: torch.Tensor, Ws: torch.Tensor,
+                                A_stack: Optional[torch.Tensor], B_stack: Optional[torch.Tensor], scale: float,
+                                xq: Optional[torch.Tensor] = None, xs: Optional[torch.Tensor] = None,
+                                y_dtype=torch.bfloat16, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """``moin_lora_linear_mx`` on a plan; ``xq``, ``xs`` (from ``moin_mx_quantize(x, blocked=True)``) let
+    projections that share their input quantise it once."""
+    if x.dim() != 2 or Wq.dim() != 2 or x.shape[1] != Wq.shape[1] or x.shape[0] != plan.T:
+        raise ValueError("x [T,d_in] (T as planned) and Wq [d_out,d_in] expected")
+    if Wq.dtype != torch.uint8 or Ws.dtype != torch.uint8 or Wq.shape[1] % 128 or \
+            tuple(Ws.shape) != (Wq.shape[1] // 128, Wq.shape[0], 4):
+        raise ValueError("Wq [d_out,d_in] / Ws [d_in/128,d_out,4] (blocked layout) uint8 expected")
+    d_in, d_out, E, r = _stack_dims(Wq, A_stack, B_stack)
+    if E and E != plan.E:
+        raise ValueError("stack holds a different number of experts than the plan was built for")
+    T = x.shape[0]
+    if (xq is None) != (xs is None):
+        raise ValueError("xq and xs go together")
+    if xq is not None and (tuple(xq.shape) != (T, d_in) or tuple(xs.shape) != (d_in // 128, T, 4)):
+        raise ValueError("xq [T,d_in] / xs [d_in/128,T,4] (blocked layout) expected")
+    y, ydt = _y_out(x, d_out, y_dtype, out)
+    bf = torch.bfloat16
+    _ck(load().moin_lora_linear_mx_planned(
+        ctx._h, plan._h, _dev_ptr(x, "x", bf) if T else None, _dev_ptr(xq, "xq", torch.uint8),
+        _dev_ptr(xs, "xs", torch.uint8), _dev_ptr(Wq, "Wq", torch.uint8), _dev_ptr(Ws, "Ws", torch.uint8),
+        _dev_ptr(A_stack, "A_stack", bf), _dev_ptr(B_stack, "B_stack", bf), d_in, d_out, r, float(scale),
+        _dev_ptr(y, "y") if T else None, ydt, _stream_ptr(stream)), "moin_lora_linear_mx_planned")
     return y
 
 
