@@ -403,6 +403,39 @@ def bench_layer(ctx, steps, warmup):
             "tokens_per_s": T / (ms * 1e-3), "kernels": kt}
 
 
+def bench_decode_mx(ctx, steps, warmup, n_draws=8):
+    """configs[2] gate projection on the quantised base: activations' quantiser, base product for all
+    256 tokens on the FP8 matrix cores (contraction range in parts), then the decode kernels' adapter
+    term.  Same request stream and byte count convention as the bf16 decode figure (W counted at
+    one byte per element plus its scales)."""
+    w = wl.config_decode()[0]
+    inp = wl.make_linear_inputs(w, "cuda")
+    Wq, Ws = moin.moin_mx_quantize(ctx, inp.W, blocked=True)
+    plans, bytes_alg = [], []
+    for k in range(n_draws):
+        ids = wl.draw_expert_ids(w.S, w.E, "zipf", w.zipf_s, 9000 + k, perm_seed=777)
+        plans.append(moin.Plan(ctx).build(inp.seq_offsets, torch.from_numpy(ids).cuda(), w.T, w.E))
+        distinct = len(np.unique(ids))
+        bytes_alg.append(w.d_in * w.d_out * (1.0 + 1.0 / 32) + distinct * 2.0 * w.r * (w.d_in + w.d_out)
+                         + 2.0 * w.T * (w.d_in + w.d_out))
+    y = torch.empty((w.T, w.d_out), dtype=torch.bfloat16, device="cuda")
+    state = {"i": 0}
+
+    def step():
+        k = state["i"] % n_draws
+        state["i"] += 1
+        moin.moin_lora_linear_mx_planned(ctx, plans[k], inp.x, Wq, Ws, inp.A_stack, inp.B_stack, w.scale, out=y)
+
+    n = max(steps, n_draws) // n_draws * n_draws
+    ms, _ = timed_region(step, n, max(warmup, n_draws))
+    ctx.check()
+    kt = kernel_times(ctx, step, n)
+    for p in plans:
+        p.close()
+    avg = float(np.mean(bytes_alg))
+    return {"ms_per_call": ms, "algorithmic_bytes": avg, "GBps": avg / (ms * 1e-3) / 1e9, "kernels": kt}
+
+
 def bench_layer_mx(ctx, steps, warmup):
     """configs[4] on a quantised base: the seven projections' weights in MXFP8 (quantised once, outside
     the step); activations quantised once per distinct input (q, k, v share theirs, gate and up theirs:
@@ -487,6 +520,7 @@ def main():
     if "mx" in extra:
         res["mx"] = bench_mx(ctx, args.steps, args.warmup)
         res["mx"]["layer"] = bench_layer_mx(ctx, max(5, args.steps // 5), 2)
+        res["mx"]["decode_gate"] = bench_decode_mx(ctx, args.steps, args.warmup)
     ctx.close()
     print(json.dumps(res))
 

@@ -191,8 +191,9 @@ int moin_mx_quantize(moin_ctx *ctx, const void *src, int64_t rows, int64_t cols,
  * block-scaled FP8 matrix cores; the adapter term uses the bf16 x and the bf16
  * stacks exactly as in moin_lora_linear.  rank_of_expert may be NULL.
  * Shapes: d_in a multiple of 128 and at least 256, r a multiple of 64, d_out a
- * multiple of 8; anything else returns MOIN_EINVAL.  Every batch size takes the
- * tiled path (no separate decode path). */
+ * multiple of 8; anything else returns MOIN_EINVAL.  Small batches (T <= 1024)
+ * compute the base product for all tokens at once on the FP8 matrix cores and
+ * add the adapter term with the decode path's gather-matvec kernels. */
 int moin_lora_linear_mx(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
                         const int32_t *expert_ids, int32_t S, int64_t T,
                         const void *Wq, const void *Ws, const void *A_stack, const void *B_stack,

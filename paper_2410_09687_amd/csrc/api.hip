@@ -345,7 +345,20 @@ int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, 
     const bool own_q = xq == nullptr;
     const size_t xq_bytes = own_q ? align_up((size_t)pv.T * (size_t)d_in, 256) : 0;
     const size_t xs_bytes = own_q ? align_up((size_t)pv.T * (size_t)(d_in / 32), 256) : 0;
-    const int rc = ensure_ws(ctx, 2 * u_bytes + xq_bytes + xs_bytes);
+    m.plain_splits = 0;
+    m.plain_kb_per_split = 0;
+    // decode-sized batches with adapters: the base product for all tokens at once as
+    // fp32 partial planes, then the decode path's own shrink and expand kernels
+    const bool decode = pv.decode && a.r > 0;
+    size_t yb_bytes = 0;
+    if (decode) {
+        mx_plain_shape(pv.T, d_in, d_out, &m.plain_splits, &m.plain_kb_per_split);
+        yb_bytes = align_up((size_t)m.plain_splits * (size_t)pv.T * (size_t)d_out * 4, 256);
+    } else if (pv.decode) {
+        m.plain_splits = 1;            // no adapters anywhere: the plain product writes y itself
+        m.plain_kb_per_split = d_in / 128;
+    }
+    const int rc = ensure_ws(ctx, 2 * u_bytes + xq_bytes + xs_bytes + yb_bytes);
     if (rc != MOIN_OK) return rc;
     char *w = static_cast<char *>(ctx->ws);
     a.u_hi = w;
@@ -354,12 +367,33 @@ int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, 
     m.xs = own_q ? w + 2 * u_bytes + xq_bytes : xs;
     m.Wq = Wq;
     m.Ws = Ws;
-    if (a.r > 0 &&
-        timed(ctx, MOIN_K_SHRINK, stream, [&] { return launch_prefill_shrink(pv, a, stream); }) != hipSuccess)
-        return MOIN_EHIP;
     if (own_q && timed(ctx, MOIN_K_MX_QUANT, stream, [&] {
             return launch_mx_quantize(x, pv.T, d_in, const_cast<void *>(m.xq), const_cast<void *>(m.xs), 1, stream);
         }) != hipSuccess)
+        return MOIN_EHIP;
+    if (decode) {
+        DecodeArgs d;
+        d.lin = a;
+        d.ug_hi = a.u_hi;
+        d.ug_lo = a.u_lo;
+        d.ybase = reinterpret_cast<float *>(w + 2 * u_bytes + xq_bytes + xs_bytes);
+        d.k_splits = m.plain_splits;
+        m.lin.y = d.ybase;
+        m.lin.y_f32 = 1;
+        if (timed(ctx, MOIN_K_MX_LINEAR, stream, [&] {
+                return launch_linear_mx_stream(pv, m, compute_units(), stream);
+            }) != hipSuccess)
+            return MOIN_EHIP;
+        if (timed(ctx, MOIN_K_DECODE_SHRINK, stream, [&] { return launch_decode_shrink(pv, d, stream); }) !=
+            hipSuccess)
+            return MOIN_EHIP;
+        if (timed(ctx, MOIN_K_DECODE_EXPAND, stream, [&] { return launch_decode_expand(pv, d, stream); }) !=
+            hipSuccess)
+            return MOIN_EHIP;
+        return MOIN_OK;
+    }
+    if (a.r > 0 && !pv.decode &&
+        timed(ctx, MOIN_K_SHRINK, stream, [&] { return launch_prefill_shrink(pv, a, stream); }) != hipSuccess)
         return MOIN_EHIP;
     if (timed(ctx, MOIN_K_MX_LINEAR, stream, [&] {
             return launch_linear_mx_stream(pv, m, compute_units(), stream);

@@ -146,7 +146,12 @@ struct MxLinearArgs {
     LinearArgs lin;        // x (bf16, for the shrink), A_stack, B_stack, u_hi / u_lo, y; lin.W unused
     const void *xq, *xs;   // [T, d_in] codes, [d_in / 128, T, 4] scales (workspace, written per call)
     const void *Wq, *Ws;   // [d_out, d_in] codes, [d_in / 128, d_out, 4] scales
+    // > 0: plain mode -- the base product alone over all T tokens, no plan tiles, the
+    // contraction range in this many parts (mx_plain_shape), part s written to
+    // lin.y + s * T * d_out elements
+    int plain_splits, plain_kb_per_split;
 };
+void mx_plain_shape(int64_t T, int d_in, int d_out, int *k_splits, int *kb_per_split);
 // codes / scales of rows x cols bf16 values (cols a multiple of 32); scales row-major
 // [rows, cols / 32] or, blocked (cols a multiple of 128), [cols / 128, rows, 4]
 hipError_t launch_mx_quantize(const void *src, int64_t rows, int64_t cols, void *codes, void *scales,

@@ -142,6 +142,11 @@ struct Params {
     int d_in, d_out, r;
     int n_tiles_n;
     int y_f32;
+    // plain mode (decode-sized batches: the base product alone, for all tokens, no
+    // plan): tiles_m row tiles of 256 tokens, the contraction range cut into k_splits
+    // parts of kb_per_split blocks, part s written to y + s * plane_bytes
+    int plain, tiles_m, k_splits, kb_per_split;
+    int64_t plane_bytes;
 };
 
 // Everything a tile needs, all wave-uniform.
@@ -152,6 +157,8 @@ struct Tile {
     int nkb1;                  // adapter blocks per half (0: no adapter)
     int total;                 // blocks of the tile: nkb0 + 2 * nkb1
     int row0, n0;
+    int kb0;                   // first contraction block (plain mode: the part's; else 0)
+    int64_t y_off;             // byte offset of the output plane (plain mode)
     int valid;
 };
 
@@ -162,13 +169,33 @@ __device__ __forceinline__ Tile load_tile(const Params &p, int id, int n_work)
     Tile t;
     t.valid = id < n_work;
     const int cid = t.valid ? id : 0;
+    const int64_t ldq = (int64_t)p.d_in * EB, ldu = (int64_t)p.r * 2;
+    if (p.plain) {
+        const int per_part = p.tiles_m * p.n_tiles_n;
+        const int part = cid / per_part, rem = cid - part * per_part;
+        const int tm = rem / p.n_tiles_n, tn = rem - tm * p.n_tiles_n;
+        t.row0 = tm * BT;
+        t.q_rows = (int)min((int64_t)BT, p.T - t.row0);
+        t.n0 = tn * BT;
+        t.p_rows = min(BT, p.d_out - t.n0);
+        t.kb0 = part * p.kb_per_split;
+        t.y_off = (int64_t)part * p.plane_bytes;
+        t.q0 = p.xq + (int64_t)t.row0 * ldq + (int64_t)t.kb0 * ROWB;
+        t.p0 = p.Wq + (int64_t)t.n0 * ldq + (int64_t)t.kb0 * ROWB;
+        t.nkb1 = 0;
+        t.total = min(p.kb_per_split, p.d_in * EB / ROWB - t.kb0);
+        t.uh = t.ul = t.q0;
+        t.be = t.p0;
+        return t;
+    }
     const int tm = cid / p.n_tiles_n, tn = cid - tm * p.n_tiles_n;
     const int e = uniform(p.tile_expert[tm]);
     t.row0 = uniform(p.tile_row0[tm]);
     t.q_rows = uniform(p.tile_rows[tm]);
     t.n0 = tn * BT;
     t.p_rows = min(BT, p.d_out - t.n0);
-    const int64_t ldq = (int64_t)p.d_in * EB, ldu = (int64_t)p.r * 2;
+    t.kb0 = 0;
+    t.y_off = 0;
     t.q0 = p.xq + (int64_t)t.row0 * ldq;
     t.p0 = p.Wq + (int64_t)t.n0 * ldq;
     const int re = min(p.r, uniform(p.tile_rank[tm]));
@@ -213,7 +240,7 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
     // work list of this workgroup: the 8 XCDs take workgroups round-robin, each
     // XCD owns one contiguous band of tile ids, and its workgroups stride
     // through the band together (neighbouring ids share W or x panels in L2)
-    const int n_work = uniform(*p.n_tiles) * p.n_tiles_n;
+    const int n_work = p.plain ? p.tiles_m * p.n_tiles_n * p.k_splits : uniform(*p.n_tiles) * p.n_tiles_n;
     const int per = (n_work + 7) >> 3;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, nslot = gridDim.x >> 3;
     const int band_end = min((xcd + 1) * per, n_work);
@@ -270,8 +297,8 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
             // block, so that the body needs no branch)
             char *sc = smem + SMEM_STAGES + st * SC_BYTES;
             const int sb = base ? b : 0;
-            const char *ps = p.Ws + ((int64_t)sb * p.d_out + t.n0) * 4;
-            const char *qs = p.xs + ((int64_t)sb * p.T + t.row0) * 4;
+            const char *ps = p.Ws + ((int64_t)(t.kb0 + sb) * p.d_out + t.n0) * 4;
+            const char *qs = p.xs + ((int64_t)(t.kb0 + sb) * p.T + t.row0) * 4;
             const uint32_t prow = min((uint32_t)(wave * 64) + ln, (uint32_t)(t.p_rows - 1));
             const uint32_t qrow = min((uint32_t)(wave * 64) + ln, (uint32_t)(t.q_rows - 1));
             __builtin_amdgcn_global_load_lds(MOIN_GPTR(ps + prow * 4u), MOIN_LPTR(sc + wave * 256), 4, 0, 0);
@@ -437,7 +464,8 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
 
         const int total = cur.total;
         int b = 0;
-        for (; b < nkb0; ++b, ++s) body(s, std::integral_constant<bool, MX>{});
+        const int nb = min(nkb0, total);   // a part of a plain tile has fewer blocks than the full range
+        for (; b < nb; ++b, ++s) body(s, std::integral_constant<bool, MX>{});
         for (; b < total; ++b, ++s) body(s, std::false_type{});
 
         // epilogue through the wave's private 4 KB of LDS beyond the stages (which
@@ -447,7 +475,7 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
         // spilled, across the main loop)
         int lane_e = lane;
         asm volatile("; lane id, rematerialised" : "+v"(lane_e));
-        stream_epilogue_as<FP, FQ, Y_F32>(smem + SMEM_STAGES + SMEM_SCALES + wave * SCR_BYTES, acc, p.y, p.d_out,
+        stream_epilogue_as<FP, FQ, Y_F32>(smem + SMEM_STAGES + SMEM_SCALES + wave * SCR_BYTES, acc, p.y + cur.y_off, p.d_out,
                                           cur.row0, cur.n0, cur.q_rows, cur.p_rows, wp, wq, lane_e);
         if (!nxt.valid) break;
         cur = nxt;
@@ -469,6 +497,28 @@ hipError_t prepare_mx_kernels()
 
 bool mx_stream_kernel_fits(int d_in, int r) { return d_in % 128 == 0 && d_in >= 256 && r % 64 == 0; }
 
+// Parts of the contraction range for the plain (decode) base product: enough
+// workgroups to keep many loads in flight, at least two blocks per part, at most
+// four parts (the decode expand kernel sums up to four partial planes).
+void mx_plain_shape(int64_t T, int d_in, int d_out, int *k_splits, int *kb_per_split)
+{
+    const int nkb = d_in / 128;
+    const int64_t tiles = ((T + mxs::BT - 1) / mxs::BT) * ((d_out + mxs::BT - 1) / mxs::BT);
+    int want = (int)((128 + tiles - 1) / (tiles > 0 ? tiles : 1));
+    if (want > 4) want = 4;
+    if (want < 1) want = 1;
+    for (;; --want) {
+        const int per = (nkb + want - 1) / want;
+        const int parts = (nkb + per - 1) / per;
+        const int last = nkb - (parts - 1) * per;
+        if (want == 1 || (per >= 2 && last >= 2)) {   // every part streams at least two blocks
+            *kb_per_split = per;
+            *k_splits = parts;
+            return;
+        }
+    }
+}
+
 hipError_t launch_linear_mx_stream(const PlanView &pv, const MxLinearArgs &a, int n_cus, hipStream_t stream_)
 {
     mxs::Params p;
@@ -483,9 +533,15 @@ hipError_t launch_linear_mx_stream(const PlanView &pv, const MxLinearArgs &a, in
     p.d_in = a.lin.d_in; p.d_out = a.lin.d_out; p.r = a.lin.r;
     p.n_tiles_n = (a.lin.d_out + mxs::BT - 1) / mxs::BT;
     p.y_f32 = a.lin.y_f32;
+    p.plain = a.plain_splits > 0;
+    p.tiles_m = (int)((pv.T + mxs::BT - 1) / mxs::BT);
+    p.k_splits = a.plain_splits > 0 ? a.plain_splits : 1;
+    p.kb_per_split = a.plain_kb_per_split;
+    p.plane_bytes = (int64_t)pv.T * a.lin.d_out * (a.lin.y_f32 ? 4 : 2);
     // one workgroup per compute unit (the LDS footprint allows no more), fewer
     // when the batch has fewer tiles than that; always a multiple of 8
-    const int64_t max_work = (int64_t)pv.max_tiles * p.n_tiles_n;
+    const int64_t max_work = p.plain ? (int64_t)p.tiles_m * p.n_tiles_n * p.k_splits
+                                     : (int64_t)pv.max_tiles * p.n_tiles_n;
     int64_t grid = n_cus > 0 ? n_cus : 256;
     if (grid > max_work) grid = max_work;
     grid = (grid + 7) / 8 * 8;

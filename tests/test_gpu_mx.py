@@ -153,6 +153,26 @@ def test_mx_linear_many_tiles_per_workgroup_and_decode_sized_batches():
     _mx_check(wl.make_linear_inputs(w, "cuda"), "mx_decode_96x1")
 
 
+def test_mx_linear_decode_sized_batches():
+    # T <= 1024: base product for all tokens at once (contraction range in parts), adapter term by
+    # the decode kernels; with and without adapters, ragged token counts, per-expert ranks
+    w = wl.LinearWorkload("mx_dec_gate", 2048, 1416, 128, 40, [1] * 256, "zipf", 1.1, 2.0, seed=51)
+    _mx_check(wl.make_linear_inputs(w, "cuda"), "mx_decode_256x1")
+    lens = [3, 1, 0, 40, 17, 300, 2]
+    ids = [2, -1, 1, 0, 2, 3, -1]
+    inp = _case("mx_dec_ragged", 640, 264, 64, 4, lens, ids, seed=52)          # 5 blocks: parts of 3 and 2
+    assert inp.wl.T <= 1024
+    _mx_check(inp, "mx_decode_ragged")
+    inp = _case("mx_dec_ranks", 384, 136, 128, 4, lens, ids, seed=53)
+    ranks = [64, 128, 8, 0]
+    for e, k in enumerate(ranks):
+        inp.A_stack[e, k:] = float("nan")
+        inp.B_stack[e, :, k:] = float("nan")
+    _mx_check(inp, "mx_decode_ranks", rank_of_expert=ranks)
+    inp = _case("mx_dec_base_only", 256, 520, 64, 2, [100, 30], [-1, -1], seed=54)
+    _mx_check(inp, "mx_decode_base_only")
+
+
 def test_mx_linear_block_scales_of_very_different_size():
     # rows and column blocks of x and W scaled by powers of two far apart: a wrong scale
     # byte or a scale applied to the wrong block shows as an error of orders of magnitude
