@@ -367,7 +367,9 @@ int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, 
     m.xs = own_q ? w + 2 * u_bytes + xq_bytes : xs;
     m.Wq = Wq;
     m.Ws = Ws;
-    if (own_q && timed(ctx, MOIN_K_MX_QUANT, stream, [&] {
+    // prefill with adapters: the shrink's pass over x writes the codes and scales as well
+    const bool fused_q = own_q && !pv.decode && a.r > 0;
+    if (own_q && !fused_q && timed(ctx, MOIN_K_MX_QUANT, stream, [&] {
             return launch_mx_quantize(x, pv.T, d_in, const_cast<void *>(m.xq), const_cast<void *>(m.xs), 1, stream);
         }) != hipSuccess)
         return MOIN_EHIP;
@@ -392,8 +394,11 @@ int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, 
             return MOIN_EHIP;
         return MOIN_OK;
     }
-    if (a.r > 0 && !pv.decode &&
-        timed(ctx, MOIN_K_SHRINK, stream, [&] { return launch_prefill_shrink(pv, a, stream); }) != hipSuccess)
+    if (a.r > 0 && !pv.decode && timed(ctx, MOIN_K_SHRINK, stream, [&] {
+            return fused_q ? launch_prefill_shrink_quant(pv, a, const_cast<void *>(m.xq),
+                                                         const_cast<void *>(m.xs), stream)
+                           : launch_prefill_shrink(pv, a, stream);
+        }) != hipSuccess)
         return MOIN_EHIP;
     if (timed(ctx, MOIN_K_MX_LINEAR, stream, [&] {
             return launch_linear_mx_stream(pv, m, compute_units(), stream);

@@ -105,6 +105,7 @@ __device__ __forceinline__ void tile_epilogue(char *smem, const typename C::Acc 
 template <int BM_, int BN_, int BK_, int WM_, int WN_>
 struct GemmCore {
     static constexpr bool IS_DMA = false;
+    static constexpr int PF = 1;                     // blocks in flight per thread (see pipelined_blocks_deep)
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
     static constexpr int NT = 64 * WM * WN;          // threads per workgroup
     static constexpr int KCH = BK / 8;               // 16-byte chunks per tile row
@@ -263,6 +264,38 @@ __device__ __forceinline__ void pipelined_blocks(char *smem, int total, Issue is
         if (more) C::store_stage(nxt, g);
         __syncthreads();
     }
+}
+
+// The same loop with the loads of PF blocks in flight per thread, for operands
+// that stream from HBM: a load to registers may stay outstanding for several
+// blocks, and the registers of block `it` go to LDS just before they are needed.
+// `on_block(it, g)` sees block `it` in registers (after its copy to LDS, before
+// the registers are reused).
+template <class C, int PF, class Issue, class OnBlock>
+__device__ __forceinline__ void pipelined_blocks_deep(char *smem, int total, Issue issue,
+                                                      typename C::Acc &acc, OnBlock on_block)
+{
+    typename C::Stage g[PF];
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+        if (u < total) issue(u, g[u]);
+    for (int it0 = 0; it0 < total; it0 += PF) {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) {
+            const int it = it0 + u;
+            if (it < total) {
+                // stage it & 1 was last read for block it - 2: every wave has left that
+                // block's MFMAs behind when it met the others at the barrier of block it - 1
+                char *st = smem + (it & 1) * C::STAGE_BYTES;
+                C::store_stage(st, g[u]);
+                on_block(it, g[u]);
+                if (it + PF < total) issue(it + PF, g[u]);
+                __syncthreads();
+                C::compute_stage(st, acc);
+            }
+        }
+    }
+    __syncthreads();
 }
 
 #define MOIN_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))

@@ -56,6 +56,9 @@ struct LinearArgs {
 
 hipError_t launch_prefill_shrink(const PlanView &pv, const LinearArgs &a, hipStream_t stream);
 hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStream_t stream);
+// shrink + MXFP8 codes / blocked scales of x in one pass over x (d_in a multiple of 128)
+hipError_t launch_prefill_shrink_quant(const PlanView &pv, const LinearArgs &a, void *xq, void *xs,
+                                       hipStream_t stream);
 
 struct DecodeArgs {
     LinearArgs lin;

@@ -24,9 +24,49 @@ struct ShrinkKParams {
     int d_in, r;
     int n_tiles_n;
     float scale;
+    // QUANT only: MXFP8 codes [T, d_in] and scale bytes [d_in / 128, T, 4] of x
+    char *xq, *xs;
+    int64_t T;
 };
 
-template <class C>
+// MXFP8 quantisation of one thread's 8 consecutive values of x (w: four words of
+// two bf16 each) whose block of 32 lies in four neighbouring lanes: the block's
+// scale byte E = max(0, exponent field of the largest magnitude - 8), 127 for a
+// block of zeros; elements = value / 2^(E - 127), clamped to +-448, rounded to
+// nearest even ("Future Works", quantising the base model; OCP Microscaling
+// format).  Returns the 8 codes; E through `scale_byte`.
+__device__ __forceinline__ uint2 mx_quantize8(const uint4 &v, int &scale_byte)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t m = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        m = max(m, w[i] & 0x7FFFu);
+        m = max(m, (w[i] >> 16) & 0x7FFFu);
+    }
+    m = max(m, (uint32_t)__shfl_xor((int)m, 1));
+    m = max(m, (uint32_t)__shfl_xor((int)m, 2));
+    const int E = m == 0 ? 127 : max(0, (int)(m >> 7) - 8);
+    const float inv = bits_f32((uint32_t)(254 - E) << 23);   // 2^(127 - E)
+    float f[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = fminf(fmaxf(bits_f32(w[i] << 16) * inv, -448.f), 448.f);
+        f[2 * i + 1] = fminf(fmaxf(bits_f32(w[i] & 0xFFFF0000u) * inv, -448.f), 448.f);
+    }
+    int lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[0], f[1], 0, false);
+    lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[2], f[3], lo, true);
+    int hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[4], f[5], 0, false);
+    hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], hi, true);
+    scale_byte = E;
+    return make_uint2((uint32_t)lo, (uint32_t)hi);
+}
+
+// QUANT (register-staged tile shapes with BK = 64, d_in a multiple of 128): the
+// pass over x also writes x in MXFP8 for the quantised-base layer, so that x
+// comes from HBM once for both.  The workgroups of the first column tile do it,
+// also for tiles without an adapter, which the plain shrink skips.
+template <class C, bool QUANT = false>
 __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
 {
     extern __shared__ __align__(16) char smem[];
@@ -40,21 +80,24 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
     const int t = tm / SUB, sub = tm % SUB;
     const int e = uniform(p.tile_expert[t]);
     int rows = uniform(p.tile_rows[t]) - sub * C::BM;
-    if (e < 0 || rows <= 0) return;
+    const bool quant = QUANT && tn == 0;
+    if (rows <= 0 || (e < 0 && !quant)) return;
     rows = min(rows, C::BM);
     const int row0 = uniform(p.tile_row0[t]) + sub * C::BM;
     const int n0 = tn * C::BN;
     // the expert's own rank: rows of A_e beyond it do not exist; the main kernel
     // reads u in blocks of 64 columns, so the rest of the last block is written as zeros
-    const int re = min(p.r, uniform(p.tile_rank[t]));
+    const int re = e < 0 ? 0 : min(p.r, uniform(p.tile_rank[t]));
     const int r_read = min(p.r, (re + 63) & ~63);
-    if (n0 >= r_read) return;
+    const bool shrink = n0 < r_read;
+    if (!shrink && !quant) return;
     const int ncols = max(1, min(C::BN, re - n0));      // rows of A_e to fetch (at least one, in bounds)
     const int ncols_out = min(C::BN, r_read - n0);      // columns of u to write
 
     const uint32_t ldx = (uint32_t)p.d_in * 2u;
     const char *xa = p.x + (int64_t)row0 * ldx;
-    const char *ae = p.A_stack + ((int64_t)e * p.r + n0) * ldx;
+    // (a walk for the quantiser alone puts x in A_e's place: valid addresses, unused products)
+    const char *ae = shrink ? p.A_stack + ((int64_t)e * p.r + n0) * ldx : xa;
     const int nkb = (p.d_in + C::BK - 1) / C::BK;
 
     typename C::Acc acc;
@@ -68,12 +111,39 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
         dma_pipelined_blocks<C>(smem, nkb, issue, acc, [](int) {});
     } else {
         const auto vx = C::template make_view<C::A_CH>(xa, ldx, rows);
-        const auto va = C::template make_view<C::B_CH>(ae, ldx, ncols);
+        const auto va = C::template make_view<C::B_CH>(ae, ldx, shrink ? ncols : rows);
         auto issue = [=](int it, typename C::Stage &g) __attribute__((always_inline)) {
             C::load_stage(g, vx, va, (uint32_t)it * (C::BK * 2), ldx);
         };
-        pipelined_blocks<C>(smem, nkb, issue, acc);
+        if constexpr (C::PF > 1) {
+            static_assert(!QUANT || C::BK == 64, "a block of 32 values in four neighbouring lanes, two per row");
+            const int qrow = threadIdx.x / C::KCH, kc = threadIdx.x % C::KCH;
+            pipelined_blocks_deep<C, C::PF>(smem, nkb, issue, acc, [&](int it, const typename C::Stage &g)
+                                                                       __attribute__((always_inline)) {
+                if constexpr (QUANT) {
+                    if (!quant) return;
+#pragma unroll
+                    for (int i = 0; i < C::A_CH; ++i) {
+                        int E;
+                        const uint2 codes = mx_quantize8(g.a[i], E);
+                        // the two scale bytes of a row's 64 values, into the row's first thread
+                        const uint32_t pair = (uint32_t)E | ((uint32_t)__shfl_down(E, 4) << 8);
+                        const int row = qrow + i * C::RPP;
+                        if (row < rows) {
+                            const int k0 = it * 64;
+                            *reinterpret_cast<uint2 *>(p.xq + (int64_t)(row0 + row) * p.d_in + k0 + kc * 8) = codes;
+                            if (kc == 0)
+                                *reinterpret_cast<uint16_t *>(p.xs + ((int64_t)(k0 >> 7) * p.T + row0 + row) * 4 +
+                                                              ((k0 >> 5) & 3)) = (uint16_t)pair;
+                        }
+                    }
+                }
+            });
+        } else {
+            pipelined_blocks<C>(smem, nkb, issue, acc);
+        }
     }
+    if (!shrink) return;
 
     const int64_t ldu = (int64_t)p.r * 2;
     char *uh = p.u_hi + (int64_t)row0 * ldu;
@@ -108,6 +178,14 @@ using CfgShrink = GemmCore<64, 64, 64, 2, 2>;        // 4 waves, wave patch 32 x
 using CfgShrinkDma = DmaCore<64, 64, 64, 2, 2, 4>;
 // ranks from 65 to 128: the whole rank in one tile, so x streams from HBM once
 using CfgShrinkR128 = DmaCore<128, 128, 32, 2, 4, 4>;
+// the quantising variant: register-staged (the quantiser works on the registers on
+// their way to LDS), the loads of four blocks in flight per thread
+template <int BM, int BN, int BK, int WM, int WN, int PF_>
+struct DeepCore : GemmCore<BM, BN, BK, WM, WN> {
+    static constexpr int PF = PF_;
+};
+using CfgShrinkDeep = DeepCore<128, 128, 64, 2, 4, 4>;   // ranks 65..128
+using CfgShrinkDeep64 = DeepCore<128, 64, 64, 4, 2, 4>;  // ranks up to 64, and above 128 in column tiles
 
 template <class K>
 static hipError_t allow_lds(K kern, int bytes)
@@ -129,7 +207,9 @@ hipError_t prepare_linear_kernels()
     if ((e = allow_lds(&linear_kernel<CfgDecodeBase>, CfgDecodeBase::SMEM_BYTES)) != hipSuccess) return e;
     if ((e = allow_lds(&shrink_kernel<CfgShrink>, CfgShrink::SMEM_BYTES)) != hipSuccess) return e;
     if ((e = allow_lds(&shrink_kernel<CfgShrinkR128>, CfgShrinkR128::SMEM_BYTES)) != hipSuccess) return e;
-    return allow_lds(&shrink_kernel<CfgShrinkDma>, CfgShrinkDma::SMEM_BYTES);
+    if ((e = allow_lds(&shrink_kernel<CfgShrinkDma>, CfgShrinkDma::SMEM_BYTES)) != hipSuccess) return e;
+    if ((e = allow_lds(&shrink_kernel<CfgShrinkDeep, true>, CfgShrinkDeep::SMEM_BYTES)) != hipSuccess) return e;
+    return allow_lds(&shrink_kernel<CfgShrinkDeep64, true>, CfgShrinkDeep64::SMEM_BYTES);
 }
 
 static inline int round_up8(int v) { return (v + 7) & ~7; }
@@ -148,10 +228,13 @@ int compute_units()
     return cached[dev];
 }
 
-template <class C>
-static hipError_t launch_shrink_as(const PlanView &pv, const LinearArgs &a, hipStream_t stream)
+// xq / xs: the quantising variant's outputs
+template <class C, bool QUANT = false>
+static hipError_t launch_shrink_as(const PlanView &pv, const LinearArgs &a, hipStream_t stream, void *xq = nullptr,
+                                   void *xs = nullptr)
 {
     ShrinkKParams p;
+    p.xq = (char *)xq; p.xs = (char *)xs; p.T = pv.T;
     p.x = (const char *)a.x; p.A_stack = (const char *)a.A_stack;
     p.u_hi = (char *)a.u_hi; p.u_lo = (char *)a.u_lo;
     p.tile_row0 = pv.tile_row0; p.tile_rows = pv.tile_rows; p.tile_expert = pv.tile_expert;
@@ -161,9 +244,20 @@ static hipError_t launch_shrink_as(const PlanView &pv, const LinearArgs &a, hipS
     p.n_tiles_n = (a.r + C::BN - 1) / C::BN;
     const int64_t grid = (int64_t)pv.max_tiles * (TILE_M / C::BM) * p.n_tiles_n;
     if (grid > 0x7ffffff0LL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(shrink_kernel<C>, dim3((unsigned)round_up8((int)grid)), dim3(C::NT),
+    hipLaunchKernelGGL((shrink_kernel<C, QUANT>), dim3((unsigned)round_up8((int)grid)), dim3(C::NT),
                        C::SMEM_BYTES, stream, p);
     return hipGetLastError();
+}
+
+// The prefill shrink and the MXFP8 quantisation of x in one pass over x (r >= 1,
+// d_in a multiple of 128).
+hipError_t launch_prefill_shrink_quant(const PlanView &pv, const LinearArgs &a, void *xq, void *xs,
+                                       hipStream_t stream)
+{
+    if (pv.max_tiles <= 0) return hipSuccess;
+    if (a.r <= 0 || a.d_in % 128) return hipErrorInvalidValue;
+    if (a.r > 64 && a.r <= 128) return launch_shrink_as<CfgShrinkDeep, true>(pv, a, stream, xq, xs);
+    return launch_shrink_as<CfgShrinkDeep64, true>(pv, a, stream, xq, xs);
 }
 
 hipError_t launch_prefill_shrink(const PlanView &pv, const LinearArgs &a, hipStream_t stream)

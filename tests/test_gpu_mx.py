@@ -213,21 +213,29 @@ def test_mx_linear_with_per_expert_ranks():
 def test_mx_linear_on_a_plan_with_shared_activations():
     # the planned entry, with the activations quantised by the call or handed in, gives the bits of the
     # unplanned one (same kernels, same order)
-    lens = [300, 200, 257, 100, 280]
-    ids = [0, 1, 2, -1, 3]
-    inp = _case("mx_planned", 256, 264, 64, 4, lens, ids, seed=42)
+    # (with adapters the call quantises x inside the shrink's pass over it: one tile shape up to rank 64
+    # and in column tiles above 128, another from 65 to 128)
+    lens = [300, 200, 257, 100, 280, 1, 700]
+    ids = [0, 1, 2, -1, 3, -1, 1]
     ctx = gc.ctx()
-    Wq, Ws = moin.moin_mx_quantize(ctx, inp.W, blocked=True)
-    y0 = moin.moin_lora_linear_mx(ctx, inp.x, inp.seq_offsets, inp.expert_ids, Wq, Ws, inp.A_stack, inp.B_stack, 2.0)
-    plan = moin.Plan(ctx).build(inp.seq_offsets, inp.expert_ids, inp.wl.T, inp.wl.E)
-    y1 = moin.moin_lora_linear_mx_planned(ctx, plan, inp.x, Wq, Ws, inp.A_stack, inp.B_stack, 2.0)
-    xq, xs = moin.moin_mx_quantize(ctx, inp.x, blocked=True)
-    y2 = moin.moin_lora_linear_mx_planned(ctx, plan, inp.x, Wq, Ws, inp.A_stack, inp.B_stack, 2.0, xq=xq, xs=xs)
-    ctx.check()
-    assert torch.equal(y0, y1) and torch.equal(y0, y2)
-    with pytest.raises(ValueError):
-        moin.moin_lora_linear_mx_planned(ctx, plan, inp.x, Wq, Ws, inp.A_stack, inp.B_stack, 2.0, xq=xq)
-    plan.close()
+    for r in (64, 128, 192):
+        print(f"[gpu] mx planned r={r}", flush=True)
+        inp = _case("mx_planned", 256, 264, r, 4, lens, ids, seed=42 + r)
+        Wq, Ws = moin.moin_mx_quantize(ctx, inp.W, blocked=True)
+        y0 = moin.moin_lora_linear_mx(ctx, inp.x, inp.seq_offsets, inp.expert_ids, Wq, Ws, inp.A_stack, inp.B_stack,
+                                      2.0)
+        plan = moin.Plan(ctx).build(inp.seq_offsets, inp.expert_ids, inp.wl.T, inp.wl.E)
+        y1 = moin.moin_lora_linear_mx_planned(ctx, plan, inp.x, Wq, Ws, inp.A_stack, inp.B_stack, 2.0)
+        xq, xs = moin.moin_mx_quantize(ctx, inp.x, blocked=True)
+        y2 = moin.moin_lora_linear_mx_planned(ctx, plan, inp.x, Wq, Ws, inp.A_stack, inp.B_stack, 2.0, xq=xq, xs=xs)
+        ctx.check()
+        assert torch.equal(y0, y1) and torch.equal(y0, y2), f"r={r}"
+        if r == 64:
+            with pytest.raises(ValueError):
+                moin.moin_lora_linear_mx_planned(ctx, plan, inp.x, Wq, Ws, inp.A_stack, inp.B_stack, 2.0, xq=xq)
+        plan.close()
+    # r = 192 against the oracle as well
+    _mx_check(inp, "mx_planned_r192")
 
 
 def test_mx_linear_rejects_unsupported_shapes():
