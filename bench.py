@@ -487,8 +487,9 @@ def main():
                     help="first run a plain device copy of this many MiB (3 times): the known-size "
                          "kernel that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--also", default="decode,router,layer,kmeans,mx",
-                    help="comma list of extra workloads to report: decode,router,layer,kmeans,cache,ranks,mx "
-                         "(or 'none'); cache (it pins 10 GB of host memory) and ranks are not in the default list")
+                    help="comma list of extra workloads to report: decode,router,layer,kmeans,cache,ranks,mx,mx-step "
+                         "(or 'none'); cache (it pins 10 GB of host memory) and ranks are not in the default list; "
+                         "mx-step is the headline step on the quantised base alone, mx adds its layer and decode")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU figure exists)",
@@ -520,8 +521,9 @@ def main():
         res["cache"] = bench_cache(ctx)
     if "ranks" in extra:
         res["ranks"] = bench_ranks(ctx, args.steps, args.warmup)
-    if "mx" in extra:
+    if "mx" in extra or "mx-step" in extra:
         res["mx"] = bench_mx(ctx, args.steps, args.warmup)
+    if "mx" in extra:
         res["mx"]["layer"] = bench_layer_mx(ctx, max(5, args.steps // 5), 2)
         res["mx"]["decode_gate"] = bench_decode_mx(ctx, args.steps, args.warmup)
     ctx.close()
