@@ -441,8 +441,8 @@ def bench_decode_mx(ctx, steps, warmup, n_draws=8):
 
 def bench_layer_mx(ctx, steps, warmup):
     """configs[4] on a quantised base: the seven projections' weights in MXFP8 (quantised once, outside
-    the step); activations quantised once per distinct input (q, k, v share theirs, gate and up theirs:
-    four quantiser launches per layer)."""
+    the step); activations quantised once per distinct input (q, k, v share theirs, gate and up theirs), by the
+    first projection that reads it."""
     wls = wl.config_layer()
     T = wls[0].T
     ids = wl.draw_expert_ids(wls[0].S, wls[0].E, "zipf", 1.5, wls[0].seed * 8 + 4)
@@ -456,16 +456,22 @@ def bench_layer_mx(ctx, steps, warmup):
     wq = {n: moin.moin_mx_quantize(ctx, i.W, blocked=True) for n, i in inputs.items()}
     plan = moin.Plan(ctx)
 
+    codes = {}
+    for n, i in inputs.items():
+        if src[n] not in codes:
+            codes[src[n]] = (torch.empty((T, i.wl.d_in), dtype=torch.uint8, device="cuda"),
+                             torch.empty((i.wl.d_in // 128, T, 4), dtype=torch.uint8, device="cuda"))
+
     def step():
         plan.build(off, eids, T, wls[0].E)
-        quantised = {}
+        quantised = set()
         for n, i in inputs.items():
             x = h0 if src[n] is None else outs[src[n]]
-            if src[n] not in quantised:
-                quantised[src[n]] = moin.moin_mx_quantize(ctx, x, blocked=True)
-            xq, xs = quantised[src[n]]
+            xq, xs = codes[src[n]]
+            # the first projection of each distinct input quantises it (in its shrink's pass over x)
             moin.moin_lora_linear_mx_planned(ctx, plan, x, wq[n][0], wq[n][1], i.A_stack, i.B_stack, i.wl.scale,
-                                             xq=xq, xs=xs, out=outs[n])
+                                             xq=xq, xs=xs, emit=src[n] not in quantised, out=outs[n])
+            quantised.add(src[n])
 
     ms, _ = timed_region(step, steps, warmup)
     ctx.check()

@@ -203,12 +203,19 @@ int moin_lora_linear_mx(moin_ctx *ctx, const void *x, const int32_t *seq_offsets
 
 /* moin_lora_linear_mx on a plan (moin_plan_build / moin_plan_build_ranked), for the
  * projections of a layer.  xq [T, d_in] / xs (MOIN_MX_BLOCKED layout,
- * [d_in/128, T, 4]): the activations as quantised by moin_mx_quantize, so that
- * projections that share their input (q, k, v; gate, up) quantise it once; both
- * NULL: the call quantises x itself, into the context's workspace.  x (bf16) is
- * needed in either case, for the adapter term. */
+ * [d_in/128, T, 4]) hold the quantised activations (device, 16-byte aligned), so
+ * that projections that share their input (q, k, v; gate, up) quantise it once:
+ *   MOIN_MX_X_INTERNAL  xq, xs NULL: the call quantises x into the context's workspace;
+ *   MOIN_MX_X_EMIT      the call quantises x into xq / xs (the caller's buffers; with
+ *                       adapters in a prefill batch that happens inside the shrink's
+ *                       pass over x) and uses them;
+ *   MOIN_MX_X_GIVEN     xq / xs are read: what an earlier MOIN_MX_X_EMIT call or
+ *                       moin_mx_quantize(x, MOIN_MX_BLOCKED) wrote for the same x.
+ * x (bf16) is needed in every case, for the adapter term.  A mode that does not
+ * fit the pointers returns MOIN_EINVAL. */
+enum { MOIN_MX_X_INTERNAL = 0, MOIN_MX_X_EMIT = 1, MOIN_MX_X_GIVEN = 2 };
 int moin_lora_linear_mx_planned(moin_ctx *ctx, const moin_plan *plan, const void *x,
-                                const void *xq, const void *xs, const void *Wq, const void *Ws,
+                                void *xq, void *xs, int32_t x_codes, const void *Wq, const void *Ws,
                                 const void *A_stack, const void *B_stack, int32_t d_in,
                                 int32_t d_out, int32_t r, float scale, void *y, moin_dtype y_dt,
                                 void *stream);

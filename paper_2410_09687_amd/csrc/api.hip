@@ -326,8 +326,8 @@ int linear_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, con
 // through the quantiser, then the block-scaled main kernel.
 // xq / xs: the activations already quantised (blocked scale layout), or both null:
 // then they are quantised here, into the workspace.
-int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, const void *xq,
-                           const void *xs, const void *Wq, const void *Ws, const void *A_stack,
+int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, void *xq,
+                           void *xs, bool x_given, const void *Wq, const void *Ws, const void *A_stack,
                            const void *B_stack, int32_t d_in, int32_t d_out, int32_t r, float scale,
                            void *y, moin_dtype y_dt, hipStream_t stream)
 {
@@ -342,9 +342,10 @@ int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, 
     a.d_in = d_in; a.d_out = d_out; a.r = adapters ? r : 0; a.scale = scale;
     a.u_hi = a.u_lo = nullptr;
     const size_t u_bytes = align_up((size_t)pv.T * (size_t)a.r * 2, 256);
-    const bool own_q = xq == nullptr;
-    const size_t xq_bytes = own_q ? align_up((size_t)pv.T * (size_t)d_in, 256) : 0;
-    const size_t xs_bytes = own_q ? align_up((size_t)pv.T * (size_t)(d_in / 32), 256) : 0;
+    const bool ws_q = xq == nullptr;      // codes and scales live in the workspace
+    const bool own_q = !x_given;          // this call quantises x
+    const size_t xq_bytes = ws_q ? align_up((size_t)pv.T * (size_t)d_in, 256) : 0;
+    const size_t xs_bytes = ws_q ? align_up((size_t)pv.T * (size_t)(d_in / 32), 256) : 0;
     m.plain_splits = 0;
     m.plain_kb_per_split = 0;
     // decode-sized batches with adapters: the base product for all tokens at once as
@@ -363,8 +364,8 @@ int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, 
     char *w = static_cast<char *>(ctx->ws);
     a.u_hi = w;
     a.u_lo = w + u_bytes;
-    m.xq = own_q ? w + 2 * u_bytes : xq;
-    m.xs = own_q ? w + 2 * u_bytes + xq_bytes : xs;
+    m.xq = ws_q ? w + 2 * u_bytes : xq;
+    m.xs = ws_q ? w + 2 * u_bytes + xq_bytes : xs;
     m.Wq = Wq;
     m.Ws = Ws;
     // prefill with adapters: the shrink's pass over x writes the codes and scales as well
@@ -698,17 +699,20 @@ int moin_lora_linear_mx(moin_ctx *ctx, const void *x, const int32_t *seq_offsets
     }
     int rc = plan_build_impl(ctx, ctx->own_plan, seq_offsets, expert_ids, S, T, E, rank_of_expert, st);
     if (rc != MOIN_OK) return rc;
-    return linear_mx_planned_impl(ctx, ctx->own_plan, x, nullptr, nullptr, Wq, Ws, A_stack, B_stack, d_in,
+    return linear_mx_planned_impl(ctx, ctx->own_plan, x, nullptr, nullptr, false, Wq, Ws, A_stack, B_stack, d_in,
                                   d_out, r, scale, y, y_dt, st);
 }
 
-int moin_lora_linear_mx_planned(moin_ctx *ctx, const moin_plan *plan, const void *x, const void *xq,
-                                const void *xs, const void *Wq, const void *Ws, const void *A_stack,
+int moin_lora_linear_mx_planned(moin_ctx *ctx, const moin_plan *plan, const void *x, void *xq, void *xs,
+                                int32_t x_codes, const void *Wq, const void *Ws, const void *A_stack,
                                 const void *B_stack, int32_t d_in, int32_t d_out, int32_t r,
                                 float scale, void *y, moin_dtype y_dt, void *stream)
 {
     if (!ctx || !plan || plan->device != ctx->device) return MOIN_EINVAL;
-    if ((xq == nullptr) != (xs == nullptr)) return MOIN_EINVAL;
+    if (x_codes != MOIN_MX_X_INTERNAL && x_codes != MOIN_MX_X_EMIT && x_codes != MOIN_MX_X_GIVEN)
+        return MOIN_EINVAL;
+    if ((xq == nullptr) != (xs == nullptr) || (xq == nullptr) != (x_codes == MOIN_MX_X_INTERNAL))
+        return MOIN_EINVAL;
     DeviceGuard guard(ctx->device);
     if (!guard.ok) return MOIN_EHIP;
     if (plan->built && plan->pv.S > 0 && plan->pv.T > 0) {
@@ -718,7 +722,7 @@ int moin_lora_linear_mx_planned(moin_ctx *ctx, const moin_plan *plan, const void
         if (xq && (misaligned(xq, 16) || misaligned(xs, 16))) return MOIN_EINVAL;
         if (!mx_stream_kernel_fits(d_in, (plan->pv.E > 0 && r > 0) ? r : 0)) return MOIN_EINVAL;
     }
-    return linear_mx_planned_impl(ctx, plan, x, xq, xs, Wq, Ws, A_stack, B_stack, d_in, d_out, r, scale, y,
+    return linear_mx_planned_impl(ctx, plan, x, xq, xs, x_codes == MOIN_MX_X_GIVEN, Wq, Ws, A_stack, B_stack, d_in, d_out, r, scale, y,
                                   y_dt, static_cast<hipStream_t>(stream));
 }
 

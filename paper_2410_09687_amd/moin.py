@@ -18,6 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmoin.so")
 
 MOIN_F32, MOIN_BF16 = 0, 1
+MOIN_MX_X_INTERNAL, MOIN_MX_X_EMIT, MOIN_MX_X_GIVEN = 0, 1, 2
 MOIN_ROUTE_RETAINED_ONLY = 1
 (K_PLAN, K_SHRINK, K_LINEAR, K_ROUTE, K_ROUTE_AUX, K_DECODE_SHRINK, K_DECODE_EXPAND, K_DECODE_BASE,
  K_KMEANS_SORT, K_KMEANS_SUM, K_KMEANS_FINAL) = range(11)
@@ -72,8 +73,8 @@ def load() -> ctypes.CDLL:
     lib.moin_mx_quantize.argtypes = [vp, vp, i64, i64, vp, vp, i32, vp]
     lib.moin_lora_linear_mx.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp, vp, i32, i32, i32, i32, vp,
                                         c.c_float, vp, c.c_int, vp]
-    lib.moin_lora_linear_mx_planned.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, c.c_float, vp,
-                                                c.c_int, vp]
+    lib.moin_lora_linear_mx_planned.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, i32, i32, c.c_float,
+                                                vp, c.c_int, vp]
     lib.moin_plan_build_ranked.argtypes = [vp, vp, vp, vp, i32, i64, i32, vp, vp]
     lib.moin_plan_create.argtypes = [vp, c.POINTER(vp)]
     lib.moin_plan_destroy.argtypes = [vp]
@@ -356,9 +357,10 @@ def moin_lora_linear_planned(ctx: Context, plan: Plan, x: torch.Tensor, W: torch
 def moin_lora_linear_mx_planned(ctx: Context, plan: "Plan", x: torch.Tensor, Wq: torch.Tensor, Ws: torch.Tensor,
                                 A_stack: Optional[torch.Tensor], B_stack: Optional[torch.Tensor], scale: float,
                                 xq: Optional[torch.Tensor] = None, xs: Optional[torch.Tensor] = None,
-                                y_dtype=torch.bfloat16, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """``moin_lora_linear_mx`` on a plan; ``xq``, ``xs`` (from ``moin_mx_quantize(x, blocked=True)``) let
-    projections that share their input quantise it once."""
+                                emit: bool = False, y_dtype=torch.bfloat16, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """``moin_lora_linear_mx`` on a plan; ``xq``, ``xs`` let projections that share their input quantise it
+    once: the first call fills them (``emit=True``; uint8 [T, d_in] and [d_in/128, T, 4]), the others read them
+    (as they read what ``moin_mx_quantize(x, blocked=True)`` returns)."""
     if x.dim() != 2 or Wq.dim() != 2 or x.shape[1] != Wq.shape[1] or x.shape[0] != plan.T:
         raise ValueError("x [T,d_in] (T as planned) and Wq [d_out,d_in] expected")
     if Wq.dtype != torch.uint8 or Ws.dtype != torch.uint8 or Wq.shape[1] % 128 or \
@@ -372,11 +374,14 @@ def moin_lora_linear_mx_planned(ctx: Context, plan: "Plan", x: torch.Tensor, Wq:
         raise ValueError("xq and xs go together")
     if xq is not None and (tuple(xq.shape) != (T, d_in) or tuple(xs.shape) != (d_in // 128, T, 4)):
         raise ValueError("xq [T,d_in] / xs [d_in/128,T,4] (blocked layout) expected")
+    if emit and xq is None:
+        raise ValueError("emit=True needs xq and xs to write to")
+    mode = MOIN_MX_X_INTERNAL if xq is None else (MOIN_MX_X_EMIT if emit else MOIN_MX_X_GIVEN)
     y, ydt = _y_out(x, d_out, y_dtype, out)
     bf = torch.bfloat16
     _ck(load().moin_lora_linear_mx_planned(
         ctx._h, plan._h, _dev_ptr(x, "x", bf) if T else None, _dev_ptr(xq, "xq", torch.uint8),
-        _dev_ptr(xs, "xs", torch.uint8), _dev_ptr(Wq, "Wq", torch.uint8), _dev_ptr(Ws, "Ws", torch.uint8),
+        _dev_ptr(xs, "xs", torch.uint8), mode, _dev_ptr(Wq, "Wq", torch.uint8), _dev_ptr(Ws, "Ws", torch.uint8),
         _dev_ptr(A_stack, "A_stack", bf), _dev_ptr(B_stack, "B_stack", bf), d_in, d_out, r, float(scale),
         _dev_ptr(y, "y") if T else None, ydt, _stream_ptr(stream)), "moin_lora_linear_mx_planned")
     return y

@@ -228,11 +228,26 @@ def test_mx_linear_on_a_plan_with_shared_activations():
         y1 = moin.moin_lora_linear_mx_planned(ctx, plan, inp.x, Wq, Ws, inp.A_stack, inp.B_stack, 2.0)
         xq, xs = moin.moin_mx_quantize(ctx, inp.x, blocked=True)
         y2 = moin.moin_lora_linear_mx_planned(ctx, plan, inp.x, Wq, Ws, inp.A_stack, inp.B_stack, 2.0, xq=xq, xs=xs)
+        # the first projection of a shared input fills the caller's buffers, the others read them
+        xq3, xs3 = torch.full_like(xq, 0xAA), torch.full_like(xs, 0xAA)
+        y3 = moin.moin_lora_linear_mx_planned(ctx, plan, inp.x, Wq, Ws, inp.A_stack, inp.B_stack, 2.0, xq=xq3, xs=xs3,
+                                              emit=True)
+        y4 = moin.moin_lora_linear_mx_planned(ctx, plan, inp.x, Wq, Ws, inp.A_stack, inp.B_stack, 2.0, xq=xq3, xs=xs3)
         ctx.check()
         assert torch.equal(y0, y1) and torch.equal(y0, y2), f"r={r}"
+        assert torch.equal(xq3, xq) and torch.equal(xs3, xs), f"r={r}: codes written by the shrink's pass"
+        assert torch.equal(y0, y3) and torch.equal(y0, y4), f"r={r}"
         if r == 64:
             with pytest.raises(ValueError):
                 moin.moin_lora_linear_mx_planned(ctx, plan, inp.x, Wq, Ws, inp.A_stack, inp.B_stack, 2.0, xq=xq)
+            with pytest.raises(ValueError):
+                moin.moin_lora_linear_mx_planned(ctx, plan, inp.x, Wq, Ws, inp.A_stack, inp.B_stack, 2.0, emit=True)
+            # emit without adapters, and on a decode-sized plan: the plain quantiser fills the buffers
+            xq5, xs5 = torch.full_like(xq, 0x55), torch.full_like(xs, 0x55)
+            y5 = moin.moin_lora_linear_mx_planned(ctx, plan, inp.x, Wq, Ws, None, None, 2.0, xq=xq5, xs=xs5, emit=True)
+            y6 = moin.moin_lora_linear_mx_planned(ctx, plan, inp.x, Wq, Ws, None, None, 2.0)
+            ctx.check()
+            assert torch.equal(xq5, xq) and torch.equal(xs5, xs) and torch.equal(y5, y6)
         plan.close()
     # r = 192 against the oracle as well
     _mx_check(inp, "mx_planned_r192")
