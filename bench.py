@@ -104,6 +104,29 @@ def cpu_baseline_prefill(inp, target_s=12.0):
                       f"fp64 oracle, {dt:.1f} s"}
 
 
+def bench_ceilings(ctx):
+    """What this very box sustains, beside the datasheet peaks: a loop of bf16 MFMAs alone on N(0,1)
+    operands (the matrix cores reach their power limit on random data well below the datasheet figure) and a
+    plain streaming read of 1 GiB.  About 40 ms of GPU time."""
+    g = torch.Generator(device="cuda").manual_seed(20241013)
+    ops = torch.randn((1 << 20,), device="cuda", generator=g).to(torch.bfloat16)
+    buf = torch.empty(1 << 28, dtype=torch.int32, device="cuda").fill_(1)
+    iters = 4000
+    flops = [0.0]
+
+    def run():
+        flops[0] = moin.moin_probe_mfma_bf16(ctx, ops, iters)[1]
+        moin.moin_probe_read(ctx, buf)
+
+    run()
+    kt = kernel_times(ctx, run, 3)
+    ctx.check()
+    return {"mfma_bf16_TFLOPs": flops[0] / (kt["probe_mfma"]["avg_ms"] * 1e-3) / 1e12,
+            "read_GBps": buf.numel() * 4.0 / (kt["probe_read"]["avg_ms"] * 1e-3) / 1e9,
+            "what": "MFMA-only loop (v_mfma_f32_32x32x16_bf16, N(0,1) operands, 2 workgroups of 8 waves per "
+                    "compute unit); streaming read of 1 GiB (16-byte loads, 8 in flight per thread)"}
+
+
 def bench_prefill(ctx, steps, warmup, with_cpu):
     w = wl.config_prefill()
     inp = wl.make_linear_inputs(w, "cuda")
@@ -489,6 +512,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the on-box ceilings (MFMA-only loop, streaming read) reported beside the datasheet peaks")
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="first run a plain device copy of this many MiB (3 times): the known-size "
                          "kernel that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -514,15 +539,29 @@ def main():
         del src, dst
     ctx = moin.Context(0)
     res = bench_prefill(ctx, args.steps, args.warmup, not args.no_cpu_baseline)
+    if not args.no_ceilings:
+        # after the headline, so that the probes do not warm or cool the chip ahead of it
+        res["measured_ceilings"] = c = bench_ceilings(ctx)
+        res["roofline"]["frac_of_measured_mfma_ceiling"] = res["roofline"]["achieved"] / c["mfma_bf16_TFLOPs"]
     extra = [s for s in args.also.split(",") if s and s != "none"]
     if "decode" in extra:
         res["decode"] = bench_decode(ctx, args.steps, args.warmup)
+        if "measured_ceilings" in res:
+            for d in res["decode"].values():
+                d["roofline"]["frac_of_measured_read_ceiling"] = d["roofline"]["achieved"] / c["read_GBps"]
     if "router" in extra:
         res["router"] = bench_router(ctx, max(5, args.steps // 5), 2)
     if "layer" in extra:
         res["layer"] = bench_layer(ctx, max(5, args.steps // 5), 2)
     if "kmeans" in extra:
         res["kmeans"] = bench_kmeans(ctx, max(5, args.steps // 5), 2)
+    if "measured_ceilings" in res:
+        for k in ("router", "layer"):
+            if k in res:
+                res[k]["frac_of_measured_mfma_ceiling"] = res[k]["TFLOPs"] / c["mfma_bf16_TFLOPs"]
+        if "kmeans" in res:
+            res["kmeans"]["roofline"]["frac_of_measured_read_ceiling"] = \
+                res["kmeans"]["roofline"]["achieved"] / c["read_GBps"]
     if "cache" in extra:
         res["cache"] = bench_cache(ctx)
     if "ranks" in extra:

@@ -65,7 +65,9 @@ typedef enum {
     MOIN_K_KMEANS_FINAL = 10, /* K-means update: means, objective; cluster pruning */
     MOIN_K_MX_QUANT = 11,     /* quantised base: bf16 -> MXFP8 codes + scales    */
     MOIN_K_MX_LINEAR = 12,    /* quantised base: y = xq Wq^T + u B_e^T           */
-    MOIN_K_COUNT = 13
+    MOIN_K_PROBE_MFMA = 13,   /* measurement aid: bf16 matrix-core loop            */
+    MOIN_K_PROBE_READ = 14,   /* measurement aid: streaming read                   */
+    MOIN_K_COUNT = 15
 } moin_kernel_id;
 
 /* ---- context ----------------------------------------------------------- */
@@ -345,6 +347,26 @@ int moin_timing_enable(moin_ctx *ctx, int on);
 int moin_timing_reset(moin_ctx *ctx);
 int moin_timing_read(moin_ctx *ctx, int kernel_id, double *ms_sum,
                      int64_t *launches);
+
+/* Measurement aids: the ceilings of this very device, beside the datasheet peaks,
+ * for the roofline fractions that bench.py reports (the hot path of the paper's
+ * method does not call them).
+ * moin_probe_out_len: elements that `out` of the two probes must hold.
+ * moin_probe_mfma_bf16: every wave of a chip-filling grid runs `iters` times 16
+ *   independent v_mfma_f32_32x32x16_bf16 on operands taken from `operands` (device,
+ *   bf16 values, n_bytes a multiple of 16 and at least 16; the values matter: the
+ *   matrix cores reach their power limit sooner on random data than on constants);
+ *   out[i] (device, fp32) = sum of thread i's accumulators; *flops (host, may be
+ *   NULL) = the flops of the launch.
+ * moin_probe_read: reads src (device, n_bytes a multiple of 16) once, eight 16-byte
+ *   loads per thread in flight; out[i] (device) = sum mod 2^32 of the 32-bit words
+ *   thread i read.
+ * Time them with moin_timing_* (MOIN_K_PROBE_MFMA, MOIN_K_PROBE_READ).  Errors:
+ * MOIN_EINVAL for null pointers or sizes as excluded above. */
+int64_t moin_probe_out_len(moin_ctx *ctx);
+int moin_probe_mfma_bf16(moin_ctx *ctx, const void *operands, int64_t n_bytes, int32_t iters,
+                         float *out, double *flops, void *stream);
+int moin_probe_read(moin_ctx *ctx, const void *src, int64_t n_bytes, uint32_t *out, void *stream);
 
 #ifdef __cplusplus
 }

@@ -165,4 +165,10 @@ int compute_units();   // of the current device
 
 hipError_t prepare_kernels();  // one-time attribute set-up (large dynamic LDS)
 
+// on-box ceilings (probe.hip): out holds probe_out_len() elements
+int64_t probe_out_len();
+hipError_t launch_probe_mfma(const void *operands, int64_t n_bytes, int iters, float *out, double *flops,
+                             hipStream_t stream);
+hipError_t launch_probe_read(const void *src, int64_t n_bytes, uint32_t *out, hipStream_t stream);
+
 }  // namespace moin

@@ -1,0 +1,92 @@
+// On-box ceilings that the roofline fractions of the real kernels are read
+// against, beside the datasheet peaks: a loop of nothing but bf16 MFMAs on
+// operands the caller supplies (matrix-core throughput depends on the data: the
+// chip runs into its power limit on random values long before it does on
+// constants), and a plain streaming read.  Measurement aids, not steps of the
+// method.
+#include "gemm_core.h"
+#include "kernels.h"
+
+namespace moin {
+
+constexpr int PROBE_BLOCK = 512;      // 8 waves
+constexpr int PROBE_WG_PER_CU = 2;
+constexpr int PROBE_OPS = 4;          // A and B operand registers per lane (16 bytes each)
+
+// Per iteration and wave: 16 independent v_mfma_f32_32x32x16_bf16 (8 accumulators,
+// each fed twice), no memory access.  out[tid] = sum of the lane's accumulators.
+__global__ __launch_bounds__(PROBE_BLOCK) void probe_mfma_kernel(const uint4 *__restrict__ in, uint32_t n16,
+                                                                 int iters, float *__restrict__ out)
+{
+    const uint32_t tid = blockIdx.x * PROBE_BLOCK + threadIdx.x;
+    bf16x8_t a[PROBE_OPS], b[PROBE_OPS];
+#pragma unroll
+    for (int j = 0; j < PROBE_OPS; ++j) {
+        a[j] = __builtin_bit_cast(bf16x8_t, in[(tid * (2u * PROBE_OPS) + j) % n16]);
+        b[j] = __builtin_bit_cast(bf16x8_t, in[(tid * (2u * PROBE_OPS) + PROBE_OPS + j) % n16]);
+    }
+    f32x16_t acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 1], b[i >> 1], acc[i], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 + (i & 1)], b[i >> 1], acc[i], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s += acc[i][e];
+    out[tid] = s;
+}
+
+// Every 16-byte word of src once, eight independent loads per thread in flight;
+// out[tid] = sum (mod 2^32) of the 32-bit words the thread read.
+__global__ __launch_bounds__(256) void probe_read_kernel(const uint4 *__restrict__ src, int64_t n16,
+                                                         uint32_t *__restrict__ out)
+{
+    const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    uint32_t s = 0;
+    int64_t i = tid;
+    for (; i + 7 * stride < n16; i += 8 * stride) {
+        uint4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u].x + v[u].y + v[u].z + v[u].w;
+    }
+    for (; i < n16; i += stride) {
+        const uint4 v = src[i];
+        s += v.x + v.y + v.z + v.w;
+    }
+    out[tid] = s;
+}
+
+int64_t probe_out_len() { return (int64_t)compute_units() * PROBE_WG_PER_CU * PROBE_BLOCK; }
+
+hipError_t launch_probe_mfma(const void *operands, int64_t n_bytes, int iters, float *out, double *flops,
+                             hipStream_t stream)
+{
+    const int grid = compute_units() * PROBE_WG_PER_CU;
+    if (flops) *flops = (double)grid * (PROBE_BLOCK / 64) * (double)iters * 16.0 * (2.0 * 32 * 32 * 16);
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3(grid), dim3(PROBE_BLOCK), 0, stream,
+                       reinterpret_cast<const uint4 *>(operands), (uint32_t)(n_bytes / 16), iters, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_read(const void *src, int64_t n_bytes, uint32_t *out, hipStream_t stream)
+{
+    const int grid = (int)(probe_out_len() / 256);
+    hipLaunchKernelGGL(probe_read_kernel, dim3(grid), dim3(256), 0, stream, reinterpret_cast<const uint4 *>(src),
+                       n_bytes / 16, out);
+    return hipGetLastError();
+}
+
+}  // namespace moin

@@ -23,7 +23,8 @@ MOIN_ROUTE_RETAINED_ONLY = 1
 (K_PLAN, K_SHRINK, K_LINEAR, K_ROUTE, K_ROUTE_AUX, K_DECODE_SHRINK, K_DECODE_EXPAND, K_DECODE_BASE,
  K_KMEANS_SORT, K_KMEANS_SUM, K_KMEANS_FINAL) = range(11)
 KERNEL_NAMES = ["plan", "shrink", "linear", "route", "route_aux", "decode_shrink", "decode_expand",
-                "decode_base", "kmeans_sort", "kmeans_sum", "kmeans_final", "mx_quant", "mx_linear"]
+                "decode_base", "kmeans_sort", "kmeans_sum", "kmeans_final", "mx_quant", "mx_linear",
+                "probe_mfma", "probe_read"]
 
 EXPORTS = [
     "moin_create", "moin_destroy", "moin_strerror", "moin_check", "moin_route", "moin_histogram",
@@ -33,6 +34,7 @@ EXPORTS = [
     "moin_cache_create", "moin_cache_destroy", "moin_cache_add_stack", "moin_cache_admit",
     "moin_cache_table", "moin_cache_stats", "moin_lora_linear_ranked", "moin_plan_build_ranked",
     "moin_mx_quantize", "moin_lora_linear_mx", "moin_lora_linear_mx_planned",
+    "moin_probe_out_len", "moin_probe_mfma_bf16", "moin_probe_read",
 ]
 CACHE_STATS = ["batches", "seq_hits", "seq_misses", "loads", "evictions", "overflows", "bytes"]
 
@@ -75,6 +77,10 @@ def load() -> ctypes.CDLL:
                                         c.c_float, vp, c.c_int, vp]
     lib.moin_lora_linear_mx_planned.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, i32, i32, c.c_float,
                                                 vp, c.c_int, vp]
+    lib.moin_probe_out_len.argtypes = [vp]
+    lib.moin_probe_out_len.restype = c.c_int64
+    lib.moin_probe_mfma_bf16.argtypes = [vp, vp, i64, i32, vp, c.POINTER(c.c_double), vp]
+    lib.moin_probe_read.argtypes = [vp, vp, i64, vp, vp]
     lib.moin_plan_build_ranked.argtypes = [vp, vp, vp, vp, i32, i64, i32, vp, vp]
     lib.moin_plan_create.argtypes = [vp, c.POINTER(vp)]
     lib.moin_plan_destroy.argtypes = [vp]
@@ -385,6 +391,31 @@ def moin_lora_linear_mx_planned(ctx: Context, plan: "Plan", x: torch.Tensor, Wq:
         _dev_ptr(A_stack, "A_stack", bf), _dev_ptr(B_stack, "B_stack", bf), d_in, d_out, r, float(scale),
         _dev_ptr(y, "y") if T else None, ydt, _stream_ptr(stream)), "moin_lora_linear_mx_planned")
     return y
+
+
+def moin_probe_mfma_bf16(ctx: Context, operands: torch.Tensor, iters: int, stream=None):
+    """Measurement aid: a loop of bf16 MFMAs alone on ``operands`` (bf16 values; a wave's lanes take 16-byte
+    pieces of it as matrix operands).  Returns (per-thread sums, flops of the launch)."""
+    if operands.dtype != torch.bfloat16 or operands.numel() % 8 or operands.numel() < 8:
+        raise ValueError("operands: bf16, a multiple of 8 values")
+    out = torch.empty(int(load().moin_probe_out_len(ctx._h)), dtype=torch.float32, device=operands.device)
+    flops = ctypes.c_double(0.0)
+    _ck(load().moin_probe_mfma_bf16(ctx._h, _dev_ptr(operands, "operands", torch.bfloat16), operands.numel() * 2,
+                                    int(iters), _dev_ptr(out, "out"), ctypes.byref(flops), _stream_ptr(stream)),
+        "moin_probe_mfma_bf16")
+    return out, flops.value
+
+
+def moin_probe_read(ctx: Context, src: torch.Tensor, stream=None) -> torch.Tensor:
+    """Measurement aid: one streaming read of ``src``; returns the per-thread sums (mod 2^32, as int32) of
+    the 32-bit words read."""
+    nbytes = src.numel() * src.element_size()
+    if nbytes % 16 or not src.is_contiguous():
+        raise ValueError("src: contiguous, a multiple of 16 bytes")
+    out = torch.empty(int(load().moin_probe_out_len(ctx._h)), dtype=torch.int32, device=src.device)
+    _ck(load().moin_probe_read(ctx._h, _dev_ptr(src, "src"), nbytes, _dev_ptr(out, "out"), _stream_ptr(stream)),
+        "moin_probe_read")
+    return out
 
 
 def _emb_dt(emb, centroids):
