@@ -1,0 +1,110 @@
+"""The calls of the hot path can be recorded into a HIP graph (no allocation, no clearing copy, no host
+read between their kernels once the workspace has its size) and every replay gives the bits of the eager
+call on the inputs then in place."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2410_09687_amd import moin
+from paper_2410_09687_amd import workloads as wl
+from tests import gpu_common as gc
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(name, d_in, d_out, r, E, lens, seed, dist="zipf"):
+    w = wl.LinearWorkload(name, d_in, d_out, r, E, lens, dist, 1.1, 2.0, seed=seed)
+    return wl.make_linear_inputs(w, "cuda")
+
+
+def _replay_check(what, inp, call):
+    """call(x, eids, out) runs the library on inp's weights; x and eids are overwritten between replays."""
+    ctx = gc.ctx()
+    g0 = torch.Generator(device="cuda").manual_seed(5)
+    xs = [inp.x.clone()] + [torch.randn(inp.x.shape, device="cuda", generator=g0).to(torch.bfloat16)
+                            for _ in range(2)]
+    ids = [inp.expert_ids.clone(), inp.expert_ids.flip(0).contiguous(),
+           torch.where(inp.expert_ids % 3 == 0, torch.full_like(inp.expert_ids, -1), inp.expert_ids)]
+    x, eids = inp.x.clone(), inp.expert_ids.clone()
+    y_graph = torch.empty((inp.wl.T, inp.wl.d_out), dtype=torch.bfloat16, device="cuda")
+    y_eager = torch.empty_like(y_graph)
+    print(f"[gpu] graph {what}: eager warm-up (sizes the workspace)", flush=True)
+    call(x, eids, y_eager)
+    ctx.check()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call(x, eids, y_graph)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    print(f"[gpu] graph {what}: capture", flush=True)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(x, eids, y_graph)
+    for rep in range(3):
+        print(f"[gpu] graph {what}: replay {rep}", flush=True)
+        # the program's own eager work and a synchronisation between the replays
+        x.copy_(xs[rep])
+        eids.copy_(ids[rep])
+        y_graph.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        call(x, eids, y_eager)
+        ctx.check()
+        assert torch.equal(y_graph.view(torch.int16), y_eager.view(torch.int16)), f"{what}: replay {rep}"
+    # and the last replay against the oracle, on the inputs it ran on
+    ref = gc.oracle_rows(wl.LinearInputs(inp.wl, x, inp.W, inp.A_stack, inp.B_stack, inp.seq_offsets, eids))
+    gc.compare_linear(y_graph, ref, what=f"{what}/graph")
+
+
+def test_decode_call_replays_from_a_graph():
+    inp = _inputs("graph_dec", 512, 520, 64, 40, [1] * 192, seed=71)
+    ctx = gc.ctx()
+    _replay_check("decode", inp, lambda x, e, out: moin.moin_lora_linear(
+        ctx, x, inp.seq_offsets, e, inp.W, inp.A_stack, inp.B_stack, 2.0, out=out))
+
+
+def test_prefill_call_replays_from_a_graph():
+    rng = np.random.default_rng(72)
+    inp = _inputs("graph_pre", 256, 264, 64, 6, rng.integers(1, 400, size=12).tolist(), seed=72, dist="uniform")
+    assert inp.wl.T > 1024
+    ctx = gc.ctx()
+    _replay_check("prefill", inp, lambda x, e, out: moin.moin_lora_linear(
+        ctx, x, inp.seq_offsets, e, inp.W, inp.A_stack, inp.B_stack, 2.0, out=out))
+
+
+def test_quantised_base_call_replays_from_a_graph():
+    rng = np.random.default_rng(73)
+    inp = _inputs("graph_mx", 256, 264, 64, 6, rng.integers(1, 400, size=12).tolist(), seed=73, dist="uniform")
+    ctx = gc.ctx()
+    Wq, Ws = moin.moin_mx_quantize(ctx, inp.W, blocked=True)
+    x, eids = inp.x.clone(), inp.expert_ids.clone()
+    y_graph = torch.empty((inp.wl.T, inp.wl.d_out), dtype=torch.bfloat16, device="cuda")
+
+    def call(out):
+        moin.moin_lora_linear_mx(ctx, x, inp.seq_offsets, eids, Wq, Ws, inp.A_stack, inp.B_stack, 2.0, out=out)
+
+    y_eager = torch.empty_like(y_graph)
+    call(y_eager)
+    ctx.check()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        call(y_graph)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(y_graph)
+    g0 = torch.Generator(device="cuda").manual_seed(6)
+    for rep in range(3):
+        print(f"[gpu] graph mx: replay {rep}", flush=True)
+        x.copy_(torch.randn(x.shape, device="cuda", generator=g0).to(torch.bfloat16))
+        y_graph.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        call(y_eager)
+        ctx.check()
+        assert torch.equal(y_graph.view(torch.int16), y_eager.view(torch.int16)), f"mx replay {rep}"
