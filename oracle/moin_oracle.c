@@ -180,6 +180,24 @@ int moin_oracle_histogram(const int32_t *ids, int64_t N, int32_t K,
 /* ---- routed LoRA linear ---------------------------------------------- */
 
 /*
+ * "Future Works", better adapters: an activation function between the two LoRA
+ * linear layers.  The paper names none; these are the textbook definitions.
+ *   0  identity (the paper's adapter)      2  SiLU  v / (1 + exp(-v))
+ *   1  ReLU  max(v, 0)                     3  GELU  v/2 (1 + erf(v / sqrt 2))
+ */
+enum { ORACLE_ACT_NONE = 0, ORACLE_ACT_RELU = 1, ORACLE_ACT_SILU = 2, ORACLE_ACT_GELU = 3 };
+
+static double adapter_activation(double v, int32_t activation)
+{
+    switch (activation) {
+    case ORACLE_ACT_RELU: return v > 0.0 ? v : 0.0;
+    case ORACLE_ACT_SILU: return v / (1.0 + exp(-v));
+    case ORACLE_ACT_GELU: return 0.5 * v * (1.0 + erf(v / sqrt(2.0)));
+    default: return v;
+    }
+}
+
+/*
  * y[p, :] for the tokens listed in rows[0..n_rows) (rows == NULL: all T
  * tokens, n_rows must then equal T).  For a token t that lies in sequence s
  * with e = expert_ids[s]:
@@ -191,6 +209,8 @@ int moin_oracle_histogram(const int32_t *ids, int64_t N, int32_t K,
  * e uses only its first rank_of_expert[e] rows of A[e] and columns of B[e]
  * (0 <= rank <= r); the stacks keep their [E, r, ...] shape and whatever lies
  * beyond an expert's rank is never read.
+ * activation (see above; 0 = the paper's linear adapter): applied to u, so
+ *     y[t,o] = base_o + scale * sum_j B[e,o,j] act(u_j).
  * x, W, A_stack, B_stack hold bf16 bit patterns; y is fp64, n_rows x d_out.
  * work: caller-provided temporaries, work_slots * (d_in + r) doubles; each
  * OpenMP thread (at most work_slots of them) keeps its widened token and its
@@ -201,12 +221,12 @@ int moin_oracle_lora_linear(const uint16_t *x, const int32_t *seq_offsets,
                             const uint16_t *W, const uint16_t *A_stack,
                             const uint16_t *B_stack, int32_t E, int32_t d_in,
                             int32_t d_out, int32_t r, double scale,
-                            const int32_t *rank_of_expert,
+                            const int32_t *rank_of_expert, int32_t activation,
                             const int64_t *rows, int64_t n_rows, double *y,
                             double *work, int32_t work_slots)
 {
     if (S < 0 || T < 0 || d_in <= 0 || d_out <= 0 || r < 0 || E < 0 ||
-        n_rows < 0 || work_slots <= 0)
+        n_rows < 0 || work_slots <= 0 || activation < ORACLE_ACT_NONE || activation > ORACLE_ACT_GELU)
         return ORACLE_EINVAL;
     if (n_rows == 0) return ORACLE_OK;
     if (!x || !seq_offsets || !W || !y || !work) return ORACLE_EINVAL;
@@ -250,7 +270,7 @@ int moin_oracle_lora_linear(const uint16_t *x, const int32_t *seq_offsets,
                 double acc = 0.0;
                 for (int32_t i = 0; i < d_in; ++i)
                     acc += bf16_to_f64(A[(size_t)j * d_in + i]) * xt[i];
-                u[j] = acc;
+                u[j] = adapter_activation(acc, activation);
             }
         }
         for (int32_t o = 0; o < d_out; ++o) {
@@ -381,7 +401,7 @@ int moin_oracle_mx_dequantize(const uint8_t *codes, const uint8_t *scales, int64
  * with Wd the dequantised MXFP8 weight (Wq codes [d_out, d_in], Ws scales
  * [d_out, d_in/32]) and xd the token's activations after a round trip through
  * the same MXFP8 quantisation; the adapter term still uses the bf16 x:
- *     y[t,o] = base_o + scale * sum_j B[e,o,j] (sum_i A[e,j,i] x[t,i]).
+ *     y[t,o] = base_o + scale * sum_j B[e,o,j] act(sum_i A[e,j,i] x[t,i]).
  * work: work_slots * (2 * d_in + r) doubles.
  */
 int moin_oracle_lora_linear_mx(const uint16_t *x, const int32_t *seq_offsets,
@@ -389,12 +409,12 @@ int moin_oracle_lora_linear_mx(const uint16_t *x, const int32_t *seq_offsets,
                                const uint8_t *Wq, const uint8_t *Ws, const uint16_t *A_stack,
                                const uint16_t *B_stack, int32_t E, int32_t d_in,
                                int32_t d_out, int32_t r, double scale,
-                               const int32_t *rank_of_expert,
+                               const int32_t *rank_of_expert, int32_t activation,
                                const int64_t *rows, int64_t n_rows, double *y,
                                double *work, int32_t work_slots)
 {
     if (S < 0 || T < 0 || d_in <= 0 || d_in % MX_BLOCK || d_out <= 0 || r < 0 || E < 0 ||
-        n_rows < 0 || work_slots <= 0)
+        n_rows < 0 || work_slots <= 0 || activation < ORACLE_ACT_NONE || activation > ORACLE_ACT_GELU)
         return ORACLE_EINVAL;
     if (n_rows == 0) return ORACLE_OK;
     if (!x || !seq_offsets || !Wq || !Ws || !y || !work) return ORACLE_EINVAL;
@@ -447,7 +467,7 @@ int moin_oracle_lora_linear_mx(const uint16_t *x, const int32_t *seq_offsets,
                 double acc = 0.0;
                 for (int32_t i = 0; i < d_in; ++i)
                     acc += bf16_to_f64(A[(size_t)j * d_in + i]) * xt[i];
-                u[j] = acc;
+                u[j] = adapter_activation(acc, activation);
             }
         }
         for (int32_t o = 0; o < d_out; ++o) {

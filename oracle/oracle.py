@@ -46,11 +46,11 @@ def _load():
         lib.moin_oracle_lora_linear.argtypes = [
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int64,
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
-            c.c_double, c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_int32]
+            c.c_double, c.c_void_p, c.c_int32, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_int32]
         lib.moin_oracle_lora_linear_mx.argtypes = [
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int64,
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
-            c.c_int32, c.c_double, c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p,
+            c.c_int32, c.c_double, c.c_void_p, c.c_int32, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p,
             c.c_int32]
         lib.moin_oracle_mx_quantize.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_void_p,
                                                 c.c_void_p]
@@ -187,9 +187,20 @@ def retain_clusters(counts, min_count):
     return slot, int(kept)
 
 
+ACTIVATIONS = {None: 0, "none": 0, "relu": 1, "silu": 2, "gelu": 3}
+
+
+def _activation_code(activation):
+    if activation not in ACTIVATIONS:
+        raise ValueError(f"activation: one of {sorted(k for k in ACTIVATIONS if k)} or None expected")
+    return ACTIVATIONS[activation]
+
+
 def lora_linear(x, seq_offsets, expert_ids, W, A_stack, B_stack, scale, rows=None,
-                threads=None, rank_of_expert=None):
-    """y = x W^T + scale * (x A_e^T) B_e^T with one expert per sequence (fp64).
+                threads=None, rank_of_expert=None, activation=None):
+    """y = x W^T + scale * act(x A_e^T) B_e^T with one expert per sequence (fp64);
+    ``activation``: None (the paper's linear adapter), "relu", "silu" or "gelu"
+    ("Future Works", better adapters: an activation between the two LoRA layers).
 
     ``x [T,d_in]``, ``W [d_out,d_in]``, ``A_stack [E,r,d_in]``, ``B_stack
     [E,d_out,r]`` are uint16 bf16 bit patterns.  ``rows`` selects the tokens to
@@ -237,8 +248,8 @@ def lora_linear(x, seq_offsets, expert_ids, W, A_stack, B_stack, scale, rows=Non
     work = np.zeros(slots * (d_in + max(r, 1)), dtype=np.float64)
     _check(_load().moin_oracle_lora_linear(
         _ptr(x), _ptr(seq_offsets), _ptr(expert_ids), S, T, _ptr(W), _ptr(A_stack),
-        _ptr(B_stack), E, d_in, d_out, r, float(scale), _ptr(ranks), _ptr(rows_arr), n_rows, _ptr(y),
-        _ptr(work), slots), "lora_linear")
+        _ptr(B_stack), E, d_in, d_out, r, float(scale), _ptr(ranks), _activation_code(activation),
+        _ptr(rows_arr), n_rows, _ptr(y), _ptr(work), slots), "lora_linear")
     return y
 
 
@@ -276,7 +287,7 @@ def mx_dequantize(codes, scales):
 
 
 def lora_linear_mx(x, seq_offsets, expert_ids, Wq, Ws, A_stack, B_stack, scale, rows=None,
-                   threads=None, rank_of_expert=None):
+                   threads=None, rank_of_expert=None, activation=None):
     """Routed LoRA linear on an MXFP8 base: y = xd Wd^T + scale * (x A_e^T) B_e^T
     with Wd the dequantised weight (``Wq [d_out,d_in]`` codes, ``Ws
     [d_out,d_in/32]`` scales), xd the bf16 activations after an MXFP8 round trip
@@ -323,8 +334,8 @@ def lora_linear_mx(x, seq_offsets, expert_ids, Wq, Ws, A_stack, B_stack, scale, 
     work = np.zeros(slots * (2 * d_in + max(r, 1)), dtype=np.float64)
     _check(_load().moin_oracle_lora_linear_mx(
         _ptr(x), _ptr(seq_offsets), _ptr(expert_ids), S, T, _ptr(Wq), _ptr(Ws), _ptr(A_stack),
-        _ptr(B_stack), E, d_in, d_out, r, float(scale), _ptr(ranks), _ptr(rows_arr), n_rows,
-        _ptr(y), _ptr(work), slots), "lora_linear_mx")
+        _ptr(B_stack), E, d_in, d_out, r, float(scale), _ptr(ranks), _activation_code(activation),
+        _ptr(rows_arr), n_rows, _ptr(y), _ptr(work), slots), "lora_linear_mx")
     return y
 
 
