@@ -343,6 +343,32 @@ def bench_mx(ctx, steps, warmup):
             "kernels": kt}
 
 
+def bench_activation(ctx, steps, warmup):
+    """configs[1] projection with an activation between the adapter's two layers ("Future Works", better
+    adapters): SiLU on W_a x in the shrink's epilogue; same kernels and bytes as the headline step."""
+    w = wl.config_prefill()
+    inp = wl.make_linear_inputs(w, "cuda")
+    y = torch.empty((w.T, w.d_out), dtype=torch.bfloat16, device="cuda")
+    plan = moin.Plan(ctx).build(inp.seq_offsets, inp.expert_ids, w.T, w.E)
+    out = {}
+    try:
+        for act in (None, "silu"):
+            ctx.set_adapter_activation(act)
+
+            def step():
+                moin.moin_lora_linear_planned(ctx, plan, inp.x, inp.W, inp.A_stack, inp.B_stack, w.scale, out=y)
+
+            ms, _ = timed_region(step, steps, warmup)
+            ctx.check()
+            kt = kernel_times(ctx, step, steps)
+            out[act or "none"] = {"ms_per_call": ms, "shrink_us": kt["shrink"]["avg_ms"] * 1e3,
+                                  "linear_us": kt["linear"]["avg_ms"] * 1e3}
+    finally:
+        ctx.set_adapter_activation(None)
+        plan.close()
+    return out
+
+
 def bench_cache(ctx, n_batches=48, n_slots=512):
     """Decode batches of the gate projection (configs[2] shapes) served through the adapter
     residency cache: 5000 experts in pinned host memory, `n_slots` resident, one request
@@ -517,8 +543,8 @@ def main():
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="first run a plain device copy of this many MiB (3 times): the known-size "
                          "kernel that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
-    ap.add_argument("--also", default="decode,router,layer,kmeans,mx",
-                    help="comma list of extra workloads to report: decode,router,layer,kmeans,cache,ranks,mx,mx-step "
+    ap.add_argument("--also", default="decode,router,layer,kmeans,mx,act",
+                    help="comma list of extra workloads to report: decode,router,layer,kmeans,cache,ranks,mx,mx-step,act "
                          "(or 'none'); cache (it pins 10 GB of host memory) and ranks are not in the default list; "
                          "mx-step is the headline step on the quantised base alone, mx adds its layer and decode")
     args = ap.parse_args()
@@ -562,6 +588,8 @@ def main():
         if "kmeans" in res:
             res["kmeans"]["roofline"]["frac_of_measured_read_ceiling"] = \
                 res["kmeans"]["roofline"]["achieved"] / c["read_GBps"]
+    if "act" in extra:
+        res["activation"] = bench_activation(ctx, args.steps, args.warmup)
     if "cache" in extra:
         res["cache"] = bench_cache(ctx)
     if "ranks" in extra:

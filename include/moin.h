@@ -348,6 +348,19 @@ int moin_timing_reset(moin_ctx *ctx);
 int moin_timing_read(moin_ctx *ctx, int kernel_id, double *ms_sum,
                      int64_t *launches);
 
+/* "Future Works", better adapters: an activation function between the adapter's
+ * two linear layers,
+ *     y = x W^T + scale * act(x A_e^T) B_e^T,
+ * applied to x A_e^T in fp32 before the scale.  The paper names no function; these
+ * are the textbook ones: ReLU max(v, 0), SiLU v / (1 + exp(-v)), GELU
+ * v/2 (1 + erf(v / sqrt 2)).  It is a property of the adapters the stacks hold (of
+ * how they were trained), not of a call, so it is set on the context and holds
+ * for every later moin_lora_linear* call on it (plain, ranked, planned, on a
+ * quantised base; prefill and decode) until set again.  Default MOIN_ACT_NONE, the
+ * paper's adapter.  Any other value: MOIN_EINVAL, setting unchanged. */
+enum { MOIN_ACT_NONE = 0, MOIN_ACT_RELU = 1, MOIN_ACT_SILU = 2, MOIN_ACT_GELU = 3 };
+int moin_set_adapter_activation(moin_ctx *ctx, int32_t activation);
+
 /* Measurement aids: the ceilings of this very device, beside the datasheet peaks,
  * for the roofline fractions that bench.py reports (the hot path of the paper's
  * method does not call them).

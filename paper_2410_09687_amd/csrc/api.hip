@@ -49,6 +49,7 @@ struct moin_ctx {
     void *ws;
     size_t ws_bytes;
     moin_plan *own_plan;
+    int act;   // activation between the adapter's two layers (MOIN_ACT_*)
     int timing;
     std::vector<TimedSpan> spans;
     std::vector<hipEvent_t> free_events;
@@ -267,7 +268,7 @@ int linear_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, con
     LinearArgs a;
     a.x = x; a.W = W; a.A_stack = A_stack; a.B_stack = B_stack;
     a.y = y; a.y_f32 = (y_dt == MOIN_F32);
-    a.d_in = d_in; a.d_out = d_out; a.r = adapters ? r : 0; a.scale = scale;
+    a.d_in = d_in; a.d_out = d_out; a.r = adapters ? r : 0; a.scale = scale; a.act = ctx->act;
     a.u_hi = a.u_lo = nullptr;
 
     const size_t u_bytes = align_up((size_t)pv.T * (size_t)a.r * 2, 256);
@@ -339,7 +340,7 @@ int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, 
     LinearArgs &a = m.lin;
     a.x = x; a.W = nullptr; a.A_stack = A_stack; a.B_stack = B_stack;
     a.y = y; a.y_f32 = (y_dt == MOIN_F32);
-    a.d_in = d_in; a.d_out = d_out; a.r = adapters ? r : 0; a.scale = scale;
+    a.d_in = d_in; a.d_out = d_out; a.r = adapters ? r : 0; a.scale = scale; a.act = ctx->act;
     a.u_hi = a.u_lo = nullptr;
     const size_t u_bytes = align_up((size_t)pv.T * (size_t)a.r * 2, 256);
     const bool ws_q = xq == nullptr;      // codes and scales live in the workspace
@@ -431,6 +432,7 @@ int moin_create(moin_ctx **out, int device)
     ctx->ws = nullptr;
     ctx->ws_bytes = 0;
     ctx->own_plan = nullptr;
+    ctx->act = MOIN_ACT_NONE;
     ctx->timing = 0;
     for (int i = 0; i < MOIN_K_COUNT; ++i) {
         ctx->ms_sum[i] = 0.0;
@@ -852,6 +854,13 @@ int moin_timing_read(moin_ctx *ctx, int kernel_id, double *ms_sum, int64_t *laun
     if (ms_sum) *ms_sum = ctx->ms_sum[kernel_id];
     if (launches) *launches = ctx->launches[kernel_id];
     return rc;
+}
+
+int moin_set_adapter_activation(moin_ctx *ctx, int32_t activation)
+{
+    if (!ctx || activation < MOIN_ACT_NONE || activation > MOIN_ACT_GELU) return MOIN_EINVAL;
+    ctx->act = activation;
+    return MOIN_OK;
 }
 
 int64_t moin_probe_out_len(moin_ctx *ctx)

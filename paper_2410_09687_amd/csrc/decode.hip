@@ -46,6 +46,7 @@ struct ShrinkDParams {
     const int *n_groups;
     int d_in, r;
     float scale;
+    int act;
 };
 
 // One (expert group g, 16-row slab of A_e) of the decode shrink; `red` is the
@@ -118,7 +119,7 @@ __device__ __forceinline__ void decode_shrink_slab(const ShrinkDParams &p, int s
                 float f = 0.f;
 #pragma unroll
                 for (int w = 0; w < NW; ++w) f += red[w][lane][i];
-                f *= scale;
+                f = adapter_act(f, p.act) * scale;
                 h[i] = f32_to_bf16_bits(f);
                 l[i] = f32_to_bf16_bits(f - bf16_bits_to_f32(h[i]));
             }
@@ -303,7 +304,7 @@ static ShrinkDParams shrink_params(const PlanView &pv, const DecodeArgs &d)
     p.x = (const char *)a.x; p.A_stack = (const char *)a.A_stack;
     p.ug_hi = (char *)d.ug_hi; p.ug_lo = (char *)d.ug_lo;
     p.tok_sorted = pv.tok_sorted; p.grp_meta = pv.grp_meta; p.n_groups = pv.n_groups;
-    p.d_in = a.d_in; p.r = a.r; p.scale = a.scale;
+    p.d_in = a.d_in; p.r = a.r; p.scale = a.scale; p.act = a.act;
     return p;
 }
 

@@ -36,6 +36,18 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) { return pack_bf16x2(f, 0.f) & 0xFFFFu; }
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return bits_f32(h << 16); }
 
+// Activation between the adapter's two linear layers ("Future Works", better
+// adapters): applied to W_a x in fp32, before the scale.  Codes as in moin.h.
+__device__ __forceinline__ float adapter_act(float v, int act)
+{
+    switch (act) {
+    case 1: return fmaxf(v, 0.f);                                  // ReLU
+    case 2: return v / (1.f + expf(-v));                           // SiLU
+    case 3: return 0.5f * v * (1.f + erff(v * 0.70710678118654752f));   // GELU
+    default: return v;
+    }
+}
+
 // Values read from global memory with a workgroup-uniform address are uniform,
 // but the compiler cannot know; telling it keeps control flow and addressing
 // that depend on them on the scalar unit.

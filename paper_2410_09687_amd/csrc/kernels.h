@@ -52,6 +52,7 @@ struct LinearArgs {
     int y_f32;
     int d_in, d_out, r;
     float scale;
+    int act = 0;           // activation on W_a x (moin_set_adapter_activation)
 };
 
 hipError_t launch_prefill_shrink(const PlanView &pv, const LinearArgs &a, hipStream_t stream);

@@ -24,6 +24,7 @@ struct ShrinkKParams {
     int d_in, r;
     int n_tiles_n;
     float scale;
+    int act;
     // QUANT only: MXFP8 codes [T, d_in] and scale bytes [d_in / 128, T, 4] of x
     char *xq, *xs;
     int64_t T;
@@ -149,12 +150,13 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
     char *uh = p.u_hi + (int64_t)row0 * ldu;
     char *ul = p.u_lo + (int64_t)row0 * ldu;
     const float s = p.scale;
+    const int act = p.act;
     C::epilogue(smem, acc, [&](int row, int col, float(&v)[8]) {
         if (row >= rows || col >= ncols_out) return;
         uint32_t h[8], l[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            const float f = (n0 + col + q < re) ? v[q] * s : 0.f;
+            const float f = (n0 + col + q < re) ? adapter_act(v[q], act) * s : 0.f;
             h[q] = f32_to_bf16_bits(f);
             l[q] = f32_to_bf16_bits(f - bf16_bits_to_f32(h[q]));
         }
@@ -240,7 +242,7 @@ static hipError_t launch_shrink_as(const PlanView &pv, const LinearArgs &a, hipS
     p.tile_row0 = pv.tile_row0; p.tile_rows = pv.tile_rows; p.tile_expert = pv.tile_expert;
     p.tile_rank = pv.tile_rank;
     p.n_tiles = pv.n_tiles;
-    p.d_in = a.d_in; p.r = a.r; p.scale = a.scale;
+    p.d_in = a.d_in; p.r = a.r; p.scale = a.scale; p.act = a.act;
     p.n_tiles_n = (a.r + C::BN - 1) / C::BN;
     const int64_t grid = (int64_t)pv.max_tiles * (TILE_M / C::BM) * p.n_tiles_n;
     if (grid > 0x7ffffff0LL) return hipErrorInvalidValue;

@@ -34,8 +34,9 @@ EXPORTS = [
     "moin_cache_create", "moin_cache_destroy", "moin_cache_add_stack", "moin_cache_admit",
     "moin_cache_table", "moin_cache_stats", "moin_lora_linear_ranked", "moin_plan_build_ranked",
     "moin_mx_quantize", "moin_lora_linear_mx", "moin_lora_linear_mx_planned",
-    "moin_probe_out_len", "moin_probe_mfma_bf16", "moin_probe_read",
+    "moin_probe_out_len", "moin_probe_mfma_bf16", "moin_probe_read", "moin_set_adapter_activation",
 ]
+ACTIVATIONS = {None: 0, "none": 0, "relu": 1, "silu": 2, "gelu": 3}
 CACHE_STATS = ["batches", "seq_hits", "seq_misses", "loads", "evictions", "overflows", "bytes"]
 
 _lib = None
@@ -77,6 +78,7 @@ def load() -> ctypes.CDLL:
                                         c.c_float, vp, c.c_int, vp]
     lib.moin_lora_linear_mx_planned.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, i32, i32, c.c_float,
                                                 vp, c.c_int, vp]
+    lib.moin_set_adapter_activation.argtypes = [vp, i32]
     lib.moin_probe_out_len.argtypes = [vp]
     lib.moin_probe_out_len.restype = c.c_int64
     lib.moin_probe_mfma_bf16.argtypes = [vp, vp, i64, i32, vp, c.POINTER(c.c_double), vp]
@@ -156,6 +158,13 @@ class Context:
     def check(self, stream=None) -> None:
         """Synchronises the stream; raises ``MoinError`` on a device-side data fault."""
         _ck(load().moin_check(self._h, _stream_ptr(stream)), "moin_check")
+
+    def set_adapter_activation(self, activation=None):
+        """Activation between the adapter's two linear layers for every later linear call on this context:
+        None (the paper's adapter), "relu", "silu" or "gelu"."""
+        if activation not in ACTIVATIONS:
+            raise ValueError("activation: None, 'relu', 'silu' or 'gelu' expected")
+        _ck(load().moin_set_adapter_activation(self._h, ACTIVATIONS[activation]), "moin_set_adapter_activation")
 
     def timing_enable(self, on: bool = True):
         _ck(load().moin_timing_enable(self._h, int(on)), "moin_timing_enable")
