@@ -369,6 +369,41 @@ def bench_activation(ctx, steps, warmup):
     return out
 
 
+def bench_per_token(ctx, steps, warmup):
+    """One expert per token ("Future Works", per token adapters) at serving size: 8192 single-token sequences
+    through the gate projection of configs[2] (2048 -> 5632, r = 128, 5000 experts, Zipf(1.1) ids).  The
+    batch takes the path that gathers tokens by expert; bound by the adapters' bytes."""
+    w0 = wl.config_decode()[0]
+    T = 8192
+    w = wl.LinearWorkload("per_token_gate", w0.d_in, w0.d_out, w0.r, w0.E, [1] * T, "zipf", 1.1, w0.scale,
+                          seed=w0.seed + 77)
+    inp = wl.make_linear_inputs(w, "cuda")
+    y = torch.empty((T, w.d_out), dtype=torch.bfloat16, device="cuda")
+    plan = moin.Plan(ctx)
+
+    def build():
+        plan.build(inp.seq_offsets, inp.expert_ids, T, w.E)
+
+    build()
+    plan_ms, _ = timed_region(build, 5, 1)
+
+    def step():
+        moin.moin_lora_linear_planned(ctx, plan, inp.x, inp.W, inp.A_stack, inp.B_stack, w.scale, out=y)
+
+    ms, _ = timed_region(step, max(5, steps // 5), 2)
+    ctx.check()
+    kt = kernel_times(ctx, step, 5)
+    distinct = int(torch.unique(inp.expert_ids).numel())
+    nbytes = 2.0 * w.d_in * w.d_out + distinct * 2.0 * w.r * (w.d_in + w.d_out) + 2.0 * T * (w.d_in + w.d_out)
+    flops = 2.0 * T * w.d_in * w.d_out + 2.0 * T * w.r * (w.d_in + w.d_out)
+    plan.close()
+    return {"tokens": T, "distinct_experts": distinct, "ms_per_call": ms, "plan_ms": plan_ms,
+            "tokens_per_s": T / (ms * 1e-3), "TFLOPs": flops / (ms * 1e-3) / 1e12,
+            "roofline": {"bound": "hbm", "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+            "algorithmic_bytes": nbytes, "kernels": kt}
+
+
 def bench_cache(ctx, n_batches=48, n_slots=512):
     """Decode batches of the gate projection (configs[2] shapes) served through the adapter
     residency cache: 5000 experts in pinned host memory, `n_slots` resident, one request
@@ -543,8 +578,8 @@ def main():
     ap.add_argument("--copy-mib", type=int, default=0,
                     help="first run a plain device copy of this many MiB (3 times): the known-size "
                          "kernel that calibrates rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
-    ap.add_argument("--also", default="decode,router,layer,kmeans,mx,act",
-                    help="comma list of extra workloads to report: decode,router,layer,kmeans,cache,ranks,mx,mx-step,act "
+    ap.add_argument("--also", default="decode,router,layer,kmeans,mx,act,pertoken",
+                    help="comma list of extra workloads to report: decode,router,layer,kmeans,cache,ranks,mx,mx-step,act,pertoken "
                          "(or 'none'); cache (it pins 10 GB of host memory) and ranks are not in the default list; "
                          "mx-step is the headline step on the quantised base alone, mx adds its layer and decode")
     args = ap.parse_args()
@@ -590,6 +625,8 @@ def main():
                 res["kmeans"]["roofline"]["achieved"] / c["read_GBps"]
     if "act" in extra:
         res["activation"] = bench_activation(ctx, args.steps, args.warmup)
+    if "pertoken" in extra:
+        res["per_token"] = bench_per_token(ctx, args.steps, args.warmup)
     if "cache" in extra:
         res["cache"] = bench_cache(ctx)
     if "ranks" in extra:

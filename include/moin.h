@@ -138,7 +138,12 @@ int moin_histogram(moin_ctx *ctx, const int32_t *ids, int64_t N, int32_t K,
  * (high part + remainder) into the expand product.
  * d_in and r must be multiples of 8; d_out a multiple of 8 (bf16 y) or 4.
  * Small batches (T <= 1024) take the decode path: tokens are grouped by
- * expert so each distinct adapter is read from HBM once.
+ * expert so each distinct adapter is read from HBM once.  So do larger batches
+ * of short sequences (T <= 128 S, i.e. 128 tokens per sequence on average or
+ * fewer, down to one expert per token: "Future Works", per token adapters),
+ * where a row tile per sequence would be mostly padding: their base product
+ * runs over plain tiles of 256 tokens and the adapter term over the tokens
+ * gathered by expert.
  */
 int moin_lora_linear(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
                      const int32_t *expert_ids, int32_t S, int64_t T,
@@ -194,6 +199,7 @@ int moin_mx_quantize(moin_ctx *ctx, const void *src, int64_t rows, int64_t cols,
  * stacks exactly as in moin_lora_linear.  rank_of_expert may be NULL.
  * Shapes: d_in a multiple of 128 and at least 256, r a multiple of 64, d_out a
  * multiple of 8; anything else returns MOIN_EINVAL.  Small batches (T <= 1024)
+ * and batches of short sequences (T <= 128 S, see moin_lora_linear)
  * compute the base product for all tokens at once on the FP8 matrix cores and
  * add the adapter term with the decode path's gather-matvec kernels. */
 int moin_lora_linear_mx(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,

@@ -6,6 +6,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -151,16 +152,19 @@ int drain_spans(moin_ctx *ctx)
 
 struct PlanLayout {
     size_t tile_row0, tile_rows, tile_expert, tile_rank, n_tiles, tok_sorted, grp_meta,
-        grp_start, n_groups, keys, tmp, total;
-    int max_tiles, max_groups, decode;
+        grp_start, grp_tmp, n_groups, keys, tmp, plain, total;
+    int max_tiles, max_groups, max_plain, decode;
 };
 
-PlanLayout plan_layout(int32_t S, int64_t T)
+PlanLayout plan_layout(int32_t S, int64_t T, int32_t E)
 {
     PlanLayout L;
-    L.decode = T <= DECODE_MAX_T;
+    // one record per distinct expert (and one for "no adapter"), plus what cutting the
+    // groups into chunks of GROUP_CHUNK tokens can add
+    const int64_t groups = std::min<int64_t>(S, (int64_t)E + 1) + T / GROUP_CHUNK + 1;
+    L.decode = (T <= DECODE_MAX_T || T <= (int64_t)GATHER_MAX_AVG_LEN * S) && groups <= 65535;
     L.max_tiles = (int)(T / TILE_M) + S + 1;
-    L.max_groups = L.decode ? S : 0;
+    L.max_groups = L.decode ? (int)groups : 0;
     size_t npow2 = 1;
     while (npow2 < (size_t)S) npow2 <<= 1;
     size_t off = 0;
@@ -178,8 +182,11 @@ PlanLayout plan_layout(int32_t S, int64_t T)
     L.tok_sorted = take(L.decode ? (size_t)T * 4 : 4);
     L.grp_meta = take((size_t)(L.max_groups + 1) * 16);
     L.grp_start = take((size_t)(L.max_groups + 2) * 4);
+    L.grp_tmp = take((size_t)(L.max_groups + 1) * 8);
     L.n_groups = take(4);
     L.tmp = take((size_t)4 * ((size_t)S + 1) * 4);
+    L.max_plain = (L.decode && T > DECODE_MAX_T) ? (int)((T + TILE_M - 1) / TILE_M) : 0;
+    L.plain = take(((size_t)4 * L.max_plain + 1) * 4);
     L.total = off;
     return L;
 }
@@ -199,7 +206,7 @@ int plan_build_impl(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
         return MOIN_OK;
     }
     if (!seq_offsets || !expert_ids) return MOIN_EINVAL;
-    const PlanLayout L = plan_layout(S, T);
+    const PlanLayout L = plan_layout(S, T, E);
     if (L.total > plan->bytes) {
         if (plan->buf && hipFree(plan->buf) != hipSuccess) return MOIN_EHIP;
         plan->buf = nullptr;
@@ -223,6 +230,13 @@ int plan_build_impl(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
     pv.tok_sorted = reinterpret_cast<int *>(b + L.tok_sorted);
     pv.grp_meta = reinterpret_cast<int4 *>(b + L.grp_meta);
     pv.grp_start = reinterpret_cast<int *>(b + L.grp_start);
+    pv.grp_tmp = reinterpret_cast<int2 *>(b + L.grp_tmp);
+    pv.plain_row0 = reinterpret_cast<int *>(b + L.plain);
+    pv.plain_rows = pv.plain_row0 + L.max_plain;
+    pv.plain_expert = pv.plain_rows + L.max_plain;
+    pv.plain_rank = pv.plain_expert + L.max_plain;
+    pv.plain_n = pv.plain_rank + L.max_plain;
+    pv.max_plain = L.max_plain;
     pv.n_groups = reinterpret_cast<int *>(b + L.n_groups);
     pv.tmp = reinterpret_cast<int *>(b + L.tmp);
     pv.max_tiles = L.max_tiles;
@@ -288,16 +302,27 @@ int linear_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, con
         return MOIN_OK;
     }
 
+    // Beyond the small-batch size the base product runs on plain row tiles in the
+    // prefill kernel (full 256-row tiles, no adapter), where its shapes allow.
+    LinearArgs ab = a;
+    ab.r = 0;
+    const bool big = pv.max_plain > 0 && stream_kernel_fits(ab);
+    PlanView pp = pv;
+    pp.tile_row0 = pv.plain_row0; pp.tile_rows = pv.plain_rows; pp.tile_expert = pv.plain_expert;
+    pp.tile_rank = pv.plain_rank; pp.n_tiles = pv.plain_n; pp.max_tiles = pv.max_plain;
     if (a.r == 0) {
         // no adapters anywhere in the call: the base GEMM writes y itself
-        if (timed(ctx, MOIN_K_DECODE_BASE, stream, [&] { return launch_decode_base_only(pv, a, stream); }) !=
-            hipSuccess)
+        if (big) {
+            if (timed(ctx, MOIN_K_LINEAR, stream, [&] { return launch_prefill_linear(pp, ab, stream); }) != hipSuccess)
+                return MOIN_EHIP;
+        } else if (timed(ctx, MOIN_K_DECODE_BASE, stream, [&] { return launch_decode_base_only(pv, a, stream); }) !=
+                   hipSuccess)
             return MOIN_EHIP;
         return MOIN_OK;
     }
     DecodeArgs d;
     d.lin = a;
-    d.k_splits = decode_base_splits(pv.T, d_in, d_out);
+    d.k_splits = big ? 1 : decode_base_splits(pv.T, d_in, d_out);
     const size_t yb_bytes = align_up((size_t)d.k_splits * (size_t)pv.T * (size_t)d_out * 4, 256);
     const int rc = ensure_ws(ctx, 2 * u_bytes + yb_bytes);
     if (rc != MOIN_OK) return rc;
@@ -305,7 +330,15 @@ int linear_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, con
     d.ug_hi = w;
     d.ug_lo = w + u_bytes;
     d.ybase = reinterpret_cast<float *>(w + 2 * u_bytes);
-    if (decode_base_shrink_fits(pv, d)) {
+    if (big) {
+        ab.y = d.ybase;
+        ab.y_f32 = 1;
+        if (timed(ctx, MOIN_K_LINEAR, stream, [&] { return launch_prefill_linear(pp, ab, stream); }) != hipSuccess)
+            return MOIN_EHIP;
+        if (timed(ctx, MOIN_K_DECODE_SHRINK, stream, [&] { return launch_decode_shrink(pv, d, stream); }) !=
+            hipSuccess)
+            return MOIN_EHIP;
+    } else if (decode_base_shrink_fits(pv, d)) {
         if (timed(ctx, MOIN_K_DECODE_SHRINK, stream, [&] { return launch_decode_base_shrink(pv, d, stream); }) !=
             hipSuccess)
             return MOIN_EHIP;

@@ -8,7 +8,14 @@
 namespace moin {
 
 constexpr int TILE_M = 256;        // rows per plan tile (prefill)
-constexpr int DECODE_MAX_T = 1024; // batches up to this many tokens take the decode path
+// The decode path (tokens gathered by expert, each distinct adapter read once, base
+// product over plain row tiles) serves batches of up to DECODE_MAX_T tokens and
+// larger ones whose sequences are short -- at most GATHER_MAX_AVG_LEN tokens on
+// average, down to one expert per token ("Future Works", per token adapters) --
+// where a row tile per sequence would be mostly padding.
+constexpr int DECODE_MAX_T = 1024;
+constexpr int GATHER_MAX_AVG_LEN = 128;
+constexpr int GROUP_CHUNK = 128;   // tokens per group record: a hot expert's tokens are spread over several
 
 // sticky error bits (device word)
 constexpr int ERR_BAD_EXPERT = 1;
@@ -25,10 +32,16 @@ struct PlanView {
     int *tile_expert;  // [max_tiles] adapter slot or -1
     int *tile_rank;    // [max_tiles] rank of that adapter (RANK_FULL without a rank table, 0 for slot -1)
     int *n_tiles;      // [1]
-    // decode grouping (built only when T <= DECODE_MAX_T)
+    // decode grouping (built only for batches that take the decode path)
     int *tok_sorted;   // [T] token index, grouped by expert
-    int4 *grp_meta;    // [max_groups] {adapter slot or -1, first, one-past-last position in tok_sorted, rank}
+    int4 *grp_meta;    // [max_groups] {adapter slot or -1, first, one-past-last position in tok_sorted, rank};
+                       // an expert with more than GROUP_CHUNK tokens has several records
     int *grp_start;    // [max_groups + 1] scratch while building
+    int2 *grp_tmp;     // [max_groups] scratch while building: {slot, rank} of each expert's group
+    // plain row tiles over all T tokens, no adapter (built with the decode grouping when
+    // T > DECODE_MAX_T): the base product of such a batch runs on them
+    int *plain_row0, *plain_rows, *plain_expert, *plain_rank, *plain_n;   // [max_plain] x 4, [1]
+    int max_plain;
     int *n_groups;     // [1]
     // scratch used while building
     unsigned long long *keys; // [pow2 >= S]
@@ -57,6 +70,8 @@ struct LinearArgs {
 
 hipError_t launch_prefill_shrink(const PlanView &pv, const LinearArgs &a, hipStream_t stream);
 hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStream_t stream);
+// shapes the persistent streaming prefill kernel takes (anything else: the tiled kernel)
+bool stream_kernel_fits(const LinearArgs &a);
 // shrink + MXFP8 codes / blocked scales of x in one pass over x (d_in a multiple of 128)
 hipError_t launch_prefill_shrink_quant(const PlanView &pv, const LinearArgs &a, void *xq, void *xs,
                                        hipStream_t stream);

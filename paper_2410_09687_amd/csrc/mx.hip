@@ -117,7 +117,6 @@ namespace mxs {
 
 constexpr int BT = 256;              // tile edge, both ways
 constexpr int ROWB = 128;            // bytes of one operand row per block
-constexpr int KB8 = 128;             // contraction steps of a base block (FP8)
 constexpr int KB16 = 64;             // contraction steps of an adapter block (bf16)
 constexpr int NW = 4, NT = NW * 64;  // one wave per SIMD: 512 registers each
 constexpr int WQ = 2;                // waves along tokens (Q); NW / WQ along outputs (P)

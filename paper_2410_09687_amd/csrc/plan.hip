@@ -109,6 +109,14 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
     }
     if (err) atomicOr(err_word, err);
     if (err & ERR_BAD_OFFSETS) bad_offsets = 1;
+    for (int j = tid; j < pv.max_plain; j += PLAN_THREADS) {
+        const int rows = min(TILE_M, T - j * TILE_M);
+        pv.plain_row0[j] = j * TILE_M;
+        pv.plain_rows[j] = max(rows, 0);
+        pv.plain_expert[j] = -1;
+        pv.plain_rank[j] = 0;
+    }
+    if (tid == 0 && pv.max_plain > 0) *pv.plain_n = min(pv.max_plain, (T + TILE_M - 1) / TILE_M);
     __syncthreads();
     if (bad_offsets) {
         // the sequences do not cover every token exactly once: one base-only
@@ -123,11 +131,11 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
         if (tid == 0) *pv.n_tiles = nt;
         if (pv.decode) {
             for (int t = tid; t < T; t += PLAN_THREADS) pv.tok_sorted[t] = t;
-            if (tid == 0) {
-                *pv.n_groups = 1;
-                pv.grp_meta[0] = make_int4(-1, 0, T, 0);
-            }
-            for (int gi = 1 + tid; gi < pv.max_groups; gi += PLAN_THREADS) pv.grp_meta[gi] = make_int4(-1, 0, 0, 0);
+            const int nc = min((T + GROUP_CHUNK - 1) / GROUP_CHUNK, pv.max_groups);
+            if (tid == 0) *pv.n_groups = nc;
+            for (int gi = tid; gi < pv.max_groups; gi += PLAN_THREADS)
+                pv.grp_meta[gi] = gi < nc ? make_int4(-1, gi * GROUP_CHUNK, min(T, (gi + 1) * GROUP_CHUNK), 0)
+                                          : make_int4(-1, 0, 0, 0);
         }
         return;
     }
@@ -163,14 +171,11 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
     __syncthreads();
     const int n_tiles = block_exclusive_scan<PLAN_THREADS>(a1, S, lds);
     if (tid == 0) *pv.n_tiles = min(n_tiles, pv.max_tiles);
-    int n_groups = 0;
+    int n_groups = 0, n_tok = 0;
     if (pv.decode) {
-        const int n_tok = block_exclusive_scan<PLAN_THREADS>(a2, S, lds);
+        n_tok = block_exclusive_scan<PLAN_THREADS>(a2, S, lds);
         n_groups = block_exclusive_scan<PLAN_THREADS>(a3, S, lds);   // a3[p] = groups before p
-        if (tid == 0) {
-            *pv.n_groups = n_groups;
-            pv.grp_start[n_groups] = min(n_tok, T);
-        }
+        if (tid == 0) pv.grp_start[n_groups] = min(n_tok, T);
     }
 
     // 4. emit
@@ -190,26 +195,48 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
         }
         if (pv.decode) {
             const int base = min(a2[p], T);
-            for (int j = 0; j < len && base + j < T; ++j) pv.tok_sorted[base + j] = lo + j;
             const bool head = (p == 0) || ((keys[p - 1] >> 32) != (key >> 32));
             if (head) {
                 const int gi = a3[p];   // exclusive count of heads before p
-                pv.grp_meta[gi].x = e;
-                pv.grp_meta[gi].w = rk;
+                pv.grp_tmp[gi] = make_int2(e, rk);
                 pv.grp_start[gi] = base;
             }
         }
     }
     if (pv.decode) {
-        // a group ends where the next one starts
-        __syncthreads();
-        for (int gi = tid; gi < n_groups; gi += PLAN_THREADS) {
-            pv.grp_meta[gi].y = pv.grp_start[gi];
-            pv.grp_meta[gi].z = pv.grp_start[gi + 1];
+        // tokens in sorted order, one per thread and step whatever the sequences' lengths:
+        // position t belongs to the last sorted sequence that starts at or before it
+        for (int t = tid; t < min(n_tok, T); t += PLAN_THREADS) {
+            int first = 0, last = S - 1;
+            while (first < last) {
+                const int mid = (first + last + 1) >> 1;
+                if (a2[mid] <= t) first = mid;
+                else last = mid - 1;
+            }
+            const int s = (int)(keys[first] & 0xffffffffu);
+            pv.tok_sorted[t] = seq_offsets[s] + (t - a2[first]);
         }
+    }
+    if (pv.decode) {
+        // A group ends where the next one starts.  It is cut into records of at most
+        // GROUP_CHUNK tokens: the decode kernels hand a record to one column of
+        // workgroups, and a hot expert's tokens must not all queue behind one column.
+        __syncthreads();   // grp_start / grp_tmp are complete, a1 is free
+        for (int gi = tid; gi < n_groups; gi += PLAN_THREADS)
+            a1[gi] = (pv.grp_start[gi + 1] - pv.grp_start[gi] + GROUP_CHUNK - 1) / GROUP_CHUNK;
+        __syncthreads();
+        const int n_rec = min(block_exclusive_scan<PLAN_THREADS>(a1, n_groups, lds), pv.max_groups);
+        for (int gi = tid; gi < n_groups; gi += PLAN_THREADS) {
+            const int2 er = pv.grp_tmp[gi];
+            const int ge = pv.grp_start[gi + 1];
+            int rec = a1[gi];
+            for (int t = pv.grp_start[gi]; t < ge && rec < pv.max_groups; t += GROUP_CHUNK, ++rec)
+                pv.grp_meta[rec] = make_int4(er.x, t, min(t + GROUP_CHUNK, ge), er.y);
+        }
+        if (tid == 0) *pv.n_groups = n_rec;
         // unused records read as empty groups, so the decode kernels need not
         // fetch the group count before their own record
-        for (int gi = n_groups + tid; gi < pv.max_groups; gi += PLAN_THREADS) pv.grp_meta[gi] = make_int4(-1, 0, 0, 0);
+        for (int gi = n_rec + tid; gi < pv.max_groups; gi += PLAN_THREADS) pv.grp_meta[gi] = make_int4(-1, 0, 0, 0);
     }
 }
 
