@@ -16,6 +16,8 @@
 //   base   : ybase[s] = x[:, range s] W[:, range s]^T   (fp32, linear.hip)
 //   shrink : ug[pos, :] = scale * A_e x_tok             (bf16 high part + remainder)
 //   expand : y[tok, :]  = sum_s ybase[s][tok, :] + B_e ug[pos]
+#include <algorithm>
+
 #include "gemm_core.h"
 #include "kernels.h"
 #include "linear_tile.h"
@@ -51,7 +53,11 @@ struct ShrinkDParams {
 
 // One (expert group g, 16-row slab of A_e) of the decode shrink; `red` is the
 // workgroup's [SHRINK_WAVES][64][4] floats of LDS.
-template <int UNR>
+// KS_HOLD > 0 (batches beyond the small-batch size, whose group records hold up
+// to GROUP_CHUNK tokens: several blocks of 16): a wave's share of the slab is at
+// most KS_HOLD k-steps and stays in registers for all of the record's token
+// blocks, instead of being fetched again for each.
+template <int UNR, int KS_HOLD = 0>
 __device__ __forceinline__ void decode_shrink_slab(const ShrinkDParams &p, int slab, int g,
                                                    float (*red)[64][4])
 {
@@ -90,11 +96,29 @@ __device__ __forceinline__ void decode_shrink_slab(const ShrinkDParams &p, int s
     const int ks_end = min(nks, ks_beg + per);
     const int klen = min(d_in, ks_end * 32);
 
+    bf16x8_t held[KS_HOLD > 0 ? KS_HOLD : 1];
+    if constexpr (KS_HOLD > 0) {
+#pragma unroll
+        for (int u = 0; u < KS_HOLD; ++u) held[u] = ldg_frag(arow, (ks_beg + u) * 32 + kq, klen);   // past the range: zero
+    }
     for (int t0 = gs; t0 < ge; t0 += 16) {
         const int pos = t0 + (lane & 15);
         const bool tvalid = pos < ge;
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
         const char *xrow = x + (int64_t)tok_sorted[tvalid ? pos : gs] * ld;
+        if constexpr (KS_HOLD > 0) {
+#pragma unroll
+            for (int u0 = 0; u0 < KS_HOLD; u0 += UNR) {
+                if (ks_beg + u0 < ks_end) {   // the same for the whole wave
+                    bf16x8_t b[UNR];
+#pragma unroll
+                    for (int u = 0; u < UNR; ++u) b[u] = ldg_frag(xrow, (ks_beg + u0 + u) * 32 + kq, klen);
+#pragma unroll
+                    for (int u = 0; u < UNR; ++u)
+                        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(held[u0 + u], b[u], acc, 0, 0, 0);
+                }
+            }
+        } else
         for (int ks0 = ks_beg; ks0 < ks_end; ks0 += UNR) {
             bf16x8_t a[UNR], b[UNR];
             // A_e first: its address needs the group record only, the x rows also the
@@ -136,10 +160,11 @@ __device__ __forceinline__ void decode_shrink_slab(const ShrinkDParams &p, int s
 
 // grid (ceil(r / 16), max_groups): the slabs of one expert are neighbours in
 // dispatch order, so its rows of A_e stream from HBM as one contiguous run.
+template <int KS_HOLD>
 __global__ __launch_bounds__(SHRINK_WAVES * 64) void decode_shrink_kernel(ShrinkDParams p)
 {
     __shared__ float red[SHRINK_WAVES][64][4];
-    decode_shrink_slab<SHRINK_BATCH>(p, (int)blockIdx.x, (int)blockIdx.y, red);
+    decode_shrink_slab<SHRINK_BATCH, KS_HOLD>(p, (int)blockIdx.x, (int)blockIdx.y, red);
 }
 
 // Base GEMM tiles and shrink slabs in one launch: the two are independent, the
@@ -313,7 +338,19 @@ hipError_t launch_decode_shrink(const PlanView &pv, const DecodeArgs &d, hipStre
     const LinearArgs &a = d.lin;
     if (a.r <= 0 || pv.max_groups <= 0) return hipSuccess;
     dim3 grid((unsigned)((a.r + 15) / 16), (unsigned)pv.max_groups);
-    hipLaunchKernelGGL(decode_shrink_kernel, grid, dim3(SHRINK_WAVES * 64), 0, stream, shrink_params(pv, d));
+    // k-steps of 32 per wave
+    const int per = ((a.d_in + 31) / 32 + SHRINK_WAVES - 1) / SHRINK_WAVES;
+    const ShrinkDParams p = shrink_params(pv, d);
+    // holding 24 k-steps costs occupancy: worth it only where records tend to span several token
+    // blocks, i.e. not with about one token per group (4 tokens per possible group on average is
+    // where it began to pay on the 5632-wide projection)
+    const bool several_blocks = pv.T >= 4 * std::min<int64_t>(pv.S, (int64_t)pv.E + 1);
+    if (pv.T > DECODE_MAX_T && per <= 8)
+        hipLaunchKernelGGL(decode_shrink_kernel<8>, grid, dim3(SHRINK_WAVES * 64), 0, stream, p);
+    else if (pv.T > DECODE_MAX_T && per <= 24 && several_blocks)
+        hipLaunchKernelGGL(decode_shrink_kernel<24>, grid, dim3(SHRINK_WAVES * 64), 0, stream, p);
+    else
+        hipLaunchKernelGGL(decode_shrink_kernel<0>, grid, dim3(SHRINK_WAVES * 64), 0, stream, p);
     return hipGetLastError();
 }
 
