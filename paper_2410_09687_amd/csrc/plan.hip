@@ -140,21 +140,58 @@ __global__ __launch_bounds__(PLAN_THREADS) void plan_kernel(PlanView pv, const i
         return;
     }
 
-    // 2. bitonic sort of the keys (workgroup-wide, in global memory)
-    for (int k = 2; k <= npow2; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int i = tid; i < npow2; i += PLAN_THREADS) {
+    // 2. bitonic sort of the keys by the one workgroup.  Element i meets element i ^ j,
+    // ascending where (i & k) == 0.  Up to PLAN_LDS_S keys everything happens in LDS.
+    // Beyond, only the steps whose partners lie PLAN_LDS_S or more apart walk global
+    // memory; all steps with j < PLAN_LDS_S stay inside an aligned chunk of PLAN_LDS_S
+    // keys, which is brought into LDS once for a whole run of them.
+    auto steps_in = [&](unsigned long long *buf, int n, int base, int k, int j_first) {
+        for (int j = j_first; j > 0; j >>= 1) {
+            for (int i = tid; i < n; i += PLAN_THREADS) {
                 const int l = i ^ j;
                 if (l > i) {
-                    const unsigned long long a = keys[i], b = keys[l];
-                    const bool up = (i & k) == 0;
+                    const unsigned long long a = buf[i], b = buf[l];
+                    const bool up = ((base + i) & k) == 0;
                     if ((a > b) == up) {
-                        keys[i] = b;
-                        keys[l] = a;
+                        buf[i] = b;
+                        buf[l] = a;
                     }
                 }
             }
             __syncthreads();
+        }
+    };
+    if (small) {
+        for (int k = 2; k <= npow2; k <<= 1) steps_in(keys, npow2, 0, k, k >> 1);
+    } else {
+        auto chunk_run = [&](int c, int k_first, int k_last, int j_first_of_last) {
+            // chunk c through LDS: whole stages k_first..k_last / 2 and, of stage k_last, the steps from j_first_of_last down
+            unsigned long long *g = keys + (size_t)c * PLAN_LDS_S;
+            for (int i = tid; i < PLAN_LDS_S; i += PLAN_THREADS) lds_keys[i] = g[i];
+            __syncthreads();
+            for (int k = k_first; k < k_last; k <<= 1) steps_in(lds_keys, PLAN_LDS_S, c * PLAN_LDS_S, k, k >> 1);
+            steps_in(lds_keys, PLAN_LDS_S, c * PLAN_LDS_S, k_last, j_first_of_last);
+            for (int i = tid; i < PLAN_LDS_S; i += PLAN_THREADS) g[i] = lds_keys[i];
+            __syncthreads();
+        };
+        const int n_chunks = npow2 / PLAN_LDS_S;
+        for (int c = 0; c < n_chunks; ++c) chunk_run(c, 2, PLAN_LDS_S, PLAN_LDS_S >> 1);
+        for (int k = 2 * PLAN_LDS_S; k <= npow2; k <<= 1) {
+            for (int j = k >> 1; j >= PLAN_LDS_S; j >>= 1) {
+                for (int i = tid; i < npow2; i += PLAN_THREADS) {
+                    const int l = i ^ j;
+                    if (l > i) {
+                        const unsigned long long a = keys[i], b = keys[l];
+                        const bool up = (i & k) == 0;
+                        if ((a > b) == up) {
+                            keys[i] = b;
+                            keys[l] = a;
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+            for (int c = 0; c < n_chunks; ++c) chunk_run(c, k, k, PLAN_LDS_S >> 1);
         }
     }
 
