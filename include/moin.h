@@ -354,6 +354,21 @@ int moin_timing_reset(moin_ctx *ctx);
 int moin_timing_read(moin_ctx *ctx, int kernel_id, double *ms_sum,
                      int64_t *launches);
 
+/* moin_lora_linear_planned for n (1..4) projections of a layer that read the same
+ * input x [T, d_in] (q, k, v; gate, up): on the prefill path the adapters' first
+ * products u_i = scale * x A_{i,e}^T of all n come out of ONE pass over x, then
+ * each projection's main product runs as in moin_lora_linear_planned; the results
+ * are, bit for bit, those of n single calls.  W, A_stack, B_stack, y: host arrays
+ * of n device pointers (stacks [E, r, d_in] / [E, d_out[i], r]; A_stack and B_stack
+ * may be NULL when there are no adapters), d_out: host array of n widths; r and
+ * scale are common.  Needs 2 n T r bf16 of workspace.  Errors as
+ * moin_lora_linear_planned; n outside 1..4: MOIN_EINVAL. */
+int moin_lora_linear_planned_shared(moin_ctx *ctx, const moin_plan *plan, const void *x, int32_t n,
+                                    const void *const *W, const void *const *A_stack,
+                                    const void *const *B_stack, int32_t d_in, const int32_t *d_out,
+                                    int32_t r, float scale, void *const *y, moin_dtype y_dt,
+                                    void *stream);
+
 /* "Future Works", better adapters: an activation function between the adapter's
  * two linear layers,
  *     y = x W^T + scale * act(x A_e^T) B_e^T,

@@ -657,6 +657,63 @@ int moin_lora_linear_planned(moin_ctx *ctx, const moin_plan *plan, const void *x
                                static_cast<hipStream_t>(stream));
 }
 
+int moin_lora_linear_planned_shared(moin_ctx *ctx, const moin_plan *plan, const void *x, int32_t n,
+                                    const void *const *W, const void *const *A_stack,
+                                    const void *const *B_stack, int32_t d_in, const int32_t *d_out, int32_t r,
+                                    float scale, void *const *y, moin_dtype y_dt, void *stream)
+{
+    if (!ctx || !plan || plan->device != ctx->device) return MOIN_EINVAL;
+    if (n < 1 || n > MAX_SHARED_X || !W || !d_out || !y) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    if (!plan->built) return MOIN_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const PlanView &pv = plan->pv;
+    if (pv.S == 0 || pv.T == 0) return MOIN_OK;
+    const bool adapters = pv.E > 0 && r > 0;
+    if (adapters && (!A_stack || !B_stack)) return MOIN_EINVAL;
+    for (int i = 0; i < n; ++i) {
+        const int vrc = validate_linear(x, W[i], adapters ? A_stack[i] : nullptr, adapters ? B_stack[i] : nullptr,
+                                        pv.E, d_in, d_out[i], r, scale, y[i], y_dt);
+        if (vrc != MOIN_OK) return vrc;
+    }
+    if (pv.decode || !adapters || n == 1) {
+        // nothing to share on these paths: the projections one after the other
+        for (int i = 0; i < n; ++i) {
+            const int rc = linear_planned_impl(ctx, plan, x, W[i], adapters ? A_stack[i] : nullptr,
+                                               adapters ? B_stack[i] : nullptr, d_in, d_out[i], r, scale, y[i],
+                                               y_dt, st);
+            if (rc != MOIN_OK) return rc;
+        }
+        return MOIN_OK;
+    }
+    const size_t u_bytes = align_up((size_t)pv.T * (size_t)r * 2, 256);
+    const int rc = ensure_ws(ctx, (size_t)n * 2 * u_bytes);
+    if (rc != MOIN_OK) return rc;
+    void *u_hi[MAX_SHARED_X], *u_lo[MAX_SHARED_X];
+    for (int i = 0; i < n; ++i) {
+        u_hi[i] = static_cast<char *>(ctx->ws) + (size_t)i * 2 * u_bytes;
+        u_lo[i] = static_cast<char *>(u_hi[i]) + u_bytes;
+    }
+    LinearArgs a;
+    a.x = x; a.W = nullptr; a.A_stack = nullptr; a.B_stack = nullptr;
+    a.u_hi = a.u_lo = nullptr;
+    a.y = nullptr; a.y_f32 = (y_dt == MOIN_F32);
+    a.d_in = d_in; a.d_out = 0; a.r = r; a.scale = scale; a.act = ctx->act;
+    if (timed(ctx, MOIN_K_SHRINK, st, [&] {
+            return launch_prefill_shrink_shared(pv, a, n, A_stack, u_hi, u_lo, st);
+        }) != hipSuccess)
+        return MOIN_EHIP;
+    for (int i = 0; i < n; ++i) {
+        a.W = W[i]; a.A_stack = A_stack[i]; a.B_stack = B_stack[i];
+        a.u_hi = u_hi[i]; a.u_lo = u_lo[i];
+        a.y = y[i]; a.d_out = d_out[i];
+        if (timed(ctx, MOIN_K_LINEAR, st, [&] { return launch_prefill_linear(pv, a, st); }) != hipSuccess)
+            return MOIN_EHIP;
+    }
+    return MOIN_OK;
+}
+
 int moin_lora_linear_ranked(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
                             const int32_t *expert_ids, int32_t S, int64_t T, const void *W,
                             const void *A_stack, const void *B_stack, int32_t E, int32_t d_in,

@@ -69,6 +69,13 @@ struct LinearArgs {
 };
 
 hipError_t launch_prefill_shrink(const PlanView &pv, const LinearArgs &a, hipStream_t stream);
+// The shrinks of up to MAX_SHARED_X projections that read the same x (q, k, v; gate, up)
+// in one launch: the column tiles of projection i take A_stack[i] and write u_hi[i] /
+// u_lo[i] ([T, r] each), and x streams from HBM once for all of them.  a: x, d_in, r,
+// scale, act as for the single shrink (its own A_stack / u pointers unused).
+constexpr int MAX_SHARED_X = 4;
+hipError_t launch_prefill_shrink_shared(const PlanView &pv, const LinearArgs &a, int n, const void *const *A_stack,
+                                        void *const *u_hi, void *const *u_lo, hipStream_t stream);
 hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStream_t stream);
 // shapes the persistent streaming prefill kernel takes (anything else: the tiled kernel)
 bool stream_kernel_fits(const LinearArgs &a);

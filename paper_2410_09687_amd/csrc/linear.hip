@@ -20,6 +20,11 @@ namespace moin {
 struct ShrinkKParams {
     const char *x, *A_stack;
     char *u_hi, *u_lo;
+    // projections that share x: column tile tn belongs to projection tn / tiles_per_proj
+    // (A_stack / u_hi / u_lo above are then those of projection 0)
+    int n_proj, tiles_per_proj;
+    const char *A_more[MAX_SHARED_X - 1];
+    char *uh_more[MAX_SHARED_X - 1], *ul_more[MAX_SHARED_X - 1];
     const int *tile_row0, *tile_rows, *tile_expert, *tile_rank, *n_tiles;
     int d_in, r;
     int n_tiles_n;
@@ -85,7 +90,17 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
     if (rows <= 0 || (e < 0 && !quant)) return;
     rows = min(rows, C::BM);
     const int row0 = uniform(p.tile_row0[t]) + sub * C::BM;
-    const int n0 = tn * C::BN;
+    const int proj = tn / p.tiles_per_proj;
+    const int n0 = (tn - proj * p.tiles_per_proj) * C::BN;
+    const char *A_stack = p.A_stack;
+    char *u_hi = p.u_hi, *u_lo = p.u_lo;
+#pragma unroll
+    for (int i = 1; i < MAX_SHARED_X; ++i)
+        if (proj == i) {   // (selected one by one: indexing the arrays would put the parameters in scratch)
+            A_stack = p.A_more[i - 1];
+            u_hi = p.uh_more[i - 1];
+            u_lo = p.ul_more[i - 1];
+        }
     // the expert's own rank: rows of A_e beyond it do not exist; the main kernel
     // reads u in blocks of 64 columns, so the rest of the last block is written as zeros
     const int re = e < 0 ? 0 : min(p.r, uniform(p.tile_rank[t]));
@@ -98,7 +113,7 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
     const uint32_t ldx = (uint32_t)p.d_in * 2u;
     const char *xa = p.x + (int64_t)row0 * ldx;
     // (a walk for the quantiser alone puts x in A_e's place: valid addresses, unused products)
-    const char *ae = shrink ? p.A_stack + ((int64_t)e * p.r + n0) * ldx : xa;
+    const char *ae = shrink ? A_stack + ((int64_t)e * p.r + n0) * ldx : xa;
     const int nkb = (p.d_in + C::BK - 1) / C::BK;
 
     typename C::Acc acc;
@@ -147,8 +162,8 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
     if (!shrink) return;
 
     const int64_t ldu = (int64_t)p.r * 2;
-    char *uh = p.u_hi + (int64_t)row0 * ldu;
-    char *ul = p.u_lo + (int64_t)row0 * ldu;
+    char *uh = u_hi + (int64_t)row0 * ldu;
+    char *ul = u_lo + (int64_t)row0 * ldu;
     const float s = p.scale;
     const int act = p.act;
     C::epilogue(smem, acc, [&](int row, int col, float(&v)[8]) {
@@ -231,9 +246,15 @@ int compute_units()
 }
 
 // xq / xs: the quantising variant's outputs
+struct SharedX {
+    int n;
+    const void *const *A_stack;
+    void *const *u_hi, *const *u_lo;
+};
+
 template <class C, bool QUANT = false>
 static hipError_t launch_shrink_as(const PlanView &pv, const LinearArgs &a, hipStream_t stream, void *xq = nullptr,
-                                   void *xs = nullptr)
+                                   void *xs = nullptr, const SharedX *shared = nullptr)
 {
     ShrinkKParams p;
     p.xq = (char *)xq; p.xs = (char *)xs; p.T = pv.T;
@@ -243,7 +264,20 @@ static hipError_t launch_shrink_as(const PlanView &pv, const LinearArgs &a, hipS
     p.tile_rank = pv.tile_rank;
     p.n_tiles = pv.n_tiles;
     p.d_in = a.d_in; p.r = a.r; p.scale = a.scale; p.act = a.act;
-    p.n_tiles_n = (a.r + C::BN - 1) / C::BN;
+    p.tiles_per_proj = (a.r + C::BN - 1) / C::BN;
+    p.n_proj = shared ? shared->n : 1;
+    for (int i = 1; i < MAX_SHARED_X; ++i) {
+        const bool on = shared && i < shared->n;
+        p.A_more[i - 1] = on ? (const char *)shared->A_stack[i] : nullptr;
+        p.uh_more[i - 1] = on ? (char *)shared->u_hi[i] : nullptr;
+        p.ul_more[i - 1] = on ? (char *)shared->u_lo[i] : nullptr;
+    }
+    if (shared) {
+        p.A_stack = (const char *)shared->A_stack[0];
+        p.u_hi = (char *)shared->u_hi[0];
+        p.u_lo = (char *)shared->u_lo[0];
+    }
+    p.n_tiles_n = p.tiles_per_proj * p.n_proj;
     const int64_t grid = (int64_t)pv.max_tiles * (TILE_M / C::BM) * p.n_tiles_n;
     if (grid > 0x7ffffff0LL) return hipErrorInvalidValue;
     hipLaunchKernelGGL((shrink_kernel<C, QUANT>), dim3((unsigned)round_up8((int)grid)), dim3(C::NT),
@@ -262,12 +296,27 @@ hipError_t launch_prefill_shrink_quant(const PlanView &pv, const LinearArgs &a, 
     return launch_shrink_as<CfgShrinkDeep64, true>(pv, a, stream, xq, xs);
 }
 
-hipError_t launch_prefill_shrink(const PlanView &pv, const LinearArgs &a, hipStream_t stream)
+static hipError_t launch_prefill_shrink_any(const PlanView &pv, const LinearArgs &a, const SharedX *shared,
+                                            hipStream_t stream)
 {
     if (a.r <= 0 || pv.max_tiles <= 0) return hipSuccess;
-    if (a.d_in % 64 == 0 && a.r > 64 && a.r <= 128) return launch_shrink_as<CfgShrinkR128>(pv, a, stream);
-    if (a.d_in % 64 == 0) return launch_shrink_as<CfgShrinkDma>(pv, a, stream);
-    return launch_shrink_as<CfgShrink>(pv, a, stream);
+    if (a.d_in % 64 == 0 && a.r > 64 && a.r <= 128)
+        return launch_shrink_as<CfgShrinkR128>(pv, a, stream, nullptr, nullptr, shared);
+    if (a.d_in % 64 == 0) return launch_shrink_as<CfgShrinkDma>(pv, a, stream, nullptr, nullptr, shared);
+    return launch_shrink_as<CfgShrink>(pv, a, stream, nullptr, nullptr, shared);
+}
+
+hipError_t launch_prefill_shrink(const PlanView &pv, const LinearArgs &a, hipStream_t stream)
+{
+    return launch_prefill_shrink_any(pv, a, nullptr, stream);
+}
+
+hipError_t launch_prefill_shrink_shared(const PlanView &pv, const LinearArgs &a, int n, const void *const *A_stack,
+                                        void *const *u_hi, void *const *u_lo, hipStream_t stream)
+{
+    if (n < 1 || n > MAX_SHARED_X) return hipErrorInvalidValue;
+    const SharedX sh{n, A_stack, u_hi, u_lo};
+    return launch_prefill_shrink_any(pv, a, &sh, stream);
 }
 
 template <class C>

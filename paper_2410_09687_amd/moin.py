@@ -35,6 +35,7 @@ EXPORTS = [
     "moin_cache_table", "moin_cache_stats", "moin_lora_linear_ranked", "moin_plan_build_ranked",
     "moin_mx_quantize", "moin_lora_linear_mx", "moin_lora_linear_mx_planned",
     "moin_probe_out_len", "moin_probe_mfma_bf16", "moin_probe_read", "moin_set_adapter_activation",
+    "moin_lora_linear_planned_shared",
 ]
 ACTIVATIONS = {None: 0, "none": 0, "relu": 1, "silu": 2, "gelu": 3}
 CACHE_STATS = ["batches", "seq_hits", "seq_misses", "loads", "evictions", "overflows", "bytes"]
@@ -79,6 +80,8 @@ def load() -> ctypes.CDLL:
     lib.moin_lora_linear_mx_planned.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, i32, i32, c.c_float,
                                                 vp, c.c_int, vp]
     lib.moin_set_adapter_activation.argtypes = [vp, i32]
+    lib.moin_lora_linear_planned_shared.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, c.c_float, vp,
+                                                    c.c_int, vp]
     lib.moin_probe_out_len.argtypes = [vp]
     lib.moin_probe_out_len.restype = c.c_int64
     lib.moin_probe_mfma_bf16.argtypes = [vp, vp, i64, i32, vp, c.POINTER(c.c_double), vp]
@@ -400,6 +403,45 @@ def moin_lora_linear_mx_planned(ctx: Context, plan: "Plan", x: torch.Tensor, Wq:
         _dev_ptr(A_stack, "A_stack", bf), _dev_ptr(B_stack, "B_stack", bf), d_in, d_out, r, float(scale),
         _dev_ptr(y, "y") if T else None, ydt, _stream_ptr(stream)), "moin_lora_linear_mx_planned")
     return y
+
+
+def moin_lora_linear_planned_shared(ctx: Context, plan: "Plan", x: torch.Tensor, Ws, A_stacks, B_stacks, scale: float,
+                                    y_dtype=torch.bfloat16, outs=None, stream=None):
+    """``moin_lora_linear_planned`` for up to four projections that read the same ``x`` (q, k, v; gate, up):
+    lists of weights ``Ws[i] [d_out_i, d_in]`` and of stacks (or ``None`` for both lists); returns the list
+    of outputs.  On the prefill path the adapters' first products come out of one pass over ``x``."""
+    n = len(Ws)
+    if not 1 <= n <= 4:
+        raise ValueError("1 to 4 projections expected")
+    if (A_stacks is None) != (B_stacks is None):
+        raise ValueError("A_stacks and B_stacks go together")
+    if A_stacks is not None and (len(A_stacks) != n or len(B_stacks) != n):
+        raise ValueError("one A_stack and one B_stack per weight expected")
+    dims = [_stack_dims(Ws[i], None if A_stacks is None else A_stacks[i], None if B_stacks is None else B_stacks[i])
+            for i in range(n)]
+    d_in, E, r = dims[0][0], dims[0][2], dims[0][3]
+    if any(d[0] != d_in or d[2] != E or d[3] != r for d in dims):
+        raise ValueError("the projections must agree in d_in, E and r")
+    if x.dim() != 2 or x.shape[1] != d_in or x.shape[0] != plan.T:
+        raise ValueError("x [T,d_in] (T as planned) expected")
+    if E and E != plan.E:
+        raise ValueError("stacks hold a different number of experts than the plan was built for")
+    T = x.shape[0]
+    ys, ydt = [], None
+    for i in range(n):
+        y, ydt = _y_out(x, dims[i][1], y_dtype, None if outs is None else outs[i])
+        ys.append(y)
+    bf = torch.bfloat16
+    vpa = ctypes.c_void_p * n
+    def ptrs(ts, name, dtype=None):
+        return vpa(*[(_dev_ptr(t, name, dtype).value if t is not None else None) for t in ts])
+    _ck(load().moin_lora_linear_planned_shared(
+        ctx._h, plan._h, _dev_ptr(x, "x", bf) if T else None, n, ptrs(Ws, "W", bf),
+        ptrs(A_stacks, "A_stack", bf) if A_stacks is not None else None,
+        ptrs(B_stacks, "B_stack", bf) if B_stacks is not None else None, d_in,
+        (ctypes.c_int32 * n)(*[d[1] for d in dims]), r, float(scale), ptrs(ys, "y") if T else vpa(), ydt,
+        _stream_ptr(stream)), "moin_lora_linear_planned_shared")
+    return ys
 
 
 def moin_probe_mfma_bf16(ctx: Context, operands: torch.Tensor, iters: int, stream=None):
