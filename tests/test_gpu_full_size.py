@@ -150,3 +150,31 @@ def test_kmeans_update_full_size():
     assert not (err > tol).any(), f"{int((err > tol).sum())} entries beyond the bound, worst {err.max():.3e}"
     print(f"[gpu] c3 kmeans: worst centre error {err.max():.3e} (bound {tol.min():.3e}), "
           f"{int((ref_counts == 0).sum())} empty clusters", flush=True)
+
+
+def test_prefill_addresses_beyond_4_gib():
+    # maximum sizes: x holds 4.8 GB, so the byte offsets of the rows from 1 048 576 on do not fit 32 bits;
+    # rows on both sides of that line, the first and the last ones against the oracle
+    lens = [4096] * 285 + [2929, 1, 0, 300]
+    w = wl.LinearWorkload("beyond_4gib", 2048, 264, 64, 6, lens, "uniform", scale=2.0, seed=4242)
+    T = w.T
+    assert T * 2048 * 2 > (1 << 32) + (1 << 28)
+    inp = wl.make_linear_inputs(w, "cuda")
+    line = (1 << 32) // (2048 * 2)
+    rows = np.unique(np.concatenate([np.arange(0, 4), np.arange(line - 4, line + 4), np.arange(T - 304, T - 296),
+                                     np.arange(T - 4, T), _sample_rows(T, inp.seq_offsets, 24, seed=5)]))
+    x_rows = wl.bf16_bits(inp.x[torch.from_numpy(rows).cuda()])
+    # the oracle on a batch made of just those rows, one sequence each, with the expert of the row's sequence
+    off = inp.seq_offsets.cpu().numpy()
+    seq_of = np.searchsorted(off, rows, side="right") - 1
+    A, B, ids = wl.compact_stacks(inp)
+    import oracle
+    ref = oracle.lora_linear(x_rows, np.arange(len(rows) + 1, dtype=np.int32), ids[seq_of], wl.bf16_bits(inp.W), A, B,
+                             w.scale)
+    for dt in (torch.bfloat16, torch.float32):
+        print(f"[gpu] rows beyond 4 GiB y={dt}", flush=True)
+        y = gc.run_linear(inp, dt)
+        print(gc.compare_linear(y[torch.from_numpy(rows).cuda()], ref, what=f"beyond_4gib/{dt}"), flush=True)
+        del y
+    del inp
+    torch.cuda.empty_cache()
