@@ -178,3 +178,22 @@ def test_prefill_addresses_beyond_4_gib():
         del y
     del inp
     torch.cuda.empty_cache()
+
+
+def test_router_addresses_beyond_4_gib():
+    # 3.2 M queries of 768 bf16 values: 4.9 GB, query rows from 2 796 203 on start beyond 32-bit byte offsets
+    rw = wl.RouteWorkload("route_beyond_4gib", N=3_200_000, K=500, D=768, dtype="bf16", normalise=True, seed=777)
+    rin = wl.make_route_inputs(rw, "cuda")
+    assert rin.emb.numel() * 2 > (1 << 32) + (1 << 28)
+    print("[gpu] router beyond 4 GiB", flush=True)
+    eids, cids, counts = moin.moin_route(gc.ctx(), rin.emb, rin.centroids, want_counts=True)
+    gc.ctx().check()
+    assert counts.sum().item() == rw.N
+    assert torch.equal(counts.long(), torch.bincount(cids.long(), minlength=rw.K))
+    line = (1 << 32) // (768 * 2)
+    sample = np.unique(np.concatenate([np.arange(0, 64), np.arange(line - 64, line + 64),
+                                       np.arange(rw.N - 300, rw.N), np.arange(0, rw.N, 4099)]))
+    n_band = gc.check_route(rin.emb, rin.centroids, cids, sample=sample)
+    print(f"[gpu] {sample.size} sampled queries, {n_band} differ inside the near-tie band", flush=True)
+    del rin
+    torch.cuda.empty_cache()
