@@ -195,5 +195,19 @@ def test_router_addresses_beyond_4_gib():
                                        np.arange(rw.N - 300, rw.N), np.arange(0, rw.N, 4099)]))
     n_band = gc.check_route(rin.emb, rin.centroids, cids, sample=sample)
     print(f"[gpu] {sample.size} sampled queries, {n_band} differ inside the near-tie band", flush=True)
+    # the centre update over the same table (its rows are gathered by index: 64-bit row addresses)
+    import oracle
+    print("[gpu] kmeans update beyond 4 GiB", flush=True)
+    new, kcounts, inertia = moin.moin_kmeans_update(gc.ctx(), rin.emb, cids, rin.centroids, out_dtype=torch.float32)
+    gc.ctx().check()
+    assert torch.equal(kcounts, counts)
+    ref_new, ref_counts, ref_inertia = oracle.kmeans_update(wl.bf16_bits(rin.emb), cids.cpu().numpy(),
+                                                            wl.bf16_bits(rin.centroids))
+    assert np.array_equal(kcounts.cpu().numpy(), ref_counts)
+    assert abs(inertia.item() - ref_inertia) <= 2e-6 * ref_inertia
+    xmax = float(rin.emb.abs().max().item())
+    tol = 520 * 2.0 ** -24 * xmax + 2 * 2.0 ** -24 * np.abs(ref_new)
+    err = np.abs(new.double().cpu().numpy() - ref_new)
+    assert not (err > tol).any(), f"{int((err > tol).sum())} entries beyond the bound, worst {err.max():.3e}"
     del rin
     torch.cuda.empty_cache()
