@@ -16,5 +16,6 @@ from .oracle import (  # noqa: F401
     mx_quantize,
     retain_clusters,
     route,
+    route_topk,
     slot_map,
 )

@@ -145,6 +145,52 @@ int moin_oracle_route(const void *emb, const void *cent, int64_t N, int32_t K,
     return ORACLE_OK;
 }
 
+/*
+ * The k nearest centroids of every query ("Future Works", creating new experts
+ * on the fly: a query on the boundary of several clusters may need several
+ * adapters): ids[i, 0..k) are the centroid indices in order of increasing
+ * ||q_i - c||^2, equal distances in order of increasing index; d2[i, m] the
+ * distances (fp64).  Column 0 is moin_oracle_route's answer.  With fewer than k
+ * eligible centroids the remaining columns hold -1 / +inf.  A NaN distance
+ * never enters the list.
+ */
+int moin_oracle_route_topk(const void *emb, const void *cent, int64_t N, int32_t K,
+                           int32_t D, int dt, const uint8_t *eligible, int32_t k,
+                           int32_t *ids, double *d2)
+{
+    if (N < 0 || K <= 0 || D <= 0 || k <= 0 || (dt != 0 && dt != 1)) return ORACLE_EINVAL;
+    if (N == 0) return ORACLE_OK;
+    if (!emb || !cent || !ids || !d2) return ORACLE_EINVAL;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < N; ++i) {
+        int32_t *li = ids + (size_t)i * k;
+        double *ld = d2 + (size_t)i * k;
+        int32_t n = 0;                       /* entries in the list so far */
+        for (int32_t m = 0; m < k; ++m) {
+            li[m] = -1;
+            ld[m] = INFINITY;
+        }
+        for (int32_t c = 0; c < K; ++c) {
+            if (eligible && !eligible[c]) continue;
+            double d = dist2(emb, cent, i, c, D, dt);
+            if (!(d == d)) continue;
+            /* c is larger than every index in the list: it goes behind its equals */
+            int32_t pos = n;
+            while (pos > 0 && d < ld[pos - 1]) --pos;
+            if (pos >= k) continue;
+            int32_t last = n < k ? n : k - 1;
+            for (int32_t m = last; m > pos; --m) {
+                li[m] = li[m - 1];
+                ld[m] = ld[m - 1];
+            }
+            li[pos] = c;
+            ld[pos] = d;
+            if (n < k) ++n;
+        }
+    }
+    return ORACLE_OK;
+}
+
 /* expert_ids[i] = slot_of_centroid[centroid_ids[i]]; -1 marks a topic whose
  * adapter was never trained, i.e. "use the base model alone". */
 int moin_oracle_slot_map(const int32_t *centroid_ids, int64_t N,

@@ -43,6 +43,8 @@ def _load():
         lib.moin_oracle_slot_map.argtypes = [c.c_void_p, c.c_int64, c.c_void_p, c.c_int32,
                                              c.c_void_p]
         lib.moin_oracle_histogram.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_void_p]
+        lib.moin_oracle_route_topk.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_int,
+                                               c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p]
         lib.moin_oracle_lora_linear.argtypes = [
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int64,
             c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
@@ -117,6 +119,29 @@ def route(emb, centroids, eligible=None, want_gaps=False):
     _check(_load().moin_oracle_route(_ptr(emb), _ptr(centroids), N, K, D, dt, _ptr(el),
                                      _ptr(ids), _ptr(best), _ptr(second)), "route")
     return (ids, best, second) if want_gaps else ids
+
+
+def route_topk(emb, centroids, k, eligible=None):
+    """The k nearest centroids of every query, nearest first, equal distances by increasing index:
+    ``(ids [N,k] int32, d2 [N,k] float64)``; -1 / inf where fewer than k centroids are eligible."""
+    emb, dt = _emb_array(emb, "emb")
+    centroids, dt2 = _emb_array(centroids, "centroids")
+    if dt != dt2 or emb.ndim != 2 or centroids.ndim != 2 or emb.shape[1] != centroids.shape[1]:
+        raise ValueError("emb [N,D] and centroids [K,D] must share dtype and D")
+    if int(k) <= 0:
+        raise ValueError("k must be positive")
+    N, D = emb.shape
+    K = centroids.shape[0]
+    ids = np.zeros((N, int(k)), dtype=np.int32)
+    d2 = np.zeros((N, int(k)), dtype=np.float64)
+    el = None
+    if eligible is not None:
+        el = np.ascontiguousarray(np.asarray(eligible).astype(np.uint8))
+        if el.shape != (K,):
+            raise ValueError("eligible must have shape [K]")
+    _check(_load().moin_oracle_route_topk(_ptr(emb), _ptr(centroids), N, K, D, dt, _ptr(el), int(k),
+                                          _ptr(ids), _ptr(d2)), "route_topk")
+    return ids, d2
 
 
 def dist2(emb, centroids, qi, ki):
