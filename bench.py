@@ -237,8 +237,17 @@ def bench_router(ctx, steps, warmup):
     ctx.check()
     kt = kernel_times(ctx, step, steps)
     tf = rw.flops() / (ms * 1e-3) / 1e12
+    # request-time batch: the four nearest topics of 4096 queries ("Future Works", creating new experts on the fly)
+    q = rin.emb[:4096]
+
+    def topk():
+        moin.moin_route_topk(ctx, q, rin.centroids, 4)
+
+    tms, _ = timed_region(topk, 10, 2)
+    ctx.check()
     return {"ms_per_call": ms, "queries_per_s": rw.N / (ms * 1e-3), "TFLOPs": tf,
-            "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS, "kernels": kt}
+            "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS,
+            "top4_of_4096_queries": {"ms_per_call": tms, "queries_per_s": 4096 / (tms * 1e-3)}, "kernels": kt}
 
 
 def bench_kmeans(ctx, steps, warmup):

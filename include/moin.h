@@ -354,6 +354,20 @@ int moin_timing_reset(moin_ctx *ctx);
 int moin_timing_read(moin_ctx *ctx, int kernel_id, double *ms_sum,
                      int64_t *launches);
 
+/* The k (1..8) nearest topic embeddings of every query, nearest first, equal
+ * distances by increasing centroid index ("Future Works", creating new experts on
+ * the fly: a query on the boundary of several clusters, or one that needs several
+ * adapters).  Arguments as moin_route; outputs are [N, k] row-major, each may be
+ * NULL: centroid_ids, expert_ids (slot_of_centroid applied; -1 also where fewer
+ * than k centroids took part), dist2 (fp32 squared distances, +inf where
+ * unfilled).  Column 0 is moin_route's answer up to fp32 rounding of the
+ * distances.  A request-time call (one wave per query, distances as plain sums of
+ * squared differences), not the bulk router.  k outside 1..8: MOIN_EINVAL. */
+int moin_route_topk(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N,
+                    int32_t K, int32_t D, moin_dtype dt, const int32_t *slot_of_centroid,
+                    uint32_t flags, int32_t k, int32_t *expert_ids, int32_t *centroid_ids,
+                    float *dist2, void *stream);
+
 /* moin_lora_linear_planned for n (1..4) projections of a layer that read the same
  * input x [T, d_in] (q, k, v; gate, up): on the prefill path the adapters' first
  * products u_i = scale * x A_{i,e}^T of all n come out of ONE pass over x, then

@@ -946,6 +946,34 @@ int moin_timing_read(moin_ctx *ctx, int kernel_id, double *ms_sum, int64_t *laun
     return rc;
 }
 
+int moin_route_topk(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N, int32_t K, int32_t D,
+                    moin_dtype dt, const int32_t *slot_of_centroid, uint32_t flags, int32_t k,
+                    int32_t *expert_ids, int32_t *centroid_ids, float *dist2, void *stream)
+{
+    if (!ctx || N < 0 || K <= 0 || D <= 0 || k < 1 || k > 8) return MOIN_EINVAL;
+    if (dt != MOIN_BF16 && dt != MOIN_F32) return MOIN_EINVAL;
+    if (flags & ~MOIN_ROUTE_RETAINED_ONLY) return MOIN_EINVAL;
+    if ((flags & MOIN_ROUTE_RETAINED_ONLY) && !slot_of_centroid) return MOIN_EINVAL;
+    if (!centroids || (N > 0 && !emb)) return MOIN_EINVAL;
+    if (dt == MOIN_BF16 ? (D % 8 != 0) : (D % 4 != 0)) return MOIN_EINVAL;
+    if (D > (1 << 20) || K > (1 << 28) || N > (int64_t)0x7fffffff / 8) return MOIN_EINVAL;
+    if (misaligned(centroids, 16) || (emb && misaligned(emb, 16))) return MOIN_EINVAL;
+    if (N == 0 || (!expert_ids && !centroid_ids && !dist2)) return MOIN_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    RouteArgs a{};
+    a.emb = emb; a.cent = centroids; a.N = N; a.K = K; a.D = D;
+    a.is_bf16 = (dt == MOIN_BF16);
+    a.slot = slot_of_centroid;
+    a.retained_only = (flags & MOIN_ROUTE_RETAINED_ONLY) ? 1 : 0;
+    a.cid = centroid_ids;
+    a.expert_ids = expert_ids;
+    if (timed(ctx, MOIN_K_ROUTE, st, [&] { return launch_route_topk(a, k, dist2, st); }) != hipSuccess)
+        return MOIN_EHIP;
+    return MOIN_OK;
+}
+
 int moin_set_adapter_activation(moin_ctx *ctx, int32_t activation)
 {
     if (!ctx || activation < MOIN_ACT_NONE || activation > MOIN_ACT_GELU) return MOIN_EINVAL;

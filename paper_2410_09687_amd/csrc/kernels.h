@@ -126,6 +126,8 @@ constexpr int ROUTE_SMALL_MAX_N = 4096;  // up to here the K range is split acro
 int route_stream_group(int64_t N, int K, int D, int is_bf16);
 hipError_t launch_centroid_norms(const RouteArgs &a, hipStream_t stream);
 hipError_t launch_route(const RouteArgs &a, hipStream_t stream);
+// the k (1..8) nearest centroids per query: a.cid / a.expert_ids are [N, k], d2 [N, k] or null
+hipError_t launch_route_topk(const RouteArgs &a, int k, float *d2, hipStream_t stream);
 // true when launch_route itself fills a.counts (no histogram launch needed)
 bool route_tallies_counts(const RouteArgs &a);
 hipError_t launch_histogram(const int *ids, int64_t N, int K, int *counts, int zero_first,

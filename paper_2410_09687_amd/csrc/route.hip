@@ -674,6 +674,127 @@ __global__ __launch_bounds__(1024) void histogram_kernel(const int *ids, int64_t
     }
 }
 
+// The k nearest centroids of every query ("Future Works", creating new experts on the
+// fly: a query on the boundary of several clusters may need several adapters).  A
+// request-time call, not the bulk router: one wave per query, the squared distance
+// written out as the sum of squared differences in fp32 (lanes split the dimension,
+// butterfly sum: every lane ends with the same bits), centroids visited in index
+// order and inserted behind their equals, so equal distances keep index order.
+// Every lane carries the same list of ROUTE_TOPK_MAX entries in registers.
+constexpr int ROUTE_TOPK_MAX = 8;
+constexpr int ROUTE_TOPK_BATCH = 8;
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void route_topk_kernel(const char *__restrict__ emb, const char *__restrict__ cent,
+                                                         int64_t N, int K, int D, int k,
+                                                         const int *__restrict__ slot, int retained_only,
+                                                         int *__restrict__ cid, int *__restrict__ expert_ids,
+                                                         float *__restrict__ d2)
+{
+    constexpr int VPC = BF16 ? 8 : 4;   // values per 16-byte chunk
+    const int lane = threadIdx.x & 63;
+    const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= N) return;
+    const int64_t row_bytes = (int64_t)D * (16 / VPC);
+    const char *q = emb + i * row_bytes;
+    const int nch = D / VPC;
+    float ld[ROUTE_TOPK_MAX];
+    int li[ROUTE_TOPK_MAX];
+#pragma unroll
+    for (int m = 0; m < ROUTE_TOPK_MAX; ++m) {
+        ld[m] = __builtin_inff();
+        li[m] = -1;
+    }
+    // ROUTE_TOPK_BATCH centroids at a time: their loads are independent and in flight together
+    for (int c0 = 0; c0 < K; c0 += ROUTE_TOPK_BATCH) {
+        float acc[ROUTE_TOPK_BATCH];
+#pragma unroll
+        for (int u = 0; u < ROUTE_TOPK_BATCH; ++u) acc[u] = 0.f;
+        for (int ch = lane; ch < nch; ch += 64) {
+            const uint4 a = *reinterpret_cast<const uint4 *>(q + (int64_t)ch * 16);
+            uint4 b[ROUTE_TOPK_BATCH];
+#pragma unroll
+            for (int u = 0; u < ROUTE_TOPK_BATCH; ++u)   // past the last centroid: the last one again, not inserted
+                b[u] = *reinterpret_cast<const uint4 *>(cent + (int64_t)min(c0 + u, K - 1) * row_bytes + (int64_t)ch * 16);
+            float x[8];
+            if constexpr (BF16) {
+                const uint32_t aw[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    x[2 * t] = bits_f32(aw[t] << 16);
+                    x[2 * t + 1] = bits_f32(aw[t] & 0xFFFF0000u);
+                }
+            } else {
+                x[0] = bits_f32(a.x); x[1] = bits_f32(a.y); x[2] = bits_f32(a.z); x[3] = bits_f32(a.w);
+            }
+#pragma unroll
+            for (int u = 0; u < ROUTE_TOPK_BATCH; ++u) {
+                float y[8];
+                if constexpr (BF16) {
+                    const uint32_t bw[4] = {b[u].x, b[u].y, b[u].z, b[u].w};
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        y[2 * t] = bits_f32(bw[t] << 16);
+                        y[2 * t + 1] = bits_f32(bw[t] & 0xFFFF0000u);
+                    }
+                } else {
+                    y[0] = bits_f32(b[u].x); y[1] = bits_f32(b[u].y); y[2] = bits_f32(b[u].z); y[3] = bits_f32(b[u].w);
+                }
+#pragma unroll
+                for (int t = 0; t < VPC; ++t) {
+                    const float df = x[t] - y[t];
+                    acc[u] += df * df;
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < ROUTE_TOPK_BATCH; ++u) {
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) acc[u] += __shfl_xor(acc[u], off);
+            const int c = c0 + u;
+            // (the same for the whole wave) past the end, or a topic left out of the search
+            if (c >= K || (retained_only && slot[c] < 0)) continue;
+            const float d = acc[u];
+            // behind its equals; a NaN compares false and never enters
+#pragma unroll
+            for (int m = ROUTE_TOPK_MAX - 1; m >= 0; --m) {
+                const bool lt = d < ld[m];
+                if (m + 1 < ROUTE_TOPK_MAX) {
+                    ld[m + 1] = lt ? ld[m] : ld[m + 1];
+                    li[m + 1] = lt ? li[m] : li[m + 1];
+                }
+                ld[m] = lt ? d : ld[m];
+                li[m] = lt ? c : li[m];
+            }
+        }
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int m = 0; m < ROUTE_TOPK_MAX; ++m)
+            if (m < k) {
+                const int c = li[m];
+                if (cid) cid[i * k + m] = c;
+                if (expert_ids) expert_ids[i * k + m] = c < 0 ? -1 : (slot ? slot[c] : c);
+                if (d2) d2[i * k + m] = ld[m];
+            }
+    }
+}
+
+hipError_t launch_route_topk(const RouteArgs &a, int k, float *d2, hipStream_t stream)
+{
+    if (a.N <= 0) return hipSuccess;
+    if (k < 1 || k > ROUTE_TOPK_MAX) return hipErrorInvalidValue;
+    const int64_t grid = (a.N + 3) / 4;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (a.is_bf16)
+        hipLaunchKernelGGL(route_topk_kernel<true>, dim3((unsigned)grid), dim3(256), 0, stream, (const char *)a.emb,
+                           (const char *)a.cent, a.N, a.K, a.D, k, a.slot, a.retained_only, a.cid, a.expert_ids, d2);
+    else
+        hipLaunchKernelGGL(route_topk_kernel<false>, dim3((unsigned)grid), dim3(256), 0, stream, (const char *)a.emb,
+                           (const char *)a.cent, a.N, a.K, a.D, k, a.slot, a.retained_only, a.cid, a.expert_ids, d2);
+    return hipGetLastError();
+}
+
 // Plain fill: a memset node recorded into a captured graph is unreliable on
 // this platform, a kernel is not.
 __global__ __launch_bounds__(256) void fill_i32_kernel(int *dst, int n, int value)

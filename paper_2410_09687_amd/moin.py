@@ -35,7 +35,7 @@ EXPORTS = [
     "moin_cache_table", "moin_cache_stats", "moin_lora_linear_ranked", "moin_plan_build_ranked",
     "moin_mx_quantize", "moin_lora_linear_mx", "moin_lora_linear_mx_planned",
     "moin_probe_out_len", "moin_probe_mfma_bf16", "moin_probe_read", "moin_set_adapter_activation",
-    "moin_lora_linear_planned_shared",
+    "moin_lora_linear_planned_shared", "moin_route_topk",
 ]
 ACTIVATIONS = {None: 0, "none": 0, "relu": 1, "silu": 2, "gelu": 3}
 CACHE_STATS = ["batches", "seq_hits", "seq_misses", "loads", "evictions", "overflows", "bytes"]
@@ -80,6 +80,7 @@ def load() -> ctypes.CDLL:
     lib.moin_lora_linear_mx_planned.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, i32, i32, c.c_float,
                                                 vp, c.c_int, vp]
     lib.moin_set_adapter_activation.argtypes = [vp, i32]
+    lib.moin_route_topk.argtypes = [vp, vp, vp, i64, i32, i32, c.c_int, vp, c.c_uint32, i32, vp, vp, vp, vp]
     lib.moin_lora_linear_planned_shared.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, c.c_float, vp,
                                                     c.c_int, vp]
     lib.moin_probe_out_len.argtypes = [vp]
@@ -204,6 +205,32 @@ def moin_route(ctx: Context, emb: torch.Tensor, centroids: torch.Tensor,
                           _dev_ptr(cids, "centroid_ids") if (cids is not None and N) else None,
                           _dev_ptr(counts, "counts"), _stream_ptr(stream)), "moin_route")
     return expert_ids, cids, counts
+
+
+def moin_route_topk(ctx: Context, emb: torch.Tensor, centroids: torch.Tensor, k: int,
+                    slot_of_centroid: Optional[torch.Tensor] = None, retained_only: bool = False, stream=None):
+    """The ``k`` (1..8) nearest centroids of every query, nearest first: ``(expert_ids, centroid_ids, dist2)``,
+    each ``[N, k]`` (int32, int32, float32); -1 / inf where fewer than ``k`` centroids took part."""
+    if emb.dim() != 2 or centroids.dim() != 2 or emb.shape[1] != centroids.shape[1]:
+        raise ValueError("emb [N,D] and centroids [K,D] expected")
+    if emb.dtype != centroids.dtype or emb.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("emb/centroids must both be float32 or both bfloat16")
+    if not 1 <= int(k) <= 8:
+        raise ValueError("k must be 1..8")
+    N, D = emb.shape
+    K = centroids.shape[0]
+    dt = MOIN_BF16 if emb.dtype == torch.bfloat16 else MOIN_F32
+    dev = centroids.device
+    eids = torch.empty((N, k), dtype=torch.int32, device=dev)
+    cids = torch.empty((N, k), dtype=torch.int32, device=dev)
+    d2 = torch.empty((N, k), dtype=torch.float32, device=dev)
+    _ck(load().moin_route_topk(ctx._h, _dev_ptr(emb, "emb") if N else None, _dev_ptr(centroids, "centroids"),
+                               N, K, D, dt, _dev_ptr(slot_of_centroid, "slot_of_centroid", torch.int32),
+                               MOIN_ROUTE_RETAINED_ONLY if retained_only else 0, int(k),
+                               _dev_ptr(eids, "expert_ids") if N else None,
+                               _dev_ptr(cids, "centroid_ids") if N else None,
+                               _dev_ptr(d2, "dist2") if N else None, _stream_ptr(stream)), "moin_route_topk")
+    return eids, cids, d2
 
 
 def moin_histogram(ctx: Context, ids: torch.Tensor, K: int, stream=None) -> torch.Tensor:
