@@ -12,6 +12,7 @@ from .oracle import (  # noqa: F401
     lora_linear,
     lora_linear_mx,
     max_threads,
+    merge_adapters,
     mx_dequantize,
     mx_quantize,
     retain_clusters,

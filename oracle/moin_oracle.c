@@ -337,6 +337,55 @@ int moin_oracle_lora_linear(const uint16_t *x, const int32_t *seq_offsets,
     return bad ? ORACLE_EINVAL : ORACLE_OK;
 }
 
+/* ---- merged adapters --------------------------------------------------- */
+
+/* fp32 -> bf16 bits, round to nearest even (finite inputs). */
+static uint16_t f32_to_bf16_rne(float f)
+{
+    union { uint32_t u; float f; } v;
+    v.f = f;
+    uint32_t lsb = (v.u >> 16) & 1u;
+    return (uint16_t)((v.u + 0x7FFFu + lsb) >> 16);
+}
+
+/*
+ * "Future Works", creating new experts on the fly: an adapter that stands for a
+ * weighted set of existing ones, sum_m w_m W_b[e_m] W_a[e_m], written as ONE
+ * adapter of rank n * r by concatenation (exact up to the rounding of the scaled
+ * W_b back to bf16):
+ *     A_out[m * r + j, :] = A[e_m][j, :]
+ *     B_out[:, m * r + j] = bf16(w_m * B[e_m][:, j])    product taken in fp32
+ * for m < n, j < r; an id of -1 contributes zeros; rows of A_out / columns of
+ * B_out from n * r up to r_out are zero.  A_stack [E, r, d_in], B_stack
+ * [E, d_out, r], A_out [r_out, d_in], B_out [d_out, r_out]: bf16 bits.
+ */
+int moin_oracle_merge_adapters(const uint16_t *A_stack, const uint16_t *B_stack, int32_t E,
+                               int32_t r, int32_t d_in, int32_t d_out, const int32_t *ids,
+                               const float *weights, int32_t n, int32_t r_out,
+                               uint16_t *A_out, uint16_t *B_out)
+{
+    if (E <= 0 || r <= 0 || d_in <= 0 || d_out <= 0 || n < 0 || r_out < 0) return ORACLE_EINVAL;
+    if ((int64_t)n * r > r_out) return ORACLE_EINVAL;
+    if (!A_stack || !B_stack || !A_out || !B_out || (n > 0 && (!ids || !weights))) return ORACLE_EINVAL;
+    for (int32_t m = 0; m < n; ++m)
+        if (ids[m] < -1 || ids[m] >= E) return ORACLE_EINVAL;
+    for (size_t q = 0; q < (size_t)r_out * d_in; ++q) A_out[q] = 0;
+    for (size_t q = 0; q < (size_t)d_out * r_out; ++q) B_out[q] = 0;
+    for (int32_t m = 0; m < n; ++m) {
+        const int32_t e = ids[m];
+        if (e < 0) continue;
+        for (int32_t j = 0; j < r; ++j)
+            for (int32_t i = 0; i < d_in; ++i)
+                A_out[((size_t)m * r + j) * d_in + i] = A_stack[((size_t)e * r + j) * d_in + i];
+        for (int32_t o = 0; o < d_out; ++o)
+            for (int32_t j = 0; j < r; ++j) {
+                const float b = (float)bf16_to_f64(B_stack[((size_t)e * d_out + o) * r + j]);
+                B_out[(size_t)o * r_out + (size_t)m * r + j] = f32_to_bf16_rne(weights[m] * b);
+            }
+    }
+    return ORACLE_OK;
+}
+
 /* ---- MX (microscaled) FP8 base operands -------------------------------- */
 
 /* Value of an FP8 E4M3 code (OCP 8-bit floating point specification): 1 sign

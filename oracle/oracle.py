@@ -43,6 +43,8 @@ def _load():
         lib.moin_oracle_slot_map.argtypes = [c.c_void_p, c.c_int64, c.c_void_p, c.c_int32,
                                              c.c_void_p]
         lib.moin_oracle_histogram.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_void_p]
+        lib.moin_oracle_merge_adapters.argtypes = [c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_int32,
+                                                   c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p]
         lib.moin_oracle_route_topk.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_int,
                                                c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p]
         lib.moin_oracle_lora_linear.argtypes = [
@@ -276,6 +278,30 @@ def lora_linear(x, seq_offsets, expert_ids, W, A_stack, B_stack, scale, rows=Non
         _ptr(B_stack), E, d_in, d_out, r, float(scale), _ptr(ranks), _activation_code(activation),
         _ptr(rows_arr), n_rows, _ptr(y), _ptr(work), slots), "lora_linear")
     return y
+
+
+def merge_adapters(A_stack, B_stack, ids, weights, r_out):
+    """One adapter of rank ``len(ids) * r`` (zero-padded to ``r_out``) that stands for
+    ``sum_m weights[m] * B[ids[m]] @ A[ids[m]]`` ("Future Works", creating new experts on the fly):
+    returns ``(A_out [r_out, d_in], B_out [d_out, r_out])`` as bf16 bit patterns."""
+    A_stack = np.ascontiguousarray(A_stack)
+    B_stack = np.ascontiguousarray(B_stack)
+    if A_stack.dtype != np.uint16 or B_stack.dtype != np.uint16 or A_stack.ndim != 3 or B_stack.ndim != 3:
+        raise TypeError("A_stack [E,r,d_in] / B_stack [E,d_out,r]: uint16 (bf16 bits) expected")
+    E, r, d_in = A_stack.shape
+    d_out = B_stack.shape[1]
+    if B_stack.shape != (E, d_out, r):
+        raise ValueError("A_stack [E,r,d_in] / B_stack [E,d_out,r] shape mismatch")
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    weights = np.ascontiguousarray(weights, dtype=np.float32)
+    if ids.shape != weights.shape or ids.ndim != 1:
+        raise ValueError("ids and weights: one entry per merged adapter")
+    A_out = np.zeros((int(r_out), d_in), dtype=np.uint16)
+    B_out = np.zeros((d_out, int(r_out)), dtype=np.uint16)
+    _check(_load().moin_oracle_merge_adapters(_ptr(A_stack), _ptr(B_stack), E, r, d_in, d_out, _ptr(ids),
+                                              _ptr(weights), ids.size, int(r_out), _ptr(A_out), _ptr(B_out)),
+           "merge_adapters")
+    return A_out, B_out
 
 
 MX_BLOCK = 32
