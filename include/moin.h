@@ -368,6 +368,27 @@ int moin_route_topk(moin_ctx *ctx, const void *emb, const void *centroids, int64
                     uint32_t flags, int32_t k, int32_t *expert_ids, int32_t *centroid_ids,
                     float *dist2, void *stream);
 
+/* "Future Works", creating new experts on the fly (a server that merges existing
+ * adapters for a query that needs several of them): writes ONE adapter of rank
+ * n * r that stands for sum_m weights[m] * W_b[ids[m]] W_a[ids[m]], by concatenation:
+ *     A_out[m r + j, :] = A[ids[m]][j, :]
+ *     B_out[:, m r + j] = bf16(weights[m] * B[ids[m]][:, j])   (fp32 product, nearest even)
+ * for m < n; an id of -1 (as moin_route_topk leaves where a list is short) gives a
+ * block of zeros, and everything from n r up to r_out is zero.
+ *   A_stack [E, r, d_in], B_stack [E, d_out, r]  bf16, device
+ *   ids [n] int32, weights [n] fp32              device (no host read: they may come
+ *                                                straight from moin_route_topk)
+ *   A_out [r_out, d_in], B_out [d_out, r_out]    bf16, device: typically one slot of
+ *                                                stacks of rank r_out, used through
+ *                                                moin_lora_linear_ranked with rank n r
+ * r, r_out, d_in multiples of 8, n r <= r_out, pointers 16-byte aligned; else
+ * MOIN_EINVAL.  An id outside [-1, E) raises the sticky data fault (moin_check)
+ * and gives a block of zeros. */
+int moin_merge_adapters(moin_ctx *ctx, const void *A_stack, const void *B_stack, int32_t E,
+                        int32_t r, int32_t d_in, int32_t d_out, const int32_t *ids,
+                        const float *weights, int32_t n, int32_t r_out, void *A_out, void *B_out,
+                        void *stream);
+
 /* moin_lora_linear_planned for n (1..4) projections of a layer that read the same
  * input x [T, d_in] (q, k, v; gate, up): on the prefill path the adapters' first
  * products u_i = scale * x A_{i,e}^T of all n come out of ONE pass over x, then

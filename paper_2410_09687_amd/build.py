@@ -14,7 +14,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmoin.so")
-SOURCES = ["api.hip", "plan.hip", "linear.hip", "linear_stream.hip", "decode.hip", "route.hip", "kmeans.hip", "cache.hip", "mx.hip", "probe.hip"]
+SOURCES = ["api.hip", "plan.hip", "linear.hip", "linear_stream.hip", "decode.hip", "route.hip", "kmeans.hip", "cache.hip", "mx.hip", "probe.hip", "merge.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -974,6 +974,26 @@ int moin_route_topk(moin_ctx *ctx, const void *emb, const void *centroids, int64
     return MOIN_OK;
 }
 
+int moin_merge_adapters(moin_ctx *ctx, const void *A_stack, const void *B_stack, int32_t E, int32_t r,
+                        int32_t d_in, int32_t d_out, const int32_t *ids, const float *weights, int32_t n,
+                        int32_t r_out, void *A_out, void *B_out, void *stream)
+{
+    if (!ctx || !A_stack || !B_stack || !A_out || !B_out) return MOIN_EINVAL;
+    if (E <= 0 || r <= 0 || d_in <= 0 || d_out <= 0 || n < 0 || r_out <= 0) return MOIN_EINVAL;
+    if (r % 8 || d_in % 8 || r_out % 8 || (int64_t)n * r > r_out) return MOIN_EINVAL;
+    if (n > 0 && (!ids || !weights)) return MOIN_EINVAL;
+    if (misaligned(A_stack, 16) || misaligned(B_stack, 16) || misaligned(A_out, 16) || misaligned(B_out, 16))
+        return MOIN_EINVAL;
+    if ((int64_t)r_out * d_in > 0x7fffffffLL * 8 || (int64_t)d_out * r_out > 0x7fffffffLL * 8) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (launch_merge_adapters(A_stack, B_stack, E, r, d_in, d_out, ids, weights, n, r_out, A_out, B_out,
+                              ctx->err_word, st) != hipSuccess)
+        return MOIN_EHIP;
+    return MOIN_OK;
+}
+
 int moin_set_adapter_activation(moin_ctx *ctx, int32_t activation)
 {
     if (!ctx || activation < MOIN_ACT_NONE || activation > MOIN_ACT_GELU) return MOIN_EINVAL;

@@ -190,6 +190,11 @@ int compute_units();   // of the current device
 
 hipError_t prepare_kernels();  // one-time attribute set-up (large dynamic LDS)
 
+// merged adapter (merge.hip): see moin_merge_adapters
+hipError_t launch_merge_adapters(const void *A_stack, const void *B_stack, int E, int r, int d_in, int d_out,
+                                 const int *ids, const float *weights, int n, int r_out, void *A_out, void *B_out,
+                                 int *err_word, hipStream_t stream);
+
 // on-box ceilings (probe.hip): out holds probe_out_len() elements
 int64_t probe_out_len();
 hipError_t launch_probe_mfma(const void *operands, int64_t n_bytes, int iters, float *out, double *flops,

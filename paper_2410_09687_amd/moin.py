@@ -35,7 +35,7 @@ EXPORTS = [
     "moin_cache_table", "moin_cache_stats", "moin_lora_linear_ranked", "moin_plan_build_ranked",
     "moin_mx_quantize", "moin_lora_linear_mx", "moin_lora_linear_mx_planned",
     "moin_probe_out_len", "moin_probe_mfma_bf16", "moin_probe_read", "moin_set_adapter_activation",
-    "moin_lora_linear_planned_shared", "moin_route_topk",
+    "moin_lora_linear_planned_shared", "moin_route_topk", "moin_merge_adapters",
 ]
 ACTIVATIONS = {None: 0, "none": 0, "relu": 1, "silu": 2, "gelu": 3}
 CACHE_STATS = ["batches", "seq_hits", "seq_misses", "loads", "evictions", "overflows", "bytes"]
@@ -80,6 +80,7 @@ def load() -> ctypes.CDLL:
     lib.moin_lora_linear_mx_planned.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, i32, i32, i32, c.c_float,
                                                 vp, c.c_int, vp]
     lib.moin_set_adapter_activation.argtypes = [vp, i32]
+    lib.moin_merge_adapters.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, i32, i32, vp, vp, vp]
     lib.moin_route_topk.argtypes = [vp, vp, vp, i64, i32, i32, c.c_int, vp, c.c_uint32, i32, vp, vp, vp, vp]
     lib.moin_lora_linear_planned_shared.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, c.c_float, vp,
                                                     c.c_int, vp]
@@ -231,6 +232,29 @@ def moin_route_topk(ctx: Context, emb: torch.Tensor, centroids: torch.Tensor, k:
                                _dev_ptr(cids, "centroid_ids") if N else None,
                                _dev_ptr(d2, "dist2") if N else None, _stream_ptr(stream)), "moin_route_topk")
     return eids, cids, d2
+
+
+def moin_merge_adapters(ctx: Context, A_stack: torch.Tensor, B_stack: torch.Tensor, ids: torch.Tensor,
+                        weights: torch.Tensor, A_out: torch.Tensor, B_out: torch.Tensor, stream=None):
+    """Writes into ``A_out [r_out, d_in]`` / ``B_out [d_out, r_out]`` (e.g. one slot of wider stacks) the adapter
+    of rank ``len(ids) * r`` that stands for ``sum_m weights[m] * B[ids[m]] @ A[ids[m]]``; ``ids`` (int32) and
+    ``weights`` (float32) live on the device."""
+    E, r, d_in = A_stack.shape
+    d_out = B_stack.shape[1]
+    if tuple(B_stack.shape) != (E, d_out, r):
+        raise ValueError("A_stack [E,r,d_in] / B_stack [E,d_out,r] shape mismatch")
+    n = ids.numel()
+    if weights.numel() != n:
+        raise ValueError("one weight per id expected")
+    r_out = A_out.shape[0]
+    if tuple(A_out.shape) != (r_out, d_in) or tuple(B_out.shape) != (d_out, r_out):
+        raise ValueError("A_out [r_out,d_in] / B_out [d_out,r_out] expected")
+    bf = torch.bfloat16
+    _ck(load().moin_merge_adapters(ctx._h, _dev_ptr(A_stack, "A_stack", bf), _dev_ptr(B_stack, "B_stack", bf), E, r,
+                                   d_in, d_out, _dev_ptr(ids, "ids", torch.int32),
+                                   _dev_ptr(weights, "weights", torch.float32), n, r_out,
+                                   _dev_ptr(A_out, "A_out", bf), _dev_ptr(B_out, "B_out", bf), _stream_ptr(stream)),
+        "moin_merge_adapters")
 
 
 def moin_histogram(ctx: Context, ids: torch.Tensor, K: int, stream=None) -> torch.Tensor:
