@@ -755,6 +755,8 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const char *__restrict_
             // (the same for the whole wave) past the end, or a topic left out of the search
             if (c >= K || (retained_only && slot[c] < 0)) continue;
             const float d = acc[u];
+            // (every lane holds the same list: the test is the same for the whole wave)
+            if (!(d < ld[ROUTE_TOPK_MAX - 1])) continue;
             // behind its equals; a NaN compares false and never enters
 #pragma unroll
             for (int m = ROUTE_TOPK_MAX - 1; m >= 0; --m) {
