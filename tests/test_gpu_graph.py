@@ -74,6 +74,14 @@ def test_prefill_call_replays_from_a_graph():
         ctx, x, inp.seq_offsets, e, inp.W, inp.A_stack, inp.B_stack, 2.0, out=out))
 
 
+def test_gathered_batch_call_replays_from_a_graph():
+    # more than 1024 tokens in single-token sequences: token grouping, plain-tile base product, gather kernels
+    inp = _inputs("graph_gather", 256, 264, 64, 30, [1] * 1500, seed=74)
+    ctx = gc.ctx()
+    _replay_check("gathered", inp, lambda x, e, out: moin.moin_lora_linear(
+        ctx, x, inp.seq_offsets, e, inp.W, inp.A_stack, inp.B_stack, 2.0, out=out))
+
+
 def test_quantised_base_call_replays_from_a_graph():
     rng = np.random.default_rng(73)
     inp = _inputs("graph_mx", 256, 264, 64, 6, rng.integers(1, 400, size=12).tolist(), seed=73, dist="uniform")
