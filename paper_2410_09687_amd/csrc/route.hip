@@ -677,8 +677,8 @@ __global__ __launch_bounds__(1024) void histogram_kernel(const int *ids, int64_t
 // The k nearest centroids of every query ("Future Works", creating new experts on the
 // fly: a query on the boundary of several clusters may need several adapters).  A
 // request-time call, not the bulk router: one wave per query, the squared distance
-// written out as the sum of squared differences in fp32 (lanes split the dimension,
-// butterfly sum: every lane ends with the same bits), centroids visited in index
+// written out as the sum of squared differences in fp32 (lanes split the dimension; the
+// cross-lane sum ends in a uniform value, so every lane sees the same bits), centroids visited in index
 // order and inserted behind their equals, so equal distances keep index order.
 // Every lane carries the same list of ROUTE_TOPK_MAX entries in registers.
 constexpr int ROUTE_TOPK_MAX = 8;
@@ -747,10 +747,35 @@ __global__ __launch_bounds__(256) void route_topk_kernel(const char *__restrict_
                 }
             }
         }
+        // The eight sums over the wave in 10 exchanges instead of 48: at distance 32 a lane hands
+        // over the four partial sums its half does not keep, at 16 two, at 8 one; then three plain
+        // butterfly steps.  Lane l ends with the sum of centroid 4 (l / 32) + 2 (l / 16 % 2) + l / 8 % 2,
+        // and a uniform read of one lane of each group gives every lane all eight.
+        static_assert(ROUTE_TOPK_BATCH == 8, "the exchange pattern below is written for eight sums");
+        float v4[4], v2[2], v1;
+        {
+            const bool hi = lane & 32;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float keep = hi ? acc[4 + j] : acc[j], give = hi ? acc[j] : acc[4 + j];
+                v4[j] = keep + __shfl_xor(give, 32);
+            }
+            const bool h16 = lane & 16;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float keep = h16 ? v4[2 + j] : v4[j], give = h16 ? v4[j] : v4[2 + j];
+                v2[j] = keep + __shfl_xor(give, 16);
+            }
+            const bool h8 = lane & 8;
+            const float keep = h8 ? v2[1] : v2[0], give = h8 ? v2[0] : v2[1];
+            v1 = keep + __shfl_xor(give, 8);
+#pragma unroll
+            for (int off = 4; off > 0; off >>= 1) v1 += __shfl_xor(v1, off);
+        }
 #pragma unroll
         for (int u = 0; u < ROUTE_TOPK_BATCH; ++u) {
-#pragma unroll
-            for (int off = 32; off > 0; off >>= 1) acc[u] += __shfl_xor(acc[u], off);
+            acc[u] = bits_f32((uint32_t)__builtin_amdgcn_readlane(
+                (int)__builtin_bit_cast(uint32_t, v1), ((u >> 2) & 1) * 32 + ((u >> 1) & 1) * 16 + (u & 1) * 8));
             const int c = c0 + u;
             // (the same for the whole wave) past the end, or a topic left out of the search
             if (c >= K || (retained_only && slot[c] < 0)) continue;
