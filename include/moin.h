@@ -52,9 +52,11 @@ typedef enum {
 /* Which kernel a timing slot refers to (moin_timing_*). */
 typedef enum {
     MOIN_K_PLAN = 0,
-    MOIN_K_SHRINK = 1,        /* prefill: u = s * x A_e^T                       */
-    MOIN_K_LINEAR = 2,        /* prefill: y = x W^T + u B_e^T (base + expand)   */
-    MOIN_K_ROUTE = 3,         /* distance GEMM fused with argmin                */
+    MOIN_K_SHRINK = 1,        /* prefill: u = s * x A_e^T (on a quantised base it
+                                 may write x in MXFP8 in the same pass)        */
+    MOIN_K_LINEAR = 2,        /* prefill: y = x W^T + u B_e^T (base + expand); the
+                                 base product of gathered batches of short sequences */
+    MOIN_K_ROUTE = 3,         /* distance GEMM fused with argmin; moin_route_topk  */
     MOIN_K_ROUTE_AUX = 4,     /* centroid norms, histogram, slot map            */
     MOIN_K_DECODE_SHRINK = 5, /* decode: gather-matvec u = s * A_e x; also holds
                                  the base GEMM when both share one launch       */
