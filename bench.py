@@ -8,10 +8,13 @@ histogram and slot map), group the batch by expert, then the routed LoRA
 linear layer.  Inputs are resident in HBM before the timed region starts.
 
 Prints ONE JSON line: whole-path TFLOP/s (`value`), the roofline of the
-dominant kernel measured with HIP events on the launch stream, and the CPU
-oracle timed on a bounded sample of the same workload.  `--also` adds the
-decode (GB/s), router (queries/s), full-layer and K-means-update workloads as
-extra objects.
+dominant kernel measured with HIP events on the launch stream, what the box
+itself sustains (an MFMA-only loop and a streaming read, beside the datasheet
+peaks), and the CPU oracle timed on a bounded sample of the same workload.
+`--also` adds further workloads as extra objects: decode (GB/s), router
+(queries/s, and the four nearest topics of a request-sized batch), the full
+layer, the K-means update, the quantised base (step, layer, decode), an
+activation inside the adapters, and one expert per token.
 """
 from __future__ import annotations
 
