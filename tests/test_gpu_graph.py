@@ -116,3 +116,37 @@ def test_quantised_base_call_replays_from_a_graph():
         call(y_eager)
         ctx.check()
         assert torch.equal(y_graph.view(torch.int16), y_eager.view(torch.int16)), f"mx replay {rep}"
+
+
+def test_two_contexts_on_two_streams_do_not_disturb_each_other():
+    # a context owns its workspace and serves one stream at a time: two of them, each on its own stream,
+    # with their calls interleaved, give what each gives alone
+    a = _inputs("two_ctx_a", 256, 264, 64, 6, [300, 500, 700], seed=75, dist="uniform")
+    b = _inputs("two_ctx_b", 384, 136, 128, 9, [1] * 400, seed=76)
+    c0 = gc.ctx()
+    want_a = moin.moin_lora_linear(c0, a.x, a.seq_offsets, a.expert_ids, a.W, a.A_stack, a.B_stack, 2.0)
+    want_b = moin.moin_lora_linear(c0, b.x, b.seq_offsets, b.expert_ids, b.W, b.A_stack, b.B_stack, 2.0)
+    c0.check()
+    c1, c2 = moin.Context(0), moin.Context(0)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    try:
+        for rep in range(4):
+            print(f"[gpu] two contexts, round {rep}", flush=True)
+            with torch.cuda.stream(s1):
+                ya = moin.moin_lora_linear(c1, a.x, a.seq_offsets, a.expert_ids, a.W, a.A_stack, a.B_stack, 2.0)
+            with torch.cuda.stream(s2):
+                yb = moin.moin_lora_linear(c2, b.x, b.seq_offsets, b.expert_ids, b.W, b.A_stack, b.B_stack, 2.0)
+            with torch.cuda.stream(s1):
+                ya2 = moin.moin_lora_linear(c1, a.x, a.seq_offsets, a.expert_ids, a.W, a.A_stack, a.B_stack, 2.0)
+            s1.synchronize()
+            s2.synchronize()
+            assert torch.equal(ya, want_a) and torch.equal(ya2, want_a) and torch.equal(yb, want_b)
+        with torch.cuda.stream(s1):
+            c1.check()
+        with torch.cuda.stream(s2):
+            c2.check()
+    finally:
+        torch.cuda.synchronize()
+        c1.close()
+        c2.close()
