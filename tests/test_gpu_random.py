@@ -109,3 +109,58 @@ def test_random_cases_quantised_base(block):
             gc.compare_linear(y, ref, what=what)
     finally:
         ctx.set_adapter_activation(None)
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_random_router_cases(block):
+    """moin_route over random sizes, both storage types, slot maps and retained-only searches: ids against the
+    oracle (a different id only inside the near-tie band), the histogram = the tally of the ids returned."""
+    ctx = gc.ctx()
+    rng = np.random.default_rng(9700 + block)
+    for i in range(10):
+        bf16 = bool(rng.random() < 0.6)
+        N = int(rng.choice([1, 7, 64, 65, 300, 1025, 4097, 9000]))
+        K = int(rng.choice([1, 2, 63, 64, 65, 257, 500, 1030]))
+        D = int(rng.choice([8, 64, 72, 128, 264, 768]) if bf16 else rng.choice([4, 36, 64, 260]))
+        normalise = bool(rng.random() < 0.5)
+        use_slot = rng.random() < 0.5
+        retained = bool(use_slot and rng.random() < 0.5)
+        what = f"router block {block} case {i}: N={N} K={K} D={D} {'bf16' if bf16 else 'f32'} slot={use_slot} retained_only={retained}"
+        print("[gpu] random " + what, flush=True)
+        rw = wl.RouteWorkload("rnd_route", N=N, K=K, D=D, dtype="bf16" if bf16 else "f32", normalise=normalise,
+                              seed=int(rng.integers(1 << 30)))
+        rin = wl.make_route_inputs(rw, "cuda")
+        slot = None
+        eligible = None
+        if use_slot:
+            sl = rng.integers(-1, 5, size=K).astype(np.int32)
+            if retained and (sl < 0).all():
+                sl[int(rng.integers(0, K))] = 3
+            slot = torch.from_numpy(sl).cuda()
+            eligible = (sl >= 0) if retained else None
+        eids, cids, counts = moin.moin_route(ctx, rin.emb, rin.centroids, slot_of_centroid=slot,
+                                             retained_only=retained, want_counts=True)
+        ctx.check()
+        gc.check_route(rin.emb, rin.centroids, cids, eligible=eligible)
+        c = cids.cpu().numpy()
+        assert np.array_equal(counts.cpu().numpy(), np.bincount(c, minlength=K))
+        want_e = c if slot is None else slot.cpu().numpy()[c]
+        assert np.array_equal(eids.cpu().numpy(), want_e)
+
+
+@pytest.mark.parametrize("block", range(2))
+def test_random_kmeans_update_cases(block):
+    from tests.test_gpu_kmeans import _check_update, _inputs
+    rng = np.random.default_rng(9800 + block)
+    for i in range(8):
+        bf16 = bool(rng.random() < 0.5)
+        N = int(rng.choice([1, 50, 1000, 5000, 70000]))
+        K = int(rng.choice([1, 3, 64, 500, 2000]))
+        D = int(rng.choice([8, 64, 136, 768]) if bf16 else rng.choice([4, 36, 64, 260]))
+        # skewed assignment with empty clusters: ids drawn from a few of the centres only
+        pool = rng.choice(K, size=max(1, K // int(rng.choice([1, 2, 10]))), replace=False)
+        ids = pool[rng.integers(0, len(pool), size=N)]
+        what = f"kmeans block {block} case {i}: N={N} K={K} D={D} {'bf16' if bf16 else 'f32'}"
+        print("[gpu] random " + what, flush=True)
+        emb, ids_t, cent = _inputs(N, K, D, torch.bfloat16 if bf16 else torch.float32, int(rng.integers(1 << 30)), ids)
+        _check_update(emb, ids_t, cent, what)
