@@ -229,3 +229,27 @@ def test_adaptive_rank_per_expert():
     assert np.array_equal(base, oracle.lora_linear(x, off, ids, W, A, B, 2.0, rank_of_expert=np.zeros(E, np.int32)))
     with pytest.raises(ValueError):
         oracle.lora_linear(x, off, ids, W, A, B, 2.0, rank_of_expert=np.array([9, 0, 0, 0]))
+
+
+def test_general_case_against_numpy_matrices():
+    """Several experts, base-only and empty sequences, per-expert ranks, a row subset: the layer written
+    sequence by sequence with numpy fp64 matrix products."""
+    rng = np.random.default_rng(77)
+    lens = [5, 0, 9, 3, 1, 7]
+    x, W, A, B, off, _ = _rand_case(rng, lens, 40, 24, 16, 4)
+    ids = np.array([2, 1, -1, 0, 3, 2], dtype=np.int32)
+    ranks = np.array([16, 8, 0, 5], dtype=np.int32)
+    s = 2.0
+    xd, Wd, Ad, Bd = bits_to_f64(x), bits_to_f64(W), bits_to_f64(A), bits_to_f64(B)
+    for rk in (None, ranks):
+        ref = xd @ Wd.T
+        for q, e in enumerate(ids):
+            if e < 0:
+                continue
+            k = 16 if rk is None else int(rk[e])
+            rows = slice(off[q], off[q + 1])
+            ref[rows] += s * (xd[rows] @ Ad[e, :k].T) @ Bd[e][:, :k].T
+        y = oracle.lora_linear(x, off, ids, W, A, B, s, rank_of_expert=rk)
+        assert np.allclose(y, ref, rtol=1e-12, atol=1e-12)
+        sub = np.array([24, 0, 13, 14, 5], dtype=np.int64)
+        assert np.array_equal(oracle.lora_linear(x, off, ids, W, A, B, s, rank_of_expert=rk, rows=sub), y[sub])
