@@ -211,3 +211,51 @@ def test_router_addresses_beyond_4_gib():
     assert not (err > tol).any(), f"{int((err > tol).sum())} entries beyond the bound, worst {err.max():.3e}"
     del rin
     torch.cuda.empty_cache()
+
+
+def test_per_token_adapters_full_size():
+    # the workload `bench.py --also pertoken` times: 8192 single-token sequences through the 2048 -> 5632
+    # projection, r = 128, 5000 experts, Zipf(1.1); sampled tokens against the oracle
+    w0 = wl.config_decode()[0]
+    T = 8192
+    w = wl.LinearWorkload("per_token_gate", w0.d_in, w0.d_out, w0.r, w0.E, [1] * T, "zipf", 1.1, w0.scale,
+                          seed=w0.seed + 77)
+    inp = wl.make_linear_inputs(w, "cuda")
+    rows = _sample_rows(T, inp.seq_offsets, 150, seed=7)
+    # the oracle on a batch of just those tokens (one sequence each) with the experts they use
+    sel = torch.from_numpy(rows).cuda()
+    sub = wl.LinearInputs(wl.LinearWorkload("sub", w.d_in, w.d_out, w.r, w.E, [1] * len(rows), "zipf", 1.1, w.scale),
+                          inp.x[sel].contiguous(), inp.W, inp.A_stack, inp.B_stack,
+                          torch.arange(len(rows) + 1, dtype=torch.int32, device="cuda"),
+                          inp.expert_ids[sel].contiguous())
+    ref = gc.oracle_rows(sub)
+    for dt in (torch.bfloat16, torch.float32):
+        print(f"[gpu] per-token full size y={dt}", flush=True)
+        y = gc.run_linear(inp, dt)
+        print(gc.compare_linear(y[sel], ref, what=f"per-token/{dt}"), flush=True)
+        assert torch.isfinite(y.float()).all()
+    del inp, sub
+    torch.cuda.empty_cache()
+
+
+def test_nearest_topics_at_request_size():
+    # what bench.py reports beside the router: the four nearest of 5000 topics for 4096 queries (D = 768, bf16);
+    # every 16th query against the oracle, place by place
+    import oracle
+    rw = wl.RouteWorkload("topk_request", N=4096, K=5000, D=768, dtype="bf16", normalise=True, seed=4321)
+    rin = wl.make_route_inputs(rw, "cuda")
+    print("[gpu] top-4 of 5000 topics, 4096 queries", flush=True)
+    _, cids, d2 = moin.moin_route_topk(gc.ctx(), rin.emb, rin.centroids, 4)
+    gc.ctx().check()
+    sample = np.arange(0, rw.N, 16)
+    emb_h, cent_h = wl.bf16_bits(rin.emb[torch.from_numpy(sample).cuda()]), wl.bf16_bits(rin.centroids)
+    ref_ids, ref_d2 = oracle.route_topk(emb_h, cent_h, 4)
+    got = cids.cpu().numpy()[sample]
+    n_band = 0
+    for i, m in zip(*np.nonzero(got != ref_ids)):
+        true_d = oracle.dist2(emb_h, cent_h, np.array([i]), np.array([got[i, m]]))[0]
+        assert true_d <= ref_d2[i, m] * (1 + 1e-4), (i, m, got[i], ref_ids[i])
+        n_band += 1
+    assert np.allclose(d2.double().cpu().numpy()[sample], oracle.dist2(
+        emb_h, cent_h, np.repeat(np.arange(len(sample)), 4), got.ravel()).reshape(-1, 4), rtol=2e-5)
+    print(f"[gpu] {len(sample)} sampled queries, {n_band} places inside the near-tie band", flush=True)
