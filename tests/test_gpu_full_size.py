@@ -123,6 +123,67 @@ def test_layer_chain_full_size():
     plan.close()
 
 
+def test_layer_chain_on_a_quantised_base_full_size():
+    """The same chain with every projection's weight in MXFP8, as `bench.py --also mx` runs it: the first
+    projection that reads an input quantises it into the caller's buffers (inside its shrink's pass), the
+    others read those codes; each projection against the oracle on the GPU's actual input, and the shared-input
+    call for q, k, v on the bf16 base against its single calls."""
+    import oracle
+    wls = wl.config_layer()
+    T = wls[0].T
+    ids = wl.draw_expert_ids(wls[0].S, wls[0].E, "zipf", 1.5, wls[0].seed * 8 + 4)
+    c = gc.ctx()
+    off = torch.from_numpy(wl.seq_offsets_of(wls[0].seq_lens)).cuda()
+    eids = torch.from_numpy(ids).cuda()
+    plan = moin.Plan(c).build(off, eids, T, wls[0].E)
+    h0 = wl._randn_bf16((T, 2048), 1.0, torch.device("cuda"), 4242)
+    outs = {"h0": h0}
+    src = {"q": "h0", "k": "h0", "v": "h0", "o": "q", "gate": "o", "up": "o", "down": "gate"}
+    codes = {}
+    rows = _sample_rows(T, off, 24, seed=9)
+    qkv = {}
+    for w in wls:
+        name = w.name.split("_", 1)[1]
+        x = outs[src[name]]
+        inp = wl.make_linear_inputs(w, "cuda", expert_ids=ids, x=x)
+        Wq, Ws = moin.moin_mx_quantize(c, inp.W, blocked=True)
+        first = src[name] not in codes
+        if first:
+            codes[src[name]] = (torch.empty((T, w.d_in), dtype=torch.uint8, device="cuda"),
+                                torch.empty((w.d_in // 128, T, 4), dtype=torch.uint8, device="cuda"))
+        xq, xs = codes[src[name]]
+        print(f"[gpu] c4 mx {name} {w.d_in}->{w.d_out} emit={first}", flush=True)
+        y = moin.moin_lora_linear_mx_planned(c, plan, x, Wq, Ws, inp.A_stack, inp.B_stack, w.scale, xq=xq, xs=xs,
+                                             emit=first)
+        c.check()
+        A, B, cid = wl.compact_stacks(inp)
+        Ws_rows = Ws.permute(1, 0, 2).reshape(w.d_out, w.d_in // 32).cpu().numpy()
+        ref = oracle.lora_linear_mx(wl.bf16_bits(x), off.cpu().numpy(), cid, Wq.cpu().numpy(), Ws_rows, A, B, w.scale,
+                                    rows=rows)
+        print(name, gc.compare_linear(y, ref, rows, what=f"c4 mx/{name}"), flush=True)
+        if first:
+            # the codes the shrink's pass wrote are the quantiser's, bit for bit, on the sampled rows
+            oc, osc = oracle.mx_quantize(wl.bf16_bits(x[torch.from_numpy(rows).cuda()]))
+            xs_rows = xs.permute(1, 0, 2).reshape(T, w.d_in // 32)
+            assert np.array_equal(xq.cpu().numpy()[rows], oc) and np.array_equal(xs_rows.cpu().numpy()[rows], osc)
+        if name in ("q", "o", "gate"):
+            outs[name] = y
+        if name in ("q", "k", "v"):
+            qkv[name] = inp
+        else:
+            del inp
+        torch.cuda.empty_cache()
+    print("[gpu] c4 q, k, v through the shared-input call", flush=True)
+    ins = [qkv[n] for n in ("q", "k", "v")]
+    single = [moin.moin_lora_linear_planned(c, plan, h0, i.W, i.A_stack, i.B_stack, i.wl.scale) for i in ins]
+    shared = moin.moin_lora_linear_planned_shared(c, plan, h0, [i.W for i in ins], [i.A_stack for i in ins],
+                                                  [i.B_stack for i in ins], ins[0].wl.scale)
+    c.check()
+    for a, b in zip(single, shared):
+        assert torch.equal(a, b)
+    plan.close()
+
+
 def test_kmeans_update_full_size():
     """One centre update at the router workload's size (1 048 576 x 768 bf16,
     5000 centres), ids from the GPU router: every centre against the oracle,
