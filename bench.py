@@ -127,9 +127,21 @@ def bench_ceilings(ctx):
     run()
     kt = kernel_times(ctx, run, 3)
     ctx.check()
+    # the block-scaled FP8 instruction on the codes of the same N(0,1) values
+    codes, _ = moin.moin_mx_quantize(ctx, ops.view(-1, 128))
+    fl8 = [0.0]
+
+    def run8():
+        fl8[0] = moin.moin_probe_mfma_mxfp8(ctx, codes.view(-1), iters)[1]
+
+    run8()
+    kt8 = kernel_times(ctx, run8, 3)
+    ctx.check()
     return {"mfma_bf16_TFLOPs": flops[0] / (kt["probe_mfma"]["avg_ms"] * 1e-3) / 1e12,
+            "mfma_mxfp8_TFLOPs": fl8[0] / (kt8["probe_mfma"]["avg_ms"] * 1e-3) / 1e12,
             "read_GBps": buf.numel() * 4.0 / (kt["probe_read"]["avg_ms"] * 1e-3) / 1e9,
-            "what": "MFMA-only loop (v_mfma_f32_32x32x16_bf16, N(0,1) operands, 2 workgroups of 8 waves per "
+            "what": "MFMA-only loops (v_mfma_f32_32x32x16_bf16 on N(0,1) operands; "
+                    "v_mfma_scale_f32_32x32x64_f8f6f4 on their MXFP8 codes; 2 workgroups of 8 waves per "
                     "compute unit); streaming read of 1 GiB (16-byte loads, 8 in flight per thread)"}
 
 
@@ -669,6 +681,9 @@ def main():
         res["ranks"] = bench_ranks(ctx, args.steps, args.warmup)
     if "mx" in extra or "mx-step" in extra:
         res["mx"] = bench_mx(ctx, args.steps, args.warmup)
+        if "measured_ceilings" in res:
+            res["mx"]["roofline"]["frac_of_measured_mfma_ceiling"] = \
+                res["mx"]["roofline"]["achieved"] / c["mfma_mxfp8_TFLOPs"]
     if "mx" in extra:
         res["mx"]["layer"] = bench_layer_mx(ctx, max(5, args.steps // 5), 2)
         res["mx"]["decode_gate"] = bench_decode_mx(ctx, args.steps, args.warmup)

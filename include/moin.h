@@ -429,6 +429,10 @@ int moin_set_adapter_activation(moin_ctx *ctx, int32_t activation);
  *   matrix cores reach their power limit sooner on random data than on constants);
  *   out[i] (device, fp32) = sum of thread i's accumulators; *flops (host, may be
  *   NULL) = the flops of the launch.
+ * moin_probe_mfma_mxfp8: the same for the block-scaled FP8 instruction of the
+ *   quantised-base kernel: `iters` times 8 independent
+ *   v_mfma_scale_f32_32x32x64_f8f6f4 per wave on FP8 E4M3 codes taken from `codes`,
+ *   all block scales 1.
  * moin_probe_read: reads src (device, n_bytes a multiple of 16) once, eight 16-byte
  *   loads per thread in flight; out[i] (device) = sum mod 2^32 of the 32-bit words
  *   thread i read.
@@ -437,6 +441,8 @@ int moin_set_adapter_activation(moin_ctx *ctx, int32_t activation);
 int64_t moin_probe_out_len(moin_ctx *ctx);
 int moin_probe_mfma_bf16(moin_ctx *ctx, const void *operands, int64_t n_bytes, int32_t iters,
                          float *out, double *flops, void *stream);
+int moin_probe_mfma_mxfp8(moin_ctx *ctx, const void *codes, int64_t n_bytes, int32_t iters,
+                          float *out, double *flops, void *stream);
 int moin_probe_read(moin_ctx *ctx, const void *src, int64_t n_bytes, uint32_t *out, void *stream);
 
 #ifdef __cplusplus

@@ -1025,6 +1025,22 @@ int moin_probe_mfma_bf16(moin_ctx *ctx, const void *operands, int64_t n_bytes, i
     return MOIN_OK;
 }
 
+int moin_probe_mfma_mxfp8(moin_ctx *ctx, const void *codes, int64_t n_bytes, int32_t iters, float *out,
+                          double *flops, void *stream)
+{
+    if (!ctx || !codes || !out || n_bytes < 16 || n_bytes % 16 || iters < 0 || misaligned(codes, 16))
+        return MOIN_EINVAL;
+    if (n_bytes / 16 > 0x7fffffffLL) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (timed(ctx, MOIN_K_PROBE_MFMA, st, [&] {
+            return launch_probe_mfma_mx(codes, n_bytes, iters, out, flops, st);
+        }) != hipSuccess)
+        return MOIN_EHIP;
+    return MOIN_OK;
+}
+
 int moin_probe_read(moin_ctx *ctx, const void *src, int64_t n_bytes, uint32_t *out, void *stream)
 {
     if (!ctx || !src || !out || n_bytes < 0 || n_bytes % 16 || misaligned(src, 16)) return MOIN_EINVAL;

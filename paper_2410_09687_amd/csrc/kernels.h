@@ -199,6 +199,8 @@ hipError_t launch_merge_adapters(const void *A_stack, const void *B_stack, int E
 int64_t probe_out_len();
 hipError_t launch_probe_mfma(const void *operands, int64_t n_bytes, int iters, float *out, double *flops,
                              hipStream_t stream);
+hipError_t launch_probe_mfma_mx(const void *codes, int64_t n_bytes, int iters, float *out, double *flops,
+                                hipStream_t stream);
 hipError_t launch_probe_read(const void *src, int64_t n_bytes, uint32_t *out, hipStream_t stream);
 
 }  // namespace moin

@@ -46,6 +46,41 @@ __global__ __launch_bounds__(PROBE_BLOCK) void probe_mfma_kernel(const uint4 *__
     out[tid] = s;
 }
 
+// The same for the block-scaled FP8 instruction of the quantised-base kernel: per
+// iteration and wave eight independent v_mfma_scale_f32_32x32x64_f8f6f4 on operand
+// registers filled from `in` (FP8 E4M3 codes), every block scale 2^0 (byte 127).
+typedef int probe_i32x8_t __attribute__((ext_vector_type(8)));
+__global__ __launch_bounds__(PROBE_BLOCK) void probe_mfma_mx_kernel(const uint4 *__restrict__ in, uint32_t n16,
+                                                                    int iters, float *__restrict__ out)
+{
+    const uint32_t tid = blockIdx.x * PROBE_BLOCK + threadIdx.x;
+    probe_i32x8_t a[2], b[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const uint4 a0 = in[(tid * 8u + 4 * j) % n16], a1 = in[(tid * 8u + 4 * j + 1) % n16];
+        const uint4 b0 = in[(tid * 8u + 4 * j + 2) % n16], b1 = in[(tid * 8u + 4 * j + 3) % n16];
+        a[j] = probe_i32x8_t{(int)a0.x, (int)a0.y, (int)a0.z, (int)a0.w, (int)a1.x, (int)a1.y, (int)a1.z, (int)a1.w};
+        b[j] = probe_i32x8_t{(int)b0.x, (int)b0.y, (int)b0.z, (int)b0.w, (int)b1.x, (int)b1.y, (int)b1.z, (int)b1.w};
+    }
+    f32x16_t acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    const int sc = 0x7F7F7F7F;   // scale bytes: 2^(127 - 127) for both 32-step blocks
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i & 1], b[(i >> 1) & 1], acc[i], 0, 0, 0, sc, 0, sc);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s += acc[i][e];
+    out[tid] = s;
+}
+
 // Every 16-byte word of src once, eight independent loads per thread in flight;
 // out[tid] = sum (mod 2^32) of the 32-bit words the thread read.
 __global__ __launch_bounds__(256) void probe_read_kernel(const uint4 *__restrict__ src, int64_t n16,
@@ -78,6 +113,16 @@ hipError_t launch_probe_mfma(const void *operands, int64_t n_bytes, int iters, f
     if (flops) *flops = (double)grid * (PROBE_BLOCK / 64) * (double)iters * 16.0 * (2.0 * 32 * 32 * 16);
     hipLaunchKernelGGL(probe_mfma_kernel, dim3(grid), dim3(PROBE_BLOCK), 0, stream,
                        reinterpret_cast<const uint4 *>(operands), (uint32_t)(n_bytes / 16), iters, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_mfma_mx(const void *codes, int64_t n_bytes, int iters, float *out, double *flops,
+                                hipStream_t stream)
+{
+    const int grid = compute_units() * PROBE_WG_PER_CU;
+    if (flops) *flops = (double)grid * (PROBE_BLOCK / 64) * (double)iters * 8.0 * (2.0 * 32 * 32 * 64);
+    hipLaunchKernelGGL(probe_mfma_mx_kernel, dim3(grid), dim3(PROBE_BLOCK), 0, stream,
+                       reinterpret_cast<const uint4 *>(codes), (uint32_t)(n_bytes / 16), iters, out);
     return hipGetLastError();
 }
 

@@ -34,7 +34,7 @@ EXPORTS = [
     "moin_cache_create", "moin_cache_destroy", "moin_cache_add_stack", "moin_cache_admit",
     "moin_cache_table", "moin_cache_stats", "moin_lora_linear_ranked", "moin_plan_build_ranked",
     "moin_mx_quantize", "moin_lora_linear_mx", "moin_lora_linear_mx_planned",
-    "moin_probe_out_len", "moin_probe_mfma_bf16", "moin_probe_read", "moin_set_adapter_activation",
+    "moin_probe_out_len", "moin_probe_mfma_bf16", "moin_probe_mfma_mxfp8", "moin_probe_read", "moin_set_adapter_activation",
     "moin_lora_linear_planned_shared", "moin_route_topk", "moin_merge_adapters",
 ]
 ACTIVATIONS = {None: 0, "none": 0, "relu": 1, "silu": 2, "gelu": 3}
@@ -87,6 +87,7 @@ def load() -> ctypes.CDLL:
     lib.moin_probe_out_len.argtypes = [vp]
     lib.moin_probe_out_len.restype = c.c_int64
     lib.moin_probe_mfma_bf16.argtypes = [vp, vp, i64, i32, vp, c.POINTER(c.c_double), vp]
+    lib.moin_probe_mfma_mxfp8.argtypes = [vp, vp, i64, i32, vp, c.POINTER(c.c_double), vp]
     lib.moin_probe_read.argtypes = [vp, vp, i64, vp, vp]
     lib.moin_plan_build_ranked.argtypes = [vp, vp, vp, vp, i32, i64, i32, vp, vp]
     lib.moin_plan_create.argtypes = [vp, c.POINTER(vp)]
@@ -505,6 +506,19 @@ def moin_probe_mfma_bf16(ctx: Context, operands: torch.Tensor, iters: int, strea
     _ck(load().moin_probe_mfma_bf16(ctx._h, _dev_ptr(operands, "operands", torch.bfloat16), operands.numel() * 2,
                                     int(iters), _dev_ptr(out, "out"), ctypes.byref(flops), _stream_ptr(stream)),
         "moin_probe_mfma_bf16")
+    return out, flops.value
+
+
+def moin_probe_mfma_mxfp8(ctx: Context, codes: torch.Tensor, iters: int, stream=None):
+    """Measurement aid: a loop of block-scaled FP8 MFMAs alone on ``codes`` (uint8 E4M3 codes, a multiple of 16
+    bytes), all block scales 1.  Returns (per-thread sums, flops of the launch)."""
+    if codes.dtype != torch.uint8 or codes.numel() % 16 or codes.numel() < 16:
+        raise ValueError("codes: uint8, a multiple of 16 bytes")
+    out = torch.empty(int(load().moin_probe_out_len(ctx._h)), dtype=torch.float32, device=codes.device)
+    flops = ctypes.c_double(0.0)
+    _ck(load().moin_probe_mfma_mxfp8(ctx._h, _dev_ptr(codes, "codes", torch.uint8), codes.numel(), int(iters),
+                                     _dev_ptr(out, "out"), ctypes.byref(flops), _stream_ptr(stream)),
+        "moin_probe_mfma_mxfp8")
     return out, flops.value
 
 

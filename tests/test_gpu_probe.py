@@ -50,6 +50,41 @@ def test_mfma_probe_computes_the_products_it_counts():
         assert np.array_equal(total, iters * want)
 
 
+def test_mxfp8_mfma_probe_computes_the_products_it_counts():
+    ctx = gc.ctx()
+    g = torch.Generator(device="cuda").manual_seed(9)
+    # codes of 0, +-0.5, +-1, +-2: every product and partial sum exact in fp32
+    table = torch.tensor([0x00, 0x30, 0xB0, 0x38, 0xB8, 0x40, 0xC0], dtype=torch.uint8, device="cuda")
+    codes = table[torch.randint(0, 7, (2048 * 16,), device="cuda", generator=g)].contiguous()
+    vals = codes.view(torch.float8_e4m3fn).double().cpu().numpy().reshape(-1, 16)
+    n16 = vals.shape[0]
+    for iters in (1, 2):
+        print(f"[gpu] mxfp8 mfma probe iters={iters}", flush=True)
+        out, flops = moin.moin_probe_mfma_mxfp8(ctx, codes, iters)
+        ctx.check()
+        n_threads = out.numel()
+        n_waves = n_threads // 64
+        assert flops == n_waves * iters * 8 * 2.0 * 32 * 32 * 64
+        t = np.arange(n_threads)
+        total = out.double().cpu().numpy().reshape(n_waves, 64).sum(axis=1)
+
+        def kvec(first):
+            # an operand of a wave: lane l holds bytes [16 h, 16 h + 16) of the first 32-step block (piece
+            # `first`) and of the second (piece `first + 1`), h = l / 32; summed over the 32 rows
+            halves = []
+            for piece in (first, first + 1):
+                p16 = vals[(8 * t + piece) % n16].reshape(n_waves, 2, 32, 16)
+                halves.append(p16.sum(axis=2).reshape(n_waves, 32))
+            return np.concatenate(halves, axis=1)            # [wave, 64 contraction steps]
+
+        ka = [kvec(0), kvec(4)]
+        kb = [kvec(2), kvec(6)]
+        want = np.zeros(n_waves)
+        for i in range(8):
+            want += (ka[i & 1] * kb[(i >> 1) & 1]).sum(axis=1)
+        assert np.array_equal(total, iters * want)
+
+
 def test_probe_rejects_bad_sizes():
     ctx = gc.ctx()
     with pytest.raises(ValueError):
