@@ -59,6 +59,41 @@ def test_queries_equal_centroids_and_duplicates():
     assert counts[17].item() == 2 and counts[400].item() == 0 and counts.sum().item() == 600
 
 
+@pytest.mark.parametrize("K,D,N", [(1280, 768, 8192), (1030, 64, 12000), (5000, 768, 10000)])
+def test_lowest_index_wins_ties_in_the_large_batch_kernel(K, D, N):
+    # More than 4096 queries: the streaming kernel, whose workgroups share a query tile and merge
+    # their winners with a packed atomic minimum.  Every query IS a centroid and a third of the
+    # centroids are copies of an earlier one (some in the same 256-centroid tile, some in another
+    # tile, i.e. held by another workgroup of the group), so each query has two or three exact
+    # minima at distance 0 and only the lowest index is right.  Ids are compared exactly.
+    rin = _route_case(8, K, D, "bf16", True, seed=K + D)
+    cent = rin.centroids.clone()
+    rng = np.random.default_rng(K)
+    src = np.arange(K)
+    third = K // 3
+    src[K - third:] = rng.integers(0, K - third, size=third)      # copies of earlier centroids, far away
+    near = rng.choice(K - third - 8, size=third // 4, replace=False)
+    src[near + 5] = src[near]                                     # copies five places further on
+    cent = cent[torch.from_numpy(src).cuda()].contiguous()
+    qsel = rng.integers(0, K, size=N)
+    qsel[:K] = np.arange(K)
+    emb = cent[torch.from_numpy(qsel).cuda()].contiguous()
+    print(f"[gpu] route ties stream N={N} K={K} D={D}", flush=True)
+    eids, cids, counts = moin.moin_route(gc.ctx(), emb, cent, want_counts=True)
+    gc.ctx().check()
+    ref = oracle.route(wl.bf16_bits(emb), wl.bf16_bits(cent))
+    # the oracle's answer is the first holder of the query's vector
+    first = np.full(K, -1)
+    seen = {}
+    cb = wl.bf16_bits(cent)
+    for k in range(K):
+        first[k] = seen.setdefault(cb[k].tobytes(), k)
+    assert np.array_equal(ref, first[qsel])
+    assert (first != np.arange(K)).sum() >= third
+    assert torch.equal(cids.cpu(), torch.from_numpy(ref.astype(np.int32)))
+    assert torch.equal(counts.long(), torch.bincount(cids.long(), minlength=K))
+
+
 def test_slot_map_and_retained_only_search():
     rin = _route_case(900, 260, 64, "bf16", True, seed=21)
     table = wl.retained_slot_table(260, 231, seed=4)
