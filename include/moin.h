@@ -43,7 +43,9 @@ typedef enum {
     MOIN_EINVAL = -1, /* null pointer, negative size, unsupported shape/alignment */
     MOIN_ENOMEM = -2, /* workspace allocation failed */
     MOIN_EHIP = -3,   /* a HIP runtime call failed */
-    MOIN_EDATA = -4   /* sticky device-side data fault, reported by moin_check */
+    MOIN_EDATA = -4,  /* sticky device-side data fault, reported by moin_check */
+    MOIN_ETOOBIG = -5,  /* size beyond the fixed limit of an entry point that does not allocate */
+    MOIN_ECAPTURE = -6  /* the call would have to grow device memory on a stream under capture */
 } moin_status;
 
 /* moin_route flags */
@@ -153,83 +155,6 @@ int moin_lora_linear(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
                      int32_t E, int32_t d_in, int32_t d_out, int32_t r,
                      float scale, void *y, moin_dtype y_dt, void *stream);
 
-/* "Future Works", adaptive rank per topic (also Section 4.2: the rank could follow
- * the amount of training data): the same layer with a rank per expert.
- * rank_of_expert [E] int32 (DEVICE) or NULL; expert e uses the first
- * rank_of_expert[e] rows of A_stack[e] and columns of B_stack[e], 0 <= rank <= r,
- * a multiple of 8 (rank 0: base model only).  The stacks keep their [E, r, ...]
- * shape.  What lies beyond an expert's rank is not used: rows of A_e beyond it are
- * never read; columns of B_e from the rank up to the next multiple of 64 are
- * multiplied by zeros on the prefill path and must therefore be finite (zero
- * padding is the natural choice), further columns are never read.  The decode
- * path reads only rank_e rows / columns of every distinct adapter.  A rank that
- * is negative or not a multiple of 8 raises the sticky data fault (it is rounded
- * down; negative: full rank); a rank above r counts as r. */
-int moin_lora_linear_ranked(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
-                            const int32_t *expert_ids, int32_t S, int64_t T,
-                            const void *W, const void *A_stack, const void *B_stack,
-                            int32_t E, int32_t d_in, int32_t d_out, int32_t r,
-                            const int32_t *rank_of_expert, float scale, void *y,
-                            moin_dtype y_dt, void *stream);
-
-/* "Future Works", quantising the base model (a QLoRA-like, aggressively quantised
- * base whose loss the experts recover; the paper names the idea only).  The
- * format here is OCP Microscaling MXFP8: along the last axis, blocks of 32
- * consecutive values share one power-of-two scale 2^(E-127) (E8M0 byte E) and
- * hold FP8 E4M3 elements (bias 7, largest finite value 448, no infinities).
- *
- * moin_mx_quantize: src [rows, cols] bf16 (DEVICE, finite values; NaN / Inf give
- * unspecified codes) -> codes [rows, cols] uint8 and rows * cols/32 scale bytes
- * (both DEVICE, caller-owned).  scale_layout: MOIN_MX_ROW_MAJOR, scales
- * [rows, cols/32]; MOIN_MX_BLOCKED (cols a multiple of 128), scales
- * [cols/128, rows, 4] -- the four bytes of 128 consecutive values of a row form
- * one word and the words of consecutive rows are adjacent, which is the order
- * the matrix-core kernel fetches them in.  E = max(0, floor(log2 max|v|) + 127 - 8) per
- * block (127 for a block of zeros); element = v / 2^(E-127) rounded to nearest
- * even, magnitudes above 448 clamped to 448.  cols must be a multiple of 32,
- * src and codes 16-byte aligned.  Used once for the weight. */
-enum { MOIN_MX_ROW_MAJOR = 0, MOIN_MX_BLOCKED = 1 };
-int moin_mx_quantize(moin_ctx *ctx, const void *src, int64_t rows, int64_t cols, void *codes,
-                     void *scales, int32_t scale_layout, void *stream);
-
-/* moin_lora_linear_ranked on a quantised base:
- *     y = dq(q(x)) dq(Wq)^T + scale * (x A_e^T) B_e^T
- * Wq [d_out, d_in] codes and Ws (MOIN_MX_BLOCKED layout: [d_in/128, d_out, 4])
- * come from moin_mx_quantize; x [T, d_in] is bf16 and is quantised by the call itself
- * (into the context's workspace) for the base product, which runs on the
- * block-scaled FP8 matrix cores; the adapter term uses the bf16 x and the bf16
- * stacks exactly as in moin_lora_linear.  rank_of_expert may be NULL.
- * Shapes: d_in a multiple of 128 and at least 256, r a multiple of 64, d_out a
- * multiple of 8; anything else returns MOIN_EINVAL.  Small batches (T <= 1024)
- * and batches of short sequences (T <= 128 S, see moin_lora_linear)
- * compute the base product for all tokens at once on the FP8 matrix cores and
- * add the adapter term with the decode path's gather-matvec kernels. */
-int moin_lora_linear_mx(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
-                        const int32_t *expert_ids, int32_t S, int64_t T,
-                        const void *Wq, const void *Ws, const void *A_stack, const void *B_stack,
-                        int32_t E, int32_t d_in, int32_t d_out, int32_t r,
-                        const int32_t *rank_of_expert, float scale, void *y,
-                        moin_dtype y_dt, void *stream);
-
-/* moin_lora_linear_mx on a plan (moin_plan_build / moin_plan_build_ranked), for the
- * projections of a layer.  xq [T, d_in] / xs (MOIN_MX_BLOCKED layout,
- * [d_in/128, T, 4]) hold the quantised activations (device, 16-byte aligned), so
- * that projections that share their input (q, k, v; gate, up) quantise it once:
- *   MOIN_MX_X_INTERNAL  xq, xs NULL: the call quantises x into the context's workspace;
- *   MOIN_MX_X_EMIT      the call quantises x into xq / xs (the caller's buffers; with
- *                       adapters in a prefill batch that happens inside the shrink's
- *                       pass over x) and uses them;
- *   MOIN_MX_X_GIVEN     xq / xs are read: what an earlier MOIN_MX_X_EMIT call or
- *                       moin_mx_quantize(x, MOIN_MX_BLOCKED) wrote for the same x.
- * x (bf16) is needed in every case, for the adapter term.  A mode that does not
- * fit the pointers returns MOIN_EINVAL. */
-enum { MOIN_MX_X_INTERNAL = 0, MOIN_MX_X_EMIT = 1, MOIN_MX_X_GIVEN = 2 };
-int moin_lora_linear_mx_planned(moin_ctx *ctx, const moin_plan *plan, const void *x,
-                                void *xq, void *xs, int32_t x_codes, const void *Wq, const void *Ws,
-                                const void *A_stack, const void *B_stack, int32_t d_in,
-                                int32_t d_out, int32_t r, float scale, void *y, moin_dtype y_dt,
-                                void *stream);
-
 /* The grouping of sequences by expert depends only on (seq_offsets,
  * expert_ids, E); a plan computes it once for all projections of a layer
  * (Section 3.2: every linear layer carries an adapter).
@@ -240,16 +165,58 @@ void moin_plan_destroy(moin_plan *plan);
 int moin_plan_build(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
                     const int32_t *expert_ids, int32_t S, int64_t T, int32_t E,
                     void *stream);
-/* moin_plan_build with per-expert ranks (see moin_lora_linear_ranked); the ranks are
- * resolved into the plan, rank_of_expert need not outlive the call's completion. */
-int moin_plan_build_ranked(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
-                           const int32_t *expert_ids, int32_t S, int64_t T, int32_t E,
-                           const int32_t *rank_of_expert, void *stream);
 int moin_lora_linear_planned(moin_ctx *ctx, const moin_plan *plan, const void *x,
                              const void *W, const void *A_stack,
                              const void *B_stack, int32_t d_in, int32_t d_out,
                              int32_t r, float scale, void *y, moin_dtype y_dt,
                              void *stream);
+
+/* moin_lora_linear_planned for n (1..4) projections of a layer that read the same
+ * input x [T, d_in] (q, k, v; gate, up): on the prefill path the adapters' first
+ * products u_i = scale * x A_{i,e}^T of all n come out of ONE pass over x, then
+ * each projection's main product runs as in moin_lora_linear_planned; the results
+ * are, bit for bit, those of n single calls.  W, A_stack, B_stack, y: host arrays
+ * of n device pointers (stacks [E, r, d_in] / [E, d_out[i], r]; A_stack and B_stack
+ * may be NULL when there are no adapters), d_out: host array of n widths; r and
+ * scale are common.  Needs 2 n T r bf16 of workspace.  Errors as
+ * moin_lora_linear_planned; n outside 1..4: MOIN_EINVAL. */
+int moin_lora_linear_planned_shared(moin_ctx *ctx, const moin_plan *plan, const void *x, int32_t n,
+                                    const void *const *W, const void *const *A_stack,
+                                    const void *const *B_stack, int32_t d_in, const int32_t *d_out,
+                                    int32_t r, float scale, void *const *y, moin_dtype y_dt,
+                                    void *stream);
+
+/* ---- HIP graphs and the library's own device memory ----------------------------
+ * The context's workspace and a plan's buffer grow on demand (hipMalloc), which a
+ * stream under capture must not do.  A call on a capturing stream that would have
+ * to grow either returns MOIN_ECAPTURE and records nothing: make the first call
+ * with the largest shapes outside the capture, or reserve beforehand.  A workspace
+ * or plan buffer that a captured call has used is kept until moin_destroy /
+ * moin_plan_destroy even when a later, larger call replaces it, so replays of the
+ * graph keep reading valid memory (results of a replay are then only defined if
+ * no other call on the context runs concurrently, as for eager calls).
+ *   moin_reserve_workspace: the workspace holds at least `bytes` afterwards.
+ *   moin_workspace_bytes:   its present size -- after an eager call with the
+ *                           largest shapes, the figure to reserve elsewhere.
+ *   moin_plan_reserve:      the plan's buffer holds the plan of any batch of at
+ *                           most S sequences, T tokens and E experts.
+ * Errors: MOIN_EINVAL (null, negative sizes), MOIN_ENOMEM, MOIN_ECAPTURE (`stream`
+ * is being captured and growth is needed). */
+int moin_reserve_workspace(moin_ctx *ctx, int64_t bytes, void *stream);
+int64_t moin_workspace_bytes(const moin_ctx *ctx);
+int moin_plan_reserve(moin_ctx *ctx, moin_plan *plan, int32_t S, int64_t T, int32_t E, void *stream);
+
+/* ---- per-kernel timing ----------------------------------------------------
+ * When enabled, every kernel launch is bracketed by HIP events on the launch
+ * stream.  moin_timing_read synchronises those events and returns, for one
+ * kernel id, the summed duration in milliseconds and the number of launches
+ * since the last moin_timing_reset.  Meant for benchmarks; off by default. */
+int moin_timing_enable(moin_ctx *ctx, int on);
+int moin_timing_reset(moin_ctx *ctx);
+int moin_timing_read(moin_ctx *ctx, int kernel_id, double *ms_sum,
+                     int64_t *launches);
+
+/* ==== beyond the two core calls: rows the paper lists as next steps ============== */
 
 /* ---- K-means (topic modelling) --------------------------------------------
  * Section 3.1: the topics are the cells of a plain K-means clustering of the
@@ -346,15 +313,102 @@ int moin_cache_table(const moin_cache *cache, int32_t *slot_of_expert,
 /* stats [MOIN_CACHE_STAT_COUNT] (HOST array), totals since creation. */
 int moin_cache_stats(const moin_cache *cache, int64_t *stats);
 
-/* ---- per-kernel timing ----------------------------------------------------
- * When enabled, every kernel launch is bracketed by HIP events on the launch
- * stream.  moin_timing_read synchronises those events and returns, for one
- * kernel id, the summed duration in milliseconds and the number of launches
- * since the last moin_timing_reset.  Meant for benchmarks; off by default. */
-int moin_timing_enable(moin_ctx *ctx, int on);
-int moin_timing_reset(moin_ctx *ctx);
-int moin_timing_read(moin_ctx *ctx, int kernel_id, double *ms_sum,
-                     int64_t *launches);
+/* "Future Works", adaptive rank per topic (also Section 4.2: the rank could follow
+ * the amount of training data): the same layer with a rank per expert.
+ * rank_of_expert [E] int32 (DEVICE) or NULL; expert e uses the first
+ * rank_of_expert[e] rows of A_stack[e] and columns of B_stack[e], 0 <= rank <= r,
+ * a multiple of 8 (rank 0: base model only).  The stacks keep their [E, r, ...]
+ * shape.  What lies beyond an expert's rank is not used: rows of A_e beyond it are
+ * never read; columns of B_e from the rank up to the next multiple of 64 are
+ * multiplied by zeros on the prefill path and must therefore be finite (zero
+ * padding is the natural choice), further columns are never read.  The decode
+ * path reads only rank_e rows / columns of every distinct adapter.  A rank that
+ * is negative or not a multiple of 8 raises the sticky data fault (it is rounded
+ * down; negative: full rank); a rank above r counts as r. */
+int moin_lora_linear_ranked(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
+                            const int32_t *expert_ids, int32_t S, int64_t T,
+                            const void *W, const void *A_stack, const void *B_stack,
+                            int32_t E, int32_t d_in, int32_t d_out, int32_t r,
+                            const int32_t *rank_of_expert, float scale, void *y,
+                            moin_dtype y_dt, void *stream);
+
+/* moin_plan_build with per-expert ranks (see moin_lora_linear_ranked); the ranks are
+ * resolved into the plan, rank_of_expert need not outlive the call's completion. */
+int moin_plan_build_ranked(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
+                           const int32_t *expert_ids, int32_t S, int64_t T, int32_t E,
+                           const int32_t *rank_of_expert, void *stream);
+/* "Future Works", quantising the base model (a QLoRA-like, aggressively quantised
+ * base whose loss the experts recover; the paper names the idea only).  The
+ * format here is OCP Microscaling MXFP8: along the last axis, blocks of 32
+ * consecutive values share one power-of-two scale 2^(E-127) (E8M0 byte E) and
+ * hold FP8 E4M3 elements (bias 7, largest finite value 448, no infinities).
+ *
+ * moin_mx_quantize: src [rows, cols] bf16 (DEVICE, finite values; NaN / Inf give
+ * unspecified codes) -> codes [rows, cols] uint8 and rows * cols/32 scale bytes
+ * (both DEVICE, caller-owned).  scale_layout: MOIN_MX_ROW_MAJOR, scales
+ * [rows, cols/32]; MOIN_MX_BLOCKED (cols a multiple of 128), scales
+ * [cols/128, rows, 4] -- the four bytes of 128 consecutive values of a row form
+ * one word and the words of consecutive rows are adjacent, which is the order
+ * the matrix-core kernel fetches them in.  E = max(0, floor(log2 max|v|) + 127 - 8) per
+ * block (127 for a block of zeros); element = v / 2^(E-127) rounded to nearest
+ * even, magnitudes above 448 clamped to 448.  cols must be a multiple of 32,
+ * src and codes 16-byte aligned.  Used once for the weight. */
+enum { MOIN_MX_ROW_MAJOR = 0, MOIN_MX_BLOCKED = 1 };
+int moin_mx_quantize(moin_ctx *ctx, const void *src, int64_t rows, int64_t cols, void *codes,
+                     void *scales, int32_t scale_layout, void *stream);
+
+/* moin_lora_linear_ranked on a quantised base:
+ *     y = dq(q(x)) dq(Wq)^T + scale * (x A_e^T) B_e^T
+ * Wq [d_out, d_in] codes and Ws (MOIN_MX_BLOCKED layout: [d_in/128, d_out, 4])
+ * come from moin_mx_quantize; x [T, d_in] is bf16 and is quantised by the call itself
+ * (into the context's workspace) for the base product, which runs on the
+ * block-scaled FP8 matrix cores; the adapter term uses the bf16 x and the bf16
+ * stacks exactly as in moin_lora_linear.  rank_of_expert may be NULL.
+ * Shapes: d_in a multiple of 128 and at least 256, r a multiple of 64, d_out a
+ * multiple of 8; anything else returns MOIN_EINVAL.  Small batches (T <= 1024)
+ * and batches of short sequences (T <= 128 S, see moin_lora_linear)
+ * compute the base product for all tokens at once on the FP8 matrix cores and
+ * add the adapter term with the decode path's gather-matvec kernels. */
+int moin_lora_linear_mx(moin_ctx *ctx, const void *x, const int32_t *seq_offsets,
+                        const int32_t *expert_ids, int32_t S, int64_t T,
+                        const void *Wq, const void *Ws, const void *A_stack, const void *B_stack,
+                        int32_t E, int32_t d_in, int32_t d_out, int32_t r,
+                        const int32_t *rank_of_expert, float scale, void *y,
+                        moin_dtype y_dt, void *stream);
+
+/* moin_lora_linear_mx on a plan (moin_plan_build / moin_plan_build_ranked), for the
+ * projections of a layer.  xq [T, d_in] / xs (MOIN_MX_BLOCKED layout,
+ * [d_in/128, T, 4]) hold the quantised activations (device, 16-byte aligned), so
+ * that projections that share their input (q, k, v; gate, up) quantise it once:
+ *   MOIN_MX_X_INTERNAL  xq, xs NULL: the call quantises x into the context's workspace;
+ *   MOIN_MX_X_EMIT      the call quantises x into xq / xs (the caller's buffers; with
+ *                       adapters in a prefill batch that happens inside the shrink's
+ *                       pass over x) and uses them;
+ *   MOIN_MX_X_GIVEN     xq / xs are read: what an earlier MOIN_MX_X_EMIT call or
+ *                       moin_mx_quantize(x, MOIN_MX_BLOCKED) wrote for the same x.
+ * x (bf16) is needed in every case, for the adapter term.  A mode that does not
+ * fit the pointers returns MOIN_EINVAL. */
+enum { MOIN_MX_X_INTERNAL = 0, MOIN_MX_X_EMIT = 1, MOIN_MX_X_GIVEN = 2 };
+int moin_lora_linear_mx_planned(moin_ctx *ctx, const moin_plan *plan, const void *x,
+                                void *xq, void *xs, int32_t x_codes, const void *Wq, const void *Ws,
+                                const void *A_stack, const void *B_stack, int32_t d_in,
+                                int32_t d_out, int32_t r, float scale, void *y, moin_dtype y_dt,
+                                void *stream);
+
+/* ==== the paper's "Future Works" variants ========================================= */
+
+/* "Future Works", better adapters: an activation function between the adapter's
+ * two linear layers,
+ *     y = x W^T + scale * act(x A_e^T) B_e^T,
+ * applied to x A_e^T in fp32 before the scale.  The paper names no function; these
+ * are the textbook ones: ReLU max(v, 0), SiLU v / (1 + exp(-v)), GELU
+ * v/2 (1 + erf(v / sqrt 2)).  It is a property of the adapters the stacks hold (of
+ * how they were trained), not of a call, so it is set on the context and holds
+ * for every later moin_lora_linear* call on it (plain, ranked, planned, on a
+ * quantised base; prefill and decode) until set again.  Default MOIN_ACT_NONE, the
+ * paper's adapter.  Any other value: MOIN_EINVAL, setting unchanged. */
+enum { MOIN_ACT_NONE = 0, MOIN_ACT_RELU = 1, MOIN_ACT_SILU = 2, MOIN_ACT_GELU = 3 };
+int moin_set_adapter_activation(moin_ctx *ctx, int32_t activation);
 
 /* The k (1..8) nearest topic embeddings of every query, nearest first, equal
  * distances by increasing centroid index ("Future Works", creating new experts on
@@ -391,33 +445,7 @@ int moin_merge_adapters(moin_ctx *ctx, const void *A_stack, const void *B_stack,
                         const float *weights, int32_t n, int32_t r_out, void *A_out, void *B_out,
                         void *stream);
 
-/* moin_lora_linear_planned for n (1..4) projections of a layer that read the same
- * input x [T, d_in] (q, k, v; gate, up): on the prefill path the adapters' first
- * products u_i = scale * x A_{i,e}^T of all n come out of ONE pass over x, then
- * each projection's main product runs as in moin_lora_linear_planned; the results
- * are, bit for bit, those of n single calls.  W, A_stack, B_stack, y: host arrays
- * of n device pointers (stacks [E, r, d_in] / [E, d_out[i], r]; A_stack and B_stack
- * may be NULL when there are no adapters), d_out: host array of n widths; r and
- * scale are common.  Needs 2 n T r bf16 of workspace.  Errors as
- * moin_lora_linear_planned; n outside 1..4: MOIN_EINVAL. */
-int moin_lora_linear_planned_shared(moin_ctx *ctx, const moin_plan *plan, const void *x, int32_t n,
-                                    const void *const *W, const void *const *A_stack,
-                                    const void *const *B_stack, int32_t d_in, const int32_t *d_out,
-                                    int32_t r, float scale, void *const *y, moin_dtype y_dt,
-                                    void *stream);
-
-/* "Future Works", better adapters: an activation function between the adapter's
- * two linear layers,
- *     y = x W^T + scale * act(x A_e^T) B_e^T,
- * applied to x A_e^T in fp32 before the scale.  The paper names no function; these
- * are the textbook ones: ReLU max(v, 0), SiLU v / (1 + exp(-v)), GELU
- * v/2 (1 + erf(v / sqrt 2)).  It is a property of the adapters the stacks hold (of
- * how they were trained), not of a call, so it is set on the context and holds
- * for every later moin_lora_linear* call on it (plain, ranked, planned, on a
- * quantised base; prefill and decode) until set again.  Default MOIN_ACT_NONE, the
- * paper's adapter.  Any other value: MOIN_EINVAL, setting unchanged. */
-enum { MOIN_ACT_NONE = 0, MOIN_ACT_RELU = 1, MOIN_ACT_SILU = 2, MOIN_ACT_GELU = 3 };
-int moin_set_adapter_activation(moin_ctx *ctx, int32_t activation);
+/* ==== measurement aids (not part of the method's path) =========================== */
 
 /* Measurement aids: the ceilings of this very device, beside the datasheet peaks,
  * for the roofline fractions that bench.py reports (the hot path of the paper's

@@ -37,6 +37,10 @@ struct moin_plan {
     size_t bytes;
     int device;
     int built;
+    // set once a call that uses the plan was recorded into a HIP graph: the graph holds
+    // buf's address, so a later regrowth keeps the old block (until moin_plan_destroy)
+    mutable int pinned;
+    std::vector<void *> retired;
 };
 
 struct TimedSpan {
@@ -49,6 +53,8 @@ struct moin_ctx {
     int *err_word;
     void *ws;
     size_t ws_bytes;
+    int ws_pinned;                  // a captured graph may hold ws's address (see moin_plan::pinned)
+    std::vector<void *> ws_retired;
     moin_plan *own_plan;
     int act;   // activation between the adapter's two layers (MOIN_ACT_*)
     int timing;
@@ -78,23 +84,45 @@ struct DeviceGuard {
     }
 };
 
-int ensure_ws(moin_ctx *ctx, size_t bytes)
+bool capturing(hipStream_t st)
 {
-    if (bytes <= ctx->ws_bytes) return MOIN_OK;
-    if (ctx->ws) {
-        // hipFree waits for work that may still read the old block
-        if (hipFree(ctx->ws) != hipSuccess) return MOIN_EHIP;
-        ctx->ws = nullptr;
-        ctx->ws_bytes = 0;
-    }
-    const size_t want = align_up(bytes + bytes / 4, 1 << 20);
-    void *p = nullptr;
-    if (hipMalloc(&p, want) != hipSuccess) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess) {
         (void)hipGetLastError();
-        return MOIN_ENOMEM;
+        return false;
     }
-    ctx->ws = p;
-    ctx->ws_bytes = want;
+    return cs == hipStreamCaptureStatusActive;
+}
+
+// Makes the context's workspace at least `bytes` large for a call on `st`.  While
+// `st` is being captured nothing is (re)allocated: a call that needs more than the
+// workspace holds fails with MOIN_ECAPTURE and records nothing.  A workspace that a
+// captured call has used is never freed before moin_destroy -- a graph replays with
+// the addresses it recorded -- so growing it later keeps the old block aside.
+int ensure_ws(moin_ctx *ctx, size_t bytes, hipStream_t st, bool exact = false)
+{
+    const bool cap = capturing(st);
+    if (bytes > ctx->ws_bytes) {
+        if (cap) return MOIN_ECAPTURE;
+        const size_t want = exact ? align_up(bytes, 256) : align_up(bytes + bytes / 4, 1 << 20);
+        void *p = nullptr;
+        if (hipMalloc(&p, want) != hipSuccess) {
+            (void)hipGetLastError();
+            return MOIN_ENOMEM;
+        }
+        if (ctx->ws) {
+            if (ctx->ws_pinned) {
+                ctx->ws_retired.push_back(ctx->ws);
+            } else if (hipFree(ctx->ws) != hipSuccess) {   // waits for work that may still read the old block
+                (void)hipFree(p);
+                return MOIN_EHIP;
+            }
+        }
+        ctx->ws = p;
+        ctx->ws_bytes = want;
+        ctx->ws_pinned = 0;
+    }
+    if (cap && bytes > 0) ctx->ws_pinned = 1;
     return MOIN_OK;
 }
 
@@ -156,15 +184,17 @@ struct PlanLayout {
     int max_tiles, max_groups, max_plain, decode;
 };
 
-PlanLayout plan_layout(int32_t S, int64_t T, int32_t E)
+// upper_bound: sizes that hold the plan of ANY batch of at most S sequences and T tokens
+// (every array at its larger variant), for moin_plan_reserve.
+PlanLayout plan_layout(int32_t S, int64_t T, int32_t E, bool upper_bound = false)
 {
     PlanLayout L;
     // one record per distinct expert (and one for "no adapter"), plus what cutting the
     // groups into chunks of GROUP_CHUNK tokens can add
     const int64_t groups = std::min<int64_t>(S, (int64_t)E + 1) + T / GROUP_CHUNK + 1;
-    L.decode = (T <= DECODE_MAX_T || T <= (int64_t)GATHER_MAX_AVG_LEN * S) && groups <= 65535;
+    L.decode = upper_bound || ((T <= DECODE_MAX_T || T <= (int64_t)GATHER_MAX_AVG_LEN * S) && groups <= 65535);
     L.max_tiles = (int)(T / TILE_M) + S + 1;
-    L.max_groups = L.decode ? (int)groups : 0;
+    L.max_groups = L.decode ? (int)std::min<int64_t>(groups, 65535) : 0;
     size_t npow2 = 1;
     while (npow2 < (size_t)S) npow2 <<= 1;
     size_t off = 0;
@@ -185,10 +215,37 @@ PlanLayout plan_layout(int32_t S, int64_t T, int32_t E)
     L.grp_tmp = take((size_t)(L.max_groups + 1) * 8);
     L.n_groups = take(4);
     L.tmp = take((size_t)4 * ((size_t)S + 1) * 4);
-    L.max_plain = (L.decode && T > DECODE_MAX_T) ? (int)((T + TILE_M - 1) / TILE_M) : 0;
+    L.max_plain = (L.decode && (T > DECODE_MAX_T || upper_bound)) ? (int)((T + TILE_M - 1) / TILE_M) : 0;
     L.plain = take(((size_t)4 * L.max_plain + 1) * 4);
     L.total = off;
     return L;
+}
+
+// The plan's buffer, at least `bytes` large; same rules under stream capture as ensure_ws.
+int plan_grow(moin_plan *plan, size_t bytes, hipStream_t st)
+{
+    const bool cap = capturing(st);
+    if (bytes > plan->bytes) {
+        if (cap) return MOIN_ECAPTURE;
+        void *p = nullptr;
+        if (hipMalloc(&p, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return MOIN_ENOMEM;
+        }
+        if (plan->buf) {
+            if (plan->pinned) {
+                plan->retired.push_back(plan->buf);
+            } else if (hipFree(plan->buf) != hipSuccess) {
+                (void)hipFree(p);
+                return MOIN_EHIP;
+            }
+        }
+        plan->buf = p;
+        plan->bytes = bytes;
+        plan->pinned = 0;
+    }
+    if (cap) plan->pinned = 1;
+    return MOIN_OK;
 }
 
 int plan_build_impl(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
@@ -207,18 +264,8 @@ int plan_build_impl(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
     }
     if (!seq_offsets || !expert_ids) return MOIN_EINVAL;
     const PlanLayout L = plan_layout(S, T, E);
-    if (L.total > plan->bytes) {
-        if (plan->buf && hipFree(plan->buf) != hipSuccess) return MOIN_EHIP;
-        plan->buf = nullptr;
-        plan->bytes = 0;
-        void *p = nullptr;
-        if (hipMalloc(&p, L.total) != hipSuccess) {
-            (void)hipGetLastError();
-            return MOIN_ENOMEM;
-        }
-        plan->buf = p;
-        plan->bytes = L.total;
-    }
+    const int grc = plan_grow(plan, L.total, stream);
+    if (grc != MOIN_OK) return grc;
     char *b = static_cast<char *>(plan->buf);
     PlanView &pv = plan->pv;
     pv.keys = reinterpret_cast<unsigned long long *>(b + L.keys);
@@ -277,6 +324,7 @@ int linear_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, con
     if (pv.S == 0 || pv.T == 0) return MOIN_OK;
     const int vrc = validate_linear(x, W, A_stack, B_stack, pv.E, d_in, d_out, r, scale, y, y_dt);
     if (vrc != MOIN_OK) return vrc;
+    if (capturing(stream)) plan->pinned = 1;
     const bool adapters = pv.E > 0 && r > 0;
 
     LinearArgs a;
@@ -288,7 +336,7 @@ int linear_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, con
     const size_t u_bytes = align_up((size_t)pv.T * (size_t)a.r * 2, 256);
     if (!pv.decode) {
         if (a.r > 0) {
-            const int rc = ensure_ws(ctx, 2 * u_bytes);
+            const int rc = ensure_ws(ctx, 2 * u_bytes, stream);
             if (rc != MOIN_OK) return rc;
             a.u_hi = ctx->ws;
             a.u_lo = static_cast<char *>(ctx->ws) + u_bytes;
@@ -324,7 +372,7 @@ int linear_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, con
     d.lin = a;
     d.k_splits = big ? 1 : decode_base_splits(pv.T, d_in, d_out);
     const size_t yb_bytes = align_up((size_t)d.k_splits * (size_t)pv.T * (size_t)d_out * 4, 256);
-    const int rc = ensure_ws(ctx, 2 * u_bytes + yb_bytes);
+    const int rc = ensure_ws(ctx, 2 * u_bytes + yb_bytes, stream);
     if (rc != MOIN_OK) return rc;
     char *w = static_cast<char *>(ctx->ws);
     d.ug_hi = w;
@@ -368,6 +416,7 @@ int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, 
     if (!plan->built) return MOIN_EINVAL;
     const PlanView &pv = plan->pv;
     if (pv.S == 0 || pv.T == 0) return MOIN_OK;
+    if (capturing(stream)) plan->pinned = 1;
     const bool adapters = pv.E > 0 && r > 0;
     MxLinearArgs m;
     LinearArgs &a = m.lin;
@@ -393,7 +442,7 @@ int linear_mx_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, 
         m.plain_splits = 1;            // no adapters anywhere: the plain product writes y itself
         m.plain_kb_per_split = d_in / 128;
     }
-    const int rc = ensure_ws(ctx, 2 * u_bytes + xq_bytes + xs_bytes + yb_bytes);
+    const int rc = ensure_ws(ctx, 2 * u_bytes + xq_bytes + xs_bytes + yb_bytes, stream);
     if (rc != MOIN_OK) return rc;
     char *w = static_cast<char *>(ctx->ws);
     a.u_hi = w;
@@ -464,6 +513,7 @@ int moin_create(moin_ctx **out, int device)
     ctx->err_word = nullptr;
     ctx->ws = nullptr;
     ctx->ws_bytes = 0;
+    ctx->ws_pinned = 0;
     ctx->own_plan = nullptr;
     ctx->act = MOIN_ACT_NONE;
     ctx->timing = 0;
@@ -497,6 +547,7 @@ void moin_destroy(moin_ctx *ctx)
     for (hipEvent_t e : ctx->free_events) (void)hipEventDestroy(e);
     if (ctx->own_plan) moin_plan_destroy(ctx->own_plan);
     if (ctx->ws) (void)hipFree(ctx->ws);
+    for (void *p : ctx->ws_retired) (void)hipFree(p);
     if (ctx->err_word) (void)hipFree(ctx->err_word);
     delete ctx;
 }
@@ -509,6 +560,8 @@ const char *moin_strerror(int code)
     case MOIN_ENOMEM: return "workspace allocation failed";
     case MOIN_EHIP: return "HIP runtime call failed";
     case MOIN_EDATA: return "device-side data fault (expert id or rank out of range, bad offsets or ids)";
+    case MOIN_ETOOBIG: return "size beyond the fixed limit of an entry point that does not allocate";
+    case MOIN_ECAPTURE: return "the call would have to reallocate its workspace while the stream is being captured";
     default: return "unknown moin status";
     }
 }
@@ -531,9 +584,9 @@ int moin_check(moin_ctx *ctx, void *stream)
     return MOIN_OK;
 }
 
-int moin_route(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N, int32_t K,
-               int32_t D, moin_dtype dt, const int32_t *slot_of_centroid, uint32_t flags,
-               int32_t *expert_ids, int32_t *centroid_ids, int32_t *counts, void *stream)
+// Host-checkable faults of a routing call.
+static int validate_route(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N, int32_t K,
+                          int32_t D, moin_dtype dt, const int32_t *slot_of_centroid, uint32_t flags)
 {
     if (!ctx || N < 0 || K <= 0 || D <= 0) return MOIN_EINVAL;
     if (dt != MOIN_BF16 && dt != MOIN_F32) return MOIN_EINVAL;
@@ -544,53 +597,107 @@ int moin_route(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N,
     if (dt == MOIN_BF16 ? (D % 8 != 0) : (D % 4 != 0)) return MOIN_EINVAL;
     if (D > (1 << 20) || K > (1 << 28)) return MOIN_EINVAL;
     if (misaligned(centroids, 16) || (emb && misaligned(emb, 16))) return MOIN_EINVAL;
-    DeviceGuard guard(ctx->device);
-    if (!guard.ok) return MOIN_EHIP;
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    return MOIN_OK;
+}
 
+// Where a routing call keeps its intermediate results inside a block of device memory.
+struct RouteScratch {
+    size_t cnorm, cinit, best, arrivals, cid, total;
+    int group;
+};
+
+static RouteScratch route_scratch(int64_t N, int32_t K, int32_t D, moin_dtype dt, bool need_cid)
+{
+    RouteScratch L;
     const size_t Kpad = align_up((size_t)K, 256);
     const size_t cn_bytes = align_up(Kpad * 4, 256);
-    const int group = route_stream_group(N, K, D, dt == MOIN_BF16);
-    const size_t n_best = group > 1 ? (size_t)N : (size_t)ROUTE_SMALL_MAX_N;
-    const size_t n_arr = 1;
-    const size_t best_bytes = align_up(n_best * 8, 256);
-    const size_t arr_bytes = align_up(n_arr * 4, 256);
-    const bool need_cid_ws = counts && !centroid_ids && N > 0;
-    const int rc = ensure_ws(ctx, 2 * cn_bytes + best_bytes + arr_bytes + (need_cid_ws ? (size_t)N * 4 : 0));
-    if (rc != MOIN_OK) return rc;
-    char *w = static_cast<char *>(ctx->ws);
+    L.group = route_stream_group(N, K, D, dt == MOIN_BF16);
+    const size_t n_best = L.group > 1 ? (size_t)N : (size_t)ROUTE_SMALL_MAX_N;
+    L.cnorm = 0;
+    L.cinit = cn_bytes;
+    L.best = 2 * cn_bytes;
+    L.arrivals = L.best + align_up(n_best * 8, 256);
+    L.cid = L.arrivals + 256;
+    L.total = L.cid + (need_cid ? align_up((size_t)N * 4, 256) : 0);
+    return L;
+}
 
+// The launches of a routing call; `w` holds L.total bytes.  With `record` off the
+// launches are not bracketed by timing events (the caller must not allocate).
+static int route_launches(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N, int32_t K,
+                          int32_t D, moin_dtype dt, const int32_t *slot_of_centroid, uint32_t flags,
+                          int32_t *expert_ids, int32_t *centroid_ids, int32_t *counts, char *w,
+                          const RouteScratch &L, bool need_cid, bool record, hipStream_t st)
+{
     RouteArgs a;
     a.emb = emb; a.cent = centroids; a.N = N; a.K = K; a.D = D;
     a.is_bf16 = (dt == MOIN_BF16);
     a.slot = slot_of_centroid;
     a.retained_only = (flags & MOIN_ROUTE_RETAINED_ONLY) ? 1 : 0;
-    a.group = group;
-    a.cnorm = reinterpret_cast<float *>(w);
-    a.cinit = reinterpret_cast<float *>(w + cn_bytes);
-    a.best = reinterpret_cast<unsigned long long *>(w + 2 * cn_bytes);
-    a.arrivals = reinterpret_cast<int *>(w + 2 * cn_bytes + best_bytes);
-    a.cid = centroid_ids ? centroid_ids
-                         : (need_cid_ws ? reinterpret_cast<int *>(w + 2 * cn_bytes + best_bytes + arr_bytes)
-                                        : nullptr);
+    a.group = L.group;
+    a.cnorm = reinterpret_cast<float *>(w + L.cnorm);
+    a.cinit = reinterpret_cast<float *>(w + L.cinit);
+    a.best = reinterpret_cast<unsigned long long *>(w + L.best);
+    a.arrivals = reinterpret_cast<int *>(w + L.arrivals);
+    a.cid = centroid_ids ? centroid_ids : (need_cid ? reinterpret_cast<int *>(w + L.cid) : nullptr);
     a.expert_ids = expert_ids;
     a.counts = counts;
 
+    auto run = [&](int kernel, auto launch) {
+        return record ? timed(ctx, kernel, st, launch) : launch();
+    };
     const bool routed = N > 0 && (a.cid || a.expert_ids);
     if (routed) {
-        if (timed(ctx, MOIN_K_ROUTE_AUX, st, [&] { return launch_centroid_norms(a, st); }) != hipSuccess)
-            return MOIN_EHIP;
-        if (timed(ctx, MOIN_K_ROUTE, st, [&] { return launch_route(a, st); }) != hipSuccess)
-            return MOIN_EHIP;
+        if (run(MOIN_K_ROUTE_AUX, [&] { return launch_centroid_norms(a, st); }) != hipSuccess) return MOIN_EHIP;
+        if (run(MOIN_K_ROUTE, [&] { return launch_route(a, st); }) != hipSuccess) return MOIN_EHIP;
     }
     if (counts && !(routed && route_tallies_counts(a))) {
         // the norms kernel, when it ran, has already zeroed counts
-        if (timed(ctx, MOIN_K_ROUTE_AUX, st, [&] {
+        if (run(MOIN_K_ROUTE_AUX, [&] {
                 return launch_histogram(a.cid, N, K, counts, routed ? 0 : 1, ctx->err_word, st);
             }) != hipSuccess)
             return MOIN_EHIP;
     }
     return MOIN_OK;
+}
+
+int moin_reserve_workspace(moin_ctx *ctx, int64_t bytes, void *stream)
+{
+    if (!ctx || bytes < 0) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    return ensure_ws(ctx, (size_t)bytes, static_cast<hipStream_t>(stream), true);
+}
+
+int64_t moin_workspace_bytes(const moin_ctx *ctx) { return ctx ? (int64_t)ctx->ws_bytes : 0; }
+
+int moin_plan_reserve(moin_ctx *ctx, moin_plan *plan, int32_t S, int64_t T, int32_t E, void *stream)
+{
+    if (!ctx || !plan || plan->device != ctx->device) return MOIN_EINVAL;
+    if (S < 0 || T < 0 || E < 0 || T > 0x7fffffffLL - TILE_M) return MOIN_EINVAL;
+    if (S == 0 || T == 0) return MOIN_OK;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    // a plan holds either kind of batch of up to this size: the larger of the two layouts
+    const size_t need = plan_layout(S, T, E, true).total;
+    return plan_grow(plan, need, static_cast<hipStream_t>(stream));
+}
+
+int moin_route(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N, int32_t K,
+               int32_t D, moin_dtype dt, const int32_t *slot_of_centroid, uint32_t flags,
+               int32_t *expert_ids, int32_t *centroid_ids, int32_t *counts, void *stream)
+{
+    const int vrc = validate_route(ctx, emb, centroids, N, K, D, dt, slot_of_centroid, flags);
+    if (vrc != MOIN_OK) return vrc;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool need_cid = counts && !centroid_ids && N > 0;
+    const RouteScratch L = route_scratch(N, K, D, dt, need_cid);
+    const int rc = ensure_ws(ctx, L.total, st);
+    if (rc != MOIN_OK) return rc;
+    return route_launches(ctx, emb, centroids, N, K, D, dt, slot_of_centroid, flags, expert_ids,
+                          centroid_ids, counts, static_cast<char *>(ctx->ws), L, need_cid, true, st);
 }
 
 int moin_histogram(moin_ctx *ctx, const int32_t *ids, int64_t N, int32_t K, int32_t *counts,
@@ -617,6 +724,7 @@ int moin_plan_create(moin_ctx *ctx, moin_plan **out)
     p->bytes = 0;
     p->device = ctx->device;
     p->built = 0;
+    p->pinned = 0;
     *out = p;
     return MOIN_OK;
 }
@@ -626,6 +734,7 @@ void moin_plan_destroy(moin_plan *plan)
     if (!plan) return;
     DeviceGuard guard(plan->device);
     if (plan->buf) (void)hipFree(plan->buf);
+    for (void *p : plan->retired) (void)hipFree(p);
     delete plan;
 }
 
@@ -670,6 +779,7 @@ int moin_lora_linear_planned_shared(moin_ctx *ctx, const moin_plan *plan, const 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const PlanView &pv = plan->pv;
     if (pv.S == 0 || pv.T == 0) return MOIN_OK;
+    if (capturing(st)) plan->pinned = 1;
     const bool adapters = pv.E > 0 && r > 0;
     if (adapters && (!A_stack || !B_stack)) return MOIN_EINVAL;
     for (int i = 0; i < n; ++i) {
@@ -688,7 +798,7 @@ int moin_lora_linear_planned_shared(moin_ctx *ctx, const moin_plan *plan, const 
         return MOIN_OK;
     }
     const size_t u_bytes = align_up((size_t)pv.T * (size_t)r * 2, 256);
-    const int rc = ensure_ws(ctx, (size_t)n * 2 * u_bytes);
+    const int rc = ensure_ws(ctx, (size_t)n * 2 * u_bytes, st);
     if (rc != MOIN_OK) return rc;
     void *u_hi[MAX_SHARED_X], *u_lo[MAX_SHARED_X];
     for (int i = 0; i < n; ++i) {
@@ -860,7 +970,7 @@ int moin_kmeans_update(moin_ctx *ctx, const void *emb, const int32_t *ids, int64
     const size_t o_perm = take((size_t)(N + 1) * 4);
     const size_t o_part = take((size_t)(a.max_pieces + 1) * D * 4);
     const size_t o_ipart = take((size_t)(a.max_pieces + 1) * a.ncb * 8);
-    const int rc = ensure_ws(ctx, off);
+    const int rc = ensure_ws(ctx, off, st);
     if (rc != MOIN_OK) return rc;
     char *w = static_cast<char *>(ctx->ws);
     a.table = reinterpret_cast<int *>(w + o_table);

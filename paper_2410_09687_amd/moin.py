@@ -36,6 +36,7 @@ EXPORTS = [
     "moin_mx_quantize", "moin_lora_linear_mx", "moin_lora_linear_mx_planned",
     "moin_probe_out_len", "moin_probe_mfma_bf16", "moin_probe_mfma_mxfp8", "moin_probe_read", "moin_set_adapter_activation",
     "moin_lora_linear_planned_shared", "moin_route_topk", "moin_merge_adapters",
+    "moin_reserve_workspace", "moin_workspace_bytes", "moin_plan_reserve",
 ]
 ACTIVATIONS = {None: 0, "none": 0, "relu": 1, "silu": 2, "gelu": 3}
 CACHE_STATS = ["batches", "seq_hits", "seq_misses", "loads", "evictions", "overflows", "bytes"]
@@ -84,6 +85,9 @@ def load() -> ctypes.CDLL:
     lib.moin_route_topk.argtypes = [vp, vp, vp, i64, i32, i32, c.c_int, vp, c.c_uint32, i32, vp, vp, vp, vp]
     lib.moin_lora_linear_planned_shared.argtypes = [vp, vp, vp, i32, vp, vp, vp, i32, vp, i32, c.c_float, vp,
                                                     c.c_int, vp]
+    lib.moin_reserve_workspace.argtypes = [vp, i64, vp]
+    lib.moin_workspace_bytes.argtypes = [vp]
+    lib.moin_plan_reserve.argtypes = [vp, vp, i32, i64, i32, vp]
     lib.moin_probe_out_len.argtypes = [vp]
     lib.moin_probe_out_len.restype = c.c_int64
     lib.moin_probe_mfma_bf16.argtypes = [vp, vp, i64, i32, vp, c.POINTER(c.c_double), vp]
@@ -110,8 +114,10 @@ def load() -> ctypes.CDLL:
     lib.moin_timing_reset.argtypes = [vp]
     lib.moin_timing_read.argtypes = [vp, c.c_int, c.POINTER(c.c_double), c.POINTER(i64)]
     for name in EXPORTS:
-        if name not in ("moin_destroy", "moin_plan_destroy", "moin_strerror", "moin_cache_destroy"):
+        if name not in ("moin_destroy", "moin_plan_destroy", "moin_strerror", "moin_cache_destroy",
+                        "moin_probe_out_len", "moin_workspace_bytes"):
             getattr(lib, name).restype = c.c_int
+    lib.moin_workspace_bytes.restype = c.c_int64
     _lib = lib
     return lib
 
@@ -171,6 +177,13 @@ class Context:
         if activation not in ACTIVATIONS:
             raise ValueError("activation: None, 'relu', 'silu' or 'gelu' expected")
         _ck(load().moin_set_adapter_activation(self._h, ACTIVATIONS[activation]), "moin_set_adapter_activation")
+
+    def reserve_workspace(self, nbytes: int, stream=None):
+        """Grows the workspace to at least ``nbytes`` (outside a stream capture)."""
+        _ck(load().moin_reserve_workspace(self._h, int(nbytes), _stream_ptr(stream)), "moin_reserve_workspace")
+
+    def workspace_bytes(self) -> int:
+        return int(load().moin_workspace_bytes(self._h))
 
     def timing_enable(self, on: bool = True):
         _ck(load().moin_timing_enable(self._h, int(on)), "moin_timing_enable")
@@ -390,6 +403,12 @@ class Plan:
                                           S, T, E, _dev_ptr(rank_of_expert, "rank_of_expert", torch.int32),
                                           _stream_ptr(stream)), "moin_plan_build_ranked")
         self.T, self.S, self.E = T, S, E
+        return self
+
+    def reserve(self, S: int, T: int, E: int, stream=None):
+        """Sizes the plan's buffer for any batch of at most S sequences, T tokens, E experts."""
+        _ck(load().moin_plan_reserve(self.ctx._h, self._h, int(S), int(T), int(E), _stream_ptr(stream)),
+            "moin_plan_reserve")
         return self
 
     def close(self):

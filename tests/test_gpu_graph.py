@@ -150,3 +150,72 @@ def test_two_contexts_on_two_streams_do_not_disturb_each_other():
         torch.cuda.synchronize()
         c1.close()
         c2.close()
+
+
+def test_capture_refuses_to_grow_and_keeps_what_a_graph_recorded():
+    # A fresh context has no workspace: a call on a capturing stream must fail (nothing may be allocated
+    # there) and record nothing.  After reserving, the same capture works.  A later eager call with larger
+    # shapes replaces workspace and plan buffer, but the blocks the graph recorded stay allocated, so a
+    # replay still computes the right thing.
+    ctx = moin.Context(0)
+    try:
+        inp = _inputs("graph_grow", 256, 264, 64, 12, [1] * 96, seed=75)
+        big = _inputs("graph_grow_big", 256, 520, 64, 12, [1] * 700, seed=76)
+        x, eids = inp.x.clone(), inp.expert_ids.clone()
+        y_graph = torch.empty((inp.wl.T, inp.wl.d_out), dtype=torch.bfloat16, device="cuda")
+        plan = moin.Plan(ctx)
+
+        def call(out):
+            plan.build(inp.seq_offsets, eids, inp.wl.T, inp.wl.E)
+            moin.moin_lora_linear_planned(ctx, plan, x, inp.W, inp.A_stack, inp.B_stack, 2.0, out=out)
+
+        assert ctx.workspace_bytes() == 0
+        torch.cuda.synchronize()
+        print("[gpu] graph growth: capture on an empty context is refused", flush=True)
+        graph = torch.cuda.CUDAGraph()
+        refused = []
+        with torch.cuda.graph(graph):
+            for step in (lambda: plan.build(inp.seq_offsets, eids, inp.wl.T, inp.wl.E),):
+                try:
+                    step()
+                except moin.MoinError as e:
+                    refused.append(e.code)
+        assert refused == [-6], refused
+        assert ctx.workspace_bytes() == 0
+        del graph
+        # reserve outside the capture: the plan for up to 128 sequences, the workspace from an eager call
+        plan.reserve(128, 128, inp.wl.E)
+        y_eager = torch.empty_like(y_graph)
+        call(y_eager)
+        ctx.check()
+        need = ctx.workspace_bytes()
+        assert need > 0
+        ctx.reserve_workspace(need)            # no-op: already that large
+        assert ctx.workspace_bytes() == need
+        print("[gpu] graph growth: capture after reserving", flush=True)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            call(y_graph)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph.view(torch.int16), y_eager.view(torch.int16))
+        # a larger eager batch on the same context and plan: both buffers are replaced ...
+        print("[gpu] graph growth: larger eager call, then replay", flush=True)
+        plan_b = plan.build(big.seq_offsets, big.expert_ids, big.wl.T, big.wl.E)
+        yb = moin.moin_lora_linear_planned(ctx, plan_b, big.x, big.W, big.A_stack, big.B_stack, 2.0)
+        ctx.check()
+        assert ctx.workspace_bytes() > need
+        gc.compare_linear(yb, gc.oracle_rows(big), what="graph_grow/big eager")
+        # ... and the graph still replays on the blocks it recorded, with new inputs in place
+        x.copy_(torch.randn(x.shape, device="cuda", generator=torch.Generator(device="cuda").manual_seed(9))
+                .to(torch.bfloat16))
+        eids.copy_(inp.expert_ids.flip(0))
+        y_graph.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref = gc.oracle_rows(wl.LinearInputs(inp.wl, x, inp.W, inp.A_stack, inp.B_stack, inp.seq_offsets, eids))
+        gc.compare_linear(y_graph, ref, what="graph_grow/replay after growth")
+        plan.close()
+    finally:
+        ctx.close()
