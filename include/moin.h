@@ -206,6 +206,25 @@ int moin_reserve_workspace(moin_ctx *ctx, int64_t bytes, void *stream);
 int64_t moin_workspace_bytes(const moin_ctx *ctx);
 int moin_plan_reserve(moin_ctx *ctx, moin_plan *plan, int32_t S, int64_t T, int32_t E, void *stream);
 
+/* moin_route for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and errors as moin_route, but every intermediate result (centroid norms,
+ * the packed per-query minima that workgroups merge, the arrival counter, centroid
+ * ids when only counts are asked for) lives in a fixed 1 MiB array in the library's
+ * device image instead of the context's workspace, so the call never calls
+ * hipMalloc / hipFree and records no timing events.  Limits: N <= 65536 queries,
+ * K <= 16384 centroids; beyond them MOIN_ETOOBIG and nothing is launched.  Every
+ * call on a GPU shares that GPU's array: the kernels re-initialise what they
+ * accumulate into on every call, and two calls that overlap on one GPU (different
+ * streams, different contexts) race. */
+#define MOIN_ROUTE_STATIC_MAX_N 65536
+#define MOIN_ROUTE_STATIC_MAX_K 16384
+int moin_route_static(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N,
+                      int32_t K, int32_t D, moin_dtype dt,
+                      const int32_t *slot_of_centroid, uint32_t flags,
+                      int32_t *expert_ids, int32_t *centroid_ids, int32_t *counts,
+                      void *stream);
+
 /* ---- per-kernel timing ----------------------------------------------------
  * When enabled, every kernel launch is bracketed by HIP events on the launch
  * stream.  moin_timing_read synchronises those events and returns, for one

@@ -64,6 +64,16 @@ struct moin_ctx {
     int64_t launches[MOIN_K_COUNT];
 };
 
+// Device memory for moin_route_static, the entry point that may not allocate: one
+// array per GPU the library is loaded on, held until the process ends.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; the address the
+// kernels get is looked up once per device (moin_create, with that device
+// current) and kept in g_scratch_ptr.
+constexpr size_t SCRATCH_BYTES = 1u << 20;
+static __device__ __align__(256) unsigned char scratch[SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void *g_scratch_ptr[MAX_DEVICES];
+
 namespace {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -525,6 +535,16 @@ int moin_create(moin_ctx **out, int device)
         delete ctx;
         return MOIN_EHIP;
     }
+    if (device < MAX_DEVICES && !g_scratch_ptr[device]) {
+        // this device's copy of the static scratch array (the guard above made it current)
+        void *sp = nullptr;
+        if (hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)) != hipSuccess || !sp) {
+            (void)hipGetLastError();
+            delete ctx;
+            return MOIN_EHIP;
+        }
+        g_scratch_ptr[device] = sp;
+    }
     if (hipMalloc(reinterpret_cast<void **>(&ctx->err_word), 256) != hipSuccess) {
         (void)hipGetLastError();
         delete ctx;
@@ -698,6 +718,25 @@ int moin_route(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N,
     if (rc != MOIN_OK) return rc;
     return route_launches(ctx, emb, centroids, N, K, D, dt, slot_of_centroid, flags, expert_ids,
                           centroid_ids, counts, static_cast<char *>(ctx->ws), L, need_cid, true, st);
+}
+
+int moin_route_static(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N, int32_t K,
+                      int32_t D, moin_dtype dt, const int32_t *slot_of_centroid, uint32_t flags,
+                      int32_t *expert_ids, int32_t *centroid_ids, int32_t *counts, void *stream)
+{
+    const int vrc = validate_route(ctx, emb, centroids, N, K, D, dt, slot_of_centroid, flags);
+    if (vrc != MOIN_OK) return vrc;
+    if (N > MOIN_ROUTE_STATIC_MAX_N || K > MOIN_ROUTE_STATIC_MAX_K) return MOIN_ETOOBIG;
+    if (ctx->device < 0 || ctx->device >= MAX_DEVICES || !g_scratch_ptr[ctx->device]) return MOIN_EHIP;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool need_cid = counts && !centroid_ids && N > 0;
+    const RouteScratch L = route_scratch(N, K, D, dt, need_cid);
+    if (L.total > SCRATCH_BYTES) return MOIN_ETOOBIG;   // cannot happen within the two limits above
+    return route_launches(ctx, emb, centroids, N, K, D, dt, slot_of_centroid, flags, expert_ids,
+                          centroid_ids, counts, static_cast<char *>(g_scratch_ptr[ctx->device]), L, need_cid,
+                          false, st);
 }
 
 int moin_histogram(moin_ctx *ctx, const int32_t *ids, int64_t N, int32_t K, int32_t *counts,

@@ -36,7 +36,7 @@ EXPORTS = [
     "moin_mx_quantize", "moin_lora_linear_mx", "moin_lora_linear_mx_planned",
     "moin_probe_out_len", "moin_probe_mfma_bf16", "moin_probe_mfma_mxfp8", "moin_probe_read", "moin_set_adapter_activation",
     "moin_lora_linear_planned_shared", "moin_route_topk", "moin_merge_adapters",
-    "moin_reserve_workspace", "moin_workspace_bytes", "moin_plan_reserve",
+    "moin_reserve_workspace", "moin_workspace_bytes", "moin_plan_reserve", "moin_route_static",
 ]
 ACTIVATIONS = {None: 0, "none": 0, "relu": 1, "silu": 2, "gelu": 3}
 CACHE_STATS = ["batches", "seq_hits", "seq_misses", "loads", "evictions", "overflows", "bytes"]
@@ -70,6 +70,7 @@ def load() -> ctypes.CDLL:
     lib.moin_strerror.restype = c.c_char_p
     lib.moin_check.argtypes = [vp, vp]
     lib.moin_route.argtypes = [vp, vp, vp, i64, i32, i32, c.c_int, vp, u32, vp, vp, vp, vp]
+    lib.moin_route_static.argtypes = lib.moin_route.argtypes
     lib.moin_histogram.argtypes = [vp, vp, i64, i32, vp, vp]
     lib.moin_lora_linear.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp, i32, i32, i32, i32,
                                      c.c_float, vp, c.c_int, vp]
@@ -200,8 +201,11 @@ class Context:
 
 def moin_route(ctx: Context, emb: torch.Tensor, centroids: torch.Tensor,
                slot_of_centroid: Optional[torch.Tensor] = None, retained_only: bool = False,
-               want_centroid_ids: bool = True, want_counts: bool = False, stream=None):
-    """Returns ``(expert_ids, centroid_ids or None, counts or None)`` as int32 tensors."""
+               want_centroid_ids: bool = True, want_counts: bool = False, stream=None, out=None,
+               static: bool = False):
+    """Returns ``(expert_ids, centroid_ids or None, counts or None)`` as int32 tensors.  ``out``: the same
+    triple preallocated by the caller.  ``static``: through ``moin_route_static``, the entry point that
+    allocates no device memory (N <= 65536, K <= 16384)."""
     if emb.dim() != 2 or centroids.dim() != 2 or emb.shape[1] != centroids.shape[1]:
         raise ValueError("emb [N,D] and centroids [K,D] expected")
     if emb.dtype != centroids.dtype or emb.dtype not in (torch.float32, torch.bfloat16):
@@ -210,15 +214,23 @@ def moin_route(ctx: Context, emb: torch.Tensor, centroids: torch.Tensor,
     K = centroids.shape[0]
     dt = MOIN_BF16 if emb.dtype == torch.bfloat16 else MOIN_F32
     dev = centroids.device
-    expert_ids = torch.empty(N, dtype=torch.int32, device=dev)
-    cids = torch.empty(N, dtype=torch.int32, device=dev) if want_centroid_ids else None
-    counts = torch.empty(K, dtype=torch.int32, device=dev) if want_counts else None
-    _ck(load().moin_route(ctx._h, _dev_ptr(emb, "emb") if N else None, _dev_ptr(centroids, "centroids"),
+    if out is not None:
+        expert_ids, cids, counts = out
+        for t, n in ((expert_ids, N), (cids, N), (counts, K)):
+            if t is not None and (t.dtype != torch.int32 or t.numel() != n):
+                raise ValueError("out: int32 tensors of N, N and K elements (or None) expected")
+    else:
+        expert_ids = torch.empty(N, dtype=torch.int32, device=dev)
+        cids = torch.empty(N, dtype=torch.int32, device=dev) if want_centroid_ids else None
+        counts = torch.empty(K, dtype=torch.int32, device=dev) if want_counts else None
+    fn = load().moin_route_static if static else load().moin_route
+    _ck(fn(ctx._h, _dev_ptr(emb, "emb") if N else None, _dev_ptr(centroids, "centroids"),
                           N, K, D, dt, _dev_ptr(slot_of_centroid, "slot_of_centroid", torch.int32),
                           MOIN_ROUTE_RETAINED_ONLY if retained_only else 0,
                           _dev_ptr(expert_ids, "expert_ids") if N else None,
                           _dev_ptr(cids, "centroid_ids") if (cids is not None and N) else None,
-                          _dev_ptr(counts, "counts"), _stream_ptr(stream)), "moin_route")
+                          _dev_ptr(counts, "counts"), _stream_ptr(stream)),
+        "moin_route_static" if static else "moin_route")
     return expert_ids, cids, counts
 
 
