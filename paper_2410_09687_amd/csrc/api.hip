@@ -388,6 +388,7 @@ int linear_planned_impl(moin_ctx *ctx, const moin_plan *plan, const void *x, con
     d.ug_hi = w;
     d.ug_lo = w + u_bytes;
     d.ybase = reinterpret_cast<float *>(w + 2 * u_bytes);
+    d.ybase_by_pos = big ? 0 : 1;   // the small-batch base product gathers its rows in the plan's order
     if (big) {
         ab.y = d.ybase;
         ab.y_f32 = 1;

@@ -37,8 +37,53 @@ __device__ __forceinline__ bf16x8_t ldg_frag(const char *row, int k, int klen)
     return __builtin_bit_cast(bf16x8_t, v);
 }
 
+// Group records and the first token indices of a group come through the scalar
+// cache: a scalar load does not queue behind the compute unit's vector-memory
+// traffic, so a workgroup knows its adapter and its tokens a few hundred
+// nanoseconds after it starts and can then issue ALL of its vector loads at once --
+// one trip to memory per workgroup instead of a chain of three.  (Under load
+// every dependent vector load costs a full queueing delay of several
+// microseconds, which is what kept these kernels at half the streaming rate.)
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+typedef int i32x16_t __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ i32x4_t sload_x4(const void *p)   // p: uniform, 4-byte aligned
+{
+    i32x4_t v;
+    asm volatile("s_load_dwordx4 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(p) : "memory");
+    return v;
+}
+__device__ __forceinline__ i32x16_t sload_x16(const void *p)
+{
+    i32x16_t v;
+    asm volatile("s_load_dwordx16 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(p) : "memory");
+    return v;
+}
+// Element (lane % 16) of sixteen wave-uniform values.
+__device__ __forceinline__ int pick16(const i32x16_t &t, int lane)
+{
+    const int i = lane & 15;
+    int v = t[0];
+#pragma unroll
+    for (int k = 1; k < 16; ++k) v = (i == k) ? t[k] : v;
+    return v;
+}
+
+// ldg_frag in two halves, so that a kernel can first issue every load it will need
+// and only then touch the data (a scheduling barrier between the two keeps the
+// compiler from waiting on one load before it has issued the next).
+__device__ __forceinline__ uint4 ldg_raw(const char *row, int k, int klen)
+{
+    return *reinterpret_cast<const uint4 *>(row + (k < klen ? k : 0) * 2);
+}
+__device__ __forceinline__ bf16x8_t frag_of(uint4 v, int k, int klen)
+{
+    const uint32_t m = k < klen ? 0xFFFFFFFFu : 0u;
+    v.x &= m; v.y &= m; v.z &= m; v.w &= m;
+    return __builtin_bit_cast(bf16x8_t, v);
+}
+
 constexpr int SHRINK_WAVES = 8;   // waves of a workgroup split the d_in range
-constexpr int SHRINK_BATCH = 4;   // k-steps (of 32) whose loads are issued together
+constexpr int SHRINK_BATCH = 8;   // k-steps (of 32) whose loads are issued together
 
 struct ShrinkDParams {
     const char *x, *A_stack;
@@ -72,17 +117,22 @@ __device__ __forceinline__ void decode_shrink_slab(const ShrinkDParams &p, int s
     const int d_in = p.d_in;
     const float scale = p.scale;
     (void)n_groups;   // records past the group count are empty
-    const int4 gm = grp_meta[g];
-    const int e = uniform(gm.x);
+    const i32x4_t gm = sload_x4(grp_meta + g);
+    const int e = gm.x;
     if (e < 0) return;
-    const int gs = uniform(gm.y), ge = uniform(gm.z);
+    const int gs = gm.y, ge = gm.z;
     if (ge <= gs) return;
     // the expert's own rank (a multiple of 8): slabs beyond it are never read, u is
     // stored [pos, p.r] and only its first r columns are written and later read
-    const int r = min(p.r, uniform(gm.w));
+    const int r = min(p.r, gm.w);
     const int ldr = p.r;
     if (slab * 16 >= r) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // tokens of the first block of 16 positions (entries past the group's end are read --
+    // the list is followed by more of the plan -- and not used)
+    const i32x16_t toks = sload_x16(tok_sorted + gs);
+    const int tok_first = pick16(toks, lane);
+    const int tok_gs = toks[0];   // lanes past the group's end take its first token (in bounds, result unused)
     const int j0 = slab * 16;
     const int jrow = j0 + (lane & 15);
     const int kq = (lane >> 4) * 8;               // element offset of this lane's k-group
@@ -105,7 +155,9 @@ __device__ __forceinline__ void decode_shrink_slab(const ShrinkDParams &p, int s
         const int pos = t0 + (lane & 15);
         const bool tvalid = pos < ge;
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-        const char *xrow = x + (int64_t)tok_sorted[tvalid ? pos : gs] * ld;
+        int tok = tvalid ? tok_first : tok_gs;
+        if (t0 != gs) tok = tok_sorted[tvalid ? pos : gs];
+        const char *xrow = x + (int64_t)tok * ld;
         if constexpr (KS_HOLD > 0) {
 #pragma unroll
             for (int u0 = 0; u0 < KS_HOLD; u0 += UNR) {
@@ -120,16 +172,19 @@ __device__ __forceinline__ void decode_shrink_slab(const ShrinkDParams &p, int s
             }
         } else
         for (int ks0 = ks_beg; ks0 < ks_end; ks0 += UNR) {
-            bf16x8_t a[UNR], b[UNR];
-            // A_e first: its address needs the group record only, the x rows also the
-            // token list -- the HBM requests must not queue behind that round trip
+            // every load of the batch is issued before the first one is used
+            uint4 ra[UNR], rb[UNR];
 #pragma unroll
-            for (int u = 0; u < UNR; ++u) a[u] = ldg_frag(arow, (ks0 + u) * 32 + kq, klen);   // past the wave's range: zero
+            for (int u = 0; u < UNR; ++u) ra[u] = ldg_raw(arow, (ks0 + u) * 32 + kq, klen);
 #pragma unroll
-            for (int u = 0; u < UNR; ++u) b[u] = ldg_frag(xrow, (ks0 + u) * 32 + kq, klen);
+            for (int u = 0; u < UNR; ++u) rb[u] = ldg_raw(xrow, (ks0 + u) * 32 + kq, klen);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int u = 0; u < UNR; ++u)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b[u], acc, 0, 0, 0);
+            for (int u = 0; u < UNR; ++u) {
+                const int k = (ks0 + u) * 32 + kq;   // past the wave's range: zero
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag_of(ra[u], k, klen), frag_of(rb[u], k, klen), acc,
+                                                              0, 0, 0);
+            }
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) red[wave][lane][i] = acc[i];
@@ -177,12 +232,13 @@ __global__ __launch_bounds__(SHRINK_WAVES * 64) void decode_base_shrink_kernel(L
                                                                              int n_base, int n_slabs)
 {
     extern __shared__ __align__(16) char smem[];
-    __shared__ float red[SHRINK_WAVES][64][4];
     if ((int)blockIdx.x < n_base) {
         linear_tile<CfgDecodeBase>(lp, (int)blockIdx.x, smem);
     } else {
+        // (the shrink role keeps its partial sums where the base role keeps its stages)
         const int idx = (int)blockIdx.x - n_base;
-        decode_shrink_slab<SHRINK_BATCH>(sp, idx % n_slabs, idx / n_slabs, red);
+        decode_shrink_slab<SHRINK_BATCH>(sp, idx % n_slabs, idx / n_slabs,
+                                         reinterpret_cast<float(*)[64][4]>(smem));
     }
 }
 
@@ -198,25 +254,6 @@ struct ExpandKParams {
 };
 
 constexpr int EXPAND_WAVES = 4;
-constexpr int EXPAND_RB = 4;                                  // 16-row blocks per wave
-constexpr int EXPAND_ROWS = EXPAND_WAVES * EXPAND_RB * 16;    // output rows per workgroup
-
-// Sum of the base partial results for four consecutive outputs of one token,
-// in part order (repeatable).  NSPLIT is a compile-time count so that all the
-// loads can be issued together, ahead of the adapter loads.
-template <int NSPLIT>
-__device__ __forceinline__ f32x4_t base_sum(const ExpandKParams &p, int tok, int o)
-{
-    const int64_t at = (int64_t)tok * p.d_out + o;
-    const int64_t plane = p.T * (int64_t)p.d_out;
-    f32x4_t part[NSPLIT];
-#pragma unroll
-    for (int s = 0; s < NSPLIT; ++s) part[s] = *reinterpret_cast<const f32x4_t *>(p.ybase + s * plane + at);
-    f32x4_t v = part[0];
-#pragma unroll
-    for (int s = 1; s < NSPLIT; ++s) v += part[s];
-    return v;
-}
 
 __device__ __forceinline__ void store_out(const ExpandKParams &p, int tok, int o, f32x4_t v)
 {
@@ -228,42 +265,53 @@ __device__ __forceinline__ void store_out(const ExpandKParams &p, int tok, int o
     }
 }
 
-// grid (ceil(d_out / EXPAND_ROWS), max_groups).  KS_HOLD > 0: r <= 32 * KS_HOLD,
-// the u fragments of a token block stay in registers and all B_e fragments of
-// the wave's rows are requested before the first MFMA; KS_HOLD == 0: any r.
-// The accumulators start from the base result, so y leaves in one pass.
-template <int KS_HOLD, int NSPLIT>
-__global__ __launch_bounds__(EXPAND_WAVES * 64) void decode_expand_kernel(ExpandKParams p)
+// One (expert group, slab of EXPAND_WAVES * RB * 16 output rows).  KS_HOLD > 0:
+// r <= 32 * KS_HOLD, the wave's RB x KS_HOLD fragments of B_e are requested at once
+// and held across the group's token blocks; KS_HOLD == 0: any r, fragment by
+// fragment.  The accumulators start from the base result, so y leaves in one pass.
+// FULL (wave-uniform): the expert's rank is exactly 32 * KS_HOLD, so no fragment
+// needs its tail cut off: loads take constant offsets from a few row addresses and
+// nothing is masked.
+// BY_POS: the rows of the base partial planes follow the by-expert token order (the
+// small-batch base product gathers its rows that way), so nothing a workgroup
+// loads depends on another load: adapter rows, u, base sums and token indices are
+// all requested at once, and the token index is needed only to place the result.
+// Phase 1 of a token block issues every load (for the first block also B_e, the HBM
+// traffic); phase 2 consumes them; a scheduling barrier between the two keeps all
+// loads ahead of the first wait.
+template <int KS_HOLD, int NSPLIT, bool BY_POS, int RB, bool FULL>
+__device__ __forceinline__ void expand_item(const ExpandKParams &p, int slab, int e, int gs, int ge, int r)
 {
-    const int g = blockIdx.y;
-    const int4 gm = p.grp_meta[g];   // records past the group count are empty
-    const int e = uniform(gm.x);
-    const int gs = uniform(gm.y), ge = uniform(gm.z);
-    if (ge <= gs) return;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int o_base = (blockIdx.x * EXPAND_WAVES + wave) * (EXPAND_RB * 16);
-    if (o_base >= p.d_out) return;
-    const int kq = (lane >> 4) * 8;
+    const int o_base = (slab * EXPAND_WAVES + wave) * (RB * 16);
     const int d_out = p.d_out;
+    if (o_base >= d_out) return;
+    const int kq = (lane >> 4) * 8;
     // rows of B_e and u are p.r long; the expert's own rank r (a multiple of 8) says how
     // much of them exists -- fragments past it are zero-filled, not read
-    const int r = min(p.r, uniform(gm.w));
     const int64_t ldb = (int64_t)p.r * 2;
     const char *bexp = p.B_stack + (int64_t)(e < 0 ? 0 : e) * d_out * ldb;
     const bool lora = e >= 0 && r > 0;
-
-    // the wave's rows of B_e do not depend on the token block: requested first
-    // (they are the HBM traffic), held across blocks
     constexpr int KH = KS_HOLD > 0 ? KS_HOLD : 1;
-    bf16x8_t a[EXPAND_RB][KH];
+    auto ld_frag = [&](const char *row, int ks) __attribute__((always_inline)) -> uint4 {
+        if constexpr (FULL) return *reinterpret_cast<const uint4 *>(row + ks * 64);   // row already at kq
+        else return ldg_raw(row, ks * 32 + kq, r);
+    };
+    auto as_frag = [&](uint4 v, int ks) __attribute__((always_inline)) -> bf16x8_t {
+        if constexpr (FULL) return __builtin_bit_cast(bf16x8_t, v);
+        else return frag_of(v, ks * 32 + kq, r);
+    };
+    const int koff = FULL ? kq * 2 : 0;
+
+    uint4 a[RB][KH];
     if constexpr (KS_HOLD > 0) {
         if (lora) {
 #pragma unroll
-            for (int c = 0; c < EXPAND_RB; ++c) {
+            for (int c = 0; c < RB; ++c) {
                 const int orow = o_base + c * 16 + (lane & 15);
-                const char *brow = bexp + (int64_t)(orow < d_out ? orow : 0) * ldb;
+                const char *brow = bexp + (int64_t)(orow < d_out ? orow : 0) * ldb + koff;
 #pragma unroll
-                for (int ks = 0; ks < KS_HOLD; ++ks) a[c][ks] = ldg_frag(brow, ks * 32 + kq, r);
+                for (int ks = 0; ks < KS_HOLD; ++ks) a[c][ks] = ld_frag(brow, ks);
             }
         }
     }
@@ -271,43 +319,67 @@ __global__ __launch_bounds__(EXPAND_WAVES * 64) void decode_expand_kernel(Expand
     for (int t0 = gs; t0 < ge; t0 += 16) {
         const int pos = t0 + (lane & 15);
         const bool tvalid = pos < ge;
-        const int tok = p.tok_sorted[tvalid ? pos : gs];
+        const int ps = tvalid ? pos : gs;
+        const int tok = p.tok_sorted[ps];
+        int brow_idx = ps;
+        if constexpr (!BY_POS) brow_idx = tok;
         // lane holds y[token = lane % 16][o_base + c*16 + 4*(lane/16) + i]; rows
         // past d_out read (and never store) the last valid group of four
-        f32x4_t acc[EXPAND_RB];
+        f32x4_t part[RB][NSPLIT];
+        {
+            const int64_t plane = p.T * (int64_t)d_out;
 #pragma unroll
-        for (int c = 0; c < EXPAND_RB; ++c) {
-            const int oo = o_base + c * 16 + 4 * (lane >> 4);
-            acc[c] = base_sum<NSPLIT>(p, tok, min(oo, d_out - 4));
+            for (int c = 0; c < RB; ++c) {
+                const int oo = min(o_base + c * 16 + 4 * (lane >> 4), d_out - 4);
+                const float *src = p.ybase + (int64_t)brow_idx * d_out + oo;
+#pragma unroll
+                for (int sp = 0; sp < NSPLIT; ++sp) part[c][sp] = *reinterpret_cast<const f32x4_t *>(src + sp * plane);
+            }
         }
-        if (lora) {
-            const char *uh = p.ug_hi + (int64_t)(tvalid ? pos : gs) * ldb;
-            const char *ul = p.ug_lo + (int64_t)(tvalid ? pos : gs) * ldb;
-            if constexpr (KS_HOLD > 0) {
-                bf16x8_t fh[KS_HOLD], fl[KS_HOLD];
+        const char *uh = p.ug_hi + (int64_t)ps * ldb + koff;
+        const char *ul = p.ug_lo + (int64_t)ps * ldb + koff;
+        uint4 rh[KH], rl[KH];
+        if constexpr (KS_HOLD > 0) {
+            if (lora) {
 #pragma unroll
                 for (int ks = 0; ks < KS_HOLD; ++ks) {
-                    fh[ks] = ldg_frag(uh, ks * 32 + kq, r);
-                    fl[ks] = ldg_frag(ul, ks * 32 + kq, r);
+                    rh[ks] = ld_frag(uh, ks);
+                    rl[ks] = ld_frag(ul, ks);
                 }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        f32x4_t acc[RB];
 #pragma unroll
-                for (int c = 0; c < EXPAND_RB; ++c)
+        for (int c = 0; c < RB; ++c) {
+            acc[c] = part[c][0];   // parts are added in order: repeatable
 #pragma unroll
-                    for (int ks = 0; ks < KS_HOLD; ++ks) {
-                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[c][ks], fh[ks], acc[c], 0, 0, 0);
-                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[c][ks], fl[ks], acc[c], 0, 0, 0);
+            for (int sp = 1; sp < NSPLIT; ++sp) acc[c] += part[c][sp];
+        }
+        if (lora) {
+            if constexpr (KS_HOLD > 0) {
+#pragma unroll
+                for (int ks = 0; ks < KS_HOLD; ++ks) {
+                    const bf16x8_t fh = as_frag(rh[ks], ks), fl = as_frag(rl[ks], ks);
+#pragma unroll
+                    for (int c = 0; c < RB; ++c) {
+                        const bf16x8_t fa = as_frag(a[c][ks], ks);
+                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fh, acc[c], 0, 0, 0);
+                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, fl, acc[c], 0, 0, 0);
                     }
+                }
             } else {
                 const int nks = (r + 31) / 32;
 #pragma unroll
-                for (int c = 0; c < EXPAND_RB; ++c) {
+                for (int c = 0; c < RB; ++c) {
                     const int orow = o_base + c * 16 + (lane & 15);
                     const char *brow = bexp + (int64_t)(orow < d_out ? orow : 0) * ldb;
                     for (int ks = 0; ks < nks; ++ks) {
                         const int k = ks * 32 + kq;
                         const bf16x8_t ab = ldg_frag(brow, k, r);
-                        const bf16x8_t bh = ldg_frag(uh, k, r);
-                        const bf16x8_t bl = ldg_frag(ul, k, r);
+                        const bf16x8_t bh = ldg_frag(p.ug_hi + (int64_t)ps * ldb, k, r);
+                        const bf16x8_t bl = ldg_frag(p.ug_lo + (int64_t)ps * ldb, k, r);
                         acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bh, acc[c], 0, 0, 0);
                         acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ab, bl, acc[c], 0, 0, 0);
                     }
@@ -315,11 +387,25 @@ __global__ __launch_bounds__(EXPAND_WAVES * 64) void decode_expand_kernel(Expand
             }
         }
 #pragma unroll
-        for (int c = 0; c < EXPAND_RB; ++c) {
+        for (int c = 0; c < RB; ++c) {
             const int oo = o_base + c * 16 + 4 * (lane >> 4);
             if (tvalid && oo < d_out) store_out(p, tok, oo, acc[c]);   // d_out % 4 == 0
         }
     }
+}
+
+// grid (ceil(d_out / (EXPAND_WAVES * RB * 16)), max_groups)
+template <int KS_HOLD, int NSPLIT, bool BY_POS, int RB>
+__global__ __launch_bounds__(EXPAND_WAVES * 64) void decode_expand_kernel(ExpandKParams p)
+{
+    const i32x4_t gm = sload_x4(p.grp_meta + blockIdx.y);   // records past the group count are empty
+    const int e = gm.x, gs = gm.y, ge = gm.z;
+    if (ge <= gs) return;
+    const int r = min(p.r, gm.w);
+    if (KS_HOLD > 0 && r == KS_HOLD * 32)
+        expand_item<KS_HOLD, NSPLIT, BY_POS, RB, true>(p, (int)blockIdx.x, e, gs, ge, r);
+    else
+        expand_item<KS_HOLD, NSPLIT, BY_POS, RB, false>(p, (int)blockIdx.x, e, gs, ge, r);
 }
 
 static ShrinkDParams shrink_params(const PlanView &pv, const DecodeArgs &d)
@@ -371,13 +457,14 @@ hipError_t launch_decode_base_shrink(const PlanView &pv, const DecodeArgs &d, hi
     const LinearArgs &a = d.lin;
     const DecodeBaseShape sh = decode_base_shape(pv.T, a.d_in, a.d_out);
     if (!sh.dma || sh.k_splits != d.k_splits) return hipErrorInvalidValue;
-    const LinearKParams lp = decode_base_params(pv, a, d.ybase, 1, sh);
+    const LinearKParams lp = decode_base_params(pv, a, d.ybase, 1, sh, pv.tok_sorted);   // rows in by-expert order
     const int n_slabs = (a.r + 15) / 16;
     const int64_t n_shrink = (int64_t)n_slabs * pv.max_groups;
-    const int64_t grid = (int64_t)sh.grid + n_shrink;
+    const int n_base = sh.grid;
+    const int64_t grid = (int64_t)n_base + n_shrink;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(decode_base_shrink_kernel, dim3((unsigned)grid), dim3(SHRINK_WAVES * 64),
-                       CfgDecodeBase::SMEM_BYTES, stream, lp, shrink_params(pv, d), sh.grid, n_slabs);
+                       CfgDecodeBase::SMEM_BYTES, stream, lp, shrink_params(pv, d), n_base, n_slabs);
     return hipGetLastError();
 }
 
@@ -390,10 +477,17 @@ hipError_t launch_decode_expand(const PlanView &pv, const DecodeArgs &d, hipStre
     p.ybase = d.ybase; p.y = (char *)a.y;
     p.tok_sorted = pv.tok_sorted; p.grp_meta = pv.grp_meta; p.n_groups = pv.n_groups;
     p.T = pv.T; p.d_out = a.d_out; p.r = a.r; p.k_splits = d.k_splits; p.y_f32 = a.y_f32;
-    dim3 grid((unsigned)((a.d_out + EXPAND_ROWS - 1) / EXPAND_ROWS), (unsigned)pv.max_groups);
+    constexpr int RB = 4;   // 16-row blocks per wave: 64 KB of B_e per workgroup and rank-128 adapter
+    const int rows = EXPAND_WAVES * RB * 16;
+    dim3 grid((unsigned)((a.d_out + rows - 1) / rows), (unsigned)pv.max_groups);
     const int nks = (a.r + 31) / 32;
-#define MOIN_EXPAND_S(KS, NS) \
-    hipLaunchKernelGGL((decode_expand_kernel<KS, NS>), grid, dim3(EXPAND_WAVES * 64), 0, stream, p)
+#define MOIN_EXPAND_R(KS, NS, BP) \
+    hipLaunchKernelGGL((decode_expand_kernel<KS, NS, BP, RB>), grid, dim3(EXPAND_WAVES * 64), 0, stream, p)
+#define MOIN_EXPAND_S(KS, NS)                                                                                  \
+    do {                                                                                                       \
+        if (d.ybase_by_pos) MOIN_EXPAND_R(KS, NS, true);                                                       \
+        else MOIN_EXPAND_R(KS, NS, false);                                                                     \
+    } while (0)
 #define MOIN_EXPAND(KS)                                  \
     switch (d.k_splits) {                                \
     case 1: MOIN_EXPAND_S(KS, 1); break;                 \
@@ -408,6 +502,7 @@ hipError_t launch_decode_expand(const PlanView &pv, const DecodeArgs &d, hipStre
     else MOIN_EXPAND(0)
 #undef MOIN_EXPAND
 #undef MOIN_EXPAND_S
+#undef MOIN_EXPAND_R
     return hipGetLastError();
 }
 

@@ -88,6 +88,7 @@ struct DecodeArgs {
     void *ug_hi, *ug_lo;   // [T, r] bf16, indexed by position in tok_sorted
     float *ybase;          // [k_splits, T, d_out] fp32 partial sums of x W^T over disjoint k ranges
     int k_splits;
+    int ybase_by_pos = 0;  // rows of ybase follow the plan's by-expert token order (else token order)
 };
 // Number of k ranges the decode base GEMM is cut into for this shape (>= 1).
 int decode_base_splits(int64_t T, int d_in, int d_out);

@@ -347,6 +347,7 @@ hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStr
     p.n_tiles_n = 0;
     p.y_f32 = a.y_f32;
     p.plain_tiles = 0;
+    p.gather = nullptr;
     p.k_splits = 1; p.kb_per_split = 0;
     return launch_linear_as<CfgMain>(p, pv.max_tiles, stream);
 }
@@ -394,7 +395,7 @@ DecodeBaseShape decode_base_shape(int64_t T, int d_in, int d_out) { return base_
 int decode_base_splits(int64_t T, int d_in, int d_out) { return decode_base_shape(T, d_in, d_out).k_splits; }
 
 LinearKParams decode_base_params(const PlanView &pv, const LinearArgs &a, void *out, int out_f32,
-                                 const DecodeBaseShape &sh)
+                                 const DecodeBaseShape &sh, const int *gather)
 {
     LinearKParams p;
     p.x = (const char *)a.x; p.W = (const char *)a.W; p.B_stack = nullptr;
@@ -407,15 +408,16 @@ LinearKParams decode_base_params(const PlanView &pv, const LinearArgs &a, void *
     p.n_tiles_n = sh.n_tiles_n;
     p.y_f32 = out_f32;
     p.plain_tiles = 1;
+    p.gather = gather;
     p.k_splits = sh.k_splits; p.kb_per_split = sh.kb_per_split;
     return p;
 }
 
 static hipError_t launch_plain(const PlanView &pv, const LinearArgs &a, void *out, int out_f32,
-                               const DecodeBaseShape &sh, hipStream_t stream)
+                               const DecodeBaseShape &sh, const int *gather, hipStream_t stream)
 {
     if (pv.T <= 0) return hipSuccess;
-    const LinearKParams p = decode_base_params(pv, a, out, out_f32, sh);
+    const LinearKParams p = decode_base_params(pv, a, out, out_f32, sh, gather);
     if (sh.dma)
         hipLaunchKernelGGL(linear_kernel<CfgDecodeBase>, dim3((unsigned)sh.grid), dim3(CfgDecodeBase::NT),
                            CfgDecodeBase::SMEM_BYTES, stream, p);
@@ -429,12 +431,12 @@ hipError_t launch_decode_base(const PlanView &pv, const DecodeArgs &d, hipStream
 {
     const DecodeBaseShape sh = decode_base_shape(pv.T, d.lin.d_in, d.lin.d_out);
     if (sh.k_splits != d.k_splits) return hipErrorInvalidValue;
-    return launch_plain(pv, d.lin, d.ybase, 1, sh, stream);
+    return launch_plain(pv, d.lin, d.ybase, 1, sh, pv.tok_sorted, stream);   // partial sums in by-expert order
 }
 
 hipError_t launch_decode_base_only(const PlanView &pv, const LinearArgs &a, hipStream_t stream)
 {
-    return launch_plain(pv, a, a.y, a.y_f32, base_shape(pv.T, a.d_in, a.d_out, false), stream);
+    return launch_plain(pv, a, a.y, a.y_f32, base_shape(pv.T, a.d_in, a.d_out, false), nullptr, stream);
 }
 
 }  // namespace moin

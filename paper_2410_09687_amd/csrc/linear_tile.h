@@ -16,6 +16,8 @@ struct LinearKParams {
     int n_tiles_n;
     int y_f32;
     int plain_tiles;         // 1: tiles are the regular grid over T, no adapters in-kernel
+    const int *gather;       // plain tiles only, or null: row i of the product is x[gather[i]] W^T (the
+                             // decode path's tokens in their by-expert order)
     int k_splits;            // plain tiles only: parts of the contraction range, one output plane each
     int kb_per_split;        // BK blocks per part
 };
@@ -79,8 +81,14 @@ __device__ __forceinline__ void linear_tile(const LinearKParams &p, int bid, cha
     if constexpr (C::IS_DMA) {
         const char *xa = p.x + (int64_t)row0 * ldx;
         const char *wb = p.W + (int64_t)n0 * ldx;
-        const auto la = C::template make_lanes<C::A_I>(rows);
+        auto la = C::template make_lanes<C::A_I>(rows);
         const auto lb = C::template make_lanes<C::B_I>(ncols);
+        if (p.plain_tiles && p.gather) {
+            // each lane's tile row becomes the token that stands at that position
+#pragma unroll
+            for (int j = 0; j < C::A_I; ++j) la.row[j] = (uint32_t)p.gather[row0 + (int)la.row[j]];
+            xa = p.x;
+        }
         // Block sequence: base blocks first, then the adapter blocks (the high
         // part of u, then the remainder); only uniform scalars differ between
         // them.  Written out here rather than through a callable: the operand
@@ -114,7 +122,13 @@ __device__ __forceinline__ void linear_tile(const LinearKParams &p, int bid, cha
         __syncthreads();
 #undef MOIN_ISSUE_BLOCK
     } else {
-        const auto vx = C::template make_view<C::A_CH>(p.x + (int64_t)row0 * ldx, ldx, rows);
+        auto vx = C::template make_view<C::A_CH>(p.x + (int64_t)row0 * ldx, ldx, rows);
+        if (p.plain_tiles && p.gather) {
+            vx.base = p.x;
+#pragma unroll
+            for (int i = 0; i < C::A_CH; ++i)
+                vx.rowoff[i] = (uint32_t)p.gather[row0 + (int)(vx.rowoff[i] / ldx)] * ldx;
+        }
         const auto vw = C::template make_view<C::B_CH>(p.W + (int64_t)n0 * ldx, ldx, ncols);
         const auto vuh = C::template make_view<C::A_CH>(uh, ldu, rows);
         const auto vul = C::template make_view<C::A_CH>(ul, ldu, rows);
@@ -174,7 +188,8 @@ struct DecodeBaseShape {
     int grid;           // workgroups, a multiple of 8
 };
 DecodeBaseShape decode_base_shape(int64_t T, int d_in, int d_out);
+// gather: null, or the plan's token order (rows of the result then follow that order)
 LinearKParams decode_base_params(const PlanView &pv, const LinearArgs &a, void *out, int out_f32,
-                                 const DecodeBaseShape &sh);
+                                 const DecodeBaseShape &sh, const int *gather);
 
 }  // namespace moin
