@@ -38,15 +38,25 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_FP8_TFLOPS = 5000.0    # MI355X dense FP8 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM-side bytes per launch of the dominant (linear) kernel on configs[1], from the
-# rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs summarised in
-# profiles/hbm_traffic_all_workloads.md: (2.0 * 212133 KiB + 1.0 * 135680 KiB) * 1024,
-# the factors being what the same counters read for a plain 1 GiB copy.
-LINEAR_KERNEL_TRAFFIC_BYTES = int((2.0 * 212133.3 + 1.0 * 135680.0) * 1024)
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_all_workloads.md")
 
 
-# the same for the quantised-base main kernel (profiles/hbm_traffic_quantised_base.md)
-MX_KERNEL_TRAFFIC_BYTES = int((2.0 * 113802.7 + 1.0 * 131072.0) * 1024)
+def measured_traffic(kernel, workload):
+    """HBM-side bytes per launch of `kernel` on `workload`, from the committed summary of the two
+    rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; KiB per dispatch, each scaled by what the same counter
+    reads for a plain copy of known size).  The summary carries one line per kernel of the form
+    `traffic: kernel=<name> workload=<name> bytes=<n>`; None when it has none for this pair (the
+    counters cannot be read from inside a timed run)."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                if line.startswith("traffic:"):
+                    kv = dict(tok.split("=", 1) for tok in line.split()[1:] if "=" in tok)
+                    if kv.get("kernel") == kernel and kv.get("workload") == workload:
+                        return int(float(kv["bytes"]))
+    except OSError:
+        pass
+    return None
 
 
 PREWARM_STEPS = 150   # untimed steps of the headline workload before its warm-up (clock ramp from idle)
@@ -68,6 +78,21 @@ def timed_region(fn, steps, warmup):
     return start.elapsed_time(stop) / steps, wall * 1e3 / steps
 
 
+def step_stats(fn, steps):
+    """Median and minimum of the single steps: a second pass over the same steps with an event between
+    every two of them (the mean that `value` is computed from comes from the undisturbed loop above)."""
+    n = max(int(steps), 50)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for i in range(n):
+        fn()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    t = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(n)])
+    return {"median_ms": float(np.median(t)), "min_ms": float(t.min()), "steps": n}
+
+
 def kernel_times(ctx, fn, steps):
     """Average launch duration per kernel id, from HIP events the library records
     around each launch on the launch stream."""
@@ -86,8 +111,18 @@ def kernel_times(ctx, fn, steps):
     return out
 
 
-def cpu_baseline_prefill(inp, target_s=12.0):
-    """Times the oracle, as it stands, on a bounded sample of the batch's rows."""
+def parity_stats(y_gpu, ref, rows=None):
+    """rel-Frobenius and max-abs error of the GPU output against oracle rows (fp64)."""
+    y = y_gpu if rows is None else y_gpu[torch.as_tensor(np.asarray(rows), device=y_gpu.device)]
+    y = y.float().cpu().double().numpy()
+    err = np.abs(y - ref)
+    return {"rel_fro": float(np.linalg.norm(y - ref) / max(np.linalg.norm(ref), 1e-30)),
+            "max_abs": float(err.max()) if err.size else 0.0, "rows": int(ref.shape[0])}
+
+
+def cpu_baseline_prefill(inp, y=None, target_s=12.0):
+    """Times the oracle, as it stands, on a bounded sample of the batch's rows; with y, the GPU's output for
+    the same batch, also reports its error against those oracle rows."""
     import oracle
     A, B, ids = wl.compact_stacks(inp)
     x, W = wl.bf16_bits(inp.x), wl.bf16_bits(inp.W)
@@ -103,11 +138,26 @@ def cpu_baseline_prefill(inp, target_s=12.0):
     n = int(min(w.T, max(len(probe), target_s / max(dt / len(probe), 1e-9))))
     rows = np.sort(rng.choice(w.T, size=n, replace=False))
     t0 = time.perf_counter()
-    oracle.lora_linear(x, off, ids, W, A, B, w.scale, rows=rows, threads=threads)
+    ref = oracle.lora_linear(x, off, ids, W, A, B, w.scale, rows=rows, threads=threads)
     dt = time.perf_counter() - t0
-    return {"value": per_row * n / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
-            "sample": f"{n} of {w.T} token rows of the same batch (all {w.d_out} outputs each), "
-                      f"fp64 oracle, {dt:.1f} s"}
+    out = {"value": per_row * n / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+           "sample": f"{n} of {w.T} token rows of the same batch (all {w.d_out} outputs each), "
+                     f"fp64 oracle, {dt:.1f} s"}
+    if y is not None:
+        out["gpu_vs_oracle"] = parity_stats(y, ref, rows)
+    return out
+
+
+def oracle_on_rows(inp, rows, y):
+    """Oracle seconds and GPU-vs-oracle error for the given token rows of a batch."""
+    import oracle
+    A, B, ids = wl.compact_stacks(inp)
+    threads = min(oracle.max_threads(), os.cpu_count() or 1)
+    t0 = time.perf_counter()
+    ref = oracle.lora_linear(wl.bf16_bits(inp.x), inp.seq_offsets.cpu().numpy(), ids, wl.bf16_bits(inp.W), A, B,
+                             inp.wl.scale, rows=rows, threads=threads)
+    dt = time.perf_counter() - t0
+    return dt, threads, parity_stats(y, ref, rows)
 
 
 def bench_ceilings(ctx):
@@ -142,7 +192,8 @@ def bench_ceilings(ctx):
             "read_GBps": buf.numel() * 4.0 / (kt["probe_read"]["avg_ms"] * 1e-3) / 1e9,
             "what": "MFMA-only loops (v_mfma_f32_32x32x16_bf16 on N(0,1) operands; "
                     "v_mfma_scale_f32_32x32x64_f8f6f4 on their MXFP8 codes; 2 workgroups of 8 waves per "
-                    "compute unit); streaming read of 1 GiB (16-byte loads, 8 in flight per thread)"}
+                    "compute unit); streaming read of 1 GiB (two workgroups per compute unit take 32 KB chunks in turn, "
+                    "non-temporal 16-byte loads, 8 in flight per thread: the fastest of the shapes swept)"}
 
 
 def bench_prefill(ctx, steps, warmup, with_cpu):
@@ -154,9 +205,14 @@ def bench_prefill(ctx, steps, warmup, with_cpu):
     slots = torch.arange(w.E, dtype=torch.int32, device="cuda")
     y = torch.empty((w.T, w.d_out), dtype=torch.bfloat16, device="cuda")
 
+    # a serving loop: every batch is routed against the same topic table, and says so
+    route_out = (torch.empty(w.S, dtype=torch.int32, device="cuda"), None,
+                 torch.empty(w.E, dtype=torch.int32, device="cuda"))
+
     def step():
         eids, _, _ = moin.moin_route(ctx, rin.emb, rin.centroids, slot_of_centroid=slots,
-                                     want_centroid_ids=False, want_counts=True)
+                                     want_centroid_ids=False, want_counts=True, out=route_out,
+                                     same_centroids=True)
         moin.moin_lora_linear(ctx, inp.x, inp.seq_offsets, eids, inp.W, inp.A_stack, inp.B_stack,
                               w.scale, out=y)
 
@@ -168,6 +224,7 @@ def bench_prefill(ctx, steps, warmup, with_cpu):
     torch.cuda.synchronize()
     ms, wall_ms = timed_region(step, steps, warmup)
     ctx.check()
+    stats = step_stats(step, steps)
     flops = w.flops() + rw.flops()
     kt = kernel_times(ctx, step, steps)
     lin = kt.get("linear", {"avg_ms": float("nan")})
@@ -180,22 +237,31 @@ def bench_prefill(ctx, steps, warmup, with_cpu):
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[1]: q_proj prefill 2048->2048, r=64, E=500, 64 seq x 512 tok, "
                                "uniform expert ids; step = route(64x768 vs 500 centroids)+histogram+"
-                               "slot map+group-by-expert+routed LoRA linear",
+                               "slot map+group-by-expert+routed LoRA linear.  `value` is this workload's (the "
+                               "one the metric's prefill figure is quoted on); the largest single-GPU "
+                               "configuration, configs[4], is reported under `layer`, decode (configs[2], per "
+                               "projection, the batch's plan built once outside the timed call as one plan "
+                               "serves every projection of every layer) under `decode`, configs[3] under `router`",
+                   "ms_per_step_median": stats["median_ms"], "ms_per_step_min": stats["min_ms"],
                    "tokens_per_step": w.T, "tokens_per_s": w.T / (ms * 1e-3),
                    "frac_of_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                    "wall_ms_per_step": wall_ms, "prewarm_steps": PREWARM_STEPS},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                     "traffic": LINEAR_KERNEL_TRAFFIC_BYTES, "kernel": "linear_stream_kernel (base GEMM + fused expand)",
+                     "traffic": measured_traffic("linear_stream_kernel", "c1"),
+                     "kernel": "linear_stream_kernel (base GEMM + fused expand)",
                      "avg_launch_ms": lin["avg_ms"]},
         "kernels": kt,
     }
     if with_cpu:
-        res["cpu_baseline"] = cpu_baseline_prefill(inp)
+        # the routed ids of the step are inp.expert_ids' topics only if the route says so: take them from it
+        eids = route_out[0].clone()
+        chk = wl.LinearInputs(inp.wl, inp.x, inp.W, inp.A_stack, inp.B_stack, inp.seq_offsets, eids)
+        res["cpu_baseline"] = cpu_baseline_prefill(chk, y)
     return res
 
 
-def bench_decode(ctx, steps, warmup, n_draws=8):
+def bench_decode(ctx, steps, warmup, n_draws=8, with_cpu=False):
     """configs[2]: three MLP projections, 256 single-token sequences, Zipf(1.1)
     ids over 5000 experts.  Rotates through independent id draws so the adapter
     working set (>= 2 GB) exceeds the 256 MB last-level cache."""
@@ -225,9 +291,23 @@ def bench_decode(ctx, steps, warmup, n_draws=8):
         ms, _ = timed_region(step, n, max(warmup, n_draws))
         ctx.check()
         state["i"] = 0
+        stats = step_stats(step, n)
+        state["i"] = 0
         kt = kernel_times(ctx, step, n)
         avg_bytes = float(np.mean(bytes_alg))
-        out[w.name] = {"ms_per_call": ms, "algorithmic_bytes": avg_bytes,
+        cpu = None
+        if with_cpu:
+            # the whole batch of draw 0 through the oracle: its time, and the GPU's error against it
+            state["i"] = 0
+            step()
+            torch.cuda.synchronize()
+            chk = wl.LinearInputs(inp.wl, inp.x, inp.W, inp.A_stack, inp.B_stack, inp.seq_offsets, draws[0])
+            dt, threads, par = oracle_on_rows(chk, None, y)
+            cpu = {"value": w.flops() / dt / 1e12, "unit": "TFLOP/s", "seconds": dt, "cores": threads,
+                   "kind": "oracle", "sample": f"all {w.T} rows of one batch", "gpu_vs_oracle": par}
+        out[w.name] = {"ms_per_call": ms, "ms_per_call_median": stats["median_ms"], "ms_per_call_min": stats["min_ms"],
+                       "plan": "built once per batch outside the timed call", "cpu_baseline": cpu,
+                       "algorithmic_bytes": avg_bytes,
                        "GBps": avg_bytes / (ms * 1e-3) / 1e9,
                        "frac_of_hbm_peak": avg_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                        "roofline": {"bound": "hbm", "achieved": avg_bytes / (ms * 1e-3) / 1e9,
@@ -241,15 +321,42 @@ def bench_decode(ctx, steps, warmup, n_draws=8):
     return out
 
 
-def bench_router(ctx, steps, warmup):
+def cpu_baseline_router(rin, rw, cids):
+    """The oracle on every 16th query (all K centroids each), its time extrapolated linearly to the whole
+    batch; the GPU's ids on those queries against it (a different id counts as a mismatch unless its
+    squared distance, in fp64, is within 1e-4 relative of the minimum)."""
+    import oracle
+    sel = np.arange(0, rw.N, 16)
+    q = wl.bf16_bits(rin.emb[::16].contiguous())
+    c = wl.bf16_bits(rin.centroids)
+    t0 = time.perf_counter()
+    ref, best, _ = oracle.route(q, c, want_gaps=True)
+    dt = time.perf_counter() - t0
+    got = cids.cpu().numpy()[sel]
+    bad = np.flatnonzero(got != ref)
+    outside = 0
+    if bad.size:
+        d = oracle.dist2(q, c, bad, got[bad])
+        outside = int((d > np.where(best[bad] > 0, best[bad] * (1 + 1e-4), 1e-30)).sum())
+    return {"value": 2.0 * sel.size * rw.K * rw.D / dt / 1e12, "unit": "TFLOP/s", "seconds_on_sample": dt,
+            "seconds_whole_batch_extrapolated": dt * rw.N / sel.size, "cores": oracle.max_threads(),
+            "kind": "oracle", "sample": f"every 16th query ({sel.size} of {rw.N}), all {rw.K} centroids",
+            "gpu_vs_oracle": {"queries": int(sel.size), "ids_differing_inside_the_near_tie_band": int(bad.size) - outside,
+                              "ids_differing_outside_it": outside}}
+
+
+def bench_router(ctx, steps, warmup, with_cpu=False):
     rw = wl.config_router()
     rin = wl.make_route_inputs(rw, "cuda")
+    outs = (torch.empty(rw.N, dtype=torch.int32, device="cuda"), torch.empty(rw.N, dtype=torch.int32, device="cuda"),
+            torch.empty(rw.K, dtype=torch.int32, device="cuda"))
 
     def step():
-        moin.moin_route(ctx, rin.emb, rin.centroids, want_counts=True)
+        moin.moin_route(ctx, rin.emb, rin.centroids, want_counts=True, out=outs)
 
     ms, _ = timed_region(step, steps, warmup)
     ctx.check()
+    stats = step_stats(step, steps)
     kt = kernel_times(ctx, step, steps)
     tf = rw.flops() / (ms * 1e-3) / 1e12
     # request-time batch: the four nearest topics of 4096 queries ("Future Works", creating new experts on the fly)
@@ -260,8 +367,11 @@ def bench_router(ctx, steps, warmup):
 
     tms, _ = timed_region(topk, 10, 2)
     ctx.check()
-    return {"ms_per_call": ms, "queries_per_s": rw.N / (ms * 1e-3), "TFLOPs": tf,
-            "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS,
+    cpu = cpu_baseline_router(rin, rw, outs[1]) if with_cpu else None
+    return {"ms_per_call": ms, "ms_per_call_median": stats["median_ms"], "ms_per_call_min": stats["min_ms"],
+            "queries_per_s": rw.N / (ms * 1e-3), "TFLOPs": tf,
+            "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS, "cpu_baseline": cpu,
+            "traffic": measured_traffic("route_stream_kernel", "c3"),
             "top4_of_4096_queries": {"ms_per_call": tms, "queries_per_s": 4096 / (tms * 1e-3)}, "kernels": kt}
 
 
@@ -368,7 +478,7 @@ def bench_mx(ctx, steps, warmup):
             "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s",
                          "frac": achieved / PEAK_FP8_TFLOPS,
                          "frac_of_mixed_peak": t_peak / (lin["avg_ms"] * 1e-3),
-                         "traffic": MX_KERNEL_TRAFFIC_BYTES,
+                         "traffic": measured_traffic("linear_stream4_kernel", "c1_mx"),
                          "kernel": "linear_mx_stream_kernel (MXFP8 base + bf16 adapter term)",
                          "avg_launch_ms": lin["avg_ms"]},
             "shrink_and_quantise_x": {"avg_launch_ms": qt["avg_ms"], "algorithmic_bytes": q_bytes,
@@ -493,7 +603,21 @@ def bench_cache(ctx, n_batches=48, n_slots=512):
             "ms_per_batch_all_resident": ms_res / len(slots_dev), "overflows": d["overflows"]}
 
 
-def bench_layer(ctx, steps, warmup):
+def rows_per_sequence(off, seed, n_edge=16, n_random=32):
+    """The first and last n_edge rows of every sequence and n_random seeded rows from its middle."""
+    rng = np.random.default_rng(seed)
+    picks = []
+    for s in range(len(off) - 1):
+        lo, hi = int(off[s]), int(off[s + 1])
+        if hi - lo <= 2 * n_edge + n_random:
+            picks.append(np.arange(lo, hi))
+            continue
+        picks += [np.arange(lo, lo + n_edge), np.arange(hi - n_edge, hi),
+                  rng.choice(np.arange(lo + n_edge, hi - n_edge), size=n_random, replace=False)]
+    return np.unique(np.concatenate(picks)).astype(np.int64)
+
+
+def bench_layer(ctx, steps, warmup, with_cpu=False):
     """configs[4]: seven chained projections, r=128, E=5000, 32 x 2048 tokens, Zipf(1.5)."""
     wls = wl.config_layer()
     T = wls[0].T
@@ -528,14 +652,51 @@ def bench_layer(ctx, steps, warmup):
 
     ms, _ = timed_region(step, steps, warmup)
     ctx.check()
+    stats = step_stats(step, steps)
     kt = kernel_times(ctx, step, steps)
+    # every projection on its own: launch durations by projection (the layer's breakdown)
+    per_proj = {}
+    plan.build(off, eids, T, wls[0].E)
+    for n, i in inputs.items():
+        x = h0 if src[n] is None else outs[src[n]]
+
+        def one():
+            moin.moin_lora_linear_planned(ctx, plan, x, i.W, i.A_stack, i.B_stack, i.wl.scale, out=outs[n])
+
+        one()
+        k1 = kernel_times(ctx, one, 5)
+        fl = i.wl.flops()
+        t_ms = sum(v["avg_ms"] for v in k1.values())
+        per_proj[n] = {"shape": f"{i.wl.d_in}->{i.wl.d_out}", "shrink_us": k1.get("shrink", {"avg_ms": 0})["avg_ms"] * 1e3,
+                       "linear_us": k1.get("linear", {"avg_ms": 0})["avg_ms"] * 1e3,
+                       "TFLOPs": fl / (t_ms * 1e-3) / 1e12, "frac_of_bf16_peak": fl / (t_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
     ms_single, _ = timed_region(step_single, steps, warmup)
     ctx.check()
     flops = sum(w.flops() for w in wls)
     tf = flops / (ms * 1e-3) / 1e12
+    cpu = None
+    if with_cpu:
+        # 64 rows of every sequence through the oracle, projection by projection on the GPU's actual input
+        step()
+        torch.cuda.synchronize()
+        rows = rows_per_sequence(off.cpu().numpy(), seed=2)
+        secs, par, threads = 0.0, {}, 0
+        for n, i in inputs.items():
+            x = h0 if src[n] is None else outs[src[n]]
+            chk = wl.LinearInputs(i.wl, x, i.W, i.A_stack, i.B_stack, off, eids)
+            dt, threads, p1 = oracle_on_rows(chk, rows, outs[n])
+            secs += dt
+            par[n] = p1
+        sample_flops = flops * rows.size / T
+        cpu = {"value": sample_flops / secs / 1e12, "unit": "TFLOP/s", "seconds_on_sample": secs,
+               "seconds_whole_layer_extrapolated": secs * T / rows.size, "cores": threads, "kind": "oracle",
+               "sample": f"64 rows of each of the {wls[0].S} sequences (first 16, last 16, 32 seeded), all outputs, "
+                         f"all 7 projections ({rows.size} of {T} rows)", "gpu_vs_oracle": par}
     plan.close()
-    return {"ms_per_layer": ms, "TFLOPs": tf, "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS,
-            "tokens_per_s": T / (ms * 1e-3), "ms_per_layer_seven_single_calls": ms_single, "kernels": kt}
+    return {"ms_per_layer": ms, "ms_per_layer_median": stats["median_ms"], "ms_per_layer_min": stats["min_ms"],
+            "TFLOPs": tf, "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS,
+            "tokens_per_s": T / (ms * 1e-3), "ms_per_layer_seven_single_calls": ms_single, "per_projection": per_proj,
+            "cpu_baseline": cpu, "kernels": kt}
 
 
 def bench_decode_mx(ctx, steps, warmup, n_draws=8):
@@ -654,14 +815,14 @@ def main():
         res["roofline"]["frac_of_measured_mfma_ceiling"] = res["roofline"]["achieved"] / c["mfma_bf16_TFLOPs"]
     extra = [s for s in args.also.split(",") if s and s != "none"]
     if "decode" in extra:
-        res["decode"] = bench_decode(ctx, args.steps, args.warmup)
+        res["decode"] = bench_decode(ctx, args.steps, args.warmup, with_cpu=not args.no_cpu_baseline)
         if "measured_ceilings" in res:
             for d in res["decode"].values():
                 d["roofline"]["frac_of_measured_read_ceiling"] = d["roofline"]["achieved"] / c["read_GBps"]
     if "router" in extra:
-        res["router"] = bench_router(ctx, max(5, args.steps // 5), 2)
+        res["router"] = bench_router(ctx, max(5, args.steps // 5), 2, with_cpu=not args.no_cpu_baseline)
     if "layer" in extra:
-        res["layer"] = bench_layer(ctx, max(5, args.steps // 5), 2)
+        res["layer"] = bench_layer(ctx, max(5, args.steps // 5), 2, with_cpu=not args.no_cpu_baseline)
     if "kmeans" in extra:
         res["kmeans"] = bench_kmeans(ctx, max(5, args.steps // 5), 2)
     if "measured_ceilings" in res:

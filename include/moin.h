@@ -50,6 +50,12 @@ typedef enum {
 
 /* moin_route flags */
 #define MOIN_ROUTE_RETAINED_ONLY 1u /* search only centroids whose slot is >= 0 */
+#define MOIN_ROUTE_SAME_CENTROIDS 2u /* the caller vouches that centroids (and, with
+                                        MOIN_ROUTE_RETAINED_ONLY, slot_of_centroid) hold the
+                                        same bits as in the previous moin_route call on this
+                                        context with the same pointers and shapes: the
+                                        centroid norms kept from that call are used again.
+                                        Ignored when there is no such call to go by. */
 
 /* Which kernel a timing slot refers to (moin_timing_*). */
 typedef enum {
@@ -104,7 +110,10 @@ int moin_check(moin_ctx *ctx, void *stream);
  *   emb              [N, D] row-major, dt (fp32 or bf16)
  *   centroids        [K, D] row-major, same dt
  *   slot_of_centroid [K] int32 or NULL: adapter slot of each centroid, -1 = none
- *   flags            0 or MOIN_ROUTE_RETAINED_ONLY (needs slot_of_centroid)
+ *   flags            0, MOIN_ROUTE_RETAINED_ONLY (needs slot_of_centroid) and / or
+ *                    MOIN_ROUTE_SAME_CENTROIDS (a serving loop routes every batch against
+ *                    the same topic table; request-sized batches -- bf16, D a multiple of
+ *                    64, N <= 4096 -- then take a single kernel launch)
  *   expert_ids       [N] int32 out or NULL: slot_of_centroid[centroid] (or the
  *                    centroid index itself when slot_of_centroid is NULL)
  *   centroid_ids     [N] int32 out or NULL: argmin centroid index

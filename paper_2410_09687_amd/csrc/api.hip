@@ -55,6 +55,16 @@ struct moin_ctx {
     size_t ws_bytes;
     int ws_pinned;                  // a captured graph may hold ws's address (see moin_plan::pinned)
     std::vector<void *> ws_retired;
+    // small routing batches: centroid norms, packed minima and the arrival counter in a block of their
+    // own, which the kernel leaves clean for the next call; `route_key` says whose norms it holds
+    void *route_buf;
+    size_t route_bytes;
+    int route_pinned;
+    std::vector<void *> route_retired;
+    struct {
+        const void *cent, *slot;
+        int K, D, dt, retained, valid;
+    } route_key;
     moin_plan *own_plan;
     int act;   // activation between the adapter's two layers (MOIN_ACT_*)
     int timing;
@@ -69,6 +79,7 @@ struct moin_ctx {
 // code the array's name is only a handle for hipGetSymbolAddress; the address the
 // kernels get is looked up once per device (moin_create, with that device
 // current) and kept in g_scratch_ptr.
+constexpr int ROUTE_SELF_CLEAN_MAX_K = 65536;   // one workgroup zeroes the histogram in these calls
 constexpr size_t SCRATCH_BYTES = 1u << 20;
 static __device__ __align__(256) unsigned char scratch[SCRATCH_BYTES];
 constexpr int MAX_DEVICES = 64;
@@ -525,6 +536,10 @@ int moin_create(moin_ctx **out, int device)
     ctx->ws = nullptr;
     ctx->ws_bytes = 0;
     ctx->ws_pinned = 0;
+    ctx->route_buf = nullptr;
+    ctx->route_bytes = 0;
+    ctx->route_pinned = 0;
+    ctx->route_key.valid = 0;
     ctx->own_plan = nullptr;
     ctx->act = MOIN_ACT_NONE;
     ctx->timing = 0;
@@ -569,6 +584,8 @@ void moin_destroy(moin_ctx *ctx)
     if (ctx->own_plan) moin_plan_destroy(ctx->own_plan);
     if (ctx->ws) (void)hipFree(ctx->ws);
     for (void *p : ctx->ws_retired) (void)hipFree(p);
+    if (ctx->route_buf) (void)hipFree(ctx->route_buf);
+    for (void *p : ctx->route_retired) (void)hipFree(p);
     if (ctx->err_word) (void)hipFree(ctx->err_word);
     delete ctx;
 }
@@ -611,7 +628,7 @@ static int validate_route(moin_ctx *ctx, const void *emb, const void *centroids,
 {
     if (!ctx || N < 0 || K <= 0 || D <= 0) return MOIN_EINVAL;
     if (dt != MOIN_BF16 && dt != MOIN_F32) return MOIN_EINVAL;
-    if (flags & ~MOIN_ROUTE_RETAINED_ONLY) return MOIN_EINVAL;
+    if (flags & ~(MOIN_ROUTE_RETAINED_ONLY | MOIN_ROUTE_SAME_CENTROIDS)) return MOIN_EINVAL;
     if ((flags & MOIN_ROUTE_RETAINED_ONLY) && !slot_of_centroid) return MOIN_EINVAL;
     if (!centroids) return MOIN_EINVAL;
     if (N > 0 && !emb) return MOIN_EINVAL;
@@ -648,7 +665,7 @@ static RouteScratch route_scratch(int64_t N, int32_t K, int32_t D, moin_dtype dt
 static int route_launches(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N, int32_t K,
                           int32_t D, moin_dtype dt, const int32_t *slot_of_centroid, uint32_t flags,
                           int32_t *expert_ids, int32_t *centroid_ids, int32_t *counts, char *w,
-                          const RouteScratch &L, bool need_cid, bool record, hipStream_t st)
+                          const RouteScratch &L, bool need_cid, bool record, hipStream_t st, int self_clean = 0)
 {
     RouteArgs a;
     a.emb = emb; a.cent = centroids; a.N = N; a.K = K; a.D = D;
@@ -663,13 +680,16 @@ static int route_launches(moin_ctx *ctx, const void *emb, const void *centroids,
     a.cid = centroid_ids ? centroid_ids : (need_cid ? reinterpret_cast<int *>(w + L.cid) : nullptr);
     a.expert_ids = expert_ids;
     a.counts = counts;
+    a.self_clean = self_clean ? 1 : 0;   // 1: norms kernel + self-cleaning kernel, 2: the norms in w are current
 
     auto run = [&](int kernel, auto launch) {
         return record ? timed(ctx, kernel, st, launch) : launch();
     };
     const bool routed = N > 0 && (a.cid || a.expert_ids);
     if (routed) {
-        if (run(MOIN_K_ROUTE_AUX, [&] { return launch_centroid_norms(a, st); }) != hipSuccess) return MOIN_EHIP;
+        if (self_clean != 2 &&
+            run(MOIN_K_ROUTE_AUX, [&] { return launch_centroid_norms(a, st); }) != hipSuccess)
+            return MOIN_EHIP;
         if (run(MOIN_K_ROUTE, [&] { return launch_route(a, st); }) != hipSuccess) return MOIN_EHIP;
     }
     if (counts && !(routed && route_tallies_counts(a))) {
@@ -714,7 +734,62 @@ int moin_route(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N,
     if (!guard.ok) return MOIN_EHIP;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool need_cid = counts && !centroid_ids && N > 0;
-    const RouteScratch L = route_scratch(N, K, D, dt, need_cid);
+    RouteScratch L = route_scratch(N, K, D, dt, need_cid);
+    if (N > 0 && (expert_ids || centroid_ids) && K <= ROUTE_SELF_CLEAN_MAX_K &&
+        route_small_batch(N, K, D, dt == MOIN_BF16)) {
+        // (minima and counter first, at offsets that do not move with K: they must stay clean)
+        const size_t cn_bytes = L.cinit - L.cnorm;
+        L.best = 0;
+        L.arrivals = (size_t)ROUTE_SMALL_MAX_N * 8;
+        L.cnorm = L.arrivals + 256;
+        L.cinit = L.cnorm + cn_bytes;
+        L.cid = L.cinit + cn_bytes;
+        L.total = L.cid + (need_cid ? align_up((size_t)N * 4, 256) : 0);
+        // Request-sized batches: one launch.  Norms, packed minima and the arrival counter live in a
+        // block of the context's own (the shared workspace is overwritten by the linear calls in
+        // between); the kernel's finishing workgroup leaves minima and counter clean and zeroes the
+        // histogram itself, and the norms are computed again only if the caller does not vouch for the
+        // table (or it is not the table they were computed from).
+        const bool cap = capturing(st);
+        if (L.total > ctx->route_bytes) {
+            if (cap) return MOIN_ECAPTURE;
+            void *p = nullptr;
+            const size_t want = align_up(L.total, 4096);
+            if (hipMalloc(&p, want) != hipSuccess) {
+                (void)hipGetLastError();
+                return MOIN_ENOMEM;
+            }
+            if (ctx->route_buf) {
+                if (ctx->route_pinned) ctx->route_retired.push_back(ctx->route_buf);
+                else if (hipFree(ctx->route_buf) != hipSuccess) {
+                    (void)hipFree(p);
+                    return MOIN_EHIP;
+                }
+            }
+            ctx->route_buf = p;
+            ctx->route_bytes = want;
+            ctx->route_pinned = 0;
+            ctx->route_key.valid = 0;
+            // minima at "nothing won yet", counter at zero (the kernels keep them so from here on)
+            char *b = static_cast<char *>(p);
+            if (hipMemsetAsync(b + L.best, 0xFF, L.arrivals - L.best, st) != hipSuccess ||
+                hipMemsetAsync(b + L.arrivals, 0, 256, st) != hipSuccess)
+                return MOIN_EHIP;
+        }
+        if (cap) ctx->route_pinned = 1;
+        const int retained = (flags & MOIN_ROUTE_RETAINED_ONLY) ? 1 : 0;
+        const bool same = ctx->route_key.valid && ctx->route_key.cent == centroids &&
+                          ctx->route_key.slot == (retained ? slot_of_centroid : nullptr) && ctx->route_key.K == K &&
+                          ctx->route_key.D == D && ctx->route_key.dt == (int)dt && ctx->route_key.retained == retained;
+        const bool reuse = (flags & MOIN_ROUTE_SAME_CENTROIDS) && same;
+        ctx->route_key.cent = centroids;
+        ctx->route_key.slot = retained ? slot_of_centroid : nullptr;
+        ctx->route_key.K = K; ctx->route_key.D = D; ctx->route_key.dt = (int)dt;
+        ctx->route_key.retained = retained; ctx->route_key.valid = 1;
+        return route_launches(ctx, emb, centroids, N, K, D, dt, slot_of_centroid, flags, expert_ids,
+                              centroid_ids, counts, static_cast<char *>(ctx->route_buf), L, need_cid, true, st,
+                              reuse ? 2 : 1);
+    }
     const int rc = ensure_ws(ctx, L.total, st);
     if (rc != MOIN_OK) return rc;
     return route_launches(ctx, emb, centroids, N, K, D, dt, slot_of_centroid, flags, expert_ids,

@@ -121,8 +121,12 @@ struct RouteArgs {
     int *arrivals;             // [1] workspace
     int *counts;               // [K] or null: zeroed by the norms kernel
     int group;                 // route_stream_group() of the call
+    int self_clean = 0;        // small batches: best / arrivals are kept clean between calls by the kernel
+                               // itself, counts are zeroed by its finishing workgroup (no reset launch)
 };
 constexpr int ROUTE_SMALL_MAX_N = 4096;  // up to here the K range is split across workgroups
+// true for the batches the small-batch kernel takes (bf16, D a multiple of 64, N <= ROUTE_SMALL_MAX_N)
+bool route_small_batch(int64_t N, int K, int D, int is_bf16);
 // Workgroups that share one query tile in the large-batch bf16 kernel (1: none).
 int route_stream_group(int64_t N, int K, int D, int is_bf16);
 hipError_t launch_centroid_norms(const RouteArgs &a, hipStream_t stream);

@@ -5,6 +5,8 @@
 // constants), and a plain streaming read.  Measurement aids, not steps of the
 // method.
 #include "gemm_core.h"
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace moin {
@@ -81,24 +83,36 @@ __global__ __launch_bounds__(PROBE_BLOCK) void probe_mfma_mx_kernel(const uint4 
     out[tid] = s;
 }
 
-// Every 16-byte word of src once, eight independent loads per thread in flight;
-// out[tid] = sum (mod 2^32) of the 32-bit words the thread read.
-__global__ __launch_bounds__(256) void probe_read_kernel(const uint4 *__restrict__ src, int64_t n16,
-                                                         uint32_t *__restrict__ out)
+// Every 16-byte word of src once: workgroups take 32 KB chunks in turn, a wave instruction
+// reads 1 KB of consecutive bytes, eight loads per thread in flight, non-temporal (each byte
+// is used once) -- the shape that read fastest in a sweep over strides, chunk sizes, depths
+// and workgroup counts on this part (a grid-strided read of the same buffer is ~20 % slower,
+// plain loads ~12 %).  out[tid] = sum (mod 2^32) of the 32-bit words the thread read.
+typedef uint32_t probe_u32x4_t __attribute__((ext_vector_type(4)));
+// Only the first `readers` workgroups read (two per compute unit: more of them read slower); the others
+// just report zero, so that every element of out is written.
+__global__ __launch_bounds__(256) void probe_read_kernel(const probe_u32x4_t *__restrict__ src, int64_t n16,
+                                                         uint32_t *__restrict__ out, int readers)
 {
+    constexpr int64_t CHUNK = 2048;   // 16-byte words per chunk
     const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * 256;
     uint32_t s = 0;
-    int64_t i = tid;
-    for (; i + 7 * stride < n16; i += 8 * stride) {
-        uint4 v[8];
+    const int64_t full = n16 / CHUNK;
+    if ((int)blockIdx.x >= readers) {
+        out[tid] = 0;
+        return;
+    }
+    for (int64_t c = blockIdx.x; c < full; c += readers) {
+        const probe_u32x4_t *p = src + c * CHUNK + threadIdx.x;
+        probe_u32x4_t v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = src[i + u * stride];
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(p + u * 256);
 #pragma unroll
         for (int u = 0; u < 8; ++u) s += v[u].x + v[u].y + v[u].z + v[u].w;
     }
-    for (; i < n16; i += stride) {
-        const uint4 v = src[i];
+    // what does not fill a chunk
+    for (int64_t i = full * CHUNK + tid; i < n16; i += (int64_t)readers * 256) {
+        const probe_u32x4_t v = src[i];
         s += v.x + v.y + v.z + v.w;
     }
     out[tid] = s;
@@ -129,8 +143,9 @@ hipError_t launch_probe_mfma_mx(const void *codes, int64_t n_bytes, int iters, f
 hipError_t launch_probe_read(const void *src, int64_t n_bytes, uint32_t *out, hipStream_t stream)
 {
     const int grid = (int)(probe_out_len() / 256);
-    hipLaunchKernelGGL(probe_read_kernel, dim3(grid), dim3(256), 0, stream, reinterpret_cast<const uint4 *>(src),
-                       n_bytes / 16, out);
+    const int readers = std::min(grid, compute_units() * 2);
+    hipLaunchKernelGGL(probe_read_kernel, dim3(grid), dim3(256), 0, stream,
+                       reinterpret_cast<const probe_u32x4_t *>(src), n_bytes / 16, out, readers);
     return hipGetLastError();
 }
 

@@ -35,6 +35,8 @@ struct RouteKParams {
     int64_t N;
     int K, D;
     int group;            // streaming kernel: workgroups that share one query tile
+    int self_clean;       // small-batch kernel: best / arrivals are clean on entry and are left clean
+                          // (the finishing workgroup resets them and zeroes counts before its tally)
 };
 
 __device__ __forceinline__ bool lex_less(float v, int i, float bv, int bi)
@@ -554,9 +556,15 @@ __global__ __launch_bounds__(C::NT) void route_small_kernel(RouteKParams p, int 
     __syncthreads();
     if (!last_flag) return;
     __threadfence();
+    if (p.self_clean && p.counts) {   // (uniform) nobody zeroed the histogram ahead of this launch
+        for (int k = threadIdx.x; k < p.K; k += C::NT) p.counts[k] = 0;
+        __syncthreads();
+    }
+    if (p.self_clean && threadIdx.x == 0) *p.arrivals = 0;
     for (int q = threadIdx.x; q < (int)p.N; q += C::NT) {
         const unsigned long long key =
             __hip_atomic_load(&p.best[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (p.self_clean) p.best[q] = ~0ull;   // ready for the next call
         const unsigned idx = (unsigned)(key & 0xffffffffu);
         const int bi = (idx < (unsigned)p.K) ? (int)idx : 0;   // nothing won: centroid 0
         if (p.cid) p.cid[q] = bi;
@@ -876,16 +884,24 @@ int route_stream_group(int64_t N, int K, int D, int is_bf16)
     return best_g;
 }
 
+bool route_small_batch(int64_t N, int K, int D, int is_bf16)
+{
+    RouteArgs a{};
+    a.N = N; a.K = K; a.D = D; a.is_bf16 = is_bf16;
+    return use_small_route(a);
+}
+
 bool route_tallies_counts(const RouteArgs &a) { return a.N > 0 && a.counts != nullptr && use_small_route(a); }
 
 hipError_t launch_centroid_norms(const RouteArgs &a, hipStream_t stream)
 {
     const int Kpad = (a.K + 255) / 256 * 256;
-    const int64_t nbest = (use_small_route(a) || a.group > 1) ? a.N : 0;
-    const int narr = 1;
+    // a self-cleaning small-batch call needs the norms only
+    const int64_t nbest = a.self_clean ? 0 : ((use_small_route(a) || a.group > 1) ? a.N : 0);
+    const int narr = a.self_clean ? 0 : 1;
     hipLaunchKernelGGL(centroid_norm_kernel, dim3((Kpad + 3) / 4), dim3(256), 0, stream,
                        (const char *)a.cent, a.K, Kpad, a.D, a.is_bf16, a.slot, a.retained_only,
-                       a.cnorm, a.cinit, a.best, nbest, a.arrivals, narr, a.counts);
+                       a.cnorm, a.cinit, a.best, nbest, a.arrivals, narr, a.self_clean ? nullptr : a.counts);
     return hipGetLastError();
 }
 
@@ -900,6 +916,7 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t stream)
         p.counts = use_small_route(a) ? a.counts : nullptr;
         p.N = a.N; p.K = a.K; p.D = a.D;
         p.group = a.group > 1 ? a.group : 1;
+        p.self_clean = use_small_route(a) ? a.self_clean : 0;
         if (use_small_route(a)) {
             using C = CfgRouteSmall;
             const int nqt = (int)((a.N + C::BN - 1) / C::BN);

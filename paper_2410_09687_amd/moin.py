@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libmoin.so")
 MOIN_F32, MOIN_BF16 = 0, 1
 MOIN_MX_X_INTERNAL, MOIN_MX_X_EMIT, MOIN_MX_X_GIVEN = 0, 1, 2
 MOIN_ROUTE_RETAINED_ONLY = 1
+MOIN_ROUTE_SAME_CENTROIDS = 2
 (K_PLAN, K_SHRINK, K_LINEAR, K_ROUTE, K_ROUTE_AUX, K_DECODE_SHRINK, K_DECODE_EXPAND, K_DECODE_BASE,
  K_KMEANS_SORT, K_KMEANS_SUM, K_KMEANS_FINAL) = range(11)
 KERNEL_NAMES = ["plan", "shrink", "linear", "route", "route_aux", "decode_shrink", "decode_expand",
@@ -202,10 +203,11 @@ class Context:
 def moin_route(ctx: Context, emb: torch.Tensor, centroids: torch.Tensor,
                slot_of_centroid: Optional[torch.Tensor] = None, retained_only: bool = False,
                want_centroid_ids: bool = True, want_counts: bool = False, stream=None, out=None,
-               static: bool = False):
+               static: bool = False, same_centroids: bool = False):
     """Returns ``(expert_ids, centroid_ids or None, counts or None)`` as int32 tensors.  ``out``: the same
     triple preallocated by the caller.  ``static``: through ``moin_route_static``, the entry point that
-    allocates no device memory (N <= 65536, K <= 16384)."""
+    allocates no device memory (N <= 65536, K <= 16384).  ``same_centroids``: the caller vouches that
+    the table is unchanged since the previous call on this context (``MOIN_ROUTE_SAME_CENTROIDS``)."""
     if emb.dim() != 2 or centroids.dim() != 2 or emb.shape[1] != centroids.shape[1]:
         raise ValueError("emb [N,D] and centroids [K,D] expected")
     if emb.dtype != centroids.dtype or emb.dtype not in (torch.float32, torch.bfloat16):
@@ -226,7 +228,8 @@ def moin_route(ctx: Context, emb: torch.Tensor, centroids: torch.Tensor,
     fn = load().moin_route_static if static else load().moin_route
     _ck(fn(ctx._h, _dev_ptr(emb, "emb") if N else None, _dev_ptr(centroids, "centroids"),
                           N, K, D, dt, _dev_ptr(slot_of_centroid, "slot_of_centroid", torch.int32),
-                          MOIN_ROUTE_RETAINED_ONLY if retained_only else 0,
+                          (MOIN_ROUTE_RETAINED_ONLY if retained_only else 0)
+                          | (MOIN_ROUTE_SAME_CENTROIDS if same_centroids else 0),
                           _dev_ptr(expert_ids, "expert_ids") if N else None,
                           _dev_ptr(cids, "centroid_ids") if (cids is not None and N) else None,
                           _dev_ptr(counts, "counts"), _stream_ptr(stream)),

@@ -134,3 +134,45 @@ def test_route_argument_errors():
         moin.moin_route(gc.ctx(), rin.emb, rin.centroids, retained_only=True)
     e, c, _ = moin.moin_route(gc.ctx(), rin.emb[:0], rin.centroids)
     assert e.numel() == 0
+
+
+def test_request_sized_batches_reuse_the_norms_and_keep_their_scratch_clean():
+    # Request-sized batches take one self-cleaning launch.  A serving loop: the same table over and over
+    # (norms reused when the caller says so), batches of different sizes, a linear call in between (it
+    # overwrites the shared workspace), then ANOTHER table at the same address claimed unchanged only
+    # after one honest call -- every result against the oracle and against a fresh context.
+    ctx = gc.ctx()
+    K, D = 700, 128
+    rin = _route_case(900, K, D, "bf16", True, seed=77)
+    cent = rin.centroids.clone()
+    slots = torch.from_numpy(wl.retained_slot_table(K, K - 50, seed=6)).cuda()
+    fresh = moin.Context(0)
+    try:
+        for i, n in enumerate([900, 64, 1, 333, 900]):
+            q = rin.emb[:n].contiguous()
+            e, c, cnt = moin.moin_route(ctx, q, cent, slot_of_centroid=slots, want_counts=True,
+                                        same_centroids=(i > 0))
+            ctx.check()
+            e2, c2, cnt2 = moin.moin_route(fresh, q, cent, slot_of_centroid=slots, want_counts=True)
+            fresh.check()
+            assert torch.equal(c, c2) and torch.equal(e, e2) and torch.equal(cnt, cnt2)
+            gc.check_route(q, cent, c)
+            assert torch.equal(cnt.long(), torch.bincount(c.long(), minlength=K))
+            if i == 1:   # a linear call between two routing calls
+                lin = wl.make_linear_inputs(wl.LinearWorkload("t", 128, 136, 16, 4, [3, 5, 2], "uniform", seed=5), "cuda")
+                gc.run_linear(lin)
+        # new contents at the same address: one call without the flag picks them up ...
+        cent.copy_(_route_case(8, K, D, "bf16", True, seed=78).centroids)
+        q = rin.emb[:500].contiguous()
+        _, c, _ = moin.moin_route(ctx, q, cent)
+        ctx.check()
+        gc.check_route(q, cent, c)
+        # ... and from then on the flag is honest again; retained-only changes what the norms mean
+        _, c, _ = moin.moin_route(ctx, q, cent, same_centroids=True)
+        ctx.check()
+        gc.check_route(q, cent, c)
+        _, c, _ = moin.moin_route(ctx, q, cent, slot_of_centroid=slots, retained_only=True, same_centroids=True)
+        ctx.check()
+        gc.check_route(q, cent, c, eligible=(slots >= 0).cpu().numpy())
+    finally:
+        fresh.close()
