@@ -334,6 +334,16 @@ int moin_cache_add_stack(moin_cache *cache, const void *A_host, const void *B_ho
                          int64_t b_bytes_per_expert);
 int moin_cache_admit(moin_cache *cache, const int32_t *expert_ids, int32_t S,
                      int32_t *slot_ids, void *stream);
+/* Overlap mode, chosen before the first batch (later: MOIN_EINVAL): the copies of an
+ * admission go on a stream the cache owns instead of `stream`, so a server can admit
+ * batch k+1 right after it has enqueued the kernels of batch k and have the adapters
+ * cross PCIe under those kernels.  For that to be safe the experts of the batch
+ * admitted just before are protected from eviction like the batch's own (a newcomer
+ * finds no slot -- slot -1 -- when every slot holds an expert of either), the copy
+ * stream waits for the compute work enqueued on `stream` before the previous
+ * admission, and `stream` is made to wait for the copies before the work enqueued on
+ * it next.  The caller keeps to the order: kernels of batch k, then admit(k+1). */
+int moin_cache_set_overlap(moin_cache *cache, int on);
 /* Copies of the tables (HOST arrays, either may be NULL): slot_of_expert [E],
  * expert_in_slot [n_slots]; -1 = not resident / free. */
 int moin_cache_table(const moin_cache *cache, int32_t *slot_of_expert,

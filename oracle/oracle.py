@@ -401,9 +401,15 @@ class AdapterCache:
       the batch does not need with the fewest uses goes (then the one used
       longest ago, then the lowest slot);
     * with no such expert left the newcomer gets no slot (-1: base model only).
+
+    protect_previous: a server that pages the adapters of batch k+1 in while batch k is
+    still computing must not overwrite what batch k reads, so the experts of the batch
+    admitted just before are as untouchable as the batch's own.
     """
 
-    def __init__(self, n_experts, n_slots):
+    def __init__(self, n_experts, n_slots, protect_previous=False):
+        self.protect_previous = bool(protect_previous)
+        self.previous = []
         self.n_experts, self.n_slots = int(n_experts), int(n_slots)
         self.slot_of = {}                      # expert -> slot
         self.expert_in = [None] * self.n_slots
@@ -435,7 +441,8 @@ class AdapterCache:
             if free:
                 slot = free[0]
             else:
-                cand = [s for s in range(self.n_slots) if self.expert_in[s] not in needed]
+                keep = needed + (self.previous if self.protect_previous else [])
+                cand = [s for s in range(self.n_slots) if self.expert_in[s] not in keep]
                 if not cand:
                     self.overflows += 1
                     continue
@@ -446,6 +453,7 @@ class AdapterCache:
             self.slot_of[e] = slot
             self.loads += 1
             loaded.append((e, slot))
+        self.previous = needed
         slots = np.array([self.slot_of.get(e, -1) if e >= 0 else -1 for e in ids], dtype=np.int32)
         return slots, loaded
 

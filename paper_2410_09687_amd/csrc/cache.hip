@@ -14,6 +14,12 @@
 //     then the least recently used, then the lowest slot index;
 //   * if every slot holds an expert of this batch, the remaining experts of the
 //     batch get slot -1: their sequences run on the base model alone.
+// Overlap mode (moin_cache_set_overlap): the copies go on a stream of the cache's
+// own, so the adapters of batch k+1 cross PCIe while batch k computes.  What
+// batch k reads must then not be overwritten: the experts of the batch admitted
+// just before are protected like the batch's own, and the copy stream first waits
+// for the compute work that was enqueued before THAT admission (everything that
+// may still read any other slot).  The compute stream waits for the copies.
 #include "../../include/moin.h"
 
 #include <hip/hip_runtime.h>
@@ -37,6 +43,12 @@ struct moin_cache {
     std::vector<int32_t> batch_count;  // [E] scratch
     std::vector<int32_t> order;        // distinct experts of the batch, first appearance first
     std::vector<CacheStack> stacks;
+    // overlap mode
+    int overlap;
+    hipStream_t copy_stream;
+    hipEvent_t compute_mark[2];   // compute stream at the last two admissions (newest: index tick % 2)
+    hipEvent_t copies_done;
+    int marks;                    // admissions that recorded a mark so far
     int64_t tick;
     int64_t stats[MOIN_CACHE_STAT_COUNT];
 };
@@ -64,12 +76,35 @@ int moin_cache_create(moin_cache **out, int32_t E, int32_t n_slots)
         return MOIN_ENOMEM;
     }
     c->tick = 0;
+    c->overlap = 0;
+    c->copy_stream = nullptr;
+    c->compute_mark[0] = c->compute_mark[1] = c->copies_done = nullptr;
+    c->marks = 0;
     for (int i = 0; i < MOIN_CACHE_STAT_COUNT; ++i) c->stats[i] = 0;
     *out = c;
     return MOIN_OK;
 }
 
-void moin_cache_destroy(moin_cache *cache) { delete cache; }
+void moin_cache_destroy(moin_cache *cache)
+{
+    if (!cache) return;
+    if (cache->copy_stream) {
+        (void)hipStreamSynchronize(cache->copy_stream);
+        (void)hipStreamDestroy(cache->copy_stream);
+    }
+    for (hipEvent_t e : {cache->compute_mark[0], cache->compute_mark[1], cache->copies_done})
+        if (e) (void)hipEventDestroy(e);
+    delete cache;
+}
+
+int moin_cache_set_overlap(moin_cache *cache, int on)
+{
+    if (!cache) return MOIN_EINVAL;
+    for (int32_t s = 0; s < cache->n_slots; ++s)
+        if (cache->expert_in[s] >= 0) return MOIN_EINVAL;   // a property of the whole request stream
+    cache->overlap = on ? 1 : 0;
+    return MOIN_OK;
+}
 
 int moin_cache_add_stack(moin_cache *cache, const void *A_host, const void *B_host, void *A_slots,
                          void *B_slots, int64_t a_bytes_per_expert, int64_t b_bytes_per_expert)
@@ -128,6 +163,26 @@ int moin_cache_admit(moin_cache *cache, const int32_t *expert_ids, int32_t S, in
 
     // 2. residency
     hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool side = c.overlap && !c.stacks.empty();
+    hipStream_t cp = st;   // the stream the copies go on
+    if (side) {
+        if (!c.copy_stream) {
+            if (hipStreamCreateWithFlags(&c.copy_stream, hipStreamNonBlocking) != hipSuccess ||
+                hipEventCreateWithFlags(&c.compute_mark[0], hipEventDisableTiming) != hipSuccess ||
+                hipEventCreateWithFlags(&c.compute_mark[1], hipEventDisableTiming) != hipSuccess ||
+                hipEventCreateWithFlags(&c.copies_done, hipEventDisableTiming) != hipSuccess) {
+                (void)hipGetLastError();
+                return MOIN_EHIP;
+            }
+        }
+        cp = c.copy_stream;
+        // Slots this admission may overwrite are read by nothing newer than the compute work that was
+        // enqueued before the PREVIOUS admission (the previous batch's experts are protected below):
+        // the copies wait for that mark, not for the batch that is computing now.
+        if (c.marks > 0 && hipStreamWaitEvent(cp, c.compute_mark[(c.marks - 1) & 1], 0) != hipSuccess) return MOIN_EHIP;
+        if (hipEventRecord(c.compute_mark[c.marks & 1], st) != hipSuccess) return MOIN_EHIP;
+        c.marks += 1;
+    }
     int32_t next_free = 0;
     for (int32_t e : c.order) {
         if (c.slot_of[e] >= 0) {
@@ -142,7 +197,12 @@ int moin_cache_admit(moin_cache *cache, const int32_t *expert_ids, int32_t S, in
         } else {
             for (int32_t s = 0; s < c.n_slots; ++s) {
                 const int32_t v = c.expert_in[s];
+                if (v < 0) {   // left free by a failed copy
+                    slot = s;
+                    break;
+                }
                 if (c.seen_in[v] == now) continue;   // needed by this batch
+                if (c.overlap && c.seen_in[v] == now - 1) continue;   // may still be read by the batch before
                 if (slot < 0) {
                     slot = s;
                     continue;
@@ -154,25 +214,38 @@ int moin_cache_admit(moin_cache *cache, const int32_t *expert_ids, int32_t S, in
                 c.stats[MOIN_CACHE_OVERFLOWS] += 1;
                 continue;   // no slot to give: base model only
             }
-            c.slot_of[c.expert_in[slot]] = -1;
-            c.stats[MOIN_CACHE_EVICTIONS] += 1;
+            // the victim leaves the tables before its slot is touched
+            if (c.expert_in[slot] >= 0) {
+                c.slot_of[c.expert_in[slot]] = -1;
+                c.expert_in[slot] = -1;
+                c.stats[MOIN_CACHE_EVICTIONS] += 1;
+            }
+        }
+        // copies first, tables after: a slot is never named as holding an expert whose bytes were not
+        // all enqueued (after a failed copy the slot stays free, its contents undefined)
+        int64_t bytes = 0;
+        for (const CacheStack &k : c.stacks) {
+            if (hipMemcpyAsync(k.a_slots + (size_t)slot * k.a_bytes, k.a_host + (size_t)e * k.a_bytes, k.a_bytes,
+                               hipMemcpyHostToDevice, cp) != hipSuccess ||
+                hipMemcpyAsync(k.b_slots + (size_t)slot * k.b_bytes, k.b_host + (size_t)e * k.b_bytes, k.b_bytes,
+                               hipMemcpyHostToDevice, cp) != hipSuccess) {
+                (void)hipGetLastError();
+                if (side) {   // what was enqueued so far still has to land before the compute stream goes on
+                    if (hipEventRecord(c.copies_done, cp) == hipSuccess) (void)hipStreamWaitEvent(st, c.copies_done, 0);
+                }
+                return MOIN_EHIP;
+            }
+            bytes += (int64_t)(k.a_bytes + k.b_bytes);
         }
         c.expert_in[slot] = e;
         c.slot_of[e] = slot;
         c.stats[MOIN_CACHE_LOADS] += 1;
-        for (const CacheStack &k : c.stacks) {
-            if (hipMemcpyAsync(k.a_slots + (size_t)slot * k.a_bytes, k.a_host + (size_t)e * k.a_bytes, k.a_bytes,
-                               hipMemcpyHostToDevice, st) != hipSuccess ||
-                hipMemcpyAsync(k.b_slots + (size_t)slot * k.b_bytes, k.b_host + (size_t)e * k.b_bytes, k.b_bytes,
-                               hipMemcpyHostToDevice, st) != hipSuccess) {
-                (void)hipGetLastError();
-                // the slot's contents are undefined now: forget the expert
-                c.expert_in[slot] = -1;
-                c.slot_of[e] = -1;
-                return MOIN_EHIP;
-            }
-            c.stats[MOIN_CACHE_BYTES] += (int64_t)(k.a_bytes + k.b_bytes);
-        }
+        c.stats[MOIN_CACHE_BYTES] += bytes;
+    }
+    if (side) {
+        // the batch's kernels, enqueued on `stream` after this call, wait for its adapters
+        if (hipEventRecord(c.copies_done, cp) != hipSuccess || hipStreamWaitEvent(st, c.copies_done, 0) != hipSuccess)
+            return MOIN_EHIP;
     }
 
     // 3. slot per sequence

@@ -38,6 +38,7 @@ EXPORTS = [
     "moin_probe_out_len", "moin_probe_mfma_bf16", "moin_probe_mfma_mxfp8", "moin_probe_read", "moin_set_adapter_activation",
     "moin_lora_linear_planned_shared", "moin_route_topk", "moin_merge_adapters",
     "moin_reserve_workspace", "moin_workspace_bytes", "moin_plan_reserve", "moin_route_static",
+    "moin_cache_set_overlap",
 ]
 ACTIVATIONS = {None: 0, "none": 0, "relu": 1, "silu": 2, "gelu": 3}
 CACHE_STATS = ["batches", "seq_hits", "seq_misses", "loads", "evictions", "overflows", "bytes"]
@@ -110,6 +111,7 @@ def load() -> ctypes.CDLL:
     lib.moin_cache_destroy.restype = None
     lib.moin_cache_add_stack.argtypes = [vp, vp, vp, vp, vp, i64, i64]
     lib.moin_cache_admit.argtypes = [vp, vp, i32, vp, vp]
+    lib.moin_cache_set_overlap.argtypes = [vp, c.c_int]
     lib.moin_cache_table.argtypes = [vp, vp, vp]
     lib.moin_cache_stats.argtypes = [vp, vp]
     lib.moin_timing_enable.argtypes = [vp, c.c_int]
@@ -642,11 +644,15 @@ class Cache:
     slot stacks on the device); ``admit`` takes a batch's expert ids as a host
     int32 tensor / array and returns the slot ids as a host int32 tensor."""
 
-    def __init__(self, E: int, n_slots: int):
+    def __init__(self, E: int, n_slots: int, overlap: bool = False):
         self._h = ctypes.c_void_p()
         _ck(load().moin_cache_create(ctypes.byref(self._h), int(E), int(n_slots)), "moin_cache_create")
         self.E, self.n_slots = int(E), int(n_slots)
         self._keep = []
+        if overlap:
+            # copies on the cache's own stream, the previous batch's experts protected: admit batch k+1
+            # right after enqueuing the kernels of batch k
+            _ck(load().moin_cache_set_overlap(self._h, 1), "moin_cache_set_overlap")
 
     def add_stack(self, A_host: torch.Tensor, B_host: torch.Tensor, A_slots: torch.Tensor, B_slots: torch.Tensor):
         for t, name in ((A_host, "A_host"), (B_host, "B_host")):

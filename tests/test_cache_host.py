@@ -7,9 +7,9 @@ import oracle
 from paper_2410_09687_amd import moin
 
 
-def _compare(E, n_slots, batches):
-    c = moin.Cache(E, n_slots)
-    ref = oracle.AdapterCache(E, n_slots)
+def _compare(E, n_slots, batches, overlap=False):
+    c = moin.Cache(E, n_slots, overlap=overlap)
+    ref = oracle.AdapterCache(E, n_slots, protect_previous=overlap)
     for ids in batches:
         got = c.admit(np.asarray(ids, np.int32)).numpy()
         want, _ = ref.admit(ids)
@@ -57,4 +57,22 @@ def test_errors_leave_the_cache_unchanged():
     assert c.admit(np.zeros(0, np.int32)).numel() == 0
     with pytest.raises(moin.MoinError):
         moin.Cache(0, 4)
+    c.close()
+
+
+def test_overlap_mode_protects_the_previous_batch_like_the_oracle():
+    # admitting batch k+1 while batch k computes: nothing batch k reads may be evicted
+    rng = np.random.default_rng(5)
+    for E, n_slots, n_batches, size in ((200, 17, 300, 12), (5000, 512, 60, 256), (10, 2, 50, 3), (40, 9, 80, 6)):
+        batches = [(rng.zipf(1.2, size=rng.integers(1, size + 1)) % (E + 1) - 1) for _ in range(n_batches)]
+        st = _compare(E, n_slots, batches, overlap=True)
+    # the hand case: two slots, batch [0, 1] then [2]: in overlap mode 2 finds both slots protected
+    c = moin.Cache(4, 2, overlap=True)
+    assert c.admit(np.array([0, 1], np.int32)).tolist() == [0, 1]
+    assert c.admit(np.array([2], np.int32)).tolist() == [-1]
+    assert c.admit(np.array([2], np.int32)).tolist() == [0]      # batch [0, 1] is two admissions back now
+    assert c.stats()["overflows"] == 1
+    with pytest.raises(moin.MoinError):
+        moin.load().moin_cache_set_overlap  # (exists)
+        moin._ck(moin.load().moin_cache_set_overlap(c._h, 0), "moin_cache_set_overlap")   # too late: slots in use
     c.close()

@@ -90,3 +90,47 @@ def test_two_projections_share_one_residency():
     with pytest.raises(moin.MoinError):   # stacks are registered before the first batch
         cache.add_stack(A1, B1, *s1)
     cache.close()
+
+
+def test_look_ahead_pipeline_pages_the_next_batch_in_under_the_current_one():
+    # Overlap mode: the copies go on the cache's own stream, batch k+1 is admitted right after the kernels
+    # of batch k were enqueued, nothing is synchronised in between.  Every batch must come out as on the
+    # full stacks, bit for bit (a slot overwritten under a kernel that still reads it, or read before its
+    # copy landed, would show here), and the slot ids must be the oracle's with the previous batch protected.
+    E, n_slots, r, d_in, d_out = 60, 8, 64, 512, 520
+    A_host, B_host = _stacks(E, r, d_in, d_out, 400)
+    A_full, B_full = A_host.cuda(), B_host.cuda()
+    A_slots = torch.zeros((n_slots, r, d_in), dtype=torch.bfloat16, device="cuda")
+    B_slots = torch.zeros((n_slots, d_out, r), dtype=torch.bfloat16, device="cuda")
+    W = wl._randn_bf16((d_out, d_in), d_in ** -0.5, torch.device("cuda"), 8)
+    cache = moin.Cache(E, n_slots, overlap=True)
+    cache.add_stack(A_host, B_host, A_slots, B_slots)
+    ref_cache = oracle.AdapterCache(E, n_slots, protect_previous=True)
+    rng = np.random.default_rng(6)
+    n_batches, S = 24, 4
+    batches = [(rng.zipf(1.3, size=S) % (E + 1) - 1).astype(np.int32) for _ in range(n_batches)]
+    lens = [700, 300, 1, 411]                     # a prefill-sized batch: its kernels take a while
+    off = torch.from_numpy(wl.seq_offsets_of(lens)).cuda()
+    T = int(sum(lens))
+    xs = [wl._randn_bf16((T, d_in), 1.0, torch.device("cuda"), 500 + b) for b in range(n_batches)]
+    ys = [torch.empty((T, d_out), dtype=torch.bfloat16, device="cuda") for _ in range(n_batches)]
+    ctx = gc.ctx()
+    torch.cuda.synchronize()
+    print("[gpu] cache look-ahead pipeline", flush=True)
+    slots = cache.admit(batches[0])
+    all_slots = []
+    for b in range(n_batches):
+        all_slots.append(slots.clone())
+        want, _ = ref_cache.admit(batches[b])
+        assert np.array_equal(slots.numpy(), want), b
+        moin.moin_lora_linear(ctx, xs[b], off, slots.cuda(non_blocking=False), W, A_slots, B_slots, 2.0, out=ys[b])
+        if b + 1 < n_batches:
+            slots = cache.admit(batches[b + 1])      # its copies run under batch b's kernels
+    ctx.check()
+    assert cache.stats()["loads"] == ref_cache.loads and cache.stats()["overflows"] == ref_cache.overflows
+    for b in range(n_batches):
+        eff = np.where(all_slots[b].numpy() >= 0, batches[b], -1).astype(np.int32)
+        y_full = moin.moin_lora_linear(ctx, xs[b], off, torch.from_numpy(eff).cuda(), W, A_full, B_full, 2.0)
+        ctx.check()
+        assert torch.equal(ys[b].view(torch.int16), y_full.view(torch.int16)), f"batch {b}"
+    cache.close()

@@ -23,6 +23,28 @@ def test_hand_worked_trace():
     assert [c.hits, c.misses, c.loads, c.evictions, c.overflows] == [int(v) for v in g["totals"]]
 
 
+def test_hand_worked_trace_with_the_previous_batch_protected():
+    g = read_golden(GOLDEN)
+    c = oracle.AdapterCache(6, 3, protect_previous=True)
+    for b in range(1, 6):
+        ids = [int(v) for v in g[f"batch{b}_ids"]]
+        slots, _ = c.admit(ids)
+        assert slots.tolist() == [int(v) for v in g[f"overlap_batch{b}_slots"]], b
+        assert c.tables()[1].tolist() == [int(v) for v in g[f"overlap_batch{b}_state"]], b
+    assert [c.hits, c.misses, c.loads, c.evictions, c.overflows] == [int(v) for v in g["overlap_totals"]]
+    # nothing a batch uses is evicted by the admission after it, whatever the stream
+    rng = np.random.default_rng(4)
+    c = oracle.AdapterCache(60, 7, protect_previous=True)
+    prev = {}
+    for _ in range(400):
+        ids = rng.zipf(1.3, size=rng.integers(1, 6)) % 61 - 1
+        slots, _ = c.admit(ids)
+        slot_of = c.tables()[0]
+        for e, s in prev.items():
+            assert slot_of[e] == s, "an expert of the previous batch lost its slot"
+        prev = {int(e): int(s) for e, s in zip(ids, slots) if e >= 0 and s >= 0}
+
+
 def test_invariants_on_random_batches():
     rng = np.random.default_rng(0)
     E, n_slots = 200, 17
