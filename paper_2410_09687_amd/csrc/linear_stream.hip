@@ -9,13 +9,13 @@
 //    of the next tile are already in flight while the current one finishes;
 //  * operands reach LDS directly (global_load_lds), two stages of 64
 //    contraction steps, rows XOR-swizzled in 16-byte chunks;
-//  * MFMA fragments are read from LDS one k-step ahead; the per-block barrier
-//    sits before the block's last k-step, whose fragments are in registers by
-//    then, and the first fragments of the next block are read during that
-//    k-step: no wave waits on LDS right after a barrier;
+//  * four waves, one per SIMD: 128 x 128 patches of v_mfma_f32_16x16x32_bf16
+//    accumulators; the fragments of a k-step are read from LDS under the
+//    MFMAs of the k-step before, the block's barrier sits between its two
+//    k-steps, and the requests for the block two ahead go out under the second;
 //  * W / B_e rows are the MFMA row operand and tokens the column operand, so a
 //    lane ends up with four consecutive outputs of one token; the epilogue
-//    regroups them through 4 KB of LDS per wave that lie outside the stages,
+//    regroups them through 8 KB of LDS per wave that lie outside the stages,
 //    so it runs while the next tile's first blocks are landing.
 // Contraction lengths (d_in, r) must be multiples of 64 and d_in >= 128.
 #include <type_traits>
@@ -30,17 +30,10 @@ namespace stream {
 
 constexpr int BT = 256;              // tile edge, both ways
 constexpr int BK = 64;
-constexpr int NW = 8, NT = NW * 64;
-constexpr int WQ = 2;                // waves along tokens (Q); NW / WQ along outputs (P)
-constexpr int FP = 2, FQ = 4;        // 32 x 32 accumulators per wave: 64 outputs x 128 tokens
 constexpr int ROWB = BK * 2;         // LDS row pitch
 constexpr int OP_BYTES = BT * ROWB;  // one operand tile: 32 KB
 constexpr int STAGE_BYTES = 2 * OP_BYTES;
 constexpr int SMEM_STAGES = 2 * STAGE_BYTES;
-constexpr int SCR_BYTES = 4096;      // per-wave epilogue scratch
-constexpr int SMEM_BYTES = SMEM_STAGES + NW * SCR_BYTES;   // 160 KB: all of a compute unit's LDS
-constexpr int LOADS = 4;             // DMA instructions per wave per operand per block
-constexpr int KSTEPS = BK / 16;
 
 struct Params {
     const char *x, *W, *B_stack, *u_hi, *u_lo;
@@ -89,18 +82,37 @@ __device__ __forceinline__ Tile load_tile(const Params &p, int id, int n_work)
 
 }  // namespace stream
 
-__global__ __launch_bounds__(stream::NT) void linear_stream_kernel(stream::Params p)
+// Four waves, one per SIMD, each with the full 512 registers: a 128 x 128 patch of the tile per
+// wave (64 accumulators of 16 outputs x 16 tokens, v_mfma_f32_16x16x32_bf16), so a k-step of 32
+// takes 8 + 8 fragment reads for 64 MFMAs.  An earlier form of this kernel ran eight waves with
+// 64 x 128 patches of 32 x 32 x 16 MFMAs (2 + 4 reads per 8 MFMAs): half more LDS bytes per flop
+// and twice the accumulator registers moved per flop -- both count where the limit is power -- and
+// it was 8-9 % slower on N(0,1) data (241 against 213 us on the 2048 -> 2048 prefill shape), though
+// a little faster on all-zero data, where a second wave per SIMD hides this kernel's barrier.
+namespace s16 {
+using stream::BK;
+using stream::BT;
+using stream::OP_BYTES;
+using stream::ROWB;
+using stream::SMEM_STAGES;
+using stream::STAGE_BYTES;
+constexpr int NW = 4, NT = NW * 64;
+constexpr int FP = 8, FQ = 8;          // 16 x 16 accumulators per wave: 128 outputs x 128 tokens
+constexpr int LOADS = 8;               // DMA instructions per wave per operand per block
+constexpr int SCR_BYTES = 8192;        // per-wave epilogue scratch: 16 tokens x 128 outputs, fp32
+constexpr int SMEM_BYTES = SMEM_STAGES + NW * SCR_BYTES;   // 160 KB
+}  // namespace s16
+
+template <bool Y_F32>
+__global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p)
 {
-    using namespace stream;
+    using namespace s16;
+    using stream::Tile;
     extern __shared__ __align__(16) char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = uniform(threadIdx.x >> 6);
-    const int wp = wave / WQ, wq = wave % WQ;
-    const int r = lane & 31, h = lane >> 5;
+    const int wp = wave >> 1, wq = wave & 1;
 
-    // work list of this workgroup: the 8 XCDs take workgroups round-robin, each
-    // XCD owns one contiguous band of tile ids, and its workgroups stride
-    // through the band together (neighbouring ids share W or x panels in L2)
     const int n_work = uniform(*p.n_tiles) * p.n_tiles_n;
     const int per = (n_work + 7) >> 3;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, nslot = gridDim.x >> 3;
@@ -111,171 +123,211 @@ __global__ __launch_bounds__(stream::NT) void linear_stream_kernel(stream::Param
     const int nkb0 = p.d_in / BK;
     const uint32_t ldx = (uint32_t)p.d_in * 2u, ldu = (uint32_t)p.r * 2u;
 
-    // DMA mapping: instruction j of a wave fills LDS rows (wave*4 + j)*8 .. +8 of
-    // an operand tile; the lane fetches logical 16-byte chunk (lane%8) ^ swz(row)
-    const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8) + (lane >> 3));   // + 8 * j
-    uint32_t dma_c16[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) dma_c16[j] = (uint32_t)(((lane & 7) ^ (((j * 8 + (lane >> 3)) >> 1) & 7)) * 16);
-    // swz(row) = (row >> 1) & 7 with row = wave*32 + j*8 + lane/8: only j's parity matters
+    // Per-lane constants are recomputed from the lane id at every use (through an opaque copy):
+    // kept alive across the main loop they would be spilled around the 256 accumulators.
+    auto fresh_lane = [&]() __attribute__((always_inline)) {
+        int v = lane;
+        asm volatile("; lane id, rematerialised" : "+v"(v));
+        return v;
+    };
 
-    // Starts the loads of block b of tile t into `stage`.
-    auto issue = [&](const Tile &t, int b, char *stage) __attribute__((always_inline)) {
+    // DMA: instruction j of a wave fills LDS rows (wave*8 + j)*8 .. +8 of an operand tile; the lane
+    // fetches logical 16-byte chunk (lane%8) ^ swz(row), swz(row) = (row >> 1) & 7, which for
+    // row = wave*64 + j*8 + lane/8 is ((j & 1) * 4 + lane/16) & 7.  A block's requests are issued
+    // one by one (issue_one, n = 0..15: eight for the output rows, eight for the tokens) so that
+    // they can be placed between the MFMAs.
+    struct Fetch {
+        const char *pp, *pq;
+        uint32_t ld, dma_row, c16;
+        uint32_t p_last, q_last;
+    };
+    auto fetch_of = [&](const Tile &t, int b) __attribute__((always_inline)) {
+        Fetch f;
         const bool base = b < nkb0;
         const int jb = b - nkb0;
         const bool hi = jb < t.nkb1;
-        const char *pq = base ? t.q0 : (hi ? t.uh : t.ul);
-        const char *pp = base ? t.p0 : t.be;
-        const uint32_t ld = base ? ldx : ldu;
+        f.pq = base ? t.q0 : (hi ? t.uh : t.ul);
+        f.pp = base ? t.p0 : t.be;
+        f.ld = base ? ldx : ldu;
         const int kb = base ? b : (hi ? jb : jb - t.nkb1);
-        const uint32_t kbyte = (uint32_t)kb * (BK * 2);
+        const uint32_t ln = (uint32_t)fresh_lane();
+        f.dma_row = (uint32_t)(wave * (LOADS * 8)) + (ln >> 3);
+        f.c16 = (((ln & 7) ^ (ln >> 4)) * 16) + (uint32_t)kb * (BK * 2);   // odd j: ^ 64
+        f.p_last = (uint32_t)(t.p_rows - 1);
+        f.q_last = (uint32_t)(t.q_rows - 1);
+        return f;
+    };
+    auto issue_one = [&](const Fetch &f, char *stage, int n) __attribute__((always_inline)) {
+        const int j = n & 7;
+        const bool q = n >= 8;
+        const uint32_t row = min(f.dma_row + 8u * j, q ? f.q_last : f.p_last);
+        const uint32_t off = __umul24(row, f.ld) + (f.c16 ^ ((j & 1) ? 64u : 0u));
+        __builtin_amdgcn_global_load_lds(MOIN_GPTR((q ? f.pq : f.pp) + off),
+                                         MOIN_LPTR(stage + (q ? OP_BYTES : 0) + (wave * LOADS + j) * 1024), 16, 0, 0);
+    };
+    auto issue = [&](const Tile &t, int b, char *stage) __attribute__((always_inline)) {
+        const Fetch f = fetch_of(t, b);
 #pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const uint32_t row = min(dma_row + 8u * j, (uint32_t)(t.p_rows - 1));
-            const uint32_t off = __umul24(row, ld) + dma_c16[j & 1] + kbyte;
-            __builtin_amdgcn_global_load_lds(MOIN_GPTR(pp + off), MOIN_LPTR(stage + (wave * LOADS + j) * 1024),
-                                             16, 0, 0);
-        }
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const uint32_t row = min(dma_row + 8u * j, (uint32_t)(t.q_rows - 1));
-            const uint32_t off = __umul24(row, ld) + dma_c16[j & 1] + kbyte;
-            __builtin_amdgcn_global_load_lds(MOIN_GPTR(pq + off),
-                                             MOIN_LPTR(stage + OP_BYTES + (wave * LOADS + j) * 1024), 16, 0, 0);
-        }
+        for (int n = 0; n < 2 * LOADS; ++n) issue_one(f, stage, n);
     };
 
-    // fragment addresses: patch bases are multiples of 32 rows, so the swizzle
-    // depends on r only
-    const int f = (r >> 1) & 7;
-    const int offP = (wp * (FP * 32) + r) * ROWB;
-    const int offQ = OP_BYTES + (wq * (FQ * 32) + r) * ROWB;
-    bf16x8_t fp[2][FP], fq[2][FQ];
-    auto read_frags = [&](const char *stage, int ks, int slot_) __attribute__((always_inline)) {
-        const int o = (((ks * 2 + h) ^ f) & 7) * 16;
-#pragma unroll
-        for (int i = 0; i < FP; ++i)
-            fp[slot_][i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(stage + offP + i * 32 * ROWB + o));
-#pragma unroll
-        for (int j = 0; j < FQ; ++j)
-            fq[slot_][j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(stage + offQ + j * 32 * ROWB + o));
+    // MFMA operand of a lane: row lane%16 of a 16-row block, elements 8 (lane/16) .. + 8 of the
+    // k-step's 32, i.e. logical chunk 4 ks + lane/16 of the row; the swizzle of a row inside a
+    // 16-row block depends on lane%16 only ((row >> 1) & 7 = (lane%16) >> 1), and k-step 1 is
+    // k-step 0's address ^ 64.  Fragment n = 0..7: output blocks, 8..15: token blocks.
+    auto lane_off = [&]() __attribute__((always_inline)) {
+        const int ln = fresh_lane();
+        return ((ln & 15) * ROWB) | ((((ln >> 4) ^ ((ln & 15) >> 1)) & 7) * 16);
     };
-    f32x16_t acc[FP][FQ];
-    auto mfmas = [&](int slot_) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < FP; ++i)
-#pragma unroll
-            for (int j = 0; j < FQ; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fp[slot_][i], fq[slot_][j], acc[i][j], 0, 0, 0);
+    const int baseP = wp * (FP * 16) * ROWB, baseQ = OP_BYTES + wq * (FQ * 16) * ROWB;
+    bf16x8_t fr[2][FP + FQ];
+    auto read_one = [&](const char *stage, int lo_, int set, int n) __attribute__((always_inline)) {
+        const int base_ = n < FP ? baseP + n * 16 * ROWB : baseQ + (n - FP) * 16 * ROWB;
+        fr[set][n] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(stage + base_ + lo_));
+    };
+    // The MFMAs are written as assembly with the accumulator tied in and out as an AccVGPR operand:
+    // the compiler's own selection for 64 four-register accumulators goes through the VGPR form and
+    // wraps every MFMA in copies.  What its hazard checks cannot see is taken care of by hand: an
+    // accumulator is touched again only 64 MFMAs later, its operands come from LDS reads (waited for by
+    // the compiler: they are inputs of the statement), and the epilogue waits before it reads.
+    f32x4_t acc[FP][FQ];
+    auto mfma = [&](int set, int i, int j) __attribute__((always_inline)) {
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fr[set][i]), "v"(fr[set][FP + j]));
     };
 
-    Tile cur = load_tile(p, id, band_end);
+    Tile cur = stream::load_tile(p, id, band_end);
     id += nslot;
-    Tile nxt = load_tile(p, id, band_end);
-
-    // fetch cursor: tile and block index of the next block to request
+    Tile nxt = stream::load_tile(p, id, band_end);
     Tile pft = cur;
     int pfb = 2;
 
-    // One block of the stream.  ISSUE: a block two positions ahead exists and is
-    // fetched into the stage this block frees; READ: a next block exists.
-    auto body = [&](int s, auto issue_tag, auto read_tag) __attribute__((always_inline)) {
-        constexpr bool ISSUE = decltype(issue_tag)::value, READ = decltype(read_tag)::value;
+    // One block of the stream: k-step 0 (its fragments were read during the block before) with the
+    // reads of k-step 1 between its MFMAs; barrier; k-step 1 with the requests for the block two
+    // ahead and the first fragments of the next block between its MFMAs.  The order below IS the
+    // instruction order (scheduling barriers after every group).  No branch after the barrier: past
+    // the stream's end the fetch repeats the last block into the free stage and the reads take stale
+    // bytes that nothing uses.
+    auto body = [&](int s) __attribute__((always_inline)) {
         char *st_cur = smem + (s & 1) * STAGE_BYTES;
         const char *st_nxt = smem + ((s + 1) & 1) * STAGE_BYTES;
-#pragma unroll
-        for (int ks = 0; ks < KSTEPS - 1; ++ks) {
-            read_frags(st_cur, ks + 1, (ks + 1) & 1);
-            mfmas(ks & 1);
-            // one MFMA, one LDS read, ...: the next k-step's fragments trickle in
-            // under this k-step's MFMAs
-#pragma unroll
-            for (int n = 0; n < FP + FQ; ++n) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, FP * FQ - (FP + FQ), 0);
-        }
-        // own share of block s+1 has landed and every fragment of block s is in
-        // registers; past the barrier that holds for all waves
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        if constexpr (ISSUE) {
-            // the fetch cursor runs two blocks ahead; when it has used up its tile
-            // it moves to the tile after the one being computed (checked here, not
-            // when the cursor advances: by now `nxt` is that tile in every case)
-            if (pfb == pft.total) {
+        // everything the second half needs besides the barrier is worked out under the first half's
+        // MFMAs, so that the matrix core has work again the moment the barrier opens
+        if (pfb == pft.total) {
+            if (nxt.valid) {
                 pft = nxt;
                 pfb = 0;
-            }
-            issue(pft, pfb, st_cur);
-            ++pfb;
-        }
-        if constexpr (READ) read_frags(st_nxt, 0, 0);
-        mfmas((KSTEPS - 1) & 1);
-        if constexpr (ISSUE && READ) {
-#pragma unroll
-            for (int n = 0; n < FP * FQ; ++n) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-                if (n < FP + FQ) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-        } else if constexpr (READ) {
-#pragma unroll
-            for (int n = 0; n < FP + FQ; ++n) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            } else {
+                pfb = pft.total - 1;
             }
         }
+        const Fetch f = fetch_of(pft, pfb);
+        ++pfb;
+        const int lo0 = lane_off();
+        const int lo1 = lo0 ^ 64;
+#pragma unroll
+        for (int n = 0; n < FP * FQ; ++n) {
+            mfma(0, n / FQ, n % FQ);
+            if ((n & 1) == 1 && n / 2 < FP + FQ) {
+                read_one(st_cur, lo1, 1, n / 2);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#pragma unroll
+        for (int n = 0; n < FP * FQ; ++n) {
+            mfma(1, n / FQ, n % FQ);
+            if (n % 3 == 2 && n / 3 < FP + FQ) {
+                read_one(st_nxt, lo0, 0, n / 3);
+                issue_one(f, st_cur, n / 3);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
     };
 
-    // prologue of the stream: two blocks in flight, the first one's leading fragments read
     issue(cur, 0, smem);
     issue(cur, 1, smem + STAGE_BYTES);   // every tile has at least two blocks
     wait_vm_then_barrier<2 * LOADS>();
-    read_frags(smem, 0, 0);
 
     int s = 0;
     for (;;) {
+        // leading fragments of the tile's first block (landed: the prologue, or the previous
+        // tile's last barrier, waited for it); not held across the epilogue
+        {
+            const int lo0 = lane_off();
+#pragma unroll
+            for (int n = 0; n < FP + FQ; ++n) read_one(smem + (s & 1) * STAGE_BYTES, lo0, 0, n);
+        }
 #pragma unroll
         for (int i = 0; i < FP; ++i)
 #pragma unroll
-            for (int j = 0; j < FQ; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
+            for (int j = 0; j < FQ; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        asm volatile("s_nop 7" ::: "memory");   // accumulator writes before the first MFMA reads them
         const int total = cur.total;
-        if (nxt.valid) {
-            for (int b = 0; b < total; ++b, ++s) body(s, std::true_type{}, std::true_type{});
-        } else {
-            int b = 0;
-            for (; b < total - 2; ++b, ++s) body(s, std::true_type{}, std::true_type{});
-            body(s, std::false_type{}, std::true_type{});
-            ++s;
-            body(s, std::false_type{}, std::false_type{});
-            ++s;
-        }
+        for (int b = 0; b < total; ++b, ++s) body(s);
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs' results before the epilogue reads them
 
-        // epilogue through the wave's private 4 KB of LDS beyond the two stages
-        // (which the next tile's loads are already filling)
-        // (the lane id goes in through an opaque copy: the epilogue's per-lane
-        // addresses are then recomputed per tile instead of being kept, and
-        // spilled, across the main loop; a reload between two stores would wait
-        // for the first store to complete)
-        int lane_e = lane;
-        asm volatile("; lane id, rematerialised" : "+v"(lane_e));
-        stream_epilogue<FP, FQ>(smem + SMEM_STAGES + wave * SCR_BYTES, acc, p.y, p.y_f32, p.d_out, cur.row0,
-                                cur.n0, cur.q_rows, cur.p_rows, wp, wq, lane_e);
+        // Epilogue through the wave's private 8 KB beyond the stages (which the next tile's loads are
+        // already filling).  A lane holds, per accumulator (i, j), token 16 j + lane%16 and outputs
+        // 16 i + 4 (lane/16) + 0..3.  One 16-token block at a time: every lane parks its 32 outputs of
+        // the block's token in the scratch row of that token (slots of four outputs, the slot index
+        // XORed with twice the token so that the 16 tokens of a write hit different banks), then the
+        // wave reads the block back 16 bytes per lane and stores whole 128-byte lines.
+        {
+            int ln = lane;
+            asm volatile("; lane id, rematerialised" : "+v"(ln));
+            char *scr = smem + SMEM_STAGES + wave * SCR_BYTES;
+            const int t16 = ln & 15, kg = ln >> 4;
+            constexpr int EB = Y_F32 ? 4 : 2;           // bytes per output
+            constexpr int SLOT = 4 * EB;                // four outputs
+            constexpr int ROW = 128 * EB;               // a token's 128 outputs
+            const int64_t ldy = (int64_t)p.d_out * EB;
+#pragma unroll
+            for (int j = 0; j < FQ; ++j) {
+#pragma unroll
+                for (int i = 0; i < FP; ++i) {
+                    const int slot_ = (i * 4 + kg) ^ (2 * t16);
+                    const f32x4_t a = acc[i][j];
+                    if constexpr (Y_F32)
+                        *reinterpret_cast<f32x4_t *>(scr + t16 * ROW + slot_ * SLOT) = a;
+                    else
+                        *reinterpret_cast<uint2 *>(scr + t16 * ROW + slot_ * SLOT) =
+                            make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
+                }
+                lds_order();
+                // read back: 16 tokens x (ROW / 16) chunks of 16 bytes, 64 lanes per pass
+                constexpr int CPR = ROW / 16;           // chunks per token row (16 bf16 / 32 fp32)
+                constexpr int SPC = 16 / SLOT;          // slots per chunk (2 / 1)
+#pragma unroll
+                for (int ps = 0; ps < 16 * CPR / 64; ++ps) {
+                    const int idx = ps * 64 + ln;
+                    const int tt = idx / CPR, ch = idx % CPR;
+                    const int pslot = (ch * SPC) ^ (2 * tt);       // XOR with an even number keeps slot pairs adjacent
+                    const uint4 v = *reinterpret_cast<const uint4 *>(scr + tt * ROW + pslot * SLOT);
+                    const int m = wq * (FQ * 16) + j * 16 + tt;
+                    const int n = wp * (FP * 16) + ch * (16 / EB);
+                    if (m < cur.q_rows && n < cur.p_rows)   // d_out % 8 == 0: a chunk is all in or all out
+                        *reinterpret_cast<uint4 *>(p.y + (int64_t)(cur.row0 + m) * ldy + (int64_t)(cur.n0 + n) * EB) = v;
+                }
+                lds_order();
+            }
+        }
         if (!nxt.valid) break;
         cur = nxt;
         id += nslot;
-        nxt = load_tile(p, id, band_end);
+        nxt = stream::load_tile(p, id, band_end);
     }
 }
 
 hipError_t prepare_stream_kernel()
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_stream_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, stream::SMEM_BYTES);
+    hipError_t e;
+    if ((e = hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_stream_kernel<false>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, s16::SMEM_BYTES)) != hipSuccess)
+        return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&linear_stream_kernel<true>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, s16::SMEM_BYTES);
 }
 
 bool stream_kernel_fits(const LinearArgs &a)
@@ -301,8 +353,10 @@ hipError_t launch_linear_stream(const PlanView &pv, const LinearArgs &a, int n_c
     int64_t grid = n_cus > 0 ? n_cus : 256;
     if (grid > max_work) grid = max_work;
     grid = (grid + 7) / 8 * 8;
-    hipLaunchKernelGGL(linear_stream_kernel, dim3((unsigned)grid), dim3(stream::NT), stream::SMEM_BYTES,
-                       stream_, p);
+    if (p.y_f32)
+        hipLaunchKernelGGL(linear_stream_kernel<true>, dim3((unsigned)grid), dim3(s16::NT), s16::SMEM_BYTES, stream_, p);
+    else
+        hipLaunchKernelGGL(linear_stream_kernel<false>, dim3((unsigned)grid), dim3(s16::NT), s16::SMEM_BYTES, stream_, p);
     return hipGetLastError();
 }
 
