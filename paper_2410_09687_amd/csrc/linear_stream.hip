@@ -203,8 +203,9 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
 
     // One block of the stream: k-step 0 (its fragments were read during the block before) with the
     // reads of k-step 1 between its MFMAs; barrier; k-step 1 with the requests for the block two
-    // ahead and the first fragments of the next block between its MFMAs.  The order below IS the
-    // instruction order (scheduling barriers after every group).  No branch after the barrier: past
+    // ahead and the first fragments of the next block between its MFMAs (one of each per four MFMAs:
+    // all requests right behind the barrier, or reads first and requests last, measured slower).  The
+    // order below IS the instruction order (scheduling barriers after every group).  No branch after the barrier: past
     // the stream's end the fetch repeats the last block into the free stage and the reads take stale
     // bytes that nothing uses.
     auto body = [&](int s) __attribute__((always_inline)) {
@@ -237,9 +238,9 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
 #pragma unroll
         for (int n = 0; n < FP * FQ; ++n) {
             mfma(1, n / FQ, n % FQ);
-            if (n % 3 == 2 && n / 3 < FP + FQ) {
-                read_one(st_nxt, lo0, 0, n / 3);
-                issue_one(f, st_cur, n / 3);
+            if (n % 4 == 3) {   // one read and one request per four MFMAs
+                read_one(st_nxt, lo0, 0, n / 4);
+                issue_one(f, st_cur, n / 4);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
