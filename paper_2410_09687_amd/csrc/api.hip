@@ -929,13 +929,25 @@ int moin_lora_linear_planned_shared(moin_ctx *ctx, const moin_plan *plan, const 
             return launch_prefill_shrink_shared(pv, a, n, A_stack, u_hi, u_lo, st);
         }) != hipSuccess)
         return MOIN_EHIP;
+    LinearArgs all[MAX_SHARED_X];
+    bool stream_all = true;
     for (int i = 0; i < n; ++i) {
-        a.W = W[i]; a.A_stack = A_stack[i]; a.B_stack = B_stack[i];
-        a.u_hi = u_hi[i]; a.u_lo = u_lo[i];
-        a.y = y[i]; a.d_out = d_out[i];
-        if (timed(ctx, MOIN_K_LINEAR, st, [&] { return launch_prefill_linear(pv, a, st); }) != hipSuccess)
-            return MOIN_EHIP;
+        all[i] = a;
+        all[i].W = W[i]; all[i].A_stack = A_stack[i]; all[i].B_stack = B_stack[i];
+        all[i].u_hi = u_hi[i]; all[i].u_lo = u_lo[i];
+        all[i].y = y[i]; all[i].d_out = d_out[i];
+        stream_all = stream_all && stream_kernel_fits(all[i]);
     }
+    if (stream_all) {
+        // one launch: the projections' column tiles side by side in the streaming kernel, so a narrow
+        // projection (k, v) shares the wide one's x panels in L2 instead of streaming x on its own
+        if (timed(ctx, MOIN_K_LINEAR, st, [&] { return launch_prefill_linear_shared(pv, all, n, st); }) != hipSuccess)
+            return MOIN_EHIP;
+        return MOIN_OK;
+    }
+    for (int i = 0; i < n; ++i)
+        if (timed(ctx, MOIN_K_LINEAR, st, [&] { return launch_prefill_linear(pv, all[i], st); }) != hipSuccess)
+            return MOIN_EHIP;
     return MOIN_OK;
 }
 

@@ -77,6 +77,10 @@ constexpr int MAX_SHARED_X = 4;
 hipError_t launch_prefill_shrink_shared(const PlanView &pv, const LinearArgs &a, int n, const void *const *A_stack,
                                         void *const *u_hi, void *const *u_lo, hipStream_t stream);
 hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStream_t stream);
+// The main products of n projections that share x, d_in, r and the output type in ONE launch of the
+// streaming kernel (a[i]: W, B_stack, u_hi, u_lo, y, d_out of projection i); every a[i] must satisfy
+// stream_kernel_fits.  Results are those of n single launches, bit for bit.
+hipError_t launch_prefill_linear_shared(const PlanView &pv, const LinearArgs *a, int n, hipStream_t stream);
 // shapes the persistent streaming prefill kernel takes (anything else: the tiled kernel)
 bool stream_kernel_fits(const LinearArgs &a);
 // shrink + MXFP8 codes / blocked scales of x in one pass over x (d_in a multiple of 128)

@@ -214,6 +214,7 @@ static hipError_t allow_lds(K kern, int bytes)
 hipError_t prepare_stream_kernel();
 bool stream_kernel_fits(const LinearArgs &a);
 hipError_t launch_linear_stream(const PlanView &pv, const LinearArgs &a, int n_cus, hipStream_t stream);
+hipError_t launch_linear_stream_shared(const PlanView &pv, const LinearArgs *a, int n, int n_cus, hipStream_t stream);
 
 hipError_t prepare_linear_kernels()
 {
@@ -329,6 +330,12 @@ static hipError_t launch_linear_as(const LinearKParams &p0, int64_t m_tiles, hip
     hipLaunchKernelGGL(linear_kernel<C>, dim3((unsigned)round_up8((int)total)), dim3(C::NT),
                        C::SMEM_BYTES, stream, p);
     return hipGetLastError();
+}
+
+hipError_t launch_prefill_linear_shared(const PlanView &pv, const LinearArgs *a, int n, hipStream_t stream)
+{
+    if (pv.max_tiles <= 0) return hipSuccess;
+    return launch_linear_stream_shared(pv, a, n, compute_units(), stream);
 }
 
 hipError_t launch_prefill_linear(const PlanView &pv, const LinearArgs &a, hipStream_t stream)

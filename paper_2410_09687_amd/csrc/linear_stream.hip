@@ -35,12 +35,19 @@ constexpr int OP_BYTES = BT * ROWB;  // one operand tile: 32 KB
 constexpr int STAGE_BYTES = 2 * OP_BYTES;
 constexpr int SMEM_STAGES = 2 * STAGE_BYTES;
 
+// Up to MAX_SHARED_X projections that read the same x (q, k, v; gate, up) in one launch: the column
+// tiles of projection i follow those of projection i - 1, so a narrow projection's tiles (k, v: one
+// column of tiles) ride in the wide one's stream and share its x panels in L2.
 struct Params {
-    const char *x, *W, *B_stack, *u_hi, *u_lo;
-    char *y;
+    const char *x;
+    const char *W[MAX_SHARED_X], *B_stack[MAX_SHARED_X], *u_hi[MAX_SHARED_X], *u_lo[MAX_SHARED_X];
+    char *y[MAX_SHARED_X];
+    int d_out[MAX_SHARED_X];
+    int tn_start[MAX_SHARED_X];   // first column tile of each projection (tn_start[0] = 0)
+    int n_proj;
     const int *tile_row0, *tile_rows, *tile_expert, *tile_rank, *n_tiles;
-    int d_in, d_out, r;
-    int n_tiles_n;
+    int d_in, r;
+    int n_tiles_n;                // column tiles of all projections together
     int y_f32;
 };
 
@@ -52,6 +59,8 @@ struct Tile {
     int nkb1;                  // adapter blocks per half (0: no adapter)
     int total;                 // blocks of the tile: nkb0 + 2 * nkb1
     int row0, n0;
+    char *y;                   // the projection's output and its width
+    int d_out;
     int valid;
 };
 
@@ -64,19 +73,33 @@ __device__ __forceinline__ Tile load_tile(const Params &p, int id, int n_work)
     const int e = uniform(p.tile_expert[tm]);
     t.row0 = uniform(p.tile_row0[tm]);
     t.q_rows = uniform(p.tile_rows[tm]);
-    t.n0 = tn * BT;
-    t.p_rows = min(BT, p.d_out - t.n0);
+    // the projection of this column tile (picked by comparison, not by indexing: indexing the
+    // parameter arrays would put them in scratch)
+    const char *W = p.W[0], *B_stack = p.B_stack[0], *u_hi = p.u_hi[0], *u_lo = p.u_lo[0];
+    int tn0 = 0;
+    t.y = p.y[0];
+    t.d_out = p.d_out[0];
+#pragma unroll
+    for (int i = 1; i < MAX_SHARED_X; ++i)
+        if (i < p.n_proj && tn >= p.tn_start[i]) {
+            W = p.W[i]; B_stack = p.B_stack[i]; u_hi = p.u_hi[i]; u_lo = p.u_lo[i];
+            t.y = p.y[i];
+            t.d_out = p.d_out[i];
+            tn0 = p.tn_start[i];
+        }
+    t.n0 = (tn - tn0) * BT;
+    t.p_rows = min(BT, t.d_out - t.n0);
     const int64_t ldx = (int64_t)p.d_in * 2, ldu = (int64_t)p.r * 2;
     t.q0 = p.x + (int64_t)t.row0 * ldx;
-    t.p0 = p.W + (int64_t)t.n0 * ldx;
+    t.p0 = W + (int64_t)t.n0 * ldx;
     // adapter blocks up to the expert's own rank (the shrink wrote zeros from there to the block end)
     const int re = min(p.r, uniform(p.tile_rank[tm]));
     const bool lora = e >= 0 && re > 0;
     t.nkb1 = lora ? (re + BK - 1) / BK : 0;
     t.total = p.d_in / BK + 2 * t.nkb1;
-    t.uh = lora ? p.u_hi + (int64_t)t.row0 * ldu : t.q0;
-    t.ul = lora ? p.u_lo + (int64_t)t.row0 * ldu : t.q0;
-    t.be = lora ? p.B_stack + ((int64_t)e * p.d_out + t.n0) * ldu : t.p0;
+    t.uh = lora ? u_hi + (int64_t)t.row0 * ldu : t.q0;
+    t.ul = lora ? u_lo + (int64_t)t.row0 * ldu : t.q0;
+    t.be = lora ? B_stack + ((int64_t)e * t.d_out + t.n0) * ldu : t.p0;
     return t;
 }
 
@@ -283,7 +306,7 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
             constexpr int EB = Y_F32 ? 4 : 2;           // bytes per output
             constexpr int SLOT = 4 * EB;                // four outputs
             constexpr int ROW = 128 * EB;               // a token's 128 outputs
-            const int64_t ldy = (int64_t)p.d_out * EB;
+            const int64_t ldy = (int64_t)cur.d_out * EB;
 #pragma unroll
             for (int j = 0; j < FQ; ++j) {
 #pragma unroll
@@ -309,7 +332,7 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
                     const int m = wq * (FQ * 16) + j * 16 + tt;
                     const int n = wp * (FP * 16) + ch * (16 / EB);
                     if (m < cur.q_rows && n < cur.p_rows)   // d_out % 8 == 0: a chunk is all in or all out
-                        *reinterpret_cast<uint4 *>(p.y + (int64_t)(cur.row0 + m) * ldy + (int64_t)(cur.n0 + n) * EB) = v;
+                        *reinterpret_cast<uint4 *>(cur.y + (int64_t)(cur.row0 + m) * ldy + (int64_t)(cur.n0 + n) * EB) = v;
                 }
                 lds_order();
             }
@@ -336,21 +359,34 @@ bool stream_kernel_fits(const LinearArgs &a)
     return a.d_in % 64 == 0 && a.r % 64 == 0 && a.d_in >= 128;
 }
 
-hipError_t launch_linear_stream(const PlanView &pv, const LinearArgs &a, int n_cus, hipStream_t stream_)
+// n projections that share x, d_in, r and the output type (a[i]: W, B_stack, u_hi, u_lo, y, d_out of
+// projection i; a[0] also x, d_in, r, y_f32)
+hipError_t launch_linear_stream_shared(const PlanView &pv, const LinearArgs *a, int n, int n_cus, hipStream_t stream_)
 {
+    if (n < 1 || n > MAX_SHARED_X) return hipErrorInvalidValue;
     stream::Params p;
-    p.x = (const char *)a.x; p.W = (const char *)a.W; p.B_stack = (const char *)a.B_stack;
-    p.u_hi = (const char *)a.u_hi; p.u_lo = (const char *)a.u_lo;
-    p.y = (char *)a.y;
+    p.x = (const char *)a[0].x;
+    p.n_proj = n;
+    int tn = 0;
+    for (int i = 0; i < MAX_SHARED_X; ++i) {
+        const LinearArgs &ai = a[i < n ? i : 0];
+        p.W[i] = (const char *)ai.W; p.B_stack[i] = (const char *)ai.B_stack;
+        p.u_hi[i] = (const char *)ai.u_hi; p.u_lo[i] = (const char *)ai.u_lo;
+        p.y[i] = (char *)ai.y;
+        p.d_out[i] = ai.d_out;
+        p.tn_start[i] = tn;
+        if (i < n) tn += (ai.d_out + stream::BT - 1) / stream::BT;
+    }
     p.tile_row0 = pv.tile_row0; p.tile_rows = pv.tile_rows; p.tile_expert = pv.tile_expert;
     p.tile_rank = pv.tile_rank;
     p.n_tiles = pv.n_tiles;
-    p.d_in = a.d_in; p.d_out = a.d_out; p.r = a.r;
-    p.n_tiles_n = (a.d_out + stream::BT - 1) / stream::BT;
-    p.y_f32 = a.y_f32;
+    p.d_in = a[0].d_in; p.r = a[0].r;
+    p.n_tiles_n = tn;
+    p.y_f32 = a[0].y_f32;
     // one workgroup per compute unit (the LDS footprint allows no more), fewer
     // when the batch has fewer tiles than that; always a multiple of 8
     const int64_t max_work = (int64_t)pv.max_tiles * p.n_tiles_n;
+    if (max_work > 0x7fffffffLL) return hipErrorInvalidValue;
     int64_t grid = n_cus > 0 ? n_cus : 256;
     if (grid > max_work) grid = max_work;
     grid = (grid + 7) / 8 * 8;
@@ -359,6 +395,11 @@ hipError_t launch_linear_stream(const PlanView &pv, const LinearArgs &a, int n_c
     else
         hipLaunchKernelGGL(linear_stream_kernel<false>, dim3((unsigned)grid), dim3(s16::NT), s16::SMEM_BYTES, stream_, p);
     return hipGetLastError();
+}
+
+hipError_t launch_linear_stream(const PlanView &pv, const LinearArgs &a, int n_cus, hipStream_t stream_)
+{
+    return launch_linear_stream_shared(pv, &a, 1, n_cus, stream_);
 }
 
 }  // namespace moin
