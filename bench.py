@@ -209,12 +209,13 @@ def bench_prefill(ctx, steps, warmup, with_cpu):
     route_out = (torch.empty(w.S, dtype=torch.int32, device="cuda"), None,
                  torch.empty(w.E, dtype=torch.int32, device="cuda"))
 
+    plan = moin.Plan(ctx)
+
     def step():
-        eids, _, _ = moin.moin_route(ctx, rin.emb, rin.centroids, slot_of_centroid=slots,
-                                     want_centroid_ids=False, want_counts=True, out=route_out,
-                                     same_centroids=True)
-        moin.moin_lora_linear(ctx, inp.x, inp.seq_offsets, eids, inp.W, inp.A_stack, inp.B_stack,
-                              w.scale, out=y)
+        # routing, histogram, slot map and grouping: one launch for a request-sized batch
+        moin.moin_route_plan(ctx, plan, rin.emb, rin.centroids, inp.seq_offsets, w.T, w.E,
+                             slot_of_centroid=slots, out=route_out, same_centroids=True)
+        moin.moin_lora_linear_planned(ctx, plan, inp.x, inp.W, inp.A_stack, inp.B_stack, w.scale, out=y)
 
     # The chip takes tens of milliseconds of load to leave its idle clocks: bring it to its working state
     # first (untimed, like the set-up above), so that the W warm-up steps and the K timed ones measure the

@@ -195,6 +195,24 @@ int moin_lora_linear_planned_shared(moin_ctx *ctx, const moin_plan *plan, const 
                                     int32_t r, float scale, void *const *y, moin_dtype y_dt,
                                     void *stream);
 
+/* moin_route followed by moin_plan_build_ranked on the ids it produced, for a batch
+ * whose N queries ARE its S = N sequences (Section 1: each query goes to one expert;
+ * Section 3.2: the expert's adapter then serves every linear layer of that query).
+ * A request-sized batch (bf16, D a multiple of 64, N <= 512, K <= 16384) takes ONE
+ * launch: the workgroup that finishes the routing groups the batch by the ids it has
+ * just written; any other batch takes the launches of the two calls.  Results are
+ * those of the two calls.  Arguments as in moin_route and moin_plan_build_ranked;
+ * expert_ids [N] is required (it is the plan's input and stays the caller's), the
+ * ids are adapter slots of [0, E) or -1 when slot_of_centroid is given and centroid
+ * indices otherwise (then E >= K is required); rank_of_expert may be NULL.
+ * Errors: those of the two calls. */
+int moin_route_plan(moin_ctx *ctx, moin_plan *plan, const void *emb, const void *centroids,
+                    int64_t N, int32_t K, int32_t D, moin_dtype dt,
+                    const int32_t *slot_of_centroid, uint32_t flags,
+                    const int32_t *seq_offsets, int64_t T, int32_t E,
+                    const int32_t *rank_of_expert, int32_t *expert_ids,
+                    int32_t *centroid_ids, int32_t *counts, void *stream);
+
 /* ---- HIP graphs and the library's own device memory ----------------------------
  * The context's workspace and a plan's buffer grow on demand (hipMalloc), which a
  * stream under capture must not do.  A call on a capturing stream that would have

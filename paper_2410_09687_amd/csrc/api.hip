@@ -269,9 +269,11 @@ int plan_grow(moin_plan *plan, size_t bytes, hipStream_t st)
     return MOIN_OK;
 }
 
-int plan_build_impl(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
-                    const int32_t *expert_ids, int32_t S, int64_t T, int32_t E,
-                    const int32_t *rank_of_expert, hipStream_t stream)
+// Sizes the plan's buffer for a batch and points the view's arrays into it; nothing is launched.
+// Returns 1 when the batch is empty (the plan is then complete as it stands), 0 when the grouping
+// has to run, a negative status on a fault.
+static int plan_prepare(moin_plan *plan, const int32_t *seq_offsets, const int32_t *expert_ids, int32_t S,
+                        int64_t T, int32_t E, hipStream_t stream)
 {
     if (S < 0 || T < 0 || E < 0 || T > 0x7fffffffLL - TILE_M) return MOIN_EINVAL;
     plan->built = 0;
@@ -281,7 +283,7 @@ int plan_build_impl(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
     if (S == 0 || T == 0) {
         // nothing to compute; a planned call returns at once
         plan->built = 1;
-        return MOIN_OK;
+        return 1;
     }
     if (!seq_offsets || !expert_ids) return MOIN_EINVAL;
     const PlanLayout L = plan_layout(S, T, E);
@@ -310,6 +312,16 @@ int plan_build_impl(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
     pv.max_tiles = L.max_tiles;
     pv.max_groups = L.max_groups;
     pv.decode = L.decode;
+    return 0;
+}
+
+int plan_build_impl(moin_ctx *ctx, moin_plan *plan, const int32_t *seq_offsets,
+                    const int32_t *expert_ids, int32_t S, int64_t T, int32_t E,
+                    const int32_t *rank_of_expert, hipStream_t stream)
+{
+    const int prc = plan_prepare(plan, seq_offsets, expert_ids, S, T, E, stream);
+    if (prc != 0) return prc < 0 ? prc : MOIN_OK;
+    const PlanView &pv = plan->pv;
     const hipError_t e = timed(ctx, MOIN_K_PLAN, stream, [&] {
         return launch_plan(pv, seq_offsets, expert_ids, rank_of_expert, ctx->err_word, stream);
     });
@@ -638,6 +650,12 @@ static int validate_route(moin_ctx *ctx, const void *emb, const void *centroids,
     return MOIN_OK;
 }
 
+// A grouping that rides in the routing launch (request-sized batches only).
+struct RoutePlanFuse {
+    const PlanView *pv;
+    const int32_t *seq_offsets, *rank_of_expert;
+};
+
 // Where a routing call keeps its intermediate results inside a block of device memory.
 struct RouteScratch {
     size_t cnorm, cinit, best, arrivals, cid, total;
@@ -665,7 +683,8 @@ static RouteScratch route_scratch(int64_t N, int32_t K, int32_t D, moin_dtype dt
 static int route_launches(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N, int32_t K,
                           int32_t D, moin_dtype dt, const int32_t *slot_of_centroid, uint32_t flags,
                           int32_t *expert_ids, int32_t *centroid_ids, int32_t *counts, char *w,
-                          const RouteScratch &L, bool need_cid, bool record, hipStream_t st, int self_clean = 0)
+                          const RouteScratch &L, bool need_cid, bool record, hipStream_t st, int self_clean = 0,
+                          const RoutePlanFuse *fuse = nullptr)
 {
     RouteArgs a;
     a.emb = emb; a.cent = centroids; a.N = N; a.K = K; a.D = D;
@@ -681,6 +700,12 @@ static int route_launches(moin_ctx *ctx, const void *emb, const void *centroids,
     a.expert_ids = expert_ids;
     a.counts = counts;
     a.self_clean = self_clean ? 1 : 0;   // 1: norms kernel + self-cleaning kernel, 2: the norms in w are current
+    if (fuse) {
+        a.plan = fuse->pv;
+        a.seq_offsets = fuse->seq_offsets;
+        a.rank_of_expert = fuse->rank_of_expert;
+        a.err_word = ctx->err_word;
+    }
 
     auto run = [&](int kernel, auto launch) {
         return record ? timed(ctx, kernel, st, launch) : launch();
@@ -724,19 +749,24 @@ int moin_plan_reserve(moin_ctx *ctx, moin_plan *plan, int32_t S, int64_t T, int3
     return plan_grow(plan, need, static_cast<hipStream_t>(stream));
 }
 
-int moin_route(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N, int32_t K,
-               int32_t D, moin_dtype dt, const int32_t *slot_of_centroid, uint32_t flags,
-               int32_t *expert_ids, int32_t *centroid_ids, int32_t *counts, void *stream)
+// True when route_impl would take the single self-cleaning launch for this call.
+static bool route_one_launch(int64_t N, int32_t K, int32_t D, moin_dtype dt, const int32_t *expert_ids,
+                             const int32_t *centroid_ids)
 {
-    const int vrc = validate_route(ctx, emb, centroids, N, K, D, dt, slot_of_centroid, flags);
-    if (vrc != MOIN_OK) return vrc;
-    DeviceGuard guard(ctx->device);
-    if (!guard.ok) return MOIN_EHIP;
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    return N > 0 && (expert_ids || centroid_ids) && K <= ROUTE_SELF_CLEAN_MAX_K &&
+           route_small_batch(N, K, D, dt == MOIN_BF16);
+}
+
+// moin_route after validation, with the device current.  `fuse` (only with route_one_launch() true):
+// the launch goes on to group the batch by the ids it has just written.
+static int route_impl(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N, int32_t K,
+                      int32_t D, moin_dtype dt, const int32_t *slot_of_centroid, uint32_t flags,
+                      int32_t *expert_ids, int32_t *centroid_ids, int32_t *counts, hipStream_t st,
+                      const RoutePlanFuse *fuse)
+{
     const bool need_cid = counts && !centroid_ids && N > 0;
     RouteScratch L = route_scratch(N, K, D, dt, need_cid);
-    if (N > 0 && (expert_ids || centroid_ids) && K <= ROUTE_SELF_CLEAN_MAX_K &&
-        route_small_batch(N, K, D, dt == MOIN_BF16)) {
+    if (route_one_launch(N, K, D, dt, expert_ids, centroid_ids)) {
         // (minima and counter first, at offsets that do not move with K: they must stay clean)
         const size_t cn_bytes = L.cinit - L.cnorm;
         L.best = 0;
@@ -788,12 +818,54 @@ int moin_route(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N,
         ctx->route_key.retained = retained; ctx->route_key.valid = 1;
         return route_launches(ctx, emb, centroids, N, K, D, dt, slot_of_centroid, flags, expert_ids,
                               centroid_ids, counts, static_cast<char *>(ctx->route_buf), L, need_cid, true, st,
-                              reuse ? 2 : 1);
+                              reuse ? 2 : 1, fuse);
     }
+    if (fuse) return MOIN_EINVAL;   // (the caller asks for it only where it applies)
     const int rc = ensure_ws(ctx, L.total, st);
     if (rc != MOIN_OK) return rc;
     return route_launches(ctx, emb, centroids, N, K, D, dt, slot_of_centroid, flags, expert_ids,
                           centroid_ids, counts, static_cast<char *>(ctx->ws), L, need_cid, true, st);
+}
+
+int moin_route(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N, int32_t K,
+               int32_t D, moin_dtype dt, const int32_t *slot_of_centroid, uint32_t flags,
+               int32_t *expert_ids, int32_t *centroid_ids, int32_t *counts, void *stream)
+{
+    const int vrc = validate_route(ctx, emb, centroids, N, K, D, dt, slot_of_centroid, flags);
+    if (vrc != MOIN_OK) return vrc;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    return route_impl(ctx, emb, centroids, N, K, D, dt, slot_of_centroid, flags, expert_ids, centroid_ids,
+                      counts, static_cast<hipStream_t>(stream), nullptr);
+}
+
+int moin_route_plan(moin_ctx *ctx, moin_plan *plan, const void *emb, const void *centroids, int64_t N,
+                    int32_t K, int32_t D, moin_dtype dt, const int32_t *slot_of_centroid, uint32_t flags,
+                    const int32_t *seq_offsets, int64_t T, int32_t E, const int32_t *rank_of_expert,
+                    int32_t *expert_ids, int32_t *centroid_ids, int32_t *counts, void *stream)
+{
+    const int vrc = validate_route(ctx, emb, centroids, N, K, D, dt, slot_of_centroid, flags);
+    if (vrc != MOIN_OK) return vrc;
+    if (!plan || plan->device != ctx->device || (N > 0 && !expert_ids) || N > 0x7fffffffLL) return MOIN_EINVAL;
+    // ids are adapter slots when a map is given, centroid indices otherwise: E must cover them
+    if (!slot_of_centroid && E < K) return MOIN_EINVAL;
+    DeviceGuard guard(ctx->device);
+    if (!guard.ok) return MOIN_EHIP;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int32_t S = (int32_t)N;
+    if (S <= ROUTE_PLAN_FUSED_MAX_S && T > 0 && route_one_launch(N, K, D, dt, expert_ids, centroid_ids)) {
+        const int prc = plan_prepare(plan, seq_offsets, expert_ids, S, T, E, st);
+        if (prc < 0) return prc;
+        const RoutePlanFuse fuse{&plan->pv, seq_offsets, rank_of_expert};
+        const int rc = route_impl(ctx, emb, centroids, N, K, D, dt, slot_of_centroid, flags, expert_ids,
+                                  centroid_ids, counts, st, &fuse);
+        if (rc == MOIN_OK) plan->built = 1;
+        return rc;
+    }
+    const int rc = route_impl(ctx, emb, centroids, N, K, D, dt, slot_of_centroid, flags, expert_ids,
+                              centroid_ids, counts, st, nullptr);
+    if (rc != MOIN_OK) return rc;
+    return plan_build_impl(ctx, plan, seq_offsets, expert_ids, S, T, E, rank_of_expert, st);
 }
 
 int moin_route_static(moin_ctx *ctx, const void *emb, const void *centroids, int64_t N, int32_t K,

@@ -127,7 +127,13 @@ struct RouteArgs {
     int group;                 // route_stream_group() of the call
     int self_clean = 0;        // small batches: best / arrivals are kept clean between calls by the kernel
                                // itself, counts are zeroed by its finishing workgroup (no reset launch)
+    // small batches, optional: the routed batch is grouped by expert in the same launch (the queries
+    // are the batch's S = N sequences; expert_ids must be given)
+    const PlanView *plan = nullptr;
+    const int *seq_offsets = nullptr, *rank_of_expert = nullptr;
+    int *err_word = nullptr;
 };
+constexpr int ROUTE_PLAN_FUSED_MAX_S = 512;  // the grouping rides in the routing launch up to this many queries
 constexpr int ROUTE_SMALL_MAX_N = 4096;  // up to here the K range is split across workgroups
 // true for the batches the small-batch kernel takes (bf16, D a multiple of 64, N <= ROUTE_SMALL_MAX_N)
 bool route_small_batch(int64_t N, int K, int D, int is_bf16);

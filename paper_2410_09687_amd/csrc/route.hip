@@ -15,6 +15,7 @@
 
 #include "gemm_core.h"
 #include "kernels.h"
+#include "plan_body.h"
 
 namespace moin {
 
@@ -37,6 +38,12 @@ struct RouteKParams {
     int group;            // streaming kernel: workgroups that share one query tile
     int self_clean;       // small-batch kernel: best / arrivals are clean on entry and are left clean
                           // (the finishing workgroup resets them and zeroes counts before its tally)
+    // small-batch kernel, optional: the finishing workgroup goes on to group the routed batch by
+    // expert (queries = the batch's sequences), so that routing and grouping are one launch
+    int with_plan;
+    PlanView plan;
+    const int *seq_offsets, *rank_of_expert;
+    int *err_word;
 };
 
 __device__ __forceinline__ bool lex_less(float v, int i, float bv, int bi)
@@ -571,6 +578,14 @@ __global__ __launch_bounds__(C::NT) void route_small_kernel(RouteKParams p, int 
         if (p.expert_ids) p.expert_ids[q] = p.slot ? p.slot[bi] : bi;
         if (p.counts) atomicAdd(&p.counts[bi], 1);
     }
+    if constexpr (C::NT == PLAN_THREADS_SMALL) {
+        if (p.with_plan) {
+            // the ids this workgroup has just written are the plan's input
+            __threadfence_block();
+            __syncthreads();
+            plan_body<PLAN_THREADS_SMALL>(p.plan, p.seq_offsets, p.expert_ids, p.rank_of_expert, p.err_word);
+        }
+    }
 }
 
 // ||c_k||^2 in fp32 (one wave per centroid), +inf for centroids left out of the
@@ -917,6 +932,19 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t stream)
         p.N = a.N; p.K = a.K; p.D = a.D;
         p.group = a.group > 1 ? a.group : 1;
         p.self_clean = use_small_route(a) ? a.self_clean : 0;
+        static_assert(ROUTE_PLAN_FUSED_MAX_S <= 2 * PLAN_THREADS_SMALL && CfgRouteSmall::NT == PLAN_THREADS_SMALL,
+                      "the grouping that rides in the small-batch launch is the four-wave one");
+        if (a.plan && !(use_small_route(a) && a.self_clean && a.expert_ids && a.seq_offsets && a.err_word &&
+                        a.N <= ROUTE_PLAN_FUSED_MAX_S && a.plan->S == (int)a.N))
+            return hipErrorInvalidValue;
+        p.with_plan = a.plan ? 1 : 0;
+        if (p.with_plan) {
+            p.plan = *a.plan;
+            p.seq_offsets = a.seq_offsets; p.rank_of_expert = a.rank_of_expert; p.err_word = a.err_word;
+        } else {
+            p.plan = PlanView{};
+            p.seq_offsets = p.rank_of_expert = nullptr; p.err_word = nullptr;
+        }
         if (use_small_route(a)) {
             using C = CfgRouteSmall;
             const int nqt = (int)((a.N + C::BN - 1) / C::BN);

@@ -38,7 +38,7 @@ EXPORTS = [
     "moin_probe_out_len", "moin_probe_mfma_bf16", "moin_probe_mfma_mxfp8", "moin_probe_read", "moin_set_adapter_activation",
     "moin_lora_linear_planned_shared", "moin_route_topk", "moin_merge_adapters",
     "moin_reserve_workspace", "moin_workspace_bytes", "moin_plan_reserve", "moin_route_static",
-    "moin_cache_set_overlap",
+    "moin_cache_set_overlap", "moin_route_plan",
 ]
 ACTIVATIONS = {None: 0, "none": 0, "relu": 1, "silu": 2, "gelu": 3}
 CACHE_STATS = ["batches", "seq_hits", "seq_misses", "loads", "evictions", "overflows", "bytes"]
@@ -97,6 +97,8 @@ def load() -> ctypes.CDLL:
     lib.moin_probe_mfma_mxfp8.argtypes = [vp, vp, i64, i32, vp, c.POINTER(c.c_double), vp]
     lib.moin_probe_read.argtypes = [vp, vp, i64, vp, vp]
     lib.moin_plan_build_ranked.argtypes = [vp, vp, vp, vp, i32, i64, i32, vp, vp]
+    lib.moin_route_plan.argtypes = [vp, vp, vp, vp, i64, i32, i32, c.c_int, vp, c.c_uint32, vp, i64, i32, vp,
+                                    vp, vp, vp, vp]
     lib.moin_plan_create.argtypes = [vp, c.POINTER(vp)]
     lib.moin_plan_destroy.argtypes = [vp]
     lib.moin_plan_destroy.restype = None
@@ -438,6 +440,51 @@ class Plan:
             self.close()
         except Exception:
             pass
+
+
+def moin_route_plan(ctx: Context, plan: Plan, emb: torch.Tensor, centroids: torch.Tensor,
+                    seq_offsets: torch.Tensor, T: int, E: int,
+                    slot_of_centroid: Optional[torch.Tensor] = None, retained_only: bool = False,
+                    rank_of_expert: Optional[torch.Tensor] = None, want_centroid_ids: bool = False,
+                    want_counts: bool = False, same_centroids: bool = False, stream=None, out=None):
+    """``moin_route`` and ``Plan.build`` on its ids in one call (one launch for a request-sized batch): the
+    ``N`` queries are the batch's sequences.  Returns ``(expert_ids, centroid_ids or None, counts or None)``;
+    ``plan`` is rebuilt.  ``out``: the same triple preallocated by the caller (``expert_ids`` required)."""
+    if emb.dim() != 2 or centroids.dim() != 2 or emb.shape[1] != centroids.shape[1]:
+        raise ValueError("emb [N,D] and centroids [K,D] expected")
+    if emb.dtype != centroids.dtype or emb.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("emb/centroids must both be float32 or both bfloat16")
+    N, D = emb.shape
+    K = centroids.shape[0]
+    if seq_offsets.numel() != N + 1:
+        raise ValueError("seq_offsets must have N+1 entries")
+    if rank_of_expert is not None and rank_of_expert.numel() != E:
+        raise ValueError("rank_of_expert must have E entries")
+    dt = MOIN_BF16 if emb.dtype == torch.bfloat16 else MOIN_F32
+    dev = centroids.device
+    if out is not None:
+        expert_ids, cids, counts = out
+        if expert_ids is None:
+            raise ValueError("out: expert_ids is required")
+        for t, n in ((expert_ids, N), (cids, N), (counts, K)):
+            if t is not None and (t.dtype != torch.int32 or t.numel() != n):
+                raise ValueError("out: int32 tensors of N, N and K elements (or None) expected")
+    else:
+        expert_ids = torch.empty(N, dtype=torch.int32, device=dev)
+        cids = torch.empty(N, dtype=torch.int32, device=dev) if want_centroid_ids else None
+        counts = torch.empty(K, dtype=torch.int32, device=dev) if want_counts else None
+    _ck(load().moin_route_plan(ctx._h, plan._h, _dev_ptr(emb, "emb") if N else None,
+                               _dev_ptr(centroids, "centroids"), N, K, D, dt,
+                               _dev_ptr(slot_of_centroid, "slot_of_centroid", torch.int32),
+                               (MOIN_ROUTE_RETAINED_ONLY if retained_only else 0)
+                               | (MOIN_ROUTE_SAME_CENTROIDS if same_centroids else 0),
+                               _dev_ptr(seq_offsets, "seq_offsets", torch.int32), int(T), int(E),
+                               _dev_ptr(rank_of_expert, "rank_of_expert", torch.int32),
+                               _dev_ptr(expert_ids, "expert_ids"),
+                               _dev_ptr(cids, "centroid_ids") if (cids is not None and N) else None,
+                               _dev_ptr(counts, "counts"), _stream_ptr(stream)), "moin_route_plan")
+    plan.T, plan.S, plan.E = int(T), N, int(E)
+    return expert_ids, cids, counts
 
 
 def moin_lora_linear_planned(ctx: Context, plan: Plan, x: torch.Tensor, W: torch.Tensor,
