@@ -116,20 +116,34 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
     const char *ae = shrink ? A_stack + ((int64_t)e * p.r + n0) * ldx : xa;
     const int nkb = (p.d_in + C::BK - 1) / C::BK;
 
+    // Workgroups that start together would all ask for the same 128 bytes of their rows, one row
+    // pitch (4 KB and up) apart from the next: requests that pile up on a few memory channels.  Each
+    // 256-row tile therefore starts its walk over the contraction at another block and wraps round
+    // (the sub-tiles of a tile, and the projections that share x, keep one phase so that they meet
+    // in L2): 88 -> 70 us for a 65536 x 2048 pass at rank 128.  The phase comes from the tile's
+    // position in the batch, not from its place in the by-expert order, and is the same in every
+    // variant of this kernel, so that a row's sum depends neither on how the experts are numbered
+    // nor on which variant ran.
+    const int k_first = (int)(((uint32_t)(row0 - sub * C::BM) / (uint32_t)TILE_M * 5u) % (uint32_t)nkb);
+    auto block_of = [=](int it) __attribute__((always_inline)) {
+        const int kb = it + k_first;
+        return kb >= nkb ? kb - nkb : kb;
+    };
+
     typename C::Acc acc;
     C::zero(acc);
     if constexpr (C::IS_DMA) {
         const auto la = C::template make_lanes<C::A_I>(rows);
         const auto lb = C::template make_lanes<C::B_I>(ncols);
         auto issue = [=](int it, char *stage) __attribute__((always_inline)) {
-            C::issue(stage, xa, ldx, la, ae, ldx, lb, (uint32_t)it * (C::BK * 2));
+            C::issue(stage, xa, ldx, la, ae, ldx, lb, (uint32_t)block_of(it) * (C::BK * 2));
         };
         dma_pipelined_blocks<C>(smem, nkb, issue, acc, [](int) {});
     } else {
         const auto vx = C::template make_view<C::A_CH>(xa, ldx, rows);
         const auto va = C::template make_view<C::B_CH>(ae, ldx, shrink ? ncols : rows);
         auto issue = [=](int it, typename C::Stage &g) __attribute__((always_inline)) {
-            C::load_stage(g, vx, va, (uint32_t)it * (C::BK * 2), ldx);
+            C::load_stage(g, vx, va, (uint32_t)block_of(it) * (C::BK * 2), ldx);
         };
         if constexpr (C::PF > 1) {
             static_assert(!QUANT || C::BK == 64, "a block of 32 values in four neighbouring lanes, two per row");
@@ -146,7 +160,7 @@ __global__ __launch_bounds__(C::NT) void shrink_kernel(ShrinkKParams p)
                         const uint32_t pair = (uint32_t)E | ((uint32_t)__shfl_down(E, 4) << 8);
                         const int row = qrow + i * C::RPP;
                         if (row < rows) {
-                            const int k0 = it * 64;
+                            const int k0 = block_of(it) * 64;
                             *reinterpret_cast<uint2 *>(p.xq + (int64_t)(row0 + row) * p.d_in + k0 + kc * 8) = codes;
                             if (kc == 0)
                                 *reinterpret_cast<uint16_t *>(p.xs + ((int64_t)(k0 >> 7) * p.T + row0 + row) * 4 +
