@@ -974,6 +974,41 @@ int moin_lora_linear_planned_shared(moin_ctx *ctx, const moin_plan *plan, const 
                                         pv.E, d_in, d_out[i], r, scale, y[i], y_dt);
         if (vrc != MOIN_OK) return vrc;
     }
+    if (pv.decode && adapters && n > 1 && pv.max_plain == 0) {
+        // Decode-sized batch: the projections' base tiles and shrink slabs in one launch, their expand
+        // blocks in another, where they agree in everything those launches share.
+        DecodeArgs d[MAX_SHARED_X];
+        size_t off[MAX_SHARED_X], total = 0;
+        const size_t u_bytes = align_up((size_t)pv.T * (size_t)r * 2, 256);
+        for (int i = 0; i < n; ++i) {
+            LinearArgs &a = d[i].lin;
+            a.x = x; a.W = W[i]; a.A_stack = A_stack[i]; a.B_stack = B_stack[i];
+            a.y = y[i]; a.y_f32 = (y_dt == MOIN_F32);
+            a.d_in = d_in; a.d_out = d_out[i]; a.r = r; a.scale = scale; a.act = ctx->act;
+            a.u_hi = a.u_lo = nullptr;
+            d[i].k_splits = decode_base_splits(pv.T, d_in, d_out[i]);
+            d[i].ybase_by_pos = 1;
+            off[i] = total;
+            total += 2 * u_bytes + align_up((size_t)d[i].k_splits * (size_t)pv.T * (size_t)d_out[i] * 4, 256);
+        }
+        if (decode_shared_fits(pv, d, n)) {
+            const int rc = ensure_ws(ctx, total, st);
+            if (rc != MOIN_OK) return rc;
+            for (int i = 0; i < n; ++i) {
+                char *w = static_cast<char *>(ctx->ws) + off[i];
+                d[i].ug_hi = w;
+                d[i].ug_lo = w + u_bytes;
+                d[i].ybase = reinterpret_cast<float *>(w + 2 * u_bytes);
+            }
+            if (timed(ctx, MOIN_K_DECODE_SHRINK, st, [&] { return launch_decode_base_shrink_shared(pv, d, n, st); }) !=
+                hipSuccess)
+                return MOIN_EHIP;
+            if (timed(ctx, MOIN_K_DECODE_EXPAND, st, [&] { return launch_decode_expand_shared(pv, d, n, st); }) !=
+                hipSuccess)
+                return MOIN_EHIP;
+            return MOIN_OK;
+        }
+    }
     if (pv.decode || !adapters || n == 1) {
         // nothing to share on these paths: the projections one after the other
         for (int i = 0; i < n; ++i) {

@@ -213,6 +213,20 @@ __device__ __forceinline__ void decode_shrink_slab(const ShrinkDParams &p, int s
     }
 }
 
+// What differs between the projections of one call that read the same x (gate, up; q, k, v): they
+// share the token groups, d_in, r, the scale and the number of base parts, so their base tiles, their
+// shrink slabs and their expand blocks stand side by side in the call's two launches and the
+// launches' ramp and tail are paid once.  Entry 0 repeats what the plain parameter blocks hold.
+struct DecodeMore {
+    int n;                          // projections of the call (1..MAX_SHARED_X)
+    int base_first[MAX_SHARED_X];   // first base-role workgroup of each (multiples of 8)
+    int xb_first[MAX_SHARED_X];     // first expand row block of each
+    const char *W[MAX_SHARED_X], *A_stack[MAX_SHARED_X], *B_stack[MAX_SHARED_X];
+    char *ug_hi[MAX_SHARED_X], *ug_lo[MAX_SHARED_X], *y[MAX_SHARED_X];
+    float *ybase[MAX_SHARED_X];
+    int d_out[MAX_SHARED_X], n_tiles_n[MAX_SHARED_X];
+};
+
 // grid (ceil(r / 16), max_groups): the slabs of one expert are neighbours in
 // dispatch order, so its rows of A_e stream from HBM as one contiguous run.
 template <int KS_HOLD>
@@ -228,15 +242,37 @@ __global__ __launch_bounds__(SHRINK_WAVES * 64) void decode_shrink_kernel(Shrink
 // first `n_base` workgroups take base tiles (dispatched first, they run
 // longest), the others one shrink slab each.
 static_assert(CfgDecodeBase::NT == SHRINK_WAVES * 64, "both roles share one workgroup size");
+// With several projections in the call (`m`): the base tiles of all of them first, then the slabs of
+// all of them, `slabs_per_proj` each.
 __global__ __launch_bounds__(SHRINK_WAVES * 64) void decode_base_shrink_kernel(LinearKParams lp, ShrinkDParams sp,
-                                                                             int n_base, int n_slabs)
+                                                                             DecodeMore m, int n_base, int n_slabs,
+                                                                             int slabs_per_proj)
 {
     extern __shared__ __align__(16) char smem[];
     if ((int)blockIdx.x < n_base) {
-        linear_tile<CfgDecodeBase>(lp, (int)blockIdx.x, smem);
+        int first = 0;
+        // (picked by comparison, not by indexing: indexing the parameter arrays would put them in scratch)
+#pragma unroll
+        for (int i = 1; i < MAX_SHARED_X; ++i)
+            if (i < m.n && (int)blockIdx.x >= m.base_first[i]) {
+                first = m.base_first[i];
+                lp.W = m.W[i];
+                lp.y = reinterpret_cast<char *>(m.ybase[i]);
+                lp.d_out = m.d_out[i];
+                lp.n_tiles_n = m.n_tiles_n[i];
+            }
+        linear_tile<CfgDecodeBase>(lp, (int)blockIdx.x - first, smem);
     } else {
         // (the shrink role keeps its partial sums where the base role keeps its stages)
-        const int idx = (int)blockIdx.x - n_base;
+        int idx = (int)blockIdx.x - n_base;
+#pragma unroll
+        for (int i = 1; i < MAX_SHARED_X; ++i)
+            if (i < m.n && idx >= slabs_per_proj) {
+                idx -= slabs_per_proj;
+                sp.A_stack = m.A_stack[i];
+                sp.ug_hi = m.ug_hi[i];
+                sp.ug_lo = m.ug_lo[i];
+            }
         decode_shrink_slab<SHRINK_BATCH>(sp, idx % n_slabs, idx / n_slabs,
                                          reinterpret_cast<float(*)[64][4]>(smem));
     }
@@ -395,17 +431,31 @@ __device__ __forceinline__ void expand_item(const ExpandKParams &p, int slab, in
 }
 
 // grid (ceil(d_out / (EXPAND_WAVES * RB * 16)), max_groups)
+// With several projections in the call (`m`): grid.x holds the row blocks of all of them.
 template <int KS_HOLD, int NSPLIT, bool BY_POS, int RB>
-__global__ __launch_bounds__(EXPAND_WAVES * 64) void decode_expand_kernel(ExpandKParams p)
+__global__ __launch_bounds__(EXPAND_WAVES * 64) void decode_expand_kernel(ExpandKParams p, DecodeMore m)
 {
     const i32x4_t gm = sload_x4(p.grp_meta + blockIdx.y);   // records past the group count are empty
     const int e = gm.x, gs = gm.y, ge = gm.z;
     if (ge <= gs) return;
     const int r = min(p.r, gm.w);
+    int first = 0;
+#pragma unroll
+    for (int i = 1; i < MAX_SHARED_X; ++i)
+        if (i < m.n && (int)blockIdx.x >= m.xb_first[i]) {
+            first = m.xb_first[i];
+            p.B_stack = m.B_stack[i];
+            p.ug_hi = m.ug_hi[i];
+            p.ug_lo = m.ug_lo[i];
+            p.ybase = m.ybase[i];
+            p.y = m.y[i];
+            p.d_out = m.d_out[i];
+        }
+    const int slab = (int)blockIdx.x - first;
     if (KS_HOLD > 0 && r == KS_HOLD * 32)
-        expand_item<KS_HOLD, NSPLIT, BY_POS, RB, true>(p, (int)blockIdx.x, e, gs, ge, r);
+        expand_item<KS_HOLD, NSPLIT, BY_POS, RB, true>(p, slab, e, gs, ge, r);
     else
-        expand_item<KS_HOLD, NSPLIT, BY_POS, RB, false>(p, (int)blockIdx.x, e, gs, ge, r);
+        expand_item<KS_HOLD, NSPLIT, BY_POS, RB, false>(p, slab, e, gs, ge, r);
 }
 
 static ShrinkDParams shrink_params(const PlanView &pv, const DecodeArgs &d)
@@ -452,44 +502,101 @@ hipError_t prepare_decode_kernels()
                                hipFuncAttributeMaxDynamicSharedMemorySize, CfgDecodeBase::SMEM_BYTES);
 }
 
-hipError_t launch_decode_base_shrink(const PlanView &pv, const DecodeArgs &d, hipStream_t stream)
+// True when the n projections of a call that share x can share its two launches: the same input,
+// contraction length, rank, scale, activation, output type and number of base parts.
+bool decode_shared_fits(const PlanView &pv, const DecodeArgs *d, int n)
 {
-    const LinearArgs &a = d.lin;
-    const DecodeBaseShape sh = decode_base_shape(pv.T, a.d_in, a.d_out);
-    if (!sh.dma || sh.k_splits != d.k_splits) return hipErrorInvalidValue;
-    const LinearKParams lp = decode_base_params(pv, a, d.ybase, 1, sh, pv.tok_sorted);   // rows in by-expert order
+    if (n < 1 || n > MAX_SHARED_X) return false;
+    for (int i = 0; i < n; ++i) {
+        if (!decode_base_shrink_fits(pv, d[i])) return false;
+        const LinearArgs &a = d[i].lin, &a0 = d[0].lin;
+        if (a.x != a0.x || a.d_in != a0.d_in || a.r != a0.r || a.scale != a0.scale || a.act != a0.act ||
+            a.y_f32 != a0.y_f32 || d[i].k_splits != d[0].k_splits || d[i].ybase_by_pos != d[0].ybase_by_pos)
+            return false;
+    }
+    return true;
+}
+
+static DecodeMore decode_more(const DecodeArgs *d, int n)
+{
+    DecodeMore m;
+    m.n = n;
+    for (int i = 0; i < MAX_SHARED_X; ++i) {
+        const DecodeArgs &q = d[i < n ? i : 0];
+        m.base_first[i] = m.xb_first[i] = 0;
+        m.W[i] = (const char *)q.lin.W; m.A_stack[i] = (const char *)q.lin.A_stack;
+        m.B_stack[i] = (const char *)q.lin.B_stack;
+        m.ug_hi[i] = (char *)q.ug_hi; m.ug_lo[i] = (char *)q.ug_lo; m.y[i] = (char *)q.lin.y;
+        m.ybase[i] = q.ybase;
+        m.d_out[i] = q.lin.d_out; m.n_tiles_n[i] = 0;
+    }
+    return m;
+}
+
+hipError_t launch_decode_base_shrink_shared(const PlanView &pv, const DecodeArgs *d, int n, hipStream_t stream)
+{
+    if (!decode_shared_fits(pv, d, n)) return hipErrorInvalidValue;
+    const LinearArgs &a = d[0].lin;
+    DecodeMore m = decode_more(d, n);
+    int64_t n_base = 0;
+    LinearKParams lp{};
+    for (int i = 0; i < n; ++i) {
+        const DecodeBaseShape sh = decode_base_shape(pv.T, a.d_in, d[i].lin.d_out);
+        if (!sh.dma || sh.k_splits != d[i].k_splits) return hipErrorInvalidValue;
+        if (i == 0) lp = decode_base_params(pv, a, d[0].ybase, 1, sh, pv.tok_sorted);   // rows in by-expert order
+        m.base_first[i] = (int)n_base;
+        m.n_tiles_n[i] = sh.n_tiles_n;
+        n_base += sh.grid;   // (a multiple of 8: every projection's tiles keep their place in the XCD rotation)
+    }
     const int n_slabs = (a.r + 15) / 16;
-    const int64_t n_shrink = (int64_t)n_slabs * pv.max_groups;
-    const int n_base = sh.grid;
-    const int64_t grid = (int64_t)n_base + n_shrink;
+    const int64_t per_proj = (int64_t)n_slabs * pv.max_groups;
+    const int64_t grid = n_base + per_proj * n;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     hipLaunchKernelGGL(decode_base_shrink_kernel, dim3((unsigned)grid), dim3(SHRINK_WAVES * 64),
-                       CfgDecodeBase::SMEM_BYTES, stream, lp, shrink_params(pv, d), n_base, n_slabs);
+                       CfgDecodeBase::SMEM_BYTES, stream, lp, shrink_params(pv, d[0]), m, (int)n_base, n_slabs,
+                       (int)per_proj);
     return hipGetLastError();
 }
 
-hipError_t launch_decode_expand(const PlanView &pv, const DecodeArgs &d, hipStream_t stream)
+hipError_t launch_decode_base_shrink(const PlanView &pv, const DecodeArgs &d, hipStream_t stream)
 {
-    const LinearArgs &a = d.lin;
+    return launch_decode_base_shrink_shared(pv, &d, 1, stream);
+}
+
+hipError_t launch_decode_expand_shared(const PlanView &pv, const DecodeArgs *d, int n, hipStream_t stream)
+{
+    if (n < 1 || n > MAX_SHARED_X) return hipErrorInvalidValue;
     if (pv.max_groups <= 0) return hipSuccess;
+    const LinearArgs &a = d[0].lin;
+    for (int i = 1; i < n; ++i)
+        if (d[i].lin.r != a.r || d[i].k_splits != d[0].k_splits || d[i].lin.y_f32 != a.y_f32 ||
+            d[i].ybase_by_pos != d[0].ybase_by_pos)
+            return hipErrorInvalidValue;
     ExpandKParams p;
-    p.B_stack = (const char *)a.B_stack; p.ug_hi = (const char *)d.ug_hi; p.ug_lo = (const char *)d.ug_lo;
-    p.ybase = d.ybase; p.y = (char *)a.y;
+    p.B_stack = (const char *)a.B_stack; p.ug_hi = (const char *)d[0].ug_hi; p.ug_lo = (const char *)d[0].ug_lo;
+    p.ybase = d[0].ybase; p.y = (char *)a.y;
     p.tok_sorted = pv.tok_sorted; p.grp_meta = pv.grp_meta; p.n_groups = pv.n_groups;
-    p.T = pv.T; p.d_out = a.d_out; p.r = a.r; p.k_splits = d.k_splits; p.y_f32 = a.y_f32;
+    p.T = pv.T; p.d_out = a.d_out; p.r = a.r; p.k_splits = d[0].k_splits; p.y_f32 = a.y_f32;
     constexpr int RB = 4;   // 16-row blocks per wave: 64 KB of B_e per workgroup and rank-128 adapter
     const int rows = EXPAND_WAVES * RB * 16;
-    dim3 grid((unsigned)((a.d_out + rows - 1) / rows), (unsigned)pv.max_groups);
+    DecodeMore m = decode_more(d, n);
+    int64_t xb = 0;
+    for (int i = 0; i < n; ++i) {
+        m.xb_first[i] = (int)xb;
+        xb += (d[i].lin.d_out + rows - 1) / rows;
+    }
+    if (xb > 0x7fffffffLL) return hipErrorInvalidValue;
+    dim3 grid((unsigned)xb, (unsigned)pv.max_groups);
     const int nks = (a.r + 31) / 32;
 #define MOIN_EXPAND_R(KS, NS, BP) \
-    hipLaunchKernelGGL((decode_expand_kernel<KS, NS, BP, RB>), grid, dim3(EXPAND_WAVES * 64), 0, stream, p)
+    hipLaunchKernelGGL((decode_expand_kernel<KS, NS, BP, RB>), grid, dim3(EXPAND_WAVES * 64), 0, stream, p, m)
 #define MOIN_EXPAND_S(KS, NS)                                                                                  \
     do {                                                                                                       \
-        if (d.ybase_by_pos) MOIN_EXPAND_R(KS, NS, true);                                                       \
+        if (d[0].ybase_by_pos) MOIN_EXPAND_R(KS, NS, true);                                                    \
         else MOIN_EXPAND_R(KS, NS, false);                                                                     \
     } while (0)
 #define MOIN_EXPAND(KS)                                  \
-    switch (d.k_splits) {                                \
+    switch (d[0].k_splits) {                             \
     case 1: MOIN_EXPAND_S(KS, 1); break;                 \
     case 2: MOIN_EXPAND_S(KS, 2); break;                 \
     case 3: MOIN_EXPAND_S(KS, 3); break;                 \
@@ -504,6 +611,11 @@ hipError_t launch_decode_expand(const PlanView &pv, const DecodeArgs &d, hipStre
 #undef MOIN_EXPAND_S
 #undef MOIN_EXPAND_R
     return hipGetLastError();
+}
+
+hipError_t launch_decode_expand(const PlanView &pv, const DecodeArgs &d, hipStream_t stream)
+{
+    return launch_decode_expand_shared(pv, &d, 1, stream);
 }
 
 }  // namespace moin

@@ -105,6 +105,13 @@ hipError_t launch_decode_expand(const PlanView &pv, const DecodeArgs &a, hipStre
 // base GEMM and shrink in one launch (shapes for which decode_base_shrink_fits)
 bool decode_base_shrink_fits(const PlanView &pv, const DecodeArgs &a);
 hipError_t launch_decode_base_shrink(const PlanView &pv, const DecodeArgs &a, hipStream_t stream);
+// The same two launches for the n (<= MAX_SHARED_X) projections of a call that read the same x
+// (gate, up; q, k, v): their base tiles, shrink slabs and expand blocks side by side, so that the
+// launches' ramp and tail are paid once.  decode_shared_fits says whether the projections agree in
+// everything the launches share.
+bool decode_shared_fits(const PlanView &pv, const DecodeArgs *d, int n);
+hipError_t launch_decode_base_shrink_shared(const PlanView &pv, const DecodeArgs *d, int n, hipStream_t stream);
+hipError_t launch_decode_expand_shared(const PlanView &pv, const DecodeArgs *d, int n, hipStream_t stream);
 // y = x W^T in one pass (no adapters anywhere in the call)
 hipError_t launch_decode_base_only(const PlanView &pv, const LinearArgs &a, hipStream_t stream);
 
