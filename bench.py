@@ -59,6 +59,12 @@ def measured_traffic(kernel, workload):
     return None
 
 
+def decode_traffic(workload):
+    """HBM-side bytes of a decode call: its two launches together (None when the summary lacks either)."""
+    parts = [measured_traffic(k, workload) for k in ("decode_base_shrink_kernel", "decode_expand_kernel")]
+    return None if None in parts else sum(parts)
+
+
 PREWARM_STEPS = 150   # untimed steps of the headline workload before its warm-up (clock ramp from idle)
 
 
@@ -313,7 +319,8 @@ def bench_decode(ctx, steps, warmup, n_draws=8, with_cpu=False):
                        "frac_of_hbm_peak": avg_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                        "roofline": {"bound": "hbm", "achieved": avg_bytes / (ms * 1e-3) / 1e9,
                                     "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                    "frac": avg_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+                                    "frac": avg_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                    "traffic": decode_traffic("c2_down" if "down" in w.name else "c2_gate_up")},
                        "kernels": kt}
         for p in plans:
             p.close()
@@ -356,7 +363,8 @@ def bench_decode(ctx, steps, warmup, n_draws=8, with_cpu=False):
         "algorithmic_bytes": avg_bytes, "GBps": avg_bytes / (ms * 1e-3) / 1e9,
         "frac_of_hbm_peak": avg_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "roofline": {"bound": "hbm", "achieved": avg_bytes / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS,
-                     "unit": "GB/s", "frac": avg_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+                     "unit": "GB/s", "frac": avg_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                     "traffic": decode_traffic("c2_gate_and_up_one_call")},
         "kernels": kt}
     for p in plans:
         p.close()
