@@ -183,8 +183,12 @@ int moin_lora_linear_planned(moin_ctx *ctx, const moin_plan *plan, const void *x
 /* moin_lora_linear_planned for n (1..4) projections of a layer that read the same
  * input x [T, d_in] (q, k, v; gate, up): on the prefill path the adapters' first
  * products u_i = scale * x A_{i,e}^T of all n come out of ONE pass over x, then
- * each projection's main product runs as in moin_lora_linear_planned; the results
- * are, bit for bit, those of n single calls.  W, A_stack, B_stack, y: host arrays
+ * each projection's main product runs as in moin_lora_linear_planned (in one launch
+ * where all of them fit the streaming kernel); on the decode path the projections'
+ * work shares the call's two launches (base products and first adapter products,
+ * then second adapter products) where they agree in the number of parts of the base
+ * product, else they run one after the other.  The results are, bit for bit, those of
+ * n single calls.  W, A_stack, B_stack, y: host arrays
  * of n device pointers (stacks [E, r, d_in] / [E, d_out[i], r]; A_stack and B_stack
  * may be NULL when there are no adapters), d_out: host array of n widths; r and
  * scale are common.  Needs 2 n T r bf16 of workspace.  Errors as
