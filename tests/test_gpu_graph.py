@@ -82,6 +82,62 @@ def test_gathered_batch_call_replays_from_a_graph():
         ctx, x, inp.seq_offsets, e, inp.W, inp.A_stack, inp.B_stack, 2.0, out=out))
 
 
+def test_whole_request_step_replays_from_a_graph():
+    # routing + histogram + slot map + grouping in one launch, then the layer: the step a serving loop
+    # repeats.  The router's scratch cleans itself, so every replay starts from what the one before left.
+    rng = np.random.default_rng(77)
+    S, K, D, E = 24, 300, 128, 260
+    inp = _inputs("graph_step", 256, 264, 64, E, rng.integers(1, 200, size=S).tolist(), seed=77, dist="uniform")
+    rin = wl.make_route_inputs(wl.RouteWorkload("graph_step", S, K, D, "bf16", True, 78), "cuda")
+    slots = torch.from_numpy(wl.retained_slot_table(K, E, seed=79)).cuda()
+    ctx = gc.ctx()
+    emb, x = rin.emb.clone(), inp.x.clone()
+    plan_g, plan_e = moin.Plan(ctx), moin.Plan(ctx)
+    outs_g = (torch.empty(S, dtype=torch.int32, device="cuda"), None, torch.empty(K, dtype=torch.int32, device="cuda"))
+    outs_e = (torch.empty(S, dtype=torch.int32, device="cuda"), None, torch.empty(K, dtype=torch.int32, device="cuda"))
+    y_graph = torch.empty((inp.wl.T, inp.wl.d_out), dtype=torch.bfloat16, device="cuda")
+    y_eager = torch.empty_like(y_graph)
+
+    def call(plan, outs, y):
+        moin.moin_route_plan(ctx, plan, emb, rin.centroids, inp.seq_offsets, inp.wl.T, E, slot_of_centroid=slots,
+                             out=outs, same_centroids=True)
+        moin.moin_lora_linear_planned(ctx, plan, x, inp.W, inp.A_stack, inp.B_stack, 2.0, out=y)
+
+    print("[gpu] graph step: eager warm-up", flush=True)
+    call(plan_e, outs_e, y_eager)
+    call(plan_g, outs_g, y_graph)
+    ctx.check()
+    torch.cuda.synchronize()
+    print("[gpu] graph step: capture", flush=True)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(plan_g, outs_g, y_graph)
+    g0 = torch.Generator(device="cuda").manual_seed(8)
+    for rep in range(3):
+        print(f"[gpu] graph step: replay {rep}", flush=True)
+        emb.copy_(rin.centroids[torch.randperm(K, device="cuda", generator=g0)[:S]]
+                  + 0.05 * torch.randn((S, D), device="cuda", generator=g0).to(torch.bfloat16))
+        x.copy_(torch.randn(x.shape, device="cuda", generator=g0).to(torch.bfloat16))
+        y_graph.fill_(float("nan"))
+        outs_g[0].fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        call(plan_e, outs_e, y_eager)
+        ctx.check()
+        assert torch.equal(outs_g[0], outs_e[0]) and torch.equal(outs_g[2], outs_e[2]), f"step replay {rep}: ids"
+        assert torch.equal(y_graph.view(torch.int16), y_eager.view(torch.int16)), f"step replay {rep}"
+    # the graph's ids are the slot-mapped winners of a plain routing call, which is checked against the oracle
+    _, cids, _ = moin.moin_route(ctx, emb, rin.centroids)
+    ctx.check()
+    gc.check_route(emb, rin.centroids, cids)
+    assert torch.equal(outs_g[0], slots[cids.long()])
+    ref = gc.oracle_rows(wl.LinearInputs(inp.wl, x, inp.W, inp.A_stack, inp.B_stack, inp.seq_offsets, outs_g[0]))
+    gc.compare_linear(y_graph, ref, what="step/graph")
+    plan_g.close()
+    plan_e.close()
+
+
 def test_quantised_base_call_replays_from_a_graph():
     rng = np.random.default_rng(73)
     inp = _inputs("graph_mx", 256, 264, 64, 6, rng.integers(1, 400, size=12).tolist(), seed=73, dist="uniform")
