@@ -202,7 +202,7 @@ int moin_lora_linear_planned_shared(moin_ctx *ctx, const moin_plan *plan, const 
 /* moin_route followed by moin_plan_build_ranked on the ids it produced, for a batch
  * whose N queries ARE its S = N sequences (Section 1: each query goes to one expert;
  * Section 3.2: the expert's adapter then serves every linear layer of that query).
- * A request-sized batch (bf16, D a multiple of 64, N <= 512, K <= 16384) takes ONE
+ * A request-sized batch (bf16, D a multiple of 64, N <= 512, K <= 65536) takes ONE
  * launch: the workgroup that finishes the routing groups the batch by the ids it has
  * just written; any other batch takes the launches of the two calls.  Results are
  * those of the two calls.  Arguments as in moin_route and moin_plan_build_ranked;
