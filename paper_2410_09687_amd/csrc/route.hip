@@ -216,16 +216,19 @@ __device__ __forceinline__ uint32_t float_order_key(float f)
 }
 
 // Large batches, D a multiple of 64: same tiling as route_kernel, with the
-// block pipeline of the prefill linear kernel -- two direct-to-LDS stages, MFMA
-// fragments read one k-step ahead, the block barrier placed before the last
-// k-step (whose fragments are already in registers) and the first fragments of
-// the next block read during that k-step.  The blocks of all centroid tiles
-// form one stream; a finished tile is folded into the running best between two
-// blocks.  argmin ||q - c||^2 is taken as argmax (q.c - ||c||^2 / 2): the first
-// MFMA of a tile takes -||c||^2 / 2 as its addend, so accumulators are never
-// cleared and the fold is a compare and two selects per score.  The position
-// inside the tile travels as a small code (tile, accumulator, element) that is
-// the same for all lanes, i.e. a scalar operand.
+// block pipeline of the prefill linear kernel -- two direct-to-LDS stages, the
+// fragments of a k-step read under the MFMAs of the one before, the block barrier
+// placed between the block's two k-steps (the second one's fragments are in
+// registers by then) and the first fragments of the next block read during the
+// second.  Eight waves, two per SIMD, each a 64 x 128 patch of
+// v_mfma_f32_16x16x32_bf16 accumulators: while one wave folds a finished tile the
+// other keeps the matrix core busy.  The blocks of all centroid tiles form one
+// stream; a finished tile is folded into the running best between two blocks.
+// argmin ||q - c||^2 is taken as argmax (q.c - ||c||^2 / 2): the first MFMA of a
+// tile takes -||c||^2 / 2 as its addend, so accumulators are never cleared and the
+// fold is a compare and two selects per score.  The position inside the tile
+// travels as a small code (tile, accumulator row block, element) that is the same
+// for all lanes, i.e. a scalar operand.
 __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKParams p)
 {
     using C = CfgRouteDma;
@@ -233,7 +236,7 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
     const int lane = threadIdx.x & 63;
     const int wave = uniform(threadIdx.x >> 6);
     const int wm = wave / C::WN, wn = wave % C::WN;
-    const int r = lane & 31, h = lane >> 5;
+    const int g = lane >> 4;
     // `group` workgroups next to each other on one XCD share a query tile and
     // take every group-th centroid tile: the XCD's L2 then holds few query
     // tiles at a time, each fetched once for all of its workgroups, instead of
@@ -257,19 +260,23 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
     // (wave*4 + j)*8 .. +8; only j's parity enters the chunk swizzle
     constexpr int LOADS = C::A_I;
     static_assert(C::A_I == 4 && C::B_I == 4 && C::KSTEPS == 4 && C::NS == 2, "pipeline shape");
-    const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8) + (lane >> 3));
-    uint32_t dma_c16[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) dma_c16[j] = (uint32_t)(((lane & 7) ^ (((j * 8 + (lane >> 3)) >> 1) & 7)) * 16);
-    uint32_t q_off[LOADS];   // query rows never change
-#pragma unroll
-    for (int j = 0; j < LOADS; ++j)
-        q_off[j] = min(dma_row + 8u * j, (uint32_t)(nq - 1)) * ld + dma_c16[j & 1];
-
+    // Per-lane constants of the requests are worked out from the lane id at every use (through an
+    // opaque copy): kept alive across the main loop they would be spilled around the accumulators,
+    // and a spill's reload waits for every request in flight.
+    auto fresh_lane = [&]() __attribute__((always_inline)) {
+        int v = lane;
+        asm volatile("; lane id, rematerialised" : "+v"(v));
+        return v;
+    };
     auto issue = [&](int ct, int kb, char *stage) __attribute__((always_inline)) {
         const char *cb = p.cent + (int64_t)ct * C::BM * ld;
         const uint32_t rows = (uint32_t)((ct == nct - 1) ? last_rows : C::BM);
         const uint32_t kbyte = (uint32_t)kb * (C::BK * 2);
+        const int ln = fresh_lane();
+        const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8) + (ln >> 3));
+        uint32_t dma_c16[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) dma_c16[j] = (uint32_t)(((ln & 7) ^ (((j * 8 + (ln >> 3)) >> 1) & 7)) * 16);
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) {
             const uint32_t row = min(dma_row + 8u * j, rows - 1u);
@@ -277,58 +284,81 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
             __builtin_amdgcn_global_load_lds(MOIN_GPTR(cb + off), MOIN_LPTR(stage + (wave * LOADS + j) * 1024), 16, 0, 0);
         }
 #pragma unroll
-        for (int j = 0; j < LOADS; ++j)
-            __builtin_amdgcn_global_load_lds(MOIN_GPTR(qb + (q_off[j] + kbyte)),
+        for (int j = 0; j < LOADS; ++j) {
+            // (worked out again per request: four more live registers would not fit beside the accumulators)
+            const uint32_t row = min(dma_row + 8u * j, (uint32_t)(nq - 1));
+            const uint32_t off = __umul24(row, ld) + dma_c16[j & 1] + kbyte;
+            __builtin_amdgcn_global_load_lds(MOIN_GPTR(qb + off),
                                              MOIN_LPTR(stage + C::A_BYTES + (wave * LOADS + j) * 1024), 16, 0, 0);
+        }
+    };
+    // -||c||^2 / 2 of a centroid tile (256 floats) into 1 KB of LDS behind the stages: one request of
+    // wave 0; the accumulators of the tile's first k-step take their start values from there.  Two
+    // such slots in turn: with one block per tile (D = 64) the next tile's values are requested while
+    // other waves may still be reading this tile's.
+    char *cbuf = smem + C::SMEM_BYTES;
+    int tseq = 0;   // tiles done so far
+    auto fetch_init = [&](int ct_, int slot) __attribute__((always_inline)) {
+        if (wave == 0)
+            __builtin_amdgcn_global_load_lds(MOIN_GPTR(reinterpret_cast<const char *>(p.cinit + ct_ * C::BM) + lane * 16),
+                                             MOIN_LPTR(cbuf + slot * 1024), 16, 0, 0);
     };
 
-    const int f = (r >> 1) & 7;
-    const int offA = (wm * C::WTM + r) * C::ROWB, offB = C::A_BYTES + (wn * C::WTN + r) * C::ROWB;
-    bf16x8_t fa[2][C::FM], fb[2][C::FN];
-    auto read_frags = [&](const char *stage, int ks, int slot) __attribute__((always_inline)) {
-        const int o = (((ks * 2 + h) ^ f) & 7) * 16;
-#pragma unroll
-        for (int i = 0; i < C::FM; ++i)
-            fa[slot][i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(stage + offA + i * 32 * C::ROWB + o));
-#pragma unroll
-        for (int j = 0; j < C::FN; ++j)
-            fb[slot][j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(stage + offB + j * 32 * C::ROWB + o));
+    // MFMA operand of a lane (v_mfma_f32_16x16x32_bf16): row lane % 16 of a 16-row block, elements
+    // 8 (lane / 16) .. + 8 of the k-step's 32, i.e. logical 16-byte chunk 4 ks + lane / 16 of the
+    // row.  ONE set of fragments: a fragment is read again, for the next k-step, as soon as the last
+    // MFMA that uses it has been issued (centroid fragment i after row i of the 4 x 8 grid of MFMAs,
+    // query fragment j after the MFMA (3, j)), so the reads travel under the MFMAs that follow and
+    // the second wave of the SIMD covers what is left.  (Two sets, as in the 32 x 32 x 16 form this
+    // kernel had, do not fit beside 128 accumulator registers at two waves per SIMD; the narrower
+    // instruction is worth it: on N(0,1) operands a loop of nothing but MFMAs sustains 13 % more
+    // flops with it before the chip throttles.)
+    constexpr int FM = C::WTM / 16, FN = C::WTN / 16;
+    static_assert(FM == 4 && FN == 8 && C::BK == 64, "fragment grid of a wave");
+    // (the swizzle of a row inside a 16-row block depends on lane % 16 only, and k-step 1 is k-step
+    // 0's address ^ 64; like the requests' constants, the lane's offset is rematerialised per k-step)
+    const int baseA = wm * C::WTM * C::ROWB, baseB = C::A_BYTES + wn * C::WTN * C::ROWB;
+    bf16x8_t fa[FM], fb[FN];
+    auto lane_off = [&](int ks) __attribute__((always_inline)) {
+        const int ln = fresh_lane();
+        return (((ln & 15) * C::ROWB) | ((((ln >> 4) ^ ((ln & 15) >> 1)) & 7) * 16)) ^ (ks * 64);
     };
-    typename C::Acc acc;
-    auto mfmas = [&](int slot) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < C::FM; ++i)
-#pragma unroll
-            for (int j = 0; j < C::FN; ++j)
-                acc.v[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc.v[i][j], 0, 0, 0);
+    auto read_a = [&](const char *stage, int lo, int i) __attribute__((always_inline)) {
+        fa[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(stage + baseA + i * 16 * C::ROWB + lo));
     };
-    // start values of the next tile's accumulators: element e of accumulator i
-    // belongs to centroid row wm*WTM + 32 i + 8 (e / 4) + 4 h + e % 4 of the tile
-    f32x16_t cin[C::FM];
-    auto load_init = [&](int ct_) __attribute__((always_inline)) {
-        const float *cn = p.cinit + ct_ * C::BM + wm * C::WTM + 4 * h;
+    auto read_b = [&](const char *stage, int lo, int j) __attribute__((always_inline)) {
+        fb[j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(stage + baseB + j * 16 * C::ROWB + lo));
+    };
+    f32x4_t acc[FM][FN];
+    // start values of a tile's accumulators: element e of accumulator (i, j) belongs to centroid row
+    // wm*WTM + 16 i + 4 (lane / 16) + e of the tile
+    // One k-step: the 4 x 8 MFMAs row by row.  FIRST: a tile's first k-step starts from
+    // -||c||^2 / 2.  RELOAD: every fragment is read again from `stage` at k-step `ks` once it is free.
+    auto kstep = [&](auto first_tag, auto reload_tag, const char *stage, int ks) __attribute__((always_inline)) {
+        constexpr bool FIRST = decltype(first_tag)::value, RELOAD = decltype(reload_tag)::value;
+        const int lo = lane_off(ks);
+        const char *cmine = cbuf + (tseq & 1) * 1024 + (wm * C::WTM + 4 * (fresh_lane() >> 4)) * 4;
 #pragma unroll
-        for (int i = 0; i < C::FM; ++i)
+        for (int i = 0; i < FM; ++i) {
+            f32x4_t ci = {0.f, 0.f, 0.f, 0.f};
+            if (FIRST) ci = *reinterpret_cast<const f32x4_t *>(cmine + i * 64);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const f32x4_t v = *reinterpret_cast<const f32x4_t *>(cn + i * 32 + g * 8);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) cin[i][4 * g + q] = v[q];
+            for (int j = 0; j < FN; ++j) {
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], FIRST ? ci : acc[i][j], 0, 0, 0);
+                if (RELOAD && i == FM - 1) {
+                    read_b(stage, lo, j);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-    };
-    auto mfmas_first = [&](int slot) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < C::FM; ++i)
-#pragma unroll
-            for (int j = 0; j < C::FN; ++j)
-                acc.v[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], cin[i], 0, 0, 0);
+            if (RELOAD) read_a(stage, lo, i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
-    float bestv[C::FN];
-    int bestc[C::FN];   // (tile << 5) | (accumulator i << 4) | element
-    static_assert(C::FM == 2, "position code");
+    float bestv[FN];
+    int bestc[FN];   // (tile << 5) | (accumulator row block i << 2) | element
 #pragma unroll
-    for (int j = 0; j < C::FN; ++j) {
+    for (int j = 0; j < FN; ++j) {
         bestv[j] = -__builtin_inff();
         bestc[j] = 0;
     }
@@ -343,39 +373,12 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
         constexpr bool ISSUE = decltype(issue_tag)::value, READ = decltype(read_tag)::value;
         char *st_cur = smem + (s & 1) * C::STAGE_BYTES;
         const char *st_nxt = smem + ((s + 1) & 1) * C::STAGE_BYTES;
-        // first k-step: a tile's first block starts from -||c||^2 / 2
-        read_frags(st_cur, 1, 1);
-        if (kb == 0) {
-            mfmas_first(0);
-#pragma unroll
-            for (int n = 0; n < C::FM + C::FN; ++n) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, C::FM * C::FN - (C::FM + C::FN), 0);
-        } else {
-            mfmas(0);
-#pragma unroll
-            for (int n = 0; n < C::FM + C::FN; ++n) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, C::FM * C::FN - (C::FM + C::FN), 0);
-        }
+        // first k-step (its fragments are in registers), the second one's read behind it
+        if (kb == 0) kstep(std::true_type{}, std::true_type{}, st_cur, 1);
+        else kstep(std::false_type{}, std::true_type{}, st_cur, 1);
         // the tile's last block fetches the next tile's start values; they land
         // before this block's barrier (vmcnt(0))
-        if (kb == nkb - 1 && ct + G < nct) load_init(ct + G);
-#pragma unroll
-        for (int ks = 1; ks < C::KSTEPS - 1; ++ks) {
-            read_frags(st_cur, ks + 1, (ks + 1) & 1);
-            mfmas(ks & 1);
-#pragma unroll
-            for (int n = 0; n < C::FM + C::FN; ++n) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, C::FM * C::FN - (C::FM + C::FN), 0);
-        }
+        if (kb == nkb - 1 && ct + G < nct) fetch_init(ct + G, (tseq + 1) & 1);
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
         if constexpr (ISSUE) {
             issue(pct, pkb, st_cur);
@@ -384,37 +387,31 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
                 pct += G;
             }
         }
-        if constexpr (READ) read_frags(st_nxt, 0, 0);
-        mfmas((C::KSTEPS - 1) & 1);
-        if constexpr (ISSUE && READ) {
-#pragma unroll
-            for (int n = 0; n < C::FM * C::FN; ++n) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-                if (n < C::FM + C::FN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-        }
+        // second k-step, the next block's first fragments behind it
+        if constexpr (READ) kstep(std::false_type{}, std::true_type{}, st_nxt, 0);
+        else kstep(std::false_type{}, std::false_type{}, st_nxt, 0);
         if (++kb == nkb) {
             // a lane's scores come in ascending centroid order, so a strict '>'
             // keeps the lowest index among equal scores
             const int code0 = ct << 5;
 #pragma unroll
-            for (int i = 0; i < C::FM; ++i)
+            for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int e = 0; e < 16; ++e)
+                for (int e = 0; e < 4; ++e)
 #pragma unroll
-                    for (int j = 0; j < C::FN; ++j) {
-                        const float sc = acc.v[i][j][e];
+                    for (int j = 0; j < FN; ++j) {
+                        const float sc = acc[i][j][e];
                         const bool gt = sc > bestv[j];
                         bestv[j] = gt ? sc : bestv[j];
-                        bestc[j] = gt ? code0 + (i * 16 + e) : bestc[j];
+                        bestc[j] = gt ? code0 + (i * 4 + e) : bestc[j];
                     }
             kb = 0;
             ct += G;
+            ++tseq;
         }
     };
 
-    load_init(member);
+    fetch_init(member, 0);
     issue(member, 0, smem);
     if (total > 1) {
         issue(nkb > 1 ? member : member + G, nkb > 1 ? 1 : 0, smem + C::STAGE_BYTES);
@@ -422,7 +419,13 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
     } else {
         wait_vm_then_barrier<0>();
     }
-    read_frags(smem, 0, 0);
+    {
+        const int lo0 = lane_off(0);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) read_a(smem, lo0, i);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) read_b(smem, lo0, j);
+    }
     int s = 0;
     for (; s < total - 2; ++s) body(s, std::true_type{}, std::true_type{});
     if (total > 1) {
@@ -432,26 +435,29 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
     body(s, std::false_type{}, std::false_type{});
     __syncthreads();
 
-    // position code -> centroid index; then merge the two lane halves (rows
-    // 4*(lane>>5) interleave) and the WM waves: higher score, else lower index
-    int besti[C::FN];
+    // position code -> centroid index; then merge the four lane groups (rows 4 * (lane / 16)
+    // interleave) and the WM waves: higher score, else lower index
+    int besti[FN];
 #pragma unroll
-    for (int j = 0; j < C::FN; ++j) {
-        const int c = bestc[j], e = c & 15;
-        besti[j] = (c >> 5) * C::BM + wm * C::WTM + ((c >> 4) & 1) * 32 + 8 * (e >> 2) + 4 * h + (e & 3);
-        const float ov = __shfl_xor(bestv[j], 32);
-        const int oi = __shfl_xor(besti[j], 32);
-        if (lex_less(-ov, oi, -bestv[j], besti[j])) {
-            bestv[j] = ov;
-            besti[j] = oi;
+    for (int j = 0; j < FN; ++j) {
+        const int c = bestc[j];
+        besti[j] = (c >> 5) * C::BM + wm * C::WTM + 16 * ((c >> 2) & 7) + 4 * g + (c & 3);
+#pragma unroll
+        for (int sh = 16; sh <= 32; sh <<= 1) {
+            const float ov = __shfl_xor(bestv[j], sh);
+            const int oi = __shfl_xor(besti[j], sh);
+            if (lex_less(-ov, oi, -bestv[j], besti[j])) {
+                bestv[j] = ov;
+                besti[j] = oi;
+            }
         }
     }
     float *sv = reinterpret_cast<float *>(smem);
     int *si = reinterpret_cast<int *>(smem + C::WM * C::BN * 4);
-    if (lane < 32) {
+    if (lane < 16) {
 #pragma unroll
-        for (int j = 0; j < C::FN; ++j) {
-            const int col = wn * C::WTN + j * 32 + lane;
+        for (int j = 0; j < FN; ++j) {
+            const int col = wn * C::WTN + j * 16 + lane;
             sv[wm * C::BN + col] = bestv[j];
             si[wm * C::BN + col] = besti[j];
         }
@@ -864,7 +870,7 @@ hipError_t prepare_route_kernels()
 {
     hipError_t e;
     if ((e = allow_lds(&route_kernel<CfgRoute>, CfgRoute::SMEM_BYTES)) != hipSuccess) return e;
-    if ((e = allow_lds(&route_stream_kernel, CfgRouteDma::SMEM_BYTES)) != hipSuccess) return e;
+    if ((e = allow_lds(&route_stream_kernel, CfgRouteDma::SMEM_BYTES + 2048)) != hipSuccess) return e;
     return allow_lds(&route_small_kernel<CfgRouteSmall>, CfgRouteSmall::SMEM_BYTES);
 }
 
@@ -961,7 +967,7 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t stream)
             const int64_t sgrid = (grid + 7) / 8 * 8 * p.group;
             if (sgrid > 0x7fffffffLL) return hipErrorInvalidValue;
             hipLaunchKernelGGL(route_stream_kernel, dim3((unsigned)sgrid), dim3(CfgRouteDma::NT),
-                               CfgRouteDma::SMEM_BYTES, stream, p);
+                               CfgRouteDma::SMEM_BYTES + 2048, stream, p);
             if (p.group > 1)
                 hipLaunchKernelGGL(route_unpack_kernel, dim3((unsigned)((a.N + 255) / 256)), dim3(256), 0,
                                    stream, p.best, a.N, a.K, a.slot, a.cid, a.expert_ids);
