@@ -196,7 +196,7 @@ def bench_ceilings(ctx):
     return {"mfma_bf16_TFLOPs": flops[0] / (kt["probe_mfma"]["avg_ms"] * 1e-3) / 1e12,
             "mfma_mxfp8_TFLOPs": fl8[0] / (kt8["probe_mfma"]["avg_ms"] * 1e-3) / 1e12,
             "read_GBps": buf.numel() * 4.0 / (kt["probe_read"]["avg_ms"] * 1e-3) / 1e9,
-            "what": "MFMA-only loops (v_mfma_f32_32x32x16_bf16 on N(0,1) operands; "
+            "what": "MFMA-only loops (v_mfma_f32_16x16x32_bf16, the instruction of the prefill and router kernels, on N(0,1) operands; "
                     "v_mfma_scale_f32_32x32x64_f8f6f4 on their MXFP8 codes; 2 workgroups of 8 waves per "
                     "compute unit); streaming read of 1 GiB (two workgroups per compute unit take 32 KB chunks in turn, "
                     "non-temporal 16-byte loads, 8 in flight per thread: the fastest of the shapes swept)"}

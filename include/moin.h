@@ -511,8 +511,8 @@ int moin_merge_adapters(moin_ctx *ctx, const void *A_stack, const void *B_stack,
  * for the roofline fractions that bench.py reports (the hot path of the paper's
  * method does not call them).
  * moin_probe_out_len: elements that `out` of the two probes must hold.
- * moin_probe_mfma_bf16: every wave of a chip-filling grid runs `iters` times 16
- *   independent v_mfma_f32_32x32x16_bf16 on operands taken from `operands` (device,
+ * moin_probe_mfma_bf16: every wave of a chip-filling grid runs `iters` times 32
+ *   independent v_mfma_f32_16x16x32_bf16 on operands taken from `operands` (device,
  *   bf16 values, n_bytes a multiple of 16 and at least 16; the values matter: the
  *   matrix cores reach their power limit sooner on random data than on constants);
  *   out[i] (device, fp32) = sum of thread i's accumulators; *flops (host, may be

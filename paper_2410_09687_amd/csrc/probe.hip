@@ -15,8 +15,10 @@ constexpr int PROBE_BLOCK = 512;      // 8 waves
 constexpr int PROBE_WG_PER_CU = 2;
 constexpr int PROBE_OPS = 4;          // A and B operand registers per lane (16 bytes each)
 
-// Per iteration and wave: 16 independent v_mfma_f32_32x32x16_bf16 (8 accumulators,
-// each fed twice), no memory access.  out[tid] = sum of the lane's accumulators.
+// Per iteration and wave: 32 independent v_mfma_f32_16x16x32_bf16 (the instruction of the prefill
+// and router kernels; on N(0,1) operands the chip sustains some 13 % more flops with it than with
+// v_mfma_f32_32x32x16_bf16 before it throttles, and the same on constants), no memory access.
+// out[tid] = sum of the lane's accumulators.
 __global__ __launch_bounds__(PROBE_BLOCK) void probe_mfma_kernel(const uint4 *__restrict__ in, uint32_t n16,
                                                                  int iters, float *__restrict__ out)
 {
@@ -27,24 +29,19 @@ __global__ __launch_bounds__(PROBE_BLOCK) void probe_mfma_kernel(const uint4 *__
         a[j] = __builtin_bit_cast(bf16x8_t, in[(tid * (2u * PROBE_OPS) + j) % n16]);
         b[j] = __builtin_bit_cast(bf16x8_t, in[(tid * (2u * PROBE_OPS) + PROBE_OPS + j) % n16]);
     }
-    f32x16_t acc[8];
+    f32x4_t acc[32];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    for (int i = 0; i < 32; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 1], b[i >> 1], acc[i], 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 + (i & 1)], b[i >> 1], acc[i], 0, 0, 0);
+        for (int i = 0; i < 32; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i & 3], b[(i >> 2) & 3], acc[i], 0, 0, 0);
     }
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 32; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) s += acc[i][e];
+        for (int e = 0; e < 4; ++e) s += acc[i][e];
     out[tid] = s;
 }
 
@@ -124,7 +121,7 @@ hipError_t launch_probe_mfma(const void *operands, int64_t n_bytes, int iters, f
                              hipStream_t stream)
 {
     const int grid = compute_units() * PROBE_WG_PER_CU;
-    if (flops) *flops = (double)grid * (PROBE_BLOCK / 64) * (double)iters * 16.0 * (2.0 * 32 * 32 * 16);
+    if (flops) *flops = (double)grid * (PROBE_BLOCK / 64) * (double)iters * 32.0 * (2.0 * 16 * 16 * 32);
     hipLaunchKernelGGL(probe_mfma_kernel, dim3(grid), dim3(PROBE_BLOCK), 0, stream,
                        reinterpret_cast<const uint4 *>(operands), (uint32_t)(n_bytes / 16), iters, out);
     return hipGetLastError();

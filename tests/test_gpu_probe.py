@@ -33,20 +33,19 @@ def test_mfma_probe_computes_the_products_it_counts():
         ctx.check()
         n_threads = out.numel()
         n_waves = n_threads // 64
-        assert flops == n_waves * iters * 16 * 2.0 * 32 * 32 * 16
+        assert flops == n_waves * iters * 32 * 2.0 * 16 * 16 * 32
         # thread t holds operand pieces in[(8 t + j) mod n16], j < 4 for A, 4 <= j < 8 for B; a wave's MFMA with
-        # pieces (ja, jb) multiplies the 32 x 16 matrices whose row l % 32, columns 8 (l / 32) .. + 8 is lane l's
+        # pieces (ja, jb) multiplies the 16 x 32 matrices whose row l % 16, columns 8 (l / 16) .. + 8 is lane l's
         # piece.  The sum of all entries of A B^T is sum_k colsum_A[k] colsum_B[k].
         v = ops.view(-1, 8).double().cpu().numpy()
         n16 = v.shape[0]
         t = np.arange(n_threads)
         total = out.double().cpu().numpy().reshape(n_waves, 64).sum(axis=1)
-        pieces = [v[(8 * t + j) % n16].reshape(n_waves, 2, 32, 8) for j in range(8)]   # [wave, half, row, 8]
-        colsum = [p.sum(axis=2).reshape(n_waves, 16) for p in pieces]                  # [wave, k]
+        pieces = [v[(8 * t + j) % n16].reshape(n_waves, 4, 16, 8) for j in range(8)]   # [wave, k group, row, 8]
+        colsum = [p.sum(axis=2).reshape(n_waves, 32) for p in pieces]                  # [wave, k]
         want = np.zeros(n_waves)
-        for i in range(8):
-            want += (colsum[i & 1] * colsum[4 + (i >> 1)]).sum(axis=1)
-            want += (colsum[2 + (i & 1)] * colsum[4 + (i >> 1)]).sum(axis=1)
+        for i in range(32):
+            want += (colsum[i & 3] * colsum[4 + ((i >> 2) & 3)]).sum(axis=1)
         assert np.array_equal(total, iters * want)
 
 
