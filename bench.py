@@ -173,7 +173,7 @@ def bench_ceilings(ctx):
     g = torch.Generator(device="cuda").manual_seed(20241013)
     ops = torch.randn((1 << 20,), device="cuda", generator=g).to(torch.bfloat16)
     buf = torch.empty(1 << 28, dtype=torch.int32, device="cuda").fill_(1)
-    iters = 4000
+    iters = 20000
     flops = [0.0]
 
     def run():
