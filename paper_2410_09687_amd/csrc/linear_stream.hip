@@ -146,45 +146,41 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
     const int nkb0 = p.d_in / BK;
     const uint32_t ldx = (uint32_t)p.d_in * 2u, ldu = (uint32_t)p.r * 2u;
 
-    // Per-lane constants are recomputed from the lane id at every use (through an opaque copy):
-    // kept alive across the main loop they would be spilled around the 256 accumulators.
-    auto fresh_lane = [&]() __attribute__((always_inline)) {
-        int v = lane;
-        asm volatile("; lane id, rematerialised" : "+v"(v));
-        return v;
-    };
-
     // DMA: instruction j of a wave fills LDS rows (wave*8 + j)*8 .. +8 of an operand tile; the lane
     // fetches logical 16-byte chunk (lane%8) ^ swz(row), swz(row) = (row >> 1) & 7, which for
     // row = wave*64 + j*8 + lane/8 is ((j & 1) * 4 + lane/16) & 7.  A block's requests are issued
     // one by one (issue_one, n = 0..15: eight for the output rows, eight for the tokens) so that
-    // they can be placed between the MFMAs.
+    // they can be placed between the MFMAs.  What a request needs per lane is kept in registers
+    // for the tile being fetched (its 16 source rows, clamped to the tile's last row) and for the
+    // kernel (the two chunk offsets); the block's position along k goes into the uniform base
+    // pointers, so a request costs one multiply-add besides itself.
+    const uint32_t c16a = (((uint32_t)lane & 7) ^ ((uint32_t)lane >> 4)) * 16, c16b = c16a ^ 64u;   // even j, odd j
+    uint32_t rowc[2 * LOADS];
+    auto rows_of = [&](const Tile &t) __attribute__((always_inline)) {
+        const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8)) + ((uint32_t)lane >> 3);
+#pragma unroll
+        for (int n = 0; n < 2 * LOADS; ++n)
+            rowc[n] = min(dma_row + 8u * (n & 7), (uint32_t)((n >= LOADS ? t.q_rows : t.p_rows) - 1));
+    };
     struct Fetch {
-        const char *pp, *pq;
-        uint32_t ld, dma_row, c16;
-        uint32_t p_last, q_last;
+        const char *pp, *pq;   // the operands' rows 0 at the block's first k
+        uint32_t ld;
     };
     auto fetch_of = [&](const Tile &t, int b) __attribute__((always_inline)) {
         Fetch f;
         const bool base = b < nkb0;
         const int jb = b - nkb0;
         const bool hi = jb < t.nkb1;
-        f.pq = base ? t.q0 : (hi ? t.uh : t.ul);
-        f.pp = base ? t.p0 : t.be;
-        f.ld = base ? ldx : ldu;
         const int kb = base ? b : (hi ? jb : jb - t.nkb1);
-        const uint32_t ln = (uint32_t)fresh_lane();
-        f.dma_row = (uint32_t)(wave * (LOADS * 8)) + (ln >> 3);
-        f.c16 = (((ln & 7) ^ (ln >> 4)) * 16) + (uint32_t)kb * (BK * 2);   // odd j: ^ 64
-        f.p_last = (uint32_t)(t.p_rows - 1);
-        f.q_last = (uint32_t)(t.q_rows - 1);
+        f.pq = (base ? t.q0 : (hi ? t.uh : t.ul)) + kb * (BK * 2);
+        f.pp = (base ? t.p0 : t.be) + kb * (BK * 2);
+        f.ld = base ? ldx : ldu;
         return f;
     };
     auto issue_one = [&](const Fetch &f, char *stage, int n) __attribute__((always_inline)) {
         const int j = n & 7;
-        const bool q = n >= 8;
-        const uint32_t row = min(f.dma_row + 8u * j, q ? f.q_last : f.p_last);
-        const uint32_t off = __umul24(row, f.ld) + (f.c16 ^ ((j & 1) ? 64u : 0u));
+        const bool q = n >= LOADS;
+        const uint32_t off = __umul24(rowc[n], f.ld) + ((j & 1) ? c16b : c16a);
         __builtin_amdgcn_global_load_lds(MOIN_GPTR((q ? f.pq : f.pp) + off),
                                          MOIN_LPTR(stage + (q ? OP_BYTES : 0) + (wave * LOADS + j) * 1024), 16, 0, 0);
     };
@@ -198,16 +194,17 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
     // k-step's 32, i.e. logical chunk 4 ks + lane/16 of the row; the swizzle of a row inside a
     // 16-row block depends on lane%16 only ((row >> 1) & 7 = (lane%16) >> 1), and k-step 1 is
     // k-step 0's address ^ 64.  Fragment n = 0..7: output blocks, 8..15: token blocks.
-    auto lane_off = [&]() __attribute__((always_inline)) {
-        const int ln = fresh_lane();
-        return ((ln & 15) * ROWB) | ((((ln >> 4) ^ ((ln & 15) >> 1)) & 7) * 16);
-    };
+    const int lo0 = ((lane & 15) * ROWB) | ((((lane >> 4) ^ ((lane & 15) >> 1)) & 7) * 16);
+    const int lo1 = lo0 ^ 64;
     const int baseP = wp * (FP * 16) * ROWB, baseQ = OP_BYTES + wq * (FQ * 16) * ROWB;
     bf16x8_t fr[2][FP + FQ];
     auto read_one = [&](const char *stage, int lo_, int set, int n) __attribute__((always_inline)) {
         const int base_ = n < FP ? baseP + n * 16 * ROWB : baseQ + (n - FP) * 16 * ROWB;
         fr[set][n] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(stage + base_ + lo_));
     };
+    // The order in which a k-step's fragments are read: the first MFMAs (output block 0 against
+    // token blocks 0..7) need output block 0 and all token blocks, output block i only from MFMA 8 i.
+    auto frag_at = [](int k) { return k == 0 ? 0 : (k <= FQ ? FP + k - 1 : k - FQ); };
     // The MFMAs are written as assembly with the accumulator tied in and out as an AccVGPR operand:
     // the compiler's own selection for 64 four-register accumulators goes through the VGPR form and
     // wraps every MFMA in copies.  What its hazard checks cannot see is taken care of by hand: an
@@ -223,36 +220,48 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
     Tile nxt = stream::load_tile(p, id, band_end);
     Tile pft = cur;
     int pfb = 2;
+    rows_of(cur);
 
     // One block of the stream: k-step 0 (its fragments were read during the block before) with the
     // reads of k-step 1 between its MFMAs; barrier; k-step 1 with the requests for the block two
-    // ahead and the first fragments of the next block between its MFMAs (one of each per four MFMAs:
-    // all requests right behind the barrier, or reads first and requests last, measured slower).  The
-    // order below IS the instruction order (scheduling barriers after every group).  No branch after the barrier: past
-    // the stream's end the fetch repeats the last block into the free stage and the reads take stale
-    // bytes that nothing uses.
+    // ahead and the first fragments of the next block between its MFMAs.  A wave issues in order and
+    // an MFMA keeps the matrix core busy for 16 cycles, 4 of them its own issue: whatever stands
+    // between two MFMAs and takes longer than the other 12 delays the second one.  So the other work
+    // is spread thin -- one LDS read, or one request's address, or the request itself (the longest:
+    // about 20 cycles) after an MFMA, never two of them -- and the order below IS the instruction
+    // order (scheduling barriers after every piece).  Measured with cycle stamps around the barrier,
+    // a block of 128 MFMAs took 3050 cycles with read, address and request together after every
+    // fourth MFMA, 2570 without the requests, 2480 without requests and reads.  No branch after the
+    // barrier: past the stream's end the fetch repeats the last block into the free stage and the
+    // reads take stale bytes that nothing uses.
     auto body = [&](int s) __attribute__((always_inline)) {
         char *st_cur = smem + (s & 1) * STAGE_BYTES;
         const char *st_nxt = smem + ((s + 1) & 1) * STAGE_BYTES;
-        // everything the second half needs besides the barrier is worked out under the first half's
-        // MFMAs, so that the matrix core has work again the moment the barrier opens
-        if (pfb == pft.total) {
-            if (nxt.valid) {
-                pft = nxt;
-                pfb = 0;
-            } else {
-                pfb = pft.total - 1;
-            }
-        }
-        const Fetch f = fetch_of(pft, pfb);
-        ++pfb;
-        const int lo0 = lane_off();
-        const int lo1 = lo0 ^ 64;
+        Fetch f;
 #pragma unroll
         for (int n = 0; n < FP * FQ; ++n) {
             mfma(0, n / FQ, n % FQ);
-            if ((n & 1) == 1 && n / 2 < FP + FQ) {
-                read_one(st_cur, lo1, 1, n / 2);
+            if (n % 2 == 1 && n / 2 < FP + FQ) {
+                read_one(st_cur, lo1, 1, frag_at(n / 2));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (n == 36) {
+                // what the second half fetches, worked out here so that the matrix core has work
+                // again the moment the barrier opens
+                if (pfb == pft.total) {
+                    if (nxt.valid) {
+                        pft = nxt;
+                        pfb = 0;
+                        rows_of(pft);
+                    } else {
+                        pfb = pft.total - 1;
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (n == 40) {
+                f = fetch_of(pft, pfb);
+                ++pfb;
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -261,8 +270,11 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
 #pragma unroll
         for (int n = 0; n < FP * FQ; ++n) {
             mfma(1, n / FQ, n % FQ);
-            if (n % 4 == 3) {   // one read and one request per four MFMAs
-                read_one(st_nxt, lo0, 0, n / 4);
+            if (n % 2 == 0 && n / 2 < FP + FQ) {   // all reads in the first half of the k-step: landed when the next block starts
+                read_one(st_nxt, lo0, 0, frag_at(n / 2));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (n % 4 == 1) {
                 issue_one(f, st_cur, n / 4);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -279,7 +291,6 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
         // leading fragments of the tile's first block (landed: the prologue, or the previous
         // tile's last barrier, waited for it); not held across the epilogue
         {
-            const int lo0 = lane_off();
 #pragma unroll
             for (int n = 0; n < FP + FQ; ++n) read_one(smem + (s & 1) * STAGE_BYTES, lo0, 0, n);
         }
@@ -297,7 +308,10 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
         // 16 i + 4 (lane/16) + 0..3.  One 16-token block at a time: every lane parks its 32 outputs of
         // the block's token in the scratch row of that token (slots of four outputs, the slot index
         // XORed with twice the token so that the 16 tokens of a write hit different banks), then the
-        // wave reads the block back 16 bytes per lane and stores whole 128-byte lines.
+        // wave reads the block back 16 bytes per lane and stores whole 128-byte lines.  All reads of a
+        // block are issued before its first store (one wait per block, not one per read), a lane's
+        // store address is a 32-bit offset worked out once per tile plus a wave-uniform base, and a
+        // bf16 block takes half the scratch, so blocks alternate between the halves.
         {
             int ln = lane;
             asm volatile("; lane id, rematerialised" : "+v"(ln));
@@ -306,33 +320,51 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
             constexpr int EB = Y_F32 ? 4 : 2;           // bytes per output
             constexpr int SLOT = 4 * EB;                // four outputs
             constexpr int ROW = 128 * EB;               // a token's 128 outputs
-            const int64_t ldy = (int64_t)cur.d_out * EB;
+            constexpr int CPR = ROW / 16;               // 16-byte chunks per token row (16 bf16 / 32 fp32)
+            constexpr int SPC = 16 / SLOT;              // slots per chunk (2 / 1)
+            constexpr int NPS = 16 * CPR / 64;          // read-back instructions per block (4 / 8)
+            constexpr int TPP = 64 / CPR;               // tokens per read-back instruction (4 / 2)
+            constexpr int BLOCK = 16 * ROW;             // scratch bytes of a block (4 KB / 8 KB)
+            constexpr bool TWO = 2 * BLOCK <= SCR_BYTES;
+            const int tl = ln / CPR, ch = ln % CPR;     // read-back: token ps * TPP + tl of the block, chunk ch
+            const int n = wp * (FP * 16) + ch * (16 / EB);
+            const bool n_ok = n < cur.p_rows;           // d_out % 8 == 0: a chunk is all in or all out
+            const uint32_t ldy = (uint32_t)cur.d_out * EB;
+            char *ybase = cur.y + (int64_t)(cur.row0 + wq * (FQ * 16)) * ldy + (int64_t)cur.n0 * EB;   // wave-uniform
+            const uint32_t voff = (uint32_t)tl * ldy + (uint32_t)n * EB;
+            const int m_lane = wq * (FQ * 16) + tl;
 #pragma unroll
             for (int j = 0; j < FQ; ++j) {
+                char *blk = scr + (TWO ? (j & 1) * BLOCK : 0);
 #pragma unroll
                 for (int i = 0; i < FP; ++i) {
                     const int slot_ = (i * 4 + kg) ^ (2 * t16);
                     const f32x4_t a = acc[i][j];
                     if constexpr (Y_F32)
-                        *reinterpret_cast<f32x4_t *>(scr + t16 * ROW + slot_ * SLOT) = a;
+                        *reinterpret_cast<f32x4_t *>(blk + t16 * ROW + slot_ * SLOT) = a;
                     else
-                        *reinterpret_cast<uint2 *>(scr + t16 * ROW + slot_ * SLOT) =
+                        *reinterpret_cast<uint2 *>(blk + t16 * ROW + slot_ * SLOT) =
                             make_uint2(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]));
                 }
                 lds_order();
-                // read back: 16 tokens x (ROW / 16) chunks of 16 bytes, 64 lanes per pass
-                constexpr int CPR = ROW / 16;           // chunks per token row (16 bf16 / 32 fp32)
-                constexpr int SPC = 16 / SLOT;          // slots per chunk (2 / 1)
-#pragma unroll
-                for (int ps = 0; ps < 16 * CPR / 64; ++ps) {
-                    const int idx = ps * 64 + ln;
-                    const int tt = idx / CPR, ch = idx % CPR;
+                auto rd = [&](int ps) {
+                    const int tt = ps * TPP + tl;
                     const int pslot = (ch * SPC) ^ (2 * tt);       // XOR with an even number keeps slot pairs adjacent
-                    const uint4 v = *reinterpret_cast<const uint4 *>(scr + tt * ROW + pslot * SLOT);
-                    const int m = wq * (FQ * 16) + j * 16 + tt;
-                    const int n = wp * (FP * 16) + ch * (16 / EB);
-                    if (m < cur.q_rows && n < cur.p_rows)   // d_out % 8 == 0: a chunk is all in or all out
-                        *reinterpret_cast<uint4 *>(cur.y + (int64_t)(cur.row0 + m) * ldy + (int64_t)(cur.n0 + n) * EB) = v;
+                    return *reinterpret_cast<const uint4 *>(blk + tt * ROW + pslot * SLOT);
+                };
+                auto st = [&](int ps, const uint4 &v) {
+                    const int m = m_lane + j * 16 + ps * TPP;
+                    if (n_ok && m < cur.q_rows)
+                        *reinterpret_cast<uint4 *>(ybase + (uint32_t)(j * 16 + ps * TPP) * ldy + voff) = v;
+                };
+                static_assert(NPS == 4 || NPS == 8, "read-back steps per block");
+                const uint4 v0 = rd(0), v1 = rd(1), v2 = rd(2), v3 = rd(3);
+                if constexpr (NPS == 8) {
+                    const uint4 v4 = rd(4), v5 = rd(5), v6 = rd(6), v7 = rd(7);
+                    st(0, v0), st(1, v1), st(2, v2), st(3, v3);
+                    st(4, v4), st(5, v5), st(6, v6), st(7, v7);
+                } else {
+                    st(0, v0), st(1, v1), st(2, v2), st(3, v3);
                 }
                 lds_order();
             }
