@@ -268,29 +268,36 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
         asm volatile("; lane id, rematerialised" : "+v"(v));
         return v;
     };
+    // requests of one block (centroid tile ct, contraction block kb): n = 0..3 centroid rows, 4..7 query rows.
+    // The block's position along k is in the uniform base pointers; a request costs an add, a min and
+    // a multiply-add besides itself.
+    struct Fetch {
+        const char *pc, *pq;
+        uint32_t dma_row, c16a, c16b, c_last;
+    };
+    auto fetch_of = [&](int ct, int kb) __attribute__((always_inline)) {
+        Fetch f;
+        f.pc = p.cent + (int64_t)ct * C::BM * ld + kb * (C::BK * 2);
+        f.pq = qb + kb * (C::BK * 2);
+        f.c_last = (uint32_t)((ct == nct - 1) ? last_rows : C::BM) - 1u;
+        const uint32_t ln = (uint32_t)fresh_lane();
+        f.dma_row = (uint32_t)(wave * (LOADS * 8)) + (ln >> 3);
+        f.c16a = ((ln & 7) ^ (ln >> 4)) * 16;   // even j; odd j: ^ 64
+        f.c16b = f.c16a ^ 64u;
+        return f;
+    };
+    auto issue_one = [&](const Fetch &f, char *stage, int n) __attribute__((always_inline)) {
+        const int j = n & (LOADS - 1);
+        const bool q = n >= LOADS;
+        const uint32_t row = min(f.dma_row + 8u * j, q ? (uint32_t)(nq - 1) : f.c_last);
+        const uint32_t off = __umul24(row, ld) + ((j & 1) ? f.c16b : f.c16a);
+        __builtin_amdgcn_global_load_lds(MOIN_GPTR((q ? f.pq : f.pc) + off),
+                                         MOIN_LPTR(stage + (q ? C::A_BYTES : 0) + (wave * LOADS + j) * 1024), 16, 0, 0);
+    };
     auto issue = [&](int ct, int kb, char *stage) __attribute__((always_inline)) {
-        const char *cb = p.cent + (int64_t)ct * C::BM * ld;
-        const uint32_t rows = (uint32_t)((ct == nct - 1) ? last_rows : C::BM);
-        const uint32_t kbyte = (uint32_t)kb * (C::BK * 2);
-        const int ln = fresh_lane();
-        const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8) + (ln >> 3));
-        uint32_t dma_c16[2];
+        const Fetch f = fetch_of(ct, kb);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) dma_c16[j] = (uint32_t)(((ln & 7) ^ (((j * 8 + (ln >> 3)) >> 1) & 7)) * 16);
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const uint32_t row = min(dma_row + 8u * j, rows - 1u);
-            const uint32_t off = __umul24(row, ld) + dma_c16[j & 1] + kbyte;
-            __builtin_amdgcn_global_load_lds(MOIN_GPTR(cb + off), MOIN_LPTR(stage + (wave * LOADS + j) * 1024), 16, 0, 0);
-        }
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            // (worked out again per request: four more live registers would not fit beside the accumulators)
-            const uint32_t row = min(dma_row + 8u * j, (uint32_t)(nq - 1));
-            const uint32_t off = __umul24(row, ld) + dma_c16[j & 1] + kbyte;
-            __builtin_amdgcn_global_load_lds(MOIN_GPTR(qb + off),
-                                             MOIN_LPTR(stage + C::A_BYTES + (wave * LOADS + j) * 1024), 16, 0, 0);
-        }
+        for (int n = 0; n < 2 * LOADS; ++n) issue_one(f, stage, n);
     };
     // -||c||^2 / 2 of a centroid tile (256 floats) into 1 KB of LDS behind the stages: one request of
     // wave 0; the accumulators of the tile's first k-step take their start values from there.  Two
@@ -334,8 +341,10 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
     // wm*WTM + 16 i + 4 (lane / 16) + e of the tile
     // One k-step: the 4 x 8 MFMAs row by row.  FIRST: a tile's first k-step starts from
     // -||c||^2 / 2.  RELOAD: every fragment is read again from `stage` at k-step `ks` once it is free.
-    auto kstep = [&](auto first_tag, auto reload_tag, const char *stage, int ks) __attribute__((always_inline)) {
+    auto kstep = [&](auto first_tag, auto reload_tag, const char *stage, int ks, auto issue_tag, const Fetch &f,
+                     char *dst) __attribute__((always_inline)) {
         constexpr bool FIRST = decltype(first_tag)::value, RELOAD = decltype(reload_tag)::value;
+        constexpr bool ISSUE = decltype(issue_tag)::value;
         const int lo = lane_off(ks);
         const char *cmine = cbuf + (tseq & 1) * 1024 + (wm * C::WTM + 4 * (fresh_lane() >> 4)) * 4;
 #pragma unroll
@@ -347,6 +356,14 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
                 acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], FIRST ? ci : acc[i][j], 0, 0, 0);
                 if (RELOAD && i == FM - 1) {
                     read_b(stage, lo, j);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // the eight requests of the block two ahead, one after every third MFMA of the rows
+                // that carry no query-fragment reads: together right behind the barrier they kept
+                // both waves of a SIMD, which leave the barrier at the same time, off the matrix
+                // core for as long as their issue takes
+                if (ISSUE && i < FM - 1 && j % 3 == 1 && i * 3 + j / 3 < 2 * LOADS) {
+                    issue_one(f, dst, i * 3 + j / 3);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -374,22 +391,26 @@ __global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKPar
         char *st_cur = smem + (s & 1) * C::STAGE_BYTES;
         const char *st_nxt = smem + ((s + 1) & 1) * C::STAGE_BYTES;
         // first k-step (its fragments are in registers), the second one's read behind it
-        if (kb == 0) kstep(std::true_type{}, std::true_type{}, st_cur, 1);
-        else kstep(std::false_type{}, std::true_type{}, st_cur, 1);
+        const Fetch none{};
+        if (kb == 0) kstep(std::true_type{}, std::true_type{}, st_cur, 1, std::false_type{}, none, nullptr);
+        else kstep(std::false_type{}, std::true_type{}, st_cur, 1, std::false_type{}, none, nullptr);
         // the tile's last block fetches the next tile's start values; they land
         // before this block's barrier (vmcnt(0))
         if (kb == nkb - 1 && ct + G < nct) fetch_init(ct + G, (tseq + 1) & 1);
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        // second k-step, the next block's first fragments and the requests for the block two ahead behind it
         if constexpr (ISSUE) {
-            issue(pct, pkb, st_cur);
+            const Fetch f = fetch_of(pct, pkb);
             if (++pkb == nkb) {
                 pkb = 0;
                 pct += G;
             }
+            kstep(std::false_type{}, std::true_type{}, st_nxt, 0, std::true_type{}, f, st_cur);
+        } else if constexpr (READ) {
+            kstep(std::false_type{}, std::true_type{}, st_nxt, 0, std::false_type{}, none, nullptr);
+        } else {
+            kstep(std::false_type{}, std::false_type{}, st_nxt, 0, std::false_type{}, none, nullptr);
         }
-        // second k-step, the next block's first fragments behind it
-        if constexpr (READ) kstep(std::false_type{}, std::true_type{}, st_nxt, 0);
-        else kstep(std::false_type{}, std::false_type{}, st_nxt, 0);
         if (++kb == nkb) {
             // a lane's scores come in ascending centroid order, so a strict '>'
             // keeps the lowest index among equal scores
