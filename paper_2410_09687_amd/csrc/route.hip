@@ -215,299 +215,269 @@ __device__ __forceinline__ uint32_t float_order_key(float f)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
-// Large batches, D a multiple of 64: same tiling as route_kernel, with the
-// block pipeline of the prefill linear kernel -- two direct-to-LDS stages, the
-// fragments of a k-step read under the MFMAs of the one before, the block barrier
-// placed between the block's two k-steps (the second one's fragments are in
-// registers by then) and the first fragments of the next block read during the
-// second.  Eight waves, two per SIMD, each a 64 x 128 patch of
-// v_mfma_f32_16x16x32_bf16 accumulators: while one wave folds a finished tile the
-// other keeps the matrix core busy.  The blocks of all centroid tiles form one
-// stream; a finished tile is folded into the running best between two blocks.
-// argmin ||q - c||^2 is taken as argmax (q.c - ||c||^2 / 2): the first MFMA of a
-// tile takes -||c||^2 / 2 as its addend, so accumulators are never cleared and the
-// fold is a compare and two selects per score.  The position inside the tile
-// travels as a small code (tile, accumulator row block, element) that is the same
-// for all lanes, i.e. a scalar operand.
-__global__ __launch_bounds__(CfgRouteDma::NT) void route_stream_kernel(RouteKParams p)
+// One (query tile, member of its group) per workgroup: 256 queries against every group-th tile of 256
+// centroids, the blocks of all its centroid tiles forming one stream.  FOUR waves, one per SIMD, in the
+// form of the prefill main kernel: 128 x 128 patches of 64 accumulators in AccVGPRs, MFMAs as assembly
+// with the accumulator tied in and out, fragments of a k-step read under the MFMAs of the one before,
+// and never more than one piece of other work (an LDS read, a request's address, the request) between
+// two MFMAs.  argmin ||q - c||^2 is taken as argmax (q.c - ||c||^2 / 2): a tile's accumulators start
+// from -||c||^2 / 2, and a finished tile is folded into the running best with a compare and two
+// selects per score; the position inside the tile travels as a small code (tile, accumulator row
+// block, element) that is the same for all lanes.
+// An eight-wave form of this kernel (two waves per SIMD, 64 x 128 patches, accumulators in VGPRs) had
+// the second wave to cover a wave's stalls, but both waves of a SIMD fold at the same time, and its
+// registers were full: cycle stamps showed 3560 cycles per block of 128 MFMAs per SIMD and 12 000 at a
+// tile's end, against 2700 per block in this form.
+namespace r4 {
+constexpr int BT = 256, BK = 64, ROWB = BK * 2, OP_BYTES = BT * ROWB, STAGE_BYTES = 2 * OP_BYTES;
+constexpr int SMEM_STAGES = 2 * STAGE_BYTES;
+constexpr int NW = 4, NT = NW * 64, FP = 8, FQ = 8, LOADS = 8;
+constexpr int CBUF_BYTES = 2048;             // -||c||^2 / 2 of a centroid tile, two slots
+constexpr int XCH_BYTES = 2 * BT * 8;        // winners of the two centroid halves, per query
+constexpr int SMEM_BYTES = SMEM_STAGES + CBUF_BYTES + XCH_BYTES;
+}  // namespace r4
+
+__global__ __launch_bounds__(r4::NT) void route_stream4_kernel(RouteKParams p)
 {
-    using C = CfgRouteDma;
+    using namespace r4;
     extern __shared__ __align__(16) char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = uniform(threadIdx.x >> 6);
-    const int wm = wave / C::WN, wn = wave % C::WN;
-    const int g = lane >> 4;
-    // `group` workgroups next to each other on one XCD share a query tile and
-    // take every group-th centroid tile: the XCD's L2 then holds few query
-    // tiles at a time, each fetched once for all of its workgroups, instead of
-    // one tile per compute unit that falls out of the cache between two uses.
+    const int wp = wave >> 1, wq = wave & 1;
     const int G = p.group;
     const int slot = blockIdx.x >> 3;
     const int member = slot % G;
     const int64_t qtile = (int64_t)(slot / G) * 8 + (blockIdx.x & 7);
-    const int64_t q0 = qtile * C::BN;
+    const int64_t q0 = qtile * BT;
     if (q0 >= p.N) return;
-    const int nq = (int)min((int64_t)C::BN, p.N - q0);
+    const int nq = (int)min((int64_t)BT, p.N - q0);
     const uint32_t ld = (uint32_t)p.D * 2u;
-    const int nkb = p.D / C::BK;
-    const int nct = (p.K + C::BM - 1) / C::BM;
-    const int last_rows = p.K - (nct - 1) * C::BM;
+    const int nkb = p.D / BK;
+    const int nct = (p.K + BT - 1) / BT;
+    const int last_rows = p.K - (nct - 1) * BT;
     const char *qb = p.emb + q0 * (int64_t)ld;
     const int my_tiles = (nct - member + G - 1) / G;   // >= 1: G <= nct
     const int total = my_tiles * nkb;
 
-    // DMA mapping (see DmaCore): instruction j of a wave fills tile rows
-    // (wave*4 + j)*8 .. +8; only j's parity enters the chunk swizzle
-    constexpr int LOADS = C::A_I;
-    static_assert(C::A_I == 4 && C::B_I == 4 && C::KSTEPS == 4 && C::NS == 2, "pipeline shape");
-    // Per-lane constants of the requests are worked out from the lane id at every use (through an
-    // opaque copy): kept alive across the main loop they would be spilled around the accumulators,
-    // and a spill's reload waits for every request in flight.
-    auto fresh_lane = [&]() __attribute__((always_inline)) {
-        int v = lane;
-        asm volatile("; lane id, rematerialised" : "+v"(v));
-        return v;
+    // requests of one block (centroid tile ct, contraction block kb): n = 0..7 centroid rows, 8..15 query
+    // rows.  Per lane: the two chunk offsets and the 16 source rows (clamped to the tile's last row; the
+    // centroid rows change with the tile being fetched only when that is the last, partial one); the
+    // block's position along k is in the uniform base pointers.
+    const uint32_t c16a = (((uint32_t)lane & 7) ^ ((uint32_t)lane >> 4)) * 16, c16b = c16a ^ 64u;   // even j, odd j
+    const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8)) + ((uint32_t)lane >> 3);
+    uint32_t rowc[2 * LOADS];
+#pragma unroll
+    for (int n = 0; n < LOADS; ++n) rowc[LOADS + n] = min(dma_row + 8u * n, (uint32_t)(nq - 1));
+    auto rows_of = [&](int ct) __attribute__((always_inline)) {
+        const uint32_t c_last = (uint32_t)((ct == nct - 1 ? last_rows : BT) - 1);
+#pragma unroll
+        for (int n = 0; n < LOADS; ++n) rowc[n] = min(dma_row + 8u * n, c_last);
     };
-    // requests of one block (centroid tile ct, contraction block kb): n = 0..3 centroid rows, 4..7 query rows.
-    // The block's position along k is in the uniform base pointers; a request costs an add, a min and
-    // a multiply-add besides itself.
     struct Fetch {
-        const char *pc, *pq;
-        uint32_t dma_row, c16a, c16b, c_last;
+        const char *pp, *pq;
     };
     auto fetch_of = [&](int ct, int kb) __attribute__((always_inline)) {
         Fetch f;
-        f.pc = p.cent + (int64_t)ct * C::BM * ld + kb * (C::BK * 2);
-        f.pq = qb + kb * (C::BK * 2);
-        f.c_last = (uint32_t)((ct == nct - 1) ? last_rows : C::BM) - 1u;
-        const uint32_t ln = (uint32_t)fresh_lane();
-        f.dma_row = (uint32_t)(wave * (LOADS * 8)) + (ln >> 3);
-        f.c16a = ((ln & 7) ^ (ln >> 4)) * 16;   // even j; odd j: ^ 64
-        f.c16b = f.c16a ^ 64u;
+        f.pp = p.cent + (int64_t)ct * BT * ld + kb * (BK * 2);
+        f.pq = qb + kb * (BK * 2);
         return f;
     };
     auto issue_one = [&](const Fetch &f, char *stage, int n) __attribute__((always_inline)) {
-        const int j = n & (LOADS - 1);
+        const int j = n & 7;
         const bool q = n >= LOADS;
-        const uint32_t row = min(f.dma_row + 8u * j, q ? (uint32_t)(nq - 1) : f.c_last);
-        const uint32_t off = __umul24(row, ld) + ((j & 1) ? f.c16b : f.c16a);
-        __builtin_amdgcn_global_load_lds(MOIN_GPTR((q ? f.pq : f.pc) + off),
-                                         MOIN_LPTR(stage + (q ? C::A_BYTES : 0) + (wave * LOADS + j) * 1024), 16, 0, 0);
+        const uint32_t off = __umul24(rowc[n], ld) + ((j & 1) ? c16b : c16a);
+        __builtin_amdgcn_global_load_lds(MOIN_GPTR((q ? f.pq : f.pp) + off),
+                                         MOIN_LPTR(stage + (q ? OP_BYTES : 0) + (wave * LOADS + j) * 1024), 16, 0, 0);
     };
-    auto issue = [&](int ct, int kb, char *stage) __attribute__((always_inline)) {
-        const Fetch f = fetch_of(ct, kb);
-#pragma unroll
-        for (int n = 0; n < 2 * LOADS; ++n) issue_one(f, stage, n);
-    };
-    // -||c||^2 / 2 of a centroid tile (256 floats) into 1 KB of LDS behind the stages: one request of
-    // wave 0; the accumulators of the tile's first k-step take their start values from there.  Two
-    // such slots in turn: with one block per tile (D = 64) the next tile's values are requested while
-    // other waves may still be reading this tile's.
-    char *cbuf = smem + C::SMEM_BYTES;
-    int tseq = 0;   // tiles done so far
-    auto fetch_init = [&](int ct_, int slot) __attribute__((always_inline)) {
+    char *cbuf = smem + SMEM_STAGES;
+    auto fetch_init = [&](int ct_, int slot_) __attribute__((always_inline)) {
         if (wave == 0)
-            __builtin_amdgcn_global_load_lds(MOIN_GPTR(reinterpret_cast<const char *>(p.cinit + ct_ * C::BM) + lane * 16),
-                                             MOIN_LPTR(cbuf + slot * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(MOIN_GPTR(reinterpret_cast<const char *>(p.cinit + ct_ * BT) + lane * 16),
+                                             MOIN_LPTR(cbuf + slot_ * 1024), 16, 0, 0);
+    };
+    // MFMA operand of a lane: row lane%16 of a 16-row block, logical 16-byte chunk 4 ks + lane/16 of the
+    // row; k-step 1 is k-step 0's address ^ 64.  Fragment n = 0..7: centroid blocks, 8..15: query blocks.
+    const int lo0 = ((lane & 15) * ROWB) | ((((lane >> 4) ^ ((lane & 15) >> 1)) & 7) * 16);
+    const int lo1 = lo0 ^ 64;
+    const int baseP = wp * (FP * 16) * ROWB, baseQ = OP_BYTES + wq * (FQ * 16) * ROWB;
+    bf16x8_t fr[2][FP + FQ];
+    auto read_one = [&](const char *stage, int lo_, int set, int n) __attribute__((always_inline)) {
+        const int base_ = n < FP ? baseP + n * 16 * ROWB : baseQ + (n - FP) * 16 * ROWB;
+        fr[set][n] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(stage + base_ + lo_));
+    };
+    // the order in which a k-step's fragments are read: the first MFMAs (centroid block 0 against query
+    // blocks 0..7) need centroid block 0 and all query blocks, centroid block i only from MFMA 8 i
+    auto frag_at = [](int k_) { return k_ == 0 ? 0 : (k_ <= FQ ? FP + k_ - 1 : k_ - FQ); };
+    // acc[i][j]: centroid rows wp*128 + 16 i + 4 (lane / 16) + 0..3 of the tile, query wq*128 + 16 j + lane % 16
+    f32x4_t acc[FP][FQ];
+    auto mfma = [&](int set, int i, int j) __attribute__((always_inline)) {
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fr[set][i]), "v"(fr[set][FP + j]));
     };
 
-    // MFMA operand of a lane (v_mfma_f32_16x16x32_bf16): row lane % 16 of a 16-row block, elements
-    // 8 (lane / 16) .. + 8 of the k-step's 32, i.e. logical 16-byte chunk 4 ks + lane / 16 of the
-    // row.  ONE set of fragments: a fragment is read again, for the next k-step, as soon as the last
-    // MFMA that uses it has been issued (centroid fragment i after row i of the 4 x 8 grid of MFMAs,
-    // query fragment j after the MFMA (3, j)), so the reads travel under the MFMAs that follow and
-    // the second wave of the SIMD covers what is left.  (Two sets, as in the 32 x 32 x 16 form this
-    // kernel had, do not fit beside 128 accumulator registers at two waves per SIMD; the narrower
-    // instruction is worth it: on N(0,1) operands a loop of nothing but MFMAs sustains 13 % more
-    // flops with it before the chip throttles.)
-    constexpr int FM = C::WTM / 16, FN = C::WTN / 16;
-    static_assert(FM == 4 && FN == 8 && C::BK == 64, "fragment grid of a wave");
-    // (the swizzle of a row inside a 16-row block depends on lane % 16 only, and k-step 1 is k-step
-    // 0's address ^ 64; like the requests' constants, the lane's offset is rematerialised per k-step)
-    const int baseA = wm * C::WTM * C::ROWB, baseB = C::A_BYTES + wn * C::WTN * C::ROWB;
-    bf16x8_t fa[FM], fb[FN];
-    auto lane_off = [&](int ks) __attribute__((always_inline)) {
-        const int ln = fresh_lane();
-        return (((ln & 15) * C::ROWB) | ((((ln >> 4) ^ ((ln & 15) >> 1)) & 7) * 16)) ^ (ks * 64);
-    };
-    auto read_a = [&](const char *stage, int lo, int i) __attribute__((always_inline)) {
-        fa[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(stage + baseA + i * 16 * C::ROWB + lo));
-    };
-    auto read_b = [&](const char *stage, int lo, int j) __attribute__((always_inline)) {
-        fb[j] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4 *>(stage + baseB + j * 16 * C::ROWB + lo));
-    };
-    f32x4_t acc[FM][FN];
-    // start values of a tile's accumulators: element e of accumulator (i, j) belongs to centroid row
-    // wm*WTM + 16 i + 4 (lane / 16) + e of the tile
-    // One k-step: the 4 x 8 MFMAs row by row.  FIRST: a tile's first k-step starts from
-    // -||c||^2 / 2.  RELOAD: every fragment is read again from `stage` at k-step `ks` once it is free.
-    auto kstep = [&](auto first_tag, auto reload_tag, const char *stage, int ks, auto issue_tag, const Fetch &f,
-                     char *dst) __attribute__((always_inline)) {
-        constexpr bool FIRST = decltype(first_tag)::value, RELOAD = decltype(reload_tag)::value;
-        constexpr bool ISSUE = decltype(issue_tag)::value;
-        const int lo = lane_off(ks);
-        const char *cmine = cbuf + (tseq & 1) * 1024 + (wm * C::WTM + 4 * (fresh_lane() >> 4)) * 4;
+    float bestv[FQ];
+    int bestc[FQ];   // (tile << 5) | (accumulator row block i << 2) | element
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            f32x4_t ci = {0.f, 0.f, 0.f, 0.f};
-            if (FIRST) ci = *reinterpret_cast<const f32x4_t *>(cmine + i * 64);
-#pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], FIRST ? ci : acc[i][j], 0, 0, 0);
-                if (RELOAD && i == FM - 1) {
-                    read_b(stage, lo, j);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                // the eight requests of the block two ahead, one after every third MFMA of the rows
-                // that carry no query-fragment reads: together right behind the barrier they kept
-                // both waves of a SIMD, which leave the barrier at the same time, off the matrix
-                // core for as long as their issue takes
-                if (ISSUE && i < FM - 1 && j % 3 == 1 && i * 3 + j / 3 < 2 * LOADS) {
-                    issue_one(f, dst, i * 3 + j / 3);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-            if (RELOAD) read_a(stage, lo, i);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    };
-
-    float bestv[FN];
-    int bestc[FN];   // (tile << 5) | (accumulator row block i << 2) | element
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
+    for (int j = 0; j < FQ; ++j) {
         bestv[j] = -__builtin_inff();
         bestc[j] = 0;
     }
 
-    int kb = 0, ct = member;   // block being computed
-    int pkb = 2, pct = member; // block to fetch next (two ahead)
-    while (pkb >= nkb) {       // D = 64: one block per centroid tile
+    // block to fetch next (two ahead of the one being computed) and how many are left to fetch
+    int pkb = 2, pct = member, pleft = total - 2;
+    while (pkb >= nkb) {       // D = 64 or 128: fewer than three blocks per centroid tile
         pkb -= nkb;
         pct += G;
     }
-    auto body = [&](int s, auto issue_tag, auto read_tag) __attribute__((always_inline)) {
-        constexpr bool ISSUE = decltype(issue_tag)::value, READ = decltype(read_tag)::value;
-        char *st_cur = smem + (s & 1) * C::STAGE_BYTES;
-        const char *st_nxt = smem + ((s + 1) & 1) * C::STAGE_BYTES;
-        // first k-step (its fragments are in registers), the second one's read behind it
-        const Fetch none{};
-        if (kb == 0) kstep(std::true_type{}, std::true_type{}, st_cur, 1, std::false_type{}, none, nullptr);
-        else kstep(std::false_type{}, std::true_type{}, st_cur, 1, std::false_type{}, none, nullptr);
-        // the tile's last block fetches the next tile's start values; they land
-        // before this block's barrier (vmcnt(0))
-        if (kb == nkb - 1 && ct + G < nct) fetch_init(ct + G, (tseq + 1) & 1);
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        // second k-step, the next block's first fragments and the requests for the block two ahead behind it
-        if constexpr (ISSUE) {
-            const Fetch f = fetch_of(pct, pkb);
-            if (++pkb == nkb) {
-                pkb = 0;
-                pct += G;
+    int pct_rows = member;   // the tile rowc's centroid part belongs to
+    rows_of(member);
+    auto body = [&](int s, bool last_of_tile, int ct_next, int slot_next) __attribute__((always_inline)) {
+        char *st_cur = smem + (s & 1) * STAGE_BYTES;
+        const char *st_nxt = smem + ((s + 1) & 1) * STAGE_BYTES;
+        Fetch f;
+#pragma unroll
+        for (int n = 0; n < FP * FQ; ++n) {
+            mfma(0, n / FQ, n % FQ);
+            if (n % 2 == 1 && n / 2 < FP + FQ) {
+                read_one(st_cur, lo1, 1, frag_at(n / 2));
+                __builtin_amdgcn_sched_barrier(0);
             }
-            kstep(std::false_type{}, std::true_type{}, st_nxt, 0, std::true_type{}, f, st_cur);
-        } else if constexpr (READ) {
-            kstep(std::false_type{}, std::true_type{}, st_nxt, 0, std::false_type{}, none, nullptr);
-        } else {
-            kstep(std::false_type{}, std::false_type{}, st_nxt, 0, std::false_type{}, none, nullptr);
+            if (n == 36) {
+                // what the second half fetches; past the stream's end the item's last block again, into
+                // the free stage
+                const bool more = pleft > 0;
+                const int fct = more ? pct : member + (my_tiles - 1) * G;
+                if (fct != pct_rows) {
+                    rows_of(fct);
+                    pct_rows = fct;
+                }
+                f = fetch_of(fct, more ? pkb : nkb - 1);
+                --pleft;
+                if (++pkb == nkb) {
+                    pkb = 0;
+                    pct += G;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (n == 44) {
+                // the tile's last block fetches the next tile's start values; they land before this block's barrier
+                if (last_of_tile && ct_next < nct) fetch_init(ct_next, slot_next);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        if (++kb == nkb) {
-            // a lane's scores come in ascending centroid order, so a strict '>'
-            // keeps the lowest index among equal scores
-            const int code0 = ct << 5;
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int j = 0; j < FN; ++j) {
-                        const float sc = acc[i][j][e];
-                        const bool gt = sc > bestv[j];
-                        bestv[j] = gt ? sc : bestv[j];
-                        bestc[j] = gt ? code0 + (i * 4 + e) : bestc[j];
-                    }
-            kb = 0;
-            ct += G;
-            ++tseq;
+        for (int n = 0; n < FP * FQ; ++n) {
+            mfma(1, n / FQ, n % FQ);
+            if (n % 2 == 0 && n / 2 < FP + FQ) {   // all reads in the first half of the k-step: landed when the next block starts
+                read_one(st_nxt, lo0, 0, frag_at(n / 2));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (n % 4 == 1) {
+                issue_one(f, st_cur, n / 4);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     fetch_init(member, 0);
-    issue(member, 0, smem);
-    if (total > 1) {
-        issue(nkb > 1 ? member : member + G, nkb > 1 ? 1 : 0, smem + C::STAGE_BYTES);
-        wait_vm_then_barrier<2 * LOADS>();
-    } else {
-        wait_vm_then_barrier<0>();
-    }
     {
-        const int lo0 = lane_off(0);
+        const Fetch f0 = fetch_of(member, 0);
 #pragma unroll
-        for (int i = 0; i < FM; ++i) read_a(smem, lo0, i);
+        for (int n = 0; n < 2 * LOADS; ++n) issue_one(f0, smem, n);
+        // (a one-block item fetches its block twice: the second copy is never read)
+        const int ct1 = nkb > 1 ? member : (total > 1 ? member + G : member);
+        if (ct1 != pct_rows) {
+            rows_of(ct1);
+            pct_rows = ct1;
+        }
+        const Fetch f1 = fetch_of(ct1, nkb > 1 ? 1 : 0);
 #pragma unroll
-        for (int j = 0; j < FN; ++j) read_b(smem, lo0, j);
+        for (int n = 0; n < 2 * LOADS; ++n) issue_one(f1, smem + STAGE_BYTES, n);
     }
-    int s = 0;
-    for (; s < total - 2; ++s) body(s, std::true_type{}, std::true_type{});
-    if (total > 1) {
-        body(s, std::false_type{}, std::true_type{});
-        ++s;
-    }
-    body(s, std::false_type{}, std::false_type{});
-    __syncthreads();
+    wait_vm_then_barrier<2 * LOADS>();
 
-    // position code -> centroid index; then merge the four lane groups (rows 4 * (lane / 16)
-    // interleave) and the WM waves: higher score, else lower index
-    int besti[FN];
+    int s = 0, ct = member;
+    for (int t = 0; t < my_tiles; ++t, ct += G) {
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
+        for (int n = 0; n < FP + FQ; ++n) read_one(smem + (s & 1) * STAGE_BYTES, lo0, 0, n);
+        {
+            // start values: -||c||^2 / 2 of the lane's 32 centroid rows
+            const char *cm = cbuf + (t & 1) * 1024 + (wp * (FP * 16) + 4 * (lane >> 4)) * 4;
+#pragma unroll
+            for (int i = 0; i < FP; ++i) {
+                const f32x4_t ci = *reinterpret_cast<const f32x4_t *>(cm + i * 64);
+#pragma unroll
+                for (int j = 0; j < FQ; ++j) acc[i][j] = ci;
+            }
+        }
+        asm volatile("s_nop 7" ::: "memory");   // accumulator writes before the first MFMA reads them
+        for (int kb = 0; kb < nkb; ++kb, ++s) body(s, kb == nkb - 1, ct + G, (t + 1) & 1);
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs' results before the fold reads them
+        // a lane's scores come in ascending centroid order, so a strict '>' keeps the lowest index among equals
+        // (every score is read out of its AccVGPR by an instruction of its own, in place: left to the
+        // compiler, all 256 are copied out at once and push everything else out of the registers)
+        const int code0 = ct << 5;
+#pragma unroll
+        for (int i = 0; i < FP; ++i)
+#pragma unroll
+            for (int j = 0; j < FQ; ++j) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float sc;
+                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(sc) : "a"(acc[i][j][e]));
+                    const bool gt = sc > bestv[j];
+                    bestv[j] = gt ? sc : bestv[j];
+                    bestc[j] = gt ? code0 + (i * 4 + e) : bestc[j];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the requests repeated past the stream's end
+
+    // position code -> centroid index; merge the four lane groups (rows 4 * (lane / 16) interleave), then
+    // the two waves that hold the other half of the tile's centroids: higher score, else lower index
+    const int g = lane >> 4;
+    float *sv = reinterpret_cast<float *>(smem + SMEM_STAGES + CBUF_BYTES);
+    int *si = reinterpret_cast<int *>(smem + SMEM_STAGES + CBUF_BYTES + 2 * BT * 4);
+#pragma unroll
+    for (int j = 0; j < FQ; ++j) {
         const int c = bestc[j];
-        besti[j] = (c >> 5) * C::BM + wm * C::WTM + 16 * ((c >> 2) & 7) + 4 * g + (c & 3);
+        int bi = (c >> 5) * BT + wp * (FP * 16) + 16 * ((c >> 2) & 7) + 4 * g + (c & 3);
+        float bv = bestv[j];
 #pragma unroll
         for (int sh = 16; sh <= 32; sh <<= 1) {
-            const float ov = __shfl_xor(bestv[j], sh);
-            const int oi = __shfl_xor(besti[j], sh);
-            if (lex_less(-ov, oi, -bestv[j], besti[j])) {
-                bestv[j] = ov;
-                besti[j] = oi;
+            const float ov = __shfl_xor(bv, sh);
+            const int oi = __shfl_xor(bi, sh);
+            if (lex_less(-ov, oi, -bv, bi)) {
+                bv = ov;
+                bi = oi;
             }
         }
-    }
-    float *sv = reinterpret_cast<float *>(smem);
-    int *si = reinterpret_cast<int *>(smem + C::WM * C::BN * 4);
-    if (lane < 16) {
-#pragma unroll
-        for (int j = 0; j < FN; ++j) {
-            const int col = wn * C::WTN + j * 16 + lane;
-            sv[wm * C::BN + col] = bestv[j];
-            si[wm * C::BN + col] = besti[j];
+        if (lane < 16) {
+            const int col = wq * (FQ * 16) + j * 16 + lane;
+            sv[wp * BT + col] = bv;
+            si[wp * BT + col] = bi;
         }
     }
     __syncthreads();
-    for (int col = threadIdx.x; col < nq; col += C::NT) {
+    for (int col = threadIdx.x; col < nq; col += NT) {
         float bv = sv[col];
         int bi = si[col];
-#pragma unroll
-        for (int w = 1; w < C::WM; ++w) {
-            const float v = sv[w * C::BN + col];
-            const int i = si[w * C::BN + col];
-            if (lex_less(-v, i, -bv, bi)) {
-                bv = v;
-                bi = i;
-            }
+        const float v = sv[BT + col];
+        const int i = si[BT + col];
+        if (lex_less(-v, i, -bv, bi)) {
+            bv = v;
+            bi = i;
         }
         if (G == 1) {
             if (p.cid) p.cid[q0 + col] = bi;
             if (p.expert_ids) p.expert_ids[q0 + col] = p.slot ? p.slot[bi] : bi;
         } else if (bv > -__builtin_inff()) {
-            // exact, order-independent merge across the group: smallest -score,
-            // then lowest index; a score of -inf (excluded centroid, NaN) never enters
             atomicMin(&p.best[q0 + col], ((unsigned long long)float_order_key(-bv) << 32) | (unsigned)bi);
         }
     }
-    // G > 1: route_unpack_kernel turns the packed winners into ids.  (Electing a
-    // finishing workgroup here would need device-scope fences, and an acquire
-    // fence drops the XCD's L2 contents -- the very thing the grouping protects.)
 }
 
 // Packed (score key, index) winners of the grouped streaming kernel -> ids.
@@ -891,7 +861,7 @@ hipError_t prepare_route_kernels()
 {
     hipError_t e;
     if ((e = allow_lds(&route_kernel<CfgRoute>, CfgRoute::SMEM_BYTES)) != hipSuccess) return e;
-    if ((e = allow_lds(&route_stream_kernel, CfgRouteDma::SMEM_BYTES + 2048)) != hipSuccess) return e;
+    if ((e = allow_lds(&route_stream4_kernel, r4::SMEM_BYTES)) != hipSuccess) return e;
     return allow_lds(&route_small_kernel<CfgRouteSmall>, CfgRouteSmall::SMEM_BYTES);
 }
 
@@ -987,8 +957,7 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t stream)
             // query tile t runs on XCD t % 8, its workgroups in consecutive slots there
             const int64_t sgrid = (grid + 7) / 8 * 8 * p.group;
             if (sgrid > 0x7fffffffLL) return hipErrorInvalidValue;
-            hipLaunchKernelGGL(route_stream_kernel, dim3((unsigned)sgrid), dim3(CfgRouteDma::NT),
-                               CfgRouteDma::SMEM_BYTES + 2048, stream, p);
+            hipLaunchKernelGGL(route_stream4_kernel, dim3((unsigned)sgrid), dim3(r4::NT), r4::SMEM_BYTES, stream, p);
             if (p.group > 1)
                 hipLaunchKernelGGL(route_unpack_kernel, dim3((unsigned)((a.N + 255) / 256)), dim3(256), 0,
                                    stream, p.best, a.N, a.K, a.slot, a.cid, a.expert_ids);
