@@ -313,6 +313,18 @@ __global__ __launch_bounds__(r4::NT) void route_stream4_kernel(RouteKParams p)
     auto mfma = [&](int set, int i, int j) __attribute__((always_inline)) {
         asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fr[set][i]), "v"(fr[set][FP + j]));
     };
+    // A tile's first k-step takes -||c||^2 / 2 of the accumulator's four centroid rows as its addend.  The
+    // eight accumulators of a row block share those four values: they are written into the block's first
+    // accumulator only (32 register writes per tile instead of 256 -- at one wave per SIMD a register
+    // write costs 8 cycles), the other seven read it as their addend, and it takes its own MFMA last.
+    auto mfma_first = [&](int i, int j) __attribute__((always_inline)) {
+        if (j == 0)
+            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][0]) : "v"(fr[0][i]), "v"(fr[0][FP]));
+        else
+            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %3"
+                         : "=&a"(acc[i][j])
+                         : "v"(fr[0][i]), "v"(fr[0][FP + j]), "a"(acc[i][0]));
+    };
 
     float bestv[FQ];
     int bestc[FQ];   // (tile << 5) | (accumulator row block i << 2) | element
@@ -330,13 +342,15 @@ __global__ __launch_bounds__(r4::NT) void route_stream4_kernel(RouteKParams p)
     }
     int pct_rows = member;   // the tile rowc's centroid part belongs to
     rows_of(member);
-    auto body = [&](int s, bool last_of_tile, int ct_next, int slot_next) __attribute__((always_inline)) {
+    auto body = [&](auto first_tag, int s, bool last_of_tile, int ct_next, int slot_next) __attribute__((always_inline)) {
+        constexpr bool FIRST = decltype(first_tag)::value;   // the tile's first block
         char *st_cur = smem + (s & 1) * STAGE_BYTES;
         const char *st_nxt = smem + ((s + 1) & 1) * STAGE_BYTES;
         Fetch f;
 #pragma unroll
         for (int n = 0; n < FP * FQ; ++n) {
-            mfma(0, n / FQ, n % FQ);
+            if constexpr (FIRST) mfma_first(n / FQ, (n + 1) % FQ);   // 1..7, then 0
+            else mfma(0, n / FQ, n % FQ);
             if (n % 2 == 1 && n / 2 < FP + FQ) {
                 read_one(st_cur, lo1, 1, frag_at(n / 2));
                 __builtin_amdgcn_sched_barrier(0);
@@ -398,10 +412,11 @@ __global__ __launch_bounds__(r4::NT) void route_stream4_kernel(RouteKParams p)
     }
     wait_vm_then_barrier<2 * LOADS>();
 
+    // the first block's leading fragments; every later block's are read under the block before it
+#pragma unroll
+    for (int n = 0; n < FP + FQ; ++n) read_one(smem, lo0, 0, n);
     int s = 0, ct = member;
     for (int t = 0; t < my_tiles; ++t, ct += G) {
-#pragma unroll
-        for (int n = 0; n < FP + FQ; ++n) read_one(smem + (s & 1) * STAGE_BYTES, lo0, 0, n);
         {
             // start values: -||c||^2 / 2 of the lane's 32 centroid rows
             const char *cm = cbuf + (t & 1) * 1024 + (wp * (FP * 16) + 4 * (lane >> 4)) * 4;
@@ -409,26 +424,31 @@ __global__ __launch_bounds__(r4::NT) void route_stream4_kernel(RouteKParams p)
             for (int i = 0; i < FP; ++i) {
                 const f32x4_t ci = *reinterpret_cast<const f32x4_t *>(cm + i * 64);
 #pragma unroll
-                for (int j = 0; j < FQ; ++j) acc[i][j] = ci;
+                for (int e = 0; e < 4; ++e) asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(acc[i][0][e]) : "v"(ci[e]));
             }
         }
-        asm volatile("s_nop 7" ::: "memory");   // accumulator writes before the first MFMA reads them
-        for (int kb = 0; kb < nkb; ++kb, ++s) body(s, kb == nkb - 1, ct + G, (t + 1) & 1);
+        asm volatile("s_nop 7" ::: "memory");   // the writes before the first MFMA reads them
+        body(std::true_type{}, s, nkb == 1, ct + G, (t + 1) & 1);
+        ++s;
+        for (int kb = 1; kb < nkb; ++kb, ++s) body(std::false_type{}, s, kb == nkb - 1, ct + G, (t + 1) & 1);
         asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs' results before the fold reads them
-        // a lane's scores come in ascending centroid order, so a strict '>' keeps the lowest index among equals
-        // (every score is read out of its AccVGPR by an instruction of its own, in place: left to the
-        // compiler, all 256 are copied out at once and push everything else out of the registers)
+        // A lane's scores come in ascending centroid order, so a strict '>' keeps the lowest index among
+        // equals.  Every score is read out of its AccVGPR by an instruction of its own, in place (left to
+        // the compiler, all 256 are copied out at once and push everything else out of the registers), and
+        // the eight queries of a lane take turns: their running bests are independent, and with one wave
+        // on the SIMD a compare that waits for the select before it costs twice its issue time.
         const int code0 = ct << 5;
 #pragma unroll
         for (int i = 0; i < FP; ++i)
 #pragma unroll
-            for (int j = 0; j < FQ; ++j) {
+            for (int e = 0; e < 4; ++e) {
+                float sc[FQ];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float sc;
-                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(sc) : "a"(acc[i][j][e]));
-                    const bool gt = sc > bestv[j];
-                    bestv[j] = gt ? sc : bestv[j];
+                for (int j = 0; j < FQ; ++j) asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(sc[j]) : "a"(acc[i][j][e]));
+#pragma unroll
+                for (int j = 0; j < FQ; ++j) {
+                    const bool gt = sc[j] > bestv[j];
+                    bestv[j] = gt ? sc[j] : bestv[j];
                     bestc[j] = gt ? code0 + (i * 4 + e) : bestc[j];
                 }
                 __builtin_amdgcn_sched_barrier(0);
