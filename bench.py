@@ -423,7 +423,7 @@ def bench_router(ctx, steps, warmup, with_cpu=False):
     return {"ms_per_call": ms, "ms_per_call_median": stats["median_ms"], "ms_per_call_min": stats["min_ms"],
             "queries_per_s": rw.N / (ms * 1e-3), "TFLOPs": tf,
             "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS, "cpu_baseline": cpu,
-            "traffic": measured_traffic("route_stream_kernel", "c3"),
+            "traffic": measured_traffic("route_stream4_kernel", "c3"),
             "top4_of_4096_queries": {"ms_per_call": tms, "queries_per_s": 4096 / (tms * 1e-3)}, "kernels": kt}
 
 

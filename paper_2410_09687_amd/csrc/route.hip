@@ -20,7 +20,6 @@
 namespace moin {
 
 using CfgRoute = GemmCore<256, 256, 64, 4, 2>;      // rows: centroids, cols: queries; any D % 8 == 0
-using CfgRouteDma = DmaCore<256, 256, 64, 4, 2, 2>;  // D % 64 == 0
 using CfgRouteSmall = DmaCore<64, 64, 64, 2, 2, 6>;  // small batches: one (centroid chunk, query tile) per workgroup
 
 struct RouteKParams {
@@ -900,7 +899,7 @@ int route_stream_group(int64_t N, int K, int D, int is_bf16)
     RouteArgs a{};
     a.N = N; a.K = K; a.D = D; a.is_bf16 = is_bf16;
     if (!use_stream_route(a)) return 1;
-    const int nct = (K + CfgRouteDma::BM - 1) / CfgRouteDma::BM;
+    const int nct = (K + r4::BT - 1) / r4::BT;
     const int pref[] = {4, 8, 2, 5, 3, 6, 7};
     int best_g = 1;
     double best_waste = 1.05;   // accept at most 5 % of idle tile slots over the plain scheme
