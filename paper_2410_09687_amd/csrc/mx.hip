@@ -356,26 +356,29 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
     };
     // acc[I][J] += fragment pair: one scaled FP8 MFMA on a base block, two bf16
     // MFMAs on an adapter block
-    auto mfma_one = [&](auto base_tag, auto ks_tag, auto i_tag, auto j_tag) __attribute__((always_inline)) {
-        constexpr bool BASE = decltype(base_tag)::value;
+    // (ZERO: the tile's first MFMA on this accumulator takes a constant zero as its addend, so the
+    // accumulators are never cleared: 256 register writes per tile, 8 cycles each at one wave per SIMD)
+    auto mfma_one = [&](auto base_tag, auto ks_tag, auto i_tag, auto j_tag, auto zero_tag) __attribute__((always_inline)) {
+        constexpr bool BASE = decltype(base_tag)::value, ZERO = decltype(zero_tag)::value;
         constexpr int KS = decltype(ks_tag)::value, I = decltype(i_tag)::value, J = decltype(j_tag)::value;
+        const f32x16_t c0 = ZERO ? f32x16_t{} : acc[I][J];
         if constexpr (BASE) {
             acc[I][J] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                fp[KS][I], fq[KS][J], acc[I][J], 0, 0, (I & 1) * 2 + KS, (int)sc[I / 2], (J & 1) * 2 + KS,
+                fp[KS][I], fq[KS][J], c0, 0, 0, (I & 1) * 2 + KS, (int)sc[I / 2], (J & 1) * 2 + KS,
                 (int)sc[FP / 2 + J / 2]);
         } else {
-            acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo16(fp[KS][I]), lo16(fq[KS][J]), acc[I][J], 0, 0, 0);
+            acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo16(fp[KS][I]), lo16(fq[KS][J]), c0, 0, 0, 0);
             acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi16(fp[KS][I]), hi16(fq[KS][J]), acc[I][J], 0, 0, 0);
         }
     };
     static_assert(FP == 4 && FQ == 4, "the MFMA list below is written out for 4 x 4 accumulators");
-    auto mfmas = [&](auto base_tag, auto ks_tag) __attribute__((always_inline)) {
+    auto mfmas = [&](auto base_tag, auto ks_tag, auto zero_tag) __attribute__((always_inline)) {
         using std::integral_constant;
-#define MOIN_MX_ROW(I)                                                                   \
-    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 0>{}); \
-    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 1>{}); \
-    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 2>{}); \
-    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 3>{});
+#define MOIN_MX_ROW(I)                                                                             \
+    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 0>{}, zero_tag); \
+    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 1>{}, zero_tag); \
+    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 2>{}, zero_tag); \
+    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 3>{}, zero_tag);
         MOIN_MX_ROW(0) MOIN_MX_ROW(1) MOIN_MX_ROW(2) MOIN_MX_ROW(3)
 #undef MOIN_MX_ROW
     };
@@ -392,12 +395,12 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
     // ahead is fetched into the stage this block frees, and the next block's scales
     // and leading fragments are read, in any case: at the stream's end they are
     // repeated requests and stale bytes of LDS that nothing uses.
-    auto body = [&](int s, auto base_tag) __attribute__((always_inline)) {
-        constexpr bool BASE = decltype(base_tag)::value;
+    auto body = [&](int s, auto base_tag, auto first_tag) __attribute__((always_inline)) {
+        constexpr bool BASE = decltype(base_tag)::value;   // first_tag: the tile's first block
         const char *st_cur = smem + (s & 1) * STAGE_BYTES;
         const char *st_nxt = smem + ((s + 1) & 1) * STAGE_BYTES;
         read_frags(st_cur, 1);
-        mfmas(base_tag, std::integral_constant<int, 0>{});
+        mfmas(base_tag, std::integral_constant<int, 0>{}, first_tag);
         // MFMAs have no side effects, so only data flow orders them against the
         // barrier: making their results operands of an (empty) volatile asm keeps the
         // first k-step's MFMAs ahead of it, where they cover the latency of the
@@ -429,7 +432,7 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
         read_frags(st_nxt, 0);
         issue(pft, pfb, s & 1);
         ++pfb;
-        mfmas(base_tag, std::integral_constant<int, 1>{});
+        mfmas(base_tag, std::integral_constant<int, 1>{}, std::false_type{});
         if constexpr (MX) regroup();
 #pragma unroll
         for (int n = 0; n < FP * FQ; ++n) {
@@ -454,18 +457,13 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
         if constexpr (MX) read_scales(smem + SMEM_STAGES + (s & 1) * SC_BYTES);
         read_frags(smem + (s & 1) * STAGE_BYTES, 0);
         if constexpr (MX) regroup();
-#pragma unroll
-        for (int i = 0; i < FP; ++i)
-#pragma unroll
-            for (int j = 0; j < FQ; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
         const int total = cur.total;
-        int b = 0;
-        const int nb = min(nkb0, total);   // a part of a plain tile has fewer blocks than the full range
-        for (; b < nb; ++b, ++s) body(s, std::integral_constant<bool, MX>{});
-        for (; b < total; ++b, ++s) body(s, std::false_type{});
+        const int nb = min(nkb0, total);   // a part of a plain tile has fewer blocks than the full range; >= 1
+        body(s, std::integral_constant<bool, MX>{}, std::true_type{});
+        ++s;
+        int b = 1;
+        for (; b < nb; ++b, ++s) body(s, std::integral_constant<bool, MX>{}, std::false_type{});
+        for (; b < total; ++b, ++s) body(s, std::false_type{}, std::false_type{});
 
         // epilogue through the wave's private 4 KB of LDS beyond the stages (which
         // the next tile's loads are already filling)
