@@ -35,6 +35,7 @@ struct RouteKParams {
     int64_t N;
     int K, D;
     int group;            // streaming kernel: workgroups that share one query tile
+    int64_t n_virtual;    // streaming kernel: work items (query tiles rounded up to 8, times group)
     int self_clean;       // small-batch kernel: best / arrivals are clean on entry and are left clean
                           // (the finishing workgroup resets them and zeroes counts before its tally)
     // small-batch kernel, optional: the finishing workgroup goes on to group the routed batch by
@@ -243,48 +244,86 @@ __global__ __launch_bounds__(r4::NT) void route_stream4_kernel(RouteKParams p)
     const int lane = threadIdx.x & 63;
     const int wave = uniform(threadIdx.x >> 6);
     const int wp = wave >> 1, wq = wave & 1;
+    // Work items: virtual workgroup v = (query tile, member of its group), query tile t on XCD t % 8 with
+    // its G members in consecutive slots there.  The launch is persistent -- one workgroup per compute
+    // unit, workgroup b takes v = b, b + gridDim, ... (gridDim is a multiple of 8 G, so the XCD and the
+    // member stay the same) -- and the blocks of ALL its items form one stream: the first blocks of the
+    // next item are requested under the last blocks of this one.  One launch per item left the matrix
+    // core idle for a workgroup's dispatch and the 3.4 us from its start to its first block landed, once
+    // per 90 us of work.
     const int G = p.group;
-    const int slot = blockIdx.x >> 3;
-    const int member = slot % G;
-    const int64_t qtile = (int64_t)(slot / G) * 8 + (blockIdx.x & 7);
-    const int64_t q0 = qtile * BT;
-    if (q0 >= p.N) return;
-    const int nq = (int)min((int64_t)BT, p.N - q0);
+    const int member = (int)(blockIdx.x >> 3) % G;
+    const int xcd = blockIdx.x & 7;
+    // (gridDim = 8 G n: item `it` of this workgroup is query tile ((blockIdx >> 3) / G + it n) * 8 + xcd)
+    const int64_t q0_first = ((int64_t)((blockIdx.x >> 3) / G) * 8 + xcd) * BT;
+    const int64_t q0_step = (int64_t)(gridDim.x / (8 * G)) * 8 * BT;
+    auto item_q0 = [&](int it) __attribute__((always_inline)) { return q0_first + (int64_t)it * q0_step; };
+    int n_items = (int)((p.n_virtual - 1 - (int64_t)blockIdx.x) / gridDim.x) + 1;   // blockIdx.x < n_virtual
+    while (n_items > 0 && item_q0(n_items - 1) >= p.N) --n_items;   // (only trailing items can lie past the batch)
+    if (n_items == 0) return;
     const uint32_t ld = (uint32_t)p.D * 2u;
     const int nkb = p.D / BK;
     const int nct = (p.K + BT - 1) / BT;
     const int last_rows = p.K - (nct - 1) * BT;
-    const char *qb = p.emb + q0 * (int64_t)ld;
     const int my_tiles = (nct - member + G - 1) / G;   // >= 1: G <= nct
-    const int total = my_tiles * nkb;
 
     // requests of one block (centroid tile ct, contraction block kb): n = 0..7 centroid rows, 8..15 query
-    // rows.  Per lane: the two chunk offsets and the 16 source rows (clamped to the tile's last row; the
-    // centroid rows change with the tile being fetched only when that is the last, partial one); the
+    // rows.  Per lane: the two chunk offsets and the eight source rows of its requests, clamped per
+    // request to the operand's last valid row (a min and a multiply-add besides the request itself); the
     // block's position along k is in the uniform base pointers.
     const uint32_t c16a = (((uint32_t)lane & 7) ^ ((uint32_t)lane >> 4)) * 16, c16b = c16a ^ 64u;   // even j, odd j
-    const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8)) + ((uint32_t)lane >> 3);
-    uint32_t rowc[2 * LOADS];
+    uint32_t rowu[LOADS];
 #pragma unroll
-    for (int n = 0; n < LOADS; ++n) rowc[LOADS + n] = min(dma_row + 8u * n, (uint32_t)(nq - 1));
-    auto rows_of = [&](int ct) __attribute__((always_inline)) {
-        const uint32_t c_last = (uint32_t)((ct == nct - 1 ? last_rows : BT) - 1);
-#pragma unroll
-        for (int n = 0; n < LOADS; ++n) rowc[n] = min(dma_row + 8u * n, c_last);
-    };
+    for (int n = 0; n < LOADS; ++n) rowu[n] = (uint32_t)(wave * (LOADS * 8)) + ((uint32_t)lane >> 3) + 8u * n;
     struct Fetch {
         const char *pp, *pq;
+        uint32_t p_last, q_last;
     };
-    auto fetch_of = [&](int ct, int kb) __attribute__((always_inline)) {
-        Fetch f;
-        f.pp = p.cent + (int64_t)ct * BT * ld + kb * (BK * 2);
-        f.pq = qb + kb * (BK * 2);
+    // The fetch cursor: what the next block to request needs (operand pointers at its first k, the operands'
+    // last valid rows), kept up to date step by step -- 128 bytes along both rows from block to block, new
+    // pointers only where a tile or an item begins -- so that taking a block under the MFMAs costs a
+    // handful of scalar instructions.  Past the stream's end it stays on the last block, which is then
+    // requested again into the stage that is free anyway.
+    int pit = 0, pct = member, pkb = 0;
+    int pleft = n_items * my_tiles * nkb;   // blocks not yet taken
+    const char *pqb = nullptr;              // the item's query rows at k = 0
+    Fetch pf;
+    auto cursor_tile = [&]() __attribute__((always_inline)) {
+        pf.pp = p.cent + (int64_t)pct * BT * ld;
+        pf.pq = pqb;
+        pf.p_last = (uint32_t)((pct == nct - 1 ? last_rows : BT) - 1);
+    };
+    auto cursor_item = [&]() __attribute__((always_inline)) {
+        const int64_t q0_ = item_q0(pit);
+        pqb = p.emb + q0_ * (int64_t)ld;
+        pf.q_last = (uint32_t)((int)min((int64_t)BT, p.N - q0_) - 1);
+    };
+    auto cursor_fetch = [&]() __attribute__((always_inline)) {
+        const Fetch f = pf;
+        if (pleft > 1) {
+            --pleft;
+            if (++pkb < nkb) {
+                pf.pp += BK * 2;
+                pf.pq += BK * 2;
+            } else {
+                pkb = 0;
+                pct += G;
+                if (pct >= nct) {
+                    pct = member;
+                    ++pit;
+                    cursor_item();
+                }
+                cursor_tile();
+            }
+        }
         return f;
     };
+    cursor_item();
+    cursor_tile();
     auto issue_one = [&](const Fetch &f, char *stage, int n) __attribute__((always_inline)) {
         const int j = n & 7;
         const bool q = n >= LOADS;
-        const uint32_t off = __umul24(rowc[n], ld) + ((j & 1) ? c16b : c16a);
+        const uint32_t off = __umul24(min(rowu[j], q ? f.q_last : f.p_last), ld) + ((j & 1) ? c16b : c16a);
         __builtin_amdgcn_global_load_lds(MOIN_GPTR((q ? f.pq : f.pp) + off),
                                          MOIN_LPTR(stage + (q ? OP_BYTES : 0) + (wave * LOADS + j) * 1024), 16, 0, 0);
     };
@@ -327,48 +366,45 @@ __global__ __launch_bounds__(r4::NT) void route_stream4_kernel(RouteKParams p)
 
     float bestv[FQ];
     int bestc[FQ];   // (tile << 5) | (accumulator row block i << 2) | element
-#pragma unroll
-    for (int j = 0; j < FQ; ++j) {
-        bestv[j] = -__builtin_inff();
-        bestc[j] = 0;
-    }
 
-    // block to fetch next (two ahead of the one being computed) and how many are left to fetch
-    int pkb = 2, pct = member, pleft = total - 2;
-    while (pkb >= nkb) {       // D = 64 or 128: fewer than three blocks per centroid tile
-        pkb -= nkb;
-        pct += G;
-    }
-    int pct_rows = member;   // the tile rowc's centroid part belongs to
-    rows_of(member);
-    auto body = [&](auto first_tag, int s, bool last_of_tile, int ct_next, int slot_next) __attribute__((always_inline)) {
+    // cm: where the lane's start values of the tile lie in LDS (first blocks only)
+    auto body = [&](auto first_tag, int s, bool last_of_tile, int ct_next, int slot_next, const char *cm) __attribute__((always_inline)) {
         constexpr bool FIRST = decltype(first_tag)::value;   // the tile's first block
         char *st_cur = smem + (s & 1) * STAGE_BYTES;
         const char *st_nxt = smem + ((s + 1) & 1) * STAGE_BYTES;
         Fetch f;
+        // A first block loads the start values of row block i straight from LDS into the AccVGPRs of
+        // accumulator (i, 0) -- one instruction, one register quad that the compiler has no reason to move
+        // (four v_accvgpr_write results it assembled into a quad with copies, placed right in front of an
+        // MFMA it cannot see) -- one row block ahead, and waits for it by count: behind that load come the
+        // row block's fragment reads (four in each of the first four) and the next row block's load.
+        const uint32_t cm_lds = (uint32_t)(size_t)MOIN_LPTR(cm);
+        if constexpr (FIRST) asm volatile("ds_read_b128 %0, %1" : "=a"(acc[0][0]) : "v"(cm_lds) : "memory");
 #pragma unroll
         for (int n = 0; n < FP * FQ; ++n) {
-            if constexpr (FIRST) mfma_first(n / FQ, (n + 1) % FQ);   // 1..7, then 0
-            else mfma(0, n / FQ, n % FQ);
+            if constexpr (FIRST) {
+                if (n % FQ == 0) {
+                    const int i = n / FQ;
+                    if (i + 1 < FP)
+                        asm volatile("ds_read_b128 %0, %1" : "=a"(acc[i + 1][0]) : "v"(cm_lds + (uint32_t)((i + 1) * 64)) : "memory");
+                    constexpr int RPR = FQ / 2;   // fragment reads per row block of MFMAs, while there are any
+                    const int behind = ((i >= 1 && (i - 1) * RPR < FP + FQ) ? RPR : 0) + (i + 1 < FP ? 1 : 0);
+                    if (behind == 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    else if (behind == 1) asm volatile("s_waitcnt lgkmcnt(1)" ::: "memory");
+                    else asm volatile("s_waitcnt lgkmcnt(5)" ::: "memory");
+                    static_assert(RPR + 1 == 5, "the counted wait above");
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                mfma_first(n / FQ, (n + 1) % FQ);   // 1..7, then 0
+            } else {
+                mfma(0, n / FQ, n % FQ);
+            }
             if (n % 2 == 1 && n / 2 < FP + FQ) {
                 read_one(st_cur, lo1, 1, frag_at(n / 2));
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (n == 36) {
-                // what the second half fetches; past the stream's end the item's last block again, into
-                // the free stage
-                const bool more = pleft > 0;
-                const int fct = more ? pct : member + (my_tiles - 1) * G;
-                if (fct != pct_rows) {
-                    rows_of(fct);
-                    pct_rows = fct;
-                }
-                f = fetch_of(fct, more ? pkb : nkb - 1);
-                --pleft;
-                if (++pkb == nkb) {
-                    pkb = 0;
-                    pct += G;
-                }
+                f = cursor_fetch();   // what the second half fetches
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (n == 44) {
@@ -396,16 +432,11 @@ __global__ __launch_bounds__(r4::NT) void route_stream4_kernel(RouteKParams p)
 
     fetch_init(member, 0);
     {
-        const Fetch f0 = fetch_of(member, 0);
+        const Fetch f0 = cursor_fetch();
 #pragma unroll
         for (int n = 0; n < 2 * LOADS; ++n) issue_one(f0, smem, n);
-        // (a one-block item fetches its block twice: the second copy is never read)
-        const int ct1 = nkb > 1 ? member : (total > 1 ? member + G : member);
-        if (ct1 != pct_rows) {
-            rows_of(ct1);
-            pct_rows = ct1;
-        }
-        const Fetch f1 = fetch_of(ct1, nkb > 1 ? 1 : 0);
+        // (a stream of one block fetches it twice: the second copy is never read)
+        const Fetch f1 = cursor_fetch();
 #pragma unroll
         for (int n = 0; n < 2 * LOADS; ++n) issue_one(f1, smem + STAGE_BYTES, n);
     }
@@ -414,22 +445,28 @@ __global__ __launch_bounds__(r4::NT) void route_stream4_kernel(RouteKParams p)
     // the first block's leading fragments; every later block's are read under the block before it
 #pragma unroll
     for (int n = 0; n < FP + FQ; ++n) read_one(smem, lo0, 0, n);
-    int s = 0, ct = member;
-    for (int t = 0; t < my_tiles; ++t, ct += G) {
-        {
-            // start values: -||c||^2 / 2 of the lane's 32 centroid rows
-            const char *cm = cbuf + (t & 1) * 1024 + (wp * (FP * 16) + 4 * (lane >> 4)) * 4;
+    const int g = lane >> 4;
+    float *sv = reinterpret_cast<float *>(smem + SMEM_STAGES + CBUF_BYTES);
+    int *si = reinterpret_cast<int *>(smem + SMEM_STAGES + CBUF_BYTES + 2 * BT * 4);
+    int s = 0;    // blocks done so far (stage parity)
+    int tt = 0;   // tiles done so far (parity of the start values' slot)
+    for (int it = 0; it < n_items; ++it) {
+    const int64_t q0 = item_q0(it);
+    const int nq = (int)min((int64_t)BT, p.N - q0);
 #pragma unroll
-            for (int i = 0; i < FP; ++i) {
-                const f32x4_t ci = *reinterpret_cast<const f32x4_t *>(cm + i * 64);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(acc[i][0][e]) : "v"(ci[e]));
-            }
-        }
-        asm volatile("s_nop 7" ::: "memory");   // the writes before the first MFMA reads them
-        body(std::true_type{}, s, nkb == 1, ct + G, (t + 1) & 1);
+    for (int j = 0; j < FQ; ++j) {
+        bestv[j] = -__builtin_inff();
+        bestc[j] = 0;
+    }
+    int ct = member;
+    for (int t = 0; t < my_tiles; ++t, ct += G, ++tt) {
+        // the tile after this one: the item's next, or the next item's first, or none (nct)
+        const int ct_next = t + 1 < my_tiles ? ct + G : (it + 1 < n_items ? member : nct);
+        // start values: -||c||^2 / 2 of the lane's 32 centroid rows
+        const char *cm = cbuf + (tt & 1) * 1024 + (wp * (FP * 16) + 4 * (lane >> 4)) * 4;
+        body(std::true_type{}, s, nkb == 1, ct_next, (tt + 1) & 1, cm);
         ++s;
-        for (int kb = 1; kb < nkb; ++kb, ++s) body(std::false_type{}, s, kb == nkb - 1, ct + G, (t + 1) & 1);
+        for (int kb = 1; kb < nkb; ++kb, ++s) body(std::false_type{}, s, kb == nkb - 1, ct_next, (tt + 1) & 1, nullptr);
         asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs' results before the fold reads them
         // A lane's scores come in ascending centroid order, so a strict '>' keeps the lowest index among
         // equals.  Every score is read out of its AccVGPR by an instruction of its own, in place (left to
@@ -453,13 +490,9 @@ __global__ __launch_bounds__(r4::NT) void route_stream4_kernel(RouteKParams p)
                 __builtin_amdgcn_sched_barrier(0);
             }
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the requests repeated past the stream's end
-
     // position code -> centroid index; merge the four lane groups (rows 4 * (lane / 16) interleave), then
-    // the two waves that hold the other half of the tile's centroids: higher score, else lower index
-    const int g = lane >> 4;
-    float *sv = reinterpret_cast<float *>(smem + SMEM_STAGES + CBUF_BYTES);
-    int *si = reinterpret_cast<int *>(smem + SMEM_STAGES + CBUF_BYTES + 2 * BT * 4);
+    // the two waves that hold the other half of the tile's centroids: higher score, else lower index.
+    // (The exchange area is written again only an item later, many block barriers after these reads.)
 #pragma unroll
     for (int j = 0; j < FQ; ++j) {
         const int c = bestc[j];
@@ -497,6 +530,8 @@ __global__ __launch_bounds__(r4::NT) void route_stream4_kernel(RouteKParams p)
             atomicMin(&p.best[q0 + col], ((unsigned long long)float_order_key(-bv) << 32) | (unsigned)bi);
         }
     }
+    }   // items
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the requests repeated past the stream's end
 }
 
 // Packed (score key, index) winners of the grouped streaming kernel -> ids.
@@ -976,7 +1011,17 @@ hipError_t launch_route(const RouteArgs &a, hipStream_t stream)
             // query tile t runs on XCD t % 8, its workgroups in consecutive slots there
             const int64_t sgrid = (grid + 7) / 8 * 8 * p.group;
             if (sgrid > 0x7fffffffLL) return hipErrorInvalidValue;
-            hipLaunchKernelGGL(route_stream4_kernel, dim3((unsigned)sgrid), dim3(r4::NT), r4::SMEM_BYTES, stream, p);
+            // persistent: one workgroup per compute unit, a multiple of 8 * group so that a workgroup's
+            // items all lie on its XCD and belong to its member of the group
+            const int64_t unit = 8 * (int64_t)p.group;
+            int64_t pgrid = (int64_t)compute_units() / unit * unit;
+            if (pgrid < unit) pgrid = unit;
+            if (pgrid > sgrid) pgrid = sgrid;
+#ifdef MOIN_ROUTE_NONPERSISTENT
+            pgrid = sgrid;
+#endif
+            p.n_virtual = sgrid;
+            hipLaunchKernelGGL(route_stream4_kernel, dim3((unsigned)pgrid), dim3(r4::NT), r4::SMEM_BYTES, stream, p);
             if (p.group > 1)
                 hipLaunchKernelGGL(route_unpack_kernel, dim3((unsigned)((a.N + 255) / 256)), dim3(256), 0,
                                    stream, p.best, a.N, a.K, a.slot, a.cid, a.expert_ids);

@@ -6,7 +6,8 @@ error.  This test compiles the kernels to assembly (no GPU) and checks, in every
  * nothing is spilled to scratch memory (a reload waits for every direct-to-LDS load in flight), and
  * every AccVGPR access the compiler emitted itself (outside the assembly statements) keeps its distance from the
    last MFMA that wrote that register, and every such write from the last MFMA that read the register as its
-   addend: at least MIN_GAP other instructions, or s_nops worth as much.
+   addend: at least MIN_GAP other instructions, or s_nops worth as much; and no MFMA reads an AccVGPR that the
+   compiler wrote fewer than MIN_GAP_AFTER_WRITE instructions before.
 The scan follows the listing top to bottom; it does not follow branches, so a copy at a loop's head is checked
 against the MFMAs listed above it, not against those at the loop's end.
 """
@@ -20,6 +21,7 @@ import pytest
 from paper_2410_09687_amd import build as B
 
 MIN_GAP = 6          # instructions (4 cycles each at the least) between an MFMA of 4 passes and a read of its result
+MIN_GAP_AFTER_WRITE = 3
 KERNELS = {"linear_stream.hip": "linear_stream_kernel", "route.hip": "route_stream4_kernel"}
 
 
@@ -66,6 +68,7 @@ def test_no_scratch_and_no_early_accvgpr_access(src):
         in_asm = False
         last_write = {}      # AccVGPR -> instruction count at the MFMA that wrote it last
         last_addend = {}     # AccVGPR -> instruction count at the MFMA that read it last as its addend
+        last_copy = {}       # AccVGPR -> instruction count at the compiler-placed instruction that wrote it last
         count = 0            # instructions so far, an s_nop N counted as its N + 1 wait states / 4
         n_mfma = 0
         for line in lines:
@@ -90,6 +93,8 @@ def test_no_scratch_and_no_early_accvgpr_access(src):
                     last_write[r_] = count
                 for r_ in _regs(args[3]) if len(args) > 3 else ():
                     last_addend[r_] = count
+                    gap = count - last_copy.get(r_, -10 ** 9)
+                    assert gap >= MIN_GAP_AFTER_WRITE, f"{sym}: `{t}` reads a{r_} {gap} instructions behind a compiler-placed write"
             elif op.startswith("v_accvgpr") and not in_asm:
                 touched = set()
                 for a in args:
@@ -99,6 +104,7 @@ def test_no_scratch_and_no_early_accvgpr_access(src):
                     assert gap > MIN_GAP, f"{sym}: compiler-placed `{t}` {gap} instructions behind the MFMA that wrote a{r_}"
                 if op in ("v_accvgpr_write_b32", "v_accvgpr_mov_b32"):
                     for r_ in _regs(args[0]):
+                        last_copy[r_] = count
                         gap = count - last_addend.get(r_, -10 ** 9)
                         assert gap > MIN_GAP, f"{sym}: compiler-placed `{t}` {gap} instructions behind an MFMA that reads a{r_}"
         assert n_mfma >= 128, f"{sym}: expected the unrolled MFMA blocks, found {n_mfma} MFMAs"

@@ -39,6 +39,18 @@ def test_bf16_router_streaming_kernel_edges(N, K, D):
     assert torch.equal(counts.long(), torch.bincount(cids.long(), minlength=K))
 
 
+@pytest.mark.parametrize("N,K,D", [(40000, 520, 64), (70000, 200, 64), (66000, 1100, 128)])
+def test_bf16_router_streaming_kernel_several_items_per_workgroup(N, K, D):
+    # more query tiles than the persistent launch has workgroups: a workgroup streams through several
+    # (query tile, group member) items, the last of them ragged; groups of 3, 1 and 5 workgroups per tile
+    rin = _route_case(N, K, D, "bf16", True, seed=N + K + D)
+    print(f"[gpu] route bf16 stream, several items N={N} K={K} D={D}", flush=True)
+    eids, cids, counts = moin.moin_route(gc.ctx(), rin.emb, rin.centroids, want_counts=True)
+    gc.ctx().check()
+    gc.check_route(rin.emb, rin.centroids, cids)
+    assert torch.equal(counts.long(), torch.bincount(cids.long(), minlength=K))
+
+
 def test_f32_router_small():
     rin = _route_case(300, 77, 100, "f32", False, seed=3)
     eids, cids, counts = moin.moin_route(gc.ctx(), rin.emb, rin.centroids, want_counts=True)
