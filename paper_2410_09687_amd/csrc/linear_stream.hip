@@ -214,6 +214,12 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
     auto mfma = [&](int set, int i, int j) __attribute__((always_inline)) {
         asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fr[set][i]), "v"(fr[set][FP + j]));
     };
+    // a tile's first MFMA on an accumulator takes a constant zero as its addend: the accumulators are never
+    // cleared (256 register writes per tile, and with one wave on the SIMD a vector instruction issues
+    // every 8 cycles)
+    auto mfma_first = [&](int i, int j) __attribute__((always_inline)) {
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=a"(acc[i][j]) : "v"(fr[0][i]), "v"(fr[0][FP + j]));
+    };
 
     Tile cur = stream::load_tile(p, id, band_end);
     id += nslot;
@@ -234,13 +240,14 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
     // fourth MFMA, 2570 without the requests, 2480 without requests and reads.  No branch after the
     // barrier: past the stream's end the fetch repeats the last block into the free stage and the
     // reads take stale bytes that nothing uses.
-    auto body = [&](int s) __attribute__((always_inline)) {
+    auto body = [&](int s, auto first_tag) __attribute__((always_inline)) {
         char *st_cur = smem + (s & 1) * STAGE_BYTES;
         const char *st_nxt = smem + ((s + 1) & 1) * STAGE_BYTES;
         Fetch f;
 #pragma unroll
         for (int n = 0; n < FP * FQ; ++n) {
-            mfma(0, n / FQ, n % FQ);
+            if constexpr (decltype(first_tag)::value) mfma_first(n / FQ, n % FQ);   // the tile's first block
+            else mfma(0, n / FQ, n % FQ);
             if (n % 2 == 1 && n / 2 < FP + FQ) {
                 read_one(st_cur, lo1, 1, frag_at(n / 2));
                 __builtin_amdgcn_sched_barrier(0);
@@ -294,13 +301,10 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
 #pragma unroll
             for (int n = 0; n < FP + FQ; ++n) read_one(smem + (s & 1) * STAGE_BYTES, lo0, 0, n);
         }
-#pragma unroll
-        for (int i = 0; i < FP; ++i)
-#pragma unroll
-            for (int j = 0; j < FQ; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        asm volatile("s_nop 7" ::: "memory");   // accumulator writes before the first MFMA reads them
-        const int total = cur.total;
-        for (int b = 0; b < total; ++b, ++s) body(s);
+        const int total = cur.total;   // >= 2
+        body(s, std::true_type{});
+        ++s;
+        for (int b = 1; b < total; ++b, ++s) body(s, std::false_type{});
         asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs' results before the epilogue reads them
 
         // Epilogue through the wave's private 8 KB beyond the stages (which the next tile's loads are
@@ -339,7 +343,10 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
 #pragma unroll
                 for (int i = 0; i < FP; ++i) {
                     const int slot_ = (i * 4 + kg) ^ (2 * t16);
-                    const f32x4_t a = acc[i][j];
+                    // (read in place: left to itself the compiler may copy all 256 accumulators out first)
+                    f32x4_t a;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a[e]) : "a"(acc[i][j][e]));
                     if constexpr (Y_F32)
                         *reinterpret_cast<f32x4_t *>(blk + t16 * ROW + slot_ * SLOT) = a;
                     else
