@@ -470,22 +470,29 @@ __global__ __launch_bounds__(r4::NT) void route_stream4_kernel(RouteKParams p)
         asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs' results before the fold reads them
         // A lane's scores come in ascending centroid order, so a strict '>' keeps the lowest index among
         // equals.  Every score is read out of its AccVGPR by an instruction of its own, in place (left to
-        // the compiler, all 256 are copied out at once and push everything else out of the registers), and
-        // the eight queries of a lane take turns: their running bests are independent, and with one wave
-        // on the SIMD a compare that waits for the select before it costs twice its issue time.
+        // the compiler, all 256 are copied out at once and push everything else out of the registers).
+        // The compares of a lane's eight queries write eight scalar register pairs, the sixteen selects
+        // follow: written as `sc > best ? ...` the compiler puts every compare's result in VCC and needs
+        // two wait states before each select -- 23 cycles per score against 16 in a loop of nothing else
+        // (one wave on the SIMD issues a vector instruction every 5.6 cycles).  A select reads its mask
+        // seven or more instructions after the compare that wrote it, which is the distance the hardware
+        // wants between a vector write of a scalar register and a vector read of it.
         const int code0 = ct << 5;
 #pragma unroll
         for (int i = 0; i < FP; ++i)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float sc[FQ];
+                unsigned long long gt[FQ];
+                const int code = code0 + (i * 4 + e);
 #pragma unroll
                 for (int j = 0; j < FQ; ++j) asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(sc[j]) : "a"(acc[i][j][e]));
 #pragma unroll
+                for (int j = 0; j < FQ; ++j) asm volatile("v_cmp_gt_f32_e64 %0, %1, %2" : "=s"(gt[j]) : "v"(sc[j]), "v"(bestv[j]));
+#pragma unroll
                 for (int j = 0; j < FQ; ++j) {
-                    const bool gt = sc[j] > bestv[j];
-                    bestv[j] = gt ? sc[j] : bestv[j];
-                    bestc[j] = gt ? code0 + (i * 4 + e) : bestc[j];
+                    asm volatile("v_cndmask_b32_e64 %0, %0, %1, %2" : "+v"(bestv[j]) : "v"(sc[j]), "s"(gt[j]));
+                    asm volatile("v_cndmask_b32_e64 %0, %0, %1, %2" : "+v"(bestc[j]) : "v"(code), "s"(gt[j]));
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
