@@ -216,7 +216,7 @@ __global__ __launch_bounds__(s16::NT) void linear_stream_kernel(stream::Params p
     };
     // a tile's first MFMA on an accumulator takes a constant zero as its addend: the accumulators are never
     // cleared (256 register writes per tile, and with one wave on the SIMD a vector instruction issues
-    // every 8 cycles)
+    // every 5.6 cycles)
     auto mfma_first = [&](int i, int j) __attribute__((always_inline)) {
         asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=a"(acc[i][j]) : "v"(fr[0][i]), "v"(fr[0][FP + j]));
     };

@@ -352,9 +352,9 @@ __global__ __launch_bounds__(r4::NT) void route_stream4_kernel(RouteKParams p)
         asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(fr[set][i]), "v"(fr[set][FP + j]));
     };
     // A tile's first k-step takes -||c||^2 / 2 of the accumulator's four centroid rows as its addend.  The
-    // eight accumulators of a row block share those four values: they are written into the block's first
-    // accumulator only (32 register writes per tile instead of 256 -- at one wave per SIMD a register
-    // write costs 8 cycles), the other seven read it as their addend, and it takes its own MFMA last.
+    // eight accumulators of a row block share those four values: they are loaded into the block's first
+    // accumulator only (one LDS read per row block instead of 256 register writes per tile, 5.6 cycles each
+    // at one wave per SIMD), the other seven read it as their addend, and it takes its own MFMA last.
     auto mfma_first = [&](int i, int j) __attribute__((always_inline)) {
         if (j == 0)
             asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][0]) : "v"(fr[0][i]), "v"(fr[0][FP]));
