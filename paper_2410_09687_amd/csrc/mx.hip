@@ -249,69 +249,68 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
     const int nkb0 = p.d_in * EB / ROWB;
     const uint32_t ldq = (uint32_t)p.d_in * EB, ldu = (uint32_t)p.r * 2u;
 
-    // Per-lane constants are recomputed from the lane id at every use (through an
-    // opaque copy): kept alive across the main loop they are spilled, and a reload
-    // goes through the same counter the DMA loads are waited on.
-    auto fresh_lane = [&]() __attribute__((always_inline)) {
-        int v = lane;
-        asm volatile("; lane id, rematerialised" : "+v"(v));
-        return v;
+    // Requests of one block.  DMA mapping: instruction j of a wave fills LDS rows (wave*8 + j)*8 .. +8 of an
+    // operand tile; the lane fetches logical 16-byte chunk (lane%8) ^ swz(row), swz(row) = (row >> 1) & 7
+    // with row = wave*64 + j*8 + lane/8, which is lane/16 for even j and lane/16 + 4 for odd j.  With them
+    // come the block's scale words: 64 rows of either operand per wave, one word per lane.  Per lane and
+    // kernel: its first source row and the two chunk offsets; per block, uniform: the operand pointers at
+    // the block's first k, the pitch, the operands' last valid rows.  A request (issue_one, n = 0..7 output
+    // rows, 8..15 tokens, 16 / 17 the scale words) then costs an add, a min and a multiply-add, and goes
+    // out behind an MFMA of its own.
+    const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8)) + ((uint32_t)lane >> 3);   // + 8 * j
+    const uint32_t c16a = (((uint32_t)lane & 7) ^ ((uint32_t)lane >> 4)) * 16, c16b = c16a ^ 64u;   // even j, odd j
+    struct Fetch {
+        const char *pp, *pq, *ps, *qs;
+        uint32_t ld, p_last, q_last;
     };
-
-    // Starts the loads of block b of tile t into stage `st` (0 / 1).
-    // DMA mapping: instruction j of a wave fills LDS rows (wave*8 + j)*8 .. +8 of an
-    // operand tile; the lane fetches logical 16-byte chunk (lane%8) ^ swz(row),
-    // swz(row) = (row >> 1) & 7 with row = wave*64 + j*8 + lane/8, which is lane/16
-    // for even j and lane/16 + 4 for odd j.  With them come the block's scale
-    // words: 64 rows of either operand per wave, one word per lane.
-    auto issue = [&](const Tile &t, int b, int st) __attribute__((always_inline)) {
-        char *stage = smem + st * STAGE_BYTES;
+    auto fetch_of = [&](const Tile &t, int b) __attribute__((always_inline)) {
+        Fetch f;
         const bool base = b < nkb0;
         const int jb = b - nkb0;
         const bool hi = jb < t.nkb1;
-        const char *pq = base ? t.q0 : (hi ? t.uh : t.ul);
-        const char *pp = base ? t.p0 : t.be;
-        const uint32_t ld = base ? ldq : ldu;
         const int kb = base ? b : (hi ? jb : jb - t.nkb1);
-        const uint32_t kbyte = (uint32_t)kb * ROWB;
-        const uint32_t ln = (uint32_t)fresh_lane();
-        const uint32_t dma_row = (uint32_t)(wave * (LOADS * 8)) + (ln >> 3);   // + 8 * j
-        const uint32_t c16 = (((ln & 7) ^ (ln >> 4)) * 16) + kbyte;             // odd j: ^ 64
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const uint32_t row = min(dma_row + 8u * j, (uint32_t)(t.p_rows - 1));
-            const uint32_t off = __umul24(row, ld) + (c16 ^ ((j & 1) ? 64u : 0u));
-            __builtin_amdgcn_global_load_lds(MOIN_GPTR(pp + off), MOIN_LPTR(stage + (wave * LOADS + j) * 1024),
-                                             16, 0, 0);
-        }
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const uint32_t row = min(dma_row + 8u * j, (uint32_t)(t.q_rows - 1));
-            const uint32_t off = __umul24(row, ld) + (c16 ^ ((j & 1) ? 64u : 0u));
-            __builtin_amdgcn_global_load_lds(MOIN_GPTR(pq + off),
-                                             MOIN_LPTR(stage + OP_BYTES + (wave * LOADS + j) * 1024), 16, 0, 0);
-        }
+        f.pq = (base ? t.q0 : (hi ? t.uh : t.ul)) + kb * ROWB;
+        f.pp = (base ? t.p0 : t.be) + kb * ROWB;
+        f.ld = base ? ldq : ldu;
+        f.p_last = (uint32_t)(t.p_rows - 1);
+        f.q_last = (uint32_t)(t.q_rows - 1);
+        f.ps = f.qs = nullptr;
         if constexpr (MX) {
             // (an adapter block has no scales; it repeats the loads of the tile's first
             // block, so that the body needs no branch)
-            char *sc = smem + SMEM_STAGES + st * SC_BYTES;
             const int sb = base ? b : 0;
-            const char *ps = p.Ws + ((int64_t)(t.kb0 + sb) * p.d_out + t.n0) * 4;
-            const char *qs = p.xs + ((int64_t)(t.kb0 + sb) * p.T + t.row0) * 4;
-            const uint32_t prow = min((uint32_t)(wave * 64) + ln, (uint32_t)(t.p_rows - 1));
-            const uint32_t qrow = min((uint32_t)(wave * 64) + ln, (uint32_t)(t.q_rows - 1));
-            __builtin_amdgcn_global_load_lds(MOIN_GPTR(ps + prow * 4u), MOIN_LPTR(sc + wave * 256), 4, 0, 0);
-            __builtin_amdgcn_global_load_lds(MOIN_GPTR(qs + qrow * 4u), MOIN_LPTR(sc + BT * 4 + wave * 256), 4, 0, 0);
+            f.ps = p.Ws + ((int64_t)(t.kb0 + sb) * p.d_out + t.n0) * 4;
+            f.qs = p.xs + ((int64_t)(t.kb0 + sb) * p.T + t.row0) * 4;
         }
+        return f;
+    };
+    auto issue_one = [&](const Fetch &f, int st, int n) __attribute__((always_inline)) {
+        char *stage = smem + st * STAGE_BYTES;
+        if (n < 2 * LOADS) {
+            const int j = n & (LOADS - 1);
+            const bool q = n >= LOADS;
+            const uint32_t row = min(dma_row + 8u * j, q ? f.q_last : f.p_last);
+            const uint32_t off = __umul24(row, f.ld) + ((j & 1) ? c16b : c16a);
+            __builtin_amdgcn_global_load_lds(MOIN_GPTR((q ? f.pq : f.pp) + off),
+                                             MOIN_LPTR(stage + (q ? OP_BYTES : 0) + (wave * LOADS + j) * 1024), 16, 0, 0);
+        } else if constexpr (MX) {
+            char *sc_ = smem + SMEM_STAGES + st * SC_BYTES;
+            const bool q = n == 2 * LOADS + 1;
+            const uint32_t row = min((uint32_t)(wave * 64) + (uint32_t)lane, q ? f.q_last : f.p_last);
+            __builtin_amdgcn_global_load_lds(MOIN_GPTR((q ? f.qs : f.ps) + row * 4u),
+                                             MOIN_LPTR(sc_ + (q ? BT * 4 : 0) + wave * 256), 4, 0, 0);
+        }
+    };
+    auto issue = [&](const Tile &t, int b, int st) __attribute__((always_inline)) {
+        const Fetch f = fetch_of(t, b);
+#pragma unroll
+        for (int n = 0; n < 2 * LOADS + (MX ? 2 : 0); ++n) issue_one(f, st, n);
     };
 
     // fragment addresses: byte (16 h) ^ (16 f) of the lane's row in the first patch of
     // each operand, f = (r >> 1) & 7; the row offsets are multiples of 128, so chunk
     // c = 4 ks + 2 * half of that row is at (this address) ^ (16 c)
-    auto lane_off = [&]() __attribute__((always_inline)) {   // r * ROWB + ((h ^ f) & 7) * 16
-        const int ln = fresh_lane();
-        return ((ln & 31) * ROWB) | ((((ln >> 5) ^ (ln >> 1)) & 7) * 16);
-    };
+    const int lo_ = ((lane & 31) * ROWB) | ((((lane >> 5) ^ (lane >> 1)) & 7) * 16);   // r * ROWB + ((h ^ f) & 7) * 16
     const int baseP = wp * (FP * 32) * ROWB, baseQ = OP_BYTES + wq * (FQ * 32) * ROWB;   // wave-uniform
     Frag fp[2][FP], fq[2][FQ];
     auto read_frag = [&](Frag &g, const char *stage_, int row, int ks) __attribute__((always_inline)) {
@@ -319,30 +318,31 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
         const i32x4_t hi = *reinterpret_cast<const i32x4_t *>(stage_ + (row ^ (ks * 64 + 32)));
         g = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
+    // fragment n of a k-step: 0..3 output blocks, 4..7 token blocks
+    auto read_frag_n = [&](const char *stage, int ks, int n) __attribute__((always_inline)) {
+        if (n < FP) read_frag(fp[ks][n], stage, baseP + lo_ + n * 32 * ROWB, ks);
+        else read_frag(fq[ks][n - FP], stage, baseQ + lo_ + (n - FP) * 32 * ROWB, ks);
+    };
     auto read_frags = [&](const char *stage, int ks) __attribute__((always_inline)) {
-        const int lo_ = lane_off();
-        const int offP = baseP + lo_, offQ = baseQ + lo_;
 #pragma unroll
-        for (int i = 0; i < FP; ++i) read_frag(fp[ks][i], stage, offP + i * 32 * ROWB, ks);
-#pragma unroll
-        for (int j = 0; j < FQ; ++j) read_frag(fq[ks][j], stage, offQ + j * 32 * ROWB, ks);
+        for (int n = 0; n < FP + FQ; ++n) read_frag_n(stage, ks, n);
     };
     // scale words of this lane's rows, as they lie in LDS (sc_raw: the four bytes of
     // a row's 128 steps) and regrouped (sc: word n holds, for fragments 2n and 2n + 1,
     // the bytes this lane feeds the MFMAs of k-steps 0 and 1; a lane supplies the
     // scale of the first 32-step block of a 64-step slice if h = 0, of the second if 1)
     uint32_t sc_raw[NSC], sc[NSC / 2];
+    auto read_scale_n = [&](const char *area, int n) __attribute__((always_inline)) {
+        const int r = lane & 31;
+        if (n < FP) sc_raw[n] = *reinterpret_cast<const uint32_t *>(area + (wp * (FP * 32) + n * 32 + r) * 4);
+        else sc_raw[n] = *reinterpret_cast<const uint32_t *>(area + (BT + wq * (FQ * 32) + (n - FP) * 32 + r) * 4);
+    };
     auto read_scales = [&](const char *area) __attribute__((always_inline)) {
-        const int r = fresh_lane() & 31;
 #pragma unroll
-        for (int i = 0; i < FP; ++i)
-            sc_raw[i] = *reinterpret_cast<const uint32_t *>(area + (wp * (FP * 32) + i * 32 + r) * 4);
-#pragma unroll
-        for (int j = 0; j < FQ; ++j)
-            sc_raw[FP + j] = *reinterpret_cast<const uint32_t *>(area + (BT + wq * (FQ * 32) + j * 32 + r) * 4);
+        for (int n = 0; n < NSC; ++n) read_scale_n(area, n);
     };
     auto regroup = [&]() __attribute__((always_inline)) {
-        const uint32_t pick = 0x06040200u + (uint32_t)(fresh_lane() >> 5) * 0x01010101u;   // h = 1: 0x07050301
+        const uint32_t pick = 0x06040200u + (uint32_t)(lane >> 5) * 0x01010101u;   // h = 1: 0x07050301
 #pragma unroll
         for (int n = 0; n < NSC / 2; ++n) sc[n] = __builtin_amdgcn_perm(sc_raw[2 * n + 1], sc_raw[2 * n], pick);
     };
@@ -371,17 +371,7 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
             acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi16(fp[KS][I]), hi16(fq[KS][J]), acc[I][J], 0, 0, 0);
         }
     };
-    static_assert(FP == 4 && FQ == 4, "the MFMA list below is written out for 4 x 4 accumulators");
-    auto mfmas = [&](auto base_tag, auto ks_tag, auto zero_tag) __attribute__((always_inline)) {
-        using std::integral_constant;
-#define MOIN_MX_ROW(I)                                                                             \
-    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 0>{}, zero_tag); \
-    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 1>{}, zero_tag); \
-    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 2>{}, zero_tag); \
-    mfma_one(base_tag, ks_tag, integral_constant<int, I>{}, integral_constant<int, 3>{}, zero_tag);
-        MOIN_MX_ROW(0) MOIN_MX_ROW(1) MOIN_MX_ROW(2) MOIN_MX_ROW(3)
-#undef MOIN_MX_ROW
-    };
+    static_assert(FP == 4 && FQ == 4 && LOADS == 8, "the steps below are written out for 4 x 4 accumulators");
 
     Tile cur = load_tile<MX>(p, id, band_end);
     id += nslot;
@@ -390,57 +380,80 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
     // fetch cursor: tile and block index of the next block to request
     Tile pft = cur;
     int pfb = 2;
+    Fetch fsecond;   // what the second half of the block under way requests
 
-    // One block of the stream.  BASE: kind of this block.  The block two positions
-    // ahead is fetched into the stage this block frees, and the next block's scales
-    // and leading fragments are read, in any case: at the stream's end they are
-    // repeated requests and stale bytes of LDS that nothing uses.
-    auto body = [&](int s, auto base_tag, auto first_tag) __attribute__((always_inline)) {
-        constexpr bool BASE = decltype(base_tag)::value;   // first_tag: the tile's first block
-        const char *st_cur = smem + (s & 1) * STAGE_BYTES;
-        const char *st_nxt = smem + ((s + 1) & 1) * STAGE_BYTES;
-        read_frags(st_cur, 1);
-        mfmas(base_tag, std::integral_constant<int, 0>{}, first_tag);
-        // MFMAs have no side effects, so only data flow orders them against the
-        // barrier: making their results operands of an (empty) volatile asm keeps the
-        // first k-step's MFMAs ahead of it, where they cover the latency of the
-        // fragment reads above
-        asm volatile("" : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]), "+a"(acc[1][0]),
-                          "+a"(acc[1][1]), "+a"(acc[1][2]), "+a"(acc[1][3]), "+a"(acc[2][0]), "+a"(acc[2][1]),
-                          "+a"(acc[2][2]), "+a"(acc[2][3]), "+a"(acc[3][0]), "+a"(acc[3][1]), "+a"(acc[3][2]),
-                          "+a"(acc[3][3]));
-        // own share of block s+1 has landed and every fragment of block s is in
-        // registers; past the barrier that holds for all waves
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        // The fetch cursor runs two blocks ahead; when it has used up its tile it
-        // moves to the tile after the one being computed (by now `nxt` is that tile
-        // in every case); past the last tile it requests that tile's last block
-        // again, into the stage that is free anyway.
-        if (pfb == pft.total) {
-            if (nxt.valid) {
-                pft = nxt;
-                pfb = 0;
-            } else {
-                pfb = pft.total - 1;
+    // One block of the stream: k-step 0 (its fragments were read during the block before) with the reads
+    // of k-step 1 between its MFMAs; barrier (own share of block s+1 has landed and every fragment of
+    // block s is in registers; past the barrier that holds for all waves); k-step 1 with the requests for
+    // the block two ahead -- into the stage this block frees -- and the next block's scales and leading
+    // fragments between its MFMAs.  One wave per SIMD: an MFMA keeps the matrix core busy for 64 cycles
+    // (32 on an adapter block), 4 of them its own issue, and whatever stands between two MFMAs and takes
+    // longer than the rest delays the second.  So the other work is dealt out one piece per MFMA -- a
+    // fragment (two LDS reads), a request with its three address instructions (about 40 cycles together),
+    // a scale word -- and the source order IS the instruction order (a scheduling barrier after every
+    // step).  With the steps left to the scheduler's group barriers a block of 32 MFMAs took 3500 cycles.
+    // BASE: kind of this block.  At the stream's end the requests and reads are repeated requests and
+    // stale bytes of LDS that nothing uses: no branch after the barrier.
+    // (An MFMA has no side effects, so only data flow keeps it in its place: its accumulator and the
+    // output-rows fragment of the NEXT step's MFMA pass through an empty assembly statement that also
+    // stands for a memory access -- the MFMA cannot sink below it, the next one cannot rise above it, and
+    // no LDS read or request crosses it.)
+    auto first_half_step = [&](auto base_tag, auto first_tag, auto n_tag, int s) __attribute__((always_inline)) {
+        constexpr int n = decltype(n_tag)::value;
+        using std::integral_constant;
+        mfma_one(base_tag, integral_constant<int, 0>{}, integral_constant<int, n / FQ>{}, integral_constant<int, n % FQ>{}, first_tag);
+        if constexpr (n + 1 < FP * FQ) asm volatile("" : "+a"(acc[n / FQ][n % FQ]), "+v"(fp[0][(n + 1) / FQ]) : : "memory");
+        else asm volatile("" : "+a"(acc[n / FQ][n % FQ]) : : "memory");
+        if (n < FP + FQ) read_frag_n(smem + (s & 1) * STAGE_BYTES, 1, n);
+        if (n == 10) {
+            // The fetch cursor runs two blocks ahead; when it has used up its tile it moves to the tile
+            // after the one being computed (by now `nxt` is that tile in every case); past the last
+            // tile it requests that tile's last block again, into the stage that is free anyway.
+            if (pfb == pft.total) {
+                if (nxt.valid) {
+                    pft = nxt;
+                    pfb = 0;
+                } else {
+                    pfb = pft.total - 1;
+                }
             }
+            fsecond = fetch_of(pft, pfb);
+            ++pfb;
         }
-        // From here to the end of the block there is no branch, so that the reads of
-        // the next block's operands, the requests for the block after it and the
-        // second k-step's MFMAs can be interleaved (one wave per SIMD: whatever
-        // delays the next MFMA leaves the matrix core idle).
-        if constexpr (MX) read_scales(smem + SMEM_STAGES + ((s + 1) & 1) * SC_BYTES);
-        read_frags(st_nxt, 0);
-        issue(pft, pfb, s & 1);
-        ++pfb;
-        mfmas(base_tag, std::integral_constant<int, 1>{}, std::false_type{});
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto second_half_step = [&](auto base_tag, auto n_tag, int s) __attribute__((always_inline)) {
+        constexpr int n = decltype(n_tag)::value;
+        using std::integral_constant;
+        mfma_one(base_tag, integral_constant<int, 1>{}, integral_constant<int, n / FQ>{}, integral_constant<int, n % FQ>{}, std::false_type{});
+        if constexpr (n + 1 < FP * FQ) asm volatile("" : "+a"(acc[n / FQ][n % FQ]), "+v"(fp[1][(n + 1) / FQ]) : : "memory");
+        else asm volatile("" : "+a"(acc[n / FQ][n % FQ]) : : "memory");
+        if (n < FP + FQ) read_frag_n(smem + ((s + 1) & 1) * STAGE_BYTES, 0, n);
+        else if constexpr (MX) read_scale_n(smem + SMEM_STAGES + ((s + 1) & 1) * SC_BYTES, n - (FP + FQ));
+        issue_one(fsecond, s & 1, n);
+        if constexpr (MX) {
+            if (n == 3) issue_one(fsecond, s & 1, 2 * LOADS);
+            if (n == 7) issue_one(fsecond, s & 1, 2 * LOADS + 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto body = [&](int s, auto base_tag, auto first_tag) __attribute__((always_inline)) {
+        using std::integral_constant;
+#define MOIN_MX_STEPS(F, ...)                                                                            \
+    F(__VA_ARGS__, integral_constant<int, 0>{}, s); F(__VA_ARGS__, integral_constant<int, 1>{}, s);       \
+    F(__VA_ARGS__, integral_constant<int, 2>{}, s); F(__VA_ARGS__, integral_constant<int, 3>{}, s);       \
+    F(__VA_ARGS__, integral_constant<int, 4>{}, s); F(__VA_ARGS__, integral_constant<int, 5>{}, s);       \
+    F(__VA_ARGS__, integral_constant<int, 6>{}, s); F(__VA_ARGS__, integral_constant<int, 7>{}, s);       \
+    F(__VA_ARGS__, integral_constant<int, 8>{}, s); F(__VA_ARGS__, integral_constant<int, 9>{}, s);       \
+    F(__VA_ARGS__, integral_constant<int, 10>{}, s); F(__VA_ARGS__, integral_constant<int, 11>{}, s);     \
+    F(__VA_ARGS__, integral_constant<int, 12>{}, s); F(__VA_ARGS__, integral_constant<int, 13>{}, s);     \
+    F(__VA_ARGS__, integral_constant<int, 14>{}, s); F(__VA_ARGS__, integral_constant<int, 15>{}, s);
+        MOIN_MX_STEPS(first_half_step, base_tag, first_tag)
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        MOIN_MX_STEPS(second_half_step, base_tag)
+#undef MOIN_MX_STEPS
         if constexpr (MX) regroup();
-#pragma unroll
-        for (int n = 0; n < FP * FQ; ++n) {
-            __builtin_amdgcn_sched_group_barrier(0x008, BASE ? 1 : 2, 0);   // MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);              // LDS reads: all issued in the first 12 groups
-            __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);              // DMA requests
-            __builtin_amdgcn_sched_group_barrier(0x006, 10, 0);             // their address arithmetic
-        }
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     // prologue of the stream: two blocks in flight, the first one landed
@@ -465,6 +478,7 @@ __global__ __launch_bounds__(mxs::NT) void linear_stream4_kernel(mxs::Params p)
         for (; b < nb; ++b, ++s) body(s, std::integral_constant<bool, MX>{}, std::false_type{});
         for (; b < total; ++b, ++s) body(s, std::false_type{}, std::false_type{});
 
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // the last MFMAs' results before the epilogue's assembly reads them
         // epilogue through the wave's private 4 KB of LDS beyond the stages (which
         // the next tile's loads are already filling)
         // (the lane id goes in through an opaque copy: the epilogue's per-lane

@@ -74,10 +74,16 @@ __device__ __forceinline__ void stream_epilogue_as(char *scr, const f32x16_t (&a
                 for (int ii = 0; ii < 2; ++ii) {
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
-                        const f32x16_t &a = acc[ip * 2 + ii][j];
+                        // (the accumulators live in AccVGPRs; each value is read in place by an instruction
+                        // of its own: left to itself the compiler copies whole accumulators out ahead of time,
+                        // and the main loop's registers pay for it)
+                        float a4[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a4[e]) : "a"(acc[ip * 2 + ii][j][4 * g + e]));
                         const int slot = ii * 8 + 2 * g + h;
                         *reinterpret_cast<uint2 *>(scr + r * 128 + ((slot ^ fw) * 8)) =
-                            make_uint2(pack_bf16x2(a[4 * g], a[4 * g + 1]), pack_bf16x2(a[4 * g + 2], a[4 * g + 3]));
+                            make_uint2(pack_bf16x2(a4[0], a4[1]), pack_bf16x2(a4[2], a4[3]));
                     }
                 }
                 lds_order();
