@@ -71,7 +71,8 @@ def test_queries_equal_centroids_and_duplicates():
     assert counts[17].item() == 2 and counts[400].item() == 0 and counts.sum().item() == 600
 
 
-@pytest.mark.parametrize("K,D,N", [(1280, 768, 8192), (1030, 64, 12000), (5000, 768, 10000)])
+# (the last case has more query tiles than workgroups in the launch: several items per workgroup, the last one ragged)
+@pytest.mark.parametrize("K,D,N", [(1280, 768, 8192), (1030, 64, 12000), (5000, 768, 10000), (1030, 64, 90001)])
 def test_lowest_index_wins_ties_in_the_large_batch_kernel(K, D, N):
     # More than 4096 queries: the streaming kernel, whose workgroups share a query tile and merge
     # their winners with a packed atomic minimum.  Every query IS a centroid and a third of the
