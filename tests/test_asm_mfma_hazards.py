@@ -108,3 +108,14 @@ def test_no_scratch_and_no_early_accvgpr_access(src):
                         gap = count - last_addend.get(r_, -10 ** 9)
                         assert gap > MIN_GAP, f"{sym}: compiler-placed `{t}` {gap} instructions behind an MFMA that reads a{r_}"
         assert n_mfma >= 128, f"{sym}: expected the unrolled MFMA blocks, found {n_mfma} MFMAs"
+
+
+def test_quantised_base_kernel_does_not_spill():
+    # its MFMAs are builtins (the compiler sees them and their hazards), but a spill inside its main loop costs
+    # the same as in the others: the reload waits for every direct-to-LDS load in flight
+    asm = _device_asm("mx.hip")
+    bodies = _kernel_bodies(asm, "linear_stream4_kernel")
+    assert bodies
+    for sym, lines in bodies:
+        assert not any(re.search(r"\bscratch_(load|store)", l) for l in lines), f"{sym} spills to scratch"
+        assert sum("v_mfma" in l for l in lines) >= 96, f"{sym}: expected the unrolled MFMA blocks"
