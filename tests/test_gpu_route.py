@@ -51,6 +51,19 @@ def test_bf16_router_streaming_kernel_several_items_per_workgroup(N, K, D):
     assert torch.equal(counts.long(), torch.bincount(cids.long(), minlength=K))
 
 
+@pytest.mark.parametrize("N,K,D", [(30000, 600, 64), (50000, 257, 64), (45000, 1281, 192), (100000, 64, 64),
+                                   (4097, 5000, 64), (33333, 2049, 128)])
+def test_bf16_router_streaming_kernel_shape_sweep(N, K, D):
+    # one block per centroid tile (D = 64) with several items per workgroup, a last centroid tile of one row,
+    # fewer centroids than a tile holds, group sizes 1 to 5, ragged last query tiles
+    rin = _route_case(N, K, D, "bf16", True, seed=3 * N + K + D)
+    print(f"[gpu] route bf16 stream sweep N={N} K={K} D={D}", flush=True)
+    eids, cids, counts = moin.moin_route(gc.ctx(), rin.emb, rin.centroids, want_counts=True)
+    gc.ctx().check()
+    gc.check_route(rin.emb, rin.centroids, cids)
+    assert torch.equal(counts.long(), torch.bincount(cids.long(), minlength=K))
+
+
 def test_f32_router_small():
     rin = _route_case(300, 77, 100, "f32", False, seed=3)
     eids, cids, counts = moin.moin_route(gc.ctx(), rin.emb, rin.centroids, want_counts=True)
